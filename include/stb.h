@@ -1,0 +1,165 @@
+/*
+ * stb.h -- C ABI of the structured-binary (STBLLM) matrix-product library for AMD MI355X (gfx950).
+ *
+ * The library computes the inference-time product  y = x . W_hat^T  where W_hat is a structured-binary
+ * weight matrix: every output row keeps exactly N of each M consecutive input weights (Sec. 3.1 "N:M
+ * Sparsity"), a kept weight is a sign (Eq. 1-2) times one of three per-(row, 128-column block) fp16 scales
+ * chosen by a 2-bit group id (Sec. 3.4 "Non-Salient Part", Alg. 2 "Trisection": dense / intermediate /
+ * sparse region), and kept weights in salient columns carry a second, residual sign and scale
+ * (Eq. 4, Alg. 2 "Res_Approx").
+ *
+ * Conventions for every function:
+ *   - returns STB_OK (0) or a negative stb_status; never throws, never allocates device memory,
+ *     never synchronises the stream;
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory of the current
+ *     device; the caller owns every buffer, before and after the call;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); device work is only
+ *     enqueued on it.
+ *
+ * Packed format ("STB1").  All planes are little-endian; bit b of byte c of a row <-> index 8c + b;
+ * padding bits and bytes are zero.  The r-th kept weight of a row (its "slot", counted over the whole
+ * row in ascending column order) is r = g*N + rank-inside-group for M-group g, because every group
+ * keeps exactly N.
+ *
+ *   plane             shape / stride                          content
+ *   mask              n rows x k/8 bytes                      bit j = weight j of the row is kept
+ *   sign              n rows x sign_stride bytes              bit r = 1 iff kept weight r is >= 0  (1 -> +1, 0 -> -1)
+ *   region            n rows x region_stride bytes            2-bit field r = group id of kept weight r:
+ *                                                             0 dense, 1 intermediate, 2 sparse, 3 salient
+ *   res_sign          n rows x n_salient_pad/8 bytes          bit u <-> u-th salient column (ascending):
+ *                                                             1 iff the weight is kept there and its residual sign is +1
+ *   scales            fp16 [n][k/128][4]                      {dense, intermediate, sparse, alpha_o}
+ *   res_scale         fp16 [n][k/128]                         alpha_r
+ *   sal_bitmap        k/32 uint32                             bit j = column j is salient
+ *   sal_block_prefix  (k/128 + 1) uint32                      number of salient columns before each block
+ *
+ *   sign_stride   = round_up(k*N/(8M), 16),  region_stride = round_up(k*N/(4M), 16),
+ *   n_salient_pad = round_up(n_salient, 128)
+ *   total_bytes   = n*(k/8 + sign_stride + region_stride + n_salient_pad/8 + 10*k/128) + k/8 + 4*(k/128 + 1)
+ *
+ * Dequantised weight (what every kernel multiplies by, and what stb_dequant / stb_unpack write):
+ *   not kept                 ->  0
+ *   kept, id in {0,1,2}      ->  s * f32(scales[row][block][id])
+ *   kept, id = 3             ->  f32( s * f32(alpha_o) + t * f32(alpha_r) )        one fp32 addition
+ */
+#ifndef STB_H
+#define STB_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define STB_BLOCK 128          /* columns per scale block */
+#define STB_MAX_BATCH 32       /* largest B accepted by stb_gemv */
+#define STB_PLANE_ALIGN 256    /* alignment of every plane inside one image */
+
+typedef enum stb_status {
+    STB_OK = 0,
+    STB_EINVAL = -1,      /* bad configuration or argument (M not 4 or 8, N outside 1..M, k % 128 != 0, B outside 1..32, T < 1, layout fields that do not match the closed form, n_salient != popcount of the bitmap) */
+    STB_ENULL = -2,       /* a required pointer is NULL */
+    STB_EALIGN = -3,      /* a plane pointer is not 16-byte aligned */
+    STB_ENONFINITE = -4,  /* NaN or Inf in W or xnorm, or xnorm < 0 */
+    STB_EHIP = -5,        /* a HIP call failed; the HIP error code is returned by stb_last_hip_error() */
+    STB_EUNSUPPORTED = -6 /* valid request that this build has no kernel for */
+} stb_status;
+
+/* Problem description. block must be 128. region_mode: 0 = break-point search of Alg. 2
+ * "NonSalientAwareQuant" (160 candidates, p2 = 2*p1), 1 = tertile split of the kept non-salient
+ * magnitudes of each block. n_salient = number of set bits of the salient-column bitmap. */
+typedef struct stb_cfg {
+    int32_t n_out;        /* n: rows of W = output features */
+    int32_t k_in;         /* k: columns of W = input features, multiple of 128 */
+    int32_t N, M;         /* keep N of every M consecutive input weights; M in {4, 8}, 1 <= N <= M */
+    int32_t block;        /* 128 */
+    int32_t n_salient;    /* S */
+    int32_t region_mode;  /* 0 | 1, only read by stb_pack */
+} stb_cfg_t;
+
+/* Sizes, offsets and plane pointers of one packed matrix.  stb_layout_sizes fills everything except the
+ * pointers; stb_layout_bind derives the pointers from one base address (host or device).  A caller may
+ * also set the eight pointers by hand (each 16-byte aligned). */
+typedef struct stb_layout {
+    stb_cfg_t cfg;
+    int32_t n_salient_pad;     /* round_up(S, 128), 0 if S = 0 */
+    int32_t n_blocks;          /* k / 128 */
+    int64_t mask_stride, sign_stride, region_stride, res_stride;          /* bytes per row */
+    int64_t mask_bytes, sign_bytes, region_bytes, res_bytes,
+            scales_bytes, res_scale_bytes, salmap_bytes, salprefix_bytes;
+    int64_t total_bytes;       /* sum of the eight planes: the "packed bytes" that throughput is quoted on */
+    int64_t off_mask, off_sign, off_region, off_res, off_scales, off_res_scale,
+            off_salmap, off_salprefix;                                    /* offsets inside one image */
+    int64_t image_bytes;       /* size of one allocation holding all planes at the offsets above */
+    uint32_t *mask, *sign, *region, *res_sign, *sal_bitmap, *sal_block_prefix;
+    uint16_t *scales, *res_scale;
+} stb_layout_t;
+
+/* Closed-form sizes and image offsets for `cfg` (Sec. 3.4 "Average Bits" gives the payload: N/M sign bits
+ * per weight, a second one on kept salient weights, 2-bit ids).  Pointers in `out` are set to NULL.
+ * Errors: STB_ENULL, STB_EINVAL. */
+int stb_layout_sizes(const stb_cfg_t* cfg, stb_layout_t* out);
+
+/* Point the eight plane pointers at base + off_*.  `base` is host or device memory of at least
+ * image_bytes bytes, 256-byte aligned.  Errors: STB_ENULL, STB_EALIGN. */
+int stb_layout_bind(stb_layout_t* layout, void* base);
+
+/* Structured binarisation of one linear layer on the host (Alg. 1 without its Hessian steps: the salient
+ * column set is an input and there is no error compensation between blocks):
+ *   Standardized Importance over the whole layer (Eq. 3) -> N:M mask (ties keep the lower column) ->
+ *   per 128-column block: residual binarisation of kept salient weights per row (Eq. 4), break points
+ *   over the kept non-salient weights of all rows (Alg. 2 "NonSalientAwareQuant", or tertiles), one scale
+ *   per (row, block, region) (Eq. 6) -> bit planes.
+ * W: host, n x k row-major fp32.  xnorm: host, k values >= 0 (L2 norm of each input feature).
+ * sal_bitmap: host, k/32 words.  out: layout from stb_layout_sizes bound to caller-allocated host memory;
+ * every byte of every plane is written.  n_threads <= 0 picks the hardware concurrency.
+ * The result is bit-for-bit reproducible and independent of n_threads.
+ * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_ENONFINITE. */
+int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_bitmap, stb_layout_t* out,
+             int32_t n_threads);
+
+/* Host dequantisation of a packed matrix into dense fp32 (definition in the header comment).
+ * host: layout bound to host memory.  W_hat: host, n x k row-major, fully overwritten.
+ * Errors: STB_ENULL, STB_EINVAL (including a mask row that does not keep k*N/M weights). */
+int stb_unpack(const stb_layout_t* host, float* W_hat);
+
+/* Device dequantisation: same result as stb_unpack, bit for bit, written by a HIP kernel.
+ * dev: layout bound to device memory holding a copy of the packed image.  W_hat_dev: device, n x k fp32.
+ * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
+int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream);
+
+/* Decode-time product (memory-bound regime, App. C "Theory Analysis": small N = batch):
+ *   y[b][i] = sum_j x[b][j] * W_hat[i][j],  b < B <= 32.
+ * x: device fp16 [B][k] row-major.  y: device [B][n] row-major, fp16 (y_fp32 = 0) or fp32 (y_fp32 = 1),
+ * fully overwritten.  Accumulation is fp32.
+ * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
+int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32, void* stream);
+
+/* Several independent layers with the same B in one launch sequence on one stream (q/k/v or gate/up
+ * share x in a decoder layer).  dev, x, y: host arrays of n_layers pointers.
+ * Errors: as stb_gemv; the first failing layer stops the sequence. */
+int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const void* const* x, int32_t B,
+                     void* const* y, int32_t y_fp32, void* stream);
+
+/* Prefill-time product (compute-bound regime, App. C: large N = batch x sequence length):
+ *   Y[t][i] = sum_j X[t][j] * W_hat[i][j],  t < T.
+ * The weights are dequantised to fp16 on the fly and contracted on the matrix cores with fp32
+ * accumulation.  X: device fp16 [T][k].  Y: device [T][n], fp16 or fp32.  workspace: device scratch of at
+ * least stb_gemm_workspace_bytes() bytes (may be NULL when that is 0).
+ * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
+int stb_gemm(const stb_layout_t* dev, const void* X, int32_t T, void* Y, int32_t y_fp32,
+             void* workspace, int64_t workspace_bytes, void* stream);
+
+/* Scratch bytes stb_gemm needs for (cfg, T); negative stb_status on a bad argument. */
+int64_t stb_gemm_workspace_bytes(const stb_cfg_t* cfg, int32_t T);
+
+/* Text for a status code (static storage). */
+const char* stb_strerror(int status);
+
+/* HIP error code of the last STB_EHIP on the calling thread (0 if none). */
+int stb_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STB_H */

@@ -1,0 +1,243 @@
+"""ctypes binding of libstb (include/stb.h).  Argument marshalling only: every step of the path runs
+inside the library.  The functions carry the names of the C entry points; `PackedMatrix` is a small
+holder for a packed image on the host and its copy in HBM.
+
+PyTorch is used for device memory and streams only.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libstb.so")
+
+STB_BLOCK = 128
+STB_MAX_BATCH = 32
+STB_PLANE_ALIGN = 256
+
+STB_OK, STB_EINVAL, STB_ENULL, STB_EALIGN, STB_ENONFINITE, STB_EHIP, STB_EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+
+
+class StbError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib().stb_strerror(status).decode() if _LIB is not None else str(status)
+        if status == STB_EHIP:
+            msg += f" [hip error {_lib().stb_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+class stb_cfg_t(C.Structure):
+    _fields_ = [("n_out", C.c_int32), ("k_in", C.c_int32), ("N", C.c_int32), ("M", C.c_int32),
+                ("block", C.c_int32), ("n_salient", C.c_int32), ("region_mode", C.c_int32)]
+
+
+class stb_layout_t(C.Structure):
+    _fields_ = (
+        [("cfg", stb_cfg_t), ("n_salient_pad", C.c_int32), ("n_blocks", C.c_int32)]
+        + [(name, C.c_int64) for name in (
+            "mask_stride", "sign_stride", "region_stride", "res_stride",
+            "mask_bytes", "sign_bytes", "region_bytes", "res_bytes",
+            "scales_bytes", "res_scale_bytes", "salmap_bytes", "salprefix_bytes",
+            "total_bytes",
+            "off_mask", "off_sign", "off_region", "off_res", "off_scales", "off_res_scale",
+            "off_salmap", "off_salprefix",
+            "image_bytes")]
+        + [(name, C.c_void_p) for name in (
+            "mask", "sign", "region", "res_sign", "sal_bitmap", "sal_block_prefix",
+            "scales", "res_scale")]
+    )
+
+
+PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_bytes"),
+                ("region", "off_region", "region_bytes"), ("res_sign", "off_res", "res_bytes"),
+                ("scales", "off_scales", "scales_bytes"), ("res_scale", "off_res_scale", "res_scale_bytes"),
+                ("sal_bitmap", "off_salmap", "salmap_bytes"),
+                ("sal_block_prefix", "off_salprefix", "salprefix_bytes"))
+
+_LIB = None
+
+EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_pack", "stb_unpack", "stb_dequant", "stb_gemv",
+           "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_strerror", "stb_last_hip_error")
+
+
+def _lib():
+    """Loads libstb.so.  There is no fallback: a missing library is an error."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(or paper_2408_01803_amd/build.py) first")
+    lib = C.CDLL(LIB_PATH)
+    P = C.POINTER
+    lib.stb_layout_sizes.argtypes = [P(stb_cfg_t), P(stb_layout_t)]
+    lib.stb_layout_bind.argtypes = [P(stb_layout_t), C.c_void_p]
+    lib.stb_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32]
+    lib.stb_unpack.argtypes = [P(stb_layout_t), C.c_void_p]
+    lib.stb_dequant.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
+    lib.stb_gemv.argtypes = [P(stb_layout_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.stb_gemv_batched.argtypes = [C.c_int32, P(P(stb_layout_t)), P(C.c_void_p), C.c_int32,
+                                     P(C.c_void_p), C.c_int32, C.c_void_p]
+    lib.stb_gemm.argtypes = [P(stb_layout_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+                             C.c_void_p, C.c_int64, C.c_void_p]
+    lib.stb_gemm_workspace_bytes.argtypes = [P(stb_cfg_t), C.c_int32]
+    lib.stb_gemm_workspace_bytes.restype = C.c_int64
+    lib.stb_strerror.argtypes = [C.c_int]
+    lib.stb_strerror.restype = C.c_char_p
+    lib.stb_last_hip_error.restype = C.c_int
+    for name in ("stb_layout_sizes", "stb_layout_bind", "stb_pack", "stb_unpack", "stb_dequant",
+                 "stb_gemv", "stb_gemv_batched", "stb_gemm"):
+        getattr(lib, name).restype = C.c_int
+    _LIB = lib
+    return lib
+
+
+def _check(status: int, where: str):
+    if status != STB_OK:
+        raise StbError(int(status), where)
+
+
+def make_cfg(n_out: int, k_in: int, N: int, M: int, n_salient: int, region_mode: int = 0) -> stb_cfg_t:
+    return stb_cfg_t(n_out, k_in, N, M, STB_BLOCK, n_salient, region_mode)
+
+
+def aligned_bytes(nbytes: int, align: int = STB_PLANE_ALIGN) -> np.ndarray:
+    """Zero-filled uint8 host buffer whose address is a multiple of `align`."""
+    raw = np.zeros(nbytes + align, dtype=np.uint8)
+    off = (-raw.ctypes.data) % align
+    return raw[off:off + nbytes]
+
+
+# ---- entry points, same names as the C ABI -----------------------------------------------------
+def stb_layout_sizes(cfg: stb_cfg_t) -> stb_layout_t:
+    out = stb_layout_t()
+    _check(_lib().stb_layout_sizes(C.byref(cfg), C.byref(out)), "stb_layout_sizes")
+    return out
+
+
+def stb_layout_bind(layout: stb_layout_t, base_ptr: int) -> stb_layout_t:
+    _check(_lib().stb_layout_bind(C.byref(layout), C.c_void_p(base_ptr)), "stb_layout_bind")
+    return layout
+
+
+def stb_pack(W: np.ndarray, xnorm: np.ndarray, sal_bitmap: np.ndarray, layout: stb_layout_t,
+             n_threads: int = 0) -> None:
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    xnorm = np.ascontiguousarray(xnorm, dtype=np.float32)
+    sal_bitmap = np.ascontiguousarray(sal_bitmap, dtype=np.uint32)
+    assert W.shape == (layout.cfg.n_out, layout.cfg.k_in) and xnorm.shape == (layout.cfg.k_in,)
+    assert sal_bitmap.shape == (layout.cfg.k_in // 32,)
+    _check(_lib().stb_pack(W.ctypes.data, xnorm.ctypes.data, sal_bitmap.ctypes.data, C.byref(layout),
+                           n_threads), "stb_pack")
+
+
+def stb_unpack(layout: stb_layout_t) -> np.ndarray:
+    out = np.empty((layout.cfg.n_out, layout.cfg.k_in), dtype=np.float32)
+    _check(_lib().stb_unpack(C.byref(layout), out.ctypes.data), "stb_unpack")
+    return out
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def stb_dequant(layout_dev: stb_layout_t, out_dev, stream=None) -> None:
+    _check(_lib().stb_dequant(C.byref(layout_dev), C.c_void_p(out_dev.data_ptr()),
+                              C.c_void_p(_stream_ptr(stream))), "stb_dequant")
+
+
+def stb_gemv(layout_dev: stb_layout_t, x_dev, B: int, y_dev, y_fp32: bool = False, stream=None) -> None:
+    _check(_lib().stb_gemv(C.byref(layout_dev), C.c_void_p(x_dev.data_ptr()), B,
+                           C.c_void_p(y_dev.data_ptr()), int(y_fp32), C.c_void_p(_stream_ptr(stream))),
+           "stb_gemv")
+
+
+def stb_gemv_batched(layouts_dev: Sequence[stb_layout_t], xs_dev, B: int, ys_dev, y_fp32: bool = False,
+                     stream=None) -> None:
+    n = len(layouts_dev)
+    LP = C.POINTER(stb_layout_t)
+    lay = (LP * n)(*[C.pointer(l) for l in layouts_dev])
+    xs = (C.c_void_p * n)(*[x.data_ptr() for x in xs_dev])
+    ys = (C.c_void_p * n)(*[y.data_ptr() for y in ys_dev])
+    _check(_lib().stb_gemv_batched(n, lay, xs, B, ys, int(y_fp32), C.c_void_p(_stream_ptr(stream))),
+           "stb_gemv_batched")
+
+
+def stb_gemm_workspace_bytes(cfg: stb_cfg_t, T: int) -> int:
+    r = _lib().stb_gemm_workspace_bytes(C.byref(cfg), T)
+    if r < 0:
+        raise StbError(int(r), "stb_gemm_workspace_bytes")
+    return int(r)
+
+
+def stb_gemm(layout_dev: stb_layout_t, X_dev, T: int, Y_dev, y_fp32: bool = False, workspace=None,
+             stream=None) -> None:
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(_lib().stb_gemm(C.byref(layout_dev), C.c_void_p(X_dev.data_ptr()), T,
+                           C.c_void_p(Y_dev.data_ptr()), int(y_fp32), C.c_void_p(ws_ptr), ws_bytes,
+                           C.c_void_p(_stream_ptr(stream))), "stb_gemm")
+
+
+# ---- holder --------------------------------------------------------------------------------------
+class PackedMatrix:
+    """A packed image on the host (numpy, 256-byte aligned) and, after `to_device`, its copy in HBM."""
+
+    def __init__(self, cfg: stb_cfg_t):
+        self.cfg = cfg
+        self.host_layout = stb_layout_sizes(cfg)
+        self.host_image = aligned_bytes(self.host_layout.image_bytes)
+        stb_layout_bind(self.host_layout, self.host_image.ctypes.data)
+        self.dev_layout: Optional[stb_layout_t] = None
+        self.dev_image = None
+
+    @classmethod
+    def pack(cls, W, xnorm, sal_bitmap, N: int, M: int, region_mode: int = 0, n_threads: int = 0):
+        n, k = W.shape
+        sal_bitmap = np.ascontiguousarray(sal_bitmap, dtype=np.uint32)
+        S = int(np.unpackbits(sal_bitmap.view(np.uint8)).sum())
+        pm = cls(make_cfg(n, k, N, M, S, region_mode))
+        stb_pack(W, xnorm, sal_bitmap, pm.host_layout, n_threads)
+        return pm
+
+    @property
+    def packed_bytes(self) -> int:
+        return int(self.host_layout.total_bytes)
+
+    def plane(self, name: str) -> np.ndarray:
+        """Bytes of one plane of the host image (a view)."""
+        for pname, off, size in PLANE_FIELDS:
+            if pname == name:
+                o, s = getattr(self.host_layout, off), getattr(self.host_layout, size)
+                return self.host_image[o:o + s]
+        raise KeyError(name)
+
+    def planes(self) -> dict:
+        return {name: self.plane(name) for name, _, _ in PLANE_FIELDS}
+
+    def unpack(self) -> np.ndarray:
+        return stb_unpack(self.host_layout)
+
+    def to_device(self, device="cuda:0"):
+        import torch
+        img = torch.from_numpy(self.host_image)
+        self.dev_image = torch.empty(self.host_layout.image_bytes + STB_PLANE_ALIGN, dtype=torch.uint8,
+                                     device=device)
+        off = (-self.dev_image.data_ptr()) % STB_PLANE_ALIGN
+        view = self.dev_image[off:off + self.host_layout.image_bytes]
+        view.copy_(img)
+        self.dev_layout = self.clone_layout_for(view.data_ptr())
+        return self
+
+    def clone_layout_for(self, base_ptr: int) -> stb_layout_t:
+        """Layout struct of the same matrix bound to another copy of the image (host or device)."""
+        lay = stb_layout_sizes(self.cfg)
+        return stb_layout_bind(lay, base_ptr)

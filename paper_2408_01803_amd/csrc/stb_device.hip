@@ -1,0 +1,334 @@
+// Device side of libstb for gfx950: dequantisation, decode GEMV and prefill GEMM on the packed planes.
+// C ABI in include/stb.h.  Everything here runs on the caller's stream; nothing allocates.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include "stb_internal.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return STB_EHIP;
+}
+
+// Plane pointers and sizes in the form the kernels take them (passed by value).
+struct Planes {
+    const uint32_t* mask;
+    const uint8_t* sign;
+    const uint8_t* region;
+    const uint8_t* res_sign;
+    const __half* scales;       // [n][nb][4]
+    const __half* res_scale;    // [n][nb]
+    const uint32_t* sal_bitmap;
+    const uint32_t* sal_prefix;
+    int n, k, N, M, nb, wpr;    // wpr = mask words per row = k/32
+    int sign_stride, region_stride, res_stride;
+    int spw;                    // kept weights ("slots") per mask word = 32*N/M
+};
+
+Planes make_planes(const stb_layout_t* L) {
+    Planes p;
+    p.mask = L->mask;
+    p.sign = (const uint8_t*)L->sign;
+    p.region = (const uint8_t*)L->region;
+    p.res_sign = (const uint8_t*)L->res_sign;
+    p.scales = (const __half*)L->scales;
+    p.res_scale = (const __half*)L->res_scale;
+    p.sal_bitmap = L->sal_bitmap;
+    p.sal_prefix = L->sal_block_prefix;
+    p.n = L->cfg.n_out;
+    p.k = L->cfg.k_in;
+    p.N = L->cfg.N;
+    p.M = L->cfg.M;
+    p.nb = L->n_blocks;
+    p.wpr = p.k / 32;
+    p.sign_stride = (int)L->sign_stride;
+    p.region_stride = (int)L->region_stride;
+    p.res_stride = (int)L->res_stride;
+    p.spw = 32 * p.N / p.M;
+    return p;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Decoder of one mask word (32 consecutive columns of one row), generic in N:M.
+// Because every M-group keeps exactly N weights, the first slot of mask word w is w * 32*N/M.
+// ------------------------------------------------------------------------------------------------
+struct WordCtx {
+    uint32_t m;            // mask bits
+    uint32_t salw;         // salient-column bits of the same 32 columns
+    int slot0;             // slot of the first kept weight of the word
+    int ord0;              // index among salient columns of the word's first column
+    float a0, a1, a2, a3;  // dense, intermediate, sparse, alpha_o
+    float ar;              // alpha_r
+    const uint8_t* srow;
+    const uint8_t* rrow;
+    const uint8_t* trow;
+};
+
+__device__ inline WordCtx load_word(const Planes& p, int row, int w) {
+    WordCtx c;
+    c.m = p.mask[(size_t)row * p.wpr + w];
+    c.salw = p.sal_bitmap[w];
+    c.slot0 = w * p.spw;
+    const int q = w >> 2;
+    int ord = (int)p.sal_prefix[q];
+    for (int v = q * 4; v < w; v++) ord += __popc(p.sal_bitmap[v]);
+    c.ord0 = ord;
+    const uint2 sc = *reinterpret_cast<const uint2*>(p.scales + ((size_t)row * p.nb + q) * 4);
+    const __half2 s01 = *reinterpret_cast<const __half2*>(&sc.x);
+    const __half2 s23 = *reinterpret_cast<const __half2*>(&sc.y);
+    c.a0 = __low2float(s01);
+    c.a1 = __high2float(s01);
+    c.a2 = __low2float(s23);
+    c.a3 = __high2float(s23);
+    c.ar = __half2float(p.res_scale[(size_t)row * p.nb + q]);
+    c.srow = p.sign + (size_t)row * p.sign_stride;
+    c.rrow = p.region + (size_t)row * p.region_stride;
+    c.trow = p.res_sign ? p.res_sign + (size_t)row * p.res_stride : nullptr;
+    return c;
+}
+
+// Dequantised value of bit position `pos` of the word (must be a kept position), `rank` = number of
+// kept positions below it inside the word.
+__device__ inline float decode_kept(const WordCtx& c, int pos, int rank) {
+    const int slot = c.slot0 + rank;
+    const bool plus = (c.srow[slot >> 3] >> (slot & 7)) & 1;
+    const unsigned id = (c.rrow[slot >> 2] >> ((slot & 3) * 2)) & 3u;
+    const float a = id == 0 ? c.a0 : (id == 1 ? c.a1 : (id == 2 ? c.a2 : c.a3));
+    float v = plus ? a : -a;
+    if (id == 3 && c.trow) {
+        const int u = c.ord0 + __popc(c.salw & ((1u << pos) - 1u));
+        const bool tplus = (c.trow[u >> 3] >> (u & 7)) & 1;
+        v = v + (tplus ? c.ar : -c.ar);      // one fp32 addition
+    }
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------------
+// stb_dequant: one thread per (row, mask word)
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dequant_kernel(Planes p, float* __restrict__ out) {
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= (int64_t)p.n * p.wpr) return;
+    const int row = (int)(gid / p.wpr), w = (int)(gid % p.wpr);
+    const WordCtx c = load_word(p, row, w);
+    float* o = out + (size_t)row * p.k + (size_t)w * 32;
+    int rank = 0;
+    for (int pos = 0; pos < 32; pos++) {
+        float v = 0.0f;
+        if ((c.m >> pos) & 1u) {
+            v = decode_kept(c, pos, rank);
+            rank++;
+        }
+        o[pos] = v;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Generic decode GEMV (any N:M): one wavefront per output row, lanes stride over the mask words.
+// ------------------------------------------------------------------------------------------------
+template <int B>
+__global__ __launch_bounds__(256) void gemv_generic_kernel(Planes p, const __half* __restrict__ x,
+                                                            void* __restrict__ y, int y_fp32) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= p.n) return;
+    float acc[B];
+#pragma unroll
+    for (int b = 0; b < B; b++) acc[b] = 0.0f;
+    for (int w = lane; w < p.wpr; w += 64) {
+        const WordCtx c = load_word(p, row, w);
+        uint32_t m = c.m;
+        int rank = 0;
+        while (m) {
+            const int pos = __ffs(m) - 1;
+            m &= m - 1;
+            const float v = decode_kept(c, pos, rank);
+            rank++;
+            const int j = w * 32 + pos;
+#pragma unroll
+            for (int b = 0; b < B; b++) acc[b] += v * __half2float(x[(size_t)b * p.k + j]);
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < B; b++) {
+        float s = acc[b];
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (lane == 0) {
+            if (y_fp32) reinterpret_cast<float*>(y)[(size_t)b * p.n + row] = s;
+            else reinterpret_cast<__half*>(y)[(size_t)b * p.n + row] = __float2half(s);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Generic prefill GEMM (any N:M): 64 tokens x 64 output rows per workgroup, one 128-column block per
+// step; the W tile is dequantised to fp16 in LDS, the contraction runs on v_mfma_f32_32x32x8_f16.
+// ------------------------------------------------------------------------------------------------
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+constexpr int GT = 64;           // tokens per tile
+constexpr int GN = 64;           // output rows per tile
+constexpr int GK = 128;          // columns per step
+constexpr int GPAD = 8;          // halves of row padding in LDS
+
+__global__ __launch_bounds__(256) void gemm_generic_kernel(Planes p, const __half* __restrict__ X, int T,
+                                                            void* __restrict__ Y, int y_fp32) {
+    __shared__ __attribute__((aligned(16))) _Float16 Ws[GN][GK + GPAD];
+    __shared__ __attribute__((aligned(16))) _Float16 Xs[GT][GK + GPAD];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n0 = blockIdx.x * GN, t0 = blockIdx.y * GT;
+    const int wt = (wave >> 1) * 32, wn = (wave & 1) * 32;     // sub-tile of this wavefront
+    float16_t acc;
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[v] = 0.0f;
+
+    const int r = tid >> 2, seg = tid & 3;                     // (row | token) and 32-column segment
+    for (int q = 0; q < p.nb; q++) {
+        // ---- W tile: thread (r, seg) decodes mask word 4q + seg of row n0 + r ----
+        {
+            _Float16* dst = &Ws[r][seg * 32];
+            const int row = n0 + r;
+            if (row < p.n) {
+                const WordCtx c = load_word(p, row, q * 4 + seg);
+                int rank = 0;
+                for (int pos = 0; pos < 32; pos++) {
+                    float v = 0.0f;
+                    if ((c.m >> pos) & 1u) {
+                        v = decode_kept(c, pos, rank);
+                        rank++;
+                    }
+                    dst[pos] = (_Float16)v;
+                }
+            } else {
+                for (int pos = 0; pos < 32; pos++) dst[pos] = (_Float16)0.0f;
+            }
+        }
+        // ---- X tile: thread (r, seg) copies 32 halves of token t0 + r ----
+        {
+            uint4* dst = reinterpret_cast<uint4*>(&Xs[r][seg * 32]);
+            const int t = t0 + r;
+            if (t < T) {
+                const uint4* src = reinterpret_cast<const uint4*>(X + (size_t)t * p.k + (size_t)q * GK + seg * 32);
+#pragma unroll
+                for (int v = 0; v < 4; v++) dst[v] = src[v];
+            } else {
+                const uint4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int v = 0; v < 4; v++) dst[v] = z;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < GK / 8; kk++) {
+            const int kc = kk * 8 + (lane >> 5) * 4;
+            const half4_t a = *reinterpret_cast<const half4_t*>(&Xs[wt + (lane & 31)][kc]);
+            const half4_t b = *reinterpret_cast<const half4_t*>(&Ws[wn + (lane & 31)][kc]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x8f16(a, b, acc, 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // D[token][row]: lane holds column (lane % 32), rows 8*(v/4) + 4*(lane/32) + v%4
+    const int col = n0 + wn + (lane & 31);
+    if (col < p.n) {
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+            const int t = t0 + wt + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+            if (t < T) {
+                if (y_fp32) reinterpret_cast<float*>(Y)[(size_t)t * p.n + col] = acc[v];
+                else reinterpret_cast<__half*>(Y)[(size_t)t * p.n + col] = __float2half(acc[v]);
+            }
+        }
+    }
+}
+
+template <int B>
+hipError_t launch_gemv_generic(const Planes& p, const void* x, void* y, int y_fp32, hipStream_t s) {
+    const int blocks = (p.n + 3) / 4;
+    hipLaunchKernelGGL(gemv_generic_kernel<B>, dim3(blocks), dim3(256), 0, s, p, (const __half*)x, y, y_fp32);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------------
+extern "C" int stb_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream) {
+    if (!W_hat_dev) return STB_ENULL;
+    int rc = stb_layout_check(dev);
+    if (rc) return rc;
+    if ((uintptr_t)W_hat_dev % 16) return STB_EALIGN;
+    const Planes p = make_planes(dev);
+    const int64_t threads = (int64_t)p.n * p.wpr;
+    const int blocks = (int)((threads + 255) / 256);
+    hipLaunchKernelGGL(dequant_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, p, W_hat_dev);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? STB_OK : hip_fail(e);
+}
+
+extern "C" int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32,
+                        void* stream) {
+    if (!x || !y) return STB_ENULL;
+    int rc = stb_layout_check(dev);
+    if (rc) return rc;
+    if (B < 1 || B > STB_MAX_BATCH || (y_fp32 != 0 && y_fp32 != 1)) return STB_EINVAL;
+    if ((uintptr_t)x % 16 || (uintptr_t)y % 4) return STB_EALIGN;
+    const Planes p = make_planes(dev);
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    int done = 0;
+    // batch rows are processed in chunks of 8, 4, 2, 1 columns of x
+    while (done < B && e == hipSuccess) {
+        const int left = B - done;
+        const __half* xb = (const __half*)x + (size_t)done * p.k;
+        void* yb = y_fp32 ? (void*)((float*)y + (size_t)done * p.n) : (void*)((__half*)y + (size_t)done * p.n);
+        if (left >= 8) { e = launch_gemv_generic<8>(p, xb, yb, y_fp32, s); done += 8; }
+        else if (left >= 4) { e = launch_gemv_generic<4>(p, xb, yb, y_fp32, s); done += 4; }
+        else if (left >= 2) { e = launch_gemv_generic<2>(p, xb, yb, y_fp32, s); done += 2; }
+        else { e = launch_gemv_generic<1>(p, xb, yb, y_fp32, s); done += 1; }
+    }
+    return e == hipSuccess ? STB_OK : hip_fail(e);
+}
+
+extern "C" int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const void* const* x,
+                                int32_t B, void* const* y, int32_t y_fp32, void* stream) {
+    if (!dev || !x || !y) return STB_ENULL;
+    if (n_layers < 1) return STB_EINVAL;
+    for (int l = 0; l < n_layers; l++) {
+        int rc = stb_gemv(dev[l], x[l], B, y[l], y_fp32, stream);
+        if (rc) return rc;
+    }
+    return STB_OK;
+}
+
+extern "C" int64_t stb_gemm_workspace_bytes(const stb_cfg_t* cfg, int32_t T) {
+    stb_layout_t tmp;
+    int rc = stb_layout_sizes(cfg, &tmp);
+    if (rc) return rc;
+    if (T < 1) return STB_EINVAL;
+    return 0;
+}
+
+extern "C" int stb_gemm(const stb_layout_t* dev, const void* X, int32_t T, void* Y, int32_t y_fp32,
+                        void* workspace, int64_t workspace_bytes, void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!X || !Y) return STB_ENULL;
+    int rc = stb_layout_check(dev);
+    if (rc) return rc;
+    if (T < 1 || (y_fp32 != 0 && y_fp32 != 1)) return STB_EINVAL;
+    if ((uintptr_t)X % 16 || (uintptr_t)Y % 4) return STB_EALIGN;
+    const Planes p = make_planes(dev);
+    dim3 grid((p.n + GN - 1) / GN, (T + GT - 1) / GT);
+    hipLaunchKernelGGL(gemm_generic_kernel, grid, dim3(256), 0, (hipStream_t)stream, p, (const __half*)X, T,
+                       Y, y_fp32);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? STB_OK : hip_fail(e);
+}

@@ -1,0 +1,492 @@
+// Host side of the structured-binary library: layout closed forms, the bit-exact packer and the host
+// dequantiser.  Pure C++ (no HIP).  Must be compiled with -ffp-contract=off: the packer's results are
+// defined by a fixed sequence of IEEE double operations (sequential ascending-index sums, one divide
+// per mean, fp64 -> fp32 -> fp16 rounding for stored scales).
+#include "stb_internal.h"
+
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <thread>
+#include <vector>
+
+namespace {
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// float -> IEEE binary16 bits, round-to-nearest-even, subnormals kept, overflow to infinity.
+inline uint16_t f32_to_f16_bits(float f) {
+    uint32_t x;
+    std::memcpy(&x, &f, 4);
+    const uint32_t sign = (x >> 16) & 0x8000u;
+    x &= 0x7fffffffu;
+    if (x >= 0x7f800000u) return (uint16_t)(sign | 0x7c00u | ((x > 0x7f800000u) ? 0x200u : 0u));
+    if (x >= 0x477ff000u) return (uint16_t)(sign | 0x7c00u);             // rounds to >= 65520 -> inf
+    if (x < 0x33000001u) return (uint16_t)sign;                         // <= 2^-25 rounds to zero
+    int32_t e = (int32_t)(x >> 23) - 127;
+    uint32_t m = (x & 0x7fffffu) | 0x800000u;                           // 24-bit significand
+    int shift = (e < -14) ? (13 + (-14 - e)) : 13;                       // bits dropped
+    uint32_t half = m >> shift;
+    uint32_t rem = m & ((1u << shift) - 1u);
+    uint32_t halfway = 1u << (shift - 1);
+    if (rem > halfway || (rem == halfway && (half & 1u))) half++;
+    uint32_t out;
+    if (e < -14) out = half;                                            // subnormal (may carry into normal)
+    else out = ((uint32_t)(e + 15) << 10) + (half - 0x400u);            // carry propagates into exponent
+    return (uint16_t)(sign | out);
+}
+
+inline float f16_bits_to_f32(uint16_t h) {
+    const uint32_t sign = ((uint32_t)h & 0x8000u) << 16;
+    uint32_t e = (h >> 10) & 0x1fu, m = h & 0x3ffu, x;
+    if (e == 0) {
+        if (m == 0) x = sign;
+        else {
+            int s = 0;
+            while (!(m & 0x400u)) { m <<= 1; s++; }
+            x = sign | ((uint32_t)(127 - 15 - s + 1) << 23) | ((m & 0x3ffu) << 13);
+        }
+    } else if (e == 31) x = sign | 0x7f800000u | (m << 13);
+    else x = sign | ((e + 112u) << 23) | (m << 13);
+    float f;
+    std::memcpy(&f, &x, 4);
+    return f;
+}
+
+inline uint16_t f64_to_f16_bits(double v) { return f32_to_f16_bits((float)v); }   // fp64 -> fp32 -> fp16
+
+int check_cfg(const stb_cfg_t* c) {
+    if (!c) return STB_ENULL;
+    if (c->block != STB_BLOCK) return STB_EINVAL;
+    if (c->M != 4 && c->M != 8) return STB_EINVAL;
+    if (c->N < 1 || c->N > c->M) return STB_EINVAL;
+    if (c->n_out < 1 || c->k_in < STB_BLOCK || c->k_in % STB_BLOCK != 0) return STB_EINVAL;
+    if (c->n_salient < 0 || c->n_salient > c->k_in) return STB_EINVAL;
+    if (c->region_mode != 0 && c->region_mode != 1) return STB_EINVAL;
+    return STB_OK;
+}
+
+template <class F>
+void parallel_for(int64_t count, int n_threads, F&& body) {
+    if (n_threads <= 1 || count <= 1) {
+        for (int64_t i = 0; i < count; i++) body(i);
+        return;
+    }
+    std::atomic<int64_t> next(0);
+    std::vector<std::thread> pool;
+    int nt = (int)std::min<int64_t>(n_threads, count);
+    for (int t = 0; t < nt; t++)
+        pool.emplace_back([&]() {
+            for (;;) {
+                int64_t i = next.fetch_add(1);
+                if (i >= count) break;
+                body(i);
+            }
+        });
+    for (auto& th : pool) th.join();
+}
+
+inline bool sal_bit(const uint32_t* bm, int j) { return (bm[j >> 5] >> (j & 31)) & 1u; }
+
+}  // namespace
+
+extern "C" int stb_layout_sizes(const stb_cfg_t* cfg, stb_layout_t* out) {
+    if (!out) return STB_ENULL;
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    std::memset(out, 0, sizeof(*out));
+    out->cfg = *cfg;
+    const int64_t n = cfg->n_out, k = cfg->k_in, nb = k / STB_BLOCK;
+    const int64_t slots = k * cfg->N / cfg->M;
+    out->n_blocks = (int32_t)nb;
+    out->n_salient_pad = cfg->n_salient > 0 ? (int32_t)round_up(cfg->n_salient, 128) : 0;
+    out->mask_stride = k / 8;
+    out->sign_stride = round_up(round_up(slots, 8) / 8, 16);
+    out->region_stride = round_up(round_up(2 * slots, 8) / 8, 16);
+    out->res_stride = out->n_salient_pad / 8;
+    out->mask_bytes = n * out->mask_stride;
+    out->sign_bytes = n * out->sign_stride;
+    out->region_bytes = n * out->region_stride;
+    out->res_bytes = n * out->res_stride;
+    out->scales_bytes = n * nb * 4 * 2;
+    out->res_scale_bytes = n * nb * 2;
+    out->salmap_bytes = k / 8;
+    out->salprefix_bytes = 4 * (nb + 1);
+    out->total_bytes = out->mask_bytes + out->sign_bytes + out->region_bytes + out->res_bytes +
+                       out->scales_bytes + out->res_scale_bytes + out->salmap_bytes + out->salprefix_bytes;
+    int64_t off = 0;
+    auto place = [&](int64_t bytes) {
+        int64_t o = off;
+        off = round_up(off + bytes, STB_PLANE_ALIGN);
+        return o;
+    };
+    out->off_mask = place(out->mask_bytes);
+    out->off_sign = place(out->sign_bytes);
+    out->off_region = place(out->region_bytes);
+    out->off_res = place(out->res_bytes);
+    out->off_scales = place(out->scales_bytes);
+    out->off_res_scale = place(out->res_scale_bytes);
+    out->off_salmap = place(out->salmap_bytes);
+    out->off_salprefix = place(out->salprefix_bytes);
+    out->image_bytes = off;
+    return STB_OK;
+}
+
+extern "C" int stb_layout_bind(stb_layout_t* L, void* base) {
+    if (!L || !base) return STB_ENULL;
+    if ((uintptr_t)base % STB_PLANE_ALIGN) return STB_EALIGN;
+    char* b = (char*)base;
+    L->mask = (uint32_t*)(b + L->off_mask);
+    L->sign = (uint32_t*)(b + L->off_sign);
+    L->region = (uint32_t*)(b + L->off_region);
+    L->res_sign = (uint32_t*)(b + L->off_res);
+    L->scales = (uint16_t*)(b + L->off_scales);
+    L->res_scale = (uint16_t*)(b + L->off_res_scale);
+    L->sal_bitmap = (uint32_t*)(b + L->off_salmap);
+    L->sal_block_prefix = (uint32_t*)(b + L->off_salprefix);
+    return STB_OK;
+}
+
+// Validates that the size fields agree with the closed form for L->cfg and that the plane pointers are
+// set and 16-byte aligned.  Shared by the host and device entry points.
+extern "C" int stb_layout_check(const stb_layout_t* L) {
+    if (!L) return STB_ENULL;
+    stb_layout_t ref;
+    int rc = stb_layout_sizes(&L->cfg, &ref);
+    if (rc) return rc;
+    if (L->n_salient_pad != ref.n_salient_pad || L->n_blocks != ref.n_blocks ||
+        L->mask_stride != ref.mask_stride || L->sign_stride != ref.sign_stride ||
+        L->region_stride != ref.region_stride || L->res_stride != ref.res_stride ||
+        L->total_bytes != ref.total_bytes)
+        return STB_EINVAL;
+    const void* ptrs[8] = {L->mask, L->sign, L->region, L->res_sign, L->scales, L->res_scale,
+                           L->sal_bitmap, L->sal_block_prefix};
+    for (int i = 0; i < 8; i++) {
+        if (i == 3 && L->cfg.n_salient == 0) continue;   // res_sign may be absent
+        if (!ptrs[i]) return STB_ENULL;
+        if ((uintptr_t)ptrs[i] % 16) return STB_EALIGN;
+    }
+    return STB_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// packer
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+struct BlockScratch {
+    std::vector<double> a;        // kept non-salient magnitudes, row after row
+    std::vector<int32_t> start;   // first entry of each row in `a` (n + 1)
+    std::vector<uint8_t> col;     // column inside the block of each entry
+};
+
+// Error of binarising the three regions separately (Eq. 5-6), rows left to right then top to bottom.
+double trisection_error(const BlockScratch& s, int n, double p1, double p2) {
+    double total = 0.0;
+    for (int i = 0; i < n; i++) {
+        const double* a = s.a.data() + s.start[i];
+        const int cnt = s.start[i + 1] - s.start[i];
+        double sum[3] = {0.0, 0.0, 0.0};
+        int c[3] = {0, 0, 0};
+        for (int e = 0; e < cnt; e++) {
+            const int r = a[e] > p2 ? 2 : (a[e] > p1 ? 1 : 0);
+            sum[r] += a[e];
+            c[r]++;
+        }
+        double alpha[3];
+        for (int r = 0; r < 3; r++) alpha[r] = c[r] > 0 ? sum[r] / (double)c[r] : 0.0;
+        double row = 0.0;
+        for (int e = 0; e < cnt; e++) {
+            const int r = a[e] > p2 ? 2 : (a[e] > p1 ? 1 : 0);
+            const double d = a[e] - alpha[r];
+            row += d * d;
+        }
+        total += row;
+    }
+    return total;
+}
+
+}  // namespace
+
+extern "C" int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_bitmap, stb_layout_t* out,
+                        int32_t n_threads) {
+    if (!W || !xnorm || !sal_bitmap || !out) return STB_ENULL;
+    int rc = stb_layout_check(out);
+    if (rc) return rc;
+    const stb_cfg_t cfg = out->cfg;
+    const int n = cfg.n_out, k = cfg.k_in, N = cfg.N, M = cfg.M, nb = k / STB_BLOCK;
+    const int slots = k * N / M;
+    int nt = n_threads > 0 ? n_threads : (int)std::thread::hardware_concurrency();
+    if (nt < 1) nt = 1;
+
+    // salient columns: count must match the configuration
+    {
+        int cnt = 0;
+        for (int j = 0; j < k; j++) cnt += sal_bit(sal_bitmap, j);
+        if (cnt != cfg.n_salient) return STB_EINVAL;
+    }
+    for (int j = 0; j < k; j++)
+        if (!(xnorm[j] >= 0.0f) || !std::isfinite(xnorm[j])) return STB_ENONFINITE;
+
+    // ---- Standardized Importance (Eq. 3): row sums, column sums of |W| ----
+    std::vector<double> rs(n), cs(k, 0.0);
+    std::atomic<int> bad(0);
+    parallel_for(n, nt, [&](int64_t i) {
+        const float* w = W + (size_t)i * k;
+        double s = 0.0;
+        for (int j = 0; j < k; j++) {
+            if (!std::isfinite(w[j])) bad.store(1);
+            s += std::fabs((double)w[j]);
+        }
+        rs[i] = s;
+    });
+    if (bad.load()) return STB_ENONFINITE;
+    {
+        // column sums must add rows in ascending order: split the columns over the threads
+        const int chunks = std::min(nt, std::max(1, k / 256));
+        parallel_for(chunks, nt, [&](int64_t c) {
+            const int j0 = (int)((int64_t)k * c / chunks), j1 = (int)((int64_t)k * (c + 1) / chunks);
+            for (int i = 0; i < n; i++) {
+                const float* w = W + (size_t)i * k;
+                for (int j = j0; j < j1; j++) cs[j] += std::fabs((double)w[j]);
+            }
+        });
+    }
+    auto mu_at = [&](int i, int j) -> double {
+        const double a = std::fabs((double)W[(size_t)i * k + j]);
+        const double t1 = rs[i] > 0.0 ? a / rs[i] : 0.0;
+        const double t2 = cs[j] > 0.0 ? a / cs[j] : 0.0;
+        return t1 + t2;
+    };
+    std::vector<double> rowacc(n);
+    parallel_for(n, nt, [&](int64_t i) {
+        double s = 0.0;
+        for (int j = 0; j < k; j++) s += mu_at((int)i, j);
+        rowacc[i] = s;
+    });
+    double tot = 0.0;
+    for (int i = 0; i < n; i++) tot += rowacc[i];
+    const double mean = tot / ((double)n * (double)k);
+    parallel_for(n, nt, [&](int64_t i) {
+        double s = 0.0;
+        for (int j = 0; j < k; j++) {
+            const double d = mu_at((int)i, j) - mean;
+            s += d * d;
+        }
+        rowacc[i] = s;
+    });
+    tot = 0.0;
+    for (int i = 0; i < n; i++) tot += rowacc[i];
+    double sd = std::sqrt(tot / ((double)n * (double)k));
+    if (sd == 0.0) sd = 1.0;
+
+    // ---- N:M mask: the N highest scores of each group, equal scores keep the lower column ----
+    std::vector<uint8_t> keep((size_t)n * k);       // 0 / 1 per weight
+    parallel_for(n, nt, [&](int64_t i) {
+        uint8_t* kp = keep.data() + (size_t)i * k;
+        double sc[8];
+        for (int g = 0; g < k / M; g++) {
+            for (int p = 0; p < M; p++) {
+                const int j = g * M + p;
+                sc[p] = ((mu_at((int)i, j) - mean) / sd) * (double)xnorm[j];
+                kp[j] = 0;
+            }
+            for (int p = 0; p < M; p++) {
+                int better = 0;   // entries that rank before p
+                for (int o = 0; o < M; o++)
+                    if (sc[o] > sc[p] || (sc[o] == sc[p] && o < p)) better++;
+                if (better < N) kp[g * M + p] = 1;
+            }
+        }
+    });
+
+    // ---- per block: salient residual binarisation, break points, region ids, scales ----
+    std::vector<uint8_t> ids((size_t)n * k, 0);      // group id of each kept weight
+    std::vector<uint8_t> tpos((size_t)n * k, 0);     // residual sign is +1 (kept salient weights)
+    uint16_t* scales = out->scales;
+    uint16_t* res_scale = out->res_scale;
+    parallel_for(nb, nt, [&](int64_t q) {
+        const int c0 = (int)q * STB_BLOCK;
+        BlockScratch s;
+        s.start.resize(n + 1);
+        s.a.reserve((size_t)n * STB_BLOCK * N / M);
+        s.col.reserve((size_t)n * STB_BLOCK * N / M);
+        double mx = 0.0;
+        for (int i = 0; i < n; i++) {
+            const float* w = W + (size_t)i * k + c0;
+            const uint8_t* kp = keep.data() + (size_t)i * k + c0;
+            // salient part of this (row, block): Eq. 4
+            double so = 0.0;
+            int co = 0;
+            for (int c = 0; c < STB_BLOCK; c++)
+                if (kp[c] && sal_bit(sal_bitmap, c0 + c)) { so += std::fabs((double)w[c]); co++; }
+            const uint16_t ao16 = f64_to_f16_bits(co > 0 ? so / (double)co : 0.0);
+            const double ao = (double)f16_bits_to_f32(ao16);
+            double sr = 0.0;
+            for (int c = 0; c < STB_BLOCK; c++)
+                if (kp[c] && sal_bit(sal_bitmap, c0 + c)) {
+                    const double sg = w[c] >= 0.0f ? 1.0 : -1.0;
+                    const double r = (double)w[c] - ao * sg;
+                    sr += std::fabs(r);
+                    tpos[(size_t)i * k + c0 + c] = r >= 0.0 ? 1 : 0;
+                }
+            scales[((size_t)i * nb + q) * 4 + 3] = ao16;
+            res_scale[(size_t)i * nb + q] = f64_to_f16_bits(co > 0 ? sr / (double)co : 0.0);
+            // non-salient kept magnitudes
+            s.start[i] = (int32_t)s.a.size();
+            for (int c = 0; c < STB_BLOCK; c++)
+                if (kp[c] && !sal_bit(sal_bitmap, c0 + c)) {
+                    const double a = std::fabs((double)w[c]);
+                    s.a.push_back(a);
+                    s.col.push_back((uint8_t)c);
+                    if (a > mx) mx = a;
+                }
+        }
+        s.start[n] = (int32_t)s.a.size();
+
+        double p1 = 0.0, p2 = 0.0;
+        if (cfg.region_mode == 0) {
+            // Alg. 2 NonSalientAwareQuant: 160 candidates c_t = 0.1 + t*(0.8/159), p2 = 2*p1,
+            // skipped when p2 > 0.9*max; first strict minimum wins
+            const double step = (0.9 - 0.1) / 159.0;
+            double best = std::numeric_limits<double>::infinity();
+            for (int t = 0; t < 160; t++) {
+                const double c = (t == 159) ? 0.9 : (double)t * step + 0.1;
+                const double q1 = c * mx, q2 = 2.0 * q1;
+                if (q2 > 0.9 * mx) continue;
+                const double e = trisection_error(s, n, q1, q2);
+                if (e < best) { best = e; p1 = q1; p2 = q2; }
+            }
+        } else {
+            std::vector<double> sorted(s.a);
+            std::sort(sorted.begin(), sorted.end());
+            const size_t m = sorted.size();
+            if (m > 0) {
+                p1 = sorted[(m + 2) / 3 - 1];
+                p2 = sorted[(2 * m + 2) / 3 - 1];
+            }
+        }
+        for (int i = 0; i < n; i++) {
+            const double* a = s.a.data() + s.start[i];
+            const uint8_t* col = s.col.data() + s.start[i];
+            const int cnt = s.start[i + 1] - s.start[i];
+            double sum[3] = {0.0, 0.0, 0.0};
+            int c3[3] = {0, 0, 0};
+            for (int e = 0; e < cnt; e++) {
+                const int r = a[e] > p2 ? 2 : (a[e] > p1 ? 1 : 0);
+                sum[r] += a[e];
+                c3[r]++;
+                ids[(size_t)i * k + c0 + col[e]] = (uint8_t)r;
+            }
+            for (int r = 0; r < 3; r++)
+                scales[((size_t)i * nb + q) * 4 + r] = f64_to_f16_bits(c3[r] > 0 ? sum[r] / (double)c3[r] : 0.0);
+            const uint8_t* kp = keep.data() + (size_t)i * k + c0;
+            for (int c = 0; c < STB_BLOCK; c++)
+                if (kp[c] && sal_bit(sal_bitmap, c0 + c)) ids[(size_t)i * k + c0 + c] = 3;
+        }
+    });
+
+    // ---- bit planes ----
+    std::vector<int32_t> ordinal(k);   // index of column j among the salient columns
+    {
+        int u = 0;
+        for (int j = 0; j < k; j++) { ordinal[j] = u; u += sal_bit(sal_bitmap, j); }
+    }
+    std::atomic<int> badrow(0);
+    parallel_for(n, nt, [&](int64_t i) {
+        uint8_t* mrow = (uint8_t*)out->mask + (size_t)i * out->mask_stride;
+        uint8_t* srow = (uint8_t*)out->sign + (size_t)i * out->sign_stride;
+        uint8_t* rrow = (uint8_t*)out->region + (size_t)i * out->region_stride;
+        uint8_t* trow = cfg.n_salient ? (uint8_t*)out->res_sign + (size_t)i * out->res_stride : nullptr;
+        std::memset(mrow, 0, out->mask_stride);
+        std::memset(srow, 0, out->sign_stride);
+        std::memset(rrow, 0, out->region_stride);
+        if (trow) std::memset(trow, 0, out->res_stride);
+        const float* w = W + (size_t)i * k;
+        const uint8_t* kp = keep.data() + (size_t)i * k;
+        int slot = 0;
+        for (int j = 0; j < k; j++) {
+            if (!kp[j]) continue;
+            mrow[j >> 3] |= (uint8_t)(1u << (j & 7));
+            if (w[j] >= 0.0f) srow[slot >> 3] |= (uint8_t)(1u << (slot & 7));
+            const unsigned id = ids[(size_t)i * k + j];
+            rrow[slot >> 2] |= (uint8_t)(id << ((slot & 3) * 2));
+            if (id == 3 && tpos[(size_t)i * k + j]) {
+                const int u = ordinal[j];
+                trow[u >> 3] |= (uint8_t)(1u << (u & 7));
+            }
+            slot++;
+        }
+        if (slot != slots) badrow.store(1);
+    });
+    if (badrow.load()) return STB_EINVAL;
+    std::memcpy(out->sal_bitmap, sal_bitmap, (size_t)k / 8);
+    {
+        uint32_t run = 0;
+        for (int q = 0; q <= nb; q++) {
+            out->sal_block_prefix[q] = run;
+            if (q < nb)
+                for (int c = 0; c < STB_BLOCK; c++) run += sal_bit(sal_bitmap, q * STB_BLOCK + c);
+        }
+    }
+    return STB_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// host dequantiser
+// ------------------------------------------------------------------------------------------------
+extern "C" int stb_unpack(const stb_layout_t* L, float* W_hat) {
+    if (!W_hat) return STB_ENULL;
+    int rc = stb_layout_check(L);
+    if (rc) return rc;
+    const int n = L->cfg.n_out, k = L->cfg.k_in, nb = k / STB_BLOCK;
+    const int slots = k * L->cfg.N / L->cfg.M;
+    std::vector<int32_t> ordinal(k);
+    {
+        int u = 0;
+        for (int j = 0; j < k; j++) { ordinal[j] = u; u += sal_bit(L->sal_bitmap, j); }
+    }
+    for (int i = 0; i < n; i++) {
+        const uint8_t* mrow = (const uint8_t*)L->mask + (size_t)i * L->mask_stride;
+        const uint8_t* srow = (const uint8_t*)L->sign + (size_t)i * L->sign_stride;
+        const uint8_t* rrow = (const uint8_t*)L->region + (size_t)i * L->region_stride;
+        const uint8_t* trow = L->cfg.n_salient ? (const uint8_t*)L->res_sign + (size_t)i * L->res_stride : nullptr;
+        float* o = W_hat + (size_t)i * k;
+        int slot = 0;
+        for (int j = 0; j < k; j++) {
+            if (!((mrow[j >> 3] >> (j & 7)) & 1)) { o[j] = 0.0f; continue; }
+            if (slot >= slots) return STB_EINVAL;
+            const float s = ((srow[slot >> 3] >> (slot & 7)) & 1) ? 1.0f : -1.0f;
+            const unsigned id = (rrow[slot >> 2] >> ((slot & 3) * 2)) & 3u;
+            const int q = j / STB_BLOCK;
+            const float a = f16_bits_to_f32(L->scales[((size_t)i * nb + q) * 4 + id]);
+            if (id == 3) {
+                if (!trow) return STB_EINVAL;
+                const int u = ordinal[j];
+                const float t = ((trow[u >> 3] >> (u & 7)) & 1) ? 1.0f : -1.0f;
+                const float ar = f16_bits_to_f32(L->res_scale[(size_t)i * nb + q]);
+                o[j] = s * a + t * ar;
+            } else {
+                o[j] = s * a;
+            }
+            slot++;
+        }
+        if (slot != slots) return STB_EINVAL;
+    }
+    return STB_OK;
+}
+
+extern "C" const char* stb_strerror(int status) {
+    switch (status) {
+        case STB_OK: return "ok";
+        case STB_EINVAL: return "invalid configuration or argument";
+        case STB_ENULL: return "required pointer is NULL";
+        case STB_EALIGN: return "pointer is not sufficiently aligned";
+        case STB_ENONFINITE: return "NaN/Inf in W or xnorm, or negative xnorm";
+        case STB_EHIP: return "HIP call failed (see stb_last_hip_error)";
+        case STB_EUNSUPPORTED: return "no kernel for this configuration";
+        default: return "unknown status";
+    }
+}

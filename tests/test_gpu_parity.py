@@ -1,0 +1,237 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle.
+
+Bars: packed bytes and dequantised fp32 weights bit-exact; outputs within
+|y_gpu - y_oracle| <= 2e-3 * sum_j |x_j| |W_hat_ij| (and exactly 0 where that bound is 0).
+"""
+import hashlib
+import json
+import os
+import sys
+
+import numpy as np
+import pytest
+
+import paper_2408_01803_amd as S
+from oracle import stb_oracle as O
+from workloads import WORKLOADS, make_layer, make_x
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "packed_digests.json")
+
+
+def _say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert os.path.exists(S.LIB_PATH), "libstb.so is missing: build it before running the GPU tests"
+    assert torch.cuda.is_available(), "no GPU visible"
+    torch.cuda.set_device(0)
+    return torch
+
+
+def _within_bound(y_gpu, y_ref, bound, what):
+    y_gpu = np.asarray(y_gpu, dtype=np.float64)
+    err = np.abs(y_gpu - y_ref)
+    ok = err <= TOL * bound
+    if not ok.all():
+        idx = np.unravel_index(np.argmax(err - TOL * bound), err.shape)
+        raise AssertionError(f"{what}: {int((~ok).sum())} outputs outside 2e-3 of the row bound; worst at {idx}: "
+                             f"gpu {y_gpu[idx]} oracle {y_ref[idx]} bound {bound[idx]}")
+    return float((err / np.maximum(bound, 1e-300)).max())
+
+
+def _oracle_planes_from(pm):
+    """The library's host image re-read as the oracle's plane dictionary (shapes restored)."""
+    lay = pm.host_layout
+    n, nb = lay.cfg.n_out, lay.n_blocks
+    P = {}
+    P["mask"] = pm.plane("mask").reshape(n, lay.mask_stride)
+    P["sign"] = pm.plane("sign").reshape(n, lay.sign_stride)
+    P["region"] = pm.plane("region").reshape(n, lay.region_stride)
+    P["res_sign"] = pm.plane("res_sign").reshape(n, lay.res_stride)
+    P["scales"] = pm.plane("scales").view(np.float16).reshape(n, nb, 4)
+    P["res_scale"] = pm.plane("res_scale").view(np.float16).reshape(n, nb)
+    P["sal_bitmap"] = pm.plane("sal_bitmap").view("<u4")
+    P["sal_block_prefix"] = pm.plane("sal_block_prefix").view("<u4")
+    return P
+
+
+SMALL = [
+    # n, k, N, M, mode, kind, seed: several 64-row / 128-column tiles with ragged tails
+    (130, 640, 4, 8, 0, "x8", 101),
+    (257, 1024, 2, 4, 0, "t3", 102),
+    (200, 768, 6, 8, 1, "x8", 103),
+    (96, 512, 5, 8, 0, "x8", 104),
+    (64, 256, 8, 8, 0, "x8", 105),
+    (5, 128, 1, 4, 1, "x8", 106),
+]
+
+
+@pytest.fixture(scope="module", params=SMALL, ids=lambda c: f"{c[0]}x{c[1]}_{c[2]}of{c[3]}_m{c[4]}")
+def small_case(request, torch_cuda):
+    n, k, N, M, mode, kind, seed = request.param
+    _say(f"[case] small {request.param}")
+    L = make_layer(n, k, seed, kind)
+    ref = O.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode)
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode)
+    for name, v in ref.items():
+        assert (pm.plane(name) == np.ascontiguousarray(v).view(np.uint8).ravel()).all(), name
+    pm.to_device()
+    What = O.unpack(ref, n, k, N, M)
+    return dict(n=n, k=k, N=N, M=M, seed=seed, pm=pm, What=What)
+
+
+def test_dequant_bit_exact_small(small_case, torch_cuda):
+    torch = torch_cuda
+    c = small_case
+    out = torch.full((c["n"], c["k"]), float("nan"), dtype=torch.float32, device="cuda")
+    _say("[step] stb_dequant")
+    S.stb_dequant(c["pm"].dev_layout, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert (got.view(np.uint32) == c["What"].view(np.uint32)).all()
+
+
+@pytest.mark.parametrize("B", [1, 2, 3, 5, 8, 16, 31, 32])
+@pytest.mark.parametrize("y_fp32", [False, True])
+def test_gemv_small(small_case, torch_cuda, B, y_fp32):
+    torch = torch_cuda
+    c = small_case
+    x = make_x(B, c["k"], c["seed"])
+    y_ref, bound = O.matmul(x, c["What"])
+    xd = torch.from_numpy(x).cuda()
+    yd = torch.full((B, c["n"]), float("nan"), dtype=torch.float32 if y_fp32 else torch.float16, device="cuda")
+    _say(f"[step] stb_gemv B={B} fp32={y_fp32}")
+    S.stb_gemv(c["pm"].dev_layout, xd, B, yd, y_fp32)
+    torch.cuda.synchronize()
+    _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemv B={B}")
+
+
+@pytest.mark.parametrize("T", [1, 63, 64, 200, 333])
+def test_gemm_small(small_case, torch_cuda, T):
+    torch = torch_cuda
+    c = small_case
+    x = make_x(T, c["k"], c["seed"] + 1)
+    y_ref, bound = O.matmul(x, c["What"])
+    xd = torch.from_numpy(x).cuda()
+    for y_fp32 in (False, True):
+        yd = torch.full((T, c["n"]), float("nan"), dtype=torch.float32 if y_fp32 else torch.float16, device="cuda")
+        _say(f"[step] stb_gemm T={T} fp32={y_fp32}")
+        S.stb_gemm(c["pm"].dev_layout, xd, T, yd, y_fp32)
+        torch.cuda.synchronize()
+        _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T}")
+
+
+def test_zero_activations_and_zero_weights(torch_cuda):
+    torch = torch_cuda
+    n, k = 70, 256
+    L = make_layer(n, k, 7)
+    pm = S.PackedMatrix.pack(np.zeros((n, k), np.float32), L["xnorm"], L["sal_bitmap"], 4, 8, 0).to_device()
+    xd = torch.from_numpy(make_x(4, k, 7)).cuda()
+    yd = torch.full((4, n), float("nan"), dtype=torch.float16, device="cuda")
+    S.stb_gemv(pm.dev_layout, xd, 4, yd)
+    torch.cuda.synchronize()
+    assert (yd.cpu().numpy() == 0).all()
+    pm2 = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], 4, 8, 0).to_device()
+    yd = torch.full((4, n), float("nan"), dtype=torch.float32, device="cuda")
+    S.stb_gemv(pm2.dev_layout, torch.zeros_like(xd), 4, yd, True)
+    torch.cuda.synchronize()
+    assert (yd.cpu().numpy() == 0).all()
+
+
+def test_device_entry_points_reject_bad_arguments(torch_cuda):
+    torch = torch_cuda
+    L = make_layer(16, 128, 9)
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], 2, 4, 0).to_device()
+    xd = torch.zeros((33, 128), dtype=torch.float16, device="cuda")
+    yd = torch.zeros((33, 16), dtype=torch.float16, device="cuda")
+    for B in (0, 33, -1):
+        with pytest.raises(S.StbError) as e:
+            S.stb_gemv(pm.dev_layout, xd, B, yd)
+        assert e.value.status == S.STB_EINVAL
+    with pytest.raises(S.StbError) as e:
+        S.stb_gemm(pm.dev_layout, xd, 0, yd)
+    assert e.value.status == S.STB_EINVAL
+    unbound = S.stb_layout_sizes(pm.cfg)
+    with pytest.raises(S.StbError) as e:
+        S.stb_gemv(unbound, xd, 1, yd)
+    assert e.value.status == S.STB_ENULL
+
+
+# --------------------------------------------------------------------------------------------------
+# full-size workloads
+# --------------------------------------------------------------------------------------------------
+def _layer_key(cfg, spec):
+    return (f"cfg{cfg}_{spec.name}_{spec.n}x{spec.k}_{spec.N}of{spec.M}"
+            f"_mode{spec.region_mode}_{spec.salient_kind}_seed{spec.seed}")
+
+
+FULL = [(cfg, i) for cfg, wl in WORKLOADS.items() for i in range(len(wl["layers"]))]
+
+
+@pytest.mark.parametrize("cfg,idx", FULL, ids=lambda v: str(v))
+def test_full_size_layer(cfg, idx, torch_cuda):
+    """One layer of a workload at full size: the library's packed planes against the oracle's digests,
+    GPU dequantisation against the oracle's decode of those bytes, then every decode batch and prefill
+    length of the workload against the oracle's float64 product (prefill: on sampled tokens)."""
+    torch = torch_cuda
+    wl = WORKLOADS[cfg]
+    spec = wl["layers"][idx]
+    key = _layer_key(cfg, spec)
+    _say(f"[case] full {key}")
+    digests = json.load(open(GOLDEN)) if os.path.exists(GOLDEN) else {}
+    L = make_layer(spec.n, spec.k, spec.seed, spec.salient_kind)
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], spec.N, spec.M, spec.region_mode)
+    del L
+    if key not in digests:
+        pytest.skip(f"no oracle digest stored for {key}")
+    for name, _, _ in S.PLANE_FIELDS:
+        assert hashlib.sha256(pm.plane(name).tobytes()).hexdigest() == digests[key][name], name
+    assert pm.packed_bytes == digests[key]["total_bytes"]
+    _say("[step] packed planes match the oracle digests")
+
+    What = O.unpack(_oracle_planes_from(pm), spec.n, spec.k, spec.N, spec.M)
+    pm.to_device()
+    out = torch.empty((spec.n, spec.k), dtype=torch.float32, device="cuda")
+    _say("[step] stb_dequant")
+    S.stb_dequant(pm.dev_layout, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    del out
+    assert (got.view(np.uint32) == What.view(np.uint32)).all()
+    del got
+
+    W64 = What.astype(np.float64)
+    A64 = np.abs(W64)
+    for B in wl["decode_batches"]:
+        x = make_x(B, spec.k, spec.seed)
+        x64 = x.astype(np.float64)
+        y_ref, bound = x64 @ W64.T, np.abs(x64) @ A64.T
+        xd = torch.from_numpy(x).cuda()
+        yd = torch.full((B, spec.n), float("nan"), dtype=torch.float16, device="cuda")
+        _say(f"[step] stb_gemv B={B}")
+        S.stb_gemv(pm.dev_layout, xd, B, yd)
+        torch.cuda.synchronize()
+        worst = _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"{key} gemv B={B}")
+        _say(f"       worst error / bound = {worst:.2e}")
+    for T in wl["prefill_tokens"]:
+        x = make_x(T, spec.k, spec.seed)
+        rng = np.random.default_rng(spec.seed + T)
+        rows = np.unique(np.concatenate([[0, 1, 63, 64, T - 65, T - 2, T - 1], rng.integers(0, T, 57)]))
+        x64 = x[rows].astype(np.float64)
+        y_ref, bound = x64 @ W64.T, np.abs(x64) @ A64.T
+        xd = torch.from_numpy(x).cuda()
+        yd = torch.full((T, spec.n), float("nan"), dtype=torch.float16, device="cuda")
+        _say(f"[step] stb_gemm T={T}")
+        S.stb_gemm(pm.dev_layout, xd, T, yd)
+        torch.cuda.synchronize()
+        y = yd.float().cpu().numpy()
+        assert np.isfinite(y).all()
+        worst = _within_bound(y[rows], y_ref, bound, f"{key} gemm T={T}")
+        _say(f"       worst error / bound on {len(rows)} sampled tokens = {worst:.2e}")
