@@ -1,0 +1,232 @@
+"""Benchmark of the structured-binary hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one decode pass over workload 2 (the LLaMA-7B MLP linears 11008x4096 and 4096x11008 at 2:4 with
+the residual salient plane): stb_gemv at batch 1, 4 and 16 on both layers, i.e. six launches.  Each launch
+reads a different copy of the packed weights out of a pool of more than 1 GiB, so the weights come from
+HBM and not from the 256 MB last-level cache.  Inputs are resident in HBM before the timed region.
+`value` is packed-weight GB/s over the whole timed region (launch gaps included).
+
+After the timed decode steps the prefill leg (stb_gemm, workload 4 shapes at 4:8) and the CPU oracle are
+timed and reported in the same JSON line under "gemm" and "cpu_baseline".
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16/bf16 matrix peak, vendor figure
+POOL_BYTES = 1 << 30
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_pool(S, torch, pm, pool_bytes):
+    """Copies of one packed image in HBM, each with its own bound layout."""
+    copies = max(2, int(np.ceil(pool_bytes / pm.host_layout.image_bytes)))
+    stride = (pm.host_layout.image_bytes + S.STB_PLANE_ALIGN - 1) // S.STB_PLANE_ALIGN * S.STB_PLANE_ALIGN
+    buf = torch.empty(copies * stride + S.STB_PLANE_ALIGN, dtype=torch.uint8, device="cuda")
+    off = (-buf.data_ptr()) % S.STB_PLANE_ALIGN
+    src = torch.from_numpy(pm.host_image).cuda()
+    layouts = []
+    for c in range(copies):
+        view = buf[off + c * stride: off + c * stride + pm.host_layout.image_bytes]
+        view.copy_(src)
+        layouts.append(pm.clone_layout_for(view.data_ptr()))
+    return buf, layouts
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-gemm", action="store_true", help="skip the prefill leg")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    import paper_2408_01803_amd as S
+    from workloads import WORKLOADS, make_layer, make_x
+
+    if not os.path.exists(S.LIB_PATH):
+        sys.exit("bench.py: libstb.so is missing; run __graft_entry__.build() first")
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    prop = torch.cuda.get_device_properties(0)
+    log(f"device: {prop.name} {prop.gcnArchName} CUs={prop.multi_processor_count} "
+        f"mem={prop.total_memory >> 20} MiB  host cores={os.cpu_count()}")
+
+    # ---------------- decode leg: workload 2 ----------------
+    wl = WORKLOADS[2]
+    batches = wl["decode_batches"]
+    layers = []
+    for spec in wl["layers"]:
+        t0 = time.time()
+        L = make_layer(spec.n, spec.k, spec.seed, spec.salient_kind)
+        pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], spec.N, spec.M, spec.region_mode)
+        buf, layouts = build_pool(S, torch, pm, POOL_BYTES // len(wl["layers"]))
+        xs = {B: torch.from_numpy(make_x(B, spec.k, spec.seed)).cuda() for B in batches}
+        ys = {B: torch.empty((B, spec.n), dtype=torch.float16, device="cuda") for B in batches}
+        layers.append(dict(spec=spec, pm=pm, buf=buf, layouts=layouts, xs=xs, ys=ys, cursor=0))
+        log(f"packed {spec.name} {spec.n}x{spec.k} {spec.N}:{spec.M}: {pm.packed_bytes / 1e6:.2f} MB, "
+            f"{len(layouts)} copies, {time.time() - t0:.1f} s")
+        del L
+
+    def decode_step():
+        for B in batches:
+            for ly in layers:
+                lay = ly["layouts"][ly["cursor"]]
+                ly["cursor"] = (ly["cursor"] + 1) % len(ly["layouts"])
+                S.stb_gemv(lay, ly["xs"][B], B, ly["ys"][B])
+
+    launches_per_step = len(batches) * len(layers)
+    packed_per_step = sum(ly["pm"].packed_bytes for ly in layers) * len(batches)
+    algo_per_step = sum(ly["pm"].packed_bytes + 2 * B * ly["spec"].k + 2 * B * ly["spec"].n
+                        for ly in layers for B in batches)
+    for _ in range(a.warmup):
+        decode_step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(a.steps):
+        decode_step()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1)
+    ms_per_step = ms / a.steps
+    value = packed_per_step / (ms_per_step * 1e-3) / 1e9
+    launch_us = ms_per_step * 1e3 / launches_per_step
+    achieved = (algo_per_step / launches_per_step) / (launch_us * 1e-6) / 1e9
+    log(f"decode: {ms_per_step:.3f} ms/step, {launch_us:.1f} us/launch, {value:.1f} GB/s packed")
+
+    # per-(layer, B) breakdown, same protocol, untimed for the headline
+    breakdown = []
+    for ly in layers:
+        for B in batches:
+            reps = 40
+            for _ in range(3):
+                S.stb_gemv(ly["layouts"][0], ly["xs"][B], B, ly["ys"][B])
+            torch.cuda.synchronize()
+            ev0.record()
+            for r in range(reps):
+                S.stb_gemv(ly["layouts"][r % len(ly["layouts"])], ly["xs"][B], B, ly["ys"][B])
+            ev1.record()
+            torch.cuda.synchronize()
+            us = ev0.elapsed_time(ev1) * 1e3 / reps
+            breakdown.append(dict(layer=ly["spec"].name, B=B, us=round(us, 2),
+                                  packed_gbs=round(ly["pm"].packed_bytes / us / 1e3, 1)))
+    log("decode breakdown:", breakdown)
+
+    result = {
+        "metric": "packed-weight GB/s (GEMV) & TFLOP/s (GEMM), % of MI355X HBM/MFMA roofline",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: LLaMA-7B MLP linears 11008x4096 + 4096x11008, 2:4 structured binary "
+                               "with residual salient plane, decode GEMV at batch 1, 4, 16 (6 launches per step)",
+                   "packed_bytes_per_step": packed_per_step,
+                   "pool_bytes": int(sum(ly["buf"].numel() for ly in layers))},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "stb_gemv", "us_per_launch": round(launch_us, 2),
+                     "algorithmic_bytes_per_launch": int(algo_per_step / launches_per_step)},
+        "decode_breakdown": breakdown,
+    }
+
+    # ---------------- prefill leg: workload 4 shapes ----------------
+    if not a.no_gemm:
+        gemm = []
+        for spec, T, reps in ((WORKLOADS[4]["layers"][0], 2048, 10), (WORKLOADS[4]["layers"][1], 8192, 3)):
+            L = make_layer(spec.n, spec.k, spec.seed, spec.salient_kind)
+            pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], spec.N, spec.M, spec.region_mode)
+            pm.to_device()
+            del L
+            X = torch.from_numpy(make_x(T, spec.k, spec.seed)).cuda()
+            Y = torch.empty((T, spec.n), dtype=torch.float16, device="cuda")
+            for _ in range(2):
+                S.stb_gemm(pm.dev_layout, X, T, Y)
+            torch.cuda.synchronize()
+            ev0.record()
+            for _ in range(reps):
+                S.stb_gemm(pm.dev_layout, X, T, Y)
+            ev1.record()
+            torch.cuda.synchronize()
+            us = ev0.elapsed_time(ev1) * 1e3 / reps
+            flops = 2.0 * T * spec.n * spec.k
+            tf = flops / us / 1e6
+            gemm.append(dict(T=T, n=spec.n, k=spec.k, nm=f"{spec.N}:{spec.M}", us=round(us, 1),
+                             tflops=round(tf, 2), frac_of_f16_mfma_peak=round(tf / MFMA_F16_PEAK_TFLOPS, 4)))
+            log("gemm:", gemm[-1])
+            del pm, X, Y
+        best = max(gemm, key=lambda g: g["tflops"])
+        result["gemm"] = {"cases": gemm,
+                          "roofline": {"bound": "mfma", "achieved": best["tflops"], "peak": MFMA_F16_PEAK_TFLOPS,
+                                       "unit": "TFLOP/s", "frac": best["frac_of_f16_mfma_peak"], "traffic": None,
+                                       "kernel": "stb_gemm"}}
+
+    # ---------------- CPU baseline: the oracle as it stands, on this machine's host cores ----------------
+    if not a.no_cpu:
+        from oracle import stb_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        ly = layers[0]
+        spec, pm = ly["spec"], ly["pm"]
+        lay = pm.host_layout
+        planes = dict(
+            mask=pm.plane("mask").reshape(spec.n, lay.mask_stride),
+            sign=pm.plane("sign").reshape(spec.n, lay.sign_stride),
+            region=pm.plane("region").reshape(spec.n, lay.region_stride),
+            res_sign=pm.plane("res_sign").reshape(spec.n, lay.res_stride),
+            scales=pm.plane("scales").view(np.float16).reshape(spec.n, lay.n_blocks, 4),
+            res_scale=pm.plane("res_scale").view(np.float16).reshape(spec.n, lay.n_blocks),
+            sal_bitmap=pm.plane("sal_bitmap").view("<u4"),
+            sal_block_prefix=pm.plane("sal_block_prefix").view("<u4"))
+        t0 = time.time()
+        What = O.unpack(planes, spec.n, spec.k, spec.N, spec.M)
+        t_deq = time.time() - t0
+        t0 = time.time()
+        for B in batches:
+            O.matmul(ly["xs"][B].cpu().numpy(), What)
+        t_mm = time.time() - t0
+        # one decode pass over this layer = len(batches) products; the oracle dequantises once per product
+        total = len(batches) * t_deq + t_mm
+        result["cpu_baseline"] = {
+            "value": round(len(batches) * pm.packed_bytes / total / 1e9, 5), "unit": "GB/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": f"layer {spec.name} {spec.n}x{spec.k} only, batches {batches}: numpy dequantisation from the "
+                      f"packed bytes ({t_deq:.2f} s, measured once and charged per product) + float64 product "
+                      f"({t_mm:.2f} s for the three batches)"}
+        log("cpu baseline:", result["cpu_baseline"])
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -60,13 +60,16 @@ def main():
     ap.add_argument("--jobs", type=int, default=4)
     ap.add_argument("--only", nargs="*", default=None)
     ap.add_argument("--cache", default=None)
+    ap.add_argument("--force", action="store_true", help="recompute layers already in the output file")
     a = ap.parse_args()
+    done = set() if a.force or not os.path.exists(OUT) else set(json.load(open(OUT)))
     tasks = []
     for cfg, wl in WORKLOADS.items():
         if a.only and f"cfg{cfg}" not in a.only:
             continue
         for spec in wl["layers"]:
-            tasks.append((cfg, spec, a.cache))
+            if layer_key(cfg, spec) not in done:
+                tasks.append((cfg, spec, a.cache))
     tasks.sort(key=lambda t: -(t[1].n * t[1].k * (1 if t[1].region_mode == 0 else 0.05)))
     result = json.load(open(OUT)) if os.path.exists(OUT) else {}
     with mp.Pool(a.jobs, maxtasksperchild=1) as pool:
