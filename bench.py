@@ -34,18 +34,19 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_pool(S, torch, pm, pool_bytes):
-    """Copies of one packed image in HBM, each with its own bound layout."""
-    copies = max(2, int(np.ceil(pool_bytes / pm.host_layout.image_bytes)))
-    stride = (pm.host_layout.image_bytes + S.STB_PLANE_ALIGN - 1) // S.STB_PLANE_ALIGN * S.STB_PLANE_ALIGN
+def build_pool(S, torch, pm, pool_bytes, tiled=True):
+    """Copies of one packed image (tiled device order) in HBM, each with its own bound layout."""
+    lay, img = pm.host_pair(tiled)
+    copies = max(2, int(np.ceil(pool_bytes / lay.image_bytes)))
+    stride = (lay.image_bytes + S.STB_PLANE_ALIGN - 1) // S.STB_PLANE_ALIGN * S.STB_PLANE_ALIGN
     buf = torch.empty(copies * stride + S.STB_PLANE_ALIGN, dtype=torch.uint8, device="cuda")
     off = (-buf.data_ptr()) % S.STB_PLANE_ALIGN
-    src = torch.from_numpy(pm.host_image).cuda()
+    src = torch.from_numpy(img).cuda()
     layouts = []
     for c in range(copies):
-        view = buf[off + c * stride: off + c * stride + pm.host_layout.image_bytes]
+        view = buf[off + c * stride: off + c * stride + lay.image_bytes]
         view.copy_(src)
-        layouts.append(pm.clone_layout_for(view.data_ptr()))
+        layouts.append(pm.clone_layout_for(view.data_ptr(), tiled))
     return buf, layouts
 
 

@@ -77,22 +77,45 @@ typedef struct stb_cfg {
     int32_t region_mode;  /* 0 | 1, only read by stb_pack */
 } stb_cfg_t;
 
-/* Sizes, offsets and plane pointers of one packed matrix.  stb_layout_sizes fills everything except the
- * pointers; stb_layout_bind derives the pointers from one base address (host or device).  A caller may
- * also set the eight pointers by hand (each 16-byte aligned). */
+/* Sizes, offsets and plane pointers of one packed matrix.  stb_layout_sizes / stb_tiled_sizes fill
+ * everything except the pointers; stb_layout_bind derives the pointers from one base address (host or
+ * device).  A caller may also set the plane pointers by hand (each 16-byte aligned).
+ *
+ * kind = STB_KIND_ROWMAJOR: the planes exactly as described above ("STB1").
+ * kind = STB_KIND_TILED: the device order read by the fast kernels, a byte permutation of STB1 plus zero
+ * padding.  Rows are grouped in tiles of 16 and 128-column blocks in groups of 4 ("superblock", 512
+ * columns); a tile record holds one 64-lane wavefront's operands, lane = 16*(block % 4) + (row % 16):
+ *   mask      [row_tile][super][lane][16 bytes]         the 16 mask bytes of (row, block)
+ *   sign      [row_tile][super][lane][sign_stride]      sign bits of the block's 128*N/M kept weights
+ *   region    [row_tile][super][lane][region_stride]    their 2-bit ids
+ *   scales    [row_tile][super][lane][4] fp16, res_scale [row_tile][super][lane] fp16
+ *   res_sign  row-major as in STB1, rows padded to a multiple of 16
+ *   sal_bitmap / sal_block_prefix as in STB1, padded to whole superblocks
+ *   sal_pos   [super][sal_stride] uint16: columns (inside the superblock, 0..511) of its salient columns
+ *             in ascending order, 0xFFFF beyond the last one -- a derived table like sal_block_prefix.
+ * Rows >= n and blocks >= k/128 of the padding are all-zero (nothing kept). */
+#define STB_KIND_ROWMAJOR 0
+#define STB_KIND_TILED 1
+
 typedef struct stb_layout {
     stb_cfg_t cfg;
     int32_t n_salient_pad;     /* round_up(S, 128), 0 if S = 0 */
     int32_t n_blocks;          /* k / 128 */
-    int64_t mask_stride, sign_stride, region_stride, res_stride;          /* bytes per row */
+    int32_t kind;              /* STB_KIND_ROWMAJOR | STB_KIND_TILED */
+    int32_t n_row_tiles;       /* tiled: ceil(n / 16), else 0 */
+    int32_t n_super;           /* tiled: ceil(n_blocks / 4), else 0 */
+    int32_t sal_stride;        /* tiled: uint16 entries per superblock in sal_pos (multiple of 32), else 0 */
+    int32_t max_sal_super;     /* tiled: largest number of salient columns in one superblock (set by stb_tile) */
+    int32_t reserved;
+    int64_t mask_stride, sign_stride, region_stride, res_stride;   /* bytes per row (row-major) or per lane record (tiled; res_stride stays per row) */
     int64_t mask_bytes, sign_bytes, region_bytes, res_bytes,
-            scales_bytes, res_scale_bytes, salmap_bytes, salprefix_bytes;
-    int64_t total_bytes;       /* sum of the eight planes: the "packed bytes" that throughput is quoted on */
+            scales_bytes, res_scale_bytes, salmap_bytes, salprefix_bytes, salpos_bytes;
+    int64_t total_bytes;       /* sum of the planes of this layout; for STB_KIND_ROWMAJOR these are the "packed bytes" that throughput is quoted on */
     int64_t off_mask, off_sign, off_region, off_res, off_scales, off_res_scale,
-            off_salmap, off_salprefix;                                    /* offsets inside one image */
+            off_salmap, off_salprefix, off_salpos;                 /* offsets inside one image */
     int64_t image_bytes;       /* size of one allocation holding all planes at the offsets above */
     uint32_t *mask, *sign, *region, *res_sign, *sal_bitmap, *sal_block_prefix;
-    uint16_t *scales, *res_scale;
+    uint16_t *scales, *res_scale, *sal_pos;
 } stb_layout_t;
 
 /* Closed-form sizes and image offsets for `cfg` (Sec. 3.4 "Average Bits" gives the payload: N/M sign bits
@@ -103,6 +126,18 @@ int stb_layout_sizes(const stb_cfg_t* cfg, stb_layout_t* out);
 /* Point the eight plane pointers at base + off_*.  `base` is host or device memory of at least
  * image_bytes bytes, 256-byte aligned.  Errors: STB_ENULL, STB_EALIGN. */
 int stb_layout_bind(stb_layout_t* layout, void* base);
+
+/* Sizes and image offsets of the tiled device order for `cfg` (kind = STB_KIND_TILED).  `n_salient` columns
+ * may all fall into one superblock, so sal_stride is sized for that worst case: round_up(min(S, 512), 32).
+ * Errors: STB_ENULL, STB_EINVAL. */
+int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out);
+
+/* Host-side byte permutation STB1 -> tiled order (and back).  Both layouts must describe the same cfg and
+ * be bound to caller-allocated host memory; every byte of the destination is written.  stb_tile also fills
+ * dst->max_sal_super.  stb_untile(stb_tile(x)) == x bit for bit.
+ * Errors: STB_ENULL, STB_EINVAL (kind or cfg mismatch), STB_EALIGN. */
+int stb_tile(const stb_layout_t* src_rowmajor, stb_layout_t* dst_tiled);
+int stb_untile(const stb_layout_t* src_tiled, stb_layout_t* dst_rowmajor);
 
 /* Structured binarisation of one linear layer on the host (Alg. 1 without its Hessian steps: the salient
  * column set is an input and there is no error compensation between blocks):
@@ -124,12 +159,15 @@ int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_bitmap, stb
 int stb_unpack(const stb_layout_t* host, float* W_hat);
 
 /* Device dequantisation: same result as stb_unpack, bit for bit, written by a HIP kernel.
- * dev: layout bound to device memory holding a copy of the packed image.  W_hat_dev: device, n x k fp32.
+ * dev: layout (either kind) bound to device memory holding a copy of the packed image.  W_hat_dev: device,
+ * n x k fp32.
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
 int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream);
 
 /* Decode-time product (memory-bound regime, App. C "Theory Analysis": small N = batch):
  *   y[b][i] = sum_j x[b][j] * W_hat[i][j],  b < B <= 32.
+ * dev: either kind; the tiled kind runs the wavefront-tiled matrix-core kernel (N:M in {2:4, 4:8, 6:8}), the
+ * row-major kind a generic kernel for any N:M.
  * x: device fp16 [B][k] row-major.  y: device [B][n] row-major, fp16 (y_fp32 = 0) or fp32 (y_fp32 = 1),
  * fully overwritten.  Accumulation is fp32.
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */

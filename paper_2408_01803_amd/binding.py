@@ -38,20 +38,25 @@ class stb_cfg_t(C.Structure):
 
 class stb_layout_t(C.Structure):
     _fields_ = (
-        [("cfg", stb_cfg_t), ("n_salient_pad", C.c_int32), ("n_blocks", C.c_int32)]
+        [("cfg", stb_cfg_t)]
+        + [(name, C.c_int32) for name in (
+            "n_salient_pad", "n_blocks", "kind", "n_row_tiles", "n_super", "sal_stride", "max_sal_super",
+            "reserved")]
         + [(name, C.c_int64) for name in (
             "mask_stride", "sign_stride", "region_stride", "res_stride",
             "mask_bytes", "sign_bytes", "region_bytes", "res_bytes",
-            "scales_bytes", "res_scale_bytes", "salmap_bytes", "salprefix_bytes",
+            "scales_bytes", "res_scale_bytes", "salmap_bytes", "salprefix_bytes", "salpos_bytes",
             "total_bytes",
             "off_mask", "off_sign", "off_region", "off_res", "off_scales", "off_res_scale",
-            "off_salmap", "off_salprefix",
+            "off_salmap", "off_salprefix", "off_salpos",
             "image_bytes")]
         + [(name, C.c_void_p) for name in (
             "mask", "sign", "region", "res_sign", "sal_bitmap", "sal_block_prefix",
-            "scales", "res_scale")]
+            "scales", "res_scale", "sal_pos")]
     )
 
+
+STB_KIND_ROWMAJOR, STB_KIND_TILED = 0, 1
 
 PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_bytes"),
                 ("region", "off_region", "region_bytes"), ("res_sign", "off_res", "res_bytes"),
@@ -61,7 +66,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 
 _LIB = None
 
-EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_pack", "stb_unpack", "stb_dequant", "stb_gemv",
+EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_dequant", "stb_gemv",
            "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_strerror", "stb_last_hip_error")
 
 
@@ -77,6 +82,9 @@ def _lib():
     P = C.POINTER
     lib.stb_layout_sizes.argtypes = [P(stb_cfg_t), P(stb_layout_t)]
     lib.stb_layout_bind.argtypes = [P(stb_layout_t), C.c_void_p]
+    lib.stb_tiled_sizes.argtypes = [P(stb_cfg_t), P(stb_layout_t)]
+    lib.stb_tile.argtypes = [P(stb_layout_t), P(stb_layout_t)]
+    lib.stb_untile.argtypes = [P(stb_layout_t), P(stb_layout_t)]
     lib.stb_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32]
     lib.stb_unpack.argtypes = [P(stb_layout_t), C.c_void_p]
     lib.stb_dequant.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
@@ -90,7 +98,7 @@ def _lib():
     lib.stb_strerror.argtypes = [C.c_int]
     lib.stb_strerror.restype = C.c_char_p
     lib.stb_last_hip_error.restype = C.c_int
-    for name in ("stb_layout_sizes", "stb_layout_bind", "stb_pack", "stb_unpack", "stb_dequant",
+    for name in ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_dequant",
                  "stb_gemv", "stb_gemv_batched", "stb_gemm"):
         getattr(lib, name).restype = C.c_int
     _LIB = lib
@@ -123,6 +131,20 @@ def stb_layout_sizes(cfg: stb_cfg_t) -> stb_layout_t:
 def stb_layout_bind(layout: stb_layout_t, base_ptr: int) -> stb_layout_t:
     _check(_lib().stb_layout_bind(C.byref(layout), C.c_void_p(base_ptr)), "stb_layout_bind")
     return layout
+
+
+def stb_tiled_sizes(cfg: stb_cfg_t) -> stb_layout_t:
+    out = stb_layout_t()
+    _check(_lib().stb_tiled_sizes(C.byref(cfg), C.byref(out)), "stb_tiled_sizes")
+    return out
+
+
+def stb_tile(src_rowmajor: stb_layout_t, dst_tiled: stb_layout_t) -> None:
+    _check(_lib().stb_tile(C.byref(src_rowmajor), C.byref(dst_tiled)), "stb_tile")
+
+
+def stb_untile(src_tiled: stb_layout_t, dst_rowmajor: stb_layout_t) -> None:
+    _check(_lib().stb_untile(C.byref(src_tiled), C.byref(dst_rowmajor)), "stb_untile")
 
 
 def stb_pack(W: np.ndarray, xnorm: np.ndarray, sal_bitmap: np.ndarray, layout: stb_layout_t,
@@ -226,18 +248,33 @@ class PackedMatrix:
     def unpack(self) -> np.ndarray:
         return stb_unpack(self.host_layout)
 
-    def to_device(self, device="cuda:0"):
+    def tiled(self):
+        """(layout, image) of the tiled device order on the host, built once by stb_tile."""
+        if getattr(self, "_tiled", None) is None:
+            lay = stb_tiled_sizes(self.cfg)
+            img = aligned_bytes(lay.image_bytes)
+            stb_layout_bind(lay, img.ctypes.data)
+            stb_tile(self.host_layout, lay)
+            self._tiled = (lay, img)
+        return self._tiled
+
+    def host_pair(self, tiled: bool):
+        return self.tiled() if tiled else (self.host_layout, self.host_image)
+
+    def to_device(self, device="cuda:0", tiled: bool = False):
+        """Copies the row-major (tiled=False) or tiled image to HBM and binds `dev_layout` to it."""
         import torch
-        img = torch.from_numpy(self.host_image)
-        self.dev_image = torch.empty(self.host_layout.image_bytes + STB_PLANE_ALIGN, dtype=torch.uint8,
-                                     device=device)
+        lay, img = self.host_pair(tiled)
+        self.dev_image = torch.empty(lay.image_bytes + STB_PLANE_ALIGN, dtype=torch.uint8, device=device)
         off = (-self.dev_image.data_ptr()) % STB_PLANE_ALIGN
-        view = self.dev_image[off:off + self.host_layout.image_bytes]
-        view.copy_(img)
-        self.dev_layout = self.clone_layout_for(view.data_ptr())
+        view = self.dev_image[off:off + lay.image_bytes]
+        view.copy_(torch.from_numpy(img))
+        self.dev_layout = self.clone_layout_for(view.data_ptr(), tiled)
         return self
 
-    def clone_layout_for(self, base_ptr: int) -> stb_layout_t:
+    def clone_layout_for(self, base_ptr: int, tiled: bool = False) -> stb_layout_t:
         """Layout struct of the same matrix bound to another copy of the image (host or device)."""
-        lay = stb_layout_sizes(self.cfg)
+        src, _ = self.host_pair(tiled)
+        lay = stb_layout_t()
+        C.memmove(C.byref(lay), C.byref(src), C.sizeof(stb_layout_t))
         return stb_layout_bind(lay, base_ptr)

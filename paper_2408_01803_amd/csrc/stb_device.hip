@@ -265,6 +265,12 @@ extern "C" int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stre
     int rc = stb_layout_check(dev);
     if (rc) return rc;
     if ((uintptr_t)W_hat_dev % 16) return STB_EALIGN;
+    if (dev->kind == STB_KIND_TILED) {
+        int herr = 0;
+        rc = stb_tiled_dequant(dev, W_hat_dev, stream, &herr);
+        if (rc == STB_EHIP) g_last_hip_error = herr;
+        return rc;
+    }
     const Planes p = make_planes(dev);
     const int64_t threads = (int64_t)p.n * p.wpr;
     const int blocks = (int)((threads + 255) / 256);
@@ -280,6 +286,20 @@ extern "C" int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void*
     if (rc) return rc;
     if (B < 1 || B > STB_MAX_BATCH || (y_fp32 != 0 && y_fp32 != 1)) return STB_EINVAL;
     if ((uintptr_t)x % 16 || (uintptr_t)y % 4) return STB_EALIGN;
+    if (dev->kind == STB_KIND_TILED) {
+        // the matrix-core kernel takes up to 16 rows of x per launch
+        for (int done = 0; done < B; done += 16) {
+            const int nb = B - done < 16 ? B - done : 16;
+            const void* xb = (const __half*)x + (size_t)done * dev->cfg.k_in;
+            void* yb = y_fp32 ? (void*)((float*)y + (size_t)done * dev->cfg.n_out)
+                              : (void*)((__half*)y + (size_t)done * dev->cfg.n_out);
+            int herr = 0;
+            rc = stb_tiled_gemv(dev, xb, nb, yb, y_fp32, stream, &herr);
+            if (rc == STB_EHIP) g_last_hip_error = herr;
+            if (rc) return rc;
+        }
+        return STB_OK;
+    }
     const Planes p = make_planes(dev);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipSuccess;
@@ -325,6 +345,7 @@ extern "C" int stb_gemm(const stb_layout_t* dev, const void* X, int32_t T, void*
     if (rc) return rc;
     if (T < 1 || (y_fp32 != 0 && y_fp32 != 1)) return STB_EINVAL;
     if ((uintptr_t)X % 16 || (uintptr_t)Y % 4) return STB_EALIGN;
+    if (dev->kind != STB_KIND_ROWMAJOR) return STB_EUNSUPPORTED;
     const Planes p = make_planes(dev);
     dim3 grid((p.n + GN - 1) / GN, (T + GT - 1) / GT);
     hipLaunchKernelGGL(gemm_generic_kernel, grid, dim3(256), 0, (hipStream_t)stream, p, (const __half*)X, T,

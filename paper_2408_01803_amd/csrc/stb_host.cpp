@@ -92,12 +92,39 @@ inline bool sal_bit(const uint32_t* bm, int j) { return (bm[j >> 5] >> (j & 31))
 
 }  // namespace
 
+namespace {
+
+void place_planes(stb_layout_t* out) {
+    out->total_bytes = out->mask_bytes + out->sign_bytes + out->region_bytes + out->res_bytes +
+                       out->scales_bytes + out->res_scale_bytes + out->salmap_bytes + out->salprefix_bytes +
+                       out->salpos_bytes;
+    int64_t off = 0;
+    auto place = [&](int64_t bytes) {
+        int64_t o = off;
+        off = round_up(off + bytes, STB_PLANE_ALIGN);
+        return o;
+    };
+    out->off_mask = place(out->mask_bytes);
+    out->off_sign = place(out->sign_bytes);
+    out->off_region = place(out->region_bytes);
+    out->off_res = place(out->res_bytes);
+    out->off_scales = place(out->scales_bytes);
+    out->off_res_scale = place(out->res_scale_bytes);
+    out->off_salmap = place(out->salmap_bytes);
+    out->off_salprefix = place(out->salprefix_bytes);
+    out->off_salpos = place(out->salpos_bytes);
+    out->image_bytes = off;
+}
+
+}  // namespace
+
 extern "C" int stb_layout_sizes(const stb_cfg_t* cfg, stb_layout_t* out) {
     if (!out) return STB_ENULL;
     int rc = check_cfg(cfg);
     if (rc) return rc;
     std::memset(out, 0, sizeof(*out));
     out->cfg = *cfg;
+    out->kind = STB_KIND_ROWMAJOR;
     const int64_t n = cfg->n_out, k = cfg->k_in, nb = k / STB_BLOCK;
     const int64_t slots = k * cfg->N / cfg->M;
     out->n_blocks = (int32_t)nb;
@@ -114,23 +141,40 @@ extern "C" int stb_layout_sizes(const stb_cfg_t* cfg, stb_layout_t* out) {
     out->res_scale_bytes = n * nb * 2;
     out->salmap_bytes = k / 8;
     out->salprefix_bytes = 4 * (nb + 1);
-    out->total_bytes = out->mask_bytes + out->sign_bytes + out->region_bytes + out->res_bytes +
-                       out->scales_bytes + out->res_scale_bytes + out->salmap_bytes + out->salprefix_bytes;
-    int64_t off = 0;
-    auto place = [&](int64_t bytes) {
-        int64_t o = off;
-        off = round_up(off + bytes, STB_PLANE_ALIGN);
-        return o;
-    };
-    out->off_mask = place(out->mask_bytes);
-    out->off_sign = place(out->sign_bytes);
-    out->off_region = place(out->region_bytes);
-    out->off_res = place(out->res_bytes);
-    out->off_scales = place(out->scales_bytes);
-    out->off_res_scale = place(out->res_scale_bytes);
-    out->off_salmap = place(out->salmap_bytes);
-    out->off_salprefix = place(out->salprefix_bytes);
-    out->image_bytes = off;
+    out->salpos_bytes = 0;
+    place_planes(out);
+    return STB_OK;
+}
+
+extern "C" int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out) {
+    if (!out) return STB_ENULL;
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    std::memset(out, 0, sizeof(*out));
+    out->cfg = *cfg;
+    out->kind = STB_KIND_TILED;
+    const int64_t n = cfg->n_out, k = cfg->k_in, nb = k / STB_BLOCK;
+    const int64_t nrt = (n + 15) / 16, nsb = (nb + 3) / 4;
+    const int64_t rec = nrt * nsb * 64;                          // lane records
+    out->n_blocks = (int32_t)nb;
+    out->n_row_tiles = (int32_t)nrt;
+    out->n_super = (int32_t)nsb;
+    out->n_salient_pad = cfg->n_salient > 0 ? (int32_t)round_up(cfg->n_salient, 128) : 0;
+    out->sal_stride = cfg->n_salient > 0 ? (int32_t)round_up(std::min<int64_t>(cfg->n_salient, 512), 32) : 0;
+    out->mask_stride = 16;
+    out->sign_stride = 16 * cfg->N / cfg->M;                     // 128*N/M sign bits per block
+    out->region_stride = 32 * cfg->N / cfg->M;
+    out->res_stride = out->n_salient_pad / 8;
+    out->mask_bytes = rec * out->mask_stride;
+    out->sign_bytes = rec * out->sign_stride;
+    out->region_bytes = rec * out->region_stride;
+    out->res_bytes = nrt * 16 * out->res_stride;
+    out->scales_bytes = rec * 8;
+    out->res_scale_bytes = rec * 2;
+    out->salmap_bytes = nsb * 4 * 16;
+    out->salprefix_bytes = 4 * (nsb * 4 + 1);
+    out->salpos_bytes = nsb * out->sal_stride * 2;
+    place_planes(out);
     return STB_OK;
 }
 
@@ -146,6 +190,7 @@ extern "C" int stb_layout_bind(stb_layout_t* L, void* base) {
     L->res_scale = (uint16_t*)(b + L->off_res_scale);
     L->sal_bitmap = (uint32_t*)(b + L->off_salmap);
     L->sal_block_prefix = (uint32_t*)(b + L->off_salprefix);
+    L->sal_pos = (uint16_t*)(b + L->off_salpos);
     return STB_OK;
 }
 
@@ -154,20 +199,110 @@ extern "C" int stb_layout_bind(stb_layout_t* L, void* base) {
 extern "C" int stb_layout_check(const stb_layout_t* L) {
     if (!L) return STB_ENULL;
     stb_layout_t ref;
-    int rc = stb_layout_sizes(&L->cfg, &ref);
+    int rc;
+    if (L->kind == STB_KIND_ROWMAJOR) rc = stb_layout_sizes(&L->cfg, &ref);
+    else if (L->kind == STB_KIND_TILED) rc = stb_tiled_sizes(&L->cfg, &ref);
+    else rc = STB_EINVAL;
     if (rc) return rc;
     if (L->n_salient_pad != ref.n_salient_pad || L->n_blocks != ref.n_blocks ||
+        L->n_row_tiles != ref.n_row_tiles || L->n_super != ref.n_super || L->sal_stride != ref.sal_stride ||
         L->mask_stride != ref.mask_stride || L->sign_stride != ref.sign_stride ||
         L->region_stride != ref.region_stride || L->res_stride != ref.res_stride ||
         L->total_bytes != ref.total_bytes)
         return STB_EINVAL;
-    const void* ptrs[8] = {L->mask, L->sign, L->region, L->res_sign, L->scales, L->res_scale,
-                           L->sal_bitmap, L->sal_block_prefix};
-    for (int i = 0; i < 8; i++) {
-        if (i == 3 && L->cfg.n_salient == 0) continue;   // res_sign may be absent
+    if (L->kind == STB_KIND_TILED && (L->max_sal_super < 0 || L->max_sal_super > L->sal_stride)) return STB_EINVAL;
+    const void* ptrs[9] = {L->mask, L->sign, L->region, L->res_sign, L->scales, L->res_scale,
+                           L->sal_bitmap, L->sal_block_prefix, L->sal_pos};
+    for (int i = 0; i < 9; i++) {
+        if ((i == 3 || i == 8) && L->cfg.n_salient == 0) continue;   // res_sign / sal_pos may be absent
+        if (i == 8 && L->kind == STB_KIND_ROWMAJOR) continue;
         if (!ptrs[i]) return STB_ENULL;
         if ((uintptr_t)ptrs[i] % 16) return STB_EALIGN;
     }
+    return STB_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// STB1 <-> tiled device order (byte permutation plus zero padding)
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+bool same_cfg(const stb_cfg_t& a, const stb_cfg_t& b) {
+    return a.n_out == b.n_out && a.k_in == b.k_in && a.N == b.N && a.M == b.M && a.block == b.block &&
+           a.n_salient == b.n_salient;
+}
+
+// Copies every (row, block) record between the two orders; to_tiled selects the direction.
+void permute_records(const stb_layout_t* rm, const stb_layout_t* tl, bool to_tiled) {
+    const int n = rm->cfg.n_out, nb = rm->n_blocks, nsb = tl->n_super;
+    const int64_t SB = tl->sign_stride, RB = tl->region_stride;
+    uint8_t* rmask = (uint8_t*)rm->mask; uint8_t* tmask = (uint8_t*)tl->mask;
+    uint8_t* rsign = (uint8_t*)rm->sign; uint8_t* tsign = (uint8_t*)tl->sign;
+    uint8_t* rreg = (uint8_t*)rm->region; uint8_t* treg = (uint8_t*)tl->region;
+    auto mv = [&](uint8_t* a_rm, uint8_t* a_tl, int64_t bytes) {
+        if (to_tiled) std::memcpy(a_tl, a_rm, bytes); else std::memcpy(a_rm, a_tl, bytes);
+    };
+    for (int r = 0; r < n; r++)
+        for (int q = 0; q < nb; q++) {
+            const int64_t rec = ((int64_t)(r / 16) * nsb + q / 4) * 64 + 16 * (q % 4) + (r % 16);
+            mv(rmask + (int64_t)r * rm->mask_stride + 16 * q, tmask + rec * 16, 16);
+            mv(rsign + (int64_t)r * rm->sign_stride + SB * q, tsign + rec * SB, SB);
+            mv(rreg + (int64_t)r * rm->region_stride + RB * q, treg + rec * RB, RB);
+            mv((uint8_t*)(rm->scales + ((int64_t)r * nb + q) * 4), (uint8_t*)(tl->scales + rec * 4), 8);
+            mv((uint8_t*)(rm->res_scale + (int64_t)r * nb + q), (uint8_t*)(tl->res_scale + rec), 2);
+        }
+    if (rm->cfg.n_salient)
+        for (int r = 0; r < n; r++)
+            mv((uint8_t*)rm->res_sign + (int64_t)r * rm->res_stride,
+               (uint8_t*)tl->res_sign + (int64_t)r * tl->res_stride, rm->res_stride);
+}
+
+}  // namespace
+
+extern "C" int stb_tile(const stb_layout_t* src, stb_layout_t* dst) {
+    int rc = stb_layout_check(src);
+    if (rc) return rc;
+    if (!dst) return STB_ENULL;
+    dst->max_sal_super = 0;
+    rc = stb_layout_check(dst);
+    if (rc) return rc;
+    if (src->kind != STB_KIND_ROWMAJOR || dst->kind != STB_KIND_TILED || !same_cfg(src->cfg, dst->cfg))
+        return STB_EINVAL;
+    std::memset(dst->mask, 0, dst->mask_bytes);
+    std::memset(dst->sign, 0, dst->sign_bytes);
+    std::memset(dst->region, 0, dst->region_bytes);
+    if (dst->res_bytes) std::memset(dst->res_sign, 0, dst->res_bytes);
+    std::memset(dst->scales, 0, dst->scales_bytes);
+    std::memset(dst->res_scale, 0, dst->res_scale_bytes);
+    std::memset(dst->sal_bitmap, 0, dst->salmap_bytes);
+    permute_records(src, dst, true);
+    const int nb = src->n_blocks, nsb = dst->n_super, k = src->cfg.k_in;
+    std::memcpy(dst->sal_bitmap, src->sal_bitmap, src->salmap_bytes);
+    for (int q = 0; q <= nsb * 4; q++) dst->sal_block_prefix[q] = src->sal_block_prefix[std::min(q, nb)];
+    int mx = 0;
+    for (int sb = 0; sb < nsb; sb++) {
+        int c = 0;
+        for (int j = sb * 512; j < std::min(k, (sb + 1) * 512); j++)
+            if (sal_bit(src->sal_bitmap, j)) dst->sal_pos[(int64_t)sb * dst->sal_stride + c++] = (uint16_t)(j - sb * 512);
+        mx = std::max(mx, c);
+        for (; c < dst->sal_stride; c++) dst->sal_pos[(int64_t)sb * dst->sal_stride + c] = 0xFFFFu;
+    }
+    dst->max_sal_super = mx;
+    return STB_OK;
+}
+
+extern "C" int stb_untile(const stb_layout_t* src, stb_layout_t* dst) {
+    int rc = stb_layout_check(src);
+    if (rc) return rc;
+    rc = stb_layout_check(dst);
+    if (rc) return rc;
+    if (src->kind != STB_KIND_TILED || dst->kind != STB_KIND_ROWMAJOR || !same_cfg(src->cfg, dst->cfg))
+        return STB_EINVAL;
+    std::memset(dst->sign, 0, dst->sign_bytes);       // row padding of the sign / region planes
+    std::memset(dst->region, 0, dst->region_bytes);
+    permute_records(dst, src, false);
+    std::memcpy(dst->sal_bitmap, src->sal_bitmap, dst->salmap_bytes);
+    for (int q = 0; q <= dst->n_blocks; q++) dst->sal_block_prefix[q] = src->sal_block_prefix[q];
     return STB_OK;
 }
 
@@ -215,6 +350,7 @@ extern "C" int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_
     if (!W || !xnorm || !sal_bitmap || !out) return STB_ENULL;
     int rc = stb_layout_check(out);
     if (rc) return rc;
+    if (out->kind != STB_KIND_ROWMAJOR) return STB_EINVAL;
     const stb_cfg_t cfg = out->cfg;
     const int n = cfg.n_out, k = cfg.k_in, N = cfg.N, M = cfg.M, nb = k / STB_BLOCK;
     const int slots = k * N / M;
@@ -441,6 +577,7 @@ extern "C" int stb_unpack(const stb_layout_t* L, float* W_hat) {
     if (!W_hat) return STB_ENULL;
     int rc = stb_layout_check(L);
     if (rc) return rc;
+    if (L->kind != STB_KIND_ROWMAJOR) return STB_EINVAL;
     const int n = L->cfg.n_out, k = L->cfg.k_in, nb = k / STB_BLOCK;
     const int slots = k * L->cfg.N / L->cfg.M;
     std::vector<int32_t> ordinal(k);

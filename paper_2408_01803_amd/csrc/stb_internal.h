@@ -9,6 +9,12 @@ extern "C" {
 // STB_OK iff the size fields agree with the closed form for L->cfg and every required plane pointer is
 // set and 16-byte aligned.
 int stb_layout_check(const stb_layout_t* L);
+
+// Kernels for the tiled device order (stb_fast.hip).  Each returns a stb_status and stores the HIP error
+// code of a failed launch in *hip_err.  stb_tiled_supported: 1 iff the fast kernels cover this N:M.
+int stb_tiled_supported(const stb_layout_t* L);
+int stb_tiled_dequant(const stb_layout_t* L, float* out, void* stream, int* hip_err);
+int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* stream, int* hip_err);
 #ifdef __cplusplus
 }
 #endif

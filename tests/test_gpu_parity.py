@@ -73,18 +73,26 @@ SMALL = [
 ]
 
 
-@pytest.fixture(scope="module", params=SMALL, ids=lambda c: f"{c[0]}x{c[1]}_{c[2]}of{c[3]}_m{c[4]}")
+def _tiled_ok(N, M):
+    return (8 * N) % M == 0 and (8 * N // M) in (4, 6)
+
+
+SMALL_KINDS = [(c, tiled) for c in SMALL for tiled in (False, True) if not tiled or _tiled_ok(c[2], c[3])]
+
+
+@pytest.fixture(scope="module", params=SMALL_KINDS,
+                ids=lambda c: f"{c[0][0]}x{c[0][1]}_{c[0][2]}of{c[0][3]}_m{c[0][4]}_{'tiled' if c[1] else 'rowmajor'}")
 def small_case(request, torch_cuda):
-    n, k, N, M, mode, kind, seed = request.param
+    (n, k, N, M, mode, kind, seed), tiled = request.param
     _say(f"[case] small {request.param}")
     L = make_layer(n, k, seed, kind)
     ref = O.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode)
     pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode)
     for name, v in ref.items():
         assert (pm.plane(name) == np.ascontiguousarray(v).view(np.uint8).ravel()).all(), name
-    pm.to_device()
+    pm.to_device(tiled=tiled)
     What = O.unpack(ref, n, k, N, M)
-    return dict(n=n, k=k, N=N, M=M, seed=seed, pm=pm, What=What)
+    return dict(n=n, k=k, N=N, M=M, seed=seed, pm=pm, What=What, tiled=tiled)
 
 
 def test_dequant_bit_exact_small(small_case, torch_cuda):
@@ -117,6 +125,8 @@ def test_gemv_small(small_case, torch_cuda, B, y_fp32):
 def test_gemm_small(small_case, torch_cuda, T):
     torch = torch_cuda
     c = small_case
+    if c["tiled"]:
+        pytest.skip("prefill kernel for the tiled order: not built yet")
     x = make_x(T, c["k"], c["seed"] + 1)
     y_ref, bound = O.matmul(x, c["What"])
     xd = torch.from_numpy(x).cuda()

@@ -139,3 +139,44 @@ def test_packer_edge_cases_zero_matrix_no_salient_and_all_salient_block():
     for name, v in _oracle_bytes(ref).items():
         assert (pm.plane(name) == v).all(), name
     assert (pm.unpack() == O.unpack(ref, 9, k, 6, 8)).all()
+
+
+@pytest.mark.parametrize("n,k,N,M,mode,kind,seed", CASES)
+def test_tile_untile_round_trip_is_a_byte_permutation(n, k, N, M, mode, kind, seed):
+    L = make_layer(n, k, seed, kind)
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode)
+    tl, timg = pm.tiled()
+    assert tl.kind == S.STB_KIND_TILED and tl.n_row_tiles == (n + 15) // 16 and tl.n_super == (k // 128 + 3) // 4
+    # same multiset of payload bytes: sorted bytes of each per-row plane agree up to zero padding
+    for name, off, size in (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_bytes"),
+                            ("region", "off_region", "region_bytes"), ("scales", "off_scales", "scales_bytes"),
+                            ("res_scale", "off_res_scale", "res_scale_bytes")):
+        a = np.sort(pm.plane(name))
+        b = np.sort(timg[getattr(tl, off):getattr(tl, off) + getattr(tl, size)])
+        a, b = a[a != 0], b[b != 0]
+        assert a.shape == b.shape and (a == b).all(), name
+    back = S.PackedMatrix(pm.cfg)
+    back.host_image[:] = 0xAB
+    S.stb_untile(tl, back.host_layout)
+    for name, _, _ in S.PLANE_FIELDS:
+        assert (back.plane(name) == pm.plane(name)).all(), name
+    # sal_pos lists the salient columns of each superblock in ascending order
+    if len(L["sal_cols"]):
+        pos = timg[tl.off_salpos:tl.off_salpos + tl.salpos_bytes].view(np.uint16).reshape(tl.n_super, tl.sal_stride)
+        cols = [int(sb) * 512 + int(p) for sb in range(tl.n_super) for p in pos[sb] if p != 0xFFFF]
+        assert cols == L["sal_cols"].tolist()
+        assert tl.max_sal_super == max((pos[sb] != 0xFFFF).sum() for sb in range(tl.n_super))
+
+
+def test_tile_rejects_mismatched_layouts():
+    L = make_layer(16, 128, 3)
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], 2, 4)
+    other = S.stb_tiled_sizes(S.make_cfg(32, 128, 2, 4, pm.cfg.n_salient))
+    img = S.aligned_bytes(other.image_bytes)
+    S.stb_layout_bind(other, img.ctypes.data)
+    with pytest.raises(S.StbError) as e:
+        S.stb_tile(pm.host_layout, other)
+    assert e.value.status == S.STB_EINVAL
+    with pytest.raises(S.StbError) as e:
+        S.stb_tile(pm.host_layout, pm.host_layout)
+    assert e.value.status == S.STB_EINVAL
