@@ -207,15 +207,25 @@ def test_full_size_layer(cfg, idx, torch_cuda):
     _say("[step] packed planes match the oracle digests")
 
     What = O.unpack(_oracle_planes_from(pm), spec.n, spec.k, spec.N, spec.M)
-    pm.to_device()
-    out = torch.empty((spec.n, spec.k), dtype=torch.float32, device="cuda")
-    _say("[step] stb_dequant")
-    S.stb_dequant(pm.dev_layout, out)
-    torch.cuda.synchronize()
-    got = out.cpu().numpy()
-    del out
-    assert (got.view(np.uint32) == What.view(np.uint32)).all()
-    del got
+    tiled = _tiled_ok(spec.N, spec.M)
+    row_major = S.PackedMatrix.__new__(S.PackedMatrix)
+    row_major.__dict__.update(pm.__dict__)
+    row_major.to_device(tiled=False)
+    if tiled:
+        pm.to_device(tiled=True)
+    else:
+        pm = row_major
+    for which, holder in (("row-major", row_major), ("tiled", pm if tiled else None)):
+        if holder is None:
+            continue
+        out = torch.empty((spec.n, spec.k), dtype=torch.float32, device="cuda")
+        _say(f"[step] stb_dequant {which}")
+        S.stb_dequant(holder.dev_layout, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        del out
+        assert (got.view(np.uint32) == What.view(np.uint32)).all(), which
+        del got
 
     W64 = What.astype(np.float64)
     A64 = np.abs(W64)
@@ -239,7 +249,7 @@ def test_full_size_layer(cfg, idx, torch_cuda):
         xd = torch.from_numpy(x).cuda()
         yd = torch.full((T, spec.n), float("nan"), dtype=torch.float16, device="cuda")
         _say(f"[step] stb_gemm T={T}")
-        S.stb_gemm(pm.dev_layout, xd, T, yd)
+        S.stb_gemm(row_major.dev_layout, xd, T, yd)
         torch.cuda.synchronize()
         y = yd.float().cpu().numpy()
         assert np.isfinite(y).all()
