@@ -89,10 +89,20 @@ typedef struct stb_cfg {
  *   sign      [row_tile][super][lane][sign_stride]      sign bits of the block's 128*N/M kept weights
  *   region    [row_tile][super][lane][region_stride]    their 2-bit ids
  *   scales    [row_tile][super][lane][4] fp16, res_scale [row_tile][super][lane] fp16
- *   res_sign  row-major as in STB1, rows padded to a multiple of 16
+ *   res_sign  [row_tile][word][row % 16] uint32: the STB1 row strings cut into 32-bit words and transposed
+ *             inside each row tile (res_stride / 4 words per row)
  *   sal_bitmap / sal_block_prefix as in STB1, padded to whole superblocks
- *   sal_pos   [super][sal_stride] uint16: columns (inside the superblock, 0..511) of its salient columns
- *             in ascending order, 0xFFFF beyond the last one -- a derived table like sal_block_prefix.
+ *   sal_tab   [block][sal_chunks] records of 12 uint32, a derived table like sal_block_prefix.  Record c of
+ *             a block covers entries 8c .. 8c+7 of the ascending list of the block's salient columns
+ *             (entry e at column p_e of the block, byte p_e >> 3 and bit p_e & 7 of the 16 mask bytes):
+ *               [0] selA0 [1] selB0   v_perm_b32 selectors that gather the mask bytes of entries 0..3 from
+ *                                     mask words {1,0} (selA) and {3,2} (selB); 0x0C (zero) where the byte
+ *                                     lies in the other pair or the entry does not exist
+ *               [2] selA1 [3] selB1   the same for entries 4..7
+ *               [4] bit0  [5] bit1    one byte per entry: 1 << (p_e & 7), 0 if the entry does not exist
+ *               [6] number of entries in this record (0..8)
+ *               [7] largest number of records any block of this superblock needs
+ *               [8..11] uint16 p_e of the 8 entries, 0xFFFF if the entry does not exist
  * Rows >= n and blocks >= k/128 of the padding are all-zero (nothing kept). */
 #define STB_KIND_ROWMAJOR 0
 #define STB_KIND_TILED 1
@@ -104,18 +114,18 @@ typedef struct stb_layout {
     int32_t kind;              /* STB_KIND_ROWMAJOR | STB_KIND_TILED */
     int32_t n_row_tiles;       /* tiled: ceil(n / 16), else 0 */
     int32_t n_super;           /* tiled: ceil(n_blocks / 4), else 0 */
-    int32_t sal_stride;        /* tiled: uint16 entries per superblock in sal_pos (multiple of 32), else 0 */
-    int32_t max_sal_super;     /* tiled: largest number of salient columns in one superblock (set by stb_tile) */
+    int32_t sal_chunks;        /* tiled: records per block in sal_tab = ceil(min(S, 128) / 8), else 0 */
+    int32_t max_sal_block;     /* tiled: largest number of salient columns in one block (set by stb_tile) */
     int32_t reserved;
     int64_t mask_stride, sign_stride, region_stride, res_stride;   /* bytes per row (row-major) or per lane record (tiled; res_stride stays per row) */
     int64_t mask_bytes, sign_bytes, region_bytes, res_bytes,
-            scales_bytes, res_scale_bytes, salmap_bytes, salprefix_bytes, salpos_bytes;
+            scales_bytes, res_scale_bytes, salmap_bytes, salprefix_bytes, saltab_bytes;
     int64_t total_bytes;       /* sum of the planes of this layout; for STB_KIND_ROWMAJOR these are the "packed bytes" that throughput is quoted on */
     int64_t off_mask, off_sign, off_region, off_res, off_scales, off_res_scale,
-            off_salmap, off_salprefix, off_salpos;                 /* offsets inside one image */
+            off_salmap, off_salprefix, off_saltab;                 /* offsets inside one image */
     int64_t image_bytes;       /* size of one allocation holding all planes at the offsets above */
-    uint32_t *mask, *sign, *region, *res_sign, *sal_bitmap, *sal_block_prefix;
-    uint16_t *scales, *res_scale, *sal_pos;
+    uint32_t *mask, *sign, *region, *res_sign, *sal_bitmap, *sal_block_prefix, *sal_tab;
+    uint16_t *scales, *res_scale;
 } stb_layout_t;
 
 /* Closed-form sizes and image offsets for `cfg` (Sec. 3.4 "Average Bits" gives the payload: N/M sign bits
@@ -128,13 +138,13 @@ int stb_layout_sizes(const stb_cfg_t* cfg, stb_layout_t* out);
 int stb_layout_bind(stb_layout_t* layout, void* base);
 
 /* Sizes and image offsets of the tiled device order for `cfg` (kind = STB_KIND_TILED).  `n_salient` columns
- * may all fall into one superblock, so sal_stride is sized for that worst case: round_up(min(S, 512), 32).
+ * may all fall into one block, so sal_chunks is sized for that worst case.
  * Errors: STB_ENULL, STB_EINVAL. */
 int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out);
 
 /* Host-side byte permutation STB1 -> tiled order (and back).  Both layouts must describe the same cfg and
  * be bound to caller-allocated host memory; every byte of the destination is written.  stb_tile also fills
- * dst->max_sal_super.  stb_untile(stb_tile(x)) == x bit for bit.
+ * dst->max_sal_block.  stb_untile(stb_tile(x)) == x bit for bit.
  * Errors: STB_ENULL, STB_EINVAL (kind or cfg mismatch), STB_EALIGN. */
 int stb_tile(const stb_layout_t* src_rowmajor, stb_layout_t* dst_tiled);
 int stb_untile(const stb_layout_t* src_tiled, stb_layout_t* dst_rowmajor);

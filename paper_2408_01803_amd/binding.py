@@ -40,19 +40,19 @@ class stb_layout_t(C.Structure):
     _fields_ = (
         [("cfg", stb_cfg_t)]
         + [(name, C.c_int32) for name in (
-            "n_salient_pad", "n_blocks", "kind", "n_row_tiles", "n_super", "sal_stride", "max_sal_super",
+            "n_salient_pad", "n_blocks", "kind", "n_row_tiles", "n_super", "sal_chunks", "max_sal_block",
             "reserved")]
         + [(name, C.c_int64) for name in (
             "mask_stride", "sign_stride", "region_stride", "res_stride",
             "mask_bytes", "sign_bytes", "region_bytes", "res_bytes",
-            "scales_bytes", "res_scale_bytes", "salmap_bytes", "salprefix_bytes", "salpos_bytes",
+            "scales_bytes", "res_scale_bytes", "salmap_bytes", "salprefix_bytes", "saltab_bytes",
             "total_bytes",
             "off_mask", "off_sign", "off_region", "off_res", "off_scales", "off_res_scale",
-            "off_salmap", "off_salprefix", "off_salpos",
+            "off_salmap", "off_salprefix", "off_saltab",
             "image_bytes")]
         + [(name, C.c_void_p) for name in (
-            "mask", "sign", "region", "res_sign", "sal_bitmap", "sal_block_prefix",
-            "scales", "res_scale", "sal_pos")]
+            "mask", "sign", "region", "res_sign", "sal_bitmap", "sal_block_prefix", "sal_tab",
+            "scales", "res_scale")]
     )
 
 

@@ -97,7 +97,7 @@ namespace {
 void place_planes(stb_layout_t* out) {
     out->total_bytes = out->mask_bytes + out->sign_bytes + out->region_bytes + out->res_bytes +
                        out->scales_bytes + out->res_scale_bytes + out->salmap_bytes + out->salprefix_bytes +
-                       out->salpos_bytes;
+                       out->saltab_bytes;
     int64_t off = 0;
     auto place = [&](int64_t bytes) {
         int64_t o = off;
@@ -112,7 +112,7 @@ void place_planes(stb_layout_t* out) {
     out->off_res_scale = place(out->res_scale_bytes);
     out->off_salmap = place(out->salmap_bytes);
     out->off_salprefix = place(out->salprefix_bytes);
-    out->off_salpos = place(out->salpos_bytes);
+    out->off_saltab = place(out->saltab_bytes);
     out->image_bytes = off;
 }
 
@@ -141,7 +141,7 @@ extern "C" int stb_layout_sizes(const stb_cfg_t* cfg, stb_layout_t* out) {
     out->res_scale_bytes = n * nb * 2;
     out->salmap_bytes = k / 8;
     out->salprefix_bytes = 4 * (nb + 1);
-    out->salpos_bytes = 0;
+    out->saltab_bytes = 0;
     place_planes(out);
     return STB_OK;
 }
@@ -160,7 +160,7 @@ extern "C" int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out) {
     out->n_row_tiles = (int32_t)nrt;
     out->n_super = (int32_t)nsb;
     out->n_salient_pad = cfg->n_salient > 0 ? (int32_t)round_up(cfg->n_salient, 128) : 0;
-    out->sal_stride = cfg->n_salient > 0 ? (int32_t)round_up(std::min<int64_t>(cfg->n_salient, 512), 32) : 0;
+    out->sal_chunks = cfg->n_salient > 0 ? (int32_t)((std::min<int64_t>(cfg->n_salient, 128) + 7) / 8) : 0;
     out->mask_stride = 16;
     out->sign_stride = 16 * cfg->N / cfg->M;                     // 128*N/M sign bits per block
     out->region_stride = 32 * cfg->N / cfg->M;
@@ -173,7 +173,7 @@ extern "C" int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out) {
     out->res_scale_bytes = rec * 2;
     out->salmap_bytes = nsb * 4 * 16;
     out->salprefix_bytes = 4 * (nsb * 4 + 1);
-    out->salpos_bytes = nsb * out->sal_stride * 2;
+    out->saltab_bytes = nsb * 4 * out->sal_chunks * 48;
     place_planes(out);
     return STB_OK;
 }
@@ -190,7 +190,7 @@ extern "C" int stb_layout_bind(stb_layout_t* L, void* base) {
     L->res_scale = (uint16_t*)(b + L->off_res_scale);
     L->sal_bitmap = (uint32_t*)(b + L->off_salmap);
     L->sal_block_prefix = (uint32_t*)(b + L->off_salprefix);
-    L->sal_pos = (uint16_t*)(b + L->off_salpos);
+    L->sal_tab = (uint32_t*)(b + L->off_saltab);
     return STB_OK;
 }
 
@@ -205,16 +205,16 @@ extern "C" int stb_layout_check(const stb_layout_t* L) {
     else rc = STB_EINVAL;
     if (rc) return rc;
     if (L->n_salient_pad != ref.n_salient_pad || L->n_blocks != ref.n_blocks ||
-        L->n_row_tiles != ref.n_row_tiles || L->n_super != ref.n_super || L->sal_stride != ref.sal_stride ||
+        L->n_row_tiles != ref.n_row_tiles || L->n_super != ref.n_super || L->sal_chunks != ref.sal_chunks ||
         L->mask_stride != ref.mask_stride || L->sign_stride != ref.sign_stride ||
         L->region_stride != ref.region_stride || L->res_stride != ref.res_stride ||
         L->total_bytes != ref.total_bytes)
         return STB_EINVAL;
-    if (L->kind == STB_KIND_TILED && (L->max_sal_super < 0 || L->max_sal_super > L->sal_stride)) return STB_EINVAL;
+    if (L->kind == STB_KIND_TILED && (L->max_sal_block < 0 || L->max_sal_block > 8 * L->sal_chunks)) return STB_EINVAL;
     const void* ptrs[9] = {L->mask, L->sign, L->region, L->res_sign, L->scales, L->res_scale,
-                           L->sal_bitmap, L->sal_block_prefix, L->sal_pos};
+                           L->sal_bitmap, L->sal_block_prefix, L->sal_tab};
     for (int i = 0; i < 9; i++) {
-        if ((i == 3 || i == 8) && L->cfg.n_salient == 0) continue;   // res_sign / sal_pos may be absent
+        if ((i == 3 || i == 8) && L->cfg.n_salient == 0) continue;   // res_sign / sal_tab may be absent
         if (i == 8 && L->kind == STB_KIND_ROWMAJOR) continue;
         if (!ptrs[i]) return STB_ENULL;
         if ((uintptr_t)ptrs[i] % 16) return STB_EALIGN;
@@ -251,10 +251,59 @@ void permute_records(const stb_layout_t* rm, const stb_layout_t* tl, bool to_til
             mv((uint8_t*)(rm->scales + ((int64_t)r * nb + q) * 4), (uint8_t*)(tl->scales + rec * 4), 8);
             mv((uint8_t*)(rm->res_scale + (int64_t)r * nb + q), (uint8_t*)(tl->res_scale + rec), 2);
         }
-    if (rm->cfg.n_salient)
+    if (rm->cfg.n_salient) {
+        const int words = (int)(rm->res_stride / 4);
         for (int r = 0; r < n; r++)
-            mv((uint8_t*)rm->res_sign + (int64_t)r * rm->res_stride,
-               (uint8_t*)tl->res_sign + (int64_t)r * tl->res_stride, rm->res_stride);
+            for (int w = 0; w < words; w++)
+                mv((uint8_t*)rm->res_sign + (int64_t)r * rm->res_stride + 4 * w,
+                   (uint8_t*)tl->res_sign + (((int64_t)(r / 16) * words + w) * 16 + r % 16) * 4, 4);
+    }
+}
+
+// Fills the derived table of salient columns (layout in stb.h); returns the largest count of one block.
+int fill_sal_tab(const stb_layout_t* tl, const uint32_t* bitmap, int k) {
+    const int nsb = tl->n_super, C = tl->sal_chunks;
+    int mx = 0;
+    std::vector<int> cols;
+    for (int sb = 0; sb < nsb; sb++) {
+        int need = 0;
+        for (int g = 0; g < 4; g++) {
+            int c = 0;
+            for (int j = (4 * sb + g) * 128; j < std::min(k, (4 * sb + g + 1) * 128); j++) c += sal_bit(bitmap, j);
+            need = std::max(need, (c + 7) / 8);
+            mx = std::max(mx, c);
+        }
+        for (int g = 0; g < 4; g++) {
+            const int q = 4 * sb + g;
+            cols.clear();
+            for (int j = q * 128; j < std::min(k, (q + 1) * 128); j++)
+                if (sal_bit(bitmap, j)) cols.push_back(j - q * 128);
+            for (int c = 0; c < C; c++) {
+                uint32_t* rec = tl->sal_tab + ((int64_t)q * C + c) * 12;
+                uint32_t sel[4] = {0, 0, 0, 0}, bit[2] = {0, 0};
+                uint16_t* pos = reinterpret_cast<uint16_t*>(rec + 8);
+                int cnt = 0;
+                for (int e = 0; e < 8; e++) {
+                    const int idx = 8 * c + e;
+                    const bool valid = idx < (int)cols.size();
+                    const uint32_t p = valid ? (uint32_t)cols[idx] : 0xFFFFu;
+                    const uint32_t byte = p >> 3;                      // 0..15 if valid
+                    const uint32_t a = valid && byte < 8 ? byte : 0x0Cu;
+                    const uint32_t b = valid && byte >= 8 ? byte - 8 : 0x0Cu;
+                    sel[2 * (e >> 2)] |= a << (8 * (e & 3));
+                    sel[2 * (e >> 2) + 1] |= b << (8 * (e & 3));
+                    if (valid) bit[e >> 2] |= (1u << (p & 7u)) << (8 * (e & 3));
+                    pos[e] = (uint16_t)p;
+                    cnt += valid;
+                }
+                rec[0] = sel[0]; rec[1] = sel[1]; rec[2] = sel[2]; rec[3] = sel[3];
+                rec[4] = bit[0]; rec[5] = bit[1];
+                rec[6] = (uint32_t)cnt;
+                rec[7] = (uint32_t)need;
+            }
+        }
+    }
+    return mx;
 }
 
 }  // namespace
@@ -263,7 +312,7 @@ extern "C" int stb_tile(const stb_layout_t* src, stb_layout_t* dst) {
     int rc = stb_layout_check(src);
     if (rc) return rc;
     if (!dst) return STB_ENULL;
-    dst->max_sal_super = 0;
+    dst->max_sal_block = 0;
     rc = stb_layout_check(dst);
     if (rc) return rc;
     if (src->kind != STB_KIND_ROWMAJOR || dst->kind != STB_KIND_TILED || !same_cfg(src->cfg, dst->cfg))
@@ -279,15 +328,8 @@ extern "C" int stb_tile(const stb_layout_t* src, stb_layout_t* dst) {
     const int nb = src->n_blocks, nsb = dst->n_super, k = src->cfg.k_in;
     std::memcpy(dst->sal_bitmap, src->sal_bitmap, src->salmap_bytes);
     for (int q = 0; q <= nsb * 4; q++) dst->sal_block_prefix[q] = src->sal_block_prefix[std::min(q, nb)];
-    int mx = 0;
-    for (int sb = 0; sb < nsb; sb++) {
-        int c = 0;
-        for (int j = sb * 512; j < std::min(k, (sb + 1) * 512); j++)
-            if (sal_bit(src->sal_bitmap, j)) dst->sal_pos[(int64_t)sb * dst->sal_stride + c++] = (uint16_t)(j - sb * 512);
-        mx = std::max(mx, c);
-        for (; c < dst->sal_stride; c++) dst->sal_pos[(int64_t)sb * dst->sal_stride + c] = 0xFFFFu;
-    }
-    dst->max_sal_super = mx;
+    const int mx = dst->cfg.n_salient ? fill_sal_tab(dst, src->sal_bitmap, k) : 0;
+    dst->max_sal_block = mx;
     return STB_OK;
 }
 

@@ -160,12 +160,34 @@ def test_tile_untile_round_trip_is_a_byte_permutation(n, k, N, M, mode, kind, se
     S.stb_untile(tl, back.host_layout)
     for name, _, _ in S.PLANE_FIELDS:
         assert (back.plane(name) == pm.plane(name)).all(), name
-    # sal_pos lists the salient columns of each superblock in ascending order
+    # res_sign: the row strings cut into 32-bit words, transposed inside each 16-row tile
+    if tl.res_bytes:
+        words = tl.res_stride // 4
+        t = timg[tl.off_res:tl.off_res + tl.res_bytes].view("<u4").reshape(tl.n_row_tiles, words, 16)
+        rm = np.zeros((tl.n_row_tiles * 16, words), "<u4")
+        rm[:n] = pm.plane("res_sign").view("<u4").reshape(n, words)
+        assert (t.transpose(0, 2, 1).reshape(-1, words) == rm).all()
+    # sal_tab: per block, records of 8 salient columns with the selectors that gather their mask bytes
     if len(L["sal_cols"]):
-        pos = timg[tl.off_salpos:tl.off_salpos + tl.salpos_bytes].view(np.uint16).reshape(tl.n_super, tl.sal_stride)
-        cols = [int(sb) * 512 + int(p) for sb in range(tl.n_super) for p in pos[sb] if p != 0xFFFF]
+        C = tl.sal_chunks
+        rec = timg[tl.off_saltab:tl.off_saltab + tl.saltab_bytes].view("<u4").reshape(tl.n_super * 4, C, 12)
+        pos = rec[:, :, 8:12].copy().view("<u2").reshape(tl.n_super * 4, C * 8)
+        cols = [int(q) * 128 + int(p) for q in range(tl.n_super * 4) for p in pos[q] if p != 0xFFFF]
         assert cols == L["sal_cols"].tolist()
-        assert tl.max_sal_super == max((pos[sb] != 0xFFFF).sum() for sb in range(tl.n_super))
+        per_block = (pos != 0xFFFF).sum(axis=1)
+        assert tl.max_sal_block == per_block.max()
+        assert (rec[:, :, 6] == (pos.reshape(-1, C, 8) != 0xFFFF).sum(axis=2)).all()
+        need = ((per_block + 7) // 8).reshape(tl.n_super, 4).max(axis=1)
+        assert (rec[:, :, 7] == np.repeat(need, 4)[:, None]).all()
+        sel = rec[:, :, 0:4].copy().view(np.uint8).reshape(tl.n_super * 4, C, 2, 2, 4)   # [half][A|B][entry]
+        bit = rec[:, :, 4:6].copy().view(np.uint8).reshape(tl.n_super * 4, C, 2, 4)
+        p = pos.reshape(tl.n_super * 4, C, 2, 4).astype(np.int64)
+        valid = p != 0xFFFF
+        byte = p >> 3
+        expA = np.where(valid & (byte < 8), byte, 0x0C)
+        expB = np.where(valid & (byte >= 8), byte - 8, 0x0C)
+        assert (sel[:, :, :, 0, :] == expA).all() and (sel[:, :, :, 1, :] == expB).all()
+        assert (bit == np.where(valid, 1 << (p & 7), 0)).all()
 
 
 def test_tile_rejects_mismatched_layouts():
