@@ -84,7 +84,8 @@ def main():
         buf, layouts = build_pool(S, torch, pm, POOL_BYTES // len(wl["layers"]))
         xs = {B: torch.from_numpy(make_x(B, spec.k, spec.seed)).cuda() for B in batches}
         ys = {B: torch.empty((B, spec.n), dtype=torch.float16, device="cuda") for B in batches}
-        layers.append(dict(spec=spec, pm=pm, buf=buf, layouts=layouts, xs=xs, ys=ys, cursor=0))
+        layers.append(dict(spec=spec, pm=pm, buf=buf, layouts=layouts, xs=xs, ys=ys, cursor=0,
+                           ws=pm.new_workspace()))
         log(f"packed {spec.name} {spec.n}x{spec.k} {spec.N}:{spec.M}: {pm.packed_bytes / 1e6:.2f} MB, "
             f"{len(layouts)} copies, {time.time() - t0:.1f} s")
         del L
@@ -94,7 +95,7 @@ def main():
             for ly in layers:
                 lay = ly["layouts"][ly["cursor"]]
                 ly["cursor"] = (ly["cursor"] + 1) % len(ly["layouts"])
-                S.stb_gemv(lay, ly["xs"][B], B, ly["ys"][B])
+                S.stb_gemv(lay, ly["xs"][B], B, ly["ys"][B], False, ly["ws"])
 
     launches_per_step = len(batches) * len(layers)
     packed_per_step = sum(ly["pm"].packed_bytes for ly in layers) * len(batches)
@@ -122,11 +123,11 @@ def main():
         for B in batches:
             reps = 40
             for _ in range(3):
-                S.stb_gemv(ly["layouts"][0], ly["xs"][B], B, ly["ys"][B])
+                S.stb_gemv(ly["layouts"][0], ly["xs"][B], B, ly["ys"][B], False, ly["ws"])
             torch.cuda.synchronize()
             ev0.record()
             for r in range(reps):
-                S.stb_gemv(ly["layouts"][r % len(ly["layouts"])], ly["xs"][B], B, ly["ys"][B])
+                S.stb_gemv(ly["layouts"][r % len(ly["layouts"])], ly["xs"][B], B, ly["ys"][B], False, ly["ws"])
             ev1.record()
             torch.cuda.synchronize()
             us = ev0.elapsed_time(ev1) * 1e3 / reps

@@ -176,18 +176,29 @@ int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream);
 
 /* Decode-time product (memory-bound regime, App. C "Theory Analysis": small N = batch):
  *   y[b][i] = sum_j x[b][j] * W_hat[i][j],  b < B <= 32.
- * dev: either kind; the tiled kind runs the wavefront-tiled matrix-core kernel (N:M in {2:4, 4:8, 6:8}), the
- * row-major kind a generic kernel for any N:M.
+ * dev: either kind; the tiled kind runs the wavefront-tiled matrix-core kernel (N:M in {2:4, 4:8, 6:8}; it
+ * assumes the stored scales are >= 0, as stb_pack writes them), the row-major kind a generic kernel for any
+ * N:M.
  * x: device fp16 [B][k] row-major.  y: device [B][n] row-major, fp16 (y_fp32 = 0) or fp32 (y_fp32 = 1),
  * fully overwritten.  Accumulation is fp32.
+ * workspace: device scratch of at least stb_gemv_workspace_bytes() bytes, 256-byte aligned (may be NULL when
+ * that is 0).  It holds the partial sums and arrival counters of the column splits used when k > 4096.  The
+ * counters (its first 4 * ceil(n / 16) bytes) must be zero before the first call that uses the buffer; every
+ * call leaves them zero.  Calls that share a workspace must not overlap in time.
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
-int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32, void* stream);
+int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32,
+             void* workspace, int64_t workspace_bytes, void* stream);
+
+/* Scratch bytes stb_gemv needs for (cfg, B), for either kind of layout; negative stb_status on a bad
+ * argument. */
+int64_t stb_gemv_workspace_bytes(const stb_cfg_t* cfg, int32_t B);
 
 /* Several independent layers with the same B in one launch sequence on one stream (q/k/v or gate/up
- * share x in a decoder layer).  dev, x, y: host arrays of n_layers pointers.
+ * share x in a decoder layer).  dev, x, y: host arrays of n_layers pointers.  The layers run one after
+ * another and share `workspace`, which must cover the largest stb_gemv_workspace_bytes() among them.
  * Errors: as stb_gemv; the first failing layer stops the sequence. */
 int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const void* const* x, int32_t B,
-                     void* const* y, int32_t y_fp32, void* stream);
+                     void* const* y, int32_t y_fp32, void* workspace, int64_t workspace_bytes, void* stream);
 
 /* Prefill-time product (compute-bound regime, App. C: large N = batch x sequence length):
  *   Y[t][i] = sum_j X[t][j] * W_hat[i][j],  t < T.

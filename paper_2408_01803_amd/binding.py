@@ -67,7 +67,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 _LIB = None
 
 EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_dequant", "stb_gemv",
-           "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_strerror", "stb_last_hip_error")
+           "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_strerror", "stb_last_hip_error")
 
 
 def _lib():
@@ -88,9 +88,12 @@ def _lib():
     lib.stb_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32]
     lib.stb_unpack.argtypes = [P(stb_layout_t), C.c_void_p]
     lib.stb_dequant.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
-    lib.stb_gemv.argtypes = [P(stb_layout_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.stb_gemv.argtypes = [P(stb_layout_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                             C.c_int64, C.c_void_p]
+    lib.stb_gemv_workspace_bytes.argtypes = [P(stb_cfg_t), C.c_int32]
+    lib.stb_gemv_workspace_bytes.restype = C.c_int64
     lib.stb_gemv_batched.argtypes = [C.c_int32, P(P(stb_layout_t)), P(C.c_void_p), C.c_int32,
-                                     P(C.c_void_p), C.c_int32, C.c_void_p]
+                                     P(C.c_void_p), C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
     lib.stb_gemm.argtypes = [P(stb_layout_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
                              C.c_void_p, C.c_int64, C.c_void_p]
     lib.stb_gemm_workspace_bytes.argtypes = [P(stb_cfg_t), C.c_int32]
@@ -176,21 +179,37 @@ def stb_dequant(layout_dev: stb_layout_t, out_dev, stream=None) -> None:
                               C.c_void_p(_stream_ptr(stream))), "stb_dequant")
 
 
-def stb_gemv(layout_dev: stb_layout_t, x_dev, B: int, y_dev, y_fp32: bool = False, stream=None) -> None:
+def _ws(workspace):
+    if workspace is None:
+        return C.c_void_p(0), 0
+    return C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def stb_gemv_workspace_bytes(cfg: stb_cfg_t, B: int) -> int:
+    r = _lib().stb_gemv_workspace_bytes(C.byref(cfg), B)
+    if r < 0:
+        raise StbError(int(r), "stb_gemv_workspace_bytes")
+    return int(r)
+
+
+def stb_gemv(layout_dev: stb_layout_t, x_dev, B: int, y_dev, y_fp32: bool = False, workspace=None,
+             stream=None) -> None:
+    ws_ptr, ws_bytes = _ws(workspace)
     _check(_lib().stb_gemv(C.byref(layout_dev), C.c_void_p(x_dev.data_ptr()), B,
-                           C.c_void_p(y_dev.data_ptr()), int(y_fp32), C.c_void_p(_stream_ptr(stream))),
-           "stb_gemv")
+                           C.c_void_p(y_dev.data_ptr()), int(y_fp32), ws_ptr, ws_bytes,
+                           C.c_void_p(_stream_ptr(stream))), "stb_gemv")
 
 
 def stb_gemv_batched(layouts_dev: Sequence[stb_layout_t], xs_dev, B: int, ys_dev, y_fp32: bool = False,
-                     stream=None) -> None:
+                     workspace=None, stream=None) -> None:
     n = len(layouts_dev)
     LP = C.POINTER(stb_layout_t)
     lay = (LP * n)(*[C.pointer(l) for l in layouts_dev])
     xs = (C.c_void_p * n)(*[x.data_ptr() for x in xs_dev])
     ys = (C.c_void_p * n)(*[y.data_ptr() for y in ys_dev])
-    _check(_lib().stb_gemv_batched(n, lay, xs, B, ys, int(y_fp32), C.c_void_p(_stream_ptr(stream))),
-           "stb_gemv_batched")
+    ws_ptr, ws_bytes = _ws(workspace)
+    _check(_lib().stb_gemv_batched(n, lay, xs, B, ys, int(y_fp32), ws_ptr, ws_bytes,
+                                   C.c_void_p(_stream_ptr(stream))), "stb_gemv_batched")
 
 
 def stb_gemm_workspace_bytes(cfg: stb_cfg_t, T: int) -> int:
@@ -270,7 +289,18 @@ class PackedMatrix:
         view = self.dev_image[off:off + lay.image_bytes]
         view.copy_(torch.from_numpy(img))
         self.dev_layout = self.clone_layout_for(view.data_ptr(), tiled)
+        self.workspace = self.new_workspace(device)
         return self
+
+    def new_workspace(self, device="cuda:0"):
+        """Zero-filled stb_gemv scratch for this matrix (None if the shape needs none), 256-byte aligned."""
+        import torch
+        need = stb_gemv_workspace_bytes(self.cfg, STB_MAX_BATCH)
+        if need == 0:
+            return None
+        raw = torch.zeros(need + STB_PLANE_ALIGN, dtype=torch.uint8, device=device)
+        off = (-raw.data_ptr()) % STB_PLANE_ALIGN
+        return raw[off:off + need]
 
     def clone_layout_for(self, base_ptr: int, tiled: bool = False) -> stb_layout_t:
         """Layout struct of the same matrix bound to another copy of the image (host or device)."""

@@ -279,12 +279,20 @@ extern "C" int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stre
     return e == hipSuccess ? STB_OK : hip_fail(e);
 }
 
+extern "C" int64_t stb_gemv_workspace_bytes(const stb_cfg_t* cfg, int32_t B) {
+    stb_layout_t tmp;
+    int rc = stb_tiled_sizes(cfg, &tmp);
+    if (rc) return rc;
+    if (B < 1 || B > STB_MAX_BATCH) return STB_EINVAL;
+    return stb_tiled_gemv_workspace(tmp.n_row_tiles, tmp.n_super);
+}
+
 extern "C" int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32,
-                        void* stream) {
+                        void* workspace, int64_t workspace_bytes, void* stream) {
     if (!x || !y) return STB_ENULL;
     int rc = stb_layout_check(dev);
     if (rc) return rc;
-    if (B < 1 || B > STB_MAX_BATCH || (y_fp32 != 0 && y_fp32 != 1)) return STB_EINVAL;
+    if (B < 1 || B > STB_MAX_BATCH || (y_fp32 != 0 && y_fp32 != 1) || workspace_bytes < 0) return STB_EINVAL;
     if ((uintptr_t)x % 16 || (uintptr_t)y % 4) return STB_EALIGN;
     if (dev->kind == STB_KIND_TILED) {
         // the matrix-core kernel takes up to 16 rows of x per launch
@@ -294,7 +302,7 @@ extern "C" int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void*
             void* yb = y_fp32 ? (void*)((float*)y + (size_t)done * dev->cfg.n_out)
                               : (void*)((__half*)y + (size_t)done * dev->cfg.n_out);
             int herr = 0;
-            rc = stb_tiled_gemv(dev, xb, nb, yb, y_fp32, stream, &herr);
+            rc = stb_tiled_gemv(dev, xb, nb, yb, y_fp32, workspace, workspace_bytes, stream, &herr);
             if (rc == STB_EHIP) g_last_hip_error = herr;
             if (rc) return rc;
         }
@@ -318,11 +326,12 @@ extern "C" int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void*
 }
 
 extern "C" int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const void* const* x,
-                                int32_t B, void* const* y, int32_t y_fp32, void* stream) {
+                                int32_t B, void* const* y, int32_t y_fp32, void* workspace,
+                                int64_t workspace_bytes, void* stream) {
     if (!dev || !x || !y) return STB_ENULL;
     if (n_layers < 1) return STB_EINVAL;
     for (int l = 0; l < n_layers; l++) {
-        int rc = stb_gemv(dev[l], x[l], B, y[l], y_fp32, stream);
+        int rc = stb_gemv(dev[l], x[l], B, y[l], y_fp32, workspace, workspace_bytes, stream);
         if (rc) return rc;
     }
     return STB_OK;

@@ -6,6 +6,21 @@
 
 using namespace stbt;
 
+#ifndef STB_VARIANT
+#define STB_VARIANT 0
+#endif
+#ifndef STB_LUT_AHEAD
+#define STB_LUT_AHEAD 2
+#endif
+
+#ifdef STB_TRACE
+__device__ long long stb_trace_buf[4096 * 32];
+#define TRACE(slot) do { if (lane == 0) stb_trace_buf[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + wave) % 4096 * 32 + (slot)] = wall_clock64(); } while (0)
+extern "C" int stb_trace_read(long long* host) { return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(stb_trace_buf), sizeof(long long) * 4096 * 32); }
+#else
+#define TRACE(slot) do {} while (0)
+#endif
+
 namespace {
 
 // ------------------------------------------------------------------------------------------------
@@ -15,8 +30,8 @@ namespace {
 // ------------------------------------------------------------------------------------------------
 template <int N8>
 __global__ __launch_bounds__(64) void dequant_tiled_kernel(TiledPlanes p, float* __restrict__ out) {
-    __shared__ uint4 lut[256];
-    build_scatter_lut<N8>(lut);
+    __shared__ ExpandLuts lut;
+    build_luts<N8>(&lut);
     __syncthreads();
     const int rt = blockIdx.x / p.nsb, sb = blockIdx.x % p.nsb;
     const int lane = threadIdx.x, i = lane & 15, g = lane >> 4;
@@ -32,7 +47,7 @@ __global__ __launch_bounds__(64) void dequant_tiled_kernel(TiledPlanes p, float*
 #pragma unroll
     for (int t = 0; t < 16; t++) {
         uint32_t e[4];
-        expand_group<N8>(d, TL, TH, t, lut, e);
+        expand_group<N8>(d, TL, TH, t, lut_fetch<N8>(d, t, &lut), e);
         const half8_t a = as_half8(e);
         const uint32_t mb = (d.m[t >> 2] >> (8 * (t & 3))) & 0xFFu;
         const uint32_t salb = p.res_words ? (p.sal_bitmap[4 * q + (t >> 2)] >> (8 * (t & 3))) & 0xFFu : 0u;
@@ -89,44 +104,68 @@ __device__ inline ResInv load_res_inv(const TiledPlanes& p, int q, int c, const 
     return r;
 }
 
+// Workgroup (gr, ks) of the grid owns the 16-row tiles [gr*R, gr*R + R) and the eight superblocks
+// 8*ks .. 8*ks + 7, one per wavefront.  With more than eight superblocks (k > 4096) the grid has several
+// column splits: each writes its partial sums to the workspace, takes a ticket, and the last split to finish
+// a row group adds the partial sums in split order and writes y.
 template <int N8, bool HAS_RES>
 __global__ __launch_bounds__(512) void gemv_stream_kernel(TiledPlanes p, const __half* __restrict__ x, int B,
-                                                           void* __restrict__ y, int y_fp32, int R) {
-    __shared__ uint4 lut[256];
-    extern __shared__ float part[];                  // [W][R][256]
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, W = blockDim.x >> 6;
+                                                           void* __restrict__ y, int y_fp32, int R,
+                                                           float* __restrict__ ws_part, uint32_t* __restrict__ ws_count) {
+    __shared__ ExpandLuts lut;
+    __shared__ uint32_t ticket;
+    extern __shared__ float part[];                  // [8][R][256]
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int i = lane & 15, g = lane >> 4;
-    const int r0 = blockIdx.x * R;
+    const int gr = blockIdx.x, ks = blockIdx.y, S = gridDim.y;
+    const int r0 = gr * R;
     const int r1 = r0 + R < p.nrt ? r0 + R : p.nrt;
     const int rl = r1 - 1;
+    const int sb = 8 * ks + wave;
+    const bool active = sb < p.nsb;                  // uniform per wavefront
+    const int Wa = p.nsb - 8 * ks < 8 ? p.nsb - 8 * ks : 8;     // wavefronts of this workgroup that have a superblock
     constexpr int L = TileLoads<N8, HAS_RES>::count;
-    build_scatter_lut<N8>(lut);
-    __syncthreads();
+    const int q = 4 * sb + g;
 
-    for (int sb = wave, pass = 0; sb < p.nsb; sb += W, pass++) {
-        const int q = 4 * sb + g;
+    LaneOffsets lo;
+    lo.o16 = lane * 16u; lo.o8 = lane * 8u; lo.o2 = lane * 2u;
+    lo.osign = lane * (2u * N8); lo.oregion = lane * (4u * N8);
+    lo.ores0 = 0u; lo.ores1 = 0u;
+    auto tile_of = [&](int rt) { return (int64_t)rt * p.nsb + sb; };
+    auto clamp = [&](int rt) { return rt < rl ? rt : rl; };
+
+    TRACE(0);
+    // ---- the packed planes of the first two tiles and the column tables go out before anything else ----
+    TileRegs<N8> t0, t1, t2;
+    uint32_t ord = 0u;
+    int nch = 0;
+    if (active) {
+        fetch_main<N8>(t0, p, tile_of(r0), lo);
+        fetch_main<N8>(t1, p, tile_of(clamp(r0 + 1)), lo);
+        if (HAS_RES) {
+            ord = p.sal_prefix[q];
+            nch = (int)p.sal_tab[((int64_t)q * p.sal_chunks) * 12 + 7];
+        }
+    }
+    build_luts<N8>(&lut);
+    TRACE(1);
+    __syncthreads();
+    TRACE(2);
+
+    if (active) {
         const bool live = i < B && q < p.nb;
         const __half* xrow = x + (int64_t)(i < B ? i : B - 1) * p.k + (int64_t)(q < p.nb ? q : 0) * 128;
-        LaneOffsets lo;
-        lo.o16 = lane * 16u; lo.o8 = lane * 8u; lo.o2 = lane * 2u;
-        lo.osign = lane * (2u * N8); lo.oregion = lane * (4u * N8);
-        lo.ores0 = 0u; lo.ores1 = 0u;
-        int nch = 0, rsh = 0;
+        int rsh = 0;
         if (HAS_RES) {
-            const uint32_t ord = p.sal_prefix[q];
+            nch = __builtin_amdgcn_readfirstlane(nch);
             rsh = (int)(ord & 31u);
             const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
             const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
             lo.ores0 = (uint32_t)(wa * 16 + i) * 4u;
             lo.ores1 = (uint32_t)(wb * 16 + i) * 4u;
         }
-        auto tile_of = [&](int rt) { return (int64_t)rt * p.nsb + sb; };
-        auto clamp = [&](int rt) { return rt < rl ? rt : rl; };
-
-        // ---- the first two tiles go out before anything else ----
-        TileRegs<N8> t0, t1, t2;
-        fetch_tile<N8, HAS_RES>(t0, p, tile_of(r0), r0, lo);
-        fetch_tile<N8, HAS_RES>(t1, p, tile_of(clamp(r0 + 1)), clamp(r0 + 1), lo);
+        fetch_res<N8, HAS_RES>(t0, p, r0, lo);
+        fetch_res<N8, HAS_RES>(t1, p, clamp(r0 + 1), lo);
 
         // ---- operands that depend on the columns only ----
         uint4 xr[16];
@@ -134,7 +173,6 @@ __global__ __launch_bounds__(512) void gemv_stream_kernel(TiledPlanes p, const _
         for (int t = 0; t < 16; t++) xr[t] = reinterpret_cast<const uint4*>(xrow)[t];
         ResInv inv0, inv1;
         if (HAS_RES) {
-            nch = __builtin_amdgcn_readfirstlane((int)p.sal_tab[((int64_t)q * p.sal_chunks) * 12 + 7]);
             inv0 = load_res_inv(p, q, 0, reinterpret_cast<const unsigned short*>(xrow), live);
             inv1 = load_res_inv(p, q, p.sal_chunks > 1 ? 1 : 0, reinterpret_cast<const unsigned short*>(xrow), live);
         }
@@ -142,20 +180,29 @@ __global__ __launch_bounds__(512) void gemv_stream_kernel(TiledPlanes p, const _
 #pragma unroll
             for (int t = 0; t < 16; t++) xr[t] = make_uint4(0u, 0u, 0u, 0u);
         }
-        // Everything the compiler tracks has arrived before the streaming loop starts, so that it places no
-        // wait of its own inside the loop (such a wait would also drain the prefetched tiles).
+        // Everything issued so far has arrived before the streaming loop starts: the compiler then places no
+        // wait of its own inside the loop (such a wait would also drain the prefetched tiles), and the fixed
+        // wait counts of the loop hold from its first iteration.
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
         __builtin_amdgcn_sched_barrier(0);
+        TRACE(3);
 
         auto product = [&](const TileRegs<N8>& tr, int rt) {
             BlockData<N8> d;
             unpack_tile<N8>(tr, d);
             const uint32_t TL = perm(d.sc.y, d.sc.x, 0x06040200u), TH = perm(d.sc.y, d.sc.x, 0x07050301u);
             float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+            constexpr int D = STB_LUT_AHEAD;                             // table reads run D groups ahead
+            GroupLut gl[D];
+#pragma unroll
+            for (int t = 0; t < D; t++) gl[t] = lut_fetch<N8>(d, t, &lut);
 #pragma unroll
             for (int t = 0; t < 16; t++) {
+                const GroupLut cur = gl[t % D];
+                if (t + D < 16) gl[t % D] = lut_fetch<N8>(d, t + D, &lut);
+                __builtin_amdgcn_sched_barrier(0);
                 uint32_t o[4];
-                expand_group<N8>(d, TL, TH, t, lut, o);
+                expand_group<N8>(d, TL, TH, t, cur, o);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(o), __builtin_bit_cast(half8_t, xr[t]), acc, 0, 0, 0);
             }
             if (HAS_RES && nch > 0) {
@@ -170,13 +217,9 @@ __global__ __launch_bounds__(512) void gemv_stream_kernel(TiledPlanes p, const _
                 }
             }
             float* dst = part + ((int64_t)(wave * R + (rt - r0)) * 256 + lane);
-            if (pass == 0) {
 #pragma unroll
-                for (int v = 0; v < 4; v++) dst[64 * v] = acc[v];
-            } else {
-#pragma unroll
-                for (int v = 0; v < 4; v++) dst[64 * v] += acc[v];
-            }
+            for (int v = 0; v < 4; v++) dst[64 * v] = acc[v];
+            TRACE(8 + (rt - r0 < 20 ? rt - r0 : 20));
         };
 
         // Three tiles in flight: while tile rt is expanded, the loads of rt + 1 and rt + 2 are outstanding.
@@ -195,6 +238,7 @@ __global__ __launch_bounds__(512) void gemv_stream_kernel(TiledPlanes p, const _
             wait_tile<2 * L>(t2);
             product(t2, rt + 2);
         }
+        TRACE(4);
         wait_tile<0>(t0);                            // drain: no load may still target a register that is reused
         wait_tile<0>(t1);
         wait_tile<0>(t2);
@@ -212,7 +256,7 @@ __global__ __launch_bounds__(512) void gemv_stream_kernel(TiledPlanes p, const _
                 float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
                 for (int c = 2; c < nch; c++) {
                     const ResInv inv = load_res_inv(p, q, c, reinterpret_cast<const unsigned short*>(xrow), live);
-                    const uint32_t u0 = p.sal_prefix[q] + 8u * (uint32_t)c;
+                    const uint32_t u0 = ord + 8u * (uint32_t)c;
                     const int wa = (int)(u0 >> 5) < p.res_words ? (int)(u0 >> 5) : p.res_words - 1;
                     const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
                     const uint32_t rlo = p.res_sign[rt * rstride + (int64_t)wa * 16 + i];
@@ -227,20 +271,54 @@ __global__ __launch_bounds__(512) void gemv_stream_kernel(TiledPlanes p, const _
             }
         }
     }
+    TRACE(5);
     __syncthreads();
-    // D[row][b] of a tile: lane l holds b = l % 16, rows 4*(l / 16) + v.  Consecutive threads write consecutive rows.
-    const int Wu = W < p.nsb ? W : p.nsb;
+    TRACE(6);
+
+    // D[row][b] of a tile: lane l holds b = l % 16, rows 4*(l / 16) + v.  Consecutive threads take consecutive rows.
     const int total = (r1 - r0) * 256;
-    for (int o = threadIdx.x; o < total; o += blockDim.x) {
+    const int64_t n16 = (int64_t)p.nrt * 16;
+    auto wg_sum = [&](int o) {
         const int j = o >> 8, b = (o >> 4) & 15, r16 = o & 15;
         const int l = b + 16 * (r16 >> 2), v = r16 & 3;
         float s = 0.0f;
-        for (int w = 0; w < Wu; w++) s += part[(int64_t)(w * R + j) * 256 + 64 * v + l];
-        const int row = (r0 + j) * 16 + r16;
+        for (int w = 0; w < Wa; w++) s += part[(int64_t)(w * R + j) * 256 + 64 * v + l];
+        return s;
+    };
+    auto store_y = [&](int o, float s) {
+        const int b = (o >> 4) & 15, row = (r0 + (o >> 8)) * 16 + (o & 15);
         if (b < B && row < p.n) {
             if (y_fp32) reinterpret_cast<float*>(y)[(int64_t)b * p.n + row] = -s;
             else reinterpret_cast<__half*>(y)[(int64_t)b * p.n + row] = __float2half(-s);
         }
+    };
+    if (S == 1) {
+        for (int o = threadIdx.x; o < total; o += blockDim.x) store_y(o, wg_sum(o));
+        TRACE(7);
+        return;
+    }
+    // ---- several column splits: partial sums to the workspace [split][16][n16], then a ticket ----
+    // The partial sums are written and read with agent-scope accesses (they go through to the level all
+    // compute dies share), so no cache write-back or invalidate is needed around the ticket: the stores have
+    // completed (vmcnt = 0, then the barrier) before thread 0 takes the ticket, and the last arrival issues
+    // its loads after it has seen the ticket.
+    for (int o = threadIdx.x; o < total; o += blockDim.x) {
+        const int b = (o >> 4) & 15, row = (r0 + (o >> 8)) * 16 + (o & 15);
+        if (b < B) __hip_atomic_store(ws_part + ((int64_t)ks * 16 + b) * n16 + row, wg_sum(o), __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x == 0) ticket = atomicInc(ws_count + gr, (uint32_t)(S - 1));    // wraps to 0 after S arrivals
+    __syncthreads();
+    if (ticket != (uint32_t)(S - 1)) return;
+    for (int o = threadIdx.x; o < total; o += blockDim.x) {
+        const int b = (o >> 4) & 15, row = (r0 + (o >> 8)) * 16 + (o & 15);
+        if (b >= B) continue;
+        float s = 0.0f;
+        for (int c = 0; c < S; c++)
+            s += __hip_atomic_load(ws_part + ((int64_t)c * 16 + b) * n16 + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        store_y(o, s);
     }
 }
 
@@ -274,30 +352,55 @@ extern "C" int stb_tiled_dequant(const stb_layout_t* L, float* out, void* stream
     return e == hipSuccess ? STB_OK : STB_EHIP;
 }
 
-extern "C" int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* stream,
-                              int* hip_err) {
+static int64_t round_up256(int64_t v) { return (v + 255) / 256 * 256; }
+
+extern "C" int64_t stb_tiled_gemv_workspace(int n_row_tiles, int n_super) {
+    const int S = (n_super + 7) / 8;
+    if (S <= 1) return 0;
+    return round_up256(4 * (int64_t)n_row_tiles) + (int64_t)S * 16 * 16 * n_row_tiles * 4;
+}
+
+template <int N8, bool HAS_RES>
+static hipError_t launch_gemv_stream(const TiledPlanes& p, const __half* x, int B, void* y, int y_fp32, int R,
+                                     dim3 grid, size_t lds, float* ws_part, uint32_t* ws_count, hipStream_t st) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv_stream_kernel<N8, HAS_RES>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((gemv_stream_kernel<N8, HAS_RES>), grid, dim3(512), lds, st, p, x, B, y, y_fp32, R, ws_part, ws_count);
+    return hipGetLastError();
+}
+
+extern "C" int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
+                              int64_t workspace_bytes, void* stream, int* hip_err) {
     if (!stb_tiled_supported(L)) return STB_EUNSUPPORTED;
     const TiledPlanes p = make_tiled(L);
+    const int S = (p.nsb + 7) / 8;                                 // column splits of eight superblocks
+    const int64_t need = stb_tiled_gemv_workspace(p.nrt, p.nsb);
+    if (need > 0) {
+        if (!workspace) return STB_ENULL;
+        if (workspace_bytes < need) return STB_EINVAL;
+        if ((uintptr_t)workspace % 256) return STB_EALIGN;
+    }
     static const int wg_target = env_int("STB_GEMV_WGS", 256);     // workgroups the launch aims for
-    static const int max_waves = env_int("STB_GEMV_WAVES", 8);
-    const int W = p.nsb < max_waves ? p.nsb : max_waves;           // wavefronts per workgroup
-    int R = (p.nrt + wg_target - 1) / wg_target;                   // row tiles per workgroup
-    const int r_max = 56 / W;                                      // partial sums stay below 56 KB of LDS
-    if (R > r_max) R = r_max;
+    int groups = wg_target / S;                                    // row groups
+    if (groups < 1) groups = 1;
+    int R = (p.nrt + groups - 1) / groups;                         // row tiles per workgroup
+    if (R > 16) R = 16;                                            // 8 x R KB of partial sums in LDS
     const int G = (p.nrt + R - 1) / R;
-    const size_t lds = (size_t)W * R * 256 * sizeof(float);
-    const dim3 grid(G), block(64 * W);
+    const size_t lds = (size_t)8 * R * 256 * sizeof(float);
+    const dim3 grid(G, S);
     const hipStream_t st = (hipStream_t)stream;
     const __half* xh = (const __half*)x;
+    uint32_t* cnt = (uint32_t*)workspace;
+    float* part = need > 0 ? (float*)((char*)workspace + round_up256(4 * (int64_t)p.nrt)) : nullptr;
     const bool res = p.res_words > 0;
-    if (kept_per_8(L) == 4) {
-        if (res) hipLaunchKernelGGL((gemv_stream_kernel<4, true>), grid, block, lds, st, p, xh, B, y, y_fp32, R);
-        else hipLaunchKernelGGL((gemv_stream_kernel<4, false>), grid, block, lds, st, p, xh, B, y, y_fp32, R);
-    } else {
-        if (res) hipLaunchKernelGGL((gemv_stream_kernel<6, true>), grid, block, lds, st, p, xh, B, y, y_fp32, R);
-        else hipLaunchKernelGGL((gemv_stream_kernel<6, false>), grid, block, lds, st, p, xh, B, y, y_fp32, R);
-    }
-    const hipError_t e = hipGetLastError();
+    hipError_t e;
+    if (kept_per_8(L) == 4)
+        e = res ? launch_gemv_stream<4, true>(p, xh, B, y, y_fp32, R, grid, lds, part, cnt, st)
+                : launch_gemv_stream<4, false>(p, xh, B, y, y_fp32, R, grid, lds, part, cnt, st);
+    else
+        e = res ? launch_gemv_stream<6, true>(p, xh, B, y, y_fp32, R, grid, lds, part, cnt, st)
+                : launch_gemv_stream<6, false>(p, xh, B, y, y_fp32, R, grid, lds, part, cnt, st);
     *hip_err = (int)e;
     return e == hipSuccess ? STB_OK : STB_EHIP;
 }

@@ -14,7 +14,10 @@ int stb_layout_check(const stb_layout_t* L);
 // code of a failed launch in *hip_err.  stb_tiled_supported: 1 iff the fast kernels cover this N:M.
 int stb_tiled_supported(const stb_layout_t* L);
 int stb_tiled_dequant(const stb_layout_t* L, float* out, void* stream, int* hip_err);
-int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* stream, int* hip_err);
+int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
+                   int64_t workspace_bytes, void* stream, int* hip_err);
+// Scratch bytes of the tiled decode kernel for L's shape (0 when k <= 4096).
+int64_t stb_tiled_gemv_workspace(int n_row_tiles, int n_super);
 #ifdef __cplusplus
 }
 #endif

@@ -4,8 +4,9 @@
 // (row i of the tile, block g of the superblock) and receives that block's 16 mask bytes, its sign and id
 // bits and its scales with one coalesced load per plane.  The lane expands 8 columns at a time into the
 // A operand (4 VGPRs of fp16) of v_mfma_f32_16x16x32_f16.  Expansion works on whole registers:
-//   * ids -> byte selectors -> v_perm_b32 over the block's scale table gives two kept weights per register
-//     in slot order (the order of the sign / id planes),
+//   * ids -> byte selectors (a 256-entry table in LDS indexed by the id byte for 2:4 and 4:8, bit arithmetic
+//     for 6:8) -> v_perm_b32 over the block's scale table gives two kept weights per register in slot order
+//     (the order of the sign / id planes),
 //   * sign bits are moved to bit 15 / 31 with one packed 16-bit shift and merged with one and-or,
 //   * a 256-entry table in LDS, indexed by the mask byte, holds the four v_perm selectors that spread the
 //     slot-ordered weights to their column positions (zero where the mask bit is clear).
@@ -74,6 +75,14 @@ __device__ inline uint32_t pk_shl(uint32_t v, unsigned lo, unsigned hi) {
     return __builtin_bit_cast(uint32_t, x);
 }
 
+// (a & b) | c in one instruction with all three operands in VGPRs (two constants cannot share the one
+// constant-bus slot a VOP3 instruction has, so the compiler would otherwise split it in two).
+__device__ inline uint32_t and_or(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 __device__ inline uint32_t pk_min_u16(uint32_t a, uint32_t b) {
     const ushort2_t x = __builtin_bit_cast(ushort2_t, a), y = __builtin_bit_cast(ushort2_t, b);
     const ushort2_t r = __builtin_elementwise_min(x, y);
@@ -123,11 +132,6 @@ __device__ inline uint4 scatter_entry(uint32_t mb) {
         sel[v] = s;
     }
     return make_uint4(sel[0], sel[1], sel[2], sel[3]);
-}
-
-template <int N8>
-__device__ inline void build_scatter_lut(uint4* lut) {
-    for (int mb = threadIdx.x; mb < 256; mb += blockDim.x) lut[mb] = scatter_entry<N8>((uint32_t)mb);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -211,9 +215,8 @@ struct LaneOffsets {
     uint32_t ores0, ores1;     // byte offsets of the two res_sign words inside the row tile
 };
 
-template <int N8, bool HAS_RES>
-__device__ inline void fetch_tile(TileRegs<N8>& d, const TiledPlanes& p, int64_t tile, int64_t rt,
-                                  const LaneOffsets& lo) {
+template <int N8>
+__device__ inline void fetch_main(TileRegs<N8>& d, const TiledPlanes& p, int64_t tile, const LaneOffsets& lo) {
     const char* bm = reinterpret_cast<const char*>(p.mask) + tile * (64 * 16);
     const char* bs = reinterpret_cast<const char*>(p.sign) + tile * (64 * 2 * N8);
     const char* br = reinterpret_cast<const char*>(p.region) + tile * (64 * 4 * N8);
@@ -230,6 +233,11 @@ __device__ inline void fetch_tile(TileRegs<N8>& d, const TiledPlanes& p, int64_t
     }
     asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.sc) : "v"(lo.o8), "s"(bc));
     asm volatile("global_load_ushort %0, %1, %2" : "=v"(d.ar) : "v"(lo.o2), "s"(ba));
+}
+
+// The two res_sign words of the lane's row in row tile rt (lo.ores0 / lo.ores1 must be final).
+template <int N8, bool HAS_RES>
+__device__ inline void fetch_res(TileRegs<N8>& d, const TiledPlanes& p, int64_t rt, const LaneOffsets& lo) {
     if constexpr (HAS_RES) {
         const char* bres = reinterpret_cast<const char*>(p.res_sign) + rt * ((int64_t)p.res_words * 64);
         asm volatile("global_load_dword %0, %1, %2" : "=v"(d.rlo) : "v"(lo.ores0), "s"(bres));
@@ -237,6 +245,13 @@ __device__ inline void fetch_tile(TileRegs<N8>& d, const TiledPlanes& p, int64_t
     } else {
         d.rlo = 0u; d.rhi = 0u;
     }
+}
+
+template <int N8, bool HAS_RES>
+__device__ inline void fetch_tile(TileRegs<N8>& d, const TiledPlanes& p, int64_t tile, int64_t rt,
+                                  const LaneOffsets& lo) {
+    fetch_main<N8>(d, p, tile, lo);
+    fetch_res<N8, HAS_RES>(d, p, rt, lo);
 }
 
 // Waits until at most K of the loads above are outstanding and hands the tile's registers over.
@@ -263,28 +278,71 @@ __device__ inline void unpack_tile(const TileRegs<N8>& t, BlockData<N8>& d) {
     d.rlo = t.rlo; d.rhi = t.rhi;
 }
 
-// Expands columns 8t .. 8t+7 of the lane's block into four registers of fp16 pairs (negated weights).
-// TL / TH = low / high bytes of the four scales.
+// Second table (N8 = 4 only): for the byte holding the four 2-bit ids of an 8-column group, the two v_perm
+// selectors that pick the low / high bytes of the scales of slots (0,1) and (2,3) out of {TH:TL}.
+__device__ inline uint2 id_entry(uint32_t idb) {
+    uint32_t sel[2];
+#pragma unroll
+    for (int v = 0; v < 2; v++) {
+        const uint32_t a = (idb >> (4 * v)) & 3u, b = (idb >> (4 * v + 2)) & 3u;
+        sel[v] = a | ((a | 4u) << 8) | (b << 16) | ((b | 4u) << 24);
+    }
+    return make_uint2(sel[0], sel[1]);
+}
+
+struct ExpandLuts {
+    uint4 scatter[256];
+    uint2 ids[256];
+};
+
 template <int N8>
-__device__ inline void expand_group(const BlockData<N8>& d, uint32_t TL, uint32_t TH, int t, const uint4* lut,
-                                    uint32_t out[4]) {
+__device__ inline void build_luts(ExpandLuts* L) {
+    for (int e = threadIdx.x; e < 256; e += blockDim.x) {
+        L->scatter[e] = scatter_entry<N8>((uint32_t)e);
+        L->ids[e] = id_entry((uint32_t)e);
+    }
+}
+
+// Table entries of group t (issued ahead of the arithmetic that uses them).
+struct GroupLut {
+    uint4 sc;
+    uint2 id;
+};
+
+template <int N8>
+__device__ inline GroupLut lut_fetch(const BlockData<N8>& d, int t, const ExpandLuts* L) {
+    GroupLut g;
     const uint32_t mb = (d.m[t >> 2] >> (8 * (t & 3))) & 0xFFu;
-    const uint4 L = lut[mb];
+#if defined(STB_VARIANT) && STB_VARIANT == 2
+    g.sc = make_uint4(mb, mb * 3u, 0x01000302u, 0x05040706u);
+    g.id = make_uint2(d.r[t >> 2], d.r[t >> 2] >> 3);
+    return g;
+#endif
+    g.sc = L->scatter[mb];
+    g.id = make_uint2(0u, 0u);
+    if (N8 == 4) {
+        const uint32_t idb = (d.r[t >> 2] >> (8 * (t & 3))) & 0xFFu;
+        g.id = L->ids[idb];
+    }
+    return g;
+}
+
+// Expands columns 8t .. 8t+7 of the lane's block into four registers of fp16 pairs (negated weights).
+// TL / TH = low / high bytes of the four scales; gl = the group's table entries.
+template <int N8>
+__device__ inline void expand_group(const BlockData<N8>& d, uint32_t TL, uint32_t TH, int t, const GroupLut& gl,
+                                    uint32_t out[4]) {
+    const uint4 L = gl.sc;
     uint32_t W[3];
     if (N8 == 4) {
-        const uint32_t rw = d.r[t >> 2], r2 = rw >> 2;
-        const uint32_t b = t & 3;
-        const uint32_t Z = perm(r2, rw, b | (b << 8) | ((4 + b) << 16) | ((4 + b) << 24));
-        const uint32_t sel0 = (Z & 0x03030303u) | 0x04000400u;
-        const uint32_t sel1 = ((Z >> 4) & 0x03030303u) | 0x04000400u;
-        W[0] = perm(TH, TL, sel0);
-        W[1] = perm(TH, TL, sel1);
+        W[0] = perm(TH, TL, gl.id.x);
+        W[1] = perm(TH, TL, gl.id.y);
         const uint32_t sw = d.s[t >> 3];
         const uint32_t sb = (t >> 1) & 3;
         const uint32_t X = perm(sw, sw, 0x000C000Cu | (sb << 8) | (sb << 24));     // halves = sign byte << 8
         const int base = 4 * (t & 1);
-        W[0] |= pk_shl(X, 7 - base, 6 - base) & 0x80008000u;     // scales are >= 0: their sign bit is clear
-        W[1] |= pk_shl(X, 5 - base, 4 - base) & 0x80008000u;
+        W[0] = and_or(pk_shl(X, 7 - base, 6 - base), 0x80008000u, W[0]);   // scales are >= 0: their sign bit is clear
+        W[1] = and_or(pk_shl(X, 5 - base, 4 - base), 0x80008000u, W[1]);
         out[0] = perm(W[1], W[0], L.x);
         out[1] = perm(W[1], W[0], L.y);
         out[2] = perm(W[1], W[0], L.z);
@@ -293,17 +351,17 @@ __device__ inline void expand_group(const BlockData<N8>& d, uint32_t TL, uint32_
         const uint32_t v = window32<BlockData<N8>::RW>(d.r, 12 * t), v2 = v >> 2;
         const uint32_t Z = perm(v2, v, 0x04040000u);
         const uint32_t Z1 = perm(v2, v, 0x05050101u);
-        const uint32_t sel0 = (Z & 0x03030303u) | 0x04000400u;
-        const uint32_t sel1 = ((Z >> 4) & 0x03030303u) | 0x04000400u;
-        const uint32_t sel2 = (Z1 & 0x03030303u) | 0x04000400u;
+        const uint32_t sel0 = and_or(Z, 0x03030303u, 0x04000400u);
+        const uint32_t sel1 = and_or(Z >> 4, 0x03030303u, 0x04000400u);
+        const uint32_t sel2 = and_or(Z1, 0x03030303u, 0x04000400u);
         W[0] = perm(TH, TL, sel0);
         W[1] = perm(TH, TL, sel1);
         W[2] = perm(TH, TL, sel2);
         const uint32_t sv = window32<BlockData<N8>::SW>(d.s, 6 * t);
         const uint32_t X = perm(sv, sv, 0x000C000Cu);                               // halves = (sign bits) << 8
-        W[0] |= pk_shl(X, 7, 6) & 0x80008000u;
-        W[1] |= pk_shl(X, 5, 4) & 0x80008000u;
-        W[2] |= pk_shl(X, 3, 2) & 0x80008000u;
+        W[0] = and_or(pk_shl(X, 7, 6), 0x80008000u, W[0]);
+        W[1] = and_or(pk_shl(X, 5, 4), 0x80008000u, W[1]);
+        W[2] = and_or(pk_shl(X, 3, 2), 0x80008000u, W[2]);
         out[0] = perm(W[1], W[0], L.x);
         out[1] = perm(W[1], W[0], L.y);
         out[2] = perm(W[2], W[1], L.z);

@@ -116,7 +116,7 @@ def test_gemv_small(small_case, torch_cuda, B, y_fp32):
     xd = torch.from_numpy(x).cuda()
     yd = torch.full((B, c["n"]), float("nan"), dtype=torch.float32 if y_fp32 else torch.float16, device="cuda")
     _say(f"[step] stb_gemv B={B} fp32={y_fp32}")
-    S.stb_gemv(c["pm"].dev_layout, xd, B, yd, y_fp32)
+    S.stb_gemv(c["pm"].dev_layout, xd, B, yd, y_fp32, c["pm"].workspace)
     torch.cuda.synchronize()
     _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemv B={B}")
 
@@ -145,12 +145,12 @@ def test_zero_activations_and_zero_weights(torch_cuda):
     pm = S.PackedMatrix.pack(np.zeros((n, k), np.float32), L["xnorm"], L["sal_bitmap"], 4, 8, 0).to_device()
     xd = torch.from_numpy(make_x(4, k, 7)).cuda()
     yd = torch.full((4, n), float("nan"), dtype=torch.float16, device="cuda")
-    S.stb_gemv(pm.dev_layout, xd, 4, yd)
+    S.stb_gemv(pm.dev_layout, xd, 4, yd, False, pm.workspace)
     torch.cuda.synchronize()
     assert (yd.cpu().numpy() == 0).all()
     pm2 = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], 4, 8, 0).to_device()
     yd = torch.full((4, n), float("nan"), dtype=torch.float32, device="cuda")
-    S.stb_gemv(pm2.dev_layout, torch.zeros_like(xd), 4, yd, True)
+    S.stb_gemv(pm2.dev_layout, torch.zeros_like(xd), 4, yd, True, pm2.workspace)
     torch.cuda.synchronize()
     assert (yd.cpu().numpy() == 0).all()
 
@@ -236,7 +236,7 @@ def test_full_size_layer(cfg, idx, torch_cuda):
         xd = torch.from_numpy(x).cuda()
         yd = torch.full((B, spec.n), float("nan"), dtype=torch.float16, device="cuda")
         _say(f"[step] stb_gemv B={B}")
-        S.stb_gemv(pm.dev_layout, xd, B, yd)
+        S.stb_gemv(pm.dev_layout, xd, B, yd, False, pm.workspace)
         torch.cuda.synchronize()
         worst = _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"{key} gemv B={B}")
         _say(f"       worst error / bound = {worst:.2e}")
