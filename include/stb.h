@@ -92,17 +92,18 @@ typedef struct stb_cfg {
  *   res_sign  [row_tile][word][row % 16] uint32: the STB1 row strings cut into 32-bit words and transposed
  *             inside each row tile (res_stride / 4 words per row)
  *   sal_bitmap / sal_block_prefix as in STB1, padded to whole superblocks
- *   sal_tab   [block][sal_chunks] records of 12 uint32, a derived table like sal_block_prefix.  Record c of
- *             a block covers entries 8c .. 8c+7 of the ascending list of the block's salient columns
- *             (entry e at column p_e of the block, byte p_e >> 3 and bit p_e & 7 of the 16 mask bytes):
- *               [0] selA0 [1] selB0   v_perm_b32 selectors that gather the mask bytes of entries 0..3 from
- *                                     mask words {1,0} (selA) and {3,2} (selB); 0x0C (zero) where the byte
- *                                     lies in the other pair or the entry does not exist
- *               [2] selA1 [3] selB1   the same for entries 4..7
- *               [4] bit0  [5] bit1    one byte per entry: 1 << (p_e & 7), 0 if the entry does not exist
- *               [6] number of entries in this record (0..8)
- *               [7] largest number of records any block of this superblock needs
- *               [8..11] uint16 p_e of the 8 entries, 0xFFFF if the entry does not exist
+ *   sal_tab   [block][half][sal_chunks] records of 12 uint32, a derived table like sal_block_prefix.  A block
+ *             is cut in two halves of 64 columns; record c of a half covers entries 8c .. 8c+7 of the
+ *             ascending list of the half's salient columns (entry e at column p_e of the block, 0..127):
+ *               [0] [1]   v_perm_b32 selectors that gather, out of the half's 8 mask bytes, the byte holding
+ *                         entries 0..3 / 4..7 ((p_e >> 3) & 7; 0x0C = zero if the entry does not exist)
+ *               [2] [3]   one byte per entry: 1 << (p_e & 7), 0 if the entry does not exist
+ *               [4]       index of the record's first entry among all salient columns of the layer (= its
+ *                         bit in a res_sign row)
+ *               [5]       largest number of records any of the four blocks of this superblock needs in this
+ *                         half
+ *               [6]       number of entries in this record (0..8)        [7] zero
+ *               [8..11]   uint16 p_e of the 8 entries, 0xFFFF if the entry does not exist
  * Rows >= n and blocks >= k/128 of the padding are all-zero (nothing kept). */
 #define STB_KIND_ROWMAJOR 0
 #define STB_KIND_TILED 1
@@ -114,7 +115,7 @@ typedef struct stb_layout {
     int32_t kind;              /* STB_KIND_ROWMAJOR | STB_KIND_TILED */
     int32_t n_row_tiles;       /* tiled: ceil(n / 16), else 0 */
     int32_t n_super;           /* tiled: ceil(n_blocks / 4), else 0 */
-    int32_t sal_chunks;        /* tiled: records per block in sal_tab = ceil(min(S, 128) / 8), else 0 */
+    int32_t sal_chunks;        /* tiled: records per half block in sal_tab = ceil(min(S, 64) / 8), else 0 */
     int32_t max_sal_block;     /* tiled: largest number of salient columns in one block (set by stb_tile) */
     int32_t reserved;
     int64_t mask_stride, sign_stride, region_stride, res_stride;   /* bytes per row (row-major) or per lane record (tiled; res_stride stays per row) */
@@ -138,7 +139,7 @@ int stb_layout_sizes(const stb_cfg_t* cfg, stb_layout_t* out);
 int stb_layout_bind(stb_layout_t* layout, void* base);
 
 /* Sizes and image offsets of the tiled device order for `cfg` (kind = STB_KIND_TILED).  `n_salient` columns
- * may all fall into one block, so sal_chunks is sized for that worst case.
+ * may all fall into one half block, so sal_chunks is sized for that worst case.
  * Errors: STB_ENULL, STB_EINVAL. */
 int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out);
 

@@ -160,7 +160,7 @@ extern "C" int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out) {
     out->n_row_tiles = (int32_t)nrt;
     out->n_super = (int32_t)nsb;
     out->n_salient_pad = cfg->n_salient > 0 ? (int32_t)round_up(cfg->n_salient, 128) : 0;
-    out->sal_chunks = cfg->n_salient > 0 ? (int32_t)((std::min<int64_t>(cfg->n_salient, 128) + 7) / 8) : 0;
+    out->sal_chunks = cfg->n_salient > 0 ? (int32_t)((std::min<int64_t>(cfg->n_salient, 64) + 7) / 8) : 0;
     out->mask_stride = 16;
     out->sign_stride = 16 * cfg->N / cfg->M;                     // 128*N/M sign bits per block
     out->region_stride = 32 * cfg->N / cfg->M;
@@ -173,7 +173,7 @@ extern "C" int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out) {
     out->res_scale_bytes = rec * 2;
     out->salmap_bytes = nsb * 4 * 16;
     out->salprefix_bytes = 4 * (nsb * 4 + 1);
-    out->saltab_bytes = nsb * 4 * out->sal_chunks * 48;
+    out->saltab_bytes = nsb * 4 * 2 * out->sal_chunks * 48;
     place_planes(out);
     return STB_OK;
 }
@@ -210,7 +210,7 @@ extern "C" int stb_layout_check(const stb_layout_t* L) {
         L->region_stride != ref.region_stride || L->res_stride != ref.res_stride ||
         L->total_bytes != ref.total_bytes)
         return STB_EINVAL;
-    if (L->kind == STB_KIND_TILED && (L->max_sal_block < 0 || L->max_sal_block > 8 * L->sal_chunks)) return STB_EINVAL;
+    if (L->kind == STB_KIND_TILED && (L->max_sal_block < 0 || L->max_sal_block > 16 * L->sal_chunks)) return STB_EINVAL;
     const void* ptrs[9] = {L->mask, L->sign, L->region, L->res_sign, L->scales, L->res_scale,
                            L->sal_bitmap, L->sal_block_prefix, L->sal_tab};
     for (int i = 0; i < 9; i++) {
@@ -261,45 +261,54 @@ void permute_records(const stb_layout_t* rm, const stb_layout_t* tl, bool to_til
 }
 
 // Fills the derived table of salient columns (layout in stb.h); returns the largest count of one block.
-int fill_sal_tab(const stb_layout_t* tl, const uint32_t* bitmap, int k) {
+int fill_sal_tab(const stb_layout_t* tl, const uint32_t* bitmap, int k, const uint32_t* prefix) {
     const int nsb = tl->n_super, C = tl->sal_chunks;
     int mx = 0;
     std::vector<int> cols;
     for (int sb = 0; sb < nsb; sb++) {
-        int need = 0;
+        int need[2] = {0, 0};
         for (int g = 0; g < 4; g++) {
-            int c = 0;
-            for (int j = (4 * sb + g) * 128; j < std::min(k, (4 * sb + g + 1) * 128); j++) c += sal_bit(bitmap, j);
-            need = std::max(need, (c + 7) / 8);
-            mx = std::max(mx, c);
+            int blk = 0;
+            for (int h = 0; h < 2; h++) {
+                int c = 0;
+                const int j0 = (4 * sb + g) * 128 + 64 * h;
+                for (int j = j0; j < std::min(k, j0 + 64); j++) c += sal_bit(bitmap, j);
+                need[h] = std::max(need[h], (c + 7) / 8);
+                blk += c;
+            }
+            mx = std::max(mx, blk);
         }
         for (int g = 0; g < 4; g++) {
             const int q = 4 * sb + g;
-            cols.clear();
-            for (int j = q * 128; j < std::min(k, (q + 1) * 128); j++)
-                if (sal_bit(bitmap, j)) cols.push_back(j - q * 128);
-            for (int c = 0; c < C; c++) {
-                uint32_t* rec = tl->sal_tab + ((int64_t)q * C + c) * 12;
-                uint32_t sel[4] = {0, 0, 0, 0}, bit[2] = {0, 0};
-                uint16_t* pos = reinterpret_cast<uint16_t*>(rec + 8);
-                int cnt = 0;
-                for (int e = 0; e < 8; e++) {
-                    const int idx = 8 * c + e;
-                    const bool valid = idx < (int)cols.size();
-                    const uint32_t p = valid ? (uint32_t)cols[idx] : 0xFFFFu;
-                    const uint32_t byte = p >> 3;                      // 0..15 if valid
-                    const uint32_t a = valid && byte < 8 ? byte : 0x0Cu;
-                    const uint32_t b = valid && byte >= 8 ? byte - 8 : 0x0Cu;
-                    sel[2 * (e >> 2)] |= a << (8 * (e & 3));
-                    sel[2 * (e >> 2) + 1] |= b << (8 * (e & 3));
-                    if (valid) bit[e >> 2] |= (1u << (p & 7u)) << (8 * (e & 3));
-                    pos[e] = (uint16_t)p;
-                    cnt += valid;
+            uint32_t ord = prefix[q];                               // ordinal of the block's first salient column
+            for (int h = 0; h < 2; h++) {
+                cols.clear();
+                const int j0 = q * 128 + 64 * h;
+                for (int j = j0; j < std::min(k, j0 + 64); j++)
+                    if (sal_bit(bitmap, j)) cols.push_back(j - q * 128);
+                for (int c = 0; c < C; c++) {
+                    uint32_t* rec = tl->sal_tab + (((int64_t)q * 2 + h) * C + c) * 12;
+                    uint32_t sel[2] = {0, 0}, bit[2] = {0, 0};
+                    uint16_t* pos = reinterpret_cast<uint16_t*>(rec + 8);
+                    int cnt = 0;
+                    for (int e = 0; e < 8; e++) {
+                        const int idx = 8 * c + e;
+                        const bool valid = idx < (int)cols.size();
+                        const uint32_t pcol = valid ? (uint32_t)cols[idx] : 0xFFFFu;
+                        const uint32_t byte = valid ? ((pcol >> 3) & 7u) : 0x0Cu;   // byte inside the half's 8 mask bytes
+                        sel[e >> 2] |= byte << (8 * (e & 3));
+                        if (valid) bit[e >> 2] |= (1u << (pcol & 7u)) << (8 * (e & 3));
+                        pos[e] = (uint16_t)pcol;
+                        cnt += valid;
+                    }
+                    rec[0] = sel[0]; rec[1] = sel[1];
+                    rec[2] = bit[0]; rec[3] = bit[1];
+                    rec[4] = ord + 8u * (uint32_t)c;
+                    rec[5] = (uint32_t)need[h];
+                    rec[6] = (uint32_t)cnt;
+                    rec[7] = 0;
                 }
-                rec[0] = sel[0]; rec[1] = sel[1]; rec[2] = sel[2]; rec[3] = sel[3];
-                rec[4] = bit[0]; rec[5] = bit[1];
-                rec[6] = (uint32_t)cnt;
-                rec[7] = (uint32_t)need;
+                ord += (uint32_t)cols.size();
             }
         }
     }
@@ -328,7 +337,7 @@ extern "C" int stb_tile(const stb_layout_t* src, stb_layout_t* dst) {
     const int nb = src->n_blocks, nsb = dst->n_super, k = src->cfg.k_in;
     std::memcpy(dst->sal_bitmap, src->sal_bitmap, src->salmap_bytes);
     for (int q = 0; q <= nsb * 4; q++) dst->sal_block_prefix[q] = src->sal_block_prefix[std::min(q, nb)];
-    const int mx = dst->cfg.n_salient ? fill_sal_tab(dst, src->sal_bitmap, k) : 0;
+    const int mx = dst->cfg.n_salient ? fill_sal_tab(dst, src->sal_bitmap, k, dst->sal_block_prefix) : 0;
     dst->max_sal_block = mx;
     return STB_OK;
 }

@@ -1,12 +1,12 @@
 // Device-side building blocks shared by the kernels that read the tiled device order (STB_KIND_TILED).
 //
-// One wavefront works on a tile of 16 output rows x 4 column blocks (512 columns): lane = 16*g + i owns
-// (row i of the tile, block g of the superblock) and receives that block's 16 mask bytes, its sign and id
-// bits and its scales with one coalesced load per plane.  The lane expands 8 columns at a time into the
-// A operand (4 VGPRs of fp16) of v_mfma_f32_16x16x32_f16.  Expansion works on whole registers:
-//   * ids -> byte selectors (a 256-entry table in LDS indexed by the id byte for 2:4 and 4:8, bit arithmetic
-//     for 6:8) -> v_perm_b32 over the block's scale table gives two kept weights per register in slot order
-//     (the order of the sign / id planes),
+// A tile is 16 output rows x 4 column blocks (512 columns): lane = 16*g + i owns (row i of the tile, block g of
+// the superblock); its record holds that block's 16 mask bytes, its sign and id bits and its scales.  Two
+// wavefronts share a tile, one per half (64 columns) of every block, so that a wavefront keeps only 32 VGPRs
+// of activations and four wavefronts fit on a SIMD.  A lane expands 8 columns at a time into the A operand
+// (4 VGPRs of fp16) of v_mfma_f32_16x16x32_f16.  Expansion works on whole registers:
+//   * ids -> byte selectors -> v_perm_b32 over the block's scale table gives two kept weights per register
+//     in slot order (the order of the sign / id planes),
 //   * sign bits are moved to bit 15 / 31 with one packed 16-bit shift and merged with one and-or,
 //   * a 256-entry table in LDS, indexed by the mask byte, holds the four v_perm selectors that spread the
 //     slot-ordered weights to their column positions (zero where the mask bit is clear).
@@ -37,7 +37,7 @@ struct TiledPlanes {
     const uint32_t* res_sign;   // [nrt][res_words][16]
     const uint32_t* sal_bitmap; // [nsb*4][4]
     const uint32_t* sal_prefix; // [nsb*4 + 1]
-    const uint32_t* sal_tab;    // [nsb*4][sal_chunks][12]
+    const uint32_t* sal_tab;    // [nsb*4][2][sal_chunks][12]
     int n, k, nb, nrt, nsb;
     int res_words;              // uint32 per row of res_sign (0 if no salient columns)
     int sal_chunks;
@@ -111,6 +111,13 @@ __device__ inline uint32_t window32(const uint32_t* w, int off) {
 // Registers W0 = slots 0,1; W1 = slots 2,3; W2 = slots 4,5.  Selectors 0,1 address {W1:W0}; for N8 = 6
 // selectors 2,3 address {W2:W1} (columns 4..7 can only hold slots 2..5), for N8 = 4 they address {W1:W0}.
 // ------------------------------------------------------------------------------------------------
+// A workgroup keeps the scatter table in LDS, eight times: entry mb of copy c sits at [mb][c], and lane l reads
+// copy l % 8, so the eight lanes that an LDS cycle serves hit eight different groups of four banks whatever
+// their mask bytes are.
+struct ScatterLds {
+    uint4 e[256][8];
+};
+
 template <int N8>
 __device__ inline uint4 scatter_entry(uint32_t mb) {
     uint32_t sel[4];
@@ -134,85 +141,102 @@ __device__ inline uint4 scatter_entry(uint32_t mb) {
     return make_uint4(sel[0], sel[1], sel[2], sel[3]);
 }
 
-// ------------------------------------------------------------------------------------------------
-// Per-lane operands of one (row, block)
-// ------------------------------------------------------------------------------------------------
+// Fills the table (any block size; a barrier must follow before it is read).
 template <int N8>
-struct BlockData {
-    static constexpr int SW = N8 / 2;   // sign words   (128*N8/8 bits = 16*N8 bits)
-    static constexpr int RW = N8;       // region words
-    uint32_t m[4];
-    uint32_t s[SW];
-    uint32_t r[RW];
-    uint2 sc;                           // the four scales {dense, inter, sparse, alpha_o} as stored
-    uint32_t ar;                        // alpha_r (fp16 bits)
-    uint32_t rlo, rhi;                  // the two res_sign words of the row that hold the block's first bits
-};
-
-// Issues the loads of lane record `rec`.  res0 = index of the first res_sign word of the lane's row in this
-// row tile (already offset by the block's first word), res1 = the next word (clamped); has_res is uniform.
-template <int N8>
-__device__ inline void load_block(const TiledPlanes& p, int64_t rec, bool has_res, int64_t res0, int64_t res1,
-                                  BlockData<N8>& d) {
-    const uint4 m = p.mask[rec];
-    d.m[0] = m.x; d.m[1] = m.y; d.m[2] = m.z; d.m[3] = m.w;
-    const uint32_t* sp = reinterpret_cast<const uint32_t*>(p.sign + rec * (4 * BlockData<N8>::SW));
-    const uint32_t* rp = reinterpret_cast<const uint32_t*>(p.region + rec * (4 * BlockData<N8>::RW));
-    if (N8 == 4) {
-        const uint2 s = *reinterpret_cast<const uint2*>(sp);
-        d.s[0] = s.x; d.s[1] = s.y;
-        const uint4 r = *reinterpret_cast<const uint4*>(rp);
-        d.r[0] = r.x; d.r[1] = r.y; d.r[2] = r.z; d.r[3] = r.w;
-    } else {
+__device__ inline void build_luts(ScatterLds* L) {
+    for (int mb = threadIdx.x; mb < 256; mb += blockDim.x) {
+        const uint4 v = scatter_entry<N8>((uint32_t)mb);
 #pragma unroll
-        for (int v = 0; v < BlockData<N8>::SW; v++) d.s[v] = sp[v];
-#pragma unroll
-        for (int v = 0; v < BlockData<N8>::RW; v += 2) {
-            const uint2 r = *reinterpret_cast<const uint2*>(rp + v);
-            d.r[v] = r.x; d.r[v + 1] = r.y;
-        }
-    }
-    d.sc = p.scales[rec];
-    d.ar = p.res_scale[rec];
-    d.rlo = 0; d.rhi = 0;
-    if (has_res) {
-        d.rlo = p.res_sign[res0];
-        d.rhi = p.res_sign[res1];
+        for (int c = 0; c < 8; c++) L->e[mb][c] = v;
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Software-pipelined fetch of lane records.  The loads are written as asm statements with the plane base
+// Per-lane operands of one (row, half block): 64 columns = 8 groups of 8.  A wavefront that works on half h of
+// its superblock reads, from each lane record, mask bytes 8h .. 8h+7, the sign bits of slots 8*N8*h ..
+// (N8 = 4: one word; N8 = 6: a 64-bit window at byte 4h, shifted right by 16h), the id fields of the same
+// slots (N8 = 4: two words; N8 = 6: three), the four scales and alpha_r.
+// ------------------------------------------------------------------------------------------------
+template <int N8>
+struct HalfData {
+    static constexpr int SW = N8 == 4 ? 1 : 2;   // sign words held
+    static constexpr int RW = N8 == 4 ? 2 : 3;   // region words held
+    uint32_t m[2];
+    uint32_t s[2];
+    uint32_t r[3];
+    uint2 sc;                           // the four scales {dense, inter, sparse, alpha_o} as stored
+    uint32_t ar;                        // alpha_r (fp16 bits)
+    uint32_t rlo, rhi;                  // the two res_sign words of the row that hold the half's first bits
+};
+
+// Byte offsets of the lane's pieces inside one tile of each plane (lane = 16*g + i, half h).
+struct LaneOffsets {
+    uint32_t omask, osign, oregion, o8, o2;
+    uint32_t ores0, ores1;     // byte offsets of the two res_sign words inside the row tile
+};
+
+template <int N8>
+__device__ inline LaneOffsets lane_offsets(int lane, int half) {
+    LaneOffsets lo;
+    lo.omask = (uint32_t)lane * 16u + 8u * half;
+    lo.osign = N8 == 4 ? (uint32_t)lane * 8u + 4u * half : (uint32_t)lane * 12u + 4u * half;
+    lo.oregion = N8 == 4 ? (uint32_t)lane * 16u + 8u * half : (uint32_t)lane * 24u + 12u * half;
+    lo.o8 = (uint32_t)lane * 8u;
+    lo.o2 = (uint32_t)lane * 2u;
+    lo.ores0 = 0u;
+    lo.ores1 = 0u;
+    return lo;
+}
+
+// Plain loads of one half record (verification kernel and prefill kernel).
+template <int N8>
+__device__ inline void load_half(const TiledPlanes& p, int64_t tile, const LaneOffsets& lo, int half, HalfData<N8>& d) {
+    const char* bm = reinterpret_cast<const char*>(p.mask) + tile * (64 * 16);
+    const char* bs = reinterpret_cast<const char*>(p.sign) + tile * (64 * 2 * N8);
+    const char* br = reinterpret_cast<const char*>(p.region) + tile * (64 * 4 * N8);
+    const uint2 m = *reinterpret_cast<const uint2*>(bm + lo.omask);
+    d.m[0] = m.x; d.m[1] = m.y;
+    if (N8 == 4) {
+        d.s[0] = *reinterpret_cast<const uint32_t*>(bs + lo.osign); d.s[1] = 0u;
+        const uint2 r = *reinterpret_cast<const uint2*>(br + lo.oregion);
+        d.r[0] = r.x; d.r[1] = r.y; d.r[2] = 0u;
+    } else {
+        const uint32_t s0 = *reinterpret_cast<const uint32_t*>(bs + lo.osign);
+        const uint32_t s1 = *reinterpret_cast<const uint32_t*>(bs + lo.osign + 4);
+        d.s[0] = __builtin_amdgcn_alignbit(s1, s0, 16u * half);
+        d.s[1] = s1 >> (16u * half);
+        const uint32_t* rp = reinterpret_cast<const uint32_t*>(br + lo.oregion);
+        d.r[0] = rp[0]; d.r[1] = rp[1]; d.r[2] = rp[2];
+    }
+    d.sc = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(p.scales) + tile * (64 * 8) + lo.o8);
+    d.ar = *reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(p.res_scale) + tile * (64 * 2) + lo.o2);
+    d.rlo = 0u; d.rhi = 0u;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Software-pipelined fetch of half records.  The loads are written as asm statements with the plane base
 // in SGPRs and a 32-bit lane offset, and the matching wait names every destination register as a read-write
 // operand: the loads of several tiles stay in flight exactly as written (the compiler neither moves them
 // nor waits for them), and no register of a tile can be read before wait_tile has been executed on it.
-// Rules for callers: every fetch_tile is followed, on every path, by a wait_tile (or wait_tiles_all) on the
-// same object before the object dies; K = number of such loads issued after the last load of the tile.
+// Rules for callers: every fetch is followed, on every path, by a wait_tile on the same object before the
+// object dies; K = number of such loads issued after the last load of the tile.
 // ------------------------------------------------------------------------------------------------
 typedef uint32_t uint3_t __attribute__((ext_vector_type(3)));
 typedef uint32_t uint2_t __attribute__((ext_vector_type(2)));
-typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
 
 template <int N8>
 struct TileRegs;
 template <>
 struct TileRegs<4> {
-    uint4_t m; uint2_t s; uint4_t r; uint2_t sc; uint32_t ar, rlo, rhi;
+    uint2_t m; uint32_t s; uint2_t r; uint2_t sc; uint32_t ar, rlo, rhi;
 };
 template <>
 struct TileRegs<6> {
-    uint4_t m; uint3_t s; uint4_t r; uint2_t r2; uint2_t sc; uint32_t ar, rlo, rhi;
+    uint2_t m; uint2_t s; uint3_t r; uint2_t sc; uint32_t ar, rlo, rhi;
 };
-template <int N8, bool HAS_RES>
+template <bool HAS_RES>
 struct TileLoads {
-    static constexpr int count = (N8 == 4 ? 5 : 6) + (HAS_RES ? 2 : 0);
-};
-
-// Per-lane byte offsets of the lane's record inside one tile of each plane.
-struct LaneOffsets {
-    uint32_t o16, o8, o2;      // lane * 16, lane * 8, lane * 2
-    uint32_t osign, oregion;   // lane * sign_stride, lane * region_stride
-    uint32_t ores0, ores1;     // byte offsets of the two res_sign words inside the row tile
+    static constexpr int count = 5 + (HAS_RES ? 2 : 0);
 };
 
 template <int N8>
@@ -222,14 +246,13 @@ __device__ inline void fetch_main(TileRegs<N8>& d, const TiledPlanes& p, int64_t
     const char* br = reinterpret_cast<const char*>(p.region) + tile * (64 * 4 * N8);
     const char* bc = reinterpret_cast<const char*>(p.scales) + tile * (64 * 8);
     const char* ba = reinterpret_cast<const char*>(p.res_scale) + tile * (64 * 2);
-    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(d.m) : "v"(lo.o16), "s"(bm));
+    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.m) : "v"(lo.omask), "s"(bm));
     if constexpr (N8 == 4) {
-        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.s) : "v"(lo.osign), "s"(bs));
-        asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(d.r) : "v"(lo.oregion), "s"(br));
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(d.s) : "v"(lo.osign), "s"(bs));
+        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.r) : "v"(lo.oregion), "s"(br));
     } else {
-        asm volatile("global_load_dwordx3 %0, %1, %2" : "=v"(d.s) : "v"(lo.osign), "s"(bs));
-        asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(d.r) : "v"(lo.oregion), "s"(br));
-        asm volatile("global_load_dwordx2 %0, %1, %2 offset:16" : "=v"(d.r2) : "v"(lo.oregion), "s"(br));
+        asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.s) : "v"(lo.osign), "s"(bs));
+        asm volatile("global_load_dwordx3 %0, %1, %2" : "=v"(d.r) : "v"(lo.oregion), "s"(br));
     }
     asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.sc) : "v"(lo.o8), "s"(bc));
     asm volatile("global_load_ushort %0, %1, %2" : "=v"(d.ar) : "v"(lo.o2), "s"(ba));
@@ -257,87 +280,47 @@ __device__ inline void fetch_tile(TileRegs<N8>& d, const TiledPlanes& p, int64_t
 // Waits until at most K of the loads above are outstanding and hands the tile's registers over.
 template <int K, int N8>
 __device__ inline void wait_tile(TileRegs<N8>& d) {
-    if constexpr (N8 == 4)
-        asm volatile("s_waitcnt vmcnt(%7)" : "+v"(d.m), "+v"(d.s), "+v"(d.r), "+v"(d.sc), "+v"(d.ar), "+v"(d.rlo), "+v"(d.rhi) : "n"(K));
-    else
-        asm volatile("s_waitcnt vmcnt(%8)" : "+v"(d.m), "+v"(d.s), "+v"(d.r), "+v"(d.r2), "+v"(d.sc), "+v"(d.ar), "+v"(d.rlo), "+v"(d.rhi) : "n"(K));
+    asm volatile("s_waitcnt vmcnt(%7)" : "+v"(d.m), "+v"(d.s), "+v"(d.r), "+v"(d.sc), "+v"(d.ar), "+v"(d.rlo), "+v"(d.rhi) : "n"(K));
 }
 
 template <int N8>
-__device__ inline void unpack_tile(const TileRegs<N8>& t, BlockData<N8>& d) {
-    d.m[0] = t.m[0]; d.m[1] = t.m[1]; d.m[2] = t.m[2]; d.m[3] = t.m[3];
+__device__ inline void unpack_tile(const TileRegs<N8>& t, int half, HalfData<N8>& d) {
+    d.m[0] = t.m[0]; d.m[1] = t.m[1];
     if constexpr (N8 == 4) {
-        d.s[0] = t.s[0]; d.s[1] = t.s[1];
-        d.r[0] = t.r[0]; d.r[1] = t.r[1]; d.r[2] = t.r[2]; d.r[3] = t.r[3];
+        d.s[0] = t.s; d.s[1] = 0u;
+        d.r[0] = t.r[0]; d.r[1] = t.r[1]; d.r[2] = 0u;
     } else {
-        d.s[0] = t.s[0]; d.s[1] = t.s[1]; d.s[2] = t.s[2];
-        d.r[0] = t.r[0]; d.r[1] = t.r[1]; d.r[2] = t.r[2]; d.r[3] = t.r[3]; d.r[4] = t.r2[0]; d.r[5] = t.r2[1];
+        d.s[0] = __builtin_amdgcn_alignbit(t.s[1], t.s[0], 16u * half);
+        d.s[1] = t.s[1] >> (16u * half);
+        d.r[0] = t.r[0]; d.r[1] = t.r[1]; d.r[2] = t.r[2];
     }
     d.sc = make_uint2(t.sc[0], t.sc[1]);
     d.ar = t.ar & 0xFFFFu;
     d.rlo = t.rlo; d.rhi = t.rhi;
 }
 
-// Second table (N8 = 4 only): for the byte holding the four 2-bit ids of an 8-column group, the two v_perm
-// selectors that pick the low / high bytes of the scales of slots (0,1) and (2,3) out of {TH:TL}.
-__device__ inline uint2 id_entry(uint32_t idb) {
-    uint32_t sel[2];
-#pragma unroll
-    for (int v = 0; v < 2; v++) {
-        const uint32_t a = (idb >> (4 * v)) & 3u, b = (idb >> (4 * v + 2)) & 3u;
-        sel[v] = a | ((a | 4u) << 8) | (b << 16) | ((b | 4u) << 24);
-    }
-    return make_uint2(sel[0], sel[1]);
-}
-
-struct ExpandLuts {
-    uint4 scatter[256];
-    uint2 ids[256];
-};
-
+// Scatter selectors of group t (issued ahead of the arithmetic that uses them).
 template <int N8>
-__device__ inline void build_luts(ExpandLuts* L) {
-    for (int e = threadIdx.x; e < 256; e += blockDim.x) {
-        L->scatter[e] = scatter_entry<N8>((uint32_t)e);
-        L->ids[e] = id_entry((uint32_t)e);
-    }
-}
-
-// Table entries of group t (issued ahead of the arithmetic that uses them).
-struct GroupLut {
-    uint4 sc;
-    uint2 id;
-};
-
-template <int N8>
-__device__ inline GroupLut lut_fetch(const BlockData<N8>& d, int t, const ExpandLuts* L) {
-    GroupLut g;
+__device__ inline uint4 lut_fetch(const HalfData<N8>& d, int t, const ScatterLds* L, int copy) {
     const uint32_t mb = (d.m[t >> 2] >> (8 * (t & 3))) & 0xFFu;
-#if defined(STB_VARIANT) && STB_VARIANT == 2
-    g.sc = make_uint4(mb, mb * 3u, 0x01000302u, 0x05040706u);
-    g.id = make_uint2(d.r[t >> 2], d.r[t >> 2] >> 3);
-    return g;
-#endif
-    g.sc = L->scatter[mb];
-    g.id = make_uint2(0u, 0u);
-    if (N8 == 4) {
-        const uint32_t idb = (d.r[t >> 2] >> (8 * (t & 3))) & 0xFFu;
-        g.id = L->ids[idb];
-    }
-    return g;
+    return L->e[mb][copy];
 }
 
-// Expands columns 8t .. 8t+7 of the lane's block into four registers of fp16 pairs (negated weights).
-// TL / TH = low / high bytes of the four scales; gl = the group's table entries.
+// Expands columns 8t .. 8t+7 (t < 8) of the lane's half block into four registers of fp16 pairs (negated
+// weights).  TL / TH = low / high bytes of the four scales; L = the group's scatter selectors.
 template <int N8>
-__device__ inline void expand_group(const BlockData<N8>& d, uint32_t TL, uint32_t TH, int t, const GroupLut& gl,
+__device__ inline void expand_group(const HalfData<N8>& d, uint32_t TL, uint32_t TH, int t, const uint4& L,
                                     uint32_t out[4]) {
-    const uint4 L = gl.sc;
     uint32_t W[3];
     if (N8 == 4) {
-        W[0] = perm(TH, TL, gl.id.x);
-        W[1] = perm(TH, TL, gl.id.y);
-        const uint32_t sw = d.s[t >> 3];
+        const uint32_t rw = d.r[t >> 2], r2 = rw >> 2;
+        const uint32_t b = t & 3;
+        const uint32_t Z = perm(r2, rw, b | (b << 8) | ((4 + b) << 16) | ((4 + b) << 24));
+        const uint32_t sel0 = and_or(Z, 0x03030303u, 0x04000400u);
+        const uint32_t sel1 = and_or(Z >> 4, 0x03030303u, 0x04000400u);
+        W[0] = perm(TH, TL, sel0);
+        W[1] = perm(TH, TL, sel1);
+        const uint32_t sw = d.s[0];
         const uint32_t sb = (t >> 1) & 3;
         const uint32_t X = perm(sw, sw, 0x000C000Cu | (sb << 8) | (sb << 24));     // halves = sign byte << 8
         const int base = 4 * (t & 1);
@@ -348,7 +331,7 @@ __device__ inline void expand_group(const BlockData<N8>& d, uint32_t TL, uint32_
         out[2] = perm(W[1], W[0], L.z);
         out[3] = perm(W[1], W[0], L.w);
     } else {
-        const uint32_t v = window32<BlockData<N8>::RW>(d.r, 12 * t), v2 = v >> 2;
+        const uint32_t v = window32<3>(d.r, 12 * t), v2 = v >> 2;
         const uint32_t Z = perm(v2, v, 0x04040000u);
         const uint32_t Z1 = perm(v2, v, 0x05050101u);
         const uint32_t sel0 = and_or(Z, 0x03030303u, 0x04000400u);
@@ -357,7 +340,7 @@ __device__ inline void expand_group(const BlockData<N8>& d, uint32_t TL, uint32_
         W[0] = perm(TH, TL, sel0);
         W[1] = perm(TH, TL, sel1);
         W[2] = perm(TH, TL, sel2);
-        const uint32_t sv = window32<BlockData<N8>::SW>(d.s, 6 * t);
+        const uint32_t sv = window32<2>(d.s, 6 * t);
         const uint32_t X = perm(sv, sv, 0x000C000Cu);                               // halves = (sign bits) << 8
         W[0] = and_or(pk_shl(X, 7, 6), 0x80008000u, W[0]);
         W[1] = and_or(pk_shl(X, 5, 4), 0x80008000u, W[1]);
@@ -376,29 +359,20 @@ __device__ inline half8_t as_half8(const uint32_t v[4]) {
 
 // ------------------------------------------------------------------------------------------------
 // Residual term of the salient columns (Eq. 4, second binarisation): one record of the salient-column
-// table covers 8 salient columns of the lane's block.
+// table covers 8 salient columns of the lane's half block.
 // ------------------------------------------------------------------------------------------------
 struct ResSel {
-    uint32_t selA0, selB0, selA1, selB1;   // gather selectors for the mask bytes of entries 0..3 / 4..7
-    uint32_t bit0, bit1;                   // per entry: the bit of the column inside its mask byte
+    uint32_t sel0, sel1;     // gather selectors for the mask bytes of entries 0..3 / 4..7
+    uint32_t bit0, bit1;     // per entry: the bit of the column inside its mask byte
 };
 
-__device__ inline ResSel load_res_sel(const uint32_t* rec) {
-    const uint4 a = *reinterpret_cast<const uint4*>(rec);
-    const uint2 b = *reinterpret_cast<const uint2*>(rec + 4);
-    ResSel s;
-    s.selA0 = a.x; s.selB0 = a.y; s.selA1 = a.z; s.selB1 = a.w;
-    s.bit0 = b.x; s.bit1 = b.y;
-    return s;
-}
-
 // A operand (negated weights) of 8 salient columns: entry e is -t_e * alpha_r where the column is kept, 0
-// where it is pruned.  m = the block's mask words, rb8 = the 8 residual sign bits of the entries (bit e in
+// where it is pruned.  m = the half's mask words, rb8 = the 8 residual sign bits of the entries (bit e in
 // bit e; other bits ignored), ar2 = alpha_r in both halves.
-__device__ inline void residual_chunk(const uint32_t m[4], uint32_t rb8, uint32_t ar2, const ResSel& s,
+__device__ inline void residual_chunk(const uint32_t m[2], uint32_t rb8, uint32_t ar2, const ResSel& s,
                                       uint32_t out[4]) {
-    const uint32_t G0 = (perm(m[1], m[0], s.selA0) | perm(m[3], m[2], s.selB0)) & s.bit0;
-    const uint32_t G1 = (perm(m[1], m[0], s.selA1) | perm(m[3], m[2], s.selB1)) & s.bit1;
+    const uint32_t G0 = perm(m[1], m[0], s.sel0) & s.bit0;
+    const uint32_t G1 = perm(m[1], m[0], s.sel1) & s.bit1;
     uint32_t K[4];
     K[0] = perm(0u, G0, 0x0C010C00u);      // halves = byte of entry 0 / 1: non-zero iff kept
     K[1] = perm(0u, G0, 0x0C030C02u);
@@ -407,7 +381,7 @@ __device__ inline void residual_chunk(const uint32_t m[4], uint32_t rb8, uint32_
     const uint32_t X = perm(rb8, rb8, 0x000C000Cu);          // halves = rb8 << 8
 #pragma unroll
     for (int v = 0; v < 4; v++) {
-        const uint32_t val = (pk_shl(X, 7 - 2 * v, 6 - 2 * v) & 0x80008000u) | ar2;
+        const uint32_t val = and_or(pk_shl(X, 7 - 2 * v, 6 - 2 * v), 0x80008000u, ar2);
         out[v] = pk_mul_u16(val, pk_min_u16(K[v], 0x00010001u));
     }
 }

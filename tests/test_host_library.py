@@ -167,27 +167,30 @@ def test_tile_untile_round_trip_is_a_byte_permutation(n, k, N, M, mode, kind, se
         rm = np.zeros((tl.n_row_tiles * 16, words), "<u4")
         rm[:n] = pm.plane("res_sign").view("<u4").reshape(n, words)
         assert (t.transpose(0, 2, 1).reshape(-1, words) == rm).all()
-    # sal_tab: per block, records of 8 salient columns with the selectors that gather their mask bytes
+    # sal_tab: per half block, records of 8 salient columns with the selectors that gather their mask bytes
     if len(L["sal_cols"]):
         C = tl.sal_chunks
-        rec = timg[tl.off_saltab:tl.off_saltab + tl.saltab_bytes].view("<u4").reshape(tl.n_super * 4, C, 12)
-        pos = rec[:, :, 8:12].copy().view("<u2").reshape(tl.n_super * 4, C * 8)
-        cols = [int(q) * 128 + int(p) for q in range(tl.n_super * 4) for p in pos[q] if p != 0xFFFF]
+        nbk = tl.n_super * 4
+        rec = timg[tl.off_saltab:tl.off_saltab + tl.saltab_bytes].view("<u4").reshape(nbk, 2, C, 12)
+        pos = rec[:, :, :, 8:12].copy().view("<u2").reshape(nbk, 2, C * 8).astype(np.int64)
+        cols = [int(q) * 128 + int(p) for q in range(nbk) for h in range(2) for p in pos[q, h] if p != 0xFFFF]
         assert cols == L["sal_cols"].tolist()
-        per_block = (pos != 0xFFFF).sum(axis=1)
-        assert tl.max_sal_block == per_block.max()
-        assert (rec[:, :, 6] == (pos.reshape(-1, C, 8) != 0xFFFF).sum(axis=2)).all()
-        need = ((per_block + 7) // 8).reshape(tl.n_super, 4).max(axis=1)
-        assert (rec[:, :, 7] == np.repeat(need, 4)[:, None]).all()
-        sel = rec[:, :, 0:4].copy().view(np.uint8).reshape(tl.n_super * 4, C, 2, 2, 4)   # [half][A|B][entry]
-        bit = rec[:, :, 4:6].copy().view(np.uint8).reshape(tl.n_super * 4, C, 2, 4)
-        p = pos.reshape(tl.n_super * 4, C, 2, 4).astype(np.int64)
-        valid = p != 0xFFFF
-        byte = p >> 3
-        expA = np.where(valid & (byte < 8), byte, 0x0C)
-        expB = np.where(valid & (byte >= 8), byte - 8, 0x0C)
-        assert (sel[:, :, :, 0, :] == expA).all() and (sel[:, :, :, 1, :] == expB).all()
-        assert (bit == np.where(valid, 1 << (p & 7), 0)).all()
+        valid = pos != 0xFFFF
+        assert ((pos >> 6) == np.arange(2)[None, :, None])[valid].all()          # entries lie in their half
+        per_half = valid.sum(axis=2)
+        assert tl.max_sal_block == per_half.sum(axis=1).max()
+        assert (rec[:, :, :, 6] == valid.reshape(nbk, 2, C, 8).sum(axis=3)).all()
+        need = ((per_half + 7) // 8).reshape(tl.n_super, 4, 2).max(axis=1)        # [superblock][half]
+        assert (rec[:, :, :, 5] == np.repeat(need, 4, axis=0)[:, :, None]).all()
+        # [4]: ordinal of the record's first entry among all salient columns
+        first = np.concatenate([[0], np.cumsum(per_half.reshape(-1))[:-1]]).reshape(nbk, 2)
+        assert (rec[:, :, :, 4] == first[:, :, None] + 8 * np.arange(C)[None, None, :]).all()
+        sel = rec[:, :, :, 0:2].copy().view(np.uint8).reshape(nbk, 2, C, 8)
+        bit = rec[:, :, :, 2:4].copy().view(np.uint8).reshape(nbk, 2, C, 8)
+        p8 = pos.reshape(nbk, 2, C, 8)
+        v8 = valid.reshape(nbk, 2, C, 8)
+        assert (sel == np.where(v8, (p8 >> 3) & 7, 0x0C)).all()
+        assert (bit == np.where(v8, 1 << (p8 & 7), 0)).all()
 
 
 def test_tile_rejects_mismatched_layouts():
