@@ -117,7 +117,7 @@ typedef struct stb_layout {
     int32_t n_super;           /* tiled: ceil(n_blocks / 4), else 0 */
     int32_t sal_chunks;        /* tiled: records per half block in sal_tab = ceil(min(S, 64) / 8), else 0 */
     int32_t max_sal_block;     /* tiled: largest number of salient columns in one block (set by stb_tile) */
-    int32_t reserved;
+    int32_t max_sal_half;      /* tiled: largest number of salient columns in one half block of 64 columns (set by stb_tile) */
     int64_t mask_stride, sign_stride, region_stride, res_stride;   /* bytes per row (row-major) or per lane record (tiled; res_stride stays per row) */
     int64_t mask_bytes, sign_bytes, region_bytes, res_bytes,
             scales_bytes, res_scale_bytes, salmap_bytes, salprefix_bytes, saltab_bytes;
@@ -145,7 +145,7 @@ int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out);
 
 /* Host-side byte permutation STB1 -> tiled order (and back).  Both layouts must describe the same cfg and
  * be bound to caller-allocated host memory; every byte of the destination is written.  stb_tile also fills
- * dst->max_sal_block.  stb_untile(stb_tile(x)) == x bit for bit.
+ * dst->max_sal_block and dst->max_sal_half.  stb_untile(stb_tile(x)) == x bit for bit.
  * Errors: STB_ENULL, STB_EINVAL (kind or cfg mismatch), STB_EALIGN. */
 int stb_tile(const stb_layout_t* src_rowmajor, stb_layout_t* dst_tiled);
 int stb_untile(const stb_layout_t* src_tiled, stb_layout_t* dst_rowmajor);
@@ -203,15 +203,22 @@ int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const voi
 
 /* Prefill-time product (compute-bound regime, App. C: large N = batch x sequence length):
  *   Y[t][i] = sum_j X[t][j] * W_hat[i][j],  t < T.
- * The weights are dequantised to fp16 on the fly and contracted on the matrix cores with fp32
- * accumulation.  X: device fp16 [T][k].  Y: device [T][n], fp16 or fp32.  workspace: device scratch of at
- * least stb_gemm_workspace_bytes() bytes (may be NULL when that is 0).
+ * The weights are dequantised to fp16 on the fly and contracted on the matrix cores with fp32 accumulation.
+ * dev: the tiled kind runs the matrix-core kernel that expands the packed bits straight into MFMA operands
+ * (N:M in {2:4, 4:8, 6:8}; the residual term of the salient columns is a second, short contraction against
+ * the gathered salient columns of X, which the call first writes to the workspace); the row-major kind runs a
+ * generic kernel for any N:M (it rounds the dequantised salient weights to fp16).
+ * X: device fp16 [T][k].  Y: device [T][n], fp16 or fp32, fully overwritten.  workspace: device scratch of at
+ * least stb_gemm_workspace_bytes() bytes, 256-byte aligned (may be NULL when that is 0); it needs no
+ * initialisation.  Calls that share a workspace must not overlap in time.
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
 int stb_gemm(const stb_layout_t* dev, const void* X, int32_t T, void* Y, int32_t y_fp32,
              void* workspace, int64_t workspace_bytes, void* stream);
 
-/* Scratch bytes stb_gemm needs for (cfg, T); negative stb_status on a bad argument. */
-int64_t stb_gemm_workspace_bytes(const stb_cfg_t* cfg, int32_t T);
+/* Scratch bytes stb_gemm needs for (layout, T): the size fields of `layout` are read (for the tiled kind
+ * including max_sal_half, which stb_tile sets), its pointers are not.  Negative stb_status on a bad
+ * argument. */
+int64_t stb_gemm_workspace_bytes(const stb_layout_t* layout, int32_t T);
 
 /* Text for a status code (static storage). */
 const char* stb_strerror(int status);

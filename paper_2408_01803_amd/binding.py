@@ -41,7 +41,7 @@ class stb_layout_t(C.Structure):
         [("cfg", stb_cfg_t)]
         + [(name, C.c_int32) for name in (
             "n_salient_pad", "n_blocks", "kind", "n_row_tiles", "n_super", "sal_chunks", "max_sal_block",
-            "reserved")]
+            "max_sal_half")]
         + [(name, C.c_int64) for name in (
             "mask_stride", "sign_stride", "region_stride", "res_stride",
             "mask_bytes", "sign_bytes", "region_bytes", "res_bytes",
@@ -96,7 +96,7 @@ def _lib():
                                      P(C.c_void_p), C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
     lib.stb_gemm.argtypes = [P(stb_layout_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
                              C.c_void_p, C.c_int64, C.c_void_p]
-    lib.stb_gemm_workspace_bytes.argtypes = [P(stb_cfg_t), C.c_int32]
+    lib.stb_gemm_workspace_bytes.argtypes = [P(stb_layout_t), C.c_int32]
     lib.stb_gemm_workspace_bytes.restype = C.c_int64
     lib.stb_strerror.argtypes = [C.c_int]
     lib.stb_strerror.restype = C.c_char_p
@@ -212,8 +212,8 @@ def stb_gemv_batched(layouts_dev: Sequence[stb_layout_t], xs_dev, B: int, ys_dev
                                    C.c_void_p(_stream_ptr(stream))), "stb_gemv_batched")
 
 
-def stb_gemm_workspace_bytes(cfg: stb_cfg_t, T: int) -> int:
-    r = _lib().stb_gemm_workspace_bytes(C.byref(cfg), T)
+def stb_gemm_workspace_bytes(layout: stb_layout_t, T: int) -> int:
+    r = _lib().stb_gemm_workspace_bytes(C.byref(layout), T)
     if r < 0:
         raise StbError(int(r), "stb_gemm_workspace_bytes")
     return int(r)
@@ -221,11 +221,21 @@ def stb_gemm_workspace_bytes(cfg: stb_cfg_t, T: int) -> int:
 
 def stb_gemm(layout_dev: stb_layout_t, X_dev, T: int, Y_dev, y_fp32: bool = False, workspace=None,
              stream=None) -> None:
-    ws_ptr = workspace.data_ptr() if workspace is not None else 0
-    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    ws_ptr, ws_bytes = _ws(workspace)
     _check(_lib().stb_gemm(C.byref(layout_dev), C.c_void_p(X_dev.data_ptr()), T,
-                           C.c_void_p(Y_dev.data_ptr()), int(y_fp32), C.c_void_p(ws_ptr), ws_bytes,
+                           C.c_void_p(Y_dev.data_ptr()), int(y_fp32), ws_ptr, ws_bytes,
                            C.c_void_p(_stream_ptr(stream))), "stb_gemm")
+
+
+def new_device_scratch(nbytes: int, device="cuda:0", zero: bool = False):
+    """256-byte aligned uint8 device tensor of `nbytes` bytes (None for 0)."""
+    import torch
+    if nbytes == 0:
+        return None
+    make = torch.zeros if zero else torch.empty
+    raw = make(nbytes + STB_PLANE_ALIGN, dtype=torch.uint8, device=device)
+    off = (-raw.data_ptr()) % STB_PLANE_ALIGN
+    return raw[off:off + nbytes]
 
 
 # ---- holder --------------------------------------------------------------------------------------
@@ -294,13 +304,11 @@ class PackedMatrix:
 
     def new_workspace(self, device="cuda:0"):
         """Zero-filled stb_gemv scratch for this matrix (None if the shape needs none), 256-byte aligned."""
-        import torch
-        need = stb_gemv_workspace_bytes(self.cfg, STB_MAX_BATCH)
-        if need == 0:
-            return None
-        raw = torch.zeros(need + STB_PLANE_ALIGN, dtype=torch.uint8, device=device)
-        off = (-raw.data_ptr()) % STB_PLANE_ALIGN
-        return raw[off:off + need]
+        return new_device_scratch(stb_gemv_workspace_bytes(self.cfg, STB_MAX_BATCH), device, zero=True)
+
+    def new_gemm_workspace(self, T: int, device="cuda:0"):
+        """stb_gemm scratch for T tokens against the layout that is on the device (None if none is needed)."""
+        return new_device_scratch(stb_gemm_workspace_bytes(self.dev_layout, T), device)
 
     def clone_layout_for(self, base_ptr: int, tiled: bool = False) -> stb_layout_t:
         """Layout struct of the same matrix bound to another copy of the image (host or device)."""

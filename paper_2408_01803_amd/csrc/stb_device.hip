@@ -337,24 +337,33 @@ extern "C" int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev
     return STB_OK;
 }
 
-extern "C" int64_t stb_gemm_workspace_bytes(const stb_cfg_t* cfg, int32_t T) {
-    stb_layout_t tmp;
-    int rc = stb_layout_sizes(cfg, &tmp);
+extern "C" int64_t stb_gemm_workspace_bytes(const stb_layout_t* layout, int32_t T) {
+    if (!layout) return STB_ENULL;
+    stb_layout_t ref;
+    int rc = layout->kind == STB_KIND_TILED ? stb_tiled_sizes(&layout->cfg, &ref)
+                                            : (layout->kind == STB_KIND_ROWMAJOR ? stb_layout_sizes(&layout->cfg, &ref) : STB_EINVAL);
     if (rc) return rc;
     if (T < 1) return STB_EINVAL;
-    return 0;
+    if (layout->kind == STB_KIND_ROWMAJOR || !stb_tiled_supported(layout)) return 0;
+    if (layout->max_sal_half < 0 || layout->max_sal_half > 8 * ref.sal_chunks) return STB_EINVAL;
+    stb_layout_t tmp = ref;
+    tmp.max_sal_half = layout->max_sal_half;
+    return layout->cfg.n_salient > 0 ? stb_tiled_gemm_workspace(&tmp, T) : 0;
 }
 
 extern "C" int stb_gemm(const stb_layout_t* dev, const void* X, int32_t T, void* Y, int32_t y_fp32,
                         void* workspace, int64_t workspace_bytes, void* stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     if (!X || !Y) return STB_ENULL;
     int rc = stb_layout_check(dev);
     if (rc) return rc;
-    if (T < 1 || (y_fp32 != 0 && y_fp32 != 1)) return STB_EINVAL;
+    if (T < 1 || (y_fp32 != 0 && y_fp32 != 1) || workspace_bytes < 0) return STB_EINVAL;
     if ((uintptr_t)X % 16 || (uintptr_t)Y % 4) return STB_EALIGN;
-    if (dev->kind != STB_KIND_ROWMAJOR) return STB_EUNSUPPORTED;
+    if (dev->kind == STB_KIND_TILED) {
+        int herr = 0;
+        rc = stb_tiled_gemm(dev, X, T, Y, y_fp32, workspace, workspace_bytes, stream, &herr);
+        if (rc == STB_EHIP) g_last_hip_error = herr;
+        return rc;
+    }
     const Planes p = make_planes(dev);
     dim3 grid((p.n + GN - 1) / GN, (T + GT - 1) / GT);
     hipLaunchKernelGGL(gemm_generic_kernel, grid, dim3(256), 0, (hipStream_t)stream, p, (const __half*)X, T,

@@ -1,0 +1,243 @@
+// Prefill GEMM for the tiled device order (STB_KIND_TILED), gfx950 (App. C: the compute-bound regime).
+//
+//   Y[t][i] = sum_j X[t][j] * W_hat[i][j]
+//
+// A workgroup of four wavefronts owns 256 output rows x 128 tokens; wavefront w owns the four 16-row tiles
+// 4w .. 4w+3 of the block.  The weights never pass through memory in dequantised form: every lane expands
+// its (row, half block) bits straight into the A operand of v_mfma_f32_16x16x32_f16 (the code of
+// stb_tiled.hpp, as in the decode kernel), so K slot g of an MFMA is 8 columns of block g of the superblock.
+// The tokens are the B operand: a window of X (128 tokens x 4 blocks x 32 columns) is staged in LDS, double
+// buffered, and every B operand read from it feeds four MFMAs (one per row tile).
+// The residual term of the salient columns (Eq. 4) is a second, short contraction: its A operand comes from
+// residual_chunk, its B operand from a compact copy of the salient columns of X that gemm_gather_kernel
+// writes to the workspace beforehand.
+#include "stb_tiled.hpp"
+
+using namespace stbt;
+
+namespace {
+
+constexpr int GM_TOK = 128;           // tokens per workgroup
+constexpr int GM_ROWT = 16;           // 16-row tiles per workgroup (four per wavefront)
+constexpr int GM_XROW = 136;          // halves per token row of the LDS window: 4 x 32 columns + 8 of padding
+
+struct ScatterOne {
+    uint4 e[256];
+};
+
+// Workspace: xsal[T][E] fp16, E = nsb * 2 * cfix * 32; entry ((sb*2 + half)*cfix + c)*32 + g*8 + e holds X at the
+// e-th salient column of record c of (block 4*sb + g, half), 0 where the record has no such entry.
+__global__ __launch_bounds__(256) void gemm_gather_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
+                                                           __half* __restrict__ xsal, int cfix) {
+    const int per_tok = p.nsb * 2 * cfix * 4;                       // 16-byte pieces per token
+    const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= (int64_t)T * per_tok) return;
+    const int tok = (int)(id / per_tok), piece = (int)(id % per_tok);
+    const int g = piece & 3, c = (piece >> 2) % cfix, sh = (piece >> 2) / cfix;
+    const int q = 4 * (sh >> 1) + g, half = sh & 1;
+    uint32_t out[4] = {0u, 0u, 0u, 0u};
+    if (c < p.sal_chunks) {
+        const uint32_t* rec = p.sal_tab + (((int64_t)q * 2 + half) * p.sal_chunks + c) * 12;
+        const uint4 pv = *reinterpret_cast<const uint4*>(rec + 8);
+        const uint32_t pw[4] = {pv.x, pv.y, pv.z, pv.w};
+        const unsigned short* xrow = reinterpret_cast<const unsigned short*>(X) + (int64_t)tok * p.k + (int64_t)q * 128;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            const uint32_t pos = (pw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+            if (pos < 128u && q < p.nb) out[e >> 1] |= (uint32_t)xrow[pos] << (16 * (e & 1));
+        }
+    }
+    *reinterpret_cast<uint4*>(xsal + ((int64_t)tok * per_tok + piece) * 8) = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+template <int N8>
+__device__ inline uint4 lut1(const HalfData<N8>& d, int t, const ScatterOne* L) {
+    const uint32_t mb = (d.m[t >> 2] >> (8 * (t & 3))) & 0xFFu;
+    return L->e[mb];
+}
+
+template <int N8, bool HAS_RES>
+__global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
+                                                          void* __restrict__ Y, int y_fp32,
+                                                          const __half* __restrict__ xsal, int cfix) {
+    __shared__ ScatterOne lut;
+    __shared__ __attribute__((aligned(16))) _Float16 xs[2][GM_TOK * GM_XROW];
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int i = lane & 15, g = lane >> 4;
+    const int t0 = blockIdx.x * GM_TOK;
+    const int rtw = blockIdx.y * GM_ROWT + wave * 4;                // first row tile of this wavefront
+    for (int mb = tid; mb < 256; mb += blockDim.x) lut.e[mb] = scatter_entry<N8>((uint32_t)mb);
+
+    float4_t acc[4][8];
+#pragma unroll
+    for (int r = 0; r < 4; r++)
+#pragma unroll
+        for (int tt = 0; tt < 8; tt++) acc[r][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+    // ---- staging of the X window: 2048 pieces of 16 bytes, 8 per thread ----
+    // piece c: token c / 16, block (c / 4) % 4, 8 columns (c % 4) of the window
+    auto x_gload = [&](int sb, int half, int win, uint4 (&st)[8]) {
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const int c = tid + 256 * u;
+            const int tok = t0 + (c >> 4), gb = (c >> 2) & 3, cc = c & 3;
+            const int q = 4 * sb + gb;
+            st[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (tok < T && q < p.nb)
+                st[u] = *reinterpret_cast<const uint4*>(X + (int64_t)tok * p.k + (int64_t)q * 128 + 64 * half + 32 * win + 8 * cc);
+        }
+    };
+    auto x_lstore = [&](int buf, const uint4 (&st)[8]) {
+#pragma unroll
+        for (int u = 0; u < 8; u++) {
+            const int c = tid + 256 * u;
+            *reinterpret_cast<uint4*>(&xs[buf][(c >> 4) * GM_XROW + ((c >> 2) & 3) * 32 + (c & 3) * 8]) = st[u];
+        }
+    };
+    // four K steps on one window: groups 4*win .. 4*win + 3 of every lane's half block
+    auto window = [&](const HalfData<N8> (&hd)[4], const uint32_t (&TL)[4], const uint32_t (&TH)[4], int win, int buf) {
+#pragma unroll
+        for (int tq = 0; tq < 4; tq++) {
+            const int t = 4 * win + tq;
+            uint32_t a[4][4];
+#pragma unroll
+            for (int r = 0; r < 4; r++) expand_group<N8>(hd[r], TL[r], TH[r], t, lut1<N8>(hd[r], t, &lut), a[r]);
+#pragma unroll
+            for (int tt = 0; tt < 8; tt++) {
+                const half8_t b = *reinterpret_cast<const half8_t*>(&xs[buf][(16 * tt + i) * GM_XROW + g * 32 + tq * 8]);
+#pragma unroll
+                for (int r = 0; r < 4; r++)
+                    acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(a[r]), b, acc[r][tt], 0, 0, 0);
+            }
+        }
+    };
+    auto load_hd = [&](int sb, int half, HalfData<N8> (&hd)[4]) {
+        const LaneOffsets lo = lane_offsets<N8>(lane, half);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
+            load_half<N8>(p, (int64_t)rt * p.nsb + sb, lo, half, hd[r]);
+        }
+    };
+
+    uint4 st[8];
+    x_gload(0, 0, 0, st);
+    x_lstore(0, st);
+    __syncthreads();
+
+    const int nsh = p.nsb * 2;                                      // (superblock, half) pairs
+    for (int sh = 0; sh < nsh; sh++) {
+        const int sb = sh >> 1, half = sh & 1;
+        HalfData<N8> hd[4];
+        load_hd(sb, half, hd);
+        uint32_t TL[4], TH[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            TL[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x06040200u);
+            TH[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x07050301u);
+        }
+        // window 0 is in xs[0]; fetch window 1 while it is used
+        x_gload(sb, half, 1, st);
+        window(hd, TL, TH, 0, 0);
+        x_lstore(1, st);
+        __syncthreads();
+        const bool more = sh + 1 < nsh;
+        if (more) x_gload((sh + 1) >> 1, (sh + 1) & 1, 0, st);
+        window(hd, TL, TH, 1, 1);
+        if (HAS_RES) {
+            const int q = 4 * sb + g;
+            const uint32_t* rec0 = p.sal_tab + (((int64_t)q * 2 + half) * p.sal_chunks) * 12;
+            const int nch = __builtin_amdgcn_readfirstlane((int)rec0[5]);
+            for (int c = 0; c < nch; c++) {
+                const uint32_t* rec = rec0 + c * 12;
+                const uint4 ra = *reinterpret_cast<const uint4*>(rec);
+                ResSel sel;
+                sel.sel0 = ra.x; sel.sel1 = ra.y; sel.bit0 = ra.z; sel.bit1 = ra.w;
+                const uint32_t ord = rec[4];
+                const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+                const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+                uint32_t a[4][4];
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
+                    const uint32_t rlo = p.res_sign[((int64_t)rt * p.res_words + wa) * 16 + i];
+                    const uint32_t rhi = p.res_sign[((int64_t)rt * p.res_words + wb) * 16 + i];
+                    residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi, rlo, ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, a[r]);
+                }
+                const int64_t ecol = ((int64_t)sh * cfix + c) * 32 + g * 8;
+                const int64_t E = (int64_t)nsh * cfix * 32;
+#pragma unroll
+                for (int tt = 0; tt < 8; tt++) {
+                    const int tok = t0 + 16 * tt + i;
+                    uint4 bv = make_uint4(0u, 0u, 0u, 0u);
+                    if (tok < T) bv = *reinterpret_cast<const uint4*>(xsal + (int64_t)tok * E + ecol);
+                    const half8_t b = __builtin_bit_cast(half8_t, bv);
+#pragma unroll
+                    for (int r = 0; r < 4; r++)
+                        acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(a[r]), b, acc[r][tt], 0, 0, 0);
+                }
+            }
+        }
+        if (more) x_lstore(0, st);
+        __syncthreads();
+    }
+
+    // ---- epilogue: D[row][token] of an MFMA: lane l holds token l % 16, rows 4*(l / 16) + v ----
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        const int row = (rtw + r) * 16 + 4 * g;
+        if (rtw + r >= p.nrt) continue;
+#pragma unroll
+        for (int tt = 0; tt < 8; tt++) {
+            const int tok = t0 + 16 * tt + i;
+            if (tok >= T) continue;
+#pragma unroll
+            for (int v = 0; v < 4; v++) {
+                if (row + v >= p.n) continue;
+                const float val = -acc[r][tt][v];
+                if (y_fp32) reinterpret_cast<float*>(Y)[(int64_t)tok * p.n + row + v] = val;
+                else reinterpret_cast<__half*>(Y)[(int64_t)tok * p.n + row + v] = __float2half(val);
+            }
+        }
+    }
+}
+
+}  // namespace
+
+static int64_t round_up256(int64_t v) { return (v + 255) / 256 * 256; }
+static int cfix_of(const stb_layout_t* L) { return (L->max_sal_half + 7) / 8; }
+
+extern "C" int64_t stb_tiled_gemm_workspace(const stb_layout_t* L, int T) {
+    return round_up256((int64_t)T * L->n_super * 2 * cfix_of(L) * 32 * 2);
+}
+
+extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void* Y, int y_fp32, void* workspace,
+                              int64_t workspace_bytes, void* stream, int* hip_err) {
+    if (!stb_tiled_supported(L)) return STB_EUNSUPPORTED;
+    const TiledPlanes p = make_tiled(L);
+    const int cfix = cfix_of(L);
+    const bool res = p.res_words > 0 && cfix > 0;
+    const hipStream_t st = (hipStream_t)stream;
+    if (res) {
+        if (!workspace) return STB_ENULL;
+        if (workspace_bytes < stb_tiled_gemm_workspace(L, T)) return STB_EINVAL;
+        if ((uintptr_t)workspace % 256) return STB_EALIGN;
+        const int64_t pieces = (int64_t)T * p.nsb * 2 * cfix * 4;
+        hipLaunchKernelGGL(gemm_gather_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, p,
+                           (const __half*)X, T, (__half*)workspace, cfix);
+    }
+    const dim3 grid((T + GM_TOK - 1) / GM_TOK, (p.nrt + GM_ROWT - 1) / GM_ROWT);
+    const int n8 = 8 * L->cfg.N / L->cfg.M;
+    const __half* xh = (const __half*)X;
+    const __half* xs = (const __half*)workspace;
+    if (n8 == 4) {
+        if (res) hipLaunchKernelGGL((gemm_tiled_kernel<4, true>), grid, dim3(256), 0, st, p, xh, T, Y, y_fp32, xs, cfix);
+        else hipLaunchKernelGGL((gemm_tiled_kernel<4, false>), grid, dim3(256), 0, st, p, xh, T, Y, y_fp32, xs, cfix);
+    } else {
+        if (res) hipLaunchKernelGGL((gemm_tiled_kernel<6, true>), grid, dim3(256), 0, st, p, xh, T, Y, y_fp32, xs, cfix);
+        else hipLaunchKernelGGL((gemm_tiled_kernel<6, false>), grid, dim3(256), 0, st, p, xh, T, Y, y_fp32, xs, cfix);
+    }
+    const hipError_t e = hipGetLastError();
+    *hip_err = (int)e;
+    return e == hipSuccess ? STB_OK : STB_EHIP;
+}

@@ -210,7 +210,8 @@ extern "C" int stb_layout_check(const stb_layout_t* L) {
         L->region_stride != ref.region_stride || L->res_stride != ref.res_stride ||
         L->total_bytes != ref.total_bytes)
         return STB_EINVAL;
-    if (L->kind == STB_KIND_TILED && (L->max_sal_block < 0 || L->max_sal_block > 16 * L->sal_chunks)) return STB_EINVAL;
+    if (L->kind == STB_KIND_TILED && (L->max_sal_block < 0 || L->max_sal_block > 16 * L->sal_chunks ||
+                                      L->max_sal_half < 0 || L->max_sal_half > 8 * L->sal_chunks)) return STB_EINVAL;
     const void* ptrs[9] = {L->mask, L->sign, L->region, L->res_sign, L->scales, L->res_scale,
                            L->sal_bitmap, L->sal_block_prefix, L->sal_tab};
     for (int i = 0; i < 9; i++) {
@@ -261,9 +262,10 @@ void permute_records(const stb_layout_t* rm, const stb_layout_t* tl, bool to_til
 }
 
 // Fills the derived table of salient columns (layout in stb.h); returns the largest count of one block.
-int fill_sal_tab(const stb_layout_t* tl, const uint32_t* bitmap, int k, const uint32_t* prefix) {
+int fill_sal_tab(const stb_layout_t* tl, const uint32_t* bitmap, int k, const uint32_t* prefix, int* max_half) {
     const int nsb = tl->n_super, C = tl->sal_chunks;
     int mx = 0;
+    *max_half = 0;
     std::vector<int> cols;
     for (int sb = 0; sb < nsb; sb++) {
         int need[2] = {0, 0};
@@ -274,6 +276,7 @@ int fill_sal_tab(const stb_layout_t* tl, const uint32_t* bitmap, int k, const ui
                 const int j0 = (4 * sb + g) * 128 + 64 * h;
                 for (int j = j0; j < std::min(k, j0 + 64); j++) c += sal_bit(bitmap, j);
                 need[h] = std::max(need[h], (c + 7) / 8);
+                *max_half = std::max(*max_half, c);
                 blk += c;
             }
             mx = std::max(mx, blk);
@@ -322,6 +325,7 @@ extern "C" int stb_tile(const stb_layout_t* src, stb_layout_t* dst) {
     if (rc) return rc;
     if (!dst) return STB_ENULL;
     dst->max_sal_block = 0;
+    dst->max_sal_half = 0;
     rc = stb_layout_check(dst);
     if (rc) return rc;
     if (src->kind != STB_KIND_ROWMAJOR || dst->kind != STB_KIND_TILED || !same_cfg(src->cfg, dst->cfg))
@@ -337,8 +341,10 @@ extern "C" int stb_tile(const stb_layout_t* src, stb_layout_t* dst) {
     const int nb = src->n_blocks, nsb = dst->n_super, k = src->cfg.k_in;
     std::memcpy(dst->sal_bitmap, src->sal_bitmap, src->salmap_bytes);
     for (int q = 0; q <= nsb * 4; q++) dst->sal_block_prefix[q] = src->sal_block_prefix[std::min(q, nb)];
-    const int mx = dst->cfg.n_salient ? fill_sal_tab(dst, src->sal_bitmap, k, dst->sal_block_prefix) : 0;
+    int mh = 0;
+    const int mx = dst->cfg.n_salient ? fill_sal_tab(dst, src->sal_bitmap, k, dst->sal_block_prefix, &mh) : 0;
     dst->max_sal_block = mx;
+    dst->max_sal_half = mh;
     return STB_OK;
 }
 

@@ -18,6 +18,10 @@ int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_f
                    int64_t workspace_bytes, void* stream, int* hip_err);
 // Scratch bytes of the tiled decode kernel for L's shape (0 when k <= 4096).
 int64_t stb_tiled_gemv_workspace(int n_row_tiles, int n_super);
+// Prefill kernel for the tiled order (stb_gemm.hip) and its scratch size for T tokens.
+int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void* Y, int y_fp32, void* workspace,
+                   int64_t workspace_bytes, void* stream, int* hip_err);
+int64_t stb_tiled_gemm_workspace(const stb_layout_t* L, int T);
 #ifdef __cplusplus
 }
 #endif

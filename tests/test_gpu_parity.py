@@ -125,15 +125,13 @@ def test_gemv_small(small_case, torch_cuda, B, y_fp32):
 def test_gemm_small(small_case, torch_cuda, T):
     torch = torch_cuda
     c = small_case
-    if c["tiled"]:
-        pytest.skip("prefill kernel for the tiled order: not built yet")
     x = make_x(T, c["k"], c["seed"] + 1)
     y_ref, bound = O.matmul(x, c["What"])
     xd = torch.from_numpy(x).cuda()
     for y_fp32 in (False, True):
         yd = torch.full((T, c["n"]), float("nan"), dtype=torch.float32 if y_fp32 else torch.float16, device="cuda")
         _say(f"[step] stb_gemm T={T} fp32={y_fp32}")
-        S.stb_gemm(c["pm"].dev_layout, xd, T, yd, y_fp32)
+        S.stb_gemm(c["pm"].dev_layout, xd, T, yd, y_fp32, c["pm"].new_gemm_workspace(T))
         torch.cuda.synchronize()
         _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T}")
 
@@ -249,9 +247,13 @@ def test_full_size_layer(cfg, idx, torch_cuda):
         xd = torch.from_numpy(x).cuda()
         yd = torch.full((T, spec.n), float("nan"), dtype=torch.float16, device="cuda")
         _say(f"[step] stb_gemm T={T}")
-        S.stb_gemm(row_major.dev_layout, xd, T, yd)
-        torch.cuda.synchronize()
-        y = yd.float().cpu().numpy()
-        assert np.isfinite(y).all()
-        worst = _within_bound(y[rows], y_ref, bound, f"{key} gemm T={T}")
-        _say(f"       worst error / bound on {len(rows)} sampled tokens = {worst:.2e}")
+        for which, holder in (("row-major", row_major), ("tiled", pm if tiled else None)):
+            if holder is None:
+                continue
+            yd.fill_(float("nan"))
+            S.stb_gemm(holder.dev_layout, xd, T, yd, False, holder.new_gemm_workspace(T))
+            torch.cuda.synchronize()
+            y = yd.float().cpu().numpy()
+            assert np.isfinite(y).all()
+            worst = _within_bound(y[rows], y_ref, bound, f"{key} gemm T={T} {which}")
+            _say(f"       {which}: worst error / bound on {len(rows)} sampled tokens = {worst:.2e}")
