@@ -94,22 +94,41 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             *reinterpret_cast<uint4*>(&xs[buf][(c >> 4) * GM_XROW + ((c >> 2) & 3) * 32 + (c & 3) * 8]) = st[u];
         }
     };
-    // four K steps on one window: groups 4*win .. 4*win + 3 of every lane's half block
-    auto window = [&](const HalfData<N8> (&hd)[4], const uint32_t (&TL)[4], const uint32_t (&TH)[4], int win, int buf) {
+    // four K steps on one window: groups 4*win .. 4*win + 3 of every lane's half block.  The B operands and the
+    // expanded A operands of step s + 1 are produced while the 32 MFMAs of step s run.
+    auto bload = [&](int buf, int tq, uint4 (&b)[8]) {
 #pragma unroll
-        for (int tq = 0; tq < 4; tq++) {
-            const int t = 4 * win + tq;
-            uint32_t a[4][4];
+        for (int tt = 0; tt < 8; tt++)
+            b[tt] = *reinterpret_cast<const uint4*>(&xs[buf][(16 * tt + i) * GM_XROW + g * 32 + tq * 8]);
+    };
+    auto expand4 = [&](const HalfData<N8> (&hd)[4], const uint32_t (&TL)[4], const uint32_t (&TH)[4], int t, uint32_t (&a)[4][4]) {
 #pragma unroll
-            for (int r = 0; r < 4; r++) expand_group<N8>(hd[r], TL[r], TH[r], t, lut1<N8>(hd[r], t, &lut), a[r]);
+        for (int r = 0; r < 4; r++) expand_group<N8>(hd[r], TL[r], TH[r], t, lut1<N8>(hd[r], t, &lut), a[r]);
+    };
+    auto mfma32 = [&](const uint32_t (&a)[4][4], const uint4 (&b)[8]) {
 #pragma unroll
-            for (int tt = 0; tt < 8; tt++) {
-                const half8_t b = *reinterpret_cast<const half8_t*>(&xs[buf][(16 * tt + i) * GM_XROW + g * 32 + tq * 8]);
+        for (int tt = 0; tt < 8; tt++) {
+            const half8_t bv = __builtin_bit_cast(half8_t, b[tt]);
 #pragma unroll
-                for (int r = 0; r < 4; r++)
-                    acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(a[r]), b, acc[r][tt], 0, 0, 0);
-            }
+            for (int r = 0; r < 4; r++)
+                acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(a[r]), bv, acc[r][tt], 0, 0, 0);
         }
+    };
+    auto window = [&](const HalfData<N8> (&hd)[4], const uint32_t (&TL)[4], const uint32_t (&TH)[4], int win, int buf) {
+        uint4 b0[8], b1[8];
+        uint32_t a0[4][4], a1[4][4];
+        bload(buf, 0, b0);
+        expand4(hd, TL, TH, 4 * win, a0);
+        bload(buf, 1, b1);
+        expand4(hd, TL, TH, 4 * win + 1, a1);
+        mfma32(a0, b0);
+        bload(buf, 2, b0);
+        expand4(hd, TL, TH, 4 * win + 2, a0);
+        mfma32(a1, b1);
+        bload(buf, 3, b1);
+        expand4(hd, TL, TH, 4 * win + 3, a1);
+        mfma32(a0, b0);
+        mfma32(a1, b1);
     };
     auto load_hd = [&](int sb, int half, HalfData<N8> (&hd)[4]) {
         const LaneOffsets lo = lane_offsets<N8>(lane, half);
