@@ -20,6 +20,7 @@ namespace {
 constexpr int GM_TOK = 128;           // tokens per workgroup
 constexpr int GM_ROWT = 16;           // 16-row tiles per workgroup (four per wavefront)
 constexpr int GM_XROW = 136;          // halves per token row of the LDS window: 4 x 32 columns + 8 of padding
+constexpr int GM_XROW1 = 168;         // second buffer: + 4 x 8 gathered salient columns (residual contraction)
 
 struct ScatterOne {
     uint4 e[256];
@@ -61,7 +62,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
                                                           void* __restrict__ Y, int y_fp32,
                                                           const __half* __restrict__ xsal, int cfix) {
     __shared__ ScatterOne lut;
-    __shared__ __attribute__((aligned(16))) _Float16 xs[2][GM_TOK * GM_XROW];
+    __shared__ __attribute__((aligned(16))) _Float16 xs0[GM_TOK * GM_XROW];
+    __shared__ __attribute__((aligned(16))) _Float16 xs1[GM_TOK * GM_XROW1];
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int i = lane & 15, g = lane >> 4;
     const int t0 = blockIdx.x * GM_TOK;
@@ -88,18 +90,45 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         }
     };
     auto x_lstore = [&](int buf, const uint4 (&st)[8]) {
+        _Float16* dst = buf ? xs1 : xs0;
+        const int stride = buf ? GM_XROW1 : GM_XROW;
 #pragma unroll
         for (int u = 0; u < 8; u++) {
             const int c = tid + 256 * u;
-            *reinterpret_cast<uint4*>(&xs[buf][(c >> 4) * GM_XROW + ((c >> 2) & 3) * 32 + (c & 3) * 8]) = st[u];
+            *reinterpret_cast<uint4*>(&dst[(c >> 4) * stride + ((c >> 2) & 3) * 32 + (c & 3) * 8]) = st[u];
+        }
+    };
+    // the gathered salient columns of this (superblock, half), record c: 128 tokens x 4 pieces of 16 bytes
+    const int64_t E = (int64_t)p.nsb * 2 * cfix * 32;               // halves per token in xsal
+    auto r_gload = [&](int sh, int c, uint4 (&sr)[2]) {
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            const int pc = tid + 256 * u;
+            const int tok = t0 + (pc >> 2), gb = pc & 3;
+            sr[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (HAS_RES && tok < T) sr[u] = *reinterpret_cast<const uint4*>(xsal + (int64_t)tok * E + ((int64_t)sh * cfix + c) * 32 + gb * 8);
+        }
+    };
+    auto r_lstore = [&](const uint4 (&sr)[2]) {
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+            const int pc = tid + 256 * u;
+            *reinterpret_cast<uint4*>(&xs1[(pc >> 2) * GM_XROW1 + 128 + (pc & 3) * 8]) = sr[u];
         }
     };
     // four K steps on one window: groups 4*win .. 4*win + 3 of every lane's half block.  The B operands and the
     // expanded A operands of step s + 1 are produced while the 32 MFMAs of step s run.
     auto bload = [&](int buf, int tq, uint4 (&b)[8]) {
+        const _Float16* src = buf ? xs1 : xs0;
+        const int stride = buf ? GM_XROW1 : GM_XROW;
 #pragma unroll
         for (int tt = 0; tt < 8; tt++)
-            b[tt] = *reinterpret_cast<const uint4*>(&xs[buf][(16 * tt + i) * GM_XROW + g * 32 + tq * 8]);
+            b[tt] = *reinterpret_cast<const uint4*>(&src[(16 * tt + i) * stride + g * 32 + tq * 8]);
+    };
+    auto bload_res = [&](uint4 (&b)[8]) {
+#pragma unroll
+        for (int tt = 0; tt < 8; tt++)
+            b[tt] = *reinterpret_cast<const uint4*>(&xs1[(16 * tt + i) * GM_XROW1 + 128 + g * 8]);
     };
     auto expand4 = [&](const HalfData<N8> (&hd)[4], const uint32_t (&TL)[4], const uint32_t (&TH)[4], int t, uint32_t (&a)[4][4]) {
 #pragma unroll
@@ -145,56 +174,78 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     __syncthreads();
 
     const int nsh = p.nsb * 2;                                      // (superblock, half) pairs
+    auto load_res_words = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) {
+        const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+        const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
+            rlo[r] = p.res_sign[((int64_t)rt * p.res_words + wa) * 16 + i];
+            rhi[r] = p.res_sign[((int64_t)rt * p.res_words + wb) * 16 + i];
+        }
+    };
+    // residual contraction of one record: A from the mask / res_sign bits, B = the gathered columns in xs1
+    auto residual = [&](const HalfData<N8> (&hd)[4], const uint4& ra, uint32_t ord, const uint32_t (&rlo)[4],
+                        const uint32_t (&rhi)[4]) {
+        ResSel sel;
+        sel.sel0 = ra.x; sel.sel1 = ra.y; sel.bit0 = ra.z; sel.bit1 = ra.w;
+        uint4 b[8];
+        bload_res(b);
+        uint32_t a[4][4];
+#pragma unroll
+        for (int r = 0; r < 4; r++)
+            residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, a[r]);
+        mfma32(a, b);
+    };
+
     for (int sh = 0; sh < nsh; sh++) {
         const int sb = sh >> 1, half = sh & 1;
+        const bool more = sh + 1 < nsh;
         HalfData<N8> hd[4];
         load_hd(sb, half, hd);
+        // the table record of this (superblock, half) and, through it, the residual sign words of the rows
+        uint4 ra = make_uint4(0u, 0u, 0u, 0u);
+        uint2 rb = make_uint2(0u, 0u);
+        const uint32_t* rec0 = nullptr;
+        if (HAS_RES) {
+            rec0 = p.sal_tab + (((int64_t)(4 * sb + g) * 2 + half) * p.sal_chunks) * 12;
+            ra = *reinterpret_cast<const uint4*>(rec0);
+            rb = *reinterpret_cast<const uint2*>(rec0 + 4);
+        }
         uint32_t TL[4], TH[4];
 #pragma unroll
         for (int r = 0; r < 4; r++) {
             TL[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x06040200u);
             TH[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x07050301u);
         }
-        // window 0 is in xs[0]; fetch window 1 while it is used
+        // window 0 is in xs0; fetch window 1 and the gathered salient columns while it is used
+        uint4 sr[2];
         x_gload(sb, half, 1, st);
+        r_gload(sh, 0, sr);
         window(hd, TL, TH, 0, 0);
         x_lstore(1, st);
+        if (HAS_RES) r_lstore(sr);
+        uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
+        int nch = 0;
+        if (HAS_RES) {
+            nch = __builtin_amdgcn_readfirstlane((int)rb.y);
+            if (nch > 0) load_res_words(rb.x, rlo, rhi);
+        }
         __syncthreads();
-        const bool more = sh + 1 < nsh;
         if (more) x_gload((sh + 1) >> 1, (sh + 1) & 1, 0, st);
         window(hd, TL, TH, 1, 1);
-        if (HAS_RES) {
-            const int q = 4 * sb + g;
-            const uint32_t* rec0 = p.sal_tab + (((int64_t)q * 2 + half) * p.sal_chunks) * 12;
-            const int nch = __builtin_amdgcn_readfirstlane((int)rec0[5]);
-            for (int c = 0; c < nch; c++) {
+        if (HAS_RES && nch > 0) {
+            residual(hd, ra, rb.x, rlo, rhi);
+            for (int c = 1; c < nch; c++) {              // half blocks with more than 8 salient columns (rare)
+                __syncthreads();                         // every wavefront is done with the gathered columns
+                r_gload(sh, c, sr);
+                r_lstore(sr);
                 const uint32_t* rec = rec0 + c * 12;
-                const uint4 ra = *reinterpret_cast<const uint4*>(rec);
-                ResSel sel;
-                sel.sel0 = ra.x; sel.sel1 = ra.y; sel.bit0 = ra.z; sel.bit1 = ra.w;
+                const uint4 rc = *reinterpret_cast<const uint4*>(rec);
                 const uint32_t ord = rec[4];
-                const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
-                const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
-                uint32_t a[4][4];
-#pragma unroll
-                for (int r = 0; r < 4; r++) {
-                    const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
-                    const uint32_t rlo = p.res_sign[((int64_t)rt * p.res_words + wa) * 16 + i];
-                    const uint32_t rhi = p.res_sign[((int64_t)rt * p.res_words + wb) * 16 + i];
-                    residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi, rlo, ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, a[r]);
-                }
-                const int64_t ecol = ((int64_t)sh * cfix + c) * 32 + g * 8;
-                const int64_t E = (int64_t)nsh * cfix * 32;
-#pragma unroll
-                for (int tt = 0; tt < 8; tt++) {
-                    const int tok = t0 + 16 * tt + i;
-                    uint4 bv = make_uint4(0u, 0u, 0u, 0u);
-                    if (tok < T) bv = *reinterpret_cast<const uint4*>(xsal + (int64_t)tok * E + ecol);
-                    const half8_t b = __builtin_bit_cast(half8_t, bv);
-#pragma unroll
-                    for (int r = 0; r < 4; r++)
-                        acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(a[r]), b, acc[r][tt], 0, 0, 0);
-                }
+                load_res_words(ord, rlo, rhi);
+                __syncthreads();
+                residual(hd, rc, ord, rlo, rhi);
             }
         }
         if (more) x_lstore(0, st);
