@@ -4,12 +4,16 @@
 
 A step is one decode pass over workload 2 (the LLaMA-7B MLP linears 11008x4096 and 4096x11008 at 2:4 with
 the residual salient plane): stb_gemv at batch 1, 4 and 16 on both layers, i.e. six launches.  Each launch
-reads a different copy of the packed weights out of a pool of more than 1 GiB, so the weights come from
-HBM and not from the 256 MB last-level cache.  Inputs are resident in HBM before the timed region.
-`value` is packed-weight GB/s over the whole timed region (launch gaps included).
+reads a different copy of the packed weights (tiled device order) out of a pool of more than 1 GiB, so the
+weights come from HBM and not from the 256 MB last-level cache.  Inputs are resident in HBM before the timed
+region.  `value` is packed-weight GB/s (STB1 bytes) over the whole timed region, launch gaps included.
 
-After the timed decode steps the prefill leg (stb_gemm, workload 4 shapes at 4:8) and the CPU oracle are
-timed and reported in the same JSON line under "gemm" and "cpu_baseline".
+`roofline` describes the dominant kernel, the decode GEMV: algorithmic bytes per launch (packed planes + x + y)
+divided by the average time of one launch, measured with events on the launch stream over the same timed
+region.  After the timed steps the same JSON line gets: a per-(layer, batch) breakdown, the streaming-read
+rate of a plain 128-bit-load kernel on a buffer of the same size ("stream_read_roof"), the largest decode
+layers of workload 5 ("decode_large"), the prefill leg (stb_gemm on workload 4 shapes, tiled order, with its
+own roofline against the fp16 matrix peak) and the CPU oracle timed on this machine's host cores.
 """
 from __future__ import annotations
 
@@ -28,6 +32,11 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16/bf16 matrix peak, vendor figure
 POOL_BYTES = 1 << 30
+
+# HBM bytes per decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this command, scaled by what
+# the same counters read for a copy of known size; see profiles/gemv_stream_workload2_decode.md.
+# None until measured for the current kernels.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
 
 
 def log(*a):
@@ -50,6 +59,20 @@ def build_pool(S, torch, pm, pool_bytes, tiled=True):
     return buf, layouts
 
 
+def timed(torch, fn, reps, warm=3):
+    """Average time of fn() in microseconds, events on the current stream."""
+    for _ in range(warm):
+        fn(0)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for r in range(reps):
+        fn(r)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +80,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-gemm", action="store_true", help="skip the prefill leg")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-graph", action="store_true", help="time host-side launches instead of a HIP graph replay")
+    ap.add_argument("--no-extra", action="store_true", help="skip the breakdown, roof probe and large decode layers")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -105,35 +130,41 @@ def main():
         decode_step()
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # (1) launched one by one from the host
     ev0.record()
     for _ in range(a.steps):
         decode_step()
     ev1.record()
     torch.cuda.synchronize()
-    ms = ev0.elapsed_time(ev1)
-    ms_per_step = ms / a.steps
+    eager_ms_per_step = ev0.elapsed_time(ev1) / a.steps
+    # (2) the same K steps captured once in a HIP graph and replayed: the decode loop is launch-bound from the
+    #     host side (a launch through the binding costs more host time than the kernel runs), so this is how a
+    #     serving loop would issue it.  The timed region is one replay = exactly K steps.
+    ms_per_step = eager_ms_per_step
+    launch_mode = "stream launches from the host"
+    if not a.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(a.steps):
+                    decode_step()
+            graph.replay()                       # untimed replay
+            side.synchronize()
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record(side)
+            graph.replay()
+            g1.record(side)
+            side.synchronize()
+        ms_per_step = g0.elapsed_time(g1) / a.steps
+        launch_mode = "one HIP graph of the K steps, replayed"
+        torch.cuda.current_stream().wait_stream(side)
     value = packed_per_step / (ms_per_step * 1e-3) / 1e9
     launch_us = ms_per_step * 1e3 / launches_per_step
     achieved = (algo_per_step / launches_per_step) / (launch_us * 1e-6) / 1e9
-    log(f"decode: {ms_per_step:.3f} ms/step, {launch_us:.1f} us/launch, {value:.1f} GB/s packed")
-
-    # per-(layer, B) breakdown, same protocol, untimed for the headline
-    breakdown = []
-    for ly in layers:
-        for B in batches:
-            reps = 40
-            for _ in range(3):
-                S.stb_gemv(ly["layouts"][0], ly["xs"][B], B, ly["ys"][B], False, ly["ws"])
-            torch.cuda.synchronize()
-            ev0.record()
-            for r in range(reps):
-                S.stb_gemv(ly["layouts"][r % len(ly["layouts"])], ly["xs"][B], B, ly["ys"][B], False, ly["ws"])
-            ev1.record()
-            torch.cuda.synchronize()
-            us = ev0.elapsed_time(ev1) * 1e3 / reps
-            breakdown.append(dict(layer=ly["spec"].name, B=B, us=round(us, 2),
-                                  packed_gbs=round(ly["pm"].packed_bytes / us / 1e3, 1)))
-    log("decode breakdown:", breakdown)
+    log(f"decode: {ms_per_step:.4f} ms/step ({launch_mode}; {eager_ms_per_step:.4f} ms/step launched one by one), "
+        f"{launch_us:.2f} us/launch, {value:.1f} GB/s packed")
 
     result = {
         "metric": "packed-weight GB/s (GEMV) & TFLOP/s (GEMM), % of MI355X HBM/MFMA roofline",
@@ -151,13 +182,62 @@ def main():
         "config": {"workload": "configs[1]: LLaMA-7B MLP linears 11008x4096 + 4096x11008, 2:4 structured binary "
                                "with residual salient plane, decode GEMV at batch 1, 4, 16 (6 launches per step)",
                    "packed_bytes_per_step": packed_per_step,
-                   "pool_bytes": int(sum(ly["buf"].numel() for ly in layers))},
+                   "pool_bytes": int(sum(ly["buf"].numel() for ly in layers)),
+                   "launch": launch_mode,
+                   "ms_per_step_host_launches": round(eager_ms_per_step, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "stb_gemv", "us_per_launch": round(launch_us, 2),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
+                     "kernel": "gemv_stream_kernel (stb_gemv)", "us_per_launch": round(launch_us, 2),
                      "algorithmic_bytes_per_launch": int(algo_per_step / launches_per_step)},
-        "decode_breakdown": breakdown,
     }
+
+    if not a.no_extra:
+        # per-(layer, B) breakdown, same protocol
+        breakdown = []
+        for ly in layers:
+            for B in batches:
+                us = timed(torch, lambda r: S.stb_gemv(ly["layouts"][r % len(ly["layouts"])], ly["xs"][B], B,
+                                                       ly["ys"][B], False, ly["ws"]), 40)
+                breakdown.append(dict(layer=ly["spec"].name, B=B, us=round(us, 2),
+                                      packed_gbs=round(ly["pm"].packed_bytes / us / 1e3, 1)))
+        log("decode breakdown:", breakdown)
+        result["decode_breakdown"] = breakdown
+        # streaming-read rate of a plain kernel on a buffer of one layer's size, same rotation over the pool
+        ly = layers[0]
+        nbytes = ly["pm"].packed_bytes // 16 * 16
+        sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
+        base = ly["buf"]
+        off0 = (-base.data_ptr()) % 256
+        stride = (nbytes + 255) // 256 * 256
+        ncopy = (base.numel() - off0) // stride
+        us = timed(torch, lambda r: S.stb_probe_read(base[off0 + (r % ncopy) * stride:], nbytes, sink), 40)
+        result["stream_read_roof"] = {"bytes": nbytes, "us": round(us, 2), "gbs": round(nbytes / us / 1e3, 1),
+                                      "note": "plain 128-bit-load read kernel on a buffer of one layer's packed size, "
+                                              "same launch-to-launch timing"}
+        log("stream read roof:", result["stream_read_roof"])
+    for ly in layers:
+        del ly["buf"], ly["layouts"]
+    torch.cuda.empty_cache()
+
+    if not a.no_extra:
+        # the two largest decode layers of workload 5 (B = 1): where the stream is long enough to ramp up
+        large = []
+        for spec in (WORKLOADS[5]["layers"][4], WORKLOADS[5]["layers"][6]):
+            L = make_layer(spec.n, spec.k, spec.seed, spec.salient_kind)
+            pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], spec.N, spec.M, spec.region_mode)
+            del L
+            buf, layouts = build_pool(S, torch, pm, POOL_BYTES)
+            ws = pm.new_workspace()
+            x = torch.from_numpy(make_x(1, spec.k, spec.seed)).cuda()
+            y = torch.empty((1, spec.n), dtype=torch.float16, device="cuda")
+            us = timed(torch, lambda r: S.stb_gemv(layouts[r % len(layouts)], x, 1, y, False, ws), 40)
+            large.append(dict(layer=spec.name, n=spec.n, k=spec.k, nm=f"{spec.N}:{spec.M}", B=1, us=round(us, 2),
+                              packed_mb=round(pm.packed_bytes / 1e6, 1), packed_gbs=round(pm.packed_bytes / us / 1e3, 1),
+                              frac_of_hbm_peak=round(pm.packed_bytes / us / 1e3 / HBM_PEAK_GBS, 4)))
+            log("decode large:", large[-1])
+            del buf, layouts, pm
+            torch.cuda.empty_cache()
+        result["decode_large"] = large
 
     # ---------------- prefill leg: workload 4 shapes ----------------
     if not a.no_gemm:
@@ -165,30 +245,24 @@ def main():
         for spec, T, reps in ((WORKLOADS[4]["layers"][0], 2048, 10), (WORKLOADS[4]["layers"][1], 8192, 3)):
             L = make_layer(spec.n, spec.k, spec.seed, spec.salient_kind)
             pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], spec.N, spec.M, spec.region_mode)
-            pm.to_device()
+            pm.to_device(tiled=True)
             del L
             X = torch.from_numpy(make_x(T, spec.k, spec.seed)).cuda()
             Y = torch.empty((T, spec.n), dtype=torch.float16, device="cuda")
-            for _ in range(2):
-                S.stb_gemm(pm.dev_layout, X, T, Y)
-            torch.cuda.synchronize()
-            ev0.record()
-            for _ in range(reps):
-                S.stb_gemm(pm.dev_layout, X, T, Y)
-            ev1.record()
-            torch.cuda.synchronize()
-            us = ev0.elapsed_time(ev1) * 1e3 / reps
+            ws = pm.new_gemm_workspace(T)
+            us = timed(torch, lambda r: S.stb_gemm(pm.dev_layout, X, T, Y, False, ws), reps, warm=2)
             flops = 2.0 * T * spec.n * spec.k
             tf = flops / us / 1e6
             gemm.append(dict(T=T, n=spec.n, k=spec.k, nm=f"{spec.N}:{spec.M}", us=round(us, 1),
                              tflops=round(tf, 2), frac_of_f16_mfma_peak=round(tf / MFMA_F16_PEAK_TFLOPS, 4)))
             log("gemm:", gemm[-1])
-            del pm, X, Y
+            del pm, X, Y, ws
         best = max(gemm, key=lambda g: g["tflops"])
         result["gemm"] = {"cases": gemm,
                           "roofline": {"bound": "mfma", "achieved": best["tflops"], "peak": MFMA_F16_PEAK_TFLOPS,
                                        "unit": "TFLOP/s", "frac": best["frac_of_f16_mfma_peak"], "traffic": None,
-                                       "kernel": "stb_gemm"}}
+                                       "kernel": "gemm_tiled_kernel (stb_gemm), flops = 2*T*n*k executed on the "
+                                                 "dequantised tile"}}
 
     # ---------------- CPU baseline: the oracle as it stands, on this machine's host cores ----------------
     if not a.no_cpu:

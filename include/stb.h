@@ -220,6 +220,13 @@ int stb_gemm(const stb_layout_t* dev, const void* X, int32_t T, void* Y, int32_t
  * argument. */
 int64_t stb_gemm_workspace_bytes(const stb_layout_t* layout, int32_t T);
 
+/* Measurement aid: reads `bytes` bytes (a multiple of 16, 16-byte aligned) of device memory with 128-bit loads
+ * from every compute unit and writes one 32-bit checksum per workgroup to `sink` (device, at least 4096
+ * bytes).  Timing it gives the streaming-read rate this GPU reaches on a buffer of that size, the practical
+ * ceiling that the decode kernel's packed-weight GB/s is compared with.
+ * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
+int stb_probe_read(const void* src, int64_t bytes, void* sink, void* stream);
+
 /* Text for a status code (static storage). */
 const char* stb_strerror(int status);
 

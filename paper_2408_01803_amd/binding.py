@@ -67,7 +67,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 _LIB = None
 
 EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_dequant", "stb_gemv",
-           "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_strerror", "stb_last_hip_error")
+           "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_strerror", "stb_last_hip_error")
 
 
 def _lib():
@@ -98,6 +98,8 @@ def _lib():
                              C.c_void_p, C.c_int64, C.c_void_p]
     lib.stb_gemm_workspace_bytes.argtypes = [P(stb_layout_t), C.c_int32]
     lib.stb_gemm_workspace_bytes.restype = C.c_int64
+    lib.stb_probe_read.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+    lib.stb_probe_read.restype = C.c_int
     lib.stb_strerror.argtypes = [C.c_int]
     lib.stb_strerror.restype = C.c_char_p
     lib.stb_last_hip_error.restype = C.c_int
@@ -225,6 +227,11 @@ def stb_gemm(layout_dev: stb_layout_t, X_dev, T: int, Y_dev, y_fp32: bool = Fals
     _check(_lib().stb_gemm(C.byref(layout_dev), C.c_void_p(X_dev.data_ptr()), T,
                            C.c_void_p(Y_dev.data_ptr()), int(y_fp32), ws_ptr, ws_bytes,
                            C.c_void_p(_stream_ptr(stream))), "stb_gemm")
+
+
+def stb_probe_read(src_dev, nbytes: int, sink_dev, stream=None) -> None:
+    _check(_lib().stb_probe_read(C.c_void_p(src_dev.data_ptr()), nbytes, C.c_void_p(sink_dev.data_ptr()),
+                                 C.c_void_p(_stream_ptr(stream))), "stb_probe_read")
 
 
 def new_device_scratch(nbytes: int, device="cuda:0", zero: bool = False):

@@ -246,6 +246,26 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Planes p, const __hal
     }
 }
 
+// Streaming read of a buffer: every workgroup pulls a contiguous slice, 4 x 16 bytes per lane in flight.
+__global__ __launch_bounds__(512) void probe_read_kernel(const uint4* __restrict__ src, int64_t n16, uint32_t* __restrict__ sink) {
+    const int64_t per = (n16 + gridDim.x - 1) / gridDim.x;
+    const int64_t lo = per * blockIdx.x, hi = lo + per < n16 ? lo + per : n16;
+    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+    for (int64_t i = lo + threadIdx.x; i < hi; i += 4 * blockDim.x) {
+        uint4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int64_t idx = i + (int64_t)j * blockDim.x;
+            v[j] = idx < hi ? src[idx] : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; j++) { acc.x ^= v[j].x; acc.y ^= v[j].y; acc.z ^= v[j].z; acc.w ^= v[j].w; }
+    }
+    uint32_t r = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    for (int off = 32; off > 0; off >>= 1) r ^= __shfl_xor(r, off, 64);
+    if ((threadIdx.x & 63) == 0) atomicXor(sink + (blockIdx.x & 1023), r);
+}
+
 template <int B>
 hipError_t launch_gemv_generic(const Planes& p, const void* x, void* y, int y_fp32, hipStream_t s) {
     const int blocks = (p.n + 3) / 4;
@@ -259,6 +279,16 @@ hipError_t launch_gemv_generic(const Planes& p, const void* x, void* y, int y_fp
 // C ABI
 // ------------------------------------------------------------------------------------------------
 extern "C" int stb_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" int stb_probe_read(const void* src, int64_t bytes, void* sink, void* stream) {
+    if (!src || !sink) return STB_ENULL;
+    if (bytes < 16 || bytes % 16) return STB_EINVAL;
+    if ((uintptr_t)src % 16 || (uintptr_t)sink % 4) return STB_EALIGN;
+    hipLaunchKernelGGL(probe_read_kernel, dim3(1024), dim3(512), 0, (hipStream_t)stream, (const uint4*)src, bytes / 16,
+                       (uint32_t*)sink);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? STB_OK : hip_fail(e);
+}
 
 extern "C" int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream) {
     if (!W_hat_dev) return STB_ENULL;

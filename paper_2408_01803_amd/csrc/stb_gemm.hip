@@ -22,10 +22,6 @@ constexpr int GM_ROWT = 16;           // 16-row tiles per workgroup (four per wa
 constexpr int GM_XROW = 136;          // halves per token row of the LDS window: 4 x 32 columns + 8 of padding
 constexpr int GM_XROW1 = 168;         // second buffer: + 4 x 8 gathered salient columns (residual contraction)
 
-struct ScatterOne {
-    uint4 e[256];
-};
-
 // Workspace: xsal[T][E] fp16, E = nsb * 2 * cfix * 32; entry ((sb*2 + half)*cfix + c)*32 + g*8 + e holds X at the
 // e-th salient column of record c of (block 4*sb + g, half), 0 where the record has no such entry.
 __global__ __launch_bounds__(256) void gemm_gather_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
@@ -51,24 +47,18 @@ __global__ __launch_bounds__(256) void gemm_gather_kernel(TiledPlanes p, const _
     *reinterpret_cast<uint4*>(xsal + ((int64_t)tok * per_tok + piece) * 8) = make_uint4(out[0], out[1], out[2], out[3]);
 }
 
-template <int N8>
-__device__ inline uint4 lut1(const HalfData<N8>& d, int t, const ScatterOne* L) {
-    const uint32_t mb = (d.m[t >> 2] >> (8 * (t & 3))) & 0xFFu;
-    return L->e[mb];
-}
-
 template <int N8, bool HAS_RES>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                           void* __restrict__ Y, int y_fp32,
                                                           const __half* __restrict__ xsal, int cfix) {
-    __shared__ ScatterOne lut;
+    __shared__ ScatterLds lut;
     __shared__ __attribute__((aligned(16))) _Float16 xs0[GM_TOK * GM_XROW];
     __shared__ __attribute__((aligned(16))) _Float16 xs1[GM_TOK * GM_XROW1];
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int i = lane & 15, g = lane >> 4;
     const int t0 = blockIdx.x * GM_TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;                // first row tile of this wavefront
-    for (int mb = tid; mb < 256; mb += blockDim.x) lut.e[mb] = scatter_entry<N8>((uint32_t)mb);
+    build_luts<N8>(&lut);
 
     float4_t acc[4][8];
 #pragma unroll
@@ -132,7 +122,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     };
     auto expand4 = [&](const HalfData<N8> (&hd)[4], const uint32_t (&TL)[4], const uint32_t (&TH)[4], int t, uint32_t (&a)[4][4]) {
 #pragma unroll
-        for (int r = 0; r < 4; r++) expand_group<N8>(hd[r], TL[r], TH[r], t, lut1<N8>(hd[r], t, &lut), a[r]);
+        for (int r = 0; r < 4; r++) expand_group<N8>(hd[r], TL[r], TH[r], t, lut_fetch<N8>(hd[r], t, &lut, lane & 7), a[r]);
     };
     auto mfma32 = [&](const uint32_t (&a)[4][4], const uint4 (&b)[8]) {
 #pragma unroll
