@@ -35,8 +35,8 @@ POOL_BYTES = 1 << 30
 
 # HBM bytes per decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this command, scaled by what
 # the same counters read for a copy of known size; see profiles/gemv_stream_workload2_decode.md.
-# None until measured for the current kernels.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+# Average over the six launches of a step (read + written).
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 19.0e6
 
 
 def log(*a):
