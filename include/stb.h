@@ -183,7 +183,8 @@ int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream);
  * x: device fp16 [B][k] row-major.  y: device [B][n] row-major, fp16 (y_fp32 = 0) or fp32 (y_fp32 = 1),
  * fully overwritten.  Accumulation is fp32.
  * workspace: device scratch of at least stb_gemv_workspace_bytes() bytes, 256-byte aligned (may be NULL when
- * that is 0).  It holds the partial sums and arrival counters of the column splits used when k > 4096.  The
+ * that is 0).  It holds the partial sums and arrival counters of the column splits (always used when
+ * k > 4096; for smaller k the launcher may still split columns to balance the grid).  The
  * counters (its first 4 * ceil(n / 16) bytes) must be zero before the first call that uses the buffer; every
  * call leaves them zero.  Calls that share a workspace must not overlap in time.
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */

@@ -119,7 +119,7 @@ __device__ inline ResInv load_res_inv(const TiledPlanes& p, int q, int half, int
 
 template <int N8, bool HAS_RES>
 __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const __half* __restrict__ x, int B,
-                                                            void* __restrict__ y, int y_fp32, int R,
+                                                            void* __restrict__ y, int y_fp32, int R, int SPS,
                                                             float* __restrict__ ws_part, uint32_t* __restrict__ ws_count) {
     __shared__ ScatterLds lut;
     __shared__ uint32_t ticket;
@@ -127,14 +127,20 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int i = lane & 15, g = lane >> 4;
     const int gr = blockIdx.x, ks = blockIdx.y, S = gridDim.y;
-    const int r0 = gr * R;
+    // Column split ks covers the SPS superblocks ks*SPS .. ks*SPS + SPS - 1; 2*SPS wavefronts (one per half
+    // block) form a row stream, and the 16 wavefronts of the workgroup hold RS = 16 / (2*SPS) row streams of R
+    // tiles each (SPS = 8: one stream, all of a 4096-column slice; SPS = 2: four streams on 1024 columns, which
+    // keeps the x traffic of a workgroup small when B is large).
+    const int WS = 2 * SPS, RS = 16 / WS;
+    const int rs = wave / WS, within = wave - rs * WS;
+    const int sb = ks * SPS + (within >> 1), half = within & 1;
+    const int r0 = (gr * RS + rs) * R;
     const int r1 = r0 + R < p.nrt ? r0 + R : p.nrt;
     const int rl = r1 - 1;
-    const int sb = 8 * ks + (wave >> 1), half = wave & 1;
-    const bool active = sb < p.nsb;                  // uniform per wavefront
+    const bool active = rs < RS && sb < p.nsb && r0 < p.nrt;      // uniform per wavefront
     constexpr int L = TileLoads<HAS_RES>::count;
     constexpr int PH = STB_GEMV_PHASE;               // half tiles a wavefront streams between two reductions
-    const int Wa = 2 * (p.nsb - 8 * ks < 8 ? p.nsb - 8 * ks : 8);    // wavefronts of this workgroup that have work
+    const int Wa = 2 * (p.nsb - ks * SPS < SPS ? p.nsb - ks * SPS : SPS);   // wavefronts of a row stream that have work
     const int q = 4 * sb + g;
     TRACE(0);
 
@@ -212,11 +218,20 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
 
     // D[row][b] of a tile: lane l holds b = l % 16, rows 4*(l / 16) + v.  Consecutive threads take consecutive rows.
     const int64_t n16 = (int64_t)p.nrt * 16;
-    auto wg_sum = [&](int o) {
-        const int j = o >> 8, b = (o >> 4) & 15, r16 = o & 15;
+    // v / B for 0 <= v < 2^27 and 2 <= B <= 16, as one multiply: with m = ceil(2^32 / B) the error v * (m*B - 2^32)
+    // stays below 2^32 (m does not fit 32 bits for B = 1, which needs no division).
+    const uint32_t b_magic = B > 1 ? (uint32_t)((0x100000000ull + (uint32_t)B - 1) / (uint32_t)B) : 0u;
+    auto div_b = [&](int v) { return B > 1 ? (int)__umulhi((uint32_t)v, b_magic) : v; };
+    // sum over the wavefronts of row stream rsq of the 16 x 16 block of phase slot j, element (b, r16)
+    auto wg_sum = [&](int rsq, int j, int b, int r16) {
         const int l = b + 16 * (r16 >> 2), v = r16 & 3;
+        const float* src = part + (int64_t)(rsq * WS * PH + j) * 256 + 64 * v + l;
+        float t[16];
+#pragma unroll
+        for (int w = 0; w < 16; w++) t[w] = w < Wa ? src[w * PH * 256] : 0.0f;      // independent reads, fixed order of adds
         float s = 0.0f;
-        for (int w = 0; w < Wa; w++) s += part[(int64_t)(w * PH + j) * 256 + 64 * v + l];
+#pragma unroll
+        for (int w = 0; w < 16; w++) s += t[w];
         return s;
     };
     auto store_y = [&](int row, int b, float s) {
@@ -264,7 +279,8 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
     // Two tiles are in flight per wavefront (four wavefronts share a SIMD): while tile rt is expanded, the
     // loads of rt + 1 are outstanding.  A fetch past the last tile of the workgroup re-reads that tile (a
     // cache hit), which keeps the number of loads between a fetch and its wait the same on every path.
-    for (int ph0 = r0; ph0 < r1; ph0 += PH) {
+    for (int ph = 0; ph < R; ph += PH) {
+        const int ph0 = r0 + ph;
         const int ph1 = ph0 + PH < r1 ? ph0 + PH : r1;
         if (active) {
             for (int rt = ph0; rt < ph1; rt += 2) {
@@ -304,15 +320,19 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
         TRACE(5);
         __syncthreads();
         TRACE(6);
-        const int total = (ph1 - ph0) * 256;
+        // outputs of this phase: (row stream, slot, b, row in tile), consecutive threads on consecutive rows
+        const int total = RS * PH * B * 16;
         for (int o = threadIdx.x; o < total; o += blockDim.x) {
-            const int b = (o >> 4) & 15, row = (ph0 + (o >> 8)) * 16 + (o & 15);
-            if (b >= B) continue;
-            const float s = wg_sum(o);
+            const int r16 = o & 15, sj = div_b(o >> 4), b = (o >> 4) - sj * B, j = sj % PH, rsq = sj / PH;
+            const int base = (gr * RS + rsq) * R;
+            const int tile = base + ph + j;
+            if (ph + j >= R || tile >= p.nrt) continue;
+            const float s = wg_sum(rsq, j, b, r16);
+            const int row = tile * 16 + r16;
             if (S == 1) store_y(row, b, s);
             else __hip_atomic_store(ws_part + ((int64_t)ks * 16 + b) * n16 + row, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        if (ph1 < r1) __syncthreads();               // the next phase overwrites the partial products
+        if (ph + PH < R) __syncthreads();            // the next phase overwrites the partial products
     }
     if (active) {
         wait_tile<0>(t0);                            // drain: no load may still target a register that is reused
@@ -331,13 +351,20 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
     if (threadIdx.x == 0) ticket = atomicInc(ws_count + gr, (uint32_t)(S - 1));    // wraps to 0 after S arrivals
     __syncthreads();
     if (ticket != (uint32_t)(S - 1)) return;
-    const int total = (r1 - r0) * 256;
+    const int g0 = gr * RS * R, g1 = g0 + RS * R < p.nrt ? g0 + RS * R : p.nrt;     // row tiles of this group
+    const int total = (g1 - g0) * 16 * B;
     for (int o = threadIdx.x; o < total; o += blockDim.x) {
-        const int b = (o >> 4) & 15, row = (r0 + (o >> 8)) * 16 + (o & 15);
-        if (b >= B) continue;
+        const int r16 = o & 15, tb = div_b(o >> 4), b = (o >> 4) - tb * B, tile = g0 + tb;
+        const int row = tile * 16 + r16;
+        float t[4];
         float s = 0.0f;
-        for (int c = 0; c < S; c++)
-            s += __hip_atomic_load(ws_part + ((int64_t)c * 16 + b) * n16 + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int c0 = 0; c0 < S; c0 += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+                t[u] = c0 + u < S ? __hip_atomic_load(ws_part + ((int64_t)(c0 + u) * 16 + b) * n16 + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0f;
+#pragma unroll
+            for (int u = 0; u < 4; u++) s += t[u];
+        }
         store_y(row, b, s);
     }
 }
@@ -374,19 +401,20 @@ extern "C" int stb_tiled_dequant(const stb_layout_t* L, float* out, void* stream
 
 static int64_t round_up256(int64_t v) { return (v + 255) / 256 * 256; }
 
+// Largest number of column splits the launcher below may choose for n_super superblocks.
+static int max_splits(int n_super) { return (n_super + 1) / 2 + 3; }
+
 extern "C" int64_t stb_tiled_gemv_workspace(int n_row_tiles, int n_super) {
-    const int S = (n_super + 7) / 8;
-    if (S <= 1) return 0;
-    return round_up256(4 * (int64_t)n_row_tiles) + (int64_t)S * 16 * 16 * n_row_tiles * 4;
+    return round_up256(4 * (int64_t)n_row_tiles) + (int64_t)max_splits(n_super) * 16 * 16 * n_row_tiles * 4;
 }
 
 template <int N8, bool HAS_RES>
-static hipError_t launch_gemv_stream(const TiledPlanes& p, const __half* x, int B, void* y, int y_fp32, int R,
+static hipError_t launch_gemv_stream(const TiledPlanes& p, const __half* x, int B, void* y, int y_fp32, int R, int SPS,
                                      dim3 grid, size_t lds, float* ws_part, uint32_t* ws_count, hipStream_t st) {
     static const hipError_t attr = hipFuncSetAttribute((const void*)gemv_stream_kernel<N8, HAS_RES>,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, 16 * STB_GEMV_PHASE * 1024);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((gemv_stream_kernel<N8, HAS_RES>), grid, dim3(1024), lds, st, p, x, B, y, y_fp32, R, ws_part, ws_count);
+    hipLaunchKernelGGL((gemv_stream_kernel<N8, HAS_RES>), grid, dim3(1024), lds, st, p, x, B, y, y_fp32, R, SPS, ws_part, ws_count);
     return hipGetLastError();
 }
 
@@ -394,32 +422,49 @@ extern "C" int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void*
                               int64_t workspace_bytes, void* stream, int* hip_err) {
     if (!stb_tiled_supported(L)) return STB_EUNSUPPORTED;
     const TiledPlanes p = make_tiled(L);
-    const int S = (p.nsb + 7) / 8;                                 // column splits of eight superblocks
+    static const int wg_target = env_int("STB_GEMV_WGS", 256);     // workgroups the launch aims for: one per compute unit
+    static const int sps_small = env_int("STB_GEMV_SPS_SMALL_B", 8), sps_large = env_int("STB_GEMV_SPS_LARGE_B", 8);
+    // Superblocks per column split: 8 (a whole 4096-column slice per workgroup).  Narrower splits with several
+    // row streams per workgroup are supported by the kernel but measured slower at every batch size so far.
+    const int sps0 = B <= 4 ? sps_small : sps_large;
+    // Among the split counts that fit, take the one with the fewest half tiles per compute unit (R tiles for each
+    // wavefront with work, times the rounds the grid needs on 256 units); ties go to the fewest splits.
+    int best_S = 0, best_R = 0, best_sps = 0;
+    int64_t best_cost = 0;
+    const int s_min = (p.nsb + sps0 - 1) / sps0;
+    for (int S = s_min; S <= s_min + 3 && S <= max_splits(p.nsb) && S <= p.nsb; S++) {
+        const int sps = (p.nsb + S - 1) / S;
+        const int rs = 16 / (2 * sps);
+        if (rs < 1 || (S - 1) * sps >= p.nsb) continue;            // a split must own at least one superblock
+        const int groups = wg_target / S > 0 ? wg_target / S : 1;
+        const int R = (p.nrt + rs * groups - 1) / (rs * groups);
+        const int G = (p.nrt + rs * R - 1) / (rs * R);
+        const int64_t cost = (int64_t)R * 2 * sps * rs * ((G * S + wg_target - 1) / wg_target);
+        if (best_S == 0 || cost < best_cost) { best_cost = cost; best_S = S; best_R = R; best_sps = sps; }
+    }
+    if (best_S == 0) return STB_EINVAL;
+    const int S = best_S, R = best_R, SPS = best_sps, RS = 16 / (2 * SPS);
+    const int G = (p.nrt + RS * R - 1) / (RS * R);
     const int64_t need = stb_tiled_gemv_workspace(p.nrt, p.nsb);
-    if (need > 0) {
+    if (S > 1) {
         if (!workspace) return STB_ENULL;
         if (workspace_bytes < need) return STB_EINVAL;
         if ((uintptr_t)workspace % 256) return STB_EALIGN;
     }
-    static const int wg_target = env_int("STB_GEMV_WGS", 256);     // workgroups the launch aims for
-    int groups = wg_target / S;                                    // row groups
-    if (groups < 1) groups = 1;
-    int R = (p.nrt + groups - 1) / groups;                         // row tiles per workgroup
-    const int G = (p.nrt + R - 1) / R;
     const size_t lds = (size_t)16 * STB_GEMV_PHASE * 256 * sizeof(float);   // + 32 KB of tables: 128 KB of LDS
     const dim3 grid(G, S);
     const hipStream_t st = (hipStream_t)stream;
     const __half* xh = (const __half*)x;
     uint32_t* cnt = (uint32_t*)workspace;
-    float* part = need > 0 ? (float*)((char*)workspace + round_up256(4 * (int64_t)p.nrt)) : nullptr;
+    float* part = S > 1 ? (float*)((char*)workspace + round_up256(4 * (int64_t)p.nrt)) : nullptr;
     const bool res = p.res_words > 0;
     hipError_t e;
     if (kept_per_8(L) == 4)
-        e = res ? launch_gemv_stream<4, true>(p, xh, B, y, y_fp32, R, grid, lds, part, cnt, st)
-                : launch_gemv_stream<4, false>(p, xh, B, y, y_fp32, R, grid, lds, part, cnt, st);
+        e = res ? launch_gemv_stream<4, true>(p, xh, B, y, y_fp32, R, SPS, grid, lds, part, cnt, st)
+                : launch_gemv_stream<4, false>(p, xh, B, y, y_fp32, R, SPS, grid, lds, part, cnt, st);
     else
-        e = res ? launch_gemv_stream<6, true>(p, xh, B, y, y_fp32, R, grid, lds, part, cnt, st)
-                : launch_gemv_stream<6, false>(p, xh, B, y, y_fp32, R, grid, lds, part, cnt, st);
+        e = res ? launch_gemv_stream<6, true>(p, xh, B, y, y_fp32, R, SPS, grid, lds, part, cnt, st)
+                : launch_gemv_stream<6, false>(p, xh, B, y, y_fp32, R, SPS, grid, lds, part, cnt, st);
     *hip_err = (int)e;
     return e == hipSuccess ? STB_OK : STB_EHIP;
 }
