@@ -85,9 +85,12 @@ typedef struct stb_cfg {
  * kind = STB_KIND_TILED: the device order read by the fast kernels, a byte permutation of STB1 plus zero
  * padding.  Rows are grouped in tiles of 16 and 128-column blocks in groups of 4 ("superblock", 512
  * columns); a tile record holds one 64-lane wavefront's operands, lane = 16*(block % 4) + (row % 16):
- *   mask      [row_tile][super][lane][16 bytes]         the 16 mask bytes of (row, block)
+ *   mask      [row_tile][super][half][lane][8 bytes]    the mask bytes of (row, block), columns 64*half .. 64*half+63
  *   sign      [row_tile][super][lane][sign_stride]      sign bits of the block's 128*N/M kept weights
  *   region    [row_tile][super][lane][region_stride]    their 2-bit ids
+ *             sign / region are cut into two halves like mask ([row_tile][super][half][lane][stride/2], the
+ *             kept weights of columns 64*half ..) when their stride is a multiple of 8 bytes, so that each
+ *             half is a whole number of 32-bit words (2:4 and 4:8: both; 6:8: region only)
  *   scales    [row_tile][super][lane][4] fp16, res_scale [row_tile][super][lane] fp16
  *   res_sign  [row_tile][word][row % 16] uint32: the STB1 row strings cut into 32-bit words and transposed
  *             inside each row tile (res_stride / 4 words per row)

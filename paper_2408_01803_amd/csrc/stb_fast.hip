@@ -10,6 +10,7 @@ using namespace stbt;
 #define STB_VARIANT 0
 #endif
 #define STB_GEMV_PHASE 6
+#define STB_GEMV_RESW 6144        // uint32 words of LDS for the res_sign words of a workgroup's row tiles
 #ifndef STB_LUT_AHEAD
 #define STB_LUT_AHEAD 2
 #endif
@@ -117,13 +118,15 @@ __device__ inline ResInv load_res_inv(const TiledPlanes& p, int q, int half, int
     return r;
 }
 
-template <int N8, bool HAS_RES>
+template <int N8, bool HAS_RES, bool STAGED>
 __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const __half* __restrict__ x, int B,
                                                             void* __restrict__ y, int y_fp32, int R, int SPS,
                                                             float* __restrict__ ws_part, uint32_t* __restrict__ ws_count) {
     __shared__ ScatterLds lut;
     __shared__ uint32_t ticket;
-    extern __shared__ float part[];                  // [16][PH][256]
+    __shared__ __attribute__((aligned(16))) uint32_t recs[STAGED && HAS_RES ? 64 * 12 : 4];   // first salient-column record of each (block, half) of the split
+    __shared__ __attribute__((aligned(16))) uint32_t resw[STAGED && HAS_RES ? STB_GEMV_RESW : 4];   // res_sign words of the workgroup's row tiles
+    extern __shared__ __attribute__((aligned(16))) float part[];                  // [16][PH][256]; before the first product: the staged x
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int i = lane & 15, g = lane >> 4;
     const int gr = blockIdx.x, ks = blockIdx.y, S = gridDim.y;
@@ -138,7 +141,8 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
     const int r1 = r0 + R < p.nrt ? r0 + R : p.nrt;
     const int rl = r1 - 1;
     const bool active = rs < RS && sb < p.nsb && r0 < p.nrt;      // uniform per wavefront
-    constexpr int L = TileLoads<HAS_RES>::count;
+    constexpr bool RES_GLOBAL = HAS_RES && !STAGED;  // the streaming loop loads res_sign words itself
+    constexpr int L = TileLoads<RES_GLOBAL>::count;
     constexpr int PH = STB_GEMV_PHASE;               // half tiles a wavefront streams between two reductions
     const int Wa = 2 * (p.nsb - ks * SPS < SPS ? p.nsb - ks * SPS : SPS);   // wavefronts of a row stream that have work
     const int q = 4 * sb + g;
@@ -148,72 +152,208 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
     auto tile_of = [&](int rt) { return (int64_t)rt * p.nsb + sb; };
     auto clamp = [&](int rt) { return rt < rl ? rt : rl; };
 
-    // ---- every load that does not depend on another one goes out first: the packed planes of the first
-    //      tile, x for the wavefront's columns, the first record of the salient-column table, the expansion
-    //      tables ----
-    TileRegs<N8> t0, t1;
-    uint4 xr[8];
-    uint4 rec_a = make_uint4(0u, 0u, 0u, 0u), rec_p = make_uint4(0u, 0u, 0u, 0u);
-    uint2 rec_b = make_uint2(0u, 0u);
-    const bool live = active && i < B && q < p.nb;
-    const __half* xblk = x + (int64_t)(i < B ? i : B - 1) * p.k + (int64_t)(active && q < p.nb ? q : 0) * 128;
-    if (active) {
-        fetch_main<N8>(t0, p, tile_of(r0), lo);
-        if (HAS_RES) {
-            const uint32_t* rec = p.sal_tab + (((int64_t)q * 2 + half) * p.sal_chunks) * 12;
-            rec_a = *reinterpret_cast<const uint4*>(rec);
-            rec_b = *reinterpret_cast<const uint2*>(rec + 4);
-            rec_p = *reinterpret_cast<const uint4*>(rec + 8);
-        }
-#pragma unroll
-        for (int t = 0; t < 8; t++) xr[t] = reinterpret_cast<const uint4*>(xblk + 64 * half)[t];
-    }
-    build_luts<N8>(&lut);                            // arithmetic only: overlaps with the loads in flight
-
-    // ---- the loads that depend on the table record: res_sign words of the first tile, x at the salient
-    //      columns ----
+    // ---- prologue.  A compute unit takes a vector memory instruction only every dozen cycles or so, whatever
+    //      its width (measured), so with three tiles per wavefront the number of load instructions decides the
+    //      start-up time.  STAGED: the workgroup brings its slice of x and the salient-column records into LDS
+    //      with a few full-width loads (B * SPS / 16 per wavefront) and every wavefront takes its B operands, its
+    //      record and the x of its salient columns from there; the alternative is 19 narrow loads per
+    //      wavefront.  The staged x lies where the partial products go later; it is only used when it fits. ----
+    TileRegs<N8> t0, t1, t2;
+    uint4_t xr[8];
     ResInv inv;
     int nch = 0, rsh = 0;
-    if (active) {
+    const bool live = active && i < B && q < p.nb;
+    const __half* xblk = x + (int64_t)(i < B ? i : B - 1) * p.k + (int64_t)(active && q < p.nb ? q : 0) * 128;
+    if constexpr (STAGED) {
+        const int per_row = SPS * 64;                               // 16-byte pieces of one batch row of the slice
+        const int total = B * per_row;                              // at most 6 * 1024 (checked by the launcher)
+        const int xstride = SPS * 1024 + 16;                        // bytes per staged row; the skew spreads rows over banks
+        const uint32_t sps_magic = (65536u + (uint32_t)SPS - 1u) / (uint32_t)SPS;    // v / SPS = (v * magic) >> 16 for v < 2^10
+        char* xs = reinterpret_cast<char*>(part);
+        uint4_t sx0, sx1, sx2, sx3, sx4, sx5;
+        uint4_t sr = {0u, 0u, 0u, 0u};
+        const int n_u = (total + 1023) >> 10;                       // staging loads per thread: uniform, at most 6
+        // piece u of this thread: destination in LDS (-1: none) and whether it lies inside x (columns past k and
+        // pieces past the slice load x[0] instead and store zeros, so that a wavefront issues n_u loads on every path)
+        auto piece = [&](int u, int& dst, bool& inside) -> const __half* {
+            const int pc = (int)threadIdx.x + 1024 * u;
+            const int b = (int)(((uint32_t)(pc >> 6) * sps_magic) >> 16), c16 = pc - b * per_row;
+            const int col = ks * SPS * 512 + c16 * 8;
+            dst = pc < total ? b * xstride + c16 * 16 : -1;
+            inside = pc < total && col < p.k;
+            return inside ? x + (int64_t)b * p.k + col : x;
+        };
+        int d0, d1, d2, d3, d4, d5;
+        bool in0, in1, in2, in3, in4, in5;
+#define STB_STAGE_LOAD(u, reg, d, in) if (u < n_u) { const __half* src = piece(u, d, in); asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(reg) : "v"(src)); }
+        STB_STAGE_LOAD(0, sx0, d0, in0) STB_STAGE_LOAD(1, sx1, d1, in1) STB_STAGE_LOAD(2, sx2, d2, in2)
+        STB_STAGE_LOAD(3, sx3, d3, in3) STB_STAGE_LOAD(4, sx4, d4, in4) STB_STAGE_LOAD(5, sx5, d5, in5)
+#undef STB_STAGE_LOAD
+        // records: three 16-byte pieces each, taken by the last three wavefronts
+        const int rt3 = (int)threadIdx.x - (1024 - 192);
+        const int rI = rt3 >= 0 ? rt3 / 3 : -1, rpc = rt3 - rI * 3;          // record (block of the split, half), piece
+        if (HAS_RES && rI >= 0 && ks * SPS + (rI >> 3) < p.nsb && (rI >> 3) < SPS) {
+            const uint32_t* src = p.sal_tab + (((int64_t)(4 * ks * SPS) * 2 + rI) * p.sal_chunks) * 12 + 4 * rpc;
+            asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(sr) : "v"(src));
+        }
+        // res_sign words of the workgroup's row tiles [g0, g1): one contiguous piece of the plane, at most two
+        // 16-byte loads per thread (the launcher checks that it fits)
+        const int g0 = gr * RS * R, g1 = g0 + RS * R < p.nrt ? g0 + RS * R : p.nrt;
+        const int rpieces = HAS_RES ? (g1 - g0) * p.res_words * 4 : 0;
+        const int n_rw = (rpieces + 1023) >> 10;
+        uint4_t rw0 = {0u, 0u, 0u, 0u}, rw1 = {0u, 0u, 0u, 0u};
+        {
+            const uint4_t* src = reinterpret_cast<const uint4_t*>(p.res_sign + (int64_t)g0 * p.res_words * 16);
+            const int t0i = (int)threadIdx.x, t1i = (int)threadIdx.x + 1024;
+            if (n_rw > 0) { const uint4_t* a = src + (t0i < rpieces ? t0i : 0); asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(rw0) : "v"(a)); }
+            if (n_rw > 1) { const uint4_t* a = src + (t1i < rpieces ? t1i : 0); asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(rw1) : "v"(a)); }
+        }
+        if (active) fetch_main<N8>(t0, p, tile_of(clamp(r0)), lo);
+        TRACE(29);
+        build_luts<N8>(&lut);                            // arithmetic only: overlaps with the loads in flight
+        TRACE(30);
+        // the staging loads are older than the five of the first tile (which a wavefront without work has not issued)
+        if (!active) asm volatile("s_waitcnt vmcnt(0)");
+        asm volatile("s_waitcnt vmcnt(5)" : "+v"(sx0), "+v"(sx1), "+v"(sx2), "+v"(sx3), "+v"(sx4), "+v"(sx5), "+v"(sr), "+v"(rw0), "+v"(rw1));
         if (HAS_RES) {
-            inv.sel.sel0 = rec_a.x; inv.sel.sel1 = rec_a.y; inv.sel.bit0 = rec_a.z; inv.sel.bit1 = rec_a.w;
-            inv.ord = rec_b.x;
-            nch = __builtin_amdgcn_readfirstlane((int)rec_b.y);
-            rsh = (int)(inv.ord & 31u);
-            const int wa = (int)(inv.ord >> 5) < p.res_words ? (int)(inv.ord >> 5) : p.res_words - 1;
-            const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
-            lo.ores0 = (uint32_t)(wa * 16 + i) * 4u;
-            lo.ores1 = (uint32_t)(wb * 16 + i) * 4u;
-            const uint32_t pw[4] = {rec_p.x, rec_p.y, rec_p.z, rec_p.w};
-            uint32_t h[8];
+            if (n_rw > 0 && (int)threadIdx.x < rpieces) *reinterpret_cast<uint4_t*>(&resw[4 * threadIdx.x]) = rw0;
+            if (n_rw > 1 && (int)threadIdx.x + 1024 < rpieces) *reinterpret_cast<uint4_t*>(&resw[4 * (threadIdx.x + 1024)]) = rw1;
+        }
+#define STB_STAGE_STORE(u, reg, d, in) if (u < n_u && d >= 0) *reinterpret_cast<uint4_t*>(xs + d) = in ? reg : uint4_t{0u, 0u, 0u, 0u};
+        STB_STAGE_STORE(0, sx0, d0, in0) STB_STAGE_STORE(1, sx1, d1, in1) STB_STAGE_STORE(2, sx2, d2, in2)
+        STB_STAGE_STORE(3, sx3, d3, in3) STB_STAGE_STORE(4, sx4, d4, in4) STB_STAGE_STORE(5, sx5, d5, in5)
+#undef STB_STAGE_STORE
+        if (HAS_RES && rI >= 0) *reinterpret_cast<uint4_t*>(&recs[rI * 12 + 4 * rpc]) = sr;
+        __syncthreads();
+        TRACE(31);
+        if (active) {
+            const int ql = 4 * (sb - ks * SPS) + g;                   // block inside the split
+            const char* xrow = xs + (i < B ? i : 0) * xstride + ql * 256;
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                const uint32_t pos = (pw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-                h[e] = reinterpret_cast<const unsigned short*>(xblk)[pos & 127u];
-                if (!(live && pos < 128u)) h[e] = 0u;
+            for (int t = 0; t < 8; t++) {
+                xr[t] = *reinterpret_cast<const uint4_t*>(xrow + 128 * half + 16 * t);
+                if (i >= B) xr[t] = uint4_t{0u, 0u, 0u, 0u};
             }
+            if (HAS_RES) {
+                const uint32_t* rec = &recs[(ql * 2 + half) * 12];
+                const uint4_t ra = *reinterpret_cast<const uint4_t*>(rec);
+                const uint2_t rb = *reinterpret_cast<const uint2_t*>(rec + 4);
+                const uint4_t rp = *reinterpret_cast<const uint4_t*>(rec + 8);
+                inv.sel.sel0 = ra.x; inv.sel.sel1 = ra.y; inv.sel.bit0 = ra.z; inv.sel.bit1 = ra.w;
+                inv.ord = rb.x;
+                nch = __builtin_amdgcn_readfirstlane((int)rb.y);
+                rsh = (int)(inv.ord & 31u);
+                const int wa = (int)(inv.ord >> 5) < p.res_words ? (int)(inv.ord >> 5) : p.res_words - 1;
+                const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+                lo.ores0 = (uint32_t)(wa * 16 + i) * 4u;
+                lo.ores1 = (uint32_t)(wb * 16 + i) * 4u;
+                const uint32_t pw[4] = {rp.x, rp.y, rp.z, rp.w};
+                uint32_t h[8];
 #pragma unroll
-            for (int v = 0; v < 4; v++) inv.xs[v] = h[2 * v] | (h[2 * v + 1] << 16);
-        }
-        fetch_res<N8, HAS_RES>(t0, p, r0, lo);
-        if (!live) {
+                for (int e = 0; e < 8; e++) {
+                    const uint32_t pos = (pw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                    h[e] = *reinterpret_cast<const unsigned short*>(xrow + 2 * (pos & 127u));
+                    if (!(i < B && pos < 128u)) h[e] = 0u;
+                }
 #pragma unroll
-            for (int t = 0; t < 8; t++) xr[t] = make_uint4(0u, 0u, 0u, 0u);
+                for (int v = 0; v < 4; v++) inv.xs[v] = h[2 * v] | (h[2 * v + 1] << 16);
+            }
+            fetch_res<N8, false>(t0, p, clamp(r0), lo);
+            fetch_tile<N8, false>(t1, p, tile_of(clamp(r0 + 1)), clamp(r0 + 1), lo);
+            fetch_tile<N8, false>(t2, p, tile_of(clamp(r0 + 2)), clamp(r0 + 2), lo);
         }
-    }
-    TRACE(1);
-    __syncthreads();
-    TRACE(2);
-
-    if (active) {
-        // Everything issued so far has arrived before the streaming loop starts: the compiler then places no
-        // wait of its own inside the loop (such a wait would also drain the prefetched tiles), and the fixed
-        // wait counts of the loop hold from its first iteration.
-        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
-        __builtin_amdgcn_sched_barrier(0);
+        TRACE(1);
+        __syncthreads();                                 // every wavefront has taken its x: the area may be overwritten
+        TRACE(2);
         TRACE(3);
+    } else {
+        // ---- every load that does not depend on another one goes out first: the packed planes of the first
+        //      tile, x for the wavefront's columns, the first record of the salient-column table, the expansion
+        //      tables ----
+        uint4_t rec_a = {0u, 0u, 0u, 0u}, rec_p = {0u, 0u, 0u, 0u};
+        uint2_t rec_b = {0u, 0u};
+        uint32_t h[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};      // x at the salient columns of the first record, one fp16 each
+        if (active) {
+            // Every load of the kernel's streaming part is an asm statement: their order, and with it the count
+            // in each wait, is fixed, and the compiler (which does not see them) places no wait of its own that
+            // would drain the prefetched tiles.
+            if (HAS_RES) {                               // first: other loads depend on this record
+                const uint32_t* rec = p.sal_tab + (((int64_t)q * 2 + half) * p.sal_chunks) * 12;
+                asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(rec_a) : "v"(rec));
+                asm volatile("global_load_dwordx2 %0, %1, off offset:16" : "=v"(rec_b) : "v"(rec));
+                asm volatile("global_load_dwordx4 %0, %1, off offset:32" : "=v"(rec_p) : "v"(rec));
+            }
+            fetch_main<N8>(t0, p, tile_of(clamp(r0)), lo);
+            // x: only the lanes that supply a batch row load (lane 0 always does, so the wavefront issues these
+            // loads on every path and the wait counts below hold); the others keep zeros.  A load by all 64 lanes
+            // would cost a full kilobyte of cache bandwidth per instruction, for B = 1 sixteen times the data.
+            const __half* xh = xblk + 64 * half;
+#pragma unroll
+            for (int t = 0; t < 8; t++) xr[t] = uint4_t{0u, 0u, 0u, 0u};
+            if (live) {
+#pragma unroll
+                for (int t = 0; t < 8; t++)
+                    asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "+v"(xr[t]) : "v"(xh), "n"(16 * t));
+            }
+        }
+        TRACE(29);
+        build_luts<N8>(&lut);                            // arithmetic only: overlaps with the loads in flight
+        TRACE(30);
 
-        (void)0;
+        // ---- the loads that depend on the table record (res_sign words of the first tile, x at the salient
+        //      columns), then the second and third tile ----
+        uint32_t pw[4] = {0u, 0u, 0u, 0u};
+        if (active) {
+            if (HAS_RES) {
+                // the record has arrived once at most the 5 plane loads and 8 x loads behind it are outstanding
+                asm volatile("s_waitcnt vmcnt(13)" : "+v"(rec_a), "+v"(rec_b), "+v"(rec_p));
+                TRACE(31);
+                inv.sel.sel0 = rec_a.x; inv.sel.sel1 = rec_a.y; inv.sel.bit0 = rec_a.z; inv.sel.bit1 = rec_a.w;
+                inv.ord = rec_b.x;
+                nch = __builtin_amdgcn_readfirstlane((int)rec_b.y);
+                rsh = (int)(inv.ord & 31u);
+                const int wa = (int)(inv.ord >> 5) < p.res_words ? (int)(inv.ord >> 5) : p.res_words - 1;
+                const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+                lo.ores0 = (uint32_t)(wa * 16 + i) * 4u;
+                lo.ores1 = (uint32_t)(wb * 16 + i) * 4u;
+                pw[0] = rec_p.x; pw[1] = rec_p.y; pw[2] = rec_p.z; pw[3] = rec_p.w;
+                if (live) {
+#pragma unroll
+                    for (int e = 0; e < 8; e++) {
+                        const uint32_t pos = (pw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                        const __half* src = xblk + (pos & 127u);
+                        asm volatile("global_load_ushort %0, %1, off" : "+v"(h[e]) : "v"(src));
+                    }
+                }
+            }
+            fetch_res<N8, HAS_RES>(t0, p, clamp(r0), lo);
+            fetch_tile<N8, HAS_RES>(t1, p, tile_of(clamp(r0 + 1)), clamp(r0 + 1), lo);
+            fetch_tile<N8, HAS_RES>(t2, p, tile_of(clamp(r0 + 2)), clamp(r0 + 2), lo);
+        }
+        TRACE(1);
+        __syncthreads();
+        TRACE(2);
+
+        if (active) {
+            // The first tile, x and the gathered x have arrived once only the 2 * L loads of the second and third
+            // tile are outstanding: the wait counts of the loop hold from its first iteration.
+            asm volatile("s_waitcnt vmcnt(%16)"
+                         : "+v"(xr[0]), "+v"(xr[1]), "+v"(xr[2]), "+v"(xr[3]), "+v"(xr[4]), "+v"(xr[5]), "+v"(xr[6]), "+v"(xr[7]),
+                           "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]), "+v"(h[4]), "+v"(h[5]), "+v"(h[6]), "+v"(h[7])
+                         : "n"(2 * L));
+            __builtin_amdgcn_sched_barrier(0);
+            if (HAS_RES) {
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    const uint32_t pos = (pw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                    h[e] = live && pos < 128u ? (h[e] & 0xFFFFu) : 0u;
+                }
+#pragma unroll
+                for (int v = 0; v < 4; v++) inv.xs[v] = h[2 * v] | (h[2 * v + 1] << 16);
+            }
+            TRACE(3);
+        }
+
     }
 
     // D[row][b] of a tile: lane l holds b = l % 16, rows 4*(l / 16) + v.  Consecutive threads take consecutive rows.
@@ -241,9 +381,15 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
         }
     };
 
-    auto product = [&](const TileRegs<N8>& tr, int slot) {
+    const int wg_t0 = gr * RS * R;                   // first row tile of the workgroup (origin of resw)
+    auto product = [&](const TileRegs<N8>& tr, int rt, int slot) {
         HalfData<N8> d;
         unpack_tile<N8>(tr, half, d);
+        if constexpr (STAGED && HAS_RES) {           // lo.ores0 / ores1 are byte offsets inside the row tile's words
+            const char* rbase = reinterpret_cast<const char*>(resw) + (int64_t)(rt - wg_t0) * p.res_words * 64;
+            d.rlo = *reinterpret_cast<const uint32_t*>(rbase + lo.ores0);
+            d.rhi = *reinterpret_cast<const uint32_t*>(rbase + lo.ores1);
+        }
         const uint32_t TL = perm(d.sc.y, d.sc.x, 0x06040200u), TH = perm(d.sc.y, d.sc.x, 0x07050301u);
         float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
         constexpr int D = STB_LUT_AHEAD;                             // table reads run D groups ahead
@@ -269,27 +415,33 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
         float* dst = part + ((int64_t)(wave * PH + slot) * 256 + lane);
 #pragma unroll
         for (int v = 0; v < 4; v++) dst[64 * v] = acc[v];
-        TRACE(8 + (slot < 20 ? slot : 20));
+        TRACE(14 + (slot < 5 ? slot : 5));
     };
 
-    // The R tiles are taken in phases of PH (an even number, so that the two tile buffers keep their roles):
+    // The R tiles are taken in phases of PH (a multiple of 3, so that the three tile buffers keep their roles):
     // the wavefronts stream PH half tiles each, the workgroup adds the partial products of the phase in a
     // fixed order and stores them, and the next phase reuses the LDS.  Prefetches run across phase boundaries.
     // (Summing through LDS float atomics instead, without phases, was measured three times slower.)
-    // Two tiles are in flight per wavefront (four wavefronts share a SIMD): while tile rt is expanded, the
-    // loads of rt + 1 are outstanding.  A fetch past the last tile of the workgroup re-reads that tile (a
+    // Three tiles are in flight per wavefront (four wavefronts share a SIMD): while tile rt is expanded, the
+    // loads of rt + 1 and rt + 2 are outstanding.  A fetch past the last tile of the workgroup re-reads that tile (a
     // cache hit), which keeps the number of loads between a fetch and its wait the same on every path.
     for (int ph = 0; ph < R; ph += PH) {
         const int ph0 = r0 + ph;
         const int ph1 = ph0 + PH < r1 ? ph0 + PH : r1;
         if (active) {
-            for (int rt = ph0; rt < ph1; rt += 2) {
-                fetch_tile<N8, HAS_RES>(t1, p, tile_of(clamp(rt + 1)), clamp(rt + 1), lo);
-                wait_tile<L>(t0);
-                product(t0, rt - ph0);
-                fetch_tile<N8, HAS_RES>(t0, p, tile_of(clamp(rt + 2)), clamp(rt + 2), lo);
-                wait_tile<L>(t1);
-                if (rt + 1 < ph1) product(t1, rt + 1 - ph0);
+            for (int rt = ph0; rt < ph1; rt += 3) {
+                wait_tile<2 * L>(t0);
+                TRACE(8 + (rt - ph0 < 5 ? rt - ph0 : 5));
+                product(t0, rt, rt - ph0);
+                fetch_tile<N8, RES_GLOBAL>(t0, p, tile_of(clamp(rt + 3)), clamp(rt + 3), lo);
+                wait_tile<2 * L>(t1);
+                TRACE(8 + (rt + 1 - ph0 < 5 ? rt + 1 - ph0 : 5));
+                if (rt + 1 < ph1) product(t1, rt + 1, rt + 1 - ph0);
+                fetch_tile<N8, RES_GLOBAL>(t1, p, tile_of(clamp(rt + 4)), clamp(rt + 4), lo);
+                wait_tile<2 * L>(t2);
+                TRACE(8 + (rt + 2 - ph0 < 5 ? rt + 2 - ph0 : 5));
+                if (rt + 2 < ph1) product(t2, rt + 2, rt + 2 - ph0);
+                fetch_tile<N8, RES_GLOBAL>(t2, p, tile_of(clamp(rt + 5)), clamp(rt + 5), lo);
             }
             // Half blocks with more than 8 salient columns: the remaining records, outside the streaming loop
             // so that its load/wait pattern stays fixed.  Rare; every operand is re-read with ordinary loads
@@ -337,6 +489,7 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
     if (active) {
         wait_tile<0>(t0);                            // drain: no load may still target a register that is reused
         wait_tile<0>(t1);
+        wait_tile<0>(t2);
     }
     TRACE(7);
     if (S == 1) return;
@@ -408,14 +561,28 @@ extern "C" int64_t stb_tiled_gemv_workspace(int n_row_tiles, int n_super) {
     return round_up256(4 * (int64_t)n_row_tiles) + (int64_t)max_splits(n_super) * 16 * 16 * n_row_tiles * 4;
 }
 
+template <int N8, bool HAS_RES, bool STAGED>
+static hipError_t launch_gemv_stream3(const TiledPlanes& p, const __half* x, int B, void* y, int y_fp32, int R, int SPS,
+                                      dim3 grid, size_t lds, float* ws_part, uint32_t* ws_count, hipStream_t st) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv_stream_kernel<N8, HAS_RES, STAGED>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 16 * STB_GEMV_PHASE * 1024);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((gemv_stream_kernel<N8, HAS_RES, STAGED>), grid, dim3(1024), lds, st, p, x, B, y, y_fp32, R, SPS, ws_part, ws_count);
+    return hipGetLastError();
+}
+
 template <int N8, bool HAS_RES>
 static hipError_t launch_gemv_stream(const TiledPlanes& p, const __half* x, int B, void* y, int y_fp32, int R, int SPS,
                                      dim3 grid, size_t lds, float* ws_part, uint32_t* ws_count, hipStream_t st) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv_stream_kernel<N8, HAS_RES>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 16 * STB_GEMV_PHASE * 1024);
-    if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((gemv_stream_kernel<N8, HAS_RES>), grid, dim3(1024), lds, st, p, x, B, y, y_fp32, R, SPS, ws_part, ws_count);
-    return hipGetLastError();
+    // x is staged through LDS when the B rows of the split (SPS * 1024 + 16 bytes each) fit into the area of the
+    // partial products
+    static const int allow = env_int("STB_GEMV_STAGED", 1);
+    // ... and the res_sign words of the workgroup's RS * R row tiles into their own area
+    const int RS = 16 / (2 * SPS);
+    const bool staged = allow && (int64_t)B * (SPS * 1024 + 16) <= (int64_t)lds &&
+                        (!HAS_RES || (int64_t)RS * R * p.res_words * 16 <= STB_GEMV_RESW);
+    return staged ? launch_gemv_stream3<N8, HAS_RES, true>(p, x, B, y, y_fp32, R, SPS, grid, lds, ws_part, ws_count, st)
+                  : launch_gemv_stream3<N8, HAS_RES, false>(p, x, B, y, y_fp32, R, SPS, grid, lds, ws_part, ws_count, st);
 }
 
 extern "C" int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,

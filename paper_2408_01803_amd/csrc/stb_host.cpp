@@ -245,10 +245,21 @@ void permute_records(const stb_layout_t* rm, const stb_layout_t* tl, bool to_til
     };
     for (int r = 0; r < n; r++)
         for (int q = 0; q < nb; q++) {
-            const int64_t rec = ((int64_t)(r / 16) * nsb + q / 4) * 64 + 16 * (q % 4) + (r % 16);
-            mv(rmask + (int64_t)r * rm->mask_stride + 16 * q, tmask + rec * 16, 16);
-            mv(rsign + (int64_t)r * rm->sign_stride + SB * q, tsign + rec * SB, SB);
-            mv(rreg + (int64_t)r * rm->region_stride + RB * q, treg + rec * RB, RB);
+            const int64_t tile = (int64_t)(r / 16) * nsb + q / 4, lane = 16 * (q % 4) + (r % 16);
+            const int64_t rec = tile * 64 + lane;
+            // a plane whose block record splits into two halves of whole 4-byte words is stored half by half
+            // ([tile][half][lane]): a wavefront that works on one half of the columns then reads contiguous bytes
+            auto mv_rec = [&](uint8_t* a_rm, uint8_t* t_plane, int64_t bytes) {
+                if (bytes % 8 == 0) {
+                    for (int h = 0; h < 2; h++)
+                        mv(a_rm + h * (bytes / 2), t_plane + tile * 64 * bytes + h * 32 * bytes + lane * (bytes / 2), bytes / 2);
+                } else {
+                    mv(a_rm, t_plane + rec * bytes, bytes);
+                }
+            };
+            mv_rec(rmask + (int64_t)r * rm->mask_stride + 16 * q, tmask, 16);
+            mv_rec(rsign + (int64_t)r * rm->sign_stride + SB * q, tsign, SB);
+            mv_rec(rreg + (int64_t)r * rm->region_stride + RB * q, treg, RB);
             mv((uint8_t*)(rm->scales + ((int64_t)r * nb + q) * 4), (uint8_t*)(tl->scales + rec * 4), 8);
             mv((uint8_t*)(rm->res_scale + (int64_t)r * nb + q), (uint8_t*)(tl->res_scale + rec), 2);
         }

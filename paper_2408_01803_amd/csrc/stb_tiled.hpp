@@ -178,9 +178,10 @@ struct LaneOffsets {
 template <int N8>
 __device__ inline LaneOffsets lane_offsets(int lane, int half) {
     LaneOffsets lo;
-    lo.omask = (uint32_t)lane * 16u + 8u * half;
-    lo.osign = N8 == 4 ? (uint32_t)lane * 8u + 4u * half : (uint32_t)lane * 12u + 4u * half;
-    lo.oregion = N8 == 4 ? (uint32_t)lane * 16u + 8u * half : (uint32_t)lane * 24u + 12u * half;
+    // mask, region (and sign for N8 = 4) are stored [tile][half][lane]: the 64 lanes of a half read contiguous bytes
+    lo.omask = 512u * half + (uint32_t)lane * 8u;
+    lo.osign = N8 == 4 ? 256u * half + (uint32_t)lane * 4u : (uint32_t)lane * 12u + 4u * half;
+    lo.oregion = N8 == 4 ? 512u * half + (uint32_t)lane * 8u : 768u * half + (uint32_t)lane * 12u;
     lo.o8 = (uint32_t)lane * 8u;
     lo.o2 = (uint32_t)lane * 2u;
     lo.ores0 = 0u;
@@ -223,6 +224,7 @@ __device__ inline void load_half(const TiledPlanes& p, int64_t tile, const LaneO
 // ------------------------------------------------------------------------------------------------
 typedef uint32_t uint3_t __attribute__((ext_vector_type(3)));
 typedef uint32_t uint2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
 
 template <int N8>
 struct TileRegs;

@@ -160,6 +160,20 @@ def test_tile_untile_round_trip_is_a_byte_permutation(n, k, N, M, mode, kind, se
     S.stb_untile(tl, back.host_layout)
     for name, _, _ in S.PLANE_FIELDS:
         assert (back.plane(name) == pm.plane(name)).all(), name
+    # mask / sign / region: lane records [row_tile][super][lane = 16*(block % 4) + row % 16], cut into two halves
+    # ([row_tile][super][half][lane]) when the record is a multiple of 8 bytes
+    nrt, nsb, nb = tl.n_row_tiles, tl.n_super, k // 128
+    for name, off, size, rec in (("mask", "off_mask", "mask_bytes", 16), ("sign", "off_sign", "sign_bytes", 16 * N // M),
+                                 ("region", "off_region", "region_bytes", 32 * N // M)):
+        t = timg[getattr(tl, off):getattr(tl, off) + getattr(tl, size)]
+        if rec % 8 == 0:
+            t = t.reshape(nrt, nsb, 2, 4, 16, rec // 2).transpose(0, 4, 1, 3, 2, 5)      # [rt][i][sb][g][half][bytes]
+        else:
+            t = t.reshape(nrt, nsb, 4, 16, rec).transpose(0, 3, 1, 2, 4)                 # [rt][i][sb][g][bytes]
+        t = t.reshape(nrt * 16, nsb * 4, rec)
+        rm = np.zeros((nrt * 16, nsb * 4, rec), np.uint8)
+        rm[:n, :nb] = pm.plane(name).reshape(n, -1)[:, :nb * rec].reshape(n, nb, rec)
+        assert (t == rm).all(), name
     # res_sign: the row strings cut into 32-bit words, transposed inside each 16-row tile
     if tl.res_bytes:
         words = tl.res_stride // 4
