@@ -588,6 +588,11 @@ static hipError_t launch_gemv_stream(const TiledPlanes& p, const __half* x, int 
 extern "C" int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
                               int64_t workspace_bytes, void* stream, int* hip_err) {
     if (!stb_tiled_supported(L)) return STB_EUNSUPPORTED;
+    static const int allow24 = env_int("STB_GEMV_24", 1);
+    if (allow24 && B <= 16) {                                       // 2:4: the kernel on the sparse matrix-core instruction
+        const int rc = stb_tiled_gemv24(L, x, B, y, y_fp32, workspace, workspace_bytes, max_splits(L->n_super), stream, hip_err);
+        if (rc != STB_EUNSUPPORTED) return rc;
+    }
     const TiledPlanes p = make_tiled(L);
     static const int wg_target = env_int("STB_GEMV_WGS", 256);     // workgroups the launch aims for: one per compute unit
     static const int sps_small = env_int("STB_GEMV_SPS_SMALL_B", 8), sps_large = env_int("STB_GEMV_SPS_LARGE_B", 8);

@@ -1,0 +1,511 @@
+// Decode GEMV for 2:4 layouts (App. C: the memory-bound regime) on the sparse matrix-core instruction.
+//
+// Every group of 4 columns keeps exactly 2 weights (Sec. 3.1), which is the operand form of
+// v_smfmac_f32_16x16x64_f16: A holds the kept weights only (8 per lane for 16 columns), an index register says
+// where inside its group of 4 each of them sits, and the instruction multiplies against 64 rows of B.  The
+// kept weights come out of the packed planes in slot order -- the order the sign and id planes are stored in
+// -- so the per-column scatter that the dense kernels need disappears, and with it their table in LDS.
+//
+// Operand layout of the instruction (found by probing single-element operands on the device):
+//   A  lane 16*g + i, element e (0..7): row i, uncompressed K = 16*g + 4*(e/2) + idx_e, idx_e = bits 2e+1:2e of
+//      the 16-bit half of the index register that ABID selects (0: low, 1: high);
+//   B  lane 16*g' + n, element j (0..15): column n, K = 32*(j/8) + 8*g' + j%8;
+//   D  as v_mfma_f32_16x16x32_f16: lane 16*q + n holds rows 4*q + v, column n.
+// The kernel maps K to columns so that lane group g reads block g of the superblock, as the tiled order stores
+// it: step s (0..7) of a block covers its columns 16*s .. 16*s+15, K = 16*g + c <-> column 16*s + c of block g.
+//
+// Measured on the device: a SIMD issues one vector instruction every ~4.6 cycles however many wavefronts share
+// it, so the kernel is bound by its instruction count.  It therefore runs two fat wavefronts per SIMD (a
+// wavefront owns a whole superblock: 64 VGPRs of x) instead of four thin ones, which halves the per-wavefront
+// set-up work a SIMD executes, and loads everything through few wide instructions.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <cstdlib>
+
+#include "stb_tiled.hpp"
+
+using namespace stbt;
+
+#ifdef STB_TRACE
+__device__ long long stb_trace_buf24[4096 * 32];
+#define TRACE(slot) do { if (lane == 0) stb_trace_buf24[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + wave) % 4096 * 32 + (slot)] = wall_clock64(); } while (0)
+extern "C" int stb_trace_read24(long long* host) { return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(stb_trace_buf24), sizeof(long long) * 4096 * 32); }
+#else
+#define TRACE(slot) do {} while (0)
+#endif
+
+namespace {
+
+typedef _Float16 half16_t __attribute__((ext_vector_type(16)));
+
+constexpr int LDS24 = 160 * 1024 - 64; // dynamic LDS a workgroup may ask for (a few bytes are static)
+constexpr int PHASE24 = 15;           // row tiles between two reductions (a multiple of 3: three tile buffers)
+
+// Packed operands of one (row, block): mask, sign and id words of the two half blocks, scales, alpha_r.
+struct Tile24 {
+    uint2_t m0, m1;
+    uint32_t s0, s1;
+    uint2_t r0, r1;
+    uint2_t sc;
+    uint32_t ar;
+    uint32_t e00, e01, e10, e11;      // res_sign words: half 0 low / high, half 1 low / high
+};
+constexpr int LMAIN24 = 8;            // load instructions per tile: packed planes ...
+constexpr int LRES24 = 4;             // ... and res_sign words
+
+// The loads are asm statements with the plane base in SGPRs; wait24 names their destination registers.  Between
+// a fetch and its wait the registers must not pass through a copy or a join of two definitions (the compiler
+// does not know that the data arrives later).
+__device__ inline void fetch24(Tile24& d, const TiledPlanes& p, int tile, uint32_t o8, uint32_t o4, uint32_t o2) {
+    // The tile's position goes into the 32-bit lane offset (the planes are smaller than 2 GiB: checked by the
+    // launcher), so that the only scalars a fetch needs are the five plane pointers.
+    const uint32_t t10 = (uint32_t)tile << 10;
+    const uint32_t vm = t10 + o8, vs = (t10 >> 1) + o4, vc = (t10 >> 1) + o8, va = (t10 >> 3) + o2;
+    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.m0) : "v"(vm), "s"(p.mask));
+    asm volatile("global_load_dwordx2 %0, %1, %2 offset:512" : "=v"(d.m1) : "v"(vm), "s"(p.mask));
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.s0) : "v"(vs), "s"(p.sign));
+    asm volatile("global_load_dword %0, %1, %2 offset:256" : "=v"(d.s1) : "v"(vs), "s"(p.sign));
+    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.r0) : "v"(vm), "s"(p.region));
+    asm volatile("global_load_dwordx2 %0, %1, %2 offset:512" : "=v"(d.r1) : "v"(vm), "s"(p.region));
+    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.sc) : "v"(vc), "s"(p.scales));
+    asm volatile("global_load_ushort %0, %1, %2" : "=v"(d.ar) : "v"(va), "s"(p.res_scale));
+}
+
+// The four res_sign words of the lane's row in row tile rt: byte offsets o[h][0 / 1] inside the tile's words.
+__device__ inline void fetch24_res(Tile24& d, const TiledPlanes& p, int rt, uint32_t o00, uint32_t o01, uint32_t o10, uint32_t o11) {
+    const uint32_t base = (uint32_t)rt * (uint32_t)p.res_words * 64u;
+    const uint32_t v00 = base + o00, v01 = base + o01, v10 = base + o10, v11 = base + o11;
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e00) : "v"(v00), "s"(p.res_sign));
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e01) : "v"(v01), "s"(p.res_sign));
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e10) : "v"(v10), "s"(p.res_sign));
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e11) : "v"(v11), "s"(p.res_sign));
+}
+
+template <int K>
+__device__ inline void wait24(Tile24& d) {
+    asm volatile("s_waitcnt vmcnt(%12)"
+                 : "+v"(d.m0), "+v"(d.m1), "+v"(d.s0), "+v"(d.s1), "+v"(d.r0), "+v"(d.r1), "+v"(d.sc), "+v"(d.ar),
+                   "+v"(d.e00), "+v"(d.e01), "+v"(d.e10), "+v"(d.e11)
+                 : "n"(K));
+}
+
+// Index register for 32 columns: every mask nibble (two bits set) becomes the positions of its two kept
+// weights, low one in bits 1:0, high one in bits 3:2.  (nibble >> 1) & 7 is 1..6 for the six valid nibbles
+// and addresses an 8-byte table through v_perm_b32; a nibble of the zero padding maps to positions 0, 1.
+__device__ inline uint32_t index_word(uint32_t m, uint32_t T0, uint32_t T1, uint32_t K7) {
+    const uint32_t t = m >> 1;
+    const uint32_t lo = perm(T1, T0, t & K7);                   // index nibbles of the low nibble of each byte
+    const uint32_t hi = perm(T1, T0, (t >> 4) & K7);            // ... of the high nibbles
+    return (hi << 4) | lo;
+}
+
+struct Res24 {
+    ResSel sel;
+    uint32_t xs[4];     // x at the 8 salient columns of the record (B operand of the dense instruction)
+    uint32_t o0, o1;    // byte offsets, inside a row tile's res_sign words, of the two words with the half's bits
+    uint32_t sh;        // bit of the first entry inside the first word
+};
+
+template <bool HAS_RES>
+__global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half* __restrict__ x, int B,
+                                                      void* __restrict__ y, int y_fp32, int R, int SPS, int PHT,
+                                                      int WREG, int AREA,
+                                                      float* __restrict__ ws_part, uint32_t* __restrict__ ws_count) {
+    __shared__ uint32_t ticket;
+    // Each wavefront owns a region of LDS of WREG bytes: an area of AREA bytes for its slice of x ([row][1040 bytes],
+    // B rows and one of zeros) and later, in the same place, its partial products [PHT][256] fp32; then its 8
+    // salient-column records.  A wavefront stages all of it itself, so nothing before
+    // the first reduction needs a barrier and every wavefront starts on its tiles as soon as its data is there.
+    extern __shared__ __attribute__((aligned(16))) char lds_base[];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int i = lane & 15, g = lane >> 4;
+    const int nthr = blockDim.x;                                  // 64 * SPS: one wavefront per superblock of the split
+    const int gr = blockIdx.x, ks = blockIdx.y, S = gridDim.y;
+    const int sb = ks * SPS + wave;
+    const int r0 = gr * R;
+    const int r1 = r0 + R < p.nrt ? r0 + R : p.nrt;
+    const int rl = r1 - 1;
+    const bool active = sb < p.nsb;                               // uniform per wavefront
+    const int Wa = p.nsb - ks * SPS < SPS ? p.nsb - ks * SPS : SPS;   // wavefronts with work
+    auto tile_of = [&](int rt) { return rt * p.nsb + sb; };
+    auto clamp = [&](int rt) { return rt < rl ? rt : rl; };
+    const uint32_t o8 = (uint32_t)lane * 8u, o4 = (uint32_t)lane * 4u, o2 = (uint32_t)lane * 2u;
+    constexpr int XROW = 1040;                                    // bytes per staged row; the 16-byte skew spreads rows over banks
+    char* const wreg = lds_base + (int64_t)wave * WREG;
+    float* const part = reinterpret_cast<float*>(wreg);
+    uint32_t* const recs = reinterpret_cast<uint32_t*>(wreg + AREA);            // [block g][half] x 12
+    TRACE(0);
+
+    half16_t xr[8];
+    Res24 inv[2];
+    int nch0 = 0, nch1 = 0;
+    Tile24 t0 = {}, t1 = {}, t2 = {};
+    constexpr int L = LMAIN24 + (HAS_RES ? LRES24 : 0);          // loads per tile in the streaming loop
+    auto fetch_res = [&](Tile24& t, int rt) {
+        if constexpr (HAS_RES) fetch24_res(t, p, __builtin_amdgcn_readfirstlane(rt), inv[0].o0, inv[0].o1, inv[1].o0, inv[1].o1);
+    };
+    auto fetch_tile = [&](Tile24& t, int rt) {
+        fetch24(t, p, tile_of(__builtin_amdgcn_readfirstlane(rt)), o8, o4, o2);
+        fetch_res(t, rt);
+    };
+    if (active) {
+        // ---- all loads go out before the first wait: lane l brings columns 8l .. 8l+7 of the superblock for every
+        //      batch row (one 16-byte load per row), lanes 0..23 the 8 records, then the res_sign words of the row
+        //      tiles in 16-byte pieces, then the packed planes of the first three row tiles ----
+        const int col = sb * 512 + lane * 8;
+        const bool col_ok = col < p.k;
+        const __half* xsrc = x + (col_ok ? col : 0);
+        uint4_t sx0, sx1, sx2, sx3, sx4, sx5, sx6, sx7, sx8, sx9, sx10, sx11, sx12, sx13, sx14, sx15;
+#define STB24_LOAD(u, reg) { const __half* a = xsrc + (int64_t)(u) * p.k; asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(reg) : "v"(a)); }
+        // B loads per lane; the conditions are nested so that a small batch passes few of them
+        STB24_LOAD(0, sx0)
+        if (B > 1) STB24_LOAD(1, sx1)
+        if (B > 2) { STB24_LOAD(2, sx2) if (B > 3) STB24_LOAD(3, sx3) }
+        if (B > 4) { STB24_LOAD(4, sx4) if (B > 5) STB24_LOAD(5, sx5) if (B > 6) STB24_LOAD(6, sx6) if (B > 7) STB24_LOAD(7, sx7) }
+        if (B > 8) {
+            STB24_LOAD(8, sx8) if (B > 9) STB24_LOAD(9, sx9) if (B > 10) STB24_LOAD(10, sx10) if (B > 11) STB24_LOAD(11, sx11)
+            if (B > 12) STB24_LOAD(12, sx12) if (B > 13) STB24_LOAD(13, sx13) if (B > 14) STB24_LOAD(14, sx14) if (B > 15) STB24_LOAD(15, sx15)
+        }
+#undef STB24_LOAD
+        uint4_t sr = {0u, 0u, 0u, 0u};
+        if (HAS_RES && lane < 24) {                  // record lane / 3 (block (lane / 3) / 2, half (lane / 3) % 2), 16-byte piece lane % 3
+            const int rI = lane / 3, rpc = lane - 3 * rI;
+            const uint32_t* src = p.sal_tab + (((int64_t)sb * 8 + rI) * p.sal_chunks) * 12 + 4 * rpc;
+            asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(sr) : "v"(src));
+        }
+        fetch24(t0, p, tile_of(clamp(r0)), o8, o4, o2);
+        TRACE(1);
+        // The second and third tile go out after the operands are in registers: a compute unit keeps a limited
+        // number of loads in flight, and the other wavefront of the SIMD should get its first tile early too.
+        // The staging loads are older than the LMAIN24 of the first tile.
+        asm volatile("s_waitcnt vmcnt(%17)"
+                     : "+v"(sx0), "+v"(sx1), "+v"(sx2), "+v"(sx3), "+v"(sx4), "+v"(sx5), "+v"(sx6), "+v"(sx7),
+                       "+v"(sx8), "+v"(sx9), "+v"(sx10), "+v"(sx11), "+v"(sx12), "+v"(sx13), "+v"(sx14), "+v"(sx15),
+                       "+v"(sr)
+                     : "n"(LMAIN24));
+        {
+            char* dst = wreg + lane * 16;
+            const uint4_t zero = {0u, 0u, 0u, 0u};
+#define STB24_STORE(u, reg) *reinterpret_cast<uint4_t*>(dst + (u) * XROW) = col_ok ? reg : zero;
+            STB24_STORE(0, sx0)
+            if (B > 1) STB24_STORE(1, sx1)
+            if (B > 2) { STB24_STORE(2, sx2) if (B > 3) STB24_STORE(3, sx3) }
+            if (B > 4) { STB24_STORE(4, sx4) if (B > 5) STB24_STORE(5, sx5) if (B > 6) STB24_STORE(6, sx6) if (B > 7) STB24_STORE(7, sx7) }
+            if (B > 8) {
+                STB24_STORE(8, sx8) if (B > 9) STB24_STORE(9, sx9) if (B > 10) STB24_STORE(10, sx10) if (B > 11) STB24_STORE(11, sx11)
+                if (B > 12) STB24_STORE(12, sx12) if (B > 13) STB24_STORE(13, sx13) if (B > 14) STB24_STORE(14, sx14) if (B > 15) STB24_STORE(15, sx15)
+            }
+#undef STB24_STORE
+            if (B < 16) *reinterpret_cast<uint4_t*>(dst + B * XROW) = zero;     // row B: zeros, read by the lanes without a batch row
+            if (HAS_RES && lane < 24) *reinterpret_cast<uint4_t*>(&recs[4 * lane]) = sr;
+        }
+        TRACE(2);
+        // ---- the wavefront takes its B operands, its records and the x of its salient columns back from LDS (its own
+        //      stores: LDS keeps a wavefront's accesses in order) ----
+        // B lane 16*g + n: elements 0..7 <-> block g/2, elements 8..15 <-> block 2 + g/2, columns 16*s + 8*(g%2) ..
+        const char* xrow = wreg + (i < B ? i : B) * XROW + (g >> 1) * 256 + (g & 1) * 16;
+#pragma unroll
+        for (int s = 0; s < 8; s++) {
+            const uint4_t lo = *reinterpret_cast<const uint4_t*>(xrow + 32 * s);
+            const uint4_t hi = *reinterpret_cast<const uint4_t*>(xrow + 512 + 32 * s);
+            typedef uint32_t uint8_vec __attribute__((ext_vector_type(8)));
+            const uint8_vec v = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            xr[s] = __builtin_bit_cast(half16_t, v);
+        }
+        if (HAS_RES) {
+            const char* xblk = wreg + (i < B ? i : B) * XROW + g * 256;     // block g of the superblock
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const uint32_t* rec = &recs[(g * 2 + h) * 12];
+                const uint4_t ra = *reinterpret_cast<const uint4_t*>(rec);
+                const uint2_t rb = *reinterpret_cast<const uint2_t*>(rec + 4);
+                const uint4_t rp = *reinterpret_cast<const uint4_t*>(rec + 8);
+                inv[h].sel.sel0 = ra.x; inv[h].sel.sel1 = ra.y; inv[h].sel.bit0 = ra.z; inv[h].sel.bit1 = ra.w;
+                const uint32_t ord = rb.x;
+                const int nc = __builtin_amdgcn_readfirstlane((int)rb.y);
+                if (h == 0) nch0 = nc; else nch1 = nc;
+                inv[h].sh = ord & 31u;
+                const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+                const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+                inv[h].o0 = (uint32_t)(wa * 16 + i) * 4u;
+                inv[h].o1 = (uint32_t)(wb * 16 + i) * 4u;
+                const uint32_t pw[4] = {rp.x, rp.y, rp.z, rp.w};
+                uint32_t hx[8];
+#pragma unroll
+                for (int e = 0; e < 8; e++) {
+                    const uint32_t pos = (pw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                    hx[e] = *reinterpret_cast<const unsigned short*>(xblk + 2 * (pos & 127u));
+                    if (pos >= 128u) hx[e] = 0u;               // no such entry
+                }
+#pragma unroll
+                for (int v = 0; v < 4; v++) inv[h].xs[v] = hx[2 * v] | (hx[2 * v + 1] << 16);
+            }
+        }
+        // the partial products overwrite the x rows: every read above must have returned
+        __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_res(t0, clamp(r0));
+        fetch_tile(t1, clamp(r0 + 1));
+        fetch_tile(t2, clamp(r0 + 2));
+        TRACE(4);
+    }
+
+    // index table of index_word and the other constants, in VGPRs (a VOP3 instruction takes one constant)
+    uint32_t T0 = 0x09080404u, T1 = 0x0E0E0D0Cu, K7 = 0x07070707u, K3 = 0x03030303u, K4 = 0x04000400u, KS = 0x80008000u;
+    asm volatile("" : "+v"(T0), "+v"(T1), "+v"(K7), "+v"(K3), "+v"(K4), "+v"(KS));
+
+    const int64_t n16 = (int64_t)p.nrt * 16;
+    const uint32_t b_magic = B > 1 ? (uint32_t)((0x100000000ull + (uint32_t)B - 1) / (uint32_t)B) : 0u;
+    auto div_b = [&](int v) { return B > 1 ? (int)__umulhi((uint32_t)v, b_magic) : v; };     // v / B, v < 2^27
+    auto store_y = [&](int row, int b, float s) {
+        if (b < B && row < p.n) {
+            if (y_fp32) reinterpret_cast<float*>(y)[(int64_t)b * p.n + row] = -s;
+            else reinterpret_cast<__half*>(y)[(int64_t)b * p.n + row] = __float2half(-s);
+        }
+    };
+
+    // One (row tile, superblock): 8 steps of 16 columns per block, then the residual term of the two halves.
+    auto product = [&](const Tile24& tr, int rt, int slot) {
+        const uint32_t TL = perm(tr.sc[1], tr.sc[0], 0x06040200u), TH = perm(tr.sc[1], tr.sc[0], 0x07050301u);
+        const uint32_t mw[4] = {tr.m0[0], tr.m0[1], tr.m1[0], tr.m1[1]};
+        const uint32_t rw[4] = {tr.r0[0], tr.r0[1], tr.r1[0], tr.r1[1]};
+        const uint32_t sw[2] = {tr.s0, tr.s1};
+        float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int w = 0; w < 4; w++) {                 // 32 columns: two steps
+            const uint32_t IDX = index_word(mw[w], T0, T1, K7);
+            const uint32_t r2 = rw[w] >> 2;
+#pragma unroll
+            for (int u = 0; u < 2; u++) {
+                const int s = 2 * w + u;
+                uint32_t W[4];
+#pragma unroll
+                for (int c = 0; c < 2; c++) {         // byte 2u + c of the id word: 4 kept weights
+                    const uint32_t bb = 2 * u + c;
+                    const uint32_t Z = perm(r2, rw[w], bb | (bb << 8) | ((4 + bb) << 16) | ((4 + bb) << 24));
+                    W[2 * c] = perm(TH, TL, and_or(Z, K3, K4));
+                    W[2 * c + 1] = perm(TH, TL, and_or(Z >> 4, K3, K4));
+                }
+                const uint32_t sbi = (uint32_t)(s & 3);   // byte of the half's sign word
+                const uint32_t X = perm(sw[w >> 1], sw[w >> 1], 0x000C000Cu | (sbi << 8) | (sbi << 24));
+#pragma unroll
+                for (int q = 0; q < 4; q++) W[q] = and_or(pk_shl(X, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
+                const half8_t a = as_half8(W);
+                if (u == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(a, xr[s], acc, (int)IDX, 0, 0);
+                else acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(a, xr[s], acc, (int)IDX, 0, 1);
+            }
+        }
+        if (HAS_RES) {
+            const uint32_t ar1 = tr.ar & 0xFFFFu, ar2 = ar1 | (ar1 << 16);
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                if ((h == 0 ? nch0 : nch1) > 0) {
+                    const uint32_t rlo = h == 0 ? tr.e00 : tr.e10, rhi = h == 0 ? tr.e01 : tr.e11;
+                    const uint32_t rb = __builtin_amdgcn_alignbit(rhi, rlo, inv[h].sh);
+                    uint32_t o[4];
+                    residual_chunk(&mw[2 * h], rb, ar2, inv[h].sel, o);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(o), as_half8(inv[h].xs), acc, 0, 0, 0);
+                }
+            }
+        }
+        float* dst = part + (slot * 256 + lane);
+#pragma unroll
+        for (int v = 0; v < 4; v++) dst[64 * v] = acc[v];
+    };
+
+    // Half blocks with more than 8 salient columns: the records after the first, outside the streaming loop (rare).
+    auto extra_records = [&](int rt, int slot) {
+        const int64_t rstride = (int64_t)p.res_words * 16;
+        const int q = 4 * sb + g;
+        const bool live = i < B && q < p.nb;
+        const unsigned short* xg = reinterpret_cast<const unsigned short*>(x + (int64_t)(i < B ? i : B - 1) * p.k + (int64_t)(q < p.nb ? q : 0) * 128);
+        float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int h = 0; h < 2; h++) {
+            const int nc = h == 0 ? nch0 : nch1;
+            if (nc <= 1) continue;
+            HalfData<4> d;
+            load_half<4>(p, (int64_t)tile_of(rt), lane_offsets<4>(lane, h), h, d);
+            const uint32_t ar2 = d.ar | (d.ar << 16);
+            for (int c = 1; c < nc; c++) {
+                const uint32_t* rec = p.sal_tab + (((int64_t)q * 2 + h) * p.sal_chunks + c) * 12;
+                ResSel sel;
+                sel.sel0 = rec[0]; sel.sel1 = rec[1]; sel.bit0 = rec[2]; sel.bit1 = rec[3];
+                const uint32_t ord = rec[4];
+                uint32_t hx[8];
+                for (int e = 0; e < 8; e++) {
+                    const uint32_t pos = (rec[8 + (e >> 1)] >> (16 * (e & 1))) & 0xFFFFu;
+                    hx[e] = live && pos < 128u ? (uint32_t)xg[pos & 127u] : 0u;
+                }
+                uint32_t xs4[4];
+                for (int v = 0; v < 4; v++) xs4[v] = hx[2 * v] | (hx[2 * v + 1] << 16);
+                const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+                const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+                const uint32_t rlo = p.res_sign[rt * rstride + (int64_t)wa * 16 + i];
+                const uint32_t rhi = p.res_sign[rt * rstride + (int64_t)wb * 16 + i];
+                uint32_t o[4];
+                residual_chunk(d.m, __builtin_amdgcn_alignbit(rhi, rlo, ord & 31u), ar2, sel, o);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(o), as_half8(xs4), acc, 0, 0, 0);
+            }
+        }
+        float* dst = part + (slot * 256 + lane);
+#pragma unroll
+        for (int v = 0; v < 4; v++) dst[64 * v] += acc[v];
+    };
+
+    // The R row tiles are taken in phases of PHT (a multiple of 3 unless it is R itself): the wavefronts stream
+    // PHT tiles each, the workgroup adds the partial products in a fixed order and stores them.  Three tiles are
+    // in flight per wavefront; a fetch past the last tile re-reads that tile, which keeps the number of loads
+    // between a fetch and its wait the same on every path.
+    for (int ph = 0; ph < R; ph += PHT) {
+        const int ph0 = r0 + ph;
+        const int ph1 = ph0 + PHT < r1 ? ph0 + PHT : r1;
+        if (active) {
+            for (int rt = ph0; rt < ph1; rt += 3) {
+                wait24<2 * L>(t0);
+                TRACE(8 + (rt - r0 < 5 ? rt - r0 : 5));
+                product(t0, rt, rt - ph0);
+                TRACE(14 + (rt - r0 < 5 ? rt - r0 : 5));
+                fetch_tile(t0, clamp(rt + 3));
+                wait24<2 * L>(t1);
+                TRACE(8 + (rt + 1 - r0 < 5 ? rt + 1 - r0 : 5));
+                if (rt + 1 < ph1) product(t1, rt + 1, rt + 1 - ph0);
+                TRACE(14 + (rt + 1 - r0 < 5 ? rt + 1 - r0 : 5));
+                fetch_tile(t1, clamp(rt + 4));
+                wait24<2 * L>(t2);
+                TRACE(8 + (rt + 2 - r0 < 5 ? rt + 2 - r0 : 5));
+                if (rt + 2 < ph1) product(t2, rt + 2, rt + 2 - ph0);
+                TRACE(14 + (rt + 2 - r0 < 5 ? rt + 2 - r0 : 5));
+                fetch_tile(t2, clamp(rt + 5));
+            }
+            if (HAS_RES && (nch0 > 1 || nch1 > 1))
+                for (int rt = ph0; rt < ph1; rt++) extra_records(rt, rt - ph0);
+        }
+        TRACE(6);
+        __syncthreads();
+        TRACE(7);
+        // outputs of this phase: (slot, b, row in tile), consecutive threads on consecutive rows
+        const int total = (ph1 > ph0 ? ph1 - ph0 : 0) * B * 16;
+        for (int o = threadIdx.x; o < total; o += nthr) {
+            const int r16 = o & 15, j = div_b(o >> 4), b = (o >> 4) - j * B;
+            const int l = b + 16 * (r16 >> 2), v = r16 & 3;
+            const char* src = lds_base + (j * 256 + 64 * v + l) * 4;
+            float t[8];
+#pragma unroll
+            for (int w = 0; w < 8; w++) t[w] = w < Wa ? *reinterpret_cast<const float*>(src + (int64_t)w * WREG) : 0.0f;   // fixed order of adds
+            float s = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 8; w++) s += t[w];
+            const int row = (ph0 + j) * 16 + r16;
+            if (S == 1) store_y(row, b, s);
+            else __hip_atomic_store(ws_part + ((int64_t)ks * 16 + b) * n16 + row, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (ph + PHT < R) __syncthreads();           // the next phase overwrites the partial products
+    }
+    if (active) {
+        wait24<0>(t0);                               // drain: no load may still target a register that is reused
+        wait24<0>(t1);
+        wait24<0>(t2);
+    }
+    TRACE(20);
+    if (S == 1) return;
+
+    // ---- several column splits: the partial sums are in the workspace [split][16][n16]; take a ticket.  They are
+    //      written and read with agent-scope accesses, so no cache write-back or invalidate is needed: the stores
+    //      have completed (vmcnt = 0, then the barrier) before thread 0 takes the ticket, and the last arrival
+    //      issues its loads after it has seen the ticket. ----
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (threadIdx.x == 0) ticket = atomicInc(ws_count + gr, (uint32_t)(S - 1));    // wraps to 0 after S arrivals
+    __syncthreads();
+    if (ticket != (uint32_t)(S - 1)) return;
+    const int total = (r1 - r0) * 16 * B;
+    for (int o = threadIdx.x; o < total; o += nthr) {
+        const int r16 = o & 15, tb = div_b(o >> 4), b = (o >> 4) - tb * B;
+        const int row = (r0 + tb) * 16 + r16;
+        float s = 0.0f;
+        for (int c0 = 0; c0 < S; c0 += 4) {
+            float t[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+                t[u] = c0 + u < S ? __hip_atomic_load(ws_part + ((int64_t)(c0 + u) * 16 + b) * n16 + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0f;
+#pragma unroll
+            for (int u = 0; u < 4; u++) s += t[u];
+        }
+        store_y(row, b, s);
+    }
+}
+
+template <bool HAS_RES>
+hipError_t launch24(const TiledPlanes& p, const __half* x, int B, void* y, int y_fp32, int R, int SPS, int PHT, int wreg, int area,
+                    dim3 grid, float* ws_part, uint32_t* ws_count, hipStream_t st) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv24_kernel<HAS_RES>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS24);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((gemv24_kernel<HAS_RES>), grid, dim3(64 * SPS), (size_t)SPS * wreg, st, p, x, B, y, y_fp32, R, SPS, PHT,
+                       wreg, area, ws_part, ws_count);
+    return hipGetLastError();
+}
+
+int64_t round_up256(int64_t v) { return (v + 255) / 256 * 256; }
+
+}  // namespace
+
+// Picks the launch shape and runs the kernel; returns STB_EUNSUPPORTED (and launches nothing) when the layout
+// is not 2:4 or a staging area would not fit, so that the caller can fall back to the general kernel.
+extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
+                                int64_t workspace_bytes, int max_splits, void* stream, int* hip_err) {
+    if (L->cfg.M != 4 || L->cfg.N != 2 || B < 1 || B > 16) return STB_EUNSUPPORTED;
+    if (L->mask_bytes >= (1ll << 31) || L->res_bytes >= (1ll << 31)) return STB_EUNSUPPORTED;   // 32-bit offsets inside a plane
+    const TiledPlanes p = make_tiled(L);
+    // Column splits of SPS <= 8 superblocks (one wavefront each); a workgroup owns R row tiles.  Among the split
+    // counts that fit, take the one with the lowest estimated time: R tiles for each of the ceil(SPS / 4)
+    // wavefronts of a SIMD, times the rounds the grid needs on 256 compute units, plus the cost of adding the
+    // splits up; ties go to the fewest splits.
+    int best_S = 0, best_R = 0, best_sps = 0;
+    int64_t best_cost = 0;
+    const int s_min = (p.nsb + 7) / 8;
+    for (int S = s_min; S <= max_splits && S <= p.nsb; S++) {
+        const int sps = (p.nsb + S - 1) / S;
+        if (sps > 8 || (S - 1) * sps >= p.nsb) continue;           // a split must own at least one superblock
+        const int groups = 256 / S > 0 ? 256 / S : 1;
+        const int R = (p.nrt + groups - 1) / groups;
+        const int G = (p.nrt + R - 1) / R;
+        // measured: ~0.75 us per (row tile, superblock) product of a SIMD; the reduction over column splits through
+        // the workspace costs ~0.09 us per split and batch row
+        const int64_t cost = (int64_t)750 * R * ((sps + 3) / 4) * ((G * S + 255) / 256) + (S > 1 ? (int64_t)90 * S * B : 0);
+        if (best_S == 0 || cost < best_cost) { best_cost = cost; best_S = S; best_R = R; best_sps = sps; }
+    }
+    if (const char* f = getenv("STB_GEMV24_S")) {                  // experiments: force the number of splits
+        const int S = atoi(f);
+        if (S >= s_min && S <= max_splits && S <= p.nsb) {
+            const int sps = (p.nsb + S - 1) / S;
+            if (sps <= 8 && (S - 1) * sps < p.nsb) {
+                const int groups = 256 / S > 0 ? 256 / S : 1;
+                best_S = S; best_sps = sps; best_R = (p.nrt + groups - 1) / groups;
+            }
+        }
+    }
+    if (best_S == 0) return STB_EUNSUPPORTED;
+    const int S = best_S, R = best_R, SPS = best_sps;
+    const int G = (p.nrt + R - 1) / R;
+    const int PHT = R < PHASE24 ? R : PHASE24;
+    const bool res = p.res_words > 0;
+    // LDS of one wavefront: the larger of (B rows of x and one of zeros, 1040 bytes each) and (PHT partial tiles),
+    // then its 8 records
+    const int xbytes = (B < 16 ? B + 1 : 16) * 1040, pbytes = PHT * 1024;
+    const int area = xbytes > pbytes ? xbytes : pbytes;
+    const int wreg = area + 384;
+    if ((int64_t)SPS * wreg > LDS24) return STB_EUNSUPPORTED;
+    if (S > 1) {
+        if (!workspace) return STB_ENULL;
+        if (workspace_bytes < round_up256(4 * (int64_t)p.nrt) + (int64_t)S * 16 * 16 * p.nrt * 4) return STB_EINVAL;
+        if ((uintptr_t)workspace % 256) return STB_EALIGN;
+    }
+    uint32_t* cnt = (uint32_t*)workspace;
+    float* part = S > 1 ? (float*)((char*)workspace + round_up256(4 * (int64_t)p.nrt)) : nullptr;
+    const hipError_t e = res ? launch24<true>(p, (const __half*)x, B, y, y_fp32, R, SPS, PHT, wreg, area, dim3(G, S), part, cnt, (hipStream_t)stream)
+                             : launch24<false>(p, (const __half*)x, B, y, y_fp32, R, SPS, PHT, wreg, area, dim3(G, S), part, cnt, (hipStream_t)stream);
+    *hip_err = (int)e;
+    return e == hipSuccess ? STB_OK : STB_EHIP;
+}

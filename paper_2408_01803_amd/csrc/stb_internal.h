@@ -16,8 +16,13 @@ int stb_tiled_supported(const stb_layout_t* L);
 int stb_tiled_dequant(const stb_layout_t* L, float* out, void* stream, int* hip_err);
 int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
                    int64_t workspace_bytes, void* stream, int* hip_err);
-// Scratch bytes of the tiled decode kernel for L's shape (0 when k <= 4096).
+// Scratch bytes of the tiled decode kernels for L's shape.
 int64_t stb_tiled_gemv_workspace(int n_row_tiles, int n_super);
+// Decode kernel for 2:4 layouts on the sparse matrix-core instruction (stb_gemv24.hip).  Returns STB_EUNSUPPORTED,
+// without launching anything, when the layout is not 2:4 or its staging areas would not fit: the caller then runs
+// the general kernel.  max_splits bounds the number of column splits (the workspace is sized for that many).
+int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
+                     int64_t workspace_bytes, int max_splits, void* stream, int* hip_err);
 // Prefill kernel for the tiled order (stb_gemm.hip) and its scratch size for T tokens.
 int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void* Y, int y_fp32, void* workspace,
                    int64_t workspace_bytes, void* stream, int* hip_err);

@@ -83,16 +83,18 @@ __device__ inline uint32_t and_or(uint32_t a, uint32_t b, uint32_t c) {
     return r;
 }
 
+// Packed 16-bit minimum and low product as single instructions (written as vector arithmetic the compiler
+// turns them into compare / select chains of four instructions per register).
 __device__ inline uint32_t pk_min_u16(uint32_t a, uint32_t b) {
-    const ushort2_t x = __builtin_bit_cast(ushort2_t, a), y = __builtin_bit_cast(ushort2_t, b);
-    const ushort2_t r = __builtin_elementwise_min(x, y);
-    return __builtin_bit_cast(uint32_t, r);
+    uint32_t r;
+    asm("v_pk_min_u16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
 }
 
 __device__ inline uint32_t pk_mul_u16(uint32_t a, uint32_t b) {
-    const ushort2_t x = __builtin_bit_cast(ushort2_t, a), y = __builtin_bit_cast(ushort2_t, b);
-    const ushort2_t r = x * y;
-    return __builtin_bit_cast(uint32_t, r);
+    uint32_t r;
+    asm("v_pk_mul_lo_u16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
 }
 
 // 32 bits of a little-endian bit string held in words w[], starting at bit `off` (compile-time constant
