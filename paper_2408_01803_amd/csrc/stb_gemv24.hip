@@ -138,7 +138,9 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
     TRACE(0);
 
     half16_t xr[8];
-    Res24 inv[2];
+    Res24 inv[2];                                                // first record of the lane's block, per half
+    ResSel sel2[2];                                              // second record (half blocks with 9..16 salient columns)
+    uint32_t xs2[2][4];
     int nch0 = 0, nch1 = 0;
     Tile24 t0 = {}, t1 = {}, t2 = {};
     constexpr int L = LMAIN24 + (HAS_RES ? LRES24 : 0);          // loads per tile in the streaming loop
@@ -169,15 +171,16 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         }
 #undef STB24_LOAD
         uint4_t sr = {0u, 0u, 0u, 0u};
-        if (HAS_RES && lane < 24) {                  // record lane / 3 (block (lane / 3) / 2, half (lane / 3) % 2), 16-byte piece lane % 3
-            const int rI = lane / 3, rpc = lane - 3 * rI;
-            const uint32_t* src = p.sal_tab + (((int64_t)sb * 8 + rI) * p.sal_chunks) * 12 + 4 * rpc;
+        if (HAS_RES && lane < 48) {                  // (block, half) lane / 6, record (lane % 6) / 3 of it, 16-byte piece lane % 3
+            const int rI = lane / 6, rc = (lane - 6 * rI) / 3, rpc = lane % 3;
+            const uint32_t* src = p.sal_tab + (((int64_t)sb * 8 + rI) * p.sal_chunks + (rc < p.sal_chunks ? rc : 0)) * 12 + 4 * rpc;
             asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(sr) : "v"(src));
         }
         fetch24(t0, p, tile_of(clamp(r0)), o8, o4, o2);
         TRACE(1);
         // The second and third tile go out after the operands are in registers: a compute unit keeps a limited
-        // number of loads in flight, and the other wavefront of the SIMD should get its first tile early too.
+        // number of loads in flight, and the other wavefront of the SIMD should get its first tile early too
+        // (issuing them here instead was measured: no faster with one wavefront per SIMD, slower with two).
         // The staging loads are older than the LMAIN24 of the first tile.
         asm volatile("s_waitcnt vmcnt(%17)"
                      : "+v"(sx0), "+v"(sx1), "+v"(sx2), "+v"(sx3), "+v"(sx4), "+v"(sx5), "+v"(sx6), "+v"(sx7),
@@ -198,7 +201,7 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
             }
 #undef STB24_STORE
             if (B < 16) *reinterpret_cast<uint4_t*>(dst + B * XROW) = zero;     // row B: zeros, read by the lanes without a batch row
-            if (HAS_RES && lane < 24) *reinterpret_cast<uint4_t*>(&recs[4 * lane]) = sr;
+            if (HAS_RES && lane < 48) *reinterpret_cast<uint4_t*>(&recs[4 * lane]) = sr;     // [block][half][record 0 / 1] x 12
         }
         TRACE(2);
         // ---- the wavefront takes its B operands, its records and the x of its salient columns back from LDS (its own
@@ -217,11 +220,11 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
             const char* xblk = wreg + (i < B ? i : B) * XROW + g * 256;     // block g of the superblock
 #pragma unroll
             for (int h = 0; h < 2; h++) {
-                const uint32_t* rec = &recs[(g * 2 + h) * 12];
+                const uint32_t* rec = &recs[(g * 2 + h) * 24];
                 const uint4_t ra = *reinterpret_cast<const uint4_t*>(rec);
-                const uint2_t rb = *reinterpret_cast<const uint2_t*>(rec + 4);
                 const uint4_t rp = *reinterpret_cast<const uint4_t*>(rec + 8);
                 inv[h].sel.sel0 = ra.x; inv[h].sel.sel1 = ra.y; inv[h].sel.bit0 = ra.z; inv[h].sel.bit1 = ra.w;
+                const uint2_t rb = *reinterpret_cast<const uint2_t*>(rec + 4);
                 const uint32_t ord = rb.x;
                 const int nc = __builtin_amdgcn_readfirstlane((int)rb.y);
                 if (h == 0) nch0 = nc; else nch1 = nc;
@@ -240,6 +243,20 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
                 }
 #pragma unroll
                 for (int v = 0; v < 4; v++) inv[h].xs[v] = hx[2 * v] | (hx[2 * v + 1] << 16);
+                if (nc > 1) {                        // the second record of the half block
+                    const uint4_t rc = *reinterpret_cast<const uint4_t*>(rec + 12);
+                    const uint4_t rq = *reinterpret_cast<const uint4_t*>(rec + 20);
+                    sel2[h].sel0 = rc.x; sel2[h].sel1 = rc.y; sel2[h].bit0 = rc.z; sel2[h].bit1 = rc.w;
+                    const uint32_t qw[4] = {rq.x, rq.y, rq.z, rq.w};
+#pragma unroll
+                    for (int e = 0; e < 8; e++) {
+                        const uint32_t pos = (qw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
+                        hx[e] = *reinterpret_cast<const unsigned short*>(xblk + 2 * (pos & 127u));
+                        if (pos >= 128u) hx[e] = 0u;
+                    }
+#pragma unroll
+                    for (int v = 0; v < 4; v++) xs2[h][v] = hx[2 * v] | (hx[2 * v + 1] << 16);
+                }
             }
         }
         // the partial products overwrite the x rows: every read above must have returned
@@ -284,13 +301,13 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
                 for (int c = 0; c < 2; c++) {         // byte 2u + c of the id word: 4 kept weights
                     const uint32_t bb = 2 * u + c;
                     const uint32_t Z = perm(r2, rw[w], bb | (bb << 8) | ((4 + bb) << 16) | ((4 + bb) << 24));
-                    W[2 * c] = perm(TH, TL, and_or(Z, K3, K4));
-                    W[2 * c + 1] = perm(TH, TL, and_or(Z >> 4, K3, K4));
+                    W[2 * c] = perm(TH, TL, and_or_v(Z, K3, K4));
+                    W[2 * c + 1] = perm(TH, TL, and_or_v(Z >> 4, K3, K4));
                 }
                 const uint32_t sbi = (uint32_t)(s & 3);   // byte of the half's sign word
                 const uint32_t X = perm(sw[w >> 1], sw[w >> 1], 0x000C000Cu | (sbi << 8) | (sbi << 24));
 #pragma unroll
-                for (int q = 0; q < 4; q++) W[q] = and_or(pk_shl(X, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
+                for (int q = 0; q < 4; q++) W[q] = and_or_v(pk_shl(X, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
                 const half8_t a = as_half8(W);
                 if (u == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(a, xr[s], acc, (int)IDX, 0, 0);
                 else acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(a, xr[s], acc, (int)IDX, 0, 1);
@@ -306,6 +323,10 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
                     uint32_t o[4];
                     residual_chunk(&mw[2 * h], rb, ar2, inv[h].sel, o);
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(o), as_half8(inv[h].xs), acc, 0, 0, 0);
+                    if ((h == 0 ? nch0 : nch1) > 1) {    // entries 8..15: their bits follow in the same 32-bit window
+                        residual_chunk(&mw[2 * h], rb >> 8, ar2, sel2[h], o);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(o), as_half8(xs2[h]), acc, 0, 0, 0);
+                    }
                 }
             }
         }
@@ -314,7 +335,7 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         for (int v = 0; v < 4; v++) dst[64 * v] = acc[v];
     };
 
-    // Half blocks with more than 8 salient columns: the records after the first, outside the streaming loop (rare).
+    // Half blocks with more than 16 salient columns: the records after the second, outside the streaming loop (rare).
     auto extra_records = [&](int rt, int slot) {
         const int64_t rstride = (int64_t)p.res_words * 16;
         const int q = 4 * sb + g;
@@ -323,11 +344,11 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
         for (int h = 0; h < 2; h++) {
             const int nc = h == 0 ? nch0 : nch1;
-            if (nc <= 1) continue;
+            if (nc <= 2) continue;
             HalfData<4> d;
             load_half<4>(p, (int64_t)tile_of(rt), lane_offsets<4>(lane, h), h, d);
             const uint32_t ar2 = d.ar | (d.ar << 16);
-            for (int c = 1; c < nc; c++) {
+            for (int c = 2; c < nc; c++) {
                 const uint32_t* rec = p.sal_tab + (((int64_t)q * 2 + h) * p.sal_chunks + c) * 12;
                 ResSel sel;
                 sel.sel0 = rec[0]; sel.sel1 = rec[1]; sel.bit0 = rec[2]; sel.bit1 = rec[3];
@@ -378,7 +399,7 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
                 TRACE(14 + (rt + 2 - r0 < 5 ? rt + 2 - r0 : 5));
                 fetch_tile(t2, clamp(rt + 5));
             }
-            if (HAS_RES && (nch0 > 1 || nch1 > 1))
+            if (HAS_RES && (nch0 > 2 || nch1 > 2))
                 for (int rt = ph0; rt < ph1; rt++) extra_records(rt, rt - ph0);
         }
         TRACE(6);
@@ -492,10 +513,10 @@ extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, voi
     const int PHT = R < PHASE24 ? R : PHASE24;
     const bool res = p.res_words > 0;
     // LDS of one wavefront: the larger of (B rows of x and one of zeros, 1040 bytes each) and (PHT partial tiles),
-    // then its 8 records
+    // then its 16 records (two per half block)
     const int xbytes = (B < 16 ? B + 1 : 16) * 1040, pbytes = PHT * 1024;
     const int area = xbytes > pbytes ? xbytes : pbytes;
-    const int wreg = area + 384;
+    const int wreg = area + 768;
     if ((int64_t)SPS * wreg > LDS24) return STB_EUNSUPPORTED;
     if (S > 1) {
         if (!workspace) return STB_ENULL;
@@ -504,8 +525,11 @@ extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, voi
     }
     uint32_t* cnt = (uint32_t*)workspace;
     float* part = S > 1 ? (float*)((char*)workspace + round_up256(4 * (int64_t)p.nrt)) : nullptr;
-    const hipError_t e = res ? launch24<true>(p, (const __half*)x, B, y, y_fp32, R, SPS, PHT, wreg, area, dim3(G, S), part, cnt, (hipStream_t)stream)
-                             : launch24<false>(p, (const __half*)x, B, y, y_fp32, R, SPS, PHT, wreg, area, dim3(G, S), part, cnt, (hipStream_t)stream);
+    const __half* xh = (const __half*)x;
+    const dim3 grid(G, S);
+    const hipStream_t st = (hipStream_t)stream;
+    const hipError_t e = res ? launch24<true>(p, xh, B, y, y_fp32, R, SPS, PHT, wreg, area, grid, part, cnt, st)
+                             : launch24<false>(p, xh, B, y, y_fp32, R, SPS, PHT, wreg, area, grid, part, cnt, st);
     *hip_err = (int)e;
     return e == hipSuccess ? STB_OK : STB_EHIP;
 }

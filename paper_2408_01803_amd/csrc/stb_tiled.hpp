@@ -83,18 +83,14 @@ __device__ inline uint32_t and_or(uint32_t a, uint32_t b, uint32_t c) {
     return r;
 }
 
-// Packed 16-bit minimum and low product as single instructions (written as vector arithmetic the compiler
-// turns them into compare / select chains of four instructions per register).
-__device__ inline uint32_t pk_min_u16(uint32_t a, uint32_t b) {
-    uint32_t r;
-    asm("v_pk_min_u16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
+// (a & b) | c for operands of which at most one is a literal constant: the compiler picks v_and_or_b32 itself,
+// and schedules it better than an asm statement (after which it also pads dependent instructions with s_nop).
+__device__ inline uint32_t and_or_v(uint32_t a, uint32_t b, uint32_t c) { return (a & b) | c; }
 
+// Low 16-bit products of the two halves (v_pk_mul_lo_u16).
 __device__ inline uint32_t pk_mul_u16(uint32_t a, uint32_t b) {
-    uint32_t r;
-    asm("v_pk_mul_lo_u16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
+    const ushort2_t r = __builtin_bit_cast(ushort2_t, a) * __builtin_bit_cast(ushort2_t, b);
+    return __builtin_bit_cast(uint32_t, r);
 }
 
 // 32 bits of a little-endian bit string held in words w[], starting at bit `off` (compile-time constant
@@ -375,18 +371,22 @@ struct ResSel {
 // bit e; other bits ignored), ar2 = alpha_r in both halves.
 __device__ inline void residual_chunk(const uint32_t m[2], uint32_t rb8, uint32_t ar2, const ResSel& s,
                                       uint32_t out[4]) {
+    // per entry: the mask byte that holds its column, reduced to its bit, then to a 0 / 1 flag (a byte b <= 128 is
+    // non-zero iff b + 127 has bit 7 set)
     const uint32_t G0 = perm(m[1], m[0], s.sel0) & s.bit0;
     const uint32_t G1 = perm(m[1], m[0], s.sel1) & s.bit1;
+    const uint32_t F0 = ((G0 + 0x7F7F7F7Fu) >> 7) & 0x01010101u;
+    const uint32_t F1 = ((G1 + 0x7F7F7F7Fu) >> 7) & 0x01010101u;
     uint32_t K[4];
-    K[0] = perm(0u, G0, 0x0C010C00u);      // halves = byte of entry 0 / 1: non-zero iff kept
-    K[1] = perm(0u, G0, 0x0C030C02u);
-    K[2] = perm(0u, G1, 0x0C010C00u);
-    K[3] = perm(0u, G1, 0x0C030C02u);
+    K[0] = perm(0u, F0, 0x0C010C00u);      // halves = flag of entry 0 / 1
+    K[1] = perm(0u, F0, 0x0C030C02u);
+    K[2] = perm(0u, F1, 0x0C010C00u);
+    K[3] = perm(0u, F1, 0x0C030C02u);
     const uint32_t X = perm(rb8, rb8, 0x000C000Cu);          // halves = rb8 << 8
 #pragma unroll
     for (int v = 0; v < 4; v++) {
-        const uint32_t val = and_or(pk_shl(X, 7 - 2 * v, 6 - 2 * v), 0x80008000u, ar2);
-        out[v] = pk_mul_u16(val, pk_min_u16(K[v], 0x00010001u));
+        const uint32_t val = and_or_v(pk_shl(X, 7 - 2 * v, 6 - 2 * v), 0x80008000u, ar2);
+        out[v] = pk_mul_u16(val, K[v]);
     }
 }
 

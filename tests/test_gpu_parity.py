@@ -70,6 +70,13 @@ SMALL = [
     (96, 512, 5, 8, 0, "x8", 104),
     (64, 256, 8, 8, 0, "x8", 105),
     (5, 128, 1, 4, 1, "x8", 106),
+    # crowded salient columns (optional 8th field = their number): about 9 and about 16 per half block of 64
+    # columns, which takes the kernels through their second salient-column record and past it
+    (48, 1024, 2, 4, 1, "x8", 108, 150),
+    (64, 512, 2, 4, 0, "t3", 107, 130),
+    (80, 512, 4, 8, 0, "x8", 109, 100),
+    # more than 4096 columns: two column splits that meet through the workspace
+    (40, 4608, 2, 4, 1, "t3", 110),
 ]
 
 
@@ -81,11 +88,11 @@ SMALL_KINDS = [(c, tiled) for c in SMALL for tiled in (False, True) if not tiled
 
 
 @pytest.fixture(scope="module", params=SMALL_KINDS,
-                ids=lambda c: f"{c[0][0]}x{c[0][1]}_{c[0][2]}of{c[0][3]}_m{c[0][4]}_{'tiled' if c[1] else 'rowmajor'}")
+                ids=lambda c: f"{c[0][0]}x{c[0][1]}_{c[0][2]}of{c[0][3]}_m{c[0][4]}{'_s%d' % c[0][7] if len(c[0]) > 7 else ''}_{'tiled' if c[1] else 'rowmajor'}")
 def small_case(request, torch_cuda):
-    (n, k, N, M, mode, kind, seed), tiled = request.param
+    (n, k, N, M, mode, kind, seed, *rest), tiled = request.param
     _say(f"[case] small {request.param}")
-    L = make_layer(n, k, seed, kind)
+    L = make_layer(n, k, seed, kind, n_salient=rest[0] if rest else None)
     ref = O.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode)
     pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode)
     for name, v in ref.items():
