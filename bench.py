@@ -34,9 +34,9 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16/bf16 matrix peak, vendor figu
 POOL_BYTES = 1 << 30
 
 # HBM bytes per decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this command, scaled by what
-# the same counters read for a copy of known size; see profiles/gemv_stream_workload2_decode.md.
+# the same counters read for a copy of known size; see profiles/gemv24_workload2_decode.md.
 # Average over the six launches of a step (read + written).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 19.0e6
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 19.6e6
 
 
 def log(*a):
@@ -187,7 +187,7 @@ def main():
                    "ms_per_step_host_launches": round(eager_ms_per_step, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
-                     "kernel": "gemv_stream_kernel (stb_gemv)", "us_per_launch": round(launch_us, 2),
+                     "kernel": "gemv24_kernel (stb_gemv on a tiled 2:4 layout)", "us_per_launch": round(launch_us, 2),
                      "algorithmic_bytes_per_launch": int(algo_per_step / launches_per_step)},
     }
 
