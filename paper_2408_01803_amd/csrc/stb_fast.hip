@@ -589,7 +589,7 @@ extern "C" int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void*
                               int64_t workspace_bytes, void* stream, int* hip_err) {
     if (!stb_tiled_supported(L)) return STB_EUNSUPPORTED;
     static const int allow24 = env_int("STB_GEMV_24", 1);
-    if (allow24 && B <= 16) {                                       // 2:4: the kernel on the sparse matrix-core instruction
+    if (allow24 && B <= 16) {                                       // the kernel with fat wavefronts, if its LDS areas fit
         const int rc = stb_tiled_gemv24(L, x, B, y, y_fp32, workspace, workspace_bytes, max_splits(L->n_super), stream, hip_err);
         if (rc != STB_EUNSUPPORTED) return rc;
     }

@@ -1,12 +1,14 @@
-// Decode GEMV for 2:4 layouts (App. C: the memory-bound regime) on the sparse matrix-core instruction.
+// Decode GEMV for the tiled order (App. C: the memory-bound regime), one fat wavefront per superblock.
 //
-// Every group of 4 columns keeps exactly 2 weights (Sec. 3.1), which is the operand form of
-// v_smfmac_f32_16x16x64_f16: A holds the kept weights only (8 per lane for 16 columns), an index register says
-// where inside its group of 4 each of them sits, and the instruction multiplies against 64 rows of B.  The
-// kept weights come out of the packed planes in slot order -- the order the sign and id planes are stored in
-// -- so the per-column scatter that the dense kernels need disappears, and with it their table in LDS.
+// 2:4 layers run on the sparse matrix-core instruction.  Every group of 4 columns keeps exactly 2 weights
+// (Sec. 3.1), which is the operand form of v_smfmac_f32_16x16x64_f16: A holds the kept weights only (8 per lane
+// for 16 columns), an index register says where inside its group of 4 each of them sits, and the instruction
+// multiplies against 64 rows of B.  The kept weights come out of the packed planes in slot order -- the order the
+// sign and id planes are stored in -- so the per-column scatter that the dense kernels need disappears, and with
+// it their table in LDS.  Layers that keep 4 or 6 of 8 columns run the same kernel in a dense mode: 16 steps of 8
+// columns on v_mfma_f32_16x16x32_f16 with the scatter table of stb_tiled.hpp.
 //
-// Operand layout of the instruction (found by probing single-element operands on the device):
+// Operand layout of the sparse instruction (found by probing single-element operands on the device):
 //   A  lane 16*g + i, element e (0..7): row i, uncompressed K = 16*g + 4*(e/2) + idx_e, idx_e = bits 2e+1:2e of
 //      the 16-bit half of the index register that ABID selects (0: low, 1: high);
 //   B  lane 16*g' + n, element j (0..15): column n, K = 32*(j/8) + 8*g' + j%8;
@@ -14,10 +16,10 @@
 // The kernel maps K to columns so that lane group g reads block g of the superblock, as the tiled order stores
 // it: step s (0..7) of a block covers its columns 16*s .. 16*s+15, K = 16*g + c <-> column 16*s + c of block g.
 //
-// Measured on the device: a SIMD issues one vector instruction every ~4.6 cycles however many wavefronts share
-// it, so the kernel is bound by its instruction count.  It therefore runs two fat wavefronts per SIMD (a
-// wavefront owns a whole superblock: 64 VGPRs of x) instead of four thin ones, which halves the per-wavefront
-// set-up work a SIMD executes, and loads everything through few wide instructions.
+// Measured on the device: a SIMD issues one wavefront-wide vector instruction every 4 cycles however many
+// wavefronts share it, so the kernel is bound by its instruction count.  It therefore runs two fat wavefronts per
+// SIMD (a wavefront owns a whole superblock: 64 VGPRs of x) instead of four thin ones, which halves the
+// per-wavefront set-up work a SIMD executes, and loads everything through few wide instructions.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
@@ -90,6 +92,107 @@ __device__ inline void wait24(Tile24& d) {
                  : "n"(K));
 }
 
+// The same for 6:8 layers: 12 bytes of sign bits per block (not cut in halves), 12 bytes of ids per half block.
+struct Tile68 {
+    uint2_t m0, m1;
+    uint3_t s;
+    uint3_t r0, r1;
+    uint2_t sc;
+    uint32_t ar;
+    uint32_t e00, e01, e10, e11;
+};
+constexpr int LMAIN68 = 7;
+
+__device__ inline void fetch24(Tile68& d, const TiledPlanes& p, int tile, uint32_t o8, uint32_t o4, uint32_t o2) {
+    const uint32_t t10 = (uint32_t)tile << 10;
+    const uint32_t o12 = o4 * 3u;
+    const uint32_t vm = t10 + o8, vs = (uint32_t)tile * 768u + o12, vr = (uint32_t)tile * 1536u + o12;
+    const uint32_t vc = (t10 >> 1) + o8, va = (t10 >> 3) + o2;
+    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.m0) : "v"(vm), "s"(p.mask));
+    asm volatile("global_load_dwordx2 %0, %1, %2 offset:512" : "=v"(d.m1) : "v"(vm), "s"(p.mask));
+    asm volatile("global_load_dwordx3 %0, %1, %2" : "=v"(d.s) : "v"(vs), "s"(p.sign));
+    asm volatile("global_load_dwordx3 %0, %1, %2" : "=v"(d.r0) : "v"(vr), "s"(p.region));
+    asm volatile("global_load_dwordx3 %0, %1, %2 offset:768" : "=v"(d.r1) : "v"(vr), "s"(p.region));
+    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.sc) : "v"(vc), "s"(p.scales));
+    asm volatile("global_load_ushort %0, %1, %2" : "=v"(d.ar) : "v"(va), "s"(p.res_scale));
+}
+
+__device__ inline void fetch24_res(Tile68& d, const TiledPlanes& p, int rt, uint32_t o00, uint32_t o01, uint32_t o10, uint32_t o11) {
+    const uint32_t base = (uint32_t)rt * (uint32_t)p.res_words * 64u;
+    const uint32_t v00 = base + o00, v01 = base + o01, v10 = base + o10, v11 = base + o11;
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e00) : "v"(v00), "s"(p.res_sign));
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e01) : "v"(v01), "s"(p.res_sign));
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e10) : "v"(v10), "s"(p.res_sign));
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e11) : "v"(v11), "s"(p.res_sign));
+}
+
+template <int K>
+__device__ inline void wait24(Tile68& d) {
+    asm volatile("s_waitcnt vmcnt(%11)"
+                 : "+v"(d.m0), "+v"(d.m1), "+v"(d.s), "+v"(d.r0), "+v"(d.r1), "+v"(d.sc), "+v"(d.ar),
+                   "+v"(d.e00), "+v"(d.e01), "+v"(d.e10), "+v"(d.e11)
+                 : "n"(K));
+}
+
+// MODE of the kernel below: 2 = 2:4 layers on the sparse instruction; 4 / 6 = layers that keep 4 / 6 of 8 columns
+// on the dense instruction with the scatter table of stb_tiled.hpp.
+template <int MODE> struct TileOf { typedef Tile24 type; static constexpr int lmain = LMAIN24; };
+template <> struct TileOf<6> { typedef Tile68 type; static constexpr int lmain = LMAIN68; };
+
+// The mask, sign and id words of half h of a tile in the form the shared expansion takes them.
+__device__ inline void half_of(const Tile24& t, int h, HalfData<4>& d) {
+    d.m[0] = h == 0 ? t.m0[0] : t.m1[0]; d.m[1] = h == 0 ? t.m0[1] : t.m1[1];
+    d.s[0] = h == 0 ? t.s0 : t.s1; d.s[1] = 0u;
+    d.r[0] = h == 0 ? t.r0[0] : t.r1[0]; d.r[1] = h == 0 ? t.r0[1] : t.r1[1]; d.r[2] = 0u;
+}
+__device__ inline void half_of(const Tile68& t, int h, HalfData<6>& d) {
+    d.m[0] = h == 0 ? t.m0[0] : t.m1[0]; d.m[1] = h == 0 ? t.m0[1] : t.m1[1];
+    if (h == 0) { d.s[0] = t.s[0]; d.s[1] = t.s[1]; }                                   // bits 0..47
+    else { d.s[0] = __builtin_amdgcn_alignbit(t.s[2], t.s[1], 16u); d.s[1] = t.s[2] >> 16; }   // bits 48..95
+    d.r[0] = h == 0 ? t.r0[0] : t.r1[0]; d.r[1] = h == 0 ? t.r0[1] : t.r1[1]; d.r[2] = h == 0 ? t.r0[2] : t.r1[2];
+}
+
+// expand_group of stb_tiled.hpp with the constants in registers (K3 = 0x03030303, K4 = 0x04000400,
+// KS = 0x80008000), so that every and-or is one compiler-scheduled instruction.
+template <int N8>
+__device__ inline void expand8(const HalfData<N8>& d, uint32_t TL, uint32_t TH, int t, const uint4& L,
+                               uint32_t K3, uint32_t K4, uint32_t KS, uint32_t out[4]) {
+    uint32_t W[3];
+    if (N8 == 4) {
+        const uint32_t rw = d.r[t >> 2], r2 = rw >> 2;
+        const uint32_t b = t & 3;
+        const uint32_t Z = perm(r2, rw, b | (b << 8) | ((4 + b) << 16) | ((4 + b) << 24));
+        W[0] = perm(TH, TL, and_or_v(Z, K3, K4));
+        W[1] = perm(TH, TL, and_or_v(Z >> 4, K3, K4));
+        const uint32_t sw = d.s[0];
+        const uint32_t sb = (t >> 1) & 3;
+        const uint32_t X = perm(sw, sw, 0x000C000Cu | (sb << 8) | (sb << 24));     // halves = sign byte << 8
+        const int base = 4 * (t & 1);
+        W[0] = and_or_v(pk_shl(X, 7 - base, 6 - base), KS, W[0]);                   // scales are >= 0: their sign bit is clear
+        W[1] = and_or_v(pk_shl(X, 5 - base, 4 - base), KS, W[1]);
+        out[0] = perm(W[1], W[0], L.x);
+        out[1] = perm(W[1], W[0], L.y);
+        out[2] = perm(W[1], W[0], L.z);
+        out[3] = perm(W[1], W[0], L.w);
+    } else {
+        const uint32_t v = window32<3>(d.r, 12 * t), v2 = v >> 2;
+        const uint32_t Z = perm(v2, v, 0x04040000u);
+        const uint32_t Z1 = perm(v2, v, 0x05050101u);
+        W[0] = perm(TH, TL, and_or_v(Z, K3, K4));
+        W[1] = perm(TH, TL, and_or_v(Z >> 4, K3, K4));
+        W[2] = perm(TH, TL, and_or_v(Z1, K3, K4));
+        const uint32_t sv = window32<2>(d.s, 6 * t);
+        const uint32_t X = perm(sv, sv, 0x000C000Cu);                               // halves = (sign bits) << 8
+        W[0] = and_or_v(pk_shl(X, 7, 6), KS, W[0]);
+        W[1] = and_or_v(pk_shl(X, 5, 4), KS, W[1]);
+        W[2] = and_or_v(pk_shl(X, 3, 2), KS, W[2]);
+        out[0] = perm(W[1], W[0], L.x);
+        out[1] = perm(W[1], W[0], L.y);
+        out[2] = perm(W[2], W[1], L.z);
+        out[3] = perm(W[2], W[1], L.w);
+    }
+}
+
 // Index register for 32 columns: every mask nibble (two bits set) becomes the positions of its two kept
 // weights, low one in bits 1:0, high one in bits 3:2.  (nibble >> 1) & 7 is 1..6 for the six valid nibbles
 // and addresses an 8-byte table through v_perm_b32; a nibble of the zero padding maps to positions 0, 1.
@@ -107,12 +210,16 @@ struct Res24 {
     uint32_t sh;        // bit of the first entry inside the first word
 };
 
-template <bool HAS_RES>
+template <int MODE, bool HAS_RES>
 __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half* __restrict__ x, int B,
                                                       void* __restrict__ y, int y_fp32, int R, int SPS, int PHT,
                                                       int WREG, int AREA,
                                                       float* __restrict__ ws_part, uint32_t* __restrict__ ws_count) {
     __shared__ uint32_t ticket;
+    constexpr int N8 = MODE == 6 ? 6 : 4;
+    typedef typename TileOf<MODE>::type Tile;
+    __shared__ uint4 lut_mem[MODE == 2 ? 1 : 256 * 8];           // dense modes: the scatter table, eight copies
+    ScatterLds* const lut = reinterpret_cast<ScatterLds*>(lut_mem);
     // Each wavefront owns a region of LDS of WREG bytes: an area of AREA bytes for its slice of x ([row][1040 bytes],
     // B rows and one of zeros) and later, in the same place, its partial products [PHT][256] fp32; then its 8
     // salient-column records.  A wavefront stages all of it itself, so nothing before
@@ -137,17 +244,20 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
     uint32_t* const recs = reinterpret_cast<uint32_t*>(wreg + AREA);            // [block g][half] x 12
     TRACE(0);
 
-    half16_t xr[8];
+    if constexpr (MODE != 2) build_luts<N8>(lut);                // arithmetic only; the barrier comes after the staging
+    half16_t xr[8];                                              // MODE 2: B operands of the 8 steps of a block
+    half8_t xd[16];                                              // dense modes: of the 16 steps
     Res24 inv[2];                                                // first record of the lane's block, per half
     ResSel sel2[2];                                              // second record (half blocks with 9..16 salient columns)
     uint32_t xs2[2][4];
     int nch0 = 0, nch1 = 0;
-    Tile24 t0 = {}, t1 = {}, t2 = {};
-    constexpr int L = LMAIN24 + (HAS_RES ? LRES24 : 0);          // loads per tile in the streaming loop
-    auto fetch_res = [&](Tile24& t, int rt) {
+    Tile t0 = {}, t1 = {}, t2 = {};
+    constexpr int LMAIN = TileOf<MODE>::lmain;
+    constexpr int L = LMAIN + (HAS_RES ? LRES24 : 0);            // loads per tile in the streaming loop
+    auto fetch_res = [&](Tile& t, int rt) {
         if constexpr (HAS_RES) fetch24_res(t, p, __builtin_amdgcn_readfirstlane(rt), inv[0].o0, inv[0].o1, inv[1].o0, inv[1].o1);
     };
-    auto fetch_tile = [&](Tile24& t, int rt) {
+    auto fetch_tile = [&](Tile& t, int rt) {
         fetch24(t, p, tile_of(__builtin_amdgcn_readfirstlane(rt)), o8, o4, o2);
         fetch_res(t, rt);
     };
@@ -181,12 +291,12 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         // The second and third tile go out after the operands are in registers: a compute unit keeps a limited
         // number of loads in flight, and the other wavefront of the SIMD should get its first tile early too
         // (issuing them here instead was measured: no faster with one wavefront per SIMD, slower with two).
-        // The staging loads are older than the LMAIN24 of the first tile.
+        // The staging loads are older than the LMAIN of the first tile.
         asm volatile("s_waitcnt vmcnt(%17)"
                      : "+v"(sx0), "+v"(sx1), "+v"(sx2), "+v"(sx3), "+v"(sx4), "+v"(sx5), "+v"(sx6), "+v"(sx7),
                        "+v"(sx8), "+v"(sx9), "+v"(sx10), "+v"(sx11), "+v"(sx12), "+v"(sx13), "+v"(sx14), "+v"(sx15),
                        "+v"(sr)
-                     : "n"(LMAIN24));
+                     : "n"(LMAIN));
         {
             char* dst = wreg + lane * 16;
             const uint4_t zero = {0u, 0u, 0u, 0u};
@@ -204,17 +314,27 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
             if (HAS_RES && lane < 48) *reinterpret_cast<uint4_t*>(&recs[4 * lane]) = sr;     // [block][half][record 0 / 1] x 12
         }
         TRACE(2);
+    }
+    if constexpr (MODE != 2) __syncthreads();       // the scatter table is complete (every wavefront comes here)
+    if (active) {
         // ---- the wavefront takes its B operands, its records and the x of its salient columns back from LDS (its own
         //      stores: LDS keeps a wavefront's accesses in order) ----
-        // B lane 16*g + n: elements 0..7 <-> block g/2, elements 8..15 <-> block 2 + g/2, columns 16*s + 8*(g%2) ..
-        const char* xrow = wreg + (i < B ? i : B) * XROW + (g >> 1) * 256 + (g & 1) * 16;
+        if constexpr (MODE == 2) {
+            // B lane 16*g + n: elements 0..7 <-> block g/2, elements 8..15 <-> block 2 + g/2, columns 16*s + 8*(g%2) ..
+            const char* xrow = wreg + (i < B ? i : B) * XROW + (g >> 1) * 256 + (g & 1) * 16;
 #pragma unroll
-        for (int s = 0; s < 8; s++) {
-            const uint4_t lo = *reinterpret_cast<const uint4_t*>(xrow + 32 * s);
-            const uint4_t hi = *reinterpret_cast<const uint4_t*>(xrow + 512 + 32 * s);
-            typedef uint32_t uint8_vec __attribute__((ext_vector_type(8)));
-            const uint8_vec v = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            xr[s] = __builtin_bit_cast(half16_t, v);
+            for (int s = 0; s < 8; s++) {
+                const uint4_t lo = *reinterpret_cast<const uint4_t*>(xrow + 32 * s);
+                const uint4_t hi = *reinterpret_cast<const uint4_t*>(xrow + 512 + 32 * s);
+                typedef uint32_t uint8_vec __attribute__((ext_vector_type(8)));
+                const uint8_vec v = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                xr[s] = __builtin_bit_cast(half16_t, v);
+            }
+        } else {
+            // B lane 16*g + n of step t: columns 8t .. 8t+7 of block g
+            const char* xrow = wreg + (i < B ? i : B) * XROW + g * 256;
+#pragma unroll
+            for (int t = 0; t < 16; t++) xd[t] = __builtin_bit_cast(half8_t, *reinterpret_cast<const uint4_t*>(xrow + 16 * t));
         }
         if (HAS_RES) {
             const char* xblk = wreg + (i < B ? i : B) * XROW + g * 256;     // block g of the superblock
@@ -282,35 +402,56 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         }
     };
 
-    // One (row tile, superblock): 8 steps of 16 columns per block, then the residual term of the two halves.
-    auto product = [&](const Tile24& tr, int rt, int slot) {
+    // One (row tile, superblock): the steps over the block's columns (sparse: 8 of 16 columns; dense: 16 of 8), then
+    // the residual term of the two halves.
+    auto product = [&](const Tile& tr, int rt, int slot) {
         const uint32_t TL = perm(tr.sc[1], tr.sc[0], 0x06040200u), TH = perm(tr.sc[1], tr.sc[0], 0x07050301u);
         const uint32_t mw[4] = {tr.m0[0], tr.m0[1], tr.m1[0], tr.m1[1]};
-        const uint32_t rw[4] = {tr.r0[0], tr.r0[1], tr.r1[0], tr.r1[1]};
-        const uint32_t sw[2] = {tr.s0, tr.s1};
         float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (MODE == 2) {
+            const uint32_t rw[4] = {tr.r0[0], tr.r0[1], tr.r1[0], tr.r1[1]};
+            const uint32_t sw[2] = {tr.s0, tr.s1};
 #pragma unroll
-        for (int w = 0; w < 4; w++) {                 // 32 columns: two steps
-            const uint32_t IDX = index_word(mw[w], T0, T1, K7);
-            const uint32_t r2 = rw[w] >> 2;
+            for (int w = 0; w < 4; w++) {                 // 32 columns: two steps
+                const uint32_t IDX = index_word(mw[w], T0, T1, K7);
+                const uint32_t r2 = rw[w] >> 2;
 #pragma unroll
-            for (int u = 0; u < 2; u++) {
-                const int s = 2 * w + u;
-                uint32_t W[4];
+                for (int u = 0; u < 2; u++) {
+                    const int s = 2 * w + u;
+                    uint32_t W[4];
 #pragma unroll
-                for (int c = 0; c < 2; c++) {         // byte 2u + c of the id word: 4 kept weights
-                    const uint32_t bb = 2 * u + c;
-                    const uint32_t Z = perm(r2, rw[w], bb | (bb << 8) | ((4 + bb) << 16) | ((4 + bb) << 24));
-                    W[2 * c] = perm(TH, TL, and_or_v(Z, K3, K4));
-                    W[2 * c + 1] = perm(TH, TL, and_or_v(Z >> 4, K3, K4));
+                    for (int c = 0; c < 2; c++) {         // byte 2u + c of the id word: 4 kept weights
+                        const uint32_t bb = 2 * u + c;
+                        const uint32_t Z = perm(r2, rw[w], bb | (bb << 8) | ((4 + bb) << 16) | ((4 + bb) << 24));
+                        W[2 * c] = perm(TH, TL, and_or_v(Z, K3, K4));
+                        W[2 * c + 1] = perm(TH, TL, and_or_v(Z >> 4, K3, K4));
+                    }
+                    const uint32_t sbi = (uint32_t)(s & 3);   // byte of the half's sign word
+                    const uint32_t X = perm(sw[w >> 1], sw[w >> 1], 0x000C000Cu | (sbi << 8) | (sbi << 24));
+#pragma unroll
+                    for (int q = 0; q < 4; q++) W[q] = and_or_v(pk_shl(X, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
+                    const half8_t a = as_half8(W);
+                    if (u == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(a, xr[s], acc, (int)IDX, 0, 0);
+                    else acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(a, xr[s], acc, (int)IDX, 0, 1);
                 }
-                const uint32_t sbi = (uint32_t)(s & 3);   // byte of the half's sign word
-                const uint32_t X = perm(sw[w >> 1], sw[w >> 1], 0x000C000Cu | (sbi << 8) | (sbi << 24));
+            }
+        } else {
 #pragma unroll
-                for (int q = 0; q < 4; q++) W[q] = and_or_v(pk_shl(X, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
-                const half8_t a = as_half8(W);
-                if (u == 0) acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(a, xr[s], acc, (int)IDX, 0, 0);
-                else acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(a, xr[s], acc, (int)IDX, 0, 1);
+            for (int h = 0; h < 2; h++) {
+                HalfData<N8> d;
+                half_of(tr, h, d);
+                constexpr int D = 4;                                  // table reads run D groups ahead
+                uint4 gl[D];
+#pragma unroll
+                for (int t = 0; t < D; t++) gl[t] = lut_fetch<N8>(d, t, lut, lane & 7);
+#pragma unroll
+                for (int t = 0; t < 8; t++) {
+                    const uint4 cur = gl[t % D];
+                    if (t + D < 8) gl[t % D] = lut_fetch<N8>(d, t + D, lut, lane & 7);
+                    uint32_t o[4];
+                    expand8<N8>(d, TL, TH, t, cur, K3, K4, KS, o);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(o), xd[8 * h + t], acc, 0, 0, 0);
+                }
             }
         }
         if (HAS_RES) {
@@ -345,8 +486,8 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         for (int h = 0; h < 2; h++) {
             const int nc = h == 0 ? nch0 : nch1;
             if (nc <= 2) continue;
-            HalfData<4> d;
-            load_half<4>(p, (int64_t)tile_of(rt), lane_offsets<4>(lane, h), h, d);
+            HalfData<N8> d;
+            load_half<N8>(p, (int64_t)tile_of(rt), lane_offsets<N8>(lane, h), h, d);
             const uint32_t ar2 = d.ar | (d.ar << 16);
             for (int c = 2; c < nc; c++) {
                 const uint32_t* rec = p.sal_tab + (((int64_t)q * 2 + h) * p.sal_chunks + c) * 12;
@@ -457,13 +598,13 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
     }
 }
 
-template <bool HAS_RES>
+template <int MODE, bool HAS_RES>
 hipError_t launch24(const TiledPlanes& p, const __half* x, int B, void* y, int y_fp32, int R, int SPS, int PHT, int wreg, int area,
                     dim3 grid, float* ws_part, uint32_t* ws_count, hipStream_t st) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv24_kernel<HAS_RES>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS24);
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv24_kernel<MODE, HAS_RES>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS24 - (MODE == 2 ? 0 : 32768));
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((gemv24_kernel<HAS_RES>), grid, dim3(64 * SPS), (size_t)SPS * wreg, st, p, x, B, y, y_fp32, R, SPS, PHT,
+    hipLaunchKernelGGL((gemv24_kernel<MODE, HAS_RES>), grid, dim3(64 * SPS), (size_t)SPS * wreg, st, p, x, B, y, y_fp32, R, SPS, PHT,
                        wreg, area, ws_part, ws_count);
     return hipGetLastError();
 }
@@ -476,48 +617,40 @@ int64_t round_up256(int64_t v) { return (v + 255) / 256 * 256; }
 // is not 2:4 or a staging area would not fit, so that the caller can fall back to the general kernel.
 extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
                                 int64_t workspace_bytes, int max_splits, void* stream, int* hip_err) {
-    if (L->cfg.M != 4 || L->cfg.N != 2 || B < 1 || B > 16) return STB_EUNSUPPORTED;
-    if (L->mask_bytes >= (1ll << 31) || L->res_bytes >= (1ll << 31)) return STB_EUNSUPPORTED;   // 32-bit offsets inside a plane
+    if (B < 1 || B > 16 || (8 * L->cfg.N) % L->cfg.M != 0) return STB_EUNSUPPORTED;
+    const int n8 = 8 * L->cfg.N / L->cfg.M;
+    const int mode = L->cfg.M == 4 && L->cfg.N == 2 ? 2 : n8;      // 2: sparse instruction; 4, 6: dense with the scatter table
+    if (mode != 2 && mode != 4 && mode != 6) return STB_EUNSUPPORTED;
+    if (L->region_bytes >= (1ll << 31) || L->res_bytes >= (1ll << 31)) return STB_EUNSUPPORTED;   // 32-bit offsets inside a plane
     const TiledPlanes p = make_tiled(L);
+    const int64_t lds_max = LDS24 - (mode == 2 ? 0 : 32768);
     // Column splits of SPS <= 8 superblocks (one wavefront each); a workgroup owns R row tiles.  Among the split
-    // counts that fit, take the one with the lowest estimated time: R tiles for each of the ceil(SPS / 4)
-    // wavefronts of a SIMD, times the rounds the grid needs on 256 compute units, plus the cost of adding the
-    // splits up; ties go to the fewest splits.
-    int best_S = 0, best_R = 0, best_sps = 0;
+    // counts whose LDS fits, take the one with the lowest estimated time: R tiles for each of the ceil(SPS / 4)
+    // wavefronts of a SIMD (measured: ~0.75 us per (row tile, superblock) product on the sparse instruction, ~1 us
+    // on the dense one), times the rounds the grid needs on 256 compute units, plus ~0.09 us per split and batch row
+    // for adding the splits up through the workspace; ties go to the fewest splits.
+    // LDS of one wavefront: the larger of (B rows of x and one of zeros, 1040 bytes each) and (PHT partial tiles),
+    // then its 16 records (two per half block).
+    static const int force_S = getenv("STB_GEMV24_S") ? atoi(getenv("STB_GEMV24_S")) : 0;      // experiments
+    const int xbytes = (B < 16 ? B + 1 : 16) * 1040;
+    int S = 0, R = 0, SPS = 0, wreg = 0, area = 0;
     int64_t best_cost = 0;
-    const int s_min = (p.nsb + 7) / 8;
-    for (int S = s_min; S <= max_splits && S <= p.nsb; S++) {
-        const int sps = (p.nsb + S - 1) / S;
-        if (sps > 8 || (S - 1) * sps >= p.nsb) continue;           // a split must own at least one superblock
-        const int groups = 256 / S > 0 ? 256 / S : 1;
-        const int R = (p.nrt + groups - 1) / groups;
-        const int G = (p.nrt + R - 1) / R;
-        // measured: ~0.75 us per (row tile, superblock) product of a SIMD; the reduction over column splits through
-        // the workspace costs ~0.09 us per split and batch row
-        const int64_t cost = (int64_t)750 * R * ((sps + 3) / 4) * ((G * S + 255) / 256) + (S > 1 ? (int64_t)90 * S * B : 0);
-        if (best_S == 0 || cost < best_cost) { best_cost = cost; best_S = S; best_R = R; best_sps = sps; }
+    for (int s = (p.nsb + 7) / 8; s <= max_splits && s <= p.nsb; s++) {
+        const int sps = (p.nsb + s - 1) / s;
+        if (sps > 8 || (s - 1) * sps >= p.nsb) continue;           // a split must own at least one superblock
+        if (force_S && s != force_S) continue;
+        const int groups = 256 / s > 0 ? 256 / s : 1;
+        const int r = (p.nrt + groups - 1) / groups, g = (p.nrt + r - 1) / r;
+        const int pht = r < PHASE24 ? r : PHASE24;
+        const int ar = xbytes > pht * 1024 ? xbytes : pht * 1024;
+        if ((int64_t)sps * (ar + 768) > lds_max) continue;
+        const int64_t cost = (int64_t)(mode == 2 ? 750 : 1000) * r * ((sps + 3) / 4) * ((g * s + 255) / 256) + (s > 1 ? (int64_t)90 * s * B : 0);
+        if (S == 0 || cost < best_cost) { best_cost = cost; S = s; R = r; SPS = sps; area = ar; wreg = ar + 768; }
     }
-    if (const char* f = getenv("STB_GEMV24_S")) {                  // experiments: force the number of splits
-        const int S = atoi(f);
-        if (S >= s_min && S <= max_splits && S <= p.nsb) {
-            const int sps = (p.nsb + S - 1) / S;
-            if (sps <= 8 && (S - 1) * sps < p.nsb) {
-                const int groups = 256 / S > 0 ? 256 / S : 1;
-                best_S = S; best_sps = sps; best_R = (p.nrt + groups - 1) / groups;
-            }
-        }
-    }
-    if (best_S == 0) return STB_EUNSUPPORTED;
-    const int S = best_S, R = best_R, SPS = best_sps;
+    if (S == 0) return STB_EUNSUPPORTED;
     const int G = (p.nrt + R - 1) / R;
     const int PHT = R < PHASE24 ? R : PHASE24;
     const bool res = p.res_words > 0;
-    // LDS of one wavefront: the larger of (B rows of x and one of zeros, 1040 bytes each) and (PHT partial tiles),
-    // then its 16 records (two per half block)
-    const int xbytes = (B < 16 ? B + 1 : 16) * 1040, pbytes = PHT * 1024;
-    const int area = xbytes > pbytes ? xbytes : pbytes;
-    const int wreg = area + 768;
-    if ((int64_t)SPS * wreg > LDS24) return STB_EUNSUPPORTED;
     if (S > 1) {
         if (!workspace) return STB_ENULL;
         if (workspace_bytes < round_up256(4 * (int64_t)p.nrt) + (int64_t)S * 16 * 16 * p.nrt * 4) return STB_EINVAL;
@@ -528,8 +661,13 @@ extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, voi
     const __half* xh = (const __half*)x;
     const dim3 grid(G, S);
     const hipStream_t st = (hipStream_t)stream;
-    const hipError_t e = res ? launch24<true>(p, xh, B, y, y_fp32, R, SPS, PHT, wreg, area, grid, part, cnt, st)
-                             : launch24<false>(p, xh, B, y, y_fp32, R, SPS, PHT, wreg, area, grid, part, cnt, st);
+    hipError_t e;
+#define STB24_GO(MODE) (res ? launch24<MODE, true>(p, xh, B, y, y_fp32, R, SPS, PHT, wreg, area, grid, part, cnt, st) \
+                            : launch24<MODE, false>(p, xh, B, y, y_fp32, R, SPS, PHT, wreg, area, grid, part, cnt, st))
+    if (mode == 2) e = STB24_GO(2);
+    else if (mode == 4) e = STB24_GO(4);
+    else e = STB24_GO(6);
+#undef STB24_GO
     *hip_err = (int)e;
     return e == hipSuccess ? STB_OK : STB_EHIP;
 }

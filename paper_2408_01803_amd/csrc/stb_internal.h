@@ -18,9 +18,9 @@ int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_f
                    int64_t workspace_bytes, void* stream, int* hip_err);
 // Scratch bytes of the tiled decode kernels for L's shape.
 int64_t stb_tiled_gemv_workspace(int n_row_tiles, int n_super);
-// Decode kernel for 2:4 layouts on the sparse matrix-core instruction (stb_gemv24.hip).  Returns STB_EUNSUPPORTED,
-// without launching anything, when the layout is not 2:4 or its staging areas would not fit: the caller then runs
-// the general kernel.  max_splits bounds the number of column splits (the workspace is sized for that many).
+// Decode kernel with one fat wavefront per superblock (stb_gemv24.hip): 2:4 layouts on the sparse matrix-core
+// instruction, 4:8 / 6:8 (and 3:4) on the dense one.  Returns STB_EUNSUPPORTED, without launching anything, when
+// its staging areas would not fit: the caller then runs the older kernel.  max_splits bounds the number of column splits (the workspace is sized for that many).
 int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
                      int64_t workspace_bytes, int max_splits, void* stream, int* hip_err);
 // Prefill kernel for the tiled order (stb_gemm.hip) and its scratch size for T tokens.
