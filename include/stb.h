@@ -190,6 +190,8 @@ int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream);
  * k > 4096; for smaller k the launcher may still split columns to balance the grid).  The
  * counters (its first 4 * ceil(n / 16) bytes) must be zero before the first call that uses the buffer; every
  * call leaves them zero.  Calls that share a workspace must not overlap in time.
+ * Environment: STB_GEMV_KERNEL=thin (read at every call) makes the tiled kind use its older kernel with thin
+ * wavefronts, which otherwise only runs when the LDS areas of the default kernel do not fit; for tests.
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
 int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32,
              void* workspace, int64_t workspace_bytes, void* stream);

@@ -75,18 +75,18 @@ __global__ __launch_bounds__(64) void dequant_tiled_kernel(TiledPlanes p, float*
 }
 
 // ------------------------------------------------------------------------------------------------
-// Decode GEMV (App. C: the memory-bound regime).
+// Decode GEMV (App. C: the memory-bound regime), the kernel with thin wavefronts.  stb_gemv uses it when the LDS
+// areas of the fat-wavefront kernel (stb_gemv24.hip) do not fit, and the tests run it on every tiled case.
 //
-// Workgroup (gr, ks) of the grid owns the 16-row tiles [gr*R, gr*R + R) and the eight superblocks
-// 8*ks .. 8*ks + 7; wavefront w works on half (w & 1) of superblock 8*ks + (w >> 1).  Everything that depends on
-// the columns only -- the 8 B operands holding x for the wavefront's 4 x 64 columns, the salient-column
-// selectors and the gathered x of the salient columns -- is loaded once and stays in registers while the
-// wavefront streams its R half tiles of packed weights, two in flight.  Partial products go to LDS
-// ([wavefront][tile][256] fp32) and are summed in a fixed order at the end.  With more than eight superblocks
-// (k > 4096) the grid has several column splits: each writes its partial sums to the workspace, takes a
-// ticket, and the last split to finish a row group adds the partial sums in split order and writes y.
-// A wavefront issues one vector instruction every ~5 cycles whatever else runs on its SIMD, so the kernel is
-// sized for four wavefronts per SIMD (at most 128 VGPRs).
+// Workgroup (gr, ks) of the grid owns SPS superblocks of the columns (column split ks) and 16 / (2*SPS) row
+// streams of R 16-row tiles; a wavefront works on one half block (64 columns of each of the 4 blocks) of one
+// superblock of one row stream.  Everything that depends on the columns only -- the 8 B operands holding x for
+// the wavefront's 4 x 64 columns, the salient-column selectors and the gathered x of the salient columns -- is
+// loaded once (through LDS when it fits) and stays in registers while the wavefront streams its R half tiles of
+// packed weights, three in flight.  Partial products go to LDS ([wavefront][tile][256] fp32) and are summed in a
+// fixed order at the end of every phase.  With several column splits each writes its partial sums to the
+// workspace, takes a ticket, and the last split to finish a row group adds the partial sums in split order and
+// writes y.  Four wavefronts share a SIMD (at most 128 VGPRs each).
 // ------------------------------------------------------------------------------------------------
 struct ResInv {
     ResSel sel;
@@ -522,11 +522,6 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
     }
 }
 
-int env_int(const char* name, int dflt) {
-    const char* v = std::getenv(name);
-    return v && *v ? std::atoi(v) : dflt;
-}
-
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
@@ -576,10 +571,9 @@ static hipError_t launch_gemv_stream(const TiledPlanes& p, const __half* x, int 
                                      dim3 grid, size_t lds, float* ws_part, uint32_t* ws_count, hipStream_t st) {
     // x is staged through LDS when the B rows of the split (SPS * 1024 + 16 bytes each) fit into the area of the
     // partial products
-    static const int allow = env_int("STB_GEMV_STAGED", 1);
     // ... and the res_sign words of the workgroup's RS * R row tiles into their own area
     const int RS = 16 / (2 * SPS);
-    const bool staged = allow && (int64_t)B * (SPS * 1024 + 16) <= (int64_t)lds &&
+    const bool staged = (int64_t)B * (SPS * 1024 + 16) <= (int64_t)lds &&
                         (!HAS_RES || (int64_t)RS * R * p.res_words * 16 <= STB_GEMV_RESW);
     return staged ? launch_gemv_stream3<N8, HAS_RES, true>(p, x, B, y, y_fp32, R, SPS, grid, lds, ws_part, ws_count, st)
                   : launch_gemv_stream3<N8, HAS_RES, false>(p, x, B, y, y_fp32, R, SPS, grid, lds, ws_part, ws_count, st);
@@ -588,17 +582,19 @@ static hipError_t launch_gemv_stream(const TiledPlanes& p, const __half* x, int 
 extern "C" int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
                               int64_t workspace_bytes, void* stream, int* hip_err) {
     if (!stb_tiled_supported(L)) return STB_EUNSUPPORTED;
-    static const int allow24 = env_int("STB_GEMV_24", 1);
-    if (allow24 && B <= 16) {                                       // the kernel with fat wavefronts, if its LDS areas fit
+    // STB_GEMV_KERNEL=thin in the environment (read at every call) sends every launch to the kernel below: the
+    // tests use it, because on ordinary shapes the fat-wavefront kernel takes everything.
+    const char* which = std::getenv("STB_GEMV_KERNEL");
+    const bool thin_only = which && which[0] == 't';
+    if (!thin_only && B <= 16) {                                    // the kernel with fat wavefronts, if its LDS areas fit
         const int rc = stb_tiled_gemv24(L, x, B, y, y_fp32, workspace, workspace_bytes, max_splits(L->n_super), stream, hip_err);
         if (rc != STB_EUNSUPPORTED) return rc;
     }
     const TiledPlanes p = make_tiled(L);
-    static const int wg_target = env_int("STB_GEMV_WGS", 256);     // workgroups the launch aims for: one per compute unit
-    static const int sps_small = env_int("STB_GEMV_SPS_SMALL_B", 8), sps_large = env_int("STB_GEMV_SPS_LARGE_B", 8);
-    // Superblocks per column split: 8 (a whole 4096-column slice per workgroup).  Narrower splits with several
-    // row streams per workgroup are supported by the kernel but measured slower at every batch size so far.
-    const int sps0 = B <= 4 ? sps_small : sps_large;
+    constexpr int wg_target = 256;                                  // workgroups the launch aims for: one per compute unit
+    // Superblocks per column split: at most 8 (a whole 4096-column slice per workgroup).  Narrower splits with
+    // several row streams per workgroup come out of the search below when they balance the grid better.
+    constexpr int sps0 = 8;
     // Among the split counts that fit, take the one with the fewest half tiles per compute unit (R tiles for each
     // wavefront with work, times the rounds the grid needs on 256 units); ties go to the fewest splits.
     int best_S = 0, best_R = 0, best_sps = 0;

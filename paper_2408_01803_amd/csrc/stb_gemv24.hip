@@ -23,8 +23,6 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
-#include <cstdlib>
-
 #include "stb_tiled.hpp"
 
 using namespace stbt;
@@ -631,14 +629,12 @@ extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, voi
     // for adding the splits up through the workspace; ties go to the fewest splits.
     // LDS of one wavefront: the larger of (B rows of x and one of zeros, 1040 bytes each) and (PHT partial tiles),
     // then its 16 records (two per half block).
-    static const int force_S = getenv("STB_GEMV24_S") ? atoi(getenv("STB_GEMV24_S")) : 0;      // experiments
     const int xbytes = (B < 16 ? B + 1 : 16) * 1040;
     int S = 0, R = 0, SPS = 0, wreg = 0, area = 0;
     int64_t best_cost = 0;
     for (int s = (p.nsb + 7) / 8; s <= max_splits && s <= p.nsb; s++) {
         const int sps = (p.nsb + s - 1) / s;
         if (sps > 8 || (s - 1) * sps >= p.nsb) continue;           // a split must own at least one superblock
-        if (force_S && s != force_S) continue;
         const int groups = 256 / s > 0 ? 256 / s : 1;
         const int r = (p.nrt + groups - 1) / groups, g = (p.nrt + r - 1) / r;
         const int pht = r < PHASE24 ? r : PHASE24;

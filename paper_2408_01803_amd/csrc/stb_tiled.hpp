@@ -1,10 +1,10 @@
 // Device-side building blocks shared by the kernels that read the tiled device order (STB_KIND_TILED).
 //
 // A tile is 16 output rows x 4 column blocks (512 columns): lane = 16*g + i owns (row i of the tile, block g of
-// the superblock); its record holds that block's 16 mask bytes, its sign and id bits and its scales.  Two
-// wavefronts share a tile, one per half (64 columns) of every block, so that a wavefront keeps only 32 VGPRs
-// of activations and four wavefronts fit on a SIMD.  A lane expands 8 columns at a time into the A operand
-// (4 VGPRs of fp16) of v_mfma_f32_16x16x32_f16.  Expansion works on whole registers:
+// the superblock); its record holds that block's 16 mask bytes, its sign and id bits and its scales.  mask and
+// id bytes (and sign bytes where they split into whole words) are stored half by half (64 columns), so that a
+// wavefront working on one half of every block reads contiguous bytes.  A lane expands 8 columns at a time into
+// the A operand (4 VGPRs of fp16) of v_mfma_f32_16x16x32_f16.  Expansion works on whole registers:
 //   * ids -> byte selectors -> v_perm_b32 over the block's scale table gives two kept weights per register
 //     in slot order (the order of the sign / id planes),
 //   * sign bits are moved to bit 15 / 31 with one packed 16-bit shift and merged with one and-or,

@@ -77,6 +77,10 @@ SMALL = [
     (80, 512, 4, 8, 0, "x8", 109, 100),
     # more than 4096 columns: two column splits that meet through the workspace
     (40, 4608, 2, 4, 1, "t3", 110),
+    # less than one tile in both directions
+    (5, 128, 2, 4, 0, "x8", 111),
+    (1, 128, 4, 8, 1, "x8", 112),
+    (17, 256, 6, 8, 0, "t3", 113),
 ]
 
 
@@ -126,6 +130,18 @@ def test_gemv_small(small_case, torch_cuda, B, y_fp32):
     S.stb_gemv(c["pm"].dev_layout, xd, B, yd, y_fp32, c["pm"].workspace)
     torch.cuda.synchronize()
     _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemv B={B}")
+    if c["tiled"]:
+        # the tiled order has two decode kernels; ordinary shapes all go to the one with fat wavefronts, so the
+        # other one is asked for by name (the library reads the variable at every call)
+        yd.fill_(float("nan"))
+        os.environ["STB_GEMV_KERNEL"] = "thin"
+        try:
+            _say(f"[step] stb_gemv B={B} fp32={y_fp32}, thin-wavefront kernel")
+            S.stb_gemv(c["pm"].dev_layout, xd, B, yd, y_fp32, c["pm"].workspace)
+            torch.cuda.synchronize()
+        finally:
+            del os.environ["STB_GEMV_KERNEL"]
+        _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemv B={B} (thin-wavefront kernel)")
 
 
 @pytest.mark.parametrize("T", [1, 63, 64, 200, 333])
