@@ -89,6 +89,17 @@ __device__ inline void wait24(Tile24& d) {
                    "+v"(d.e00), "+v"(d.e01), "+v"(d.e10), "+v"(d.e11)
                  : "n"(K));
 }
+// The same in two steps: the packed planes (the older loads of a tile), then the res_sign words.
+template <int K>
+__device__ inline void wait24_main(Tile24& d) {
+    asm volatile("s_waitcnt vmcnt(%8)"
+                 : "+v"(d.m0), "+v"(d.m1), "+v"(d.s0), "+v"(d.s1), "+v"(d.r0), "+v"(d.r1), "+v"(d.sc), "+v"(d.ar)
+                 : "n"(K));
+}
+template <int K, typename T>
+__device__ inline void wait24_res(T& d) {
+    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(d.e00), "+v"(d.e01), "+v"(d.e10), "+v"(d.e11) : "n"(K));
+}
 
 // The same for 6:8 layers: 12 bytes of sign bits per block (not cut in halves), 12 bytes of ids per half block.
 struct Tile68 {
@@ -129,6 +140,12 @@ __device__ inline void wait24(Tile68& d) {
     asm volatile("s_waitcnt vmcnt(%11)"
                  : "+v"(d.m0), "+v"(d.m1), "+v"(d.s), "+v"(d.r0), "+v"(d.r1), "+v"(d.sc), "+v"(d.ar),
                    "+v"(d.e00), "+v"(d.e01), "+v"(d.e10), "+v"(d.e11)
+                 : "n"(K));
+}
+template <int K>
+__device__ inline void wait24_main(Tile68& d) {
+    asm volatile("s_waitcnt vmcnt(%7)"
+                 : "+v"(d.m0), "+v"(d.m1), "+v"(d.s), "+v"(d.r0), "+v"(d.r1), "+v"(d.sc), "+v"(d.ar)
                  : "n"(K));
 }
 
@@ -309,7 +326,25 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
             }
 #undef STB24_STORE
             if (B < 16) *reinterpret_cast<uint4_t*>(dst + B * XROW) = zero;     // row B: zeros, read by the lanes without a batch row
-            if (HAS_RES && lane < 48) *reinterpret_cast<uint4_t*>(&recs[4 * lane]) = sr;     // [block][half][record 0 / 1] x 12
+            if (HAS_RES) {
+                // the 16 bytes after each row's 1024: zeros, the target of the table entries that hold no column
+                if (lane <= B && lane < 16) *reinterpret_cast<uint4_t*>(wreg + lane * XROW + 1024) = zero;
+                if (lane < 48) {
+                    if (lane % 3 == 2) {
+                        // the piece with the 8 column positions (inside the block; 0xFFFF = no entry) becomes byte
+                        // offsets inside a staged row: 2 * (128 * block + position), 1024 for no entry
+                        // (two 16-bit fields per word, worked on in place: no field carries into the other)
+                        const uint32_t g2 = (uint32_t)(lane / 12) * (128u * 0x00010001u);
+#pragma unroll
+                        for (int w = 0; w < 4; w++) {
+                            const uint32_t none = sr[w] & 0x80008000u;                      // bit 15: no entry
+                            const uint32_t full = __umul24(none >> 15, 0xFFFFu);            // 0xFFFF in such a field
+                            sr[w] = ((((sr[w] & 0x007F007Fu) + g2) << 1) & ~full) | (none >> 5);
+                        }
+                    }
+                    *reinterpret_cast<uint4_t*>(&recs[4 * lane]) = sr;     // [block][half][record 0 / 1] x 12
+                }
+            }
         }
         TRACE(2);
     }
@@ -335,7 +370,16 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
             for (int t = 0; t < 16; t++) xd[t] = __builtin_bit_cast(half8_t, *reinterpret_cast<const uint4_t*>(xrow + 16 * t));
         }
         if (HAS_RES) {
-            const char* xblk = wreg + (i < B ? i : B) * XROW + g * 256;     // block g of the superblock
+            const char* xrow0 = wreg + (i < B ? i : B) * XROW;              // the lane's staged row of x (or the zeros)
+            auto gather = [&](const uint4_t& q, uint32_t out[4]) {          // x at the 8 byte offsets of a record
+                const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int v = 0; v < 4; v++) {
+                    const ushort2_t pr = {*reinterpret_cast<const unsigned short*>(xrow0 + (qw[v] & 0xFFFFu)),
+                                          *reinterpret_cast<const unsigned short*>(xrow0 + (qw[v] >> 16))};
+                    out[v] = __builtin_bit_cast(uint32_t, pr);
+                }
+            };
 #pragma unroll
             for (int h = 0; h < 2; h++) {
                 const uint32_t* rec = &recs[(g * 2 + h) * 24];
@@ -351,29 +395,12 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
                 const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
                 inv[h].o0 = (uint32_t)(wa * 16 + i) * 4u;
                 inv[h].o1 = (uint32_t)(wb * 16 + i) * 4u;
-                const uint32_t pw[4] = {rp.x, rp.y, rp.z, rp.w};
-                uint32_t hx[8];
-#pragma unroll
-                for (int e = 0; e < 8; e++) {
-                    const uint32_t pos = (pw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-                    hx[e] = *reinterpret_cast<const unsigned short*>(xblk + 2 * (pos & 127u));
-                    if (pos >= 128u) hx[e] = 0u;               // no such entry
-                }
-#pragma unroll
-                for (int v = 0; v < 4; v++) inv[h].xs[v] = hx[2 * v] | (hx[2 * v + 1] << 16);
+                gather(rp, inv[h].xs);
                 if (nc > 1) {                        // the second record of the half block
                     const uint4_t rc = *reinterpret_cast<const uint4_t*>(rec + 12);
                     const uint4_t rq = *reinterpret_cast<const uint4_t*>(rec + 20);
                     sel2[h].sel0 = rc.x; sel2[h].sel1 = rc.y; sel2[h].bit0 = rc.z; sel2[h].bit1 = rc.w;
-                    const uint32_t qw[4] = {rq.x, rq.y, rq.z, rq.w};
-#pragma unroll
-                    for (int e = 0; e < 8; e++) {
-                        const uint32_t pos = (qw[e >> 1] >> (16 * (e & 1))) & 0xFFFFu;
-                        hx[e] = *reinterpret_cast<const unsigned short*>(xblk + 2 * (pos & 127u));
-                        if (pos >= 128u) hx[e] = 0u;
-                    }
-#pragma unroll
-                    for (int v = 0; v < 4; v++) xs2[h][v] = hx[2 * v] | (hx[2 * v + 1] << 16);
+                    gather(rq, xs2[h]);
                 }
             }
         }
@@ -402,7 +429,7 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
 
     // One (row tile, superblock): the steps over the block's columns (sparse: 8 of 16 columns; dense: 16 of 8), then
     // the residual term of the two halves.
-    auto product = [&](const Tile& tr, int rt, int slot) {
+    auto product = [&](Tile& tr, int rt, int slot) {
         const uint32_t TL = perm(tr.sc[1], tr.sc[0], 0x06040200u), TH = perm(tr.sc[1], tr.sc[0], 0x07050301u);
         const uint32_t mw[4] = {tr.m0[0], tr.m0[1], tr.m1[0], tr.m1[1]};
         float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -453,6 +480,7 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
             }
         }
         if (HAS_RES) {
+            wait24_res<2 * L>(tr);                    // the tile's res_sign words: younger than its packed planes
             const uint32_t ar1 = tr.ar & 0xFFFFu, ar2 = ar1 | (ar1 << 16);
 #pragma unroll
             for (int h = 0; h < 2; h++) {
@@ -522,17 +550,17 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         const int ph1 = ph0 + PHT < r1 ? ph0 + PHT : r1;
         if (active) {
             for (int rt = ph0; rt < ph1; rt += 3) {
-                wait24<2 * L>(t0);
+                wait24_main<2 * L + (HAS_RES ? LRES24 : 0)>(t0);
                 TRACE(8 + (rt - r0 < 5 ? rt - r0 : 5));
                 product(t0, rt, rt - ph0);
                 TRACE(14 + (rt - r0 < 5 ? rt - r0 : 5));
                 fetch_tile(t0, clamp(rt + 3));
-                wait24<2 * L>(t1);
+                wait24_main<2 * L + (HAS_RES ? LRES24 : 0)>(t1);
                 TRACE(8 + (rt + 1 - r0 < 5 ? rt + 1 - r0 : 5));
                 if (rt + 1 < ph1) product(t1, rt + 1, rt + 1 - ph0);
                 TRACE(14 + (rt + 1 - r0 < 5 ? rt + 1 - r0 : 5));
                 fetch_tile(t1, clamp(rt + 4));
-                wait24<2 * L>(t2);
+                wait24_main<2 * L + (HAS_RES ? LRES24 : 0)>(t2);
                 TRACE(8 + (rt + 2 - r0 < 5 ? rt + 2 - r0 : 5));
                 if (rt + 2 < ph1) product(t2, rt + 2, rt + 2 - ph0);
                 TRACE(14 + (rt + 2 - r0 < 5 ? rt + 2 - r0 : 5));
