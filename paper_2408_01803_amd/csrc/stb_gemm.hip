@@ -19,8 +19,14 @@ namespace {
 
 constexpr int GM_TOK = 128;           // tokens per workgroup
 constexpr int GM_ROWT = 16;           // 16-row tiles per workgroup (four per wavefront)
-constexpr int GM_XROW = 136;          // halves per token row of the LDS window: 4 x 32 columns + 8 of padding
-constexpr int GM_XROW1 = 168;         // second buffer: + 4 x 8 gathered salient columns (residual contraction)
+// LDS of the main kernel (dynamic, carved by hand so that the positions are fixed):
+//   [0, 64 KB)    two X windows: 128 token rows x 256 bytes (4 blocks x 32 columns); the 16-byte piece p of row r
+//                 sits at position p ^ (r % 16), so the 16 lanes that read one piece of 16 consecutive rows (a B
+//                 operand) hit 16 different positions and a wavefront's global->LDS load fills 4 whole rows
+//   [64, 80 KB)   gathered salient columns, by parity of the pass: 128 rows x 64 bytes, piece g of row r at
+//                 position g ^ ((r / 4) % 4)
+//   [80, 112 KB)  the scatter table
+constexpr int GM_XW = 0, GM_XWSZ = 32768, GM_XG = 65536, GM_XGSZ = 8192, GM_LUT = 81920, GM_LDS = 81920 + 32768;
 
 // Workspace: xsal[T][E] fp16, E = nsb * 2 * cfix * 32; entry ((sb*2 + half)*cfix + c)*32 + g*8 + e holds X at the
 // e-th salient column of record c of (block 4*sb + g, half), 0 where the record has no such entry.
@@ -47,17 +53,26 @@ __global__ __launch_bounds__(256) void gemm_gather_kernel(TiledPlanes p, const _
     *reinterpret_cast<uint4*>(xsal + ((int64_t)tok * per_tok + piece) * 8) = make_uint4(out[0], out[1], out[2], out[3]);
 }
 
+template <int V> struct IntC { static constexpr int value = V; };
+
+// One wavefront-wide global -> LDS load of 16 bytes per lane: lane l's bytes land at LDS address m0 + 16 * l.
+// No register is written: the data is in LDS once vmcnt has counted the load down.
+__device__ inline void load_to_lds(uint32_t lds_addr, uint32_t voff, const void* base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
+}
+
 template <int N8, bool HAS_RES>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                           void* __restrict__ Y, int y_fp32,
                                                           const __half* __restrict__ xsal, int cfix) {
-    __shared__ ScatterLds lut;
-    __shared__ __attribute__((aligned(16))) _Float16 xs0[GM_TOK * GM_XROW];
-    __shared__ __attribute__((aligned(16))) _Float16 xs1[GM_TOK * GM_XROW1];
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    ScatterLds& lut = *reinterpret_cast<ScatterLds*>(lds + GM_LUT);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;     // LDS address of lds[0]
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int i = lane & 15, g = lane >> 4;
     const int t0 = blockIdx.x * GM_TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;                // first row tile of this wavefront
+    const int nsh = p.nsb * 2;                                      // (superblock, half) pairs
     build_luts<N8>(&lut);
 
     float4_t acc[4][8];
@@ -66,104 +81,91 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
 #pragma unroll
         for (int tt = 0; tt < 8; tt++) acc[r][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // ---- staging of the X window: 2048 pieces of 16 bytes, 8 per thread ----
-    // piece c: token c / 16, block (c / 4) % 4, 8 columns (c % 4) of the window
-    auto x_gload = [&](int sb, int half, int win, uint4 (&st)[8]) {
+    // Every global load of the main loop is an asm statement, and every use sits behind a vmcnt wait written by
+    // hand (for loads into registers the wait names them, the rules of the fetch helpers in stb_tiled.hpp): the
+    // loads go out where they are written, K steps ahead of their use, and the compiler neither sinks them down to
+    // it nor waits for them on its own.
+
+    // ---- X window -> LDS: 32 wavefront loads of 4 token rows each, 8 per wavefront.  Load u of wavefront w covers
+    //      rows 4 * (8w + u) ..; lane l = row l / 16 of them, position l % 16, i.e. piece (l % 16) ^ (row % 16):
+    //      block piece / 4, 8 columns (piece % 4).  Tokens past T are clamped to the last token (their outputs are
+    //      never stored); a piece past column k is clamped to the row's last 16 bytes (it meets zero weights). ----
+    const uint32_t tok_last = (uint32_t)(T - 1 - t0), k2 = (uint32_t)p.k * 2u;
+    uint32_t xrow[8], xpc[4];
+#pragma unroll
+    for (int u = 0; u < 8; u++) {
+        const uint32_t row = (uint32_t)(4 * (8 * wave + u) + g);
+        xrow[u] = (row < tok_last ? row : tok_last) * k2;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        const uint32_t pc = (uint32_t)i ^ (uint32_t)(4 * j + g);   // rows 4 * (8w + u) + g: row % 16 = 4 * (u % 4) + g
+        xpc[j] = (pc >> 2) * 256u + (pc & 3u) * 16u;
+    }
+    const __half* const Xt = X + (int64_t)t0 * p.k;
+    auto x_gload = [&](int sh, int win, int buf) {
+        const uint32_t wcol = (uint32_t)((sh >> 1) * 1024 + (sh & 1) * 128 + win * 64);      // bytes inside a token row
+        const uint32_t dst = lds0 + GM_XW + buf * GM_XWSZ + wave * 8192;
 #pragma unroll
         for (int u = 0; u < 8; u++) {
-            const int c = tid + 256 * u;
-            const int tok = t0 + (c >> 4), gb = (c >> 2) & 3, cc = c & 3;
-            const int q = 4 * sb + gb;
-            st[u] = make_uint4(0u, 0u, 0u, 0u);
-            if (tok < T && q < p.nb)
-                st[u] = *reinterpret_cast<const uint4*>(X + (int64_t)tok * p.k + (int64_t)q * 128 + 64 * half + 32 * win + 8 * cc);
+            const uint32_t c = xpc[u & 3] + wcol;
+            load_to_lds(dst + u * 1024, xrow[u] + (c < k2 - 16u ? c : k2 - 16u), Xt);
         }
     };
-    auto x_lstore = [&](int buf, const uint4 (&st)[8]) {
-        _Float16* dst = buf ? xs1 : xs0;
-        const int stride = buf ? GM_XROW1 : GM_XROW;
-#pragma unroll
-        for (int u = 0; u < 8; u++) {
-            const int c = tid + 256 * u;
-            *reinterpret_cast<uint4*>(&dst[(c >> 4) * stride + ((c >> 2) & 3) * 32 + (c & 3) * 8]) = st[u];
-        }
-    };
-    // the gathered salient columns of this (superblock, half), record c: 128 tokens x 4 pieces of 16 bytes
+    // the gathered salient columns of (superblock, half) sh, record c: 8 wavefront loads of 16 token rows, 2 per
+    // wavefront; lane l = row l / 4 of them, position l % 4 = piece (l % 4) ^ ((row / 4) % 4)
     const int64_t E = (int64_t)p.nsb * 2 * cfix * 32;               // halves per token in xsal
-    auto r_gload = [&](int sh, int c, uint4 (&sr)[2]) {
+    const __half* const xsal_t = xsal + (int64_t)t0 * E;
+    uint32_t grow[2];
 #pragma unroll
-        for (int u = 0; u < 2; u++) {
-            const int pc = tid + 256 * u;
-            const int tok = t0 + (pc >> 2), gb = pc & 3;
-            sr[u] = make_uint4(0u, 0u, 0u, 0u);
-            if (HAS_RES && tok < T) sr[u] = *reinterpret_cast<const uint4*>(xsal + (int64_t)tok * E + ((int64_t)sh * cfix + c) * 32 + gb * 8);
+    for (int u = 0; u < 2; u++) {
+        const uint32_t row = (uint32_t)(16 * (2 * wave + u) + (lane >> 2));
+        grow[u] = (row < tok_last ? row : tok_last) * (uint32_t)E * 2u + (((uint32_t)lane & 3u) ^ (((uint32_t)lane >> 4) & 3u)) * 16u;
+    }
+    auto r_gload = [&](int sh, int c, int par) {
+        if (HAS_RES) {
+#pragma unroll
+            for (int u = 0; u < 2; u++)
+                load_to_lds(lds0 + GM_XG + par * GM_XGSZ + (2 * wave + u) * 1024, grow[u] + (uint32_t)(sh * cfix + c) * 64u, xsal_t);
         }
     };
-    auto r_lstore = [&](const uint4 (&sr)[2]) {
-#pragma unroll
-        for (int u = 0; u < 2; u++) {
-            const int pc = tid + 256 * u;
-            *reinterpret_cast<uint4*>(&xs1[(pc >> 2) * GM_XROW1 + 128 + (pc & 3) * 8]) = sr[u];
-        }
-    };
-    // four K steps on one window: groups 4*win .. 4*win + 3 of every lane's half block.  The B operands and the
-    // expanded A operands of step s + 1 are produced while the 32 MFMAs of step s run.
-    auto bload = [&](int buf, int tq, uint4 (&b)[8]) {
-        const _Float16* src = buf ? xs1 : xs0;
-        const int stride = buf ? GM_XROW1 : GM_XROW;
-#pragma unroll
-        for (int tt = 0; tt < 8; tt++)
-            b[tt] = *reinterpret_cast<const uint4*>(&src[(16 * tt + i) * stride + g * 32 + tq * 8]);
-    };
-    auto bload_res = [&](uint4 (&b)[8]) {
-#pragma unroll
-        for (int tt = 0; tt < 8; tt++)
-            b[tt] = *reinterpret_cast<const uint4*>(&xs1[(16 * tt + i) * GM_XROW1 + 128 + g * 8]);
-    };
-    auto expand4 = [&](const HalfData<N8> (&hd)[4], const uint32_t (&TL)[4], const uint32_t (&TH)[4], int t, uint32_t (&a)[4][4]) {
-#pragma unroll
-        for (int r = 0; r < 4; r++) expand_group<N8>(hd[r], TL[r], TH[r], t, lut_fetch<N8>(hd[r], t, &lut, lane & 7), a[r]);
-    };
-    auto mfma32 = [&](const uint32_t (&a)[4][4], const uint4 (&b)[8]) {
-#pragma unroll
-        for (int tt = 0; tt < 8; tt++) {
-            const half8_t bv = __builtin_bit_cast(half8_t, b[tt]);
-#pragma unroll
-            for (int r = 0; r < 4; r++)
-                acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(a[r]), bv, acc[r][tt], 0, 0, 0);
-        }
-    };
-    auto window = [&](const HalfData<N8> (&hd)[4], const uint32_t (&TL)[4], const uint32_t (&TH)[4], int win, int buf) {
-        uint4 b0[8], b1[8];
-        uint32_t a0[4][4], a1[4][4];
-        bload(buf, 0, b0);
-        expand4(hd, TL, TH, 4 * win, a0);
-        bload(buf, 1, b1);
-        expand4(hd, TL, TH, 4 * win + 1, a1);
-        mfma32(a0, b0);
-        bload(buf, 2, b0);
-        expand4(hd, TL, TH, 4 * win + 2, a0);
-        mfma32(a1, b1);
-        bload(buf, 3, b1);
-        expand4(hd, TL, TH, 4 * win + 3, a1);
-        mfma32(a0, b0);
-        mfma32(a1, b1);
-    };
-    auto load_hd = [&](int sb, int half, HalfData<N8> (&hd)[4]) {
-        const LaneOffsets lo = lane_offsets<N8>(lane, half);
+    auto load_hd = [&](int sh, HalfData<N8> (&hd)[4]) {
+        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
 #pragma unroll
         for (int r = 0; r < 4; r++) {
             const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
-            load_half<N8>(p, (int64_t)rt * p.nsb + sb, lo, half, hd[r]);
+            load_half<N8>(p, (int64_t)rt * p.nsb + (sh >> 1), lo, sh & 1, hd[r]);
         }
     };
-
-    uint4 st[8];
-    x_gload(0, 0, 0, st);
-    x_lstore(0, st);
-    __syncthreads();
-
-    const int nsh = p.nsb * 2;                                      // (superblock, half) pairs
+    auto load_rec = [&](int sh, uint4& ra, uint2& rb) {
+        if (HAS_RES) {
+            const uint32_t* rec0 = p.sal_tab + (((int64_t)(4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 12;
+            ra = *reinterpret_cast<const uint4*>(rec0);
+            rb = *reinterpret_cast<const uint2*>(rec0 + 4);
+        }
+    };
+    // the same as asm loads (2 loads), and the half records of the four row tiles (4 x 5 loads)
+    auto fetch_rec = [&](int sh, uint4_t& ra, uint2_t& rb) {
+        if (HAS_RES) {
+            const uint32_t off = (uint32_t)(((4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 48u;
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(ra) : "v"(off), "s"(p.sal_tab));
+            asm volatile("global_load_dwordx2 %0, %1, %2 offset:16" : "=v"(rb) : "v"(off), "s"(p.sal_tab));
+        }
+    };
+    auto fetch_hd = [&](int sh, TileRegs<N8> (&tn)[4]) {
+        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
+            fetch_main<N8>(tn[r], p, (int64_t)__builtin_amdgcn_readfirstlane(rt * p.nsb + (sh >> 1)), lo);
+        }
+    };
+    uint32_t rsrow[4];                                              // byte offset of the lane's row in res_sign, per row tile
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
+        rsrow[r] = (uint32_t)(rt * p.res_words * 16 + i) * 4u;
+    }
     auto load_res_words = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) {
         const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
         const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
@@ -174,73 +176,169 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             rhi[r] = p.res_sign[((int64_t)rt * p.res_words + wb) * 16 + i];
         }
     };
-    // residual contraction of one record: A from the mask / res_sign bits, B = the gathered columns in xs1
-    auto residual = [&](const HalfData<N8> (&hd)[4], const uint4& ra, uint32_t ord, const uint32_t (&rlo)[4],
-                        const uint32_t (&rhi)[4]) {
-        ResSel sel;
-        sel.sel0 = ra.x; sel.sel1 = ra.y; sel.bit0 = ra.z; sel.bit1 = ra.w;
-        uint4 b[8];
-        bload_res(b);
-        uint32_t a[4][4];
+    auto fetch_res_words = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) {
+        const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+        const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
 #pragma unroll
-        for (int r = 0; r < 4; r++)
-            residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, a[r]);
-        mfma32(a, b);
-    };
-
-    for (int sh = 0; sh < nsh; sh++) {
-        const int sb = sh >> 1, half = sh & 1;
-        const bool more = sh + 1 < nsh;
-        HalfData<N8> hd[4];
-        load_hd(sb, half, hd);
-        // the table record of this (superblock, half) and, through it, the residual sign words of the rows
-        uint4 ra = make_uint4(0u, 0u, 0u, 0u);
-        uint2 rb = make_uint2(0u, 0u);
-        const uint32_t* rec0 = nullptr;
-        if (HAS_RES) {
-            rec0 = p.sal_tab + (((int64_t)(4 * sb + g) * 2 + half) * p.sal_chunks) * 12;
-            ra = *reinterpret_cast<const uint4*>(rec0);
-            rb = *reinterpret_cast<const uint2*>(rec0 + 4);
+        for (int r = 0; r < 4; r++) {
+            const uint32_t oa = rsrow[r] + (uint32_t)wa * 64u, ob = rsrow[r] + (uint32_t)wb * 64u;
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(rlo[r]) : "v"(oa), "s"(p.res_sign));
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(rhi[r]) : "v"(ob), "s"(p.res_sign));
         }
-        uint32_t TL[4], TH[4];
+    };
+    auto scale_tables = [&](const HalfData<N8> (&hd)[4], uint32_t (&TL)[4], uint32_t (&TH)[4]) {
 #pragma unroll
         for (int r = 0; r < 4; r++) {
             TL[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x06040200u);
             TH[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x07050301u);
         }
-        // window 0 is in xs0; fetch window 1 and the gathered salient columns while it is used
-        uint4 sr[2];
-        x_gload(sb, half, 1, st);
-        r_gload(sh, 0, sr);
-        window(hd, TL, TH, 0, 0);
-        x_lstore(1, st);
-        if (HAS_RES) r_lstore(sr);
-        uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
-        int nch = 0;
-        if (HAS_RES) {
-            nch = __builtin_amdgcn_readfirstlane((int)rb.y);
-            if (nch > 0) load_res_words(rb.x, rlo, rhi);
+    };
+
+    // ---- the K step: 32 MFMAs (4 row tiles x 8 token tiles) on the A operands `ac` and the B operands b[]; in
+    //      their shadow the lane builds the A operands of the next step (`next_a(r)` for row tile r) and, as soon
+    //      as the four MFMAs of a token tile have been issued, reloads that tile's B operand for the next step
+    //      (`next_b(tt)`).  `extra()` is the step's share of the staging work. ----
+    uint4 b[8];
+    auto kstep = [&](const uint32_t (&ac)[4][4], auto&& next_a, auto&& next_b, auto&& extra) {
+#pragma unroll
+        for (int tt = 0; tt < 8; tt++) {
+            const half8_t bv = __builtin_bit_cast(half8_t, b[tt]);
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(ac[r]), bv, acc[r][tt], 0, 0, 0);
+            next_b(tt);
+            if (tt % 2 == 0) next_a(tt / 2);
+            if (tt == 1) extra();
         }
-        __syncthreads();
-        if (more) x_gload((sh + 1) >> 1, (sh + 1) & 1, 0, st);
-        window(hd, TL, TH, 1, 1);
+        // the order the scheduler is asked for: one MFMA (16 cycles in the matrix pipe), then what fits in its
+        // shadow: an LDS read while there are any, three vector instructions
+#pragma unroll
+        for (int q = 0; q < 32; q++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // LDS read
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);       // VALU
+        }
+    };
+    // B operand of token tile tt: rows 16 tt + i, piece 4 g + tq, at position piece ^ i
+    uint32_t bx[4];
+#pragma unroll
+    for (int tq = 0; tq < 4; tq++) bx[tq] = (uint32_t)(i * 256 + ((4 * g + tq) ^ i) * 16);
+    auto bread = [&](int buf, int tq, int tt) {
+        b[tt] = *reinterpret_cast<const uint4*>(lds + GM_XW + buf * GM_XWSZ + tt * 4096 + bx[tq]);
+    };
+    const uint32_t gx = (uint32_t)(i * 64 + (g ^ ((i >> 2) & 3)) * 16);
+
+    // ---- prologue: both windows of the first half block, its records, the operands of step 0 ----
+    HalfData<N8> hd[4];
+    uint32_t TL[4], TH[4];
+    uint4 ra = make_uint4(0u, 0u, 0u, 0u);
+    uint2 rb = make_uint2(0u, 0u);
+    uint32_t a0[4][4], a1[4][4];
+    uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
+    x_gload(0, 0, 0);
+    x_gload(0, 1, 1);
+    r_gload(0, 0, 0);
+    load_hd(0, hd);
+    load_rec(0, ra, rb);
+    if (HAS_RES) fetch_res_words(rb.x, rlo, rhi);
+    scale_tables(hd, TL, TH);
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(HAS_RES ? 8 : 0) : "memory");      // all but the res_sign words
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; r++) expand_group<N8>(hd[r], TL[r], TH[r], 0, lut_fetch<N8>(hd[r], 0, &lut, lane & 7), a0[r]);
+#pragma unroll
+    for (int tt = 0; tt < 8; tt++) bread(0, 0, tt);
+
+    // Loads of one pass, in issue order (NR res_sign words of this pass are older than all of them):
+    //   [step 3, after the first barrier]  window 0 of the next pass (8)
+    //   [step 4]                           the next pass's half records (NH) and table record (NC)
+    //   [step 7, after the second barrier] window 1 (8) and gathered columns (NG) of the next pass
+    //   [end]                              res_sign words of the next pass (NR)
+    constexpr int NG = HAS_RES ? 2 : 0, NR = HAS_RES ? 8 : 0, NC = HAS_RES ? 2 : 0, NH = 4 * TileLoads<false>::count;
+    for (int sh = 0; sh < nsh; sh++) {
+        const int shn = sh + 1 < nsh ? sh + 1 : sh;                 // the last pass prefetches its own data again
+        const int par = sh & 1;
+        const int nch = HAS_RES ? __builtin_amdgcn_readfirstlane((int)rb.y) : 0;
+        TileRegs<N8> tn[4];
+        uint4_t ran = {0u, 0u, 0u, 0u};
+        uint2_t rbn = {0u, 0u};
+        auto produce = [&](int t, uint32_t (&an)[4][4]) {
+            return [&, t](int r) { expand_group<N8>(hd[r], TL[r], TH[r], t, lut_fetch<N8>(hd[r], t, &lut, lane & 7), an[r]); };
+        };
+        auto reload = [&](int t) { return [&, t](int tt) { bread(t >> 2, t & 3, tt); }; };
+        auto nothing = [] {};
+
+        // steps 0 .. 7 = column groups 0 .. 7 of the half block; window 0 holds groups 0..3, window 1 groups 4..7
+        kstep(a0, produce(1, a1), reload(1), nothing);
+        kstep(a1, produce(2, a0), reload(2), nothing);
+        kstep(a0, produce(3, a1), reload(3), nothing);
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR) : "memory");  // window 1 and the gathered columns of this pass are in LDS
+        __syncthreads();                                            // ... everyone's; and everyone is done with window 0
+        kstep(a1, produce(4, a0), reload(4), [&] { x_gload(shn, 0, 0); });
+        kstep(a0, produce(5, a1), reload(5), [&] { fetch_hd(shn, tn); fetch_rec(shn, ran, rbn); });
+        kstep(a1, produce(6, a0), reload(6), nothing);
+        kstep(a0, produce(7, a1), reload(7), nothing);
+        // everything in flight has arrived: window 0 of the next pass, its half records and table record, and the
+        // res_sign words of this pass
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]),
+                     "+v"(ran), "+v"(rbn) : : "memory");
+#pragma unroll
+        for (int r = 0; r < 4; r++) asm volatile("s_waitcnt vmcnt(0)" : "+v"(tn[r].m), "+v"(tn[r].s), "+v"(tn[r].r), "+v"(tn[r].sc), "+v"(tn[r].ar));
+        __syncthreads();                                            // everyone is done with window 1
+        HalfData<N8> hn[4];
+        uint32_t TLn[4], THn[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) { tn[r].rlo = 0u; tn[r].rhi = 0u; unpack_tile<N8>(tn[r], shn & 1, hn[r]); }
+        scale_tables(hn, TLn, THn);
+        auto produce_n = [&](uint32_t (&an)[4][4]) {
+            return [&](int r) { expand_group<N8>(hn[r], TLn[r], THn[r], 0, lut_fetch<N8>(hn[r], 0, &lut, lane & 7), an[r]); };
+        };
+        auto reload_n = [&](int tt) { bread(0, 0, tt); };
+        auto next_loads = [&] { x_gload(shn, 1, 1); r_gload(shn, 0, par ^ 1); };
         if (HAS_RES && nch > 0) {
-            residual(hd, ra, rb.x, rlo, rhi);
-            for (int c = 1; c < nch; c++) {              // half blocks with more than 8 salient columns (rare)
-                __syncthreads();                         // every wavefront is done with the gathered columns
-                r_gload(sh, c, sr);
-                r_lstore(sr);
-                const uint32_t* rec = rec0 + c * 12;
+            // residual contraction (Eq. 4): A from the mask / res_sign bits, B = the gathered columns
+            auto res_a = [&](const uint4& rr, uint32_t ord, uint32_t (&an)[4][4]) {
+                return [&, ord](int r) {
+                    ResSel sel;
+                    sel.sel0 = rr.x; sel.sel1 = rr.y; sel.bit0 = rr.z; sel.bit1 = rr.w;
+                    residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, an[r]);
+                };
+            };
+            const uint32_t gxp = gx + (uint32_t)(GM_XG + par * GM_XGSZ);
+            auto reload_g = [&](int tt) { b[tt] = *reinterpret_cast<const uint4*>(lds + tt * 1024 + gxp); };
+            kstep(a1, res_a(ra, rb.x, a0), reload_g, next_loads);
+            for (int c = 1; c < nch; c++) {                  // half blocks with more than 8 salient columns (rare)
+                kstep(a0, [](int) {}, [](int) {}, nothing);
+                asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+                __syncthreads();                             // every wavefront is done with the gathered columns
+                r_gload(sh, c, par);
+                const uint32_t* rec = p.sal_tab + (((int64_t)(4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks + c) * 12;
                 const uint4 rc = *reinterpret_cast<const uint4*>(rec);
                 const uint32_t ord = rec[4];
                 load_res_words(ord, rlo, rhi);
+                asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
                 __syncthreads();
-                residual(hd, rc, ord, rlo, rhi);
+#pragma unroll
+                for (int r = 0; r < 4; r++) res_a(rc, ord, a0)(r);
+#pragma unroll
+                for (int tt = 0; tt < 8; tt++) reload_g(tt);
             }
+            kstep(a0, produce_n(a1), reload_n, nothing);
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+#pragma unroll
+                for (int v = 0; v < 4; v++) a0[r][v] = a1[r][v];
+        } else {
+            kstep(a1, produce_n(a0), reload_n, next_loads);
         }
-        if (more) x_lstore(0, st);
-        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; r++) { hd[r] = hn[r]; TL[r] = TLn[r]; TH[r] = THn[r]; }
+        ra = make_uint4(ran.x, ran.y, ran.z, ran.w);
+        rb = make_uint2(rbn.x, rbn.y);
+        if (HAS_RES) fetch_res_words(rb.x, rlo, rhi);
     }
+    // nothing may still be on its way to this workgroup's LDS or registers when the wavefront ends
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
 
     // ---- epilogue: D[row][token] of an MFMA: lane l holds token l % 16, rows 4*(l / 16) + v ----
 #pragma unroll
@@ -260,6 +358,16 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             }
         }
     }
+}
+
+template <int N8, bool HAS_RES>
+hipError_t launch_gemm(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
+                       const __half* xsal, int cfix) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_tiled_kernel<N8, HAS_RES>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GM_LDS);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES>), grid, dim3(256), GM_LDS, st, p, X, T, Y, y_fp32, xsal, cfix);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -290,14 +398,9 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
     const int n8 = 8 * L->cfg.N / L->cfg.M;
     const __half* xh = (const __half*)X;
     const __half* xs = (const __half*)workspace;
-    if (n8 == 4) {
-        if (res) hipLaunchKernelGGL((gemm_tiled_kernel<4, true>), grid, dim3(256), 0, st, p, xh, T, Y, y_fp32, xs, cfix);
-        else hipLaunchKernelGGL((gemm_tiled_kernel<4, false>), grid, dim3(256), 0, st, p, xh, T, Y, y_fp32, xs, cfix);
-    } else {
-        if (res) hipLaunchKernelGGL((gemm_tiled_kernel<6, true>), grid, dim3(256), 0, st, p, xh, T, Y, y_fp32, xs, cfix);
-        else hipLaunchKernelGGL((gemm_tiled_kernel<6, false>), grid, dim3(256), 0, st, p, xh, T, Y, y_fp32, xs, cfix);
-    }
-    const hipError_t e = hipGetLastError();
+    hipError_t e;
+    if (n8 == 4) e = res ? launch_gemm<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
+    else e = res ? launch_gemm<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
     *hip_err = (int)e;
     return e == hipSuccess ? STB_OK : STB_EHIP;
 }
