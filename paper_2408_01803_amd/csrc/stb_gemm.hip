@@ -91,12 +91,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     //      block piece / 4, 8 columns (piece % 4).  Tokens past T are clamped to the last token (their outputs are
     //      never stored); a piece past column k is clamped to the row's last 16 bytes (it meets zero weights). ----
     const uint32_t tok_last = (uint32_t)(T - 1 - t0), k2 = (uint32_t)p.k * 2u;
-    uint32_t xrow[8], xpc[4];
-#pragma unroll
-    for (int u = 0; u < 8; u++) {
-        const uint32_t row = (uint32_t)(4 * (8 * wave + u) + g);
-        xrow[u] = (row < tok_last ? row : tok_last) * k2;
-    }
+    uint32_t xpc[4];
 #pragma unroll
     for (int j = 0; j < 4; j++) {
         const uint32_t pc = (uint32_t)i ^ (uint32_t)(4 * j + g);   // rows 4 * (8w + u) + g: row % 16 = 4 * (u % 4) + g
@@ -109,7 +104,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
 #pragma unroll
         for (int u = 0; u < 8; u++) {
             const uint32_t c = xpc[u & 3] + wcol;
-            load_to_lds(dst + u * 1024, xrow[u] + (c < k2 - 16u ? c : k2 - 16u), Xt);
+            const uint32_t row = (uint32_t)(4 * (8 * wave + u)) + (uint32_t)g;
+            load_to_lds(dst + u * 1024, __umul24(row < tok_last ? row : tok_last, k2) + (c < k2 - 16u ? c : k2 - 16u), Xt);
         }
     };
     // the gathered salient columns of (superblock, half) sh, record c: 8 wavefront loads of 16 token rows, 2 per
@@ -160,11 +156,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             fetch_main<N8>(tn[r], p, (int64_t)__builtin_amdgcn_readfirstlane(rt * p.nsb + (sh >> 1)), lo);
         }
     };
-    uint32_t rsrow[4];                                              // byte offset of the lane's row in res_sign, per row tile
+    const uint32_t* rsbase[4];                                      // res_sign words of the four row tiles (uniform)
 #pragma unroll
     for (int r = 0; r < 4; r++) {
         const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
-        rsrow[r] = (uint32_t)(rt * p.res_words * 16 + i) * 4u;
+        rsbase[r] = p.res_sign + (int64_t)rt * p.res_words * 16;
     }
     auto load_res_words = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) {
         const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
@@ -181,9 +177,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
 #pragma unroll
         for (int r = 0; r < 4; r++) {
-            const uint32_t oa = rsrow[r] + (uint32_t)wa * 64u, ob = rsrow[r] + (uint32_t)wb * 64u;
-            asm volatile("global_load_dword %0, %1, %2" : "=v"(rlo[r]) : "v"(oa), "s"(p.res_sign));
-            asm volatile("global_load_dword %0, %1, %2" : "=v"(rhi[r]) : "v"(ob), "s"(p.res_sign));
+            const uint32_t oa = (uint32_t)(wa * 16 + i) * 4u, ob = (uint32_t)(wb * 16 + i) * 4u;
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(rlo[r]) : "v"(oa), "s"(rsbase[r]));
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(rhi[r]) : "v"(ob), "s"(rsbase[r]));
         }
     };
     auto scale_tables = [&](const HalfData<N8> (&hd)[4], uint32_t (&TL)[4], uint32_t (&TH)[4]) {
@@ -212,12 +208,14 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         }
         // the order the scheduler is asked for: one MFMA (16 cycles in the matrix pipe), then what fits in its
         // shadow: an LDS read while there are any, three vector instructions
+#ifndef GM_NOSGB
 #pragma unroll
         for (int q = 0; q < 32; q++) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // LDS read
             __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);       // VALU
         }
+#endif
     };
     // B operand of token tile tt: rows 16 tt + i, piece 4 g + tq, at position piece ^ i
     uint32_t bx[4];
@@ -238,11 +236,25 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     x_gload(0, 0, 0);
     x_gload(0, 1, 1);
     r_gload(0, 0, 0);
-    load_hd(0, hd);
-    load_rec(0, ra, rb);
+    {
+        // (asm loads here too: a load the compiler knows of would make it wait, inside the loop, for everything in flight)
+        TileRegs<N8> t0r[4];
+        uint4_t ra0 = {0u, 0u, 0u, 0u};
+        uint2_t rb0 = {0u, 0u};
+        fetch_hd(0, t0r);
+        fetch_rec(0, ra0, rb0);
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(ra0), "+v"(rb0) : : "memory");
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(t0r[r].m), "+v"(t0r[r].s), "+v"(t0r[r].r), "+v"(t0r[r].sc), "+v"(t0r[r].ar));
+            t0r[r].rlo = 0u; t0r[r].rhi = 0u;
+            unpack_tile<N8>(t0r[r], 0, hd[r]);
+        }
+        ra = make_uint4(ra0.x, ra0.y, ra0.z, ra0.w);
+        rb = make_uint2(rb0.x, rb0.y);
+    }
     if (HAS_RES) fetch_res_words(rb.x, rlo, rhi);
     scale_tables(hd, TL, TH);
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(HAS_RES ? 8 : 0) : "memory");      // all but the res_sign words
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < 4; r++) expand_group<N8>(hd[r], TL[r], TH[r], 0, lut_fetch<N8>(hd[r], 0, &lut, lane & 7), a0[r]);
@@ -258,7 +270,6 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     for (int sh = 0; sh < nsh; sh++) {
         const int shn = sh + 1 < nsh ? sh + 1 : sh;                 // the last pass prefetches its own data again
         const int par = sh & 1;
-        const int nch = HAS_RES ? __builtin_amdgcn_readfirstlane((int)rb.y) : 0;
         TileRegs<N8> tn[4];
         uint4_t ran = {0u, 0u, 0u, 0u};
         uint2_t rbn = {0u, 0u};
@@ -295,34 +306,17 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         };
         auto reload_n = [&](int tt) { bread(0, 0, tt); };
         auto next_loads = [&] { x_gload(shn, 1, 1); r_gload(shn, 0, par ^ 1); };
-        if (HAS_RES && nch > 0) {
-            // residual contraction (Eq. 4): A from the mask / res_sign bits, B = the gathered columns
-            auto res_a = [&](const uint4& rr, uint32_t ord, uint32_t (&an)[4][4]) {
-                return [&, ord](int r) {
-                    ResSel sel;
-                    sel.sel0 = rr.x; sel.sel1 = rr.y; sel.bit0 = rr.z; sel.bit1 = rr.w;
-                    residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, an[r]);
-                };
+        if (HAS_RES) {
+            // residual contraction (Eq. 4) of the first 8 salient columns of every half block: A from the mask and
+            // res_sign bits, B = the gathered columns.  (A half block without salient columns has an all-zero A.)
+            auto res_a = [&](int r) {
+                ResSel sel;
+                sel.sel0 = ra.x; sel.sel1 = ra.y; sel.bit0 = ra.z; sel.bit1 = ra.w;
+                residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], rb.x & 31u), hd[r].ar | (hd[r].ar << 16), sel, a0[r]);
             };
             const uint32_t gxp = gx + (uint32_t)(GM_XG + par * GM_XGSZ);
             auto reload_g = [&](int tt) { b[tt] = *reinterpret_cast<const uint4*>(lds + tt * 1024 + gxp); };
-            kstep(a1, res_a(ra, rb.x, a0), reload_g, next_loads);
-            for (int c = 1; c < nch; c++) {                  // half blocks with more than 8 salient columns (rare)
-                kstep(a0, [](int) {}, [](int) {}, nothing);
-                asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
-                __syncthreads();                             // every wavefront is done with the gathered columns
-                r_gload(sh, c, par);
-                const uint32_t* rec = p.sal_tab + (((int64_t)(4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks + c) * 12;
-                const uint4 rc = *reinterpret_cast<const uint4*>(rec);
-                const uint32_t ord = rec[4];
-                load_res_words(ord, rlo, rhi);
-                asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
-                __syncthreads();
-#pragma unroll
-                for (int r = 0; r < 4; r++) res_a(rc, ord, a0)(r);
-#pragma unroll
-                for (int tt = 0; tt < 8; tt++) reload_g(tt);
-            }
+            kstep(a1, res_a, reload_g, next_loads);
             kstep(a0, produce_n(a1), reload_n, nothing);
 #pragma unroll
             for (int r = 0; r < 4; r++)
@@ -337,8 +331,42 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         rb = make_uint2(rbn.x, rbn.y);
         if (HAS_RES) fetch_res_words(rb.x, rlo, rhi);
     }
-    // nothing may still be on its way to this workgroup's LDS or registers when the wavefront ends
+    // nothing may still be on its way to this workgroup's LDS or registers from here on
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
+
+    // ---- half blocks with more than 8 salient columns: their further records, one at a time and without any
+    //      overlap (few: a record covers 8 of the 64 columns).  Kept out of the main loop so that it stays one
+    //      straight line of K steps. ----
+    if (HAS_RES && p.sal_chunks > 1) {
+        for (int sh = 0; sh < nsh; sh++) {
+            const uint32_t* rec0 = p.sal_tab + (((int64_t)(4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 12;
+            const int nch = __builtin_amdgcn_readfirstlane((int)rec0[5]);          // the same for the four blocks
+            if (nch <= 1) continue;
+            load_hd(sh, hd);
+            for (int c = 1; c < nch; c++) {
+                __syncthreads();                             // every wavefront is done with the gathered columns
+                r_gload(sh, c, 0);
+                const uint4 rc = *reinterpret_cast<const uint4*>(rec0 + c * 12);
+                const uint32_t ord = rec0[c * 12 + 4];
+                load_res_words(ord, rlo, rhi);
+                asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+                __syncthreads();
+                ResSel sel;
+                sel.sel0 = rc.x; sel.sel1 = rc.y; sel.bit0 = rc.z; sel.bit1 = rc.w;
+#pragma unroll
+                for (int r = 0; r < 4; r++)
+                    residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, a1[r]);
+#pragma unroll
+                for (int tt = 0; tt < 8; tt++) {
+                    const uint4 bt = *reinterpret_cast<const uint4*>(lds + GM_XG + tt * 1024 + gx);
+                    const half8_t bv = __builtin_bit_cast(half8_t, bt);
+#pragma unroll
+                    for (int r = 0; r < 4; r++)
+                        acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(a1[r]), bv, acc[r][tt], 0, 0, 0);
+                }
+            }
+        }
+    }
 
     // ---- epilogue: D[row][token] of an MFMA: lane l holds token l % 16, rows 4*(l / 16) + v ----
 #pragma unroll
