@@ -98,15 +98,16 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         xpc[j] = (pc >> 2) * 256u + (pc & 3u) * 16u;
     }
     const __half* const Xt = X + (int64_t)t0 * p.k;
-    auto x_gload = [&](int sh, int win, int buf) {
+    auto x_gload1 = [&](int sh, int win, int buf, int u) {          // load u (0..7) of the wavefront's share of a window
         const uint32_t wcol = (uint32_t)((sh >> 1) * 1024 + (sh & 1) * 128 + win * 64);      // bytes inside a token row
         const uint32_t dst = lds0 + GM_XW + buf * GM_XWSZ + wave * 8192;
+        const uint32_t c = xpc[u & 3] + wcol;
+        const uint32_t row = (uint32_t)(4 * (8 * wave + u)) + (uint32_t)g;
+        load_to_lds(dst + u * 1024, __umul24(row < tok_last ? row : tok_last, k2) + (c < k2 - 16u ? c : k2 - 16u), Xt);
+    };
+    auto x_gload = [&](int sh, int win, int buf) {
 #pragma unroll
-        for (int u = 0; u < 8; u++) {
-            const uint32_t c = xpc[u & 3] + wcol;
-            const uint32_t row = (uint32_t)(4 * (8 * wave + u)) + (uint32_t)g;
-            load_to_lds(dst + u * 1024, __umul24(row < tok_last ? row : tok_last, k2) + (c < k2 - 16u ? c : k2 - 16u), Xt);
-        }
+        for (int u = 0; u < 8; u++) x_gload1(sh, win, buf, u);
     };
     // the gathered salient columns of (superblock, half) sh, record c: 8 wavefront loads of 16 token rows, 2 per
     // wavefront; lane l = row l / 4 of them, position l % 4 = piece (l % 4) ^ ((row / 4) % 4)
@@ -118,12 +119,12 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         const uint32_t row = (uint32_t)(16 * (2 * wave + u) + (lane >> 2));
         grow[u] = (row < tok_last ? row : tok_last) * (uint32_t)E * 2u + (((uint32_t)lane & 3u) ^ (((uint32_t)lane >> 4) & 3u)) * 16u;
     }
+    auto r_gload1 = [&](int sh, int c, int par, int u) {
+        if (HAS_RES) load_to_lds(lds0 + GM_XG + par * GM_XGSZ + (2 * wave + u) * 1024, grow[u] + (uint32_t)(sh * cfix + c) * 64u, xsal_t);
+    };
     auto r_gload = [&](int sh, int c, int par) {
-        if (HAS_RES) {
 #pragma unroll
-            for (int u = 0; u < 2; u++)
-                load_to_lds(lds0 + GM_XG + par * GM_XGSZ + (2 * wave + u) * 1024, grow[u] + (uint32_t)(sh * cfix + c) * 64u, xsal_t);
-        }
+        for (int u = 0; u < 2; u++) r_gload1(sh, c, par, u);
     };
     auto load_hd = [&](int sh, HalfData<N8> (&hd)[4]) {
         const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
@@ -148,13 +149,14 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             asm volatile("global_load_dwordx2 %0, %1, %2 offset:16" : "=v"(rb) : "v"(off), "s"(p.sal_tab));
         }
     };
-    auto fetch_hd = [&](int sh, TileRegs<N8> (&tn)[4]) {
+    auto fetch_hd1 = [&](int sh, TileRegs<N8> (&tn)[4], int r) {      // the 5 loads of row tile r
         const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
+        const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
+        fetch_main<N8>(tn[r], p, (int64_t)__builtin_amdgcn_readfirstlane(rt * p.nsb + (sh >> 1)), lo);
+    };
+    auto fetch_hd = [&](int sh, TileRegs<N8> (&tn)[4]) {
 #pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
-            fetch_main<N8>(tn[r], p, (int64_t)__builtin_amdgcn_readfirstlane(rt * p.nsb + (sh >> 1)), lo);
-        }
+        for (int r = 0; r < 4; r++) fetch_hd1(sh, tn, r);
     };
     const uint32_t* rsbase[4];                                      // res_sign words of the four row tiles (uniform)
 #pragma unroll
@@ -172,15 +174,16 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             rhi[r] = p.res_sign[((int64_t)rt * p.res_words + wb) * 16 + i];
         }
     };
-    auto fetch_res_words = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) {
+    auto fetch_res_words1 = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4], int r) {     // the 2 loads of row tile r
         const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
         const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+        const uint32_t oa = (uint32_t)(wa * 16 + i) * 4u, ob = (uint32_t)(wb * 16 + i) * 4u;
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(rlo[r]) : "v"(oa), "s"(rsbase[r]));
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(rhi[r]) : "v"(ob), "s"(rsbase[r]));
+    };
+    auto fetch_res_words = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) {
 #pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const uint32_t oa = (uint32_t)(wa * 16 + i) * 4u, ob = (uint32_t)(wb * 16 + i) * 4u;
-            asm volatile("global_load_dword %0, %1, %2" : "=v"(rlo[r]) : "v"(oa), "s"(rsbase[r]));
-            asm volatile("global_load_dword %0, %1, %2" : "=v"(rhi[r]) : "v"(ob), "s"(rsbase[r]));
-        }
+        for (int r = 0; r < 4; r++) fetch_res_words1(ord, rlo, rhi, r);
     };
     auto scale_tables = [&](const HalfData<N8> (&hd)[4], uint32_t (&TL)[4], uint32_t (&TH)[4]) {
 #pragma unroll
@@ -204,7 +207,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
                 acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(ac[r]), bv, acc[r][tt], 0, 0, 0);
             next_b(tt);
             if (tt % 2 == 0) next_a(tt / 2);
-            if (tt == 1) extra();
+            extra(tt);
         }
         // the order the scheduler is asked for: one MFMA (16 cycles in the matrix pipe), then what fits in its
         // shadow: an LDS read while there are any, three vector instructions
@@ -265,7 +268,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     //   [step 3, after the first barrier]  window 0 of the next pass (8)
     //   [step 4]                           the next pass's half records (NH) and table record (NC)
     //   [step 7, after the second barrier] window 1 (8) and gathered columns (NG) of the next pass
-    //   [end]                              res_sign words of the next pass (NR)
+    //   [residual step]                    res_sign words of the next pass (NR)
     constexpr int NG = HAS_RES ? 2 : 0, NR = HAS_RES ? 8 : 0, NC = HAS_RES ? 2 : 0, NH = 4 * TileLoads<false>::count;
     for (int sh = 0; sh < nsh; sh++) {
         const int shn = sh + 1 < nsh ? sh + 1 : sh;                 // the last pass prefetches its own data again
@@ -277,7 +280,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             return [&, t](int r) { expand_group<N8>(hd[r], TL[r], TH[r], t, lut_fetch<N8>(hd[r], t, &lut, lane & 7), an[r]); };
         };
         auto reload = [&](int t) { return [&, t](int tt) { bread(t >> 2, t & 3, tt); }; };
-        auto nothing = [] {};
+        auto nothing = [](int) {};
 
         // steps 0 .. 7 = column groups 0 .. 7 of the half block; window 0 holds groups 0..3, window 1 groups 4..7
         kstep(a0, produce(1, a1), reload(1), nothing);
@@ -285,8 +288,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         kstep(a0, produce(3, a1), reload(3), nothing);
         asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR) : "memory");  // window 1 and the gathered columns of this pass are in LDS
         __syncthreads();                                            // ... everyone's; and everyone is done with window 0
-        kstep(a1, produce(4, a0), reload(4), [&] { x_gload(shn, 0, 0); });
-        kstep(a0, produce(5, a1), reload(5), [&] { fetch_hd(shn, tn); fetch_rec(shn, ran, rbn); });
+        // (the loads are spread over the token tiles of a step, a few at a time: the four wavefronts share one path
+        //  to memory, and a burst of loads stalls them all)
+        kstep(a1, produce(4, a0), reload(4), [&](int tt) { x_gload1(shn, 0, 0, tt); });
+        kstep(a0, produce(5, a1), reload(5), [&](int tt) { if (tt % 2 == 0) fetch_hd1(shn, tn, tt / 2); if (tt == 7) fetch_rec(shn, ran, rbn); });
         kstep(a1, produce(6, a0), reload(6), nothing);
         kstep(a0, produce(7, a1), reload(7), nothing);
         // everything in flight has arrived: window 0 of the next pass, its half records and table record, and the
@@ -305,7 +310,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             return [&](int r) { expand_group<N8>(hn[r], TLn[r], THn[r], 0, lut_fetch<N8>(hn[r], 0, &lut, lane & 7), an[r]); };
         };
         auto reload_n = [&](int tt) { bread(0, 0, tt); };
-        auto next_loads = [&] { x_gload(shn, 1, 1); r_gload(shn, 0, par ^ 1); };
+        auto next_loads = [&](int tt) { x_gload1(shn, 1, 1, tt); if (tt >= 6) r_gload1(shn, 0, par ^ 1, tt - 6); };
         if (HAS_RES) {
             // residual contraction (Eq. 4) of the first 8 salient columns of every half block: A from the mask and
             // res_sign bits, B = the gathered columns.  (A half block without salient columns has an all-zero A.)
@@ -317,7 +322,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             const uint32_t gxp = gx + (uint32_t)(GM_XG + par * GM_XGSZ);
             auto reload_g = [&](int tt) { b[tt] = *reinterpret_cast<const uint4*>(lds + tt * 1024 + gxp); };
             kstep(a1, res_a, reload_g, next_loads);
-            kstep(a0, produce_n(a1), reload_n, nothing);
+            // (the res_sign words of the next pass: its table record arrived before the barrier above)
+            kstep(a0, produce_n(a1), reload_n, [&](int tt) { if (tt < 4) fetch_res_words1(rbn.x, rlo, rhi, tt); });
 #pragma unroll
             for (int r = 0; r < 4; r++)
 #pragma unroll
@@ -329,7 +335,6 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         for (int r = 0; r < 4; r++) { hd[r] = hn[r]; TL[r] = TLn[r]; TH[r] = THn[r]; }
         ra = make_uint4(ran.x, ran.y, ran.z, ran.w);
         rb = make_uint2(rbn.x, rbn.y);
-        if (HAS_RES) fetch_res_words(rb.x, rlo, rhi);
     }
     // nothing may still be on its way to this workgroup's LDS or registers from here on
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
