@@ -343,10 +343,16 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     //      overlap (few: a record covers 8 of the 64 columns).  Kept out of the main loop so that it stays one
     //      straight line of K steps. ----
     if (HAS_RES && p.sal_chunks > 1) {
-        for (int sh = 0; sh < nsh; sh++) {
+      for (int sh0 = 0; sh0 < nsh; sh0 += 64) {
+        // which of the next 64 half blocks have such records: lane l looks at half block sh0 + l
+        const int shl = sh0 + lane < nsh ? sh0 + lane : nsh - 1;
+        const uint32_t need_l = p.sal_tab[(((int64_t)(4 * (shl >> 1)) * 2 + (shl & 1)) * p.sal_chunks) * 12 + 5];
+        uint64_t todo = __ballot(need_l > 1u && sh0 + lane < nsh);
+        while (todo) {
+            const int sh = sh0 + __builtin_ctzll(todo);
+            todo &= todo - 1;
             const uint32_t* rec0 = p.sal_tab + (((int64_t)(4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 12;
             const int nch = __builtin_amdgcn_readfirstlane((int)rec0[5]);          // the same for the four blocks
-            if (nch <= 1) continue;
             load_hd(sh, hd);
             for (int c = 1; c < nch; c++) {
                 __syncthreads();                             // every wavefront is done with the gathered columns
@@ -371,9 +377,38 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
                 }
             }
         }
+      }
     }
 
     // ---- epilogue: D[row][token] of an MFMA: lane l holds token l % 16, rows 4*(l / 16) + v ----
+    // fp16 output whose rows of Y can be written in 16-byte pieces: the wavefront transposes its 64 rows x 128 tokens
+    // through LDS (its own region; token rows of 144 bytes), so that a store instruction writes whole 128-byte runs
+    // of Y (8 tokens x the wavefront's 64 rows) instead of 32-byte pieces.
+    const bool wide = !y_fp32 && (p.n & 7) == 0 && ((uintptr_t)Y & 15) == 0 && (rtw + 4) * 16 <= p.n;     // uniform per wavefront
+    __syncthreads();                                                // every wavefront is done with the windows
+    if (wide) {
+        char* const ep = lds + wave * (GM_TOK * 144);
+#pragma unroll
+        for (int r = 0; r < 4; r++)
+#pragma unroll
+            for (int tt = 0; tt < 8; tt++) {
+                const __half2 lo = __floats2half2_rn(-acc[r][tt][0], -acc[r][tt][1]);
+                const __half2 hi = __floats2half2_rn(-acc[r][tt][2], -acc[r][tt][3]);
+                uint2 v;
+                v.x = __builtin_bit_cast(uint32_t, lo);
+                v.y = __builtin_bit_cast(uint32_t, hi);
+                *reinterpret_cast<uint2*>(ep + (16 * tt + i) * 144 + (16 * r + 4 * g) * 2) = v;
+            }
+        // (the wavefront reads back only what it wrote itself: LDS keeps a wavefront's accesses in order)
+        __half* const Yh = reinterpret_cast<__half*>(Y);
+#pragma unroll
+        for (int it = 0; it < 16; it++) {
+            const int tl = 8 * it + (lane >> 3), tok = t0 + tl;
+            const uint4 v = *reinterpret_cast<const uint4*>(ep + tl * 144 + (lane & 7) * 16);
+            if (tok < T) *reinterpret_cast<uint4*>(Yh + (int64_t)tok * p.n + rtw * 16 + (lane & 7) * 8) = v;
+        }
+        return;
+    }
 #pragma unroll
     for (int r = 0; r < 4; r++) {
         const int row = (rtw + r) * 16 + 4 * g;
