@@ -11,6 +11,8 @@
 // The residual term of the salient columns (Eq. 4) is a second, short contraction: its A operand comes from
 // residual_chunk, its B operand from a compact copy of the salient columns of X that gemm_gather_kernel
 // writes to the workspace beforehand.
+#include <cstdlib>
+
 #include "stb_tiled.hpp"
 
 using namespace stbt;
@@ -54,6 +56,57 @@ __global__ __launch_bounds__(256) void gemm_gather_kernel(TiledPlanes p, const _
 }
 
 template <int V> struct IntC { static constexpr int value = V; };
+
+// Writes a wavefront's 64 rows x 128 tokens: D[row][token] of an MFMA, lane l holds token l % 16, rows 4*(l / 16) + v.
+// (The caller has passed a barrier after the last use of LDS.)
+__device__ inline void store_tile(const float4_t (&acc)[4][8], char* lds, const TiledPlanes& p, void* __restrict__ Y, int y_fp32,
+                                  int T, int t0, int rtw, int wave, int lane) {
+    const int i = lane & 15, g = lane >> 4;
+    // fp16 output whose rows of Y can be written in 16-byte pieces: the wavefront transposes its 64 rows x 128 tokens
+    // through LDS (its own region; token rows of 144 bytes), so that a store instruction writes whole 128-byte runs
+    // of Y (8 tokens x the wavefront's 64 rows) instead of 32-byte pieces.
+    const bool wide = !y_fp32 && (p.n & 7) == 0 && ((uintptr_t)Y & 15) == 0 && (rtw + 4) * 16 <= p.n;     // uniform per wavefront
+    if (wide) {
+        char* const ep = lds + wave * (GM_TOK * 144);
+#pragma unroll
+        for (int r = 0; r < 4; r++)
+#pragma unroll
+            for (int tt = 0; tt < 8; tt++) {
+                const __half2 lo = __floats2half2_rn(-acc[r][tt][0], -acc[r][tt][1]);
+                const __half2 hi = __floats2half2_rn(-acc[r][tt][2], -acc[r][tt][3]);
+                uint2 v;
+                v.x = __builtin_bit_cast(uint32_t, lo);
+                v.y = __builtin_bit_cast(uint32_t, hi);
+                *reinterpret_cast<uint2*>(ep + (16 * tt + i) * 144 + (16 * r + 4 * g) * 2) = v;
+            }
+        // (the wavefront reads back only what it wrote itself: LDS keeps a wavefront's accesses in order)
+        __half* const Yh = reinterpret_cast<__half*>(Y);
+#pragma unroll
+        for (int it = 0; it < 16; it++) {
+            const int tl = 8 * it + (lane >> 3), tok = t0 + tl;
+            const uint4 v = *reinterpret_cast<const uint4*>(ep + tl * 144 + (lane & 7) * 16);
+            if (tok < T) *reinterpret_cast<uint4*>(Yh + (int64_t)tok * p.n + rtw * 16 + (lane & 7) * 8) = v;
+        }
+        return;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        const int row = (rtw + r) * 16 + 4 * g;
+        if (rtw + r >= p.nrt) continue;
+#pragma unroll
+        for (int tt = 0; tt < 8; tt++) {
+            const int tok = t0 + 16 * tt + i;
+            if (tok >= T) continue;
+#pragma unroll
+            for (int v = 0; v < 4; v++) {
+                if (row + v >= p.n) continue;
+                const float val = -acc[r][tt][v];
+                if (y_fp32) reinterpret_cast<float*>(Y)[(int64_t)tok * p.n + row + v] = val;
+                else reinterpret_cast<__half*>(Y)[(int64_t)tok * p.n + row + v] = __float2half(val);
+            }
+        }
+    }
+}
 
 // One wavefront-wide global -> LDS load of 16 bytes per lane: lane l's bytes land at LDS address m0 + 16 * l.
 // No register is written: the data is in LDS once vmcnt has counted the load down.
@@ -380,52 +433,332 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
       }
     }
 
-    // ---- epilogue: D[row][token] of an MFMA: lane l holds token l % 16, rows 4*(l / 16) + v ----
-    // fp16 output whose rows of Y can be written in 16-byte pieces: the wavefront transposes its 64 rows x 128 tokens
-    // through LDS (its own region; token rows of 144 bytes), so that a store instruction writes whole 128-byte runs
-    // of Y (8 tokens x the wavefront's 64 rows) instead of 32-byte pieces.
-    const bool wide = !y_fp32 && (p.n & 7) == 0 && ((uintptr_t)Y & 15) == 0 && (rtw + 4) * 16 <= p.n;     // uniform per wavefront
-    __syncthreads();                                                // every wavefront is done with the windows
-    if (wide) {
-        char* const ep = lds + wave * (GM_TOK * 144);
+    __syncthreads();                                                // every wavefront is done with LDS
+    store_tile(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// 2:4 layers on the structured-sparse matrix instruction (Sec. 3.1 / App. C: the paper's own kernel form):
+// v_smfmac_f32_16x16x64_f16 takes the kept weights only (8 per lane = 16 columns of the lane's block) and an index
+// word that says which 2 of every 4 columns they are, and contracts them with 64 columns of X at once.  Half the
+// matrix instructions of the dense kernel above, no scatter table, and a cheaper operand (nothing to spread).
+// A pass over a half block is 4 sparse steps of 16 columns per block plus the dense residual step.
+// ------------------------------------------------------------------------------------------------
+typedef _Float16 half16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t uint8_t32 __attribute__((ext_vector_type(8)));
+constexpr int GM_LDS24 = 81920;       // the two windows and the gathered columns; no scatter table
+
+// Index register for 32 columns: every mask nibble (two bits set) becomes the positions of its two kept weights,
+// low one in bits 1:0, high one in bits 3:2, looked up in an 8-byte table by (nibble >> 1) & 7.
+__device__ inline uint32_t index_word24(uint32_t m, uint32_t T0, uint32_t T1, uint32_t K7) {
+    const uint32_t t = m >> 1;
+    const uint32_t lo = perm(T1, T0, t & K7);
+    const uint32_t hi = perm(T1, T0, (t >> 4) & K7);
+    return (hi << 4) | lo;
+}
+
+template <bool HAS_RES>
+__global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
+                                                      void* __restrict__ Y, int y_fp32,
+                                                      const __half* __restrict__ xsal, int cfix) {
+    constexpr int N8 = 4;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int i = lane & 15, g = lane >> 4;
+    const int t0 = blockIdx.x * GM_TOK;
+    const int rtw = blockIdx.y * GM_ROWT + wave * 4;
+    const int nsh = p.nsb * 2;
+
+    float4_t acc[4][8];
 #pragma unroll
-        for (int r = 0; r < 4; r++)
+    for (int r = 0; r < 4; r++)
 #pragma unroll
-            for (int tt = 0; tt < 8; tt++) {
-                const __half2 lo = __floats2half2_rn(-acc[r][tt][0], -acc[r][tt][1]);
-                const __half2 hi = __floats2half2_rn(-acc[r][tt][2], -acc[r][tt][3]);
-                uint2 v;
-                v.x = __builtin_bit_cast(uint32_t, lo);
-                v.y = __builtin_bit_cast(uint32_t, hi);
-                *reinterpret_cast<uint2*>(ep + (16 * tt + i) * 144 + (16 * r + 4 * g) * 2) = v;
-            }
-        // (the wavefront reads back only what it wrote itself: LDS keeps a wavefront's accesses in order)
-        __half* const Yh = reinterpret_cast<__half*>(Y);
+        for (int tt = 0; tt < 8; tt++) acc[r][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+    // ---- global -> LDS loads of the X windows and the gathered columns: as in gemm_tiled_kernel ----
+    const uint32_t tok_last = (uint32_t)(T - 1 - t0), k2 = (uint32_t)p.k * 2u;
+    uint32_t xpc[4];
 #pragma unroll
-        for (int it = 0; it < 16; it++) {
-            const int tl = 8 * it + (lane >> 3), tok = t0 + tl;
-            const uint4 v = *reinterpret_cast<const uint4*>(ep + tl * 144 + (lane & 7) * 16);
-            if (tok < T) *reinterpret_cast<uint4*>(Yh + (int64_t)tok * p.n + rtw * 16 + (lane & 7) * 8) = v;
-        }
-        return;
+    for (int j = 0; j < 4; j++) {
+        const uint32_t pc = (uint32_t)i ^ (uint32_t)(4 * j + g);
+        xpc[j] = (pc >> 2) * 256u + (pc & 3u) * 16u;
     }
+    const __half* const Xt = X + (int64_t)t0 * p.k;
+    auto x_gload1 = [&](int sh, int win, int buf, int u) {
+        const uint32_t wcol = (uint32_t)((sh >> 1) * 1024 + (sh & 1) * 128 + win * 64);
+        const uint32_t dst = lds0 + GM_XW + buf * GM_XWSZ + wave * 8192;
+        const uint32_t c = xpc[u & 3] + wcol;
+        const uint32_t row = (uint32_t)(4 * (8 * wave + u)) + (uint32_t)g;
+        load_to_lds(dst + u * 1024, __umul24(row < tok_last ? row : tok_last, k2) + (c < k2 - 16u ? c : k2 - 16u), Xt);
+    };
+    const int64_t E = (int64_t)p.nsb * 2 * cfix * 32;
+    const __half* const xsal_t = xsal + (int64_t)t0 * E;
+    uint32_t grow[2];
+#pragma unroll
+    for (int u = 0; u < 2; u++) {
+        const uint32_t row = (uint32_t)(16 * (2 * wave + u) + (lane >> 2));
+        grow[u] = (row < tok_last ? row : tok_last) * (uint32_t)E * 2u + (((uint32_t)lane & 3u) ^ (((uint32_t)lane >> 4) & 3u)) * 16u;
+    }
+    auto r_gload1 = [&](int sh, int c, int par, int u) {
+        if (HAS_RES) load_to_lds(lds0 + GM_XG + par * GM_XGSZ + (2 * wave + u) * 1024, grow[u] + (uint32_t)(sh * cfix + c) * 64u, xsal_t);
+    };
+    auto load_hd = [&](int sh, HalfData<N8> (&hd)[4]) {
+        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
+            load_half<N8>(p, (int64_t)rt * p.nsb + (sh >> 1), lo, sh & 1, hd[r]);
+        }
+    };
+    auto fetch_rec = [&](int sh, uint4_t& ra, uint2_t& rb) {
+        if (HAS_RES) {
+            const uint32_t off = (uint32_t)(((4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 48u;
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(ra) : "v"(off), "s"(p.sal_tab));
+            asm volatile("global_load_dwordx2 %0, %1, %2 offset:16" : "=v"(rb) : "v"(off), "s"(p.sal_tab));
+        }
+    };
+    auto fetch_hd1 = [&](int sh, TileRegs<N8> (&tn)[4], int r) {
+        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
+        const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
+        fetch_main<N8>(tn[r], p, (int64_t)__builtin_amdgcn_readfirstlane(rt * p.nsb + (sh >> 1)), lo);
+    };
+    const uint32_t* rsbase[4];
 #pragma unroll
     for (int r = 0; r < 4; r++) {
-        const int row = (rtw + r) * 16 + 4 * g;
-        if (rtw + r >= p.nrt) continue;
+        const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
+        rsbase[r] = p.res_sign + (int64_t)rt * p.res_words * 16;
+    }
+    auto load_res_words = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) {
+        const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+        const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            rlo[r] = rsbase[r][wa * 16 + i];
+            rhi[r] = rsbase[r][wb * 16 + i];
+        }
+    };
+    auto fetch_res_words1 = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4], int r) {
+        const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+        const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+        const uint32_t oa = (uint32_t)(wa * 16 + i) * 4u, ob = (uint32_t)(wb * 16 + i) * 4u;
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(rlo[r]) : "v"(oa), "s"(rsbase[r]));
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(rhi[r]) : "v"(ob), "s"(rsbase[r]));
+    };
+    auto scale_tables = [&](const HalfData<N8> (&hd)[4], uint32_t (&TL)[4], uint32_t (&TH)[4]) {
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            TL[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x06040200u);
+            TH[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x07050301u);
+        }
+    };
+    // constants of the operand build, in VGPRs (a VOP3 instruction takes one literal)
+    uint32_t T0 = 0x09080404u, T1 = 0x0E0E0D0Cu, K7 = 0x07070707u, K3 = 0x03030303u, K4 = 0x04000400u, KS = 0x80008000u;
+    asm volatile("" : "+v"(T0), "+v"(T1), "+v"(K7), "+v"(K3), "+v"(K4), "+v"(KS));
+    // A operand of step s (columns 16 s .. 16 s + 15 of the half block): its 8 kept weights in slot order
+    auto build_a = [&](const HalfData<N8>& d, uint32_t TLr, uint32_t THr, int s, uint32_t (&W)[4]) {
+        const uint32_t rw = d.r[s >> 1], r2 = rw >> 2;
+#pragma unroll
+        for (int c = 0; c < 2; c++) {                         // byte 2 (s % 2) + c of the id word: 4 kept weights
+            const uint32_t bb = 2 * (s & 1) + c;
+            const uint32_t Z = perm(r2, rw, bb | (bb << 8) | ((4 + bb) << 16) | ((4 + bb) << 24));
+            W[2 * c] = perm(THr, TLr, and_or_v(Z, K3, K4));
+            W[2 * c + 1] = perm(THr, TLr, and_or_v(Z >> 4, K3, K4));
+        }
+        const uint32_t sbi = (uint32_t)s;                     // byte of the half's sign word
+        const uint32_t Xs = perm(d.s[0], d.s[0], 0x000C000Cu | (sbi << 8) | (sbi << 24));
+#pragma unroll
+        for (int q = 0; q < 4; q++) W[q] = and_or_v(pk_shl(Xs, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
+    };
+
+    // B operand of a sparse step, lane 16 g + n of token tile tt: elements 0..7 = X[token][block g / 2, columns
+    // 16 s + 8 (g % 2) ..], elements 8..15 = the same columns of block 2 + g / 2: pieces P and P + 8 of the window row.
+    uint32_t bxl[2];
+#pragma unroll
+    for (int u = 0; u < 2; u++) bxl[u] = (uint32_t)(i * 256 + ((4 * (g >> 1) + 2 * u + (g & 1)) ^ i) * 16);
+    uint8_t32 b[8];
+    auto bread = [&](int buf, int u, int tt) {
+        const char* base = lds + GM_XW + buf * GM_XWSZ + tt * 4096;
+        const uint4 lo = *reinterpret_cast<const uint4*>(base + bxl[u]);
+        const uint4 hi = *reinterpret_cast<const uint4*>(base + (bxl[u] ^ 128u));
+        b[tt] = uint8_t32{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    };
+    const uint32_t gx = (uint32_t)(i * 64 + (g ^ ((i >> 2) & 3)) * 16);
+
+    // ---- K steps: a sparse one (32 sparse instructions) and the dense residual one (32 MFMAs on the low half of b[]) ----
+    auto sstep = [&](auto abid_, const uint32_t (&ac)[4][4], const uint32_t (&idx)[4], auto&& next_a, auto&& next_b, auto&& extra) {
+        constexpr int ABID = decltype(abid_)::value;
 #pragma unroll
         for (int tt = 0; tt < 8; tt++) {
-            const int tok = t0 + 16 * tt + i;
-            if (tok >= T) continue;
+            const half16_t bv = __builtin_bit_cast(half16_t, b[tt]);
 #pragma unroll
-            for (int v = 0; v < 4; v++) {
-                if (row + v >= p.n) continue;
-                const float val = -acc[r][tt][v];
-                if (y_fp32) reinterpret_cast<float*>(Y)[(int64_t)tok * p.n + row + v] = val;
-                else reinterpret_cast<__half*>(Y)[(int64_t)tok * p.n + row + v] = __float2half(val);
+            for (int r = 0; r < 4; r++)
+                acc[r][tt] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(ac[r]), bv, acc[r][tt], (int)idx[r], 0, ABID);
+            next_b(tt);
+            if (tt % 2 == 0) next_a(tt / 2);
+            extra(tt);
+        }
+    };
+    auto dstep = [&](const uint32_t (&ac)[4][4], auto&& next_a, auto&& next_b, auto&& extra) {
+#pragma unroll
+        for (int tt = 0; tt < 8; tt++) {
+            const uint4 bl = make_uint4(b[tt][0], b[tt][1], b[tt][2], b[tt][3]);
+            const half8_t bv = __builtin_bit_cast(half8_t, bl);
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(ac[r]), bv, acc[r][tt], 0, 0, 0);
+            next_b(tt);
+            if (tt % 2 == 0) next_a(tt / 2);
+            extra(tt);
+        }
+    };
+
+    // ---- prologue ----
+    HalfData<N8> hd[4];
+    uint32_t TL[4], TH[4];
+    uint4 ra = make_uint4(0u, 0u, 0u, 0u);
+    uint2 rb = make_uint2(0u, 0u);
+    uint32_t a0[4][4], a1[4][4], ia[4], ib[4];
+    uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int u = 0; u < 8; u++) x_gload1(0, 0, 0, u);
+#pragma unroll
+    for (int u = 0; u < 8; u++) x_gload1(0, 1, 1, u);
+    r_gload1(0, 0, 0, 0);
+    r_gload1(0, 0, 0, 1);
+    {
+        TileRegs<N8> t0r[4];
+        uint4_t ra0 = {0u, 0u, 0u, 0u};
+        uint2_t rb0 = {0u, 0u};
+#pragma unroll
+        for (int r = 0; r < 4; r++) fetch_hd1(0, t0r, r);
+        fetch_rec(0, ra0, rb0);
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(ra0), "+v"(rb0) : : "memory");
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(t0r[r].m), "+v"(t0r[r].s), "+v"(t0r[r].r), "+v"(t0r[r].sc), "+v"(t0r[r].ar));
+            t0r[r].rlo = 0u; t0r[r].rhi = 0u;
+            unpack_tile<N8>(t0r[r], 0, hd[r]);
+        }
+        ra = make_uint4(ra0.x, ra0.y, ra0.z, ra0.w);
+        rb = make_uint2(rb0.x, rb0.y);
+    }
+    if (HAS_RES) {
+#pragma unroll
+        for (int r = 0; r < 4; r++) fetch_res_words1(rb.x, rlo, rhi, r);
+    }
+    scale_tables(hd, TL, TH);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; r++) { build_a(hd[r], TL[r], TH[r], 0, a0[r]); ia[r] = index_word24(hd[r].m[0], T0, T1, K7); }
+#pragma unroll
+    for (int tt = 0; tt < 8; tt++) bread(0, 0, tt);
+
+    // Loads of one pass, in issue order (the NR res_sign words of this pass are older than all of them):
+    //   [step 0]                           the next pass's half records (NH) and table record (NC)
+    //   [step 1, after the first barrier]  window 0 of the next pass (8)
+    //   [step 3, after the second barrier] window 1 (8) and gathered columns (NG) of the next pass
+    //   [residual step]                    res_sign words of the next pass (NR)
+    constexpr int NR = HAS_RES ? 8 : 0, NC = HAS_RES ? 2 : 0, NH = 4 * TileLoads<false>::count;
+    for (int sh = 0; sh < nsh; sh++) {
+        const int shn = sh + 1 < nsh ? sh + 1 : sh;
+        const int par = sh & 1;
+        TileRegs<N8> tn[4];
+        uint4_t ran = {0u, 0u, 0u, 0u};
+        uint2_t rbn = {0u, 0u};
+        auto nothing = [](int) {};
+        // step 0 (window 0): builds step 1, fetches the next pass's records
+        sstep(IntC<0>{}, a0, ia, [&](int r) { build_a(hd[r], TL[r], TH[r], 1, a1[r]); }, [&](int tt) { bread(0, 1, tt); },
+              [&](int tt) { if (tt % 2 == 0) fetch_hd1(shn, tn, tt / 2); if (tt == 7) fetch_rec(shn, ran, rbn); });
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR + NH + NC) : "memory");     // window 1 and the gathered columns of this pass
+        __syncthreads();                                            // ... everyone's; and everyone is done with window 0
+        // step 1: builds step 2 (window 1) and its index word, loads window 0 of the next pass
+        sstep(IntC<1>{}, a1, ia, [&](int r) { build_a(hd[r], TL[r], TH[r], 2, a0[r]); ib[r] = index_word24(hd[r].m[1], T0, T1, K7); },
+              [&](int tt) { bread(1, 0, tt); }, [&](int tt) { x_gload1(shn, 0, 0, tt); });
+        sstep(IntC<0>{}, a0, ib, [&](int r) { build_a(hd[r], TL[r], TH[r], 3, a1[r]); }, [&](int tt) { bread(1, 1, tt); }, nothing);
+        // everything in flight has arrived
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]),
+                     "+v"(ran), "+v"(rbn) : : "memory");
+#pragma unroll
+        for (int r = 0; r < 4; r++) asm volatile("s_waitcnt vmcnt(0)" : "+v"(tn[r].m), "+v"(tn[r].s), "+v"(tn[r].r), "+v"(tn[r].sc), "+v"(tn[r].ar));
+        __syncthreads();                                            // everyone is done with window 1
+        HalfData<N8> hn[4];
+        uint32_t TLn[4], THn[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) { tn[r].rlo = 0u; tn[r].rhi = 0u; unpack_tile<N8>(tn[r], shn & 1, hn[r]); }
+        scale_tables(hn, TLn, THn);
+        auto next_loads = [&](int tt) { x_gload1(shn, 1, 1, tt); if (tt >= 6) r_gload1(shn, 0, par ^ 1, tt - 6); };
+        auto reload_n = [&](int tt) { bread(0, 0, tt); };
+        if (HAS_RES) {
+            auto res_a = [&](int r) {
+                ResSel sel;
+                sel.sel0 = ra.x; sel.sel1 = ra.y; sel.bit0 = ra.z; sel.bit1 = ra.w;
+                residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], rb.x & 31u), hd[r].ar | (hd[r].ar << 16), sel, a0[r]);
+            };
+            const uint32_t gxp = gx + (uint32_t)(GM_XG + par * GM_XGSZ);
+            auto reload_g = [&](int tt) {
+                const uint4 v = *reinterpret_cast<const uint4*>(lds + tt * 1024 + gxp);
+                b[tt][0] = v.x; b[tt][1] = v.y; b[tt][2] = v.z; b[tt][3] = v.w;
+            };
+            sstep(IntC<1>{}, a1, ib, res_a, reload_g, next_loads);
+            dstep(a0, [&](int r) { build_a(hn[r], TLn[r], THn[r], 0, a1[r]); ia[r] = index_word24(hn[r].m[0], T0, T1, K7); }, reload_n,
+                  [&](int tt) { if (tt < 4) fetch_res_words1(rbn.x, rlo, rhi, tt); });
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+#pragma unroll
+                for (int v = 0; v < 4; v++) a0[r][v] = a1[r][v];
+        } else {
+            sstep(IntC<1>{}, a1, ib, [&](int r) { build_a(hn[r], TLn[r], THn[r], 0, a0[r]); }, reload_n, next_loads);
+#pragma unroll
+            for (int r = 0; r < 4; r++) ia[r] = index_word24(hn[r].m[0], T0, T1, K7);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; r++) { hd[r] = hn[r]; TL[r] = TLn[r]; TH[r] = THn[r]; }
+        ra = make_uint4(ran.x, ran.y, ran.z, ran.w);
+        rb = make_uint2(rbn.x, rbn.y);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
+
+    // ---- further records of half blocks with more than 8 salient columns (as in gemm_tiled_kernel) ----
+    if (HAS_RES && p.sal_chunks > 1) {
+      for (int sh0 = 0; sh0 < nsh; sh0 += 64) {
+        const int shl = sh0 + lane < nsh ? sh0 + lane : nsh - 1;
+        const uint32_t need_l = p.sal_tab[(((int64_t)(4 * (shl >> 1)) * 2 + (shl & 1)) * p.sal_chunks) * 12 + 5];
+        uint64_t todo = __ballot(need_l > 1u && sh0 + lane < nsh);
+        while (todo) {
+            const int sh = sh0 + __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const uint32_t* rec0 = p.sal_tab + (((int64_t)(4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 12;
+            const int nch = __builtin_amdgcn_readfirstlane((int)rec0[5]);
+            load_hd(sh, hd);
+            for (int c = 1; c < nch; c++) {
+                __syncthreads();
+                r_gload1(sh, c, 0, 0);
+                r_gload1(sh, c, 0, 1);
+                const uint4 rc = *reinterpret_cast<const uint4*>(rec0 + c * 12);
+                const uint32_t ord = rec0[c * 12 + 4];
+                load_res_words(ord, rlo, rhi);
+                asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+                __syncthreads();
+                ResSel sel;
+                sel.sel0 = rc.x; sel.sel1 = rc.y; sel.bit0 = rc.z; sel.bit1 = rc.w;
+#pragma unroll
+                for (int r = 0; r < 4; r++)
+                    residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, a1[r]);
+#pragma unroll
+                for (int tt = 0; tt < 8; tt++) {
+                    const uint4 bt = *reinterpret_cast<const uint4*>(lds + GM_XG + tt * 1024 + gx);
+                    const half8_t bv = __builtin_bit_cast(half8_t, bt);
+#pragma unroll
+                    for (int r = 0; r < 4; r++)
+                        acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(a1[r]), bv, acc[r][tt], 0, 0, 0);
+                }
             }
         }
+      }
     }
+    __syncthreads();
+    store_tile(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
 }
 
 template <int N8, bool HAS_RES>
@@ -435,6 +768,16 @@ hipError_t launch_gemm(dim3 grid, hipStream_t st, const TiledPlanes& p, const __
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, GM_LDS);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES>), grid, dim3(256), GM_LDS, st, p, X, T, Y, y_fp32, xsal, cfix);
+    return hipGetLastError();
+}
+
+template <bool HAS_RES>
+hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
+                         const __half* xsal, int cfix) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm24_kernel<HAS_RES>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GM_LDS24);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((gemm24_kernel<HAS_RES>), grid, dim3(256), GM_LDS24, st, p, X, T, Y, y_fp32, xsal, cfix);
     return hipGetLastError();
 }
 
@@ -467,7 +810,12 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
     const __half* xh = (const __half*)X;
     const __half* xs = (const __half*)workspace;
     hipError_t e;
-    if (n8 == 4) e = res ? launch_gemm<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
+    // STB_GEMM_KERNEL=dense in the environment (read at every call) keeps 2:4 layers on the dense-instruction kernel:
+    // the tests use it to run both kernels on every 2:4 case.
+    const char* which = std::getenv("STB_GEMM_KERNEL");
+    const bool sparse_ok = L->cfg.N == 2 && L->cfg.M == 4 && !(which && which[0] == 'd');
+    if (sparse_ok) e = res ? launch_gemm24<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm24<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
+    else if (n8 == 4) e = res ? launch_gemm<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
     else e = res ? launch_gemm<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
     *hip_err = (int)e;
     return e == hipSuccess ? STB_OK : STB_EHIP;

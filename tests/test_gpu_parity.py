@@ -157,6 +157,18 @@ def test_gemm_small(small_case, torch_cuda, T):
         S.stb_gemm(c["pm"].dev_layout, xd, T, yd, y_fp32, c["pm"].new_gemm_workspace(T))
         torch.cuda.synchronize()
         _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T}")
+        if c["tiled"] and (c["N"], c["M"]) == (2, 4):
+            # tiled 2:4 layers go to the sparse-instruction kernel; the dense-instruction kernel is asked for by name
+            # (the library reads the variable at every call)
+            yd.fill_(float("nan"))
+            os.environ["STB_GEMM_KERNEL"] = "dense"
+            try:
+                _say(f"[step] stb_gemm T={T} fp32={y_fp32}, dense-instruction kernel")
+                S.stb_gemm(c["pm"].dev_layout, xd, T, yd, y_fp32, c["pm"].new_gemm_workspace(T))
+                torch.cuda.synchronize()
+            finally:
+                del os.environ["STB_GEMM_KERNEL"]
+            _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T} (dense-instruction kernel)")
 
 
 def test_zero_activations_and_zero_weights(torch_cuda):
