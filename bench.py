@@ -266,12 +266,26 @@ def main():
             gemm.append(case)
             log("gemm:", gemm[-1])
             del pm, X, Y, ws
+        # what the matrix instructions themselves sustain on this GPU: one wavefront per SIMD on every compute unit,
+        # 32 independent accumulators, alone and with the three vector instructions per MFMA of the kernels' K step
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        sink = torch.empty(n_cu * 4096, dtype=torch.uint8, device="cuda")
+        steps = 2000
+        roof = {}
+        for kind, name, flop in ((0, "v_mfma_f32_16x16x32_f16", 16384.0), (1, "v_smfmac_f32_16x16x64_f16", 32768.0)):
+            for valu in (0, 3):
+                us = timed(torch, lambda r: S.stb_probe_mfma(kind, valu, steps, n_cu, sink), 3, warm=1)
+                ns = us * 1e3 / (steps * 32)
+                roof[f"{name}+{valu}valu"] = {"ns_per_instruction_per_simd": round(ns, 2),
+                                              "tflops_all_simds": round(flop * 4 * n_cu / ns / 1e3, 1)}
+        log("matrix instruction issue roof:", roof)
         best = max((g for g in gemm if g["nm"] != "2:4"), key=lambda g: g["tflops"])
         result["gemm"] = {"cases": gemm,
                           "roofline": {"bound": "mfma", "achieved": best["tflops"], "peak": MFMA_F16_PEAK_TFLOPS,
                                        "unit": "TFLOP/s", "frac": best["frac_of_f16_mfma_peak"], "traffic": None,
                                        "kernel": "gemm_tiled_kernel (stb_gemm), flops = 2*T*n*k executed on the "
-                                                 "dequantised tile"}}
+                                                 "dequantised tile"},
+                          "instruction_issue_roof": roof}
 
     # ---------------- CPU baseline: the oracle as it stands, on this machine's host cores ----------------
     if not a.no_cpu:

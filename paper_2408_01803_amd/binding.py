@@ -67,7 +67,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 _LIB = None
 
 EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_dequant", "stb_gemv",
-           "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_strerror", "stb_last_hip_error")
+           "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_strerror", "stb_last_hip_error")
 
 
 def _lib():
@@ -100,6 +100,8 @@ def _lib():
     lib.stb_gemm_workspace_bytes.restype = C.c_int64
     lib.stb_probe_read.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     lib.stb_probe_read.restype = C.c_int
+    lib.stb_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.stb_probe_mfma.restype = C.c_int
     lib.stb_strerror.argtypes = [C.c_int]
     lib.stb_strerror.restype = C.c_char_p
     lib.stb_last_hip_error.restype = C.c_int
@@ -232,6 +234,11 @@ def stb_gemm(layout_dev: stb_layout_t, X_dev, T: int, Y_dev, y_fp32: bool = Fals
 def stb_probe_read(src_dev, nbytes: int, sink_dev, stream=None) -> None:
     _check(_lib().stb_probe_read(C.c_void_p(src_dev.data_ptr()), nbytes, C.c_void_p(sink_dev.data_ptr()),
                                  C.c_void_p(_stream_ptr(stream))), "stb_probe_read")
+
+
+def stb_probe_mfma(kind: int, valu: int, steps: int, n_workgroups: int, sink_dev, stream=None) -> None:
+    _check(_lib().stb_probe_mfma(kind, valu, steps, n_workgroups, C.c_void_p(sink_dev.data_ptr()),
+                                 C.c_void_p(_stream_ptr(stream))), "stb_probe_mfma")
 
 
 def new_device_scratch(nbytes: int, device="cuda:0", zero: bool = False):

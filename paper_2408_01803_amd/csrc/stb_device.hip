@@ -290,6 +290,16 @@ extern "C" int stb_probe_read(const void* src, int64_t bytes, void* sink, void* 
     return e == hipSuccess ? STB_OK : hip_fail(e);
 }
 
+extern "C" int stb_probe_mfma(int32_t kind, int32_t valu, int32_t steps, int32_t n_workgroups, void* sink, void* stream) {
+    if (!sink) return STB_ENULL;
+    if (steps < 1 || n_workgroups < 1 || n_workgroups > 65536) return STB_EINVAL;
+    if ((uintptr_t)sink % 16) return STB_EALIGN;
+    int herr = 0;
+    const int rc = stb_tiled_probe_mfma(kind, valu, steps, n_workgroups, sink, stream, &herr);
+    if (rc == STB_EHIP) g_last_hip_error = herr;
+    return rc;
+}
+
 extern "C" int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream) {
     if (!W_hat_dev) return STB_ENULL;
     int rc = stb_layout_check(dev);

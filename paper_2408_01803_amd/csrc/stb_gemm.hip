@@ -783,6 +783,62 @@ hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const 
 
 }  // namespace
 
+// ------------------------------------------------------------------------------------------------
+// Measurement aid: the rate at which one wavefront per SIMD issues the matrix instruction of the kernels above
+// (32 independent accumulators, as a K step has them), alone or with V vector instructions after each.
+// ------------------------------------------------------------------------------------------------
+namespace {
+template <int KIND, int V>
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int steps, float4_t* __restrict__ sink) {
+    float4_t acc[32];
+#pragma unroll
+    for (int q = 0; q < 32; q++) acc[q] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    const uint32_t seed = threadIdx.x * 0x9E3779B9u + blockIdx.x;
+    uint32_t w[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) w[j] = 0x3C003C00u ^ ((seed >> j) & 0x00010001u);      // fp16 values next to 1.0
+    const uint4 av4 = make_uint4(w[0], w[1], w[2], w[3]);
+    const half8_t av = __builtin_bit_cast(half8_t, av4);
+    typedef uint32_t u8v __attribute__((ext_vector_type(8)));
+    const u8v bv8 = {w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]};
+    uint32_t x0 = seed, x1 = seed * 3u, x2 = seed * 5u;
+    const uint32_t sel = 0x05040100u + (blockIdx.x & 1u);
+    for (int it = 0; it < steps; it++) {
+#pragma unroll
+        for (int q = 0; q < 32; q++) {
+            if (KIND == 0) acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, __builtin_bit_cast(half8_t, make_uint4(w[4], w[5], w[6], w[7])), acc[q], 0, 0, 0);
+            else acc[q] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(av, __builtin_bit_cast(half16_t, bv8), acc[q], 0x44444444, 0, 0);
+            if (V >= 1) x0 = perm(x0, x1, sel);
+            if (V >= 2) x1 = perm(x1, x2, sel);
+            if (V >= 3) x2 = perm(x2, x0, sel);
+        }
+    }
+    float4_t t = acc[0];
+#pragma unroll
+    for (int q = 1; q < 32; q++) t += acc[q];
+    t[0] += (float)((x0 ^ x1 ^ x2) & 1u);
+    sink[blockIdx.x * 256 + threadIdx.x] = t;
+}
+}  // namespace
+
+extern "C" int stb_tiled_probe_mfma(int kind, int valu, int steps, int n_workgroups, void* sink, void* stream, int* hip_err) {
+    const dim3 grid(n_workgroups), wg(256);
+    const hipStream_t st = (hipStream_t)stream;
+    float4_t* out = (float4_t*)sink;
+#define STB_PROBE(K, V) hipLaunchKernelGGL((probe_mfma_kernel<K, V>), grid, wg, 0, st, steps, out)
+    if (kind == 0 && valu == 0) STB_PROBE(0, 0);
+    else if (kind == 0 && valu == 2) STB_PROBE(0, 2);
+    else if (kind == 0 && valu == 3) STB_PROBE(0, 3);
+    else if (kind == 1 && valu == 0) STB_PROBE(1, 0);
+    else if (kind == 1 && valu == 2) STB_PROBE(1, 2);
+    else if (kind == 1 && valu == 3) STB_PROBE(1, 3);
+    else return STB_EINVAL;
+#undef STB_PROBE
+    const hipError_t e = hipGetLastError();
+    *hip_err = (int)e;
+    return e == hipSuccess ? STB_OK : STB_EHIP;
+}
+
 static int64_t round_up256(int64_t v) { return (v + 255) / 256 * 256; }
 static int cfix_of(const stb_layout_t* L) { return (L->max_sal_half + 7) / 8; }
 

@@ -27,6 +27,8 @@ int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y
 int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void* Y, int y_fp32, void* workspace,
                    int64_t workspace_bytes, void* stream, int* hip_err);
 int64_t stb_tiled_gemm_workspace(const stb_layout_t* L, int T);
+// Issue-rate probe of the matrix instructions the prefill kernels use (stb_gemm.hip); see stb_probe_mfma in stb.h.
+int stb_tiled_probe_mfma(int kind, int valu, int steps, int n_workgroups, void* sink, void* stream, int* hip_err);
 #ifdef __cplusplus
 }
 #endif
