@@ -214,7 +214,11 @@ int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const voi
  * (N:M in {2:4, 4:8, 6:8}; the residual term of the salient columns is a second, short contraction against
  * the gathered salient columns of X, which the call first writes to the workspace); the row-major kind runs a
  * generic kernel for any N:M (it rounds the dequantised salient weights to fp16).
- * X: device fp16 [T][k].  Y: device [T][n], fp16 or fp32, fully overwritten.  workspace: device scratch of at
+ * Tiled 2:4 layers run on the structured-sparse matrix instruction (kept weights plus an index word as the operand,
+ * Sec. 3.1 / App. C); Environment: STB_GEMM_KERNEL=dense (read at every call) keeps them on the dense-instruction
+ * kernel that 4:8 and 6:8 layers use: for tests and comparisons.
+ * X: device fp16 [T][k], finite values (a padding column or token re-reads valid elements of X and meets zero
+ * weights or an output that is never stored).  Y: device [T][n], fp16 or fp32, fully overwritten.  workspace: device scratch of at
  * least stb_gemm_workspace_bytes() bytes, 256-byte aligned (may be NULL when that is 0); it needs no
  * initialisation.  Calls that share a workspace must not overlap in time.
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
