@@ -2,12 +2,18 @@
 //
 //   Y[t][i] = sum_j X[t][j] * W_hat[i][j]
 //
-// A workgroup of four wavefronts owns 256 output rows x 128 tokens; wavefront w owns the four 16-row tiles
-// 4w .. 4w+3 of the block.  The weights never pass through memory in dequantised form: every lane expands
-// its (row, half block) bits straight into the A operand of v_mfma_f32_16x16x32_f16 (the code of
-// stb_tiled.hpp, as in the decode kernel), so K slot g of an MFMA is 8 columns of block g of the superblock.
-// The tokens are the B operand: a window of X (128 tokens x 4 blocks x 32 columns) is staged in LDS, double
-// buffered, and every B operand read from it feeds four MFMAs (one per row tile).
+// A workgroup of four wavefronts (one per SIMD) owns 256 output rows x 128 tokens; wavefront w owns the four
+// 16-row tiles 4w .. 4w+3 of the block and their 128 accumulator registers.  The weights never pass through
+// memory in dequantised form: every lane expands its (row, half block) bits straight into the A operand of the
+// matrix instruction (the code of stb_tiled.hpp, as in the decode kernel), so K slot g of an instruction is 8 (dense)
+// or 16 (sparse) columns of block g of the superblock.  The tokens are the B operand: windows of X (128 tokens x 4
+// blocks x 32 columns) go from global memory straight to LDS, two per half block, and every B operand read from
+// them feeds four matrix instructions (one per row tile).
+// The main loop is a software pipeline of K steps: a step issues its 32 matrix instructions and, between them,
+// builds the A operands and reloads the B operands of the next step; the global loads of later steps are spread
+// over the steps as asm statements with hand-written waits.
+//   gemm_tiled_kernel  4:8 and 6:8 layers (and 2:4 on request): v_mfma_f32_16x16x32_f16 on the expanded operand
+//   gemm24_kernel      2:4 layers: v_smfmac_f32_16x16x64_f16 on the kept weights and an index word
 // The residual term of the salient columns (Eq. 4) is a second, short contraction: its A operand comes from
 // residual_chunk, its B operand from a compact copy of the salient columns of X that gemm_gather_kernel
 // writes to the workspace beforehand.
