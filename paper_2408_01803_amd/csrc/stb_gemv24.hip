@@ -23,6 +23,8 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
+#include <cstdlib>
+
 #include "stb_tiled.hpp"
 
 using namespace stbt;
@@ -218,6 +220,11 @@ __device__ inline uint32_t index_word(uint32_t m, uint32_t T0, uint32_t T1, uint
     return (hi << 4) | lo;
 }
 
+// One wavefront-wide global -> LDS load of 16 bytes per active lane: lane l's bytes land at LDS address m0 + 16 * l.
+__device__ inline void load_to_lds24(uint32_t lds_addr, uint32_t voff, const void* base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
+}
+
 struct Res24 {
     ResSel sel;
     uint32_t xs[4];     // x at the 8 salient columns of the record (B operand of the dense instruction)
@@ -225,38 +232,45 @@ struct Res24 {
     uint32_t sh;        // bit of the first entry inside the first word
 };
 
-template <int MODE, bool HAS_RES>
+template <int MODE, bool HAS_RES, bool MULTI>
 __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half* __restrict__ x, int B,
                                                       void* __restrict__ y, int y_fp32, int R, int SPS, int PHT,
-                                                      int WREG, int AREA,
+                                                      int WREG, int REC_OFF, int PART_OFF, int V_, int XS,
                                                       float* __restrict__ ws_part, uint32_t* __restrict__ ws_count) {
     __shared__ uint32_t ticket;
+    const int V = MULTI ? V_ : 1;                                // visits per wavefront (a kernel of its own for V > 1: the code is larger)
     constexpr int N8 = MODE == 6 ? 6 : 4;
     typedef typename TileOf<MODE>::type Tile;
     __shared__ uint4 lut_mem[MODE == 2 ? 1 : 256 * 8];           // dense modes: the scatter table, eight copies
     ScatterLds* const lut = reinterpret_cast<ScatterLds*>(lut_mem);
-    // Each wavefront owns a region of LDS of WREG bytes: an area of AREA bytes for its slice of x ([row][1040 bytes],
-    // B rows and one of zeros) and later, in the same place, its partial products [PHT][256] fp32; then its 8
-    // salient-column records.  A wavefront stages all of it itself, so nothing before
-    // the first reduction needs a barrier and every wavefront starts on its tiles as soon as its data is there.
+    // Each wavefront owns a region of LDS of WREG bytes: its slice of x ([row][1040 bytes], B rows and one of zeros),
+    // its 16 salient-column records at REC_OFF, its partial products [PHT][256] fp32 at PART_OFF (with one visit
+    // per wavefront: 0, on top of the x rows, which are in registers by then).  A wavefront stages all of it itself,
+    // so nothing before the first reduction needs a barrier and every wavefront starts on its tiles as soon as its
+    // data is there.
+    // V > 1 (layers with more than 8 superblocks, small batches): a wavefront visits V superblocks, sb, sb + SPS, ..,
+    // for every row tile and adds their products up in registers, so that no other workgroup holds a part of the
+    // row's sum; it keeps V slices of x (XS bytes apart) and V record sets in LDS and takes the operands of a
+    // visit from there before each product.
     extern __shared__ __attribute__((aligned(16))) char lds_base[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int i = lane & 15, g = lane >> 4;
     const int nthr = blockDim.x;                                  // 64 * SPS: one wavefront per superblock of the split
     const int gr = blockIdx.x, ks = blockIdx.y, S = gridDim.y;
-    const int sb = ks * SPS + wave;
+    const int sb = ks * SPS * V + wave;                           // superblock of the first visit
     const int r0 = gr * R;
     const int r1 = r0 + R < p.nrt ? r0 + R : p.nrt;
     const int rl = r1 - 1;
     const bool active = sb < p.nsb;                               // uniform per wavefront
-    const int Wa = p.nsb - ks * SPS < SPS ? p.nsb - ks * SPS : SPS;   // wavefronts with work
-    auto tile_of = [&](int rt) { return rt * p.nsb + sb; };
+    const int Wa = p.nsb - ks * SPS * V < SPS ? p.nsb - ks * SPS * V : SPS;   // wavefronts with work
+    auto sb_of = [&](int v) { return sb + v * SPS < p.nsb ? sb + v * SPS : sb; };       // a visit past the last superblock re-reads the first
+    auto tile_of = [&](int rt, int v = 0) { return rt * p.nsb + sb_of(v); };
     auto clamp = [&](int rt) { return rt < rl ? rt : rl; };
     const uint32_t o8 = (uint32_t)lane * 8u, o4 = (uint32_t)lane * 4u, o2 = (uint32_t)lane * 2u;
     constexpr int XROW = 1040;                                    // bytes per staged row; the 16-byte skew spreads rows over banks
     char* const wreg = lds_base + (int64_t)wave * WREG;
-    float* const part = reinterpret_cast<float*>(wreg);
-    uint32_t* const recs = reinterpret_cast<uint32_t*>(wreg + AREA);            // [block g][half] x 12
+    float* const part = reinterpret_cast<float*>(wreg + PART_OFF);
+    uint32_t* const recs = reinterpret_cast<uint32_t*>(wreg + REC_OFF);         // [visit][block g][half][record 0 / 1] x 12
     TRACE(0);
 
     if constexpr (MODE != 2) build_luts<N8>(lut);                // arithmetic only; the barrier comes after the staging
@@ -266,17 +280,71 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
     ResSel sel2[2];                                              // second record (half blocks with 9..16 salient columns)
     uint32_t xs2[2][4];
     int nch0 = 0, nch1 = 0;
+    // per visit: byte offsets of the res_sign words (half 0 low / high, half 1 low / high); separate variables and
+    // uniform branches, not an array indexed by the visit (that would live in scratch memory)
+    uint32_t ova[4] = {0u, 0u, 0u, 0u}, ovb[4] = {0u, 0u, 0u, 0u}, ovc[4] = {0u, 0u, 0u, 0u};
     Tile t0 = {}, t1 = {}, t2 = {};
     constexpr int LMAIN = TileOf<MODE>::lmain;
     constexpr int L = LMAIN + (HAS_RES ? LRES24 : 0);            // loads per tile in the streaming loop
-    auto fetch_res = [&](Tile& t, int rt) {
-        if constexpr (HAS_RES) fetch24_res(t, p, __builtin_amdgcn_readfirstlane(rt), inv[0].o0, inv[0].o1, inv[1].o0, inv[1].o1);
+    auto fetch_res = [&](Tile& t, int rt, int v) {
+        if constexpr (HAS_RES) {
+            const int rtu = __builtin_amdgcn_readfirstlane(rt);
+            if (!MULTI || v == 0) fetch24_res(t, p, rtu, ova[0], ova[1], ova[2], ova[3]);  // v is uniform
+            else if (v == 1) fetch24_res(t, p, rtu, ovb[0], ovb[1], ovb[2], ovb[3]);
+            else fetch24_res(t, p, rtu, ovc[0], ovc[1], ovc[2], ovc[3]);
+        }
     };
-    auto fetch_tile = [&](Tile& t, int rt) {
-        fetch24(t, p, tile_of(__builtin_amdgcn_readfirstlane(rt)), o8, o4, o2);
-        fetch_res(t, rt);
+    auto fetch_tile = [&](Tile& t, int rt, int v) {
+        fetch24(t, p, tile_of(__builtin_amdgcn_readfirstlane(rt), __builtin_amdgcn_readfirstlane(v)), o8, o4, o2);
+        fetch_res(t, rt, v);
     };
-    if (active) {
+    if (MULTI && active) {
+        // ---- several visits: the slices of x and the record sets go from global memory straight to LDS (no staging
+        //      registers); rows of zeros, the zero pads behind the rows and the lanes past column k are stored first ----
+        const uint4_t zero = {0u, 0u, 0u, 0u};
+        for (int v = 0; v < V; v++) {
+            const int sbv = sb + v * SPS;
+            if (sbv >= p.nsb) break;
+            char* slice = wreg + v * XS;
+            if (sbv * 512 + 512 > p.k)
+                for (int b = 0; b < B; b++) *reinterpret_cast<uint4_t*>(slice + b * XROW + lane * 16) = zero;
+            if (B < 16) *reinterpret_cast<uint4_t*>(slice + B * XROW + lane * 16) = zero;
+            if (HAS_RES && lane <= B && lane < 16) *reinterpret_cast<uint4_t*>(slice + lane * XROW + 1024) = zero;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
+        const uint32_t lds_w = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)wreg;
+        for (int v = 0; v < V; v++) {
+            const int sbv = sb + v * SPS;
+            if (sbv >= p.nsb) break;
+            const int col = sbv * 512 + lane * 8;
+            if (col < p.k)
+                for (int b = 0; b < B; b++)
+                    load_to_lds24(lds_w + v * XS + b * XROW, (uint32_t)(b * p.k + col) * 2u, x);
+            if (HAS_RES && lane < 48) {
+                const int rI = lane / 6, rc = (lane - 6 * rI) / 3, rpc = lane % 3;
+                const uint32_t off = (uint32_t)((((sbv * 8 + rI) * p.sal_chunks + (rc < p.sal_chunks ? rc : 0)) * 12 + 4 * rpc) * 4);
+                load_to_lds24(lds_w + REC_OFF + v * 768, off, p.sal_tab);
+            }
+        }
+        fetch24(t0, p, tile_of(clamp(r0)), o8, o4, o2);
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(LMAIN) : "memory");
+        if (HAS_RES && lane < 48 && lane % 3 == 2) {
+            // the pieces with the column positions become byte offsets inside a staged row (see below)
+            const uint32_t g2 = (uint32_t)(lane / 12) * (128u * 0x00010001u);
+            for (int v = 0; v < V; v++) {
+                if (sb + v * SPS >= p.nsb) break;
+                uint4_t sr = *reinterpret_cast<const uint4_t*>(&recs[v * 192 + 4 * lane]);
+#pragma unroll
+                for (int w = 0; w < 4; w++) {
+                    const uint32_t none = sr[w] & 0x80008000u;
+                    const uint32_t full = __umul24(none >> 15, 0xFFFFu);
+                    sr[w] = ((((sr[w] & 0x007F007Fu) + g2) << 1) & ~full) | (none >> 5);
+                }
+                *reinterpret_cast<uint4_t*>(&recs[v * 192 + 4 * lane]) = sr;
+            }
+        }
+    }
+    if (!MULTI && active) {
         // ---- all loads go out before the first wait: lane l brings columns 8l .. 8l+7 of the superblock for every
         //      batch row (one 16-byte load per row), lanes 0..23 the 8 records, then the res_sign words of the row
         //      tiles in 16-byte pieces, then the packed planes of the first three row tiles ----
@@ -349,12 +417,14 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         TRACE(2);
     }
     if constexpr (MODE != 2) __syncthreads();       // the scatter table is complete (every wavefront comes here)
-    if (active) {
-        // ---- the wavefront takes its B operands, its records and the x of its salient columns back from LDS (its own
-        //      stores: LDS keeps a wavefront's accesses in order) ----
+    // ---- the wavefront takes the B operands, the records and the x of the salient columns of visit v back from LDS
+    //      (its own stores: LDS keeps a wavefront's accesses in order) ----
+    auto visit_setup = [&](int v) {
+        const char* const xsl = wreg + v * XS;
+        const uint32_t* const recv = recs + v * 192;
         if constexpr (MODE == 2) {
             // B lane 16*g + n: elements 0..7 <-> block g/2, elements 8..15 <-> block 2 + g/2, columns 16*s + 8*(g%2) ..
-            const char* xrow = wreg + (i < B ? i : B) * XROW + (g >> 1) * 256 + (g & 1) * 16;
+            const char* xrow = xsl + (i < B ? i : B) * XROW + (g >> 1) * 256 + (g & 1) * 16;
 #pragma unroll
             for (int s = 0; s < 8; s++) {
                 const uint4_t lo = *reinterpret_cast<const uint4_t*>(xrow + 32 * s);
@@ -365,12 +435,12 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
             }
         } else {
             // B lane 16*g + n of step t: columns 8t .. 8t+7 of block g
-            const char* xrow = wreg + (i < B ? i : B) * XROW + g * 256;
+            const char* xrow = xsl + (i < B ? i : B) * XROW + g * 256;
 #pragma unroll
             for (int t = 0; t < 16; t++) xd[t] = __builtin_bit_cast(half8_t, *reinterpret_cast<const uint4_t*>(xrow + 16 * t));
         }
         if (HAS_RES) {
-            const char* xrow0 = wreg + (i < B ? i : B) * XROW;              // the lane's staged row of x (or the zeros)
+            const char* xrow0 = xsl + (i < B ? i : B) * XROW;               // the lane's staged row of x (or the zeros)
             auto gather = [&](const uint4_t& q, uint32_t out[4]) {          // x at the 8 byte offsets of a record
                 const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
@@ -382,7 +452,7 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
             };
 #pragma unroll
             for (int h = 0; h < 2; h++) {
-                const uint32_t* rec = &recs[(g * 2 + h) * 24];
+                const uint32_t* rec = &recv[(g * 2 + h) * 24];
                 const uint4_t ra = *reinterpret_cast<const uint4_t*>(rec);
                 const uint4_t rp = *reinterpret_cast<const uint4_t*>(rec + 8);
                 inv[h].sel.sel0 = ra.x; inv[h].sel.sel1 = ra.y; inv[h].sel.bit0 = ra.z; inv[h].sel.bit1 = ra.w;
@@ -404,12 +474,45 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
                 }
             }
         }
-        // the partial products overwrite the x rows: every read above must have returned
+    };
+    // producer side of the three tile buffers: the next (row tile, visit) to fetch, row tile first
+    int prt = r0, pv = 0;
+    auto fetch_next = [&](Tile& t) {
+        if (prt <= rl) {
+            fetch_tile(t, prt, pv);
+            if (++pv == V) { pv = 0; ++prt; }
+        } else {
+            fetch_tile(t, rl, V - 1);                // past the end: the last one again (same number of loads on every path)
+        }
+    };
+    if (active) {
+        if (!MULTI) {
+            visit_setup(0);
+            ova[0] = inv[0].o0; ova[1] = inv[0].o1; ova[2] = inv[1].o0; ova[3] = inv[1].o1;
+        } else if (HAS_RES) {
+            // the res_sign offsets of every visit (the tiles are fetched ahead of the visits' other operands)
+            auto res_offsets = [&](int v, uint32_t (&o)[4]) {
+                const int ve = sb + v * SPS < p.nsb ? v : 0;
+#pragma unroll
+                for (int h = 0; h < 2; h++) {
+                    const uint32_t ord = recs[ve * 192 + (g * 2 + h) * 24 + 4];
+                    const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+                    const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+                    o[2 * h] = (uint32_t)(wa * 16 + i) * 4u;
+                    o[2 * h + 1] = (uint32_t)(wb * 16 + i) * 4u;
+                }
+            };
+            res_offsets(0, ova);
+            res_offsets(1, ovb);
+            if (V > 2) res_offsets(2, ovc);
+        }
+        // with one visit the partial products overwrite the x rows: every read above must have returned
         __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
         __builtin_amdgcn_sched_barrier(0);
-        fetch_res(t0, clamp(r0));
-        fetch_tile(t1, clamp(r0 + 1));
-        fetch_tile(t2, clamp(r0 + 2));
+        fetch_res(t0, clamp(r0), 0);
+        if (++pv == V) { pv = 0; ++prt; }            // t0 holds (r0, visit 0)
+        fetch_next(t1);
+        fetch_next(t2);
         TRACE(4);
     }
 
@@ -429,10 +532,10 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
 
     // One (row tile, superblock): the steps over the block's columns (sparse: 8 of 16 columns; dense: 16 of 8), then
     // the residual term of the two halves.
+    float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};         // sum over the visits of the current row tile
     auto product = [&](Tile& tr, int rt, int slot) {
         const uint32_t TL = perm(tr.sc[1], tr.sc[0], 0x06040200u), TH = perm(tr.sc[1], tr.sc[0], 0x07050301u);
         const uint32_t mw[4] = {tr.m0[0], tr.m0[1], tr.m1[0], tr.m1[1]};
-        float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
         if constexpr (MODE == 2) {
             const uint32_t rw[4] = {tr.r0[0], tr.r0[1], tr.r1[0], tr.r1[1]};
             const uint32_t sw[2] = {tr.s0, tr.s1};
@@ -497,15 +600,18 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
                 }
             }
         }
+    };
+    auto store_partial = [&](int slot) {
         float* dst = part + (slot * 256 + lane);
 #pragma unroll
         for (int v = 0; v < 4; v++) dst[64 * v] = acc[v];
+        acc = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
     };
 
     // Half blocks with more than 16 salient columns: the records after the second, outside the streaming loop (rare).
-    auto extra_records = [&](int rt, int slot) {
+    auto extra_records = [&](int rt, int v) {
         const int64_t rstride = (int64_t)p.res_words * 16;
-        const int q = 4 * sb + g;
+        const int q = 4 * sb_of(v) + g;
         const bool live = i < B && q < p.nb;
         const unsigned short* xg = reinterpret_cast<const unsigned short*>(x + (int64_t)(i < B ? i : B - 1) * p.k + (int64_t)(q < p.nb ? q : 0) * 128);
         float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -513,7 +619,7 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
             const int nc = h == 0 ? nch0 : nch1;
             if (nc <= 2) continue;
             HalfData<N8> d;
-            load_half<N8>(p, (int64_t)tile_of(rt), lane_offsets<N8>(lane, h), h, d);
+            load_half<N8>(p, (int64_t)tile_of(rt, v), lane_offsets<N8>(lane, h), h, d);
             const uint32_t ar2 = d.ar | (d.ar << 16);
             for (int c = 2; c < nc; c++) {
                 const uint32_t* rec = p.sal_tab + (((int64_t)q * 2 + h) * p.sal_chunks + c) * 12;
@@ -536,9 +642,7 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(o), as_half8(xs4), acc, 0, 0, 0);
             }
         }
-        float* dst = part + (slot * 256 + lane);
-#pragma unroll
-        for (int v = 0; v < 4; v++) dst[64 * v] += acc[v];
+        return acc;
     };
 
     // The R row tiles are taken in phases of PHT (a multiple of 3 unless it is R itself): the wavefronts stream
@@ -549,25 +653,33 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         const int ph0 = r0 + ph;
         const int ph1 = ph0 + PHT < r1 ? ph0 + PHT : r1;
         if (active) {
-            for (int rt = ph0; rt < ph1; rt += 3) {
-                wait24_main<2 * L + (HAS_RES ? LRES24 : 0)>(t0);
-                TRACE(8 + (rt - r0 < 5 ? rt - r0 : 5));
-                product(t0, rt, rt - ph0);
-                TRACE(14 + (rt - r0 < 5 ? rt - r0 : 5));
-                fetch_tile(t0, clamp(rt + 3));
-                wait24_main<2 * L + (HAS_RES ? LRES24 : 0)>(t1);
-                TRACE(8 + (rt + 1 - r0 < 5 ? rt + 1 - r0 : 5));
-                if (rt + 1 < ph1) product(t1, rt + 1, rt + 1 - ph0);
-                TRACE(14 + (rt + 1 - r0 < 5 ? rt + 1 - r0 : 5));
-                fetch_tile(t1, clamp(rt + 4));
-                wait24_main<2 * L + (HAS_RES ? LRES24 : 0)>(t2);
-                TRACE(8 + (rt + 2 - r0 < 5 ? rt + 2 - r0 : 5));
-                if (rt + 2 < ph1) product(t2, rt + 2, rt + 2 - ph0);
-                TRACE(14 + (rt + 2 - r0 < 5 ? rt + 2 - r0 : 5));
-                fetch_tile(t2, clamp(rt + 5));
+            // consumer side of the three tile buffers: the (row tile, visit) of the next product.  A row tile's sum is
+            // stored after its last visit; a step past the phase's last tile only keeps the fetches going.
+            int crt = ph0, cv = 0;
+            auto step = [&](Tile& t) {
+                wait24_main<2 * L + (HAS_RES ? LRES24 : 0)>(t);
+                if (crt < ph1) {
+                    if (sb + cv * SPS < p.nsb) {
+                        if (MULTI) visit_setup(cv);
+                        product(t, crt, crt - ph0);
+                        if (MULTI && HAS_RES && (nch0 > 2 || nch1 > 2)) acc += extra_records(crt, cv);
+                    }
+                    if (++cv == V) { store_partial(crt - ph0); cv = 0; ++crt; }
+                }
+                fetch_next(t);
+            };
+            while (crt < ph1) {
+                step(t0);
+                step(t1);
+                step(t2);
             }
-            if (HAS_RES && (nch0 > 2 || nch1 > 2))
-                for (int rt = ph0; rt < ph1; rt++) extra_records(rt, rt - ph0);
+            if (!MULTI && HAS_RES && (nch0 > 2 || nch1 > 2))
+                for (int rt = ph0; rt < ph1; rt++) {
+                    const float4_t e = extra_records(rt, 0);
+                    float* dst = part + ((rt - ph0) * 256 + lane);
+#pragma unroll
+                    for (int v = 0; v < 4; v++) dst[64 * v] += e[v];
+                }
         }
         TRACE(6);
         __syncthreads();
@@ -577,7 +689,7 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         for (int o = threadIdx.x; o < total; o += nthr) {
             const int r16 = o & 15, j = div_b(o >> 4), b = (o >> 4) - j * B;
             const int l = b + 16 * (r16 >> 2), v = r16 & 3;
-            const char* src = lds_base + (j * 256 + 64 * v + l) * 4;
+            const char* src = lds_base + PART_OFF + (j * 256 + 64 * v + l) * 4;
             float t[8];
 #pragma unroll
             for (int w = 0; w < 8; w++) t[w] = w < Wa ? *reinterpret_cast<const float*>(src + (int64_t)w * WREG) : 0.0f;   // fixed order of adds
@@ -624,14 +736,14 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
     }
 }
 
-template <int MODE, bool HAS_RES>
-hipError_t launch24(const TiledPlanes& p, const __half* x, int B, void* y, int y_fp32, int R, int SPS, int PHT, int wreg, int area,
-                    dim3 grid, float* ws_part, uint32_t* ws_count, hipStream_t st) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv24_kernel<MODE, HAS_RES>,
+template <int MODE, bool HAS_RES, bool MULTI>
+hipError_t launch24(const TiledPlanes& p, const __half* x, int B, void* y, int y_fp32, int R, int SPS, int PHT, int wreg, int rec_off,
+                    int part_off, int V, int xs, dim3 grid, float* ws_part, uint32_t* ws_count, hipStream_t st) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv24_kernel<MODE, HAS_RES, MULTI>,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS24 - (MODE == 2 ? 0 : 32768));
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((gemv24_kernel<MODE, HAS_RES>), grid, dim3(64 * SPS), (size_t)SPS * wreg, st, p, x, B, y, y_fp32, R, SPS, PHT,
-                       wreg, area, ws_part, ws_count);
+    hipLaunchKernelGGL((gemv24_kernel<MODE, HAS_RES, MULTI>), grid, dim3(64 * SPS), (size_t)SPS * wreg, st, p, x, B, y, y_fp32, R, SPS, PHT,
+                       wreg, rec_off, part_off, V, xs, ws_part, ws_count);
     return hipGetLastError();
 }
 
@@ -650,26 +762,43 @@ extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, voi
     if (L->region_bytes >= (1ll << 31) || L->res_bytes >= (1ll << 31)) return STB_EUNSUPPORTED;   // 32-bit offsets inside a plane
     const TiledPlanes p = make_tiled(L);
     const int64_t lds_max = LDS24 - (mode == 2 ? 0 : 32768);
-    // Column splits of SPS <= 8 superblocks (one wavefront each); a workgroup owns R row tiles.  Among the split
-    // counts whose LDS fits, take the one with the lowest estimated time: R tiles for each of the ceil(SPS / 4)
-    // wavefronts of a SIMD (measured: ~0.75 us per (row tile, superblock) product on the sparse instruction, ~1 us
-    // on the dense one), times the rounds the grid needs on 256 compute units, plus ~0.09 us per split and batch row
-    // for adding the splits up through the workspace; ties go to the fewest splits.
-    // LDS of one wavefront: the larger of (B rows of x and one of zeros, 1040 bytes each) and (PHT partial tiles),
-    // then its 16 records (two per half block).
+    // Column splits of SPS <= 8 wavefronts; a wavefront takes V superblocks (V = 1: its own; V = 2, 3: it visits
+    // them one after the other for every row tile); a workgroup owns R row tiles.  Among the shapes whose LDS fits,
+    // take the one with the lowest estimated time, in ns: per (row tile, superblock) product ~750 on the sparse
+    // instruction, ~1000 on the dense one, ~200 more when the operands of a visit have to be taken from LDS first;
+    // R * V products for each of the ceil(SPS / 4) wavefronts of a SIMD, times the rounds the grid needs on 256
+    // compute units; adding the column splits up through the workspace costs ~2000 plus ~90 per split and batch
+    // row.  Ties go to the fewest splits.
+    // LDS of one wavefront: per visit the x rows (B rows and one of zeros, 1040 bytes each) and 16 records; the PHT
+    // partial tiles lie on top of the x rows when there is one visit, behind everything otherwise.
     const int xbytes = (B < 16 ? B + 1 : 16) * 1040;
-    int S = 0, R = 0, SPS = 0, wreg = 0, area = 0;
+    int S = 0, R = 0, SPS = 0, V = 0, wreg = 0, rec_off = 0, part_off = 0;
     int64_t best_cost = 0;
-    for (int s = (p.nsb + 7) / 8; s <= max_splits && s <= p.nsb; s++) {
-        const int sps = (p.nsb + s - 1) / s;
-        if (sps > 8 || (s - 1) * sps >= p.nsb) continue;           // a split must own at least one superblock
-        const int groups = 256 / s > 0 ? 256 / s : 1;
-        const int r = (p.nrt + groups - 1) / groups, g = (p.nrt + r - 1) / r;
-        const int pht = r < PHASE24 ? r : PHASE24;
-        const int ar = xbytes > pht * 1024 ? xbytes : pht * 1024;
-        if ((int64_t)sps * (ar + 768) > lds_max) continue;
-        const int64_t cost = (int64_t)(mode == 2 ? 750 : 1000) * r * ((sps + 3) / 4) * ((g * s + 255) / 256) + (s > 1 ? (int64_t)90 * s * B : 0);
-        if (S == 0 || cost < best_cost) { best_cost = cost; S = s; R = r; SPS = sps; area = ar; wreg = ar + 768; }
+    // STB_GEMV_VISITS=2 or 3 in the environment (read at every call) restricts the choice to that many visits where
+    // such a shape exists: the tests use it, because small layers never choose several visits themselves.
+    const char* vis = std::getenv("STB_GEMV_VISITS");
+    const int v_only = vis && (vis[0] == '2' || vis[0] == '3') && p.nsb >= vis[0] - '0' ? vis[0] - '0' : 0;
+    for (int v = 1; v <= 3; v++) {
+        if (v_only && v != v_only) continue;
+        for (int s = (p.nsb + 8 * v - 1) / (8 * v); s <= max_splits && s * v <= p.nsb; s++) {
+            const int sps = (p.nsb + s * v - 1) / (s * v);
+            if (sps > 8 || (s - 1) * sps * v >= p.nsb) continue;   // a split must own at least one superblock
+            if ((s * v - 1) * sps >= p.nsb) continue;              // ... and so must the last visit of the last split
+            const int groups = 256 / s > 0 ? 256 / s : 1;
+            const int r = (p.nrt + groups - 1) / groups, g = (p.nrt + r - 1) / r;
+            const int pht = r < PHASE24 ? r : PHASE24;
+            int w, ro, po;
+            if (v == 1) {
+                const int ar = xbytes > pht * 1024 ? xbytes : pht * 1024;
+                ro = ar; po = 0; w = ar + 768;
+            } else {
+                ro = v * xbytes; po = ro + v * 768; w = po + pht * 1024;
+            }
+            if ((int64_t)sps * w > lds_max) continue;
+            const int64_t cost = (int64_t)((mode == 2 ? 750 : 1000) + (v > 1 ? 200 : 0)) * r * v * ((sps + 3) / 4) * ((g * s + 255) / 256)
+                                 + (s > 1 ? 2000 + (int64_t)90 * s * B : 0);
+            if (S == 0 || cost < best_cost) { best_cost = cost; S = s; R = r; SPS = sps; V = v; wreg = w; rec_off = ro; part_off = po; }
+        }
     }
     if (S == 0) return STB_EUNSUPPORTED;
     const int G = (p.nrt + R - 1) / R;
@@ -686,12 +815,14 @@ extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, voi
     const dim3 grid(G, S);
     const hipStream_t st = (hipStream_t)stream;
     hipError_t e;
-#define STB24_GO(MODE) (res ? launch24<MODE, true>(p, xh, B, y, y_fp32, R, SPS, PHT, wreg, area, grid, part, cnt, st) \
-                            : launch24<MODE, false>(p, xh, B, y, y_fp32, R, SPS, PHT, wreg, area, grid, part, cnt, st))
+#define STB24_ARGS p, xh, B, y, y_fp32, R, SPS, PHT, wreg, rec_off, part_off, V, xbytes, grid, part, cnt, st
+#define STB24_GO(MODE) (V > 1 ? (res ? launch24<MODE, true, true>(STB24_ARGS) : launch24<MODE, false, true>(STB24_ARGS)) \
+                              : (res ? launch24<MODE, true, false>(STB24_ARGS) : launch24<MODE, false, false>(STB24_ARGS)))
     if (mode == 2) e = STB24_GO(2);
     else if (mode == 4) e = STB24_GO(4);
     else e = STB24_GO(6);
 #undef STB24_GO
+#undef STB24_ARGS
     *hip_err = (int)e;
     return e == hipSuccess ? STB_OK : STB_EHIP;
 }

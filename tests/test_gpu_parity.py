@@ -142,6 +142,19 @@ def test_gemv_small(small_case, torch_cuda, B, y_fp32):
         finally:
             del os.environ["STB_GEMV_KERNEL"]
         _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemv B={B} (thin-wavefront kernel)")
+        # ... and small layers never choose several superblock visits per wavefront themselves
+        for visits in ("2", "3"):
+            if (c["k"] + 511) // 512 < int(visits) or B > 16:
+                continue
+            yd.fill_(float("nan"))
+            os.environ["STB_GEMV_VISITS"] = visits
+            try:
+                _say(f"[step] stb_gemv B={B} fp32={y_fp32}, {visits} visits per wavefront")
+                S.stb_gemv(c["pm"].dev_layout, xd, B, yd, y_fp32, c["pm"].workspace)
+                torch.cuda.synchronize()
+            finally:
+                del os.environ["STB_GEMV_VISITS"]
+            _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemv B={B} ({visits} visits per wavefront)")
 
 
 @pytest.mark.parametrize("T", [1, 63, 64, 200, 333])
