@@ -186,12 +186,14 @@ int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream);
  * x: device fp16 [B][k] row-major.  y: device [B][n] row-major, fp16 (y_fp32 = 0) or fp32 (y_fp32 = 1),
  * fully overwritten.  Accumulation is fp32.
  * workspace: device scratch of at least stb_gemv_workspace_bytes() bytes, 256-byte aligned (may be NULL when
- * that is 0).  It holds the partial sums and arrival counters of the column splits (always used when
- * k > 4096; for smaller k the launcher may still split columns to balance the grid).  The
+ * that is 0).  It holds the partial sums and arrival counters of the column splits (used by most layers
+ * with k > 4096; for smaller k the launcher may still split columns to balance the grid).  The
  * counters (its first 4 * ceil(n / 16) bytes) must be zero before the first call that uses the buffer; every
  * call leaves them zero.  Calls that share a workspace must not overlap in time.
  * Environment: STB_GEMV_KERNEL=thin (read at every call) makes the tiled kind use its older kernel with thin
- * wavefronts, which otherwise only runs when the LDS areas of the default kernel do not fit; for tests.
+ * wavefronts, which otherwise only runs when the LDS areas of the default kernel do not fit; STB_GEMV_VISITS=2
+ * or 3 makes the default kernel take that many superblocks per wavefront where the layer has as many (it chooses
+ * that by itself for wide layers at small batches, instead of column splits).  Both are for tests.
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
 int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32,
              void* workspace, int64_t workspace_bytes, void* stream);
