@@ -36,7 +36,7 @@ POOL_BYTES = 1 << 30
 # HBM bytes per decode launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this command, scaled by what
 # the same counters read for a copy of known size; see profiles/gemv24_workload2_decode.md.
 # Average over the six launches of a step (read + written).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 19.6e6
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 19.5e6
 
 
 def log(*a):
