@@ -25,16 +25,25 @@ using namespace stbt;
 
 namespace {
 
-constexpr int GM_TOK = 128;           // tokens per workgroup
+// Tokens per workgroup: 16 * TT, TT token tiles per wavefront (a multiple of 4).
+
 constexpr int GM_ROWT = 16;           // 16-row tiles per workgroup (four per wavefront)
 // LDS of the main kernel (dynamic, carved by hand so that the positions are fixed):
+//   (sizes for 128 tokens; they grow with the tile)
 //   [0, 64 KB)    two X windows: 128 token rows x 256 bytes (4 blocks x 32 columns); the 16-byte piece p of row r
 //                 sits at position p ^ (r % 16), so the 16 lanes that read one piece of 16 consecutive rows (a B
 //                 operand) hit 16 different positions and a wavefront's global->LDS load fills 4 whole rows
 //   [64, 80 KB)   gathered salient columns, by parity of the pass: 128 rows x 64 bytes, piece g of row r at
 //                 position g ^ ((r / 4) % 4)
 //   [80, 112 KB)  the scatter table
-constexpr int GM_XW = 0, GM_XWSZ = 32768, GM_XG = 65536, GM_XGSZ = 8192, GM_LUT = 81920, GM_LDS = 81920 + 32768;
+template <int TT>
+struct GmLds {
+    static constexpr int TOK = 16 * TT;
+    static constexpr int XW = 0, XWSZ = TOK * 256, XG = 2 * XWSZ, XGSZ = TOK * 64, LUT = XG + 2 * XGSZ;
+    static constexpr int TOTAL = LUT + 32768;      // with the scatter table (dense kernel)
+    static constexpr int TOTAL24 = LUT;            // without (sparse kernel)
+};
+constexpr int GM_TT = 8, GM_TT24 = 8;       // (12 in the dense kernel was tried: 192 accumulators leave too few registers, the compiler spills)
 
 // Workspace: xsal[T][E] fp16, E = nsb * 2 * cfix * 32; entry ((sb*2 + half)*cfix + c)*32 + g*8 + e holds X at the
 // e-th salient column of record c of (block 4*sb + g, half), 0 where the record has no such entry.
@@ -65,7 +74,8 @@ template <int V> struct IntC { static constexpr int value = V; };
 
 // Writes a wavefront's 64 rows x 128 tokens: D[row][token] of an MFMA, lane l holds token l % 16, rows 4*(l / 16) + v.
 // (The caller has passed a barrier after the last use of LDS.)
-__device__ inline void store_tile(const float4_t (&acc)[4][8], char* lds, const TiledPlanes& p, void* __restrict__ Y, int y_fp32,
+template <int TT>
+__device__ inline void store_tile(const float4_t (&acc)[4][TT], char* lds, const TiledPlanes& p, void* __restrict__ Y, int y_fp32,
                                   int T, int t0, int rtw, int wave, int lane) {
     const int i = lane & 15, g = lane >> 4;
     // fp16 output whose rows of Y can be written in 16-byte pieces: the wavefront transposes its 64 rows x 128 tokens
@@ -73,11 +83,11 @@ __device__ inline void store_tile(const float4_t (&acc)[4][8], char* lds, const 
     // of Y (8 tokens x the wavefront's 64 rows) instead of 32-byte pieces.
     const bool wide = !y_fp32 && (p.n & 7) == 0 && ((uintptr_t)Y & 15) == 0 && (rtw + 4) * 16 <= p.n;     // uniform per wavefront
     if (wide) {
-        char* const ep = lds + wave * (GM_TOK * 144);
+        char* const ep = lds + wave * (16 * TT * 144);
 #pragma unroll
         for (int r = 0; r < 4; r++)
 #pragma unroll
-            for (int tt = 0; tt < 8; tt++) {
+            for (int tt = 0; tt < TT; tt++) {
                 const __half2 lo = __floats2half2_rn(-acc[r][tt][0], -acc[r][tt][1]);
                 const __half2 hi = __floats2half2_rn(-acc[r][tt][2], -acc[r][tt][3]);
                 uint2 v;
@@ -88,7 +98,7 @@ __device__ inline void store_tile(const float4_t (&acc)[4][8], char* lds, const 
         // (the wavefront reads back only what it wrote itself: LDS keeps a wavefront's accesses in order)
         __half* const Yh = reinterpret_cast<__half*>(Y);
 #pragma unroll
-        for (int it = 0; it < 16; it++) {
+        for (int it = 0; it < 2 * TT; it++) {
             const int tl = 8 * it + (lane >> 3), tok = t0 + tl;
             const uint4 v = *reinterpret_cast<const uint4*>(ep + tl * 144 + (lane & 7) * 16);
             if (tok < T) *reinterpret_cast<uint4*>(Yh + (int64_t)tok * p.n + rtw * 16 + (lane & 7) * 8) = v;
@@ -100,7 +110,7 @@ __device__ inline void store_tile(const float4_t (&acc)[4][8], char* lds, const 
         const int row = (rtw + r) * 16 + 4 * g;
         if (rtw + r >= p.nrt) continue;
 #pragma unroll
-        for (int tt = 0; tt < 8; tt++) {
+        for (int tt = 0; tt < TT; tt++) {
             const int tok = t0 + 16 * tt + i;
             if (tok >= T) continue;
 #pragma unroll
@@ -124,21 +134,23 @@ template <int N8, bool HAS_RES>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                           void* __restrict__ Y, int y_fp32,
                                                           const __half* __restrict__ xsal, int cfix) {
+    constexpr int TT = GM_TT;
+    typedef GmLds<TT> G;
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    ScatterLds& lut = *reinterpret_cast<ScatterLds*>(lds + GM_LUT);
+    ScatterLds& lut = *reinterpret_cast<ScatterLds*>(lds + G::LUT);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;     // LDS address of lds[0]
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int i = lane & 15, g = lane >> 4;
-    const int t0 = blockIdx.x * GM_TOK;
+    const int t0 = blockIdx.x * G::TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;                // first row tile of this wavefront
     const int nsh = p.nsb * 2;                                      // (superblock, half) pairs
     build_luts<N8>(&lut);
 
-    float4_t acc[4][8];
+    float4_t acc[4][TT];
 #pragma unroll
     for (int r = 0; r < 4; r++)
 #pragma unroll
-        for (int tt = 0; tt < 8; tt++) acc[r][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        for (int tt = 0; tt < TT; tt++) acc[r][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
     // Every global load of the main loop is an asm statement, and every use sits behind a vmcnt wait written by
     // hand (for loads into registers the wait names them, the rules of the fetch helpers in stb_tiled.hpp): the
@@ -159,31 +171,32 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     const __half* const Xt = X + (int64_t)t0 * p.k;
     auto x_gload1 = [&](int sh, int win, int buf, int u) {          // load u (0..7) of the wavefront's share of a window
         const uint32_t wcol = (uint32_t)((sh >> 1) * 1024 + (sh & 1) * 128 + win * 64);      // bytes inside a token row
-        const uint32_t dst = lds0 + GM_XW + buf * GM_XWSZ + wave * 8192;
+        const uint32_t dst = lds0 + G::XW + buf * G::XWSZ + wave * (TT * 1024);
         const uint32_t c = xpc[u & 3] + wcol;
-        const uint32_t row = (uint32_t)(4 * (8 * wave + u)) + (uint32_t)g;
+        const uint32_t row = (uint32_t)(4 * (TT * wave + u)) + (uint32_t)g;
         load_to_lds(dst + u * 1024, __umul24(row < tok_last ? row : tok_last, k2) + (c < k2 - 16u ? c : k2 - 16u), Xt);
     };
     auto x_gload = [&](int sh, int win, int buf) {
 #pragma unroll
-        for (int u = 0; u < 8; u++) x_gload1(sh, win, buf, u);
+        for (int u = 0; u < TT; u++) x_gload1(sh, win, buf, u);
     };
     // the gathered salient columns of (superblock, half) sh, record c: 8 wavefront loads of 16 token rows, 2 per
     // wavefront; lane l = row l / 4 of them, position l % 4 = piece (l % 4) ^ ((row / 4) % 4)
     const int64_t E = (int64_t)p.nsb * 2 * cfix * 32;               // halves per token in xsal
     const __half* const xsal_t = xsal + (int64_t)t0 * E;
-    uint32_t grow[2];
+    constexpr int NGL = TT / 4;                                     // gathered-column loads per wavefront (16 token rows each)
+    uint32_t grow[NGL];
 #pragma unroll
-    for (int u = 0; u < 2; u++) {
-        const uint32_t row = (uint32_t)(16 * (2 * wave + u) + (lane >> 2));
+    for (int u = 0; u < NGL; u++) {
+        const uint32_t row = (uint32_t)(16 * (NGL * wave + u) + (lane >> 2));
         grow[u] = (row < tok_last ? row : tok_last) * (uint32_t)E * 2u + (((uint32_t)lane & 3u) ^ (((uint32_t)lane >> 4) & 3u)) * 16u;
     }
     auto r_gload1 = [&](int sh, int c, int par, int u) {
-        if (HAS_RES) load_to_lds(lds0 + GM_XG + par * GM_XGSZ + (2 * wave + u) * 1024, grow[u] + (uint32_t)(sh * cfix + c) * 64u, xsal_t);
+        if (HAS_RES) load_to_lds(lds0 + G::XG + par * G::XGSZ + (NGL * wave + u) * 1024, grow[u] + (uint32_t)(sh * cfix + c) * 64u, xsal_t);
     };
     auto r_gload = [&](int sh, int c, int par) {
 #pragma unroll
-        for (int u = 0; u < 2; u++) r_gload1(sh, c, par, u);
+        for (int u = 0; u < NGL; u++) r_gload1(sh, c, par, u);
     };
     auto load_hd = [&](int sh, HalfData<N8> (&hd)[4]) {
         const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
@@ -256,10 +269,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     //      their shadow the lane builds the A operands of the next step (`next_a(r)` for row tile r) and, as soon
     //      as the four MFMAs of a token tile have been issued, reloads that tile's B operand for the next step
     //      (`next_b(tt)`).  `extra()` is the step's share of the staging work. ----
-    uint4 b[8];
+    uint4 b[TT];
     auto kstep = [&](const uint32_t (&ac)[4][4], auto&& next_a, auto&& next_b, auto&& extra) {
 #pragma unroll
-        for (int tt = 0; tt < 8; tt++) {
+        for (int tt = 0; tt < TT; tt++) {
             const half8_t bv = __builtin_bit_cast(half8_t, b[tt]);
 #pragma unroll
             for (int r = 0; r < 4; r++)
@@ -272,7 +285,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         // shadow: an LDS read while there are any, three vector instructions
 #ifndef GM_NOSGB
 #pragma unroll
-        for (int q = 0; q < 32; q++) {
+        for (int q = 0; q < 4 * TT; q++) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // LDS read
             __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);       // VALU
@@ -280,11 +293,13 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
 #endif
     };
     // B operand of token tile tt: rows 16 tt + i, piece 4 g + tq, at position piece ^ i
-    uint32_t bx[4];
+    uint32_t bx[2][4];                                              // per window buffer (the offset of a token tile is an immediate)
 #pragma unroll
-    for (int tq = 0; tq < 4; tq++) bx[tq] = (uint32_t)(i * 256 + ((4 * g + tq) ^ i) * 16);
+    for (int buf = 0; buf < 2; buf++)
+#pragma unroll
+        for (int tq = 0; tq < 4; tq++) bx[buf][tq] = (uint32_t)(G::XW + buf * G::XWSZ + i * 256 + ((4 * g + tq) ^ i) * 16);
     auto bread = [&](int buf, int tq, int tt) {
-        b[tt] = *reinterpret_cast<const uint4*>(lds + GM_XW + buf * GM_XWSZ + tt * 4096 + bx[tq]);
+        b[tt] = *reinterpret_cast<const uint4*>(lds + tt * 4096 + bx[buf][tq]);
     };
     const uint32_t gx = (uint32_t)(i * 64 + (g ^ ((i >> 2) & 3)) * 16);
 
@@ -321,7 +336,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
 #pragma unroll
     for (int r = 0; r < 4; r++) expand_group<N8>(hd[r], TL[r], TH[r], 0, lut_fetch<N8>(hd[r], 0, &lut, lane & 7), a0[r]);
 #pragma unroll
-    for (int tt = 0; tt < 8; tt++) bread(0, 0, tt);
+    for (int tt = 0; tt < TT; tt++) bread(0, 0, tt);
 
     // Loads of one pass, in issue order (NR res_sign words of this pass are older than all of them):
     //   [step 3, after the first barrier]  window 0 of the next pass (8)
@@ -369,7 +384,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             return [&](int r) { expand_group<N8>(hn[r], TLn[r], THn[r], 0, lut_fetch<N8>(hn[r], 0, &lut, lane & 7), an[r]); };
         };
         auto reload_n = [&](int tt) { bread(0, 0, tt); };
-        auto next_loads = [&](int tt) { x_gload1(shn, 1, 1, tt); if (tt >= 6) r_gload1(shn, 0, par ^ 1, tt - 6); };
+        auto next_loads = [&](int tt) { x_gload1(shn, 1, 1, tt); if (tt >= TT - NGL) r_gload1(shn, 0, par ^ 1, tt - (TT - NGL)); };
         if (HAS_RES) {
             // residual contraction (Eq. 4) of the first 8 salient columns of every half block: A from the mask and
             // res_sign bits, B = the gathered columns.  (A half block without salient columns has an all-zero A.)
@@ -378,7 +393,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
                 sel.sel0 = ra.x; sel.sel1 = ra.y; sel.bit0 = ra.z; sel.bit1 = ra.w;
                 residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], rb.x & 31u), hd[r].ar | (hd[r].ar << 16), sel, a0[r]);
             };
-            const uint32_t gxp = gx + (uint32_t)(GM_XG + par * GM_XGSZ);
+            const uint32_t gxp = gx + (uint32_t)(G::XG + par * G::XGSZ);
             auto reload_g = [&](int tt) { b[tt] = *reinterpret_cast<const uint4*>(lds + tt * 1024 + gxp); };
             kstep(a1, res_a, reload_g, next_loads);
             // (the res_sign words of the next pass: its table record arrived before the barrier above)
@@ -427,8 +442,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
                 for (int r = 0; r < 4; r++)
                     residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, a1[r]);
 #pragma unroll
-                for (int tt = 0; tt < 8; tt++) {
-                    const uint4 bt = *reinterpret_cast<const uint4*>(lds + GM_XG + tt * 1024 + gx);
+                for (int tt = 0; tt < TT; tt++) {
+                    const uint4 bt = *reinterpret_cast<const uint4*>(lds + G::XG + tt * 1024 + gx);
                     const half8_t bv = __builtin_bit_cast(half8_t, bt);
 #pragma unroll
                     for (int r = 0; r < 4; r++)
@@ -440,7 +455,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     }
 
     __syncthreads();                                                // every wavefront is done with LDS
-    store_tile(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
+    store_tile<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -452,7 +467,6 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
 // ------------------------------------------------------------------------------------------------
 typedef _Float16 half16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t uint8_t32 __attribute__((ext_vector_type(8)));
-constexpr int GM_LDS24 = 81920;       // the two windows and the gathered columns; no scatter table
 
 // Index register for 32 columns: every mask nibble (two bits set) becomes the positions of its two kept weights,
 // low one in bits 1:0, high one in bits 3:2, looked up in an 8-byte table by (nibble >> 1) & 7.
@@ -468,19 +482,21 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
                                                       void* __restrict__ Y, int y_fp32,
                                                       const __half* __restrict__ xsal, int cfix) {
     constexpr int N8 = 4;
+    constexpr int TT = GM_TT24;
+    typedef GmLds<TT> G;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int i = lane & 15, g = lane >> 4;
-    const int t0 = blockIdx.x * GM_TOK;
+    const int t0 = blockIdx.x * G::TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;
     const int nsh = p.nsb * 2;
 
-    float4_t acc[4][8];
+    float4_t acc[4][TT];
 #pragma unroll
     for (int r = 0; r < 4; r++)
 #pragma unroll
-        for (int tt = 0; tt < 8; tt++) acc[r][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        for (int tt = 0; tt < TT; tt++) acc[r][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
     // ---- global -> LDS loads of the X windows and the gathered columns: as in gemm_tiled_kernel ----
     const uint32_t tok_last = (uint32_t)(T - 1 - t0), k2 = (uint32_t)p.k * 2u;
@@ -493,21 +509,22 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     const __half* const Xt = X + (int64_t)t0 * p.k;
     auto x_gload1 = [&](int sh, int win, int buf, int u) {
         const uint32_t wcol = (uint32_t)((sh >> 1) * 1024 + (sh & 1) * 128 + win * 64);
-        const uint32_t dst = lds0 + GM_XW + buf * GM_XWSZ + wave * 8192;
+        const uint32_t dst = lds0 + G::XW + buf * G::XWSZ + wave * (TT * 1024);
         const uint32_t c = xpc[u & 3] + wcol;
-        const uint32_t row = (uint32_t)(4 * (8 * wave + u)) + (uint32_t)g;
+        const uint32_t row = (uint32_t)(4 * (TT * wave + u)) + (uint32_t)g;
         load_to_lds(dst + u * 1024, __umul24(row < tok_last ? row : tok_last, k2) + (c < k2 - 16u ? c : k2 - 16u), Xt);
     };
     const int64_t E = (int64_t)p.nsb * 2 * cfix * 32;
     const __half* const xsal_t = xsal + (int64_t)t0 * E;
-    uint32_t grow[2];
+    constexpr int NGL = TT / 4;                                     // gathered-column loads per wavefront (16 token rows each)
+    uint32_t grow[NGL];
 #pragma unroll
-    for (int u = 0; u < 2; u++) {
-        const uint32_t row = (uint32_t)(16 * (2 * wave + u) + (lane >> 2));
+    for (int u = 0; u < NGL; u++) {
+        const uint32_t row = (uint32_t)(16 * (NGL * wave + u) + (lane >> 2));
         grow[u] = (row < tok_last ? row : tok_last) * (uint32_t)E * 2u + (((uint32_t)lane & 3u) ^ (((uint32_t)lane >> 4) & 3u)) * 16u;
     }
     auto r_gload1 = [&](int sh, int c, int par, int u) {
-        if (HAS_RES) load_to_lds(lds0 + GM_XG + par * GM_XGSZ + (2 * wave + u) * 1024, grow[u] + (uint32_t)(sh * cfix + c) * 64u, xsal_t);
+        if (HAS_RES) load_to_lds(lds0 + G::XG + par * G::XGSZ + (NGL * wave + u) * 1024, grow[u] + (uint32_t)(sh * cfix + c) * 64u, xsal_t);
     };
     auto load_hd = [&](int sh, HalfData<N8> (&hd)[4]) {
         const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
@@ -582,9 +599,9 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     uint32_t bxl[2];
 #pragma unroll
     for (int u = 0; u < 2; u++) bxl[u] = (uint32_t)(i * 256 + ((4 * (g >> 1) + 2 * u + (g & 1)) ^ i) * 16);
-    uint8_t32 b[8];
+    uint8_t32 b[TT];
     auto bread = [&](int buf, int u, int tt) {
-        const char* base = lds + GM_XW + buf * GM_XWSZ + tt * 4096;
+        const char* base = lds + G::XW + buf * G::XWSZ + tt * 4096;
         const uint4 lo = *reinterpret_cast<const uint4*>(base + bxl[u]);
         const uint4 hi = *reinterpret_cast<const uint4*>(base + (bxl[u] ^ 128u));
         b[tt] = uint8_t32{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
@@ -595,7 +612,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     auto sstep = [&](auto abid_, const uint32_t (&ac)[4][4], const uint32_t (&idx)[4], auto&& next_a, auto&& next_b, auto&& extra) {
         constexpr int ABID = decltype(abid_)::value;
 #pragma unroll
-        for (int tt = 0; tt < 8; tt++) {
+        for (int tt = 0; tt < TT; tt++) {
             const half16_t bv = __builtin_bit_cast(half16_t, b[tt]);
 #pragma unroll
             for (int r = 0; r < 4; r++)
@@ -607,7 +624,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     };
     auto dstep = [&](const uint32_t (&ac)[4][4], auto&& next_a, auto&& next_b, auto&& extra) {
 #pragma unroll
-        for (int tt = 0; tt < 8; tt++) {
+        for (int tt = 0; tt < TT; tt++) {
             const uint4 bl = make_uint4(b[tt][0], b[tt][1], b[tt][2], b[tt][3]);
             const half8_t bv = __builtin_bit_cast(half8_t, bl);
 #pragma unroll
@@ -627,9 +644,9 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     uint32_t a0[4][4], a1[4][4], ia[4], ib[4];
     uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int u = 0; u < 8; u++) x_gload1(0, 0, 0, u);
+    for (int u = 0; u < TT; u++) x_gload1(0, 0, 0, u);
 #pragma unroll
-    for (int u = 0; u < 8; u++) x_gload1(0, 1, 1, u);
+    for (int u = 0; u < TT; u++) x_gload1(0, 1, 1, u);
     r_gload1(0, 0, 0, 0);
     r_gload1(0, 0, 0, 1);
     {
@@ -658,7 +675,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
 #pragma unroll
     for (int r = 0; r < 4; r++) { build_a(hd[r], TL[r], TH[r], 0, a0[r]); ia[r] = index_word24(hd[r].m[0], T0, T1, K7); }
 #pragma unroll
-    for (int tt = 0; tt < 8; tt++) bread(0, 0, tt);
+    for (int tt = 0; tt < TT; tt++) bread(0, 0, tt);
 
     // Loads of one pass, in issue order (the NR res_sign words of this pass are older than all of them):
     //   [step 0]                           the next pass's half records (NH) and table record (NC)
@@ -693,7 +710,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
 #pragma unroll
         for (int r = 0; r < 4; r++) { tn[r].rlo = 0u; tn[r].rhi = 0u; unpack_tile<N8>(tn[r], shn & 1, hn[r]); }
         scale_tables(hn, TLn, THn);
-        auto next_loads = [&](int tt) { x_gload1(shn, 1, 1, tt); if (tt >= 6) r_gload1(shn, 0, par ^ 1, tt - 6); };
+        auto next_loads = [&](int tt) { x_gload1(shn, 1, 1, tt); if (tt >= TT - NGL) r_gload1(shn, 0, par ^ 1, tt - (TT - NGL)); };
         auto reload_n = [&](int tt) { bread(0, 0, tt); };
         if (HAS_RES) {
             auto res_a = [&](int r) {
@@ -701,7 +718,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
                 sel.sel0 = ra.x; sel.sel1 = ra.y; sel.bit0 = ra.z; sel.bit1 = ra.w;
                 residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], rb.x & 31u), hd[r].ar | (hd[r].ar << 16), sel, a0[r]);
             };
-            const uint32_t gxp = gx + (uint32_t)(GM_XG + par * GM_XGSZ);
+            const uint32_t gxp = gx + (uint32_t)(G::XG + par * G::XGSZ);
             auto reload_g = [&](int tt) {
                 const uint4 v = *reinterpret_cast<const uint4*>(lds + tt * 1024 + gxp);
                 b[tt][0] = v.x; b[tt][1] = v.y; b[tt][2] = v.z; b[tt][3] = v.w;
@@ -752,8 +769,8 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
                 for (int r = 0; r < 4; r++)
                     residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, a1[r]);
 #pragma unroll
-                for (int tt = 0; tt < 8; tt++) {
-                    const uint4 bt = *reinterpret_cast<const uint4*>(lds + GM_XG + tt * 1024 + gx);
+                for (int tt = 0; tt < TT; tt++) {
+                    const uint4 bt = *reinterpret_cast<const uint4*>(lds + G::XG + tt * 1024 + gx);
                     const half8_t bv = __builtin_bit_cast(half8_t, bt);
 #pragma unroll
                     for (int r = 0; r < 4; r++)
@@ -764,16 +781,16 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
       }
     }
     __syncthreads();
-    store_tile(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
+    store_tile<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
 }
 
 template <int N8, bool HAS_RES>
 hipError_t launch_gemm(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                        const __half* xsal, int cfix) {
     static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_tiled_kernel<N8, HAS_RES>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GM_LDS);
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES>), grid, dim3(256), GM_LDS, st, p, X, T, Y, y_fp32, xsal, cfix);
+    hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix);
     return hipGetLastError();
 }
 
@@ -781,9 +798,9 @@ template <bool HAS_RES>
 hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                          const __half* xsal, int cfix) {
     static const hipError_t attr = hipFuncSetAttribute((const void*)gemm24_kernel<HAS_RES>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GM_LDS24);
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
     if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((gemm24_kernel<HAS_RES>), grid, dim3(256), GM_LDS24, st, p, X, T, Y, y_fp32, xsal, cfix);
+    hipLaunchKernelGGL((gemm24_kernel<HAS_RES>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix);
     return hipGetLastError();
 }
 
@@ -867,15 +884,16 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
         hipLaunchKernelGGL(gemm_gather_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, p,
                            (const __half*)X, T, (__half*)workspace, cfix);
     }
-    const dim3 grid((T + GM_TOK - 1) / GM_TOK, (p.nrt + GM_ROWT - 1) / GM_ROWT);
-    const int n8 = 8 * L->cfg.N / L->cfg.M;
-    const __half* xh = (const __half*)X;
-    const __half* xs = (const __half*)workspace;
-    hipError_t e;
     // STB_GEMM_KERNEL=dense in the environment (read at every call) keeps 2:4 layers on the dense-instruction kernel:
     // the tests use it to run both kernels on every 2:4 case.
     const char* which = std::getenv("STB_GEMM_KERNEL");
     const bool sparse_ok = L->cfg.N == 2 && L->cfg.M == 4 && !(which && which[0] == 'd');
+    const int tok = sparse_ok ? GmLds<GM_TT24>::TOK : GmLds<GM_TT>::TOK;      // tokens per workgroup of the kernel that runs
+    const dim3 grid((T + tok - 1) / tok, (p.nrt + GM_ROWT - 1) / GM_ROWT);
+    const int n8 = 8 * L->cfg.N / L->cfg.M;
+    const __half* xh = (const __half*)X;
+    const __half* xs = (const __half*)workspace;
+    hipError_t e;
     if (sparse_ok) e = res ? launch_gemm24<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm24<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
     else if (n8 == 4) e = res ? launch_gemm<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
     else e = res ? launch_gemm<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
