@@ -20,6 +20,9 @@
 // wavefronts share it, so the kernel is bound by its instruction count.  It therefore runs two fat wavefronts per
 // SIMD (a wavefront owns a whole superblock: 64 VGPRs of x) instead of four thin ones, which halves the
 // per-wavefront set-up work a SIMD executes, and loads everything through few wide instructions.
+// Layers with more than 8 superblocks are cut into column splits whose sums meet through the caller's workspace,
+// or, at small batches, handled by the MULTI form of the kernel: a wavefront visits up to three superblocks per
+// row tile and adds their products up itself.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
