@@ -43,7 +43,7 @@ struct GmLds {
     static constexpr int TOTAL = LUT + 32768;      // with the scatter table (dense kernel)
     static constexpr int TOTAL24 = LUT;            // without (sparse kernel)
 };
-constexpr int GM_TT = 8, GM_TT24 = 8;       // (12 in the dense kernel was tried: 192 accumulators leave too few registers, the compiler spills)
+constexpr int GM_TT = 8, GM_TT24 = 8;       // (12 in the dense kernel was measured: 15 - 30 % slower, fewer and fatter workgroups)
 
 // Workspace: xsal[T][E] fp16, E = nsb * 2 * cfix * 32; entry ((sb*2 + half)*cfix + c)*32 + g*8 + e holds X at the
 // e-th salient column of record c of (block 4*sb + g, half), 0 where the record has no such entry.
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     // ---- the K step: 32 MFMAs (4 row tiles x 8 token tiles) on the A operands `ac` and the B operands b[]; in
     //      their shadow the lane builds the A operands of the next step (`next_a(r)` for row tile r) and, as soon
     //      as the four MFMAs of a token tile have been issued, reloads that tile's B operand for the next step
-    //      (`next_b(tt)`).  `extra()` is the step's share of the staging work. ----
+    //      (`next_b(tt)`).  `extra(tt)` is the share of the staging work that goes with token tile tt. ----
     uint4 b[TT];
     auto kstep = [&](const uint32_t (&ac)[4][4], auto&& next_a, auto&& next_b, auto&& extra) {
 #pragma unroll
@@ -278,19 +278,11 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             for (int r = 0; r < 4; r++)
                 acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(ac[r]), bv, acc[r][tt], 0, 0, 0);
             next_b(tt);
-            if (tt % 2 == 0) next_a(tt / 2);
+            if (tt % (TT / 4) == 0) next_a(tt / (TT / 4));
             extra(tt);
         }
-        // the order the scheduler is asked for: one MFMA (16 cycles in the matrix pipe), then what fits in its
-        // shadow: an LDS read while there are any, three vector instructions
-#ifndef GM_NOSGB
-#pragma unroll
-        for (int q = 0; q < 4 * TT; q++) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // LDS read
-            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);       // VALU
-        }
-#endif
+        // (Asking the scheduler for an MFMA / LDS read / three vector instructions rhythm through sched_group_barrier
+        //  was measured: 6 - 8 % slower on 4:8 layers than its own order, and 20 times the compile time.)
     };
     // B operand of token tile tt: rows 16 tt + i, piece 4 g + tq, at position piece ^ i
     uint32_t bx[2][4];                                              // per window buffer (the offset of a token tile is an immediate)
@@ -365,7 +357,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         // (the loads are spread over the token tiles of a step, a few at a time: the four wavefronts share one path
         //  to memory, and a burst of loads stalls them all)
         kstep(a1, produce(4, a0), reload(4), [&](int tt) { x_gload1(shn, 0, 0, tt); });
-        kstep(a0, produce(5, a1), reload(5), [&](int tt) { if (tt % 2 == 0) fetch_hd1(shn, tn, tt / 2); if (tt == 7) fetch_rec(shn, ran, rbn); });
+        kstep(a0, produce(5, a1), reload(5), [&](int tt) { if (tt % 2 == 0 && tt < 8) fetch_hd1(shn, tn, tt / 2); if (tt == 7) fetch_rec(shn, ran, rbn); });
         kstep(a1, produce(6, a0), reload(6), nothing);
         kstep(a0, produce(7, a1), reload(7), nothing);
         // everything in flight has arrived: window 0 of the next pass, its half records and table record, and the
@@ -618,7 +610,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
             for (int r = 0; r < 4; r++)
                 acc[r][tt] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(ac[r]), bv, acc[r][tt], (int)idx[r], 0, ABID);
             next_b(tt);
-            if (tt % 2 == 0) next_a(tt / 2);
+            if (tt % (TT / 4) == 0) next_a(tt / (TT / 4));
             extra(tt);
         }
     };
@@ -631,7 +623,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
             for (int r = 0; r < 4; r++)
                 acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(ac[r]), bv, acc[r][tt], 0, 0, 0);
             next_b(tt);
-            if (tt % 2 == 0) next_a(tt / 2);
+            if (tt % (TT / 4) == 0) next_a(tt / (TT / 4));
             extra(tt);
         }
     };
@@ -692,7 +684,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
         auto nothing = [](int) {};
         // step 0 (window 0): builds step 1, fetches the next pass's records
         sstep(IntC<0>{}, a0, ia, [&](int r) { build_a(hd[r], TL[r], TH[r], 1, a1[r]); }, [&](int tt) { bread(0, 1, tt); },
-              [&](int tt) { if (tt % 2 == 0) fetch_hd1(shn, tn, tt / 2); if (tt == 7) fetch_rec(shn, ran, rbn); });
+              [&](int tt) { if (tt % 2 == 0 && tt < 8) fetch_hd1(shn, tn, tt / 2); if (tt == 7) fetch_rec(shn, ran, rbn); });
         asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR + NH + NC) : "memory");     // window 1 and the gathered columns of this pass
         __syncthreads();                                            // ... everyone's; and everyone is done with window 0
         // step 1: builds step 2 (window 1) and its index word, loads window 0 of the next pass
