@@ -754,16 +754,12 @@ int64_t round_up256(int64_t v) { return (v + 255) / 256 * 256; }
 
 }  // namespace
 
-// Picks the launch shape and runs the kernel; returns STB_EUNSUPPORTED (and launches nothing) when the layout
-// is not 2:4 or a staging area would not fit, so that the caller can fall back to the general kernel.
-extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
-                                int64_t workspace_bytes, int max_splits, void* stream, int* hip_err) {
-    if (B < 1 || B > 16 || (8 * L->cfg.N) % L->cfg.M != 0) return STB_EUNSUPPORTED;
-    const int n8 = 8 * L->cfg.N / L->cfg.M;
-    const int mode = L->cfg.M == 4 && L->cfg.N == 2 ? 2 : n8;      // 2: sparse instruction; 4, 6: dense with the scatter table
-    if (mode != 2 && mode != 4 && mode != 6) return STB_EUNSUPPORTED;
-    if (L->region_bytes >= (1ll << 31) || L->res_bytes >= (1ll << 31)) return STB_EUNSUPPORTED;   // 32-bit offsets inside a plane
-    const TiledPlanes p = make_tiled(L);
+// The launch shape of gemv24_kernel for a layer of nrt row tiles and nsb superblocks at batch B (mode 2: sparse
+// instruction, 4 / 6: dense): out = {S column splits, R row tiles per workgroup, SPS wavefronts per workgroup, V visits
+// per wavefront, bytes of LDS per wavefront, offset of its records, offset of its partial tiles}.  Pure host
+// arithmetic (the tests check its invariants over many shapes).  STB_EUNSUPPORTED when nothing fits.
+extern "C" int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_splits, int* out) {
+    if (nrt < 1 || nsb < 1 || B < 1 || B > 16 || (mode != 2 && mode != 4 && mode != 6) || !out) return STB_EUNSUPPORTED;
     const int64_t lds_max = LDS24 - (mode == 2 ? 0 : 32768);
     // Column splits of SPS <= 8 wavefronts; a wavefront takes V superblocks (V = 1: its own; V = 2, 3: it visits
     // them one after the other for every row tile); a workgroup owns R row tiles.  Among the shapes whose LDS fits,
@@ -780,15 +776,15 @@ extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, voi
     // STB_GEMV_VISITS=2 or 3 in the environment (read at every call) restricts the choice to that many visits where
     // such a shape exists: the tests use it, because small layers never choose several visits themselves.
     const char* vis = std::getenv("STB_GEMV_VISITS");
-    const int v_only = vis && (vis[0] == '2' || vis[0] == '3') && p.nsb >= vis[0] - '0' ? vis[0] - '0' : 0;
+    const int v_only = vis && (vis[0] == '2' || vis[0] == '3') && nsb >= vis[0] - '0' ? vis[0] - '0' : 0;
     for (int v = 1; v <= 3; v++) {
         if (v_only && v != v_only) continue;
-        for (int s = (p.nsb + 8 * v - 1) / (8 * v); s <= max_splits && s * v <= p.nsb; s++) {
-            const int sps = (p.nsb + s * v - 1) / (s * v);
-            if (sps > 8 || (s - 1) * sps * v >= p.nsb) continue;   // a split must own at least one superblock
-            if ((s * v - 1) * sps >= p.nsb) continue;              // ... and so must the last visit of the last split
+        for (int s = (nsb + 8 * v - 1) / (8 * v); s <= max_splits && s * v <= nsb; s++) {
+            const int sps = (nsb + s * v - 1) / (s * v);
+            if (sps > 8 || (s - 1) * sps * v >= nsb) continue;   // a split must own at least one superblock
+            if ((s * v - 1) * sps >= nsb) continue;              // ... and so must the last visit of the last split
             const int groups = 256 / s > 0 ? 256 / s : 1;
-            const int r = (p.nrt + groups - 1) / groups, g = (p.nrt + r - 1) / r;
+            const int r = (nrt + groups - 1) / groups, g = (nrt + r - 1) / r;
             const int pht = r < PHASE24 ? r : PHASE24;
             int w, ro, po;
             if (v == 1) {
@@ -804,6 +800,24 @@ extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, voi
         }
     }
     if (S == 0) return STB_EUNSUPPORTED;
+    out[0] = S; out[1] = R; out[2] = SPS; out[3] = V; out[4] = wreg; out[5] = rec_off; out[6] = part_off;
+    return STB_OK;
+}
+
+// Picks the launch shape and runs the kernel; returns STB_EUNSUPPORTED (and launches nothing) when the layout
+// is not 2:4 or a staging area would not fit, so that the caller can fall back to the general kernel.
+extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
+                                int64_t workspace_bytes, int max_splits, void* stream, int* hip_err) {
+    if (B < 1 || B > 16 || (8 * L->cfg.N) % L->cfg.M != 0) return STB_EUNSUPPORTED;
+    const int n8 = 8 * L->cfg.N / L->cfg.M;
+    const int mode = L->cfg.M == 4 && L->cfg.N == 2 ? 2 : n8;      // 2: sparse instruction; 4, 6: dense with the scatter table
+    if (mode != 2 && mode != 4 && mode != 6) return STB_EUNSUPPORTED;
+    if (L->region_bytes >= (1ll << 31) || L->res_bytes >= (1ll << 31)) return STB_EUNSUPPORTED;   // 32-bit offsets inside a plane
+    const TiledPlanes p = make_tiled(L);
+    int plan[7];
+    if (stb_tiled_gemv24_plan(p.nrt, p.nsb, B, mode, max_splits, plan) != STB_OK) return STB_EUNSUPPORTED;
+    const int S = plan[0], R = plan[1], SPS = plan[2], V = plan[3], wreg = plan[4], rec_off = plan[5], part_off = plan[6];
+    const int xbytes = (B < 16 ? B + 1 : 16) * 1040;
     const int G = (p.nrt + R - 1) / R;
     const int PHT = R < PHASE24 ? R : PHASE24;
     const bool res = p.res_words > 0;

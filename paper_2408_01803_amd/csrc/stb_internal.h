@@ -23,6 +23,9 @@ int64_t stb_tiled_gemv_workspace(int n_row_tiles, int n_super);
 // its staging areas would not fit: the caller then runs the older kernel.  max_splits bounds the number of column splits (the workspace is sized for that many).
 int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
                      int64_t workspace_bytes, int max_splits, void* stream, int* hip_err);
+// The launch shape stb_tiled_gemv24 takes (host arithmetic only; out[7] = S, R, SPS, V, LDS bytes per wavefront, record
+// offset, partial-tile offset).
+int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_splits, int* out);
 // Prefill kernel for the tiled order (stb_gemm.hip) and its scratch size for T tokens.
 int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void* Y, int y_fp32, void* workspace,
                    int64_t workspace_bytes, void* stream, int* hip_err);

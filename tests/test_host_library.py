@@ -219,3 +219,45 @@ def test_tile_rejects_mismatched_layouts():
     with pytest.raises(S.StbError) as e:
         S.stb_tile(pm.host_layout, pm.host_layout)
     assert e.value.status == S.STB_EINVAL
+
+
+def test_decode_launch_plan_invariants():
+    """The launch shape the decode kernel picks (host arithmetic, no GPU): over many layer shapes, batches and
+    modes the column splits and superblock visits cover every superblock, no split and no last visit is empty, the
+    LDS areas do not overlap and fit, and the split count stays inside what the workspace is sized for."""
+    import ctypes as C
+    lib = S.binding._lib()
+    plan = lib.stb_tiled_gemv24_plan
+    plan.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_int)]
+    plan.restype = C.c_int
+    out = (C.c_int * 7)()
+    LDS, PHASE = 160 * 1024 - 64, 15
+    seen_multi = 0
+    for mode in (2, 4, 6):
+        lds_max = LDS - (0 if mode == 2 else 32768)
+        for nsb in list(range(1, 60)) + [64, 100, 112]:
+            max_splits = (nsb + 1) // 2 + 3            # the bound the workspace is sized for
+            for nrt in (1, 2, 3, 16, 63, 256, 257, 320, 512, 688, 864, 1792, 4000):
+                for B in (1, 2, 4, 5, 8, 15, 16):
+                    rc = plan(nrt, nsb, B, mode, max_splits, out)
+                    if rc != 0:
+                        continue
+                    Sn, R, SPS, V, wreg, rec_off, part_off = list(out)
+                    what = (mode, nsb, nrt, B, list(out))
+                    assert 1 <= SPS <= 8 and 1 <= V <= 3 and 1 <= Sn <= max_splits and R >= 1, what
+                    assert Sn * SPS * V >= nsb, what                      # every superblock has a wavefront and a visit
+                    assert (Sn - 1) * SPS * V < nsb, what                 # no empty split
+                    assert (Sn * V - 1) * SPS < nsb, what                 # no empty last visit
+                    assert R == -(-nrt // max(256 // Sn, 1)), what           # row tiles per workgroup: one round on 256 units if it can be
+                    pht = min(R, PHASE)
+                    assert pht == R or pht % 3 == 0, what                 # phases end on a whole round of the three tile buffers
+                    xbytes = (B + 1 if B < 16 else 16) * 1040
+                    if V == 1:
+                        assert part_off == 0 and rec_off >= max(xbytes, pht * 1024) and wreg == rec_off + 768, what
+                    else:
+                        assert rec_off == V * xbytes and part_off == rec_off + V * 768 and wreg == part_off + pht * 1024, what
+                        seen_multi += 1
+                    assert SPS * wreg <= lds_max, what
+    assert seen_multi > 0
+    # arguments outside the kernel's range are refused
+    assert plan(16, 8, 17, 2, 7, out) != 0 and plan(16, 8, 1, 5, 7, out) != 0 and plan(0, 8, 1, 2, 7, out) != 0
