@@ -266,6 +266,102 @@ __global__ __launch_bounds__(512) void probe_read_kernel(const uint4* __restrict
     if ((threadIdx.x & 63) == 0) atomicXor(sink + (blockIdx.x & 1023), r);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Generic decode GEMV, second form (any N:M; used when B rows of x fit in LDS): a workgroup stages x once, in a
+// transposed order, and takes 16 output rows, four per wavefront one after the other.  A lane owns one mask word
+// (32 columns) at a time and reads that word's sign bits, id fields and residual-sign bits as bit windows (two or
+// three aligned 32-bit loads each) instead of one byte load per kept weight.
+// LDS order: x[b][32 w + pos] at ((b * 32 + pos) * (W + 1) + w), W = k / 32: the lanes of a wavefront differ in w.
+// ------------------------------------------------------------------------------------------------
+__device__ inline uint32_t bit_window(const uint32_t* words, int n_words, int bit) {
+    // 32 bits of a little-endian bit string starting at `bit`; words past the end read as the last word (their
+    // bits are never used: a window is cut to its own length by the caller)
+    const int dw = bit >> 5;
+    const uint32_t lo = words[dw < n_words ? dw : n_words - 1];
+    const uint32_t hi = words[dw + 1 < n_words ? dw + 1 : n_words - 1];
+    return __builtin_amdgcn_alignbit(hi, lo, (uint32_t)(bit & 31));
+}
+
+template <int B>
+__global__ __launch_bounds__(256) void gemv_rows_kernel(Planes p, const __half* __restrict__ x, void* __restrict__ y, int y_fp32) {
+    extern __shared__ __attribute__((aligned(16))) __half xs[];
+    const int W = p.wpr, WP = W + 1;
+    for (int idx = threadIdx.x; idx < B * p.k; idx += 256) {
+        const int b = idx / p.k, j = idx - b * p.k;
+        xs[(b * 32 + (j & 31)) * WP + (j >> 5)] = x[idx];
+    }
+    __syncthreads();
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sign_words = p.sign_stride / 4, region_words = p.region_stride / 4, res_words = p.res_stride / 4;
+    for (int rr = 0; rr < 4; rr++) {
+        const int row = blockIdx.x * 16 + wave * 4 + rr;
+        if (row >= p.n) break;                                      // uniform per wavefront
+        const uint32_t* srow = reinterpret_cast<const uint32_t*>(p.sign + (size_t)row * p.sign_stride);
+        const uint32_t* rrow = reinterpret_cast<const uint32_t*>(p.region + (size_t)row * p.region_stride);
+        const uint32_t* trow = p.res_sign ? reinterpret_cast<const uint32_t*>(p.res_sign + (size_t)row * p.res_stride) : nullptr;
+        float acc[B];
+#pragma unroll
+        for (int b = 0; b < B; b++) acc[b] = 0.0f;
+        for (int w = lane; w < W; w += 64) {
+            uint32_t m = p.mask[(size_t)row * W + w];
+            const uint32_t salw = p.sal_bitmap[w];
+            const int slot0 = w * p.spw, q = w >> 2;
+            const uint32_t sw = bit_window(srow, sign_words, slot0);                 // spw <= 32 sign bits
+            const uint32_t r0 = bit_window(rrow, region_words, 2 * slot0);           // ids of the first 16 slots
+            const uint32_t r1 = bit_window(rrow, region_words, 2 * slot0 + 32);      // ... of the next 16
+            uint32_t tw = 0u;
+            if (trow) {
+                int ord = (int)p.sal_prefix[q];
+                for (int v = q * 4; v < w; v++) ord += __popc(p.sal_bitmap[v]);
+                tw = bit_window(trow, res_words, ord);                               // residual signs of the word's salient columns
+            }
+            const uint2 sc = *reinterpret_cast<const uint2*>(p.scales + ((size_t)row * p.nb + q) * 4);
+            const __half2 s01 = *reinterpret_cast<const __half2*>(&sc.x);
+            const __half2 s23 = *reinterpret_cast<const __half2*>(&sc.y);
+            const float a0 = __low2float(s01), a1 = __high2float(s01), a2 = __low2float(s23), a3 = __high2float(s23);
+            const float ar = __half2float(p.res_scale[(size_t)row * p.nb + q]);
+            const __half* xw = xs + w;
+            int rank = 0;
+            while (m) {                                             // every word keeps 32 N / M weights: the same trip count in all lanes
+                const int pos = __ffs(m) - 1;
+                m &= m - 1;
+                const bool plus = (sw >> rank) & 1u;
+                const uint32_t id = ((rank < 16 ? r0 >> (2 * rank) : r1 >> (2 * rank - 32))) & 3u;
+                const float a = id == 0 ? a0 : (id == 1 ? a1 : (id == 2 ? a2 : a3));
+                float v = plus ? a : -a;
+                if (id == 3 && trow) {
+                    const int u = __popc(salw & ((1u << pos) - 1u));
+                    v = v + (((tw >> u) & 1u) ? ar : -ar);          // one fp32 addition
+                }
+                rank++;
+#pragma unroll
+                for (int b = 0; b < B; b++) acc[b] += v * __half2float(xw[(b * 32 + pos) * WP]);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < B; b++) {
+            float s = acc[b];
+            for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+            if (lane == 0) {
+                if (y_fp32) reinterpret_cast<float*>(y)[(size_t)b * p.n + row] = s;
+                else reinterpret_cast<__half*>(y)[(size_t)b * p.n + row] = __float2half(s);
+            }
+        }
+    }
+}
+
+constexpr int64_t GEMV_ROWS_LDS_MAX = 120 * 1024;
+static int64_t gemv_rows_lds(const Planes& p, int B) { return (int64_t)B * 32 * (p.wpr + 1) * 2; }
+
+template <int B>
+hipError_t launch_gemv_rows(const Planes& p, const void* x, void* y, int y_fp32, hipStream_t s) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv_rows_kernel<B>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                       (int)GEMV_ROWS_LDS_MAX);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL(gemv_rows_kernel<B>, dim3((p.n + 15) / 16), dim3(256), (size_t)gemv_rows_lds(p, B), s, p, (const __half*)x, y, y_fp32);
+    return hipGetLastError();
+}
+
 template <int B>
 hipError_t launch_gemv_generic(const Planes& p, const void* x, void* y, int y_fp32, hipStream_t s) {
     const int blocks = (p.n + 3) / 4;
@@ -357,7 +453,12 @@ extern "C" int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void*
         const int left = B - done;
         const __half* xb = (const __half*)x + (size_t)done * p.k;
         void* yb = y_fp32 ? (void*)((float*)y + (size_t)done * p.n) : (void*)((__half*)y + (size_t)done * p.n);
-        if (left >= 8) { e = launch_gemv_generic<8>(p, xb, yb, y_fp32, s); done += 8; }
+        // (the kernel with x in LDS where that many rows of x fit, the older one otherwise)
+        if (left >= 8 && gemv_rows_lds(p, 8) <= GEMV_ROWS_LDS_MAX) { e = launch_gemv_rows<8>(p, xb, yb, y_fp32, s); done += 8; }
+        else if (left >= 4 && gemv_rows_lds(p, 4) <= GEMV_ROWS_LDS_MAX) { e = launch_gemv_rows<4>(p, xb, yb, y_fp32, s); done += 4; }
+        else if (left >= 2 && gemv_rows_lds(p, 2) <= GEMV_ROWS_LDS_MAX) { e = launch_gemv_rows<2>(p, xb, yb, y_fp32, s); done += 2; }
+        else if (gemv_rows_lds(p, 1) <= GEMV_ROWS_LDS_MAX) { e = launch_gemv_rows<1>(p, xb, yb, y_fp32, s); done += 1; }
+        else if (left >= 8) { e = launch_gemv_generic<8>(p, xb, yb, y_fp32, s); done += 8; }
         else if (left >= 4) { e = launch_gemv_generic<4>(p, xb, yb, y_fp32, s); done += 4; }
         else if (left >= 2) { e = launch_gemv_generic<2>(p, xb, yb, y_fp32, s); done += 2; }
         else { e = launch_gemv_generic<1>(p, xb, yb, y_fp32, s); done += 1; }
