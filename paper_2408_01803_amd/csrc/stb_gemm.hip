@@ -130,6 +130,182 @@ __device__ inline void load_to_lds(uint32_t lds_addr, uint32_t voff, const void*
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
 }
 
+// ------------------------------------------------------------------------------------------------
+// What the two main kernels share: the per-lane constants and the loads of a pass.
+// Every global load of a main loop is an asm statement, and every use sits behind a vmcnt wait written by hand
+// (for loads into registers the wait names them, the rules of the fetch helpers in stb_tiled.hpp): the loads go
+// out where they are written, K steps ahead of their use, and the compiler neither sinks them down to it nor
+// waits for them on its own (a load the compiler knows of makes it wait for everything in flight).
+// ------------------------------------------------------------------------------------------------
+template <int N8, bool HAS_RES, int TT>
+struct GemmStage {
+    typedef GmLds<TT> G;
+    static constexpr int NGL = TT / 4;         // gathered-column loads per wavefront (16 token rows each)
+    const TiledPlanes& p;
+    const __half* Xt;                          // X at the workgroup's first token
+    const __half* xsal_t;                      // gathered salient columns at the workgroup's first token
+    const uint32_t* rsbase[4];                 // res_sign words of the wavefront's four row tiles (uniform)
+    uint32_t lds0, tok_last, k2, xpc[4], grow[NGL];
+    int cfix, rtw, wave, lane, i, g;
+
+    __device__ GemmStage(const TiledPlanes& p_, const __half* X, const __half* xsal, int T, int cfix_, uint32_t lds0_, int t0,
+                         int rtw_, int wave_, int lane_)
+        : p(p_), lds0(lds0_), cfix(cfix_), rtw(rtw_), wave(wave_), lane(lane_), i(lane_ & 15), g(lane_ >> 4) {
+        tok_last = (uint32_t)(T - 1 - t0);
+        k2 = (uint32_t)p.k * 2u;
+        Xt = X + (int64_t)t0 * p.k;
+        // X window -> LDS: 4 TT wavefront loads of 4 token rows each, TT per wavefront.  Load u of wavefront w covers
+        // rows 4 * (TT w + u) ..; lane l = row l / 16 of them, position l % 16, i.e. piece (l % 16) ^ (row % 16):
+        // block piece / 4, 8 columns (piece % 4).  Tokens past T are clamped to the last token (their outputs are
+        // never stored); a piece past column k is clamped to the row's last 16 bytes (it meets zero weights).
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const uint32_t pc = (uint32_t)i ^ (uint32_t)(4 * j + g);   // rows 4 * (TT w + u) + g: row % 16 = 4 * (u % 4) + g
+            xpc[j] = (pc >> 2) * 256u + (pc & 3u) * 16u;
+        }
+        // gathered salient columns: TT wavefront loads of 16 token rows, NGL per wavefront; lane l = row l / 4 of
+        // them, position l % 4 = piece (l % 4) ^ ((row / 4) % 4)
+        const int64_t E = (int64_t)p.nsb * 2 * cfix * 32;           // halves per token in xsal
+        xsal_t = xsal + (int64_t)t0 * E;
+#pragma unroll
+        for (int u = 0; u < NGL; u++) {
+            const uint32_t row = (uint32_t)(16 * (NGL * wave + u) + (lane >> 2));
+            grow[u] = (row < tok_last ? row : tok_last) * (uint32_t)E * 2u + (((uint32_t)lane & 3u) ^ (((uint32_t)lane >> 4) & 3u)) * 16u;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; r++) rsbase[r] = p.res_sign + (int64_t)row_tile(r) * p.res_words * 16;
+    }
+    __device__ int row_tile(int r) const { return rtw + r < p.nrt ? rtw + r : p.nrt - 1; }
+
+    // load u (0 .. TT-1) of the wavefront's share of window `win` of (superblock, half) sh into window buffer `buf`
+    __device__ void x_gload1(int sh, int win, int buf, int u) const {
+        const uint32_t wcol = (uint32_t)((sh >> 1) * 1024 + (sh & 1) * 128 + win * 64);      // bytes inside a token row
+        const uint32_t dst = lds0 + G::XW + buf * G::XWSZ + wave * (TT * 1024);
+        const uint32_t c = xpc[u & 3] + wcol;
+        const uint32_t row = (uint32_t)(4 * (TT * wave + u)) + (uint32_t)g;
+        load_to_lds(dst + u * 1024, __umul24(row < tok_last ? row : tok_last, k2) + (c < k2 - 16u ? c : k2 - 16u), Xt);
+    }
+    __device__ void x_gload(int sh, int win, int buf) const {
+#pragma unroll
+        for (int u = 0; u < TT; u++) x_gload1(sh, win, buf, u);
+    }
+    // load u (0 .. NGL-1) of the gathered salient columns of (superblock, half) sh, record c, into buffer `par`
+    __device__ void r_gload1(int sh, int c, int par, int u) const {
+        if (HAS_RES) load_to_lds(lds0 + G::XG + par * G::XGSZ + (NGL * wave + u) * 1024, grow[u] + (uint32_t)(sh * cfix + c) * 64u, xsal_t);
+    }
+    __device__ void r_gload(int sh, int c, int par) const {
+#pragma unroll
+        for (int u = 0; u < NGL; u++) r_gload1(sh, c, par, u);
+    }
+    // plain loads (tail loop only)
+    __device__ void load_hd(int sh, HalfData<N8> (&hd)[4]) const {
+        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
+#pragma unroll
+        for (int r = 0; r < 4; r++) load_half<N8>(p, (int64_t)row_tile(r) * p.nsb + (sh >> 1), lo, sh & 1, hd[r]);
+    }
+    __device__ void load_res_words(uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) const {
+        const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+        const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            rlo[r] = rsbase[r][wa * 16 + i];
+            rhi[r] = rsbase[r][wb * 16 + i];
+        }
+    }
+    // asm loads: the table record of (superblock, half) sh (2 loads), the half records of row tile r (5 loads), the
+    // res_sign words of row tile r (2 loads)
+    __device__ void fetch_rec(int sh, uint4_t& ra, uint2_t& rb) const {
+        if (HAS_RES) {
+            const uint32_t off = (uint32_t)(((4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 48u;
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(ra) : "v"(off), "s"(p.sal_tab));
+            asm volatile("global_load_dwordx2 %0, %1, %2 offset:16" : "=v"(rb) : "v"(off), "s"(p.sal_tab));
+        }
+    }
+    __device__ void fetch_hd1(int sh, TileRegs<N8> (&tn)[4], int r) const {
+        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
+        fetch_main<N8>(tn[r], p, (int64_t)__builtin_amdgcn_readfirstlane(row_tile(r) * p.nsb + (sh >> 1)), lo);
+    }
+    __device__ void fetch_res_words1(uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4], int r) const {
+        const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+        const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+        const uint32_t oa = (uint32_t)(wa * 16 + i) * 4u, ob = (uint32_t)(wb * 16 + i) * 4u;
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(rlo[r]) : "v"(oa), "s"(rsbase[r]));
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(rhi[r]) : "v"(ob), "s"(rsbase[r]));
+    }
+    __device__ void fetch_res_words(uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) const {
+#pragma unroll
+        for (int r = 0; r < 4; r++) fetch_res_words1(ord, rlo, rhi, r);
+    }
+    __device__ static void scale_tables(const HalfData<N8> (&hd)[4], uint32_t (&TL)[4], uint32_t (&TH)[4]) {
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            TL[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x06040200u);
+            TH[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x07050301u);
+        }
+    }
+    // the first pass's half records and table record (asm loads here too), waited for on the spot
+    __device__ void first_records(HalfData<N8> (&hd)[4], uint4& ra, uint2& rb) const {
+        TileRegs<N8> t0r[4];
+        uint4_t ra0 = {0u, 0u, 0u, 0u};
+        uint2_t rb0 = {0u, 0u};
+#pragma unroll
+        for (int r = 0; r < 4; r++) fetch_hd1(0, t0r, r);
+        fetch_rec(0, ra0, rb0);
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(ra0), "+v"(rb0) : : "memory");
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(t0r[r].m), "+v"(t0r[r].s), "+v"(t0r[r].r), "+v"(t0r[r].sc), "+v"(t0r[r].ar));
+            t0r[r].rlo = 0u; t0r[r].rhi = 0u;
+            unpack_tile<N8>(t0r[r], 0, hd[r]);
+        }
+        ra = make_uint4(ra0.x, ra0.y, ra0.z, ra0.w);
+        rb = make_uint2(rb0.x, rb0.y);
+    }
+    // Half blocks with more than 8 salient columns: their further records, one at a time and without any overlap
+    // (few: a record covers 8 of the 64 columns).  Kept out of the main loops so that they stay one straight line of
+    // K steps (a branch around matrix instructions costs two register copies of the accumulators).
+    __device__ void further_records(float4_t (&acc)[4][TT], HalfData<N8> (&hd)[4], uint32_t (&a1)[4][4], uint32_t (&rlo)[4],
+                                    uint32_t (&rhi)[4], const char* lds, int nsh) const {
+        if (!(HAS_RES && p.sal_chunks > 1)) return;
+        const uint32_t gx = (uint32_t)(i * 64 + (g ^ ((i >> 2) & 3)) * 16);
+        for (int sh0 = 0; sh0 < nsh; sh0 += 64) {
+            // which of the next 64 half blocks have such records: lane l looks at half block sh0 + l
+            const int shl = sh0 + lane < nsh ? sh0 + lane : nsh - 1;
+            const uint32_t need_l = p.sal_tab[(((int64_t)(4 * (shl >> 1)) * 2 + (shl & 1)) * p.sal_chunks) * 12 + 5];
+            uint64_t todo = __ballot(need_l > 1u && sh0 + lane < nsh);
+            while (todo) {
+                const int sh = sh0 + __builtin_ctzll(todo);
+                todo &= todo - 1;
+                const uint32_t* rec0 = p.sal_tab + (((int64_t)(4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 12;
+                const int nch = __builtin_amdgcn_readfirstlane((int)rec0[5]);          // the same for the four blocks
+                load_hd(sh, hd);
+                for (int c = 1; c < nch; c++) {
+                    __syncthreads();                             // every wavefront is done with the gathered columns
+                    r_gload(sh, c, 0);
+                    const uint4 rc = *reinterpret_cast<const uint4*>(rec0 + c * 12);
+                    const uint32_t ord = rec0[c * 12 + 4];
+                    load_res_words(ord, rlo, rhi);
+                    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+                    __syncthreads();
+                    ResSel sel;
+                    sel.sel0 = rc.x; sel.sel1 = rc.y; sel.bit0 = rc.z; sel.bit1 = rc.w;
+#pragma unroll
+                    for (int r = 0; r < 4; r++)
+                        residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, a1[r]);
+#pragma unroll
+                    for (int tt = 0; tt < TT; tt++) {
+                        const uint4 bt = *reinterpret_cast<const uint4*>(lds + G::XG + tt * 1024 + gx);
+                        const half8_t bv = __builtin_bit_cast(half8_t, bt);
+#pragma unroll
+                        for (int r = 0; r < 4; r++)
+                            acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(a1[r]), bv, acc[r][tt], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+};
+
 template <int N8, bool HAS_RES>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                           void* __restrict__ Y, int y_fp32,
@@ -152,118 +328,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
 #pragma unroll
         for (int tt = 0; tt < TT; tt++) acc[r][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // Every global load of the main loop is an asm statement, and every use sits behind a vmcnt wait written by
-    // hand (for loads into registers the wait names them, the rules of the fetch helpers in stb_tiled.hpp): the
-    // loads go out where they are written, K steps ahead of their use, and the compiler neither sinks them down to
-    // it nor waits for them on its own.
-
-    // ---- X window -> LDS: 32 wavefront loads of 4 token rows each, 8 per wavefront.  Load u of wavefront w covers
-    //      rows 4 * (8w + u) ..; lane l = row l / 16 of them, position l % 16, i.e. piece (l % 16) ^ (row % 16):
-    //      block piece / 4, 8 columns (piece % 4).  Tokens past T are clamped to the last token (their outputs are
-    //      never stored); a piece past column k is clamped to the row's last 16 bytes (it meets zero weights). ----
-    const uint32_t tok_last = (uint32_t)(T - 1 - t0), k2 = (uint32_t)p.k * 2u;
-    uint32_t xpc[4];
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-        const uint32_t pc = (uint32_t)i ^ (uint32_t)(4 * j + g);   // rows 4 * (8w + u) + g: row % 16 = 4 * (u % 4) + g
-        xpc[j] = (pc >> 2) * 256u + (pc & 3u) * 16u;
-    }
-    const __half* const Xt = X + (int64_t)t0 * p.k;
-    auto x_gload1 = [&](int sh, int win, int buf, int u) {          // load u (0..7) of the wavefront's share of a window
-        const uint32_t wcol = (uint32_t)((sh >> 1) * 1024 + (sh & 1) * 128 + win * 64);      // bytes inside a token row
-        const uint32_t dst = lds0 + G::XW + buf * G::XWSZ + wave * (TT * 1024);
-        const uint32_t c = xpc[u & 3] + wcol;
-        const uint32_t row = (uint32_t)(4 * (TT * wave + u)) + (uint32_t)g;
-        load_to_lds(dst + u * 1024, __umul24(row < tok_last ? row : tok_last, k2) + (c < k2 - 16u ? c : k2 - 16u), Xt);
-    };
-    auto x_gload = [&](int sh, int win, int buf) {
-#pragma unroll
-        for (int u = 0; u < TT; u++) x_gload1(sh, win, buf, u);
-    };
-    // the gathered salient columns of (superblock, half) sh, record c: 8 wavefront loads of 16 token rows, 2 per
-    // wavefront; lane l = row l / 4 of them, position l % 4 = piece (l % 4) ^ ((row / 4) % 4)
-    const int64_t E = (int64_t)p.nsb * 2 * cfix * 32;               // halves per token in xsal
-    const __half* const xsal_t = xsal + (int64_t)t0 * E;
-    constexpr int NGL = TT / 4;                                     // gathered-column loads per wavefront (16 token rows each)
-    uint32_t grow[NGL];
-#pragma unroll
-    for (int u = 0; u < NGL; u++) {
-        const uint32_t row = (uint32_t)(16 * (NGL * wave + u) + (lane >> 2));
-        grow[u] = (row < tok_last ? row : tok_last) * (uint32_t)E * 2u + (((uint32_t)lane & 3u) ^ (((uint32_t)lane >> 4) & 3u)) * 16u;
-    }
-    auto r_gload1 = [&](int sh, int c, int par, int u) {
-        if (HAS_RES) load_to_lds(lds0 + G::XG + par * G::XGSZ + (NGL * wave + u) * 1024, grow[u] + (uint32_t)(sh * cfix + c) * 64u, xsal_t);
-    };
-    auto r_gload = [&](int sh, int c, int par) {
-#pragma unroll
-        for (int u = 0; u < NGL; u++) r_gload1(sh, c, par, u);
-    };
-    auto load_hd = [&](int sh, HalfData<N8> (&hd)[4]) {
-        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
-            load_half<N8>(p, (int64_t)rt * p.nsb + (sh >> 1), lo, sh & 1, hd[r]);
-        }
-    };
-    auto load_rec = [&](int sh, uint4& ra, uint2& rb) {
-        if (HAS_RES) {
-            const uint32_t* rec0 = p.sal_tab + (((int64_t)(4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 12;
-            ra = *reinterpret_cast<const uint4*>(rec0);
-            rb = *reinterpret_cast<const uint2*>(rec0 + 4);
-        }
-    };
-    // the same as asm loads (2 loads), and the half records of the four row tiles (4 x 5 loads)
-    auto fetch_rec = [&](int sh, uint4_t& ra, uint2_t& rb) {
-        if (HAS_RES) {
-            const uint32_t off = (uint32_t)(((4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 48u;
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(ra) : "v"(off), "s"(p.sal_tab));
-            asm volatile("global_load_dwordx2 %0, %1, %2 offset:16" : "=v"(rb) : "v"(off), "s"(p.sal_tab));
-        }
-    };
-    auto fetch_hd1 = [&](int sh, TileRegs<N8> (&tn)[4], int r) {      // the 5 loads of row tile r
-        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
-        const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
-        fetch_main<N8>(tn[r], p, (int64_t)__builtin_amdgcn_readfirstlane(rt * p.nsb + (sh >> 1)), lo);
-    };
-    auto fetch_hd = [&](int sh, TileRegs<N8> (&tn)[4]) {
-#pragma unroll
-        for (int r = 0; r < 4; r++) fetch_hd1(sh, tn, r);
-    };
-    const uint32_t* rsbase[4];                                      // res_sign words of the four row tiles (uniform)
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-        const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
-        rsbase[r] = p.res_sign + (int64_t)rt * p.res_words * 16;
-    }
-    auto load_res_words = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) {
-        const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
-        const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
-            rlo[r] = p.res_sign[((int64_t)rt * p.res_words + wa) * 16 + i];
-            rhi[r] = p.res_sign[((int64_t)rt * p.res_words + wb) * 16 + i];
-        }
-    };
-    auto fetch_res_words1 = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4], int r) {     // the 2 loads of row tile r
-        const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
-        const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
-        const uint32_t oa = (uint32_t)(wa * 16 + i) * 4u, ob = (uint32_t)(wb * 16 + i) * 4u;
-        asm volatile("global_load_dword %0, %1, %2" : "=v"(rlo[r]) : "v"(oa), "s"(rsbase[r]));
-        asm volatile("global_load_dword %0, %1, %2" : "=v"(rhi[r]) : "v"(ob), "s"(rsbase[r]));
-    };
-    auto fetch_res_words = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) {
-#pragma unroll
-        for (int r = 0; r < 4; r++) fetch_res_words1(ord, rlo, rhi, r);
-    };
-    auto scale_tables = [&](const HalfData<N8> (&hd)[4], uint32_t (&TL)[4], uint32_t (&TH)[4]) {
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            TL[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x06040200u);
-            TH[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x07050301u);
-        }
-    };
+    const GemmStage<N8, HAS_RES, TT> st(p, X, xsal, T, cfix, lds0, t0, rtw, wave, lane);
+    constexpr int NGL = TT / 4;
 
     // ---- the K step: 32 MFMAs (4 row tiles x 8 token tiles) on the A operands `ac` and the B operands b[]; in
     //      their shadow the lane builds the A operands of the next step (`next_a(r)` for row tile r) and, as soon
@@ -302,28 +368,12 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     uint2 rb = make_uint2(0u, 0u);
     uint32_t a0[4][4], a1[4][4];
     uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
-    x_gload(0, 0, 0);
-    x_gload(0, 1, 1);
-    r_gload(0, 0, 0);
-    {
-        // (asm loads here too: a load the compiler knows of would make it wait, inside the loop, for everything in flight)
-        TileRegs<N8> t0r[4];
-        uint4_t ra0 = {0u, 0u, 0u, 0u};
-        uint2_t rb0 = {0u, 0u};
-        fetch_hd(0, t0r);
-        fetch_rec(0, ra0, rb0);
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(ra0), "+v"(rb0) : : "memory");
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            asm volatile("s_waitcnt vmcnt(0)" : "+v"(t0r[r].m), "+v"(t0r[r].s), "+v"(t0r[r].r), "+v"(t0r[r].sc), "+v"(t0r[r].ar));
-            t0r[r].rlo = 0u; t0r[r].rhi = 0u;
-            unpack_tile<N8>(t0r[r], 0, hd[r]);
-        }
-        ra = make_uint4(ra0.x, ra0.y, ra0.z, ra0.w);
-        rb = make_uint2(rb0.x, rb0.y);
-    }
-    if (HAS_RES) fetch_res_words(rb.x, rlo, rhi);
-    scale_tables(hd, TL, TH);
+    st.x_gload(0, 0, 0);
+    st.x_gload(0, 1, 1);
+    st.r_gload(0, 0, 0);
+    st.first_records(hd, ra, rb);
+    if (HAS_RES) st.fetch_res_words(rb.x, rlo, rhi);
+    st.scale_tables(hd, TL, TH);
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < 4; r++) expand_group<N8>(hd[r], TL[r], TH[r], 0, lut_fetch<N8>(hd[r], 0, &lut, lane & 7), a0[r]);
@@ -356,8 +406,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         __syncthreads();                                            // ... everyone's; and everyone is done with window 0
         // (the loads are spread over the token tiles of a step, a few at a time: the four wavefronts share one path
         //  to memory, and a burst of loads stalls them all)
-        kstep(a1, produce(4, a0), reload(4), [&](int tt) { x_gload1(shn, 0, 0, tt); });
-        kstep(a0, produce(5, a1), reload(5), [&](int tt) { if (tt % 2 == 0 && tt < 8) fetch_hd1(shn, tn, tt / 2); if (tt == 7) fetch_rec(shn, ran, rbn); });
+        kstep(a1, produce(4, a0), reload(4), [&](int tt) { st.x_gload1(shn, 0, 0, tt); });
+        kstep(a0, produce(5, a1), reload(5), [&](int tt) { if (tt % 2 == 0 && tt < 8) st.fetch_hd1(shn, tn, tt / 2); if (tt == 7) st.fetch_rec(shn, ran, rbn); });
         kstep(a1, produce(6, a0), reload(6), nothing);
         kstep(a0, produce(7, a1), reload(7), nothing);
         // everything in flight has arrived: window 0 of the next pass, its half records and table record, and the
@@ -371,12 +421,12 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         uint32_t TLn[4], THn[4];
 #pragma unroll
         for (int r = 0; r < 4; r++) { tn[r].rlo = 0u; tn[r].rhi = 0u; unpack_tile<N8>(tn[r], shn & 1, hn[r]); }
-        scale_tables(hn, TLn, THn);
+        st.scale_tables(hn, TLn, THn);
         auto produce_n = [&](uint32_t (&an)[4][4]) {
             return [&](int r) { expand_group<N8>(hn[r], TLn[r], THn[r], 0, lut_fetch<N8>(hn[r], 0, &lut, lane & 7), an[r]); };
         };
         auto reload_n = [&](int tt) { bread(0, 0, tt); };
-        auto next_loads = [&](int tt) { x_gload1(shn, 1, 1, tt); if (tt >= TT - NGL) r_gload1(shn, 0, par ^ 1, tt - (TT - NGL)); };
+        auto next_loads = [&](int tt) { st.x_gload1(shn, 1, 1, tt); if (tt >= TT - NGL) st.r_gload1(shn, 0, par ^ 1, tt - (TT - NGL)); };
         if (HAS_RES) {
             // residual contraction (Eq. 4) of the first 8 salient columns of every half block: A from the mask and
             // res_sign bits, B = the gathered columns.  (A half block without salient columns has an all-zero A.)
@@ -389,7 +439,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
             auto reload_g = [&](int tt) { b[tt] = *reinterpret_cast<const uint4*>(lds + tt * 1024 + gxp); };
             kstep(a1, res_a, reload_g, next_loads);
             // (the res_sign words of the next pass: its table record arrived before the barrier above)
-            kstep(a0, produce_n(a1), reload_n, [&](int tt) { if (tt < 4) fetch_res_words1(rbn.x, rlo, rhi, tt); });
+            kstep(a0, produce_n(a1), reload_n, [&](int tt) { if (tt < 4) st.fetch_res_words1(rbn.x, rlo, rhi, tt); });
 #pragma unroll
             for (int r = 0; r < 4; r++)
 #pragma unroll
@@ -405,46 +455,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     // nothing may still be on its way to this workgroup's LDS or registers from here on
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
 
-    // ---- half blocks with more than 8 salient columns: their further records, one at a time and without any
-    //      overlap (few: a record covers 8 of the 64 columns).  Kept out of the main loop so that it stays one
-    //      straight line of K steps. ----
-    if (HAS_RES && p.sal_chunks > 1) {
-      for (int sh0 = 0; sh0 < nsh; sh0 += 64) {
-        // which of the next 64 half blocks have such records: lane l looks at half block sh0 + l
-        const int shl = sh0 + lane < nsh ? sh0 + lane : nsh - 1;
-        const uint32_t need_l = p.sal_tab[(((int64_t)(4 * (shl >> 1)) * 2 + (shl & 1)) * p.sal_chunks) * 12 + 5];
-        uint64_t todo = __ballot(need_l > 1u && sh0 + lane < nsh);
-        while (todo) {
-            const int sh = sh0 + __builtin_ctzll(todo);
-            todo &= todo - 1;
-            const uint32_t* rec0 = p.sal_tab + (((int64_t)(4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 12;
-            const int nch = __builtin_amdgcn_readfirstlane((int)rec0[5]);          // the same for the four blocks
-            load_hd(sh, hd);
-            for (int c = 1; c < nch; c++) {
-                __syncthreads();                             // every wavefront is done with the gathered columns
-                r_gload(sh, c, 0);
-                const uint4 rc = *reinterpret_cast<const uint4*>(rec0 + c * 12);
-                const uint32_t ord = rec0[c * 12 + 4];
-                load_res_words(ord, rlo, rhi);
-                asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
-                __syncthreads();
-                ResSel sel;
-                sel.sel0 = rc.x; sel.sel1 = rc.y; sel.bit0 = rc.z; sel.bit1 = rc.w;
-#pragma unroll
-                for (int r = 0; r < 4; r++)
-                    residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, a1[r]);
-#pragma unroll
-                for (int tt = 0; tt < TT; tt++) {
-                    const uint4 bt = *reinterpret_cast<const uint4*>(lds + G::XG + tt * 1024 + gx);
-                    const half8_t bv = __builtin_bit_cast(half8_t, bt);
-#pragma unroll
-                    for (int r = 0; r < 4; r++)
-                        acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(a1[r]), bv, acc[r][tt], 0, 0, 0);
-                }
-            }
-        }
-      }
-    }
+    st.further_records(acc, hd, a1, rlo, rhi, lds, nsh);
 
     __syncthreads();                                                // every wavefront is done with LDS
     store_tile<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
@@ -490,83 +501,8 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
 #pragma unroll
         for (int tt = 0; tt < TT; tt++) acc[r][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // ---- global -> LDS loads of the X windows and the gathered columns: as in gemm_tiled_kernel ----
-    const uint32_t tok_last = (uint32_t)(T - 1 - t0), k2 = (uint32_t)p.k * 2u;
-    uint32_t xpc[4];
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-        const uint32_t pc = (uint32_t)i ^ (uint32_t)(4 * j + g);
-        xpc[j] = (pc >> 2) * 256u + (pc & 3u) * 16u;
-    }
-    const __half* const Xt = X + (int64_t)t0 * p.k;
-    auto x_gload1 = [&](int sh, int win, int buf, int u) {
-        const uint32_t wcol = (uint32_t)((sh >> 1) * 1024 + (sh & 1) * 128 + win * 64);
-        const uint32_t dst = lds0 + G::XW + buf * G::XWSZ + wave * (TT * 1024);
-        const uint32_t c = xpc[u & 3] + wcol;
-        const uint32_t row = (uint32_t)(4 * (TT * wave + u)) + (uint32_t)g;
-        load_to_lds(dst + u * 1024, __umul24(row < tok_last ? row : tok_last, k2) + (c < k2 - 16u ? c : k2 - 16u), Xt);
-    };
-    const int64_t E = (int64_t)p.nsb * 2 * cfix * 32;
-    const __half* const xsal_t = xsal + (int64_t)t0 * E;
-    constexpr int NGL = TT / 4;                                     // gathered-column loads per wavefront (16 token rows each)
-    uint32_t grow[NGL];
-#pragma unroll
-    for (int u = 0; u < NGL; u++) {
-        const uint32_t row = (uint32_t)(16 * (NGL * wave + u) + (lane >> 2));
-        grow[u] = (row < tok_last ? row : tok_last) * (uint32_t)E * 2u + (((uint32_t)lane & 3u) ^ (((uint32_t)lane >> 4) & 3u)) * 16u;
-    }
-    auto r_gload1 = [&](int sh, int c, int par, int u) {
-        if (HAS_RES) load_to_lds(lds0 + G::XG + par * G::XGSZ + (NGL * wave + u) * 1024, grow[u] + (uint32_t)(sh * cfix + c) * 64u, xsal_t);
-    };
-    auto load_hd = [&](int sh, HalfData<N8> (&hd)[4]) {
-        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
-            load_half<N8>(p, (int64_t)rt * p.nsb + (sh >> 1), lo, sh & 1, hd[r]);
-        }
-    };
-    auto fetch_rec = [&](int sh, uint4_t& ra, uint2_t& rb) {
-        if (HAS_RES) {
-            const uint32_t off = (uint32_t)(((4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 48u;
-            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(ra) : "v"(off), "s"(p.sal_tab));
-            asm volatile("global_load_dwordx2 %0, %1, %2 offset:16" : "=v"(rb) : "v"(off), "s"(p.sal_tab));
-        }
-    };
-    auto fetch_hd1 = [&](int sh, TileRegs<N8> (&tn)[4], int r) {
-        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
-        const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
-        fetch_main<N8>(tn[r], p, (int64_t)__builtin_amdgcn_readfirstlane(rt * p.nsb + (sh >> 1)), lo);
-    };
-    const uint32_t* rsbase[4];
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-        const int rt = rtw + r < p.nrt ? rtw + r : p.nrt - 1;
-        rsbase[r] = p.res_sign + (int64_t)rt * p.res_words * 16;
-    }
-    auto load_res_words = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) {
-        const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
-        const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            rlo[r] = rsbase[r][wa * 16 + i];
-            rhi[r] = rsbase[r][wb * 16 + i];
-        }
-    };
-    auto fetch_res_words1 = [&](uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4], int r) {
-        const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
-        const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
-        const uint32_t oa = (uint32_t)(wa * 16 + i) * 4u, ob = (uint32_t)(wb * 16 + i) * 4u;
-        asm volatile("global_load_dword %0, %1, %2" : "=v"(rlo[r]) : "v"(oa), "s"(rsbase[r]));
-        asm volatile("global_load_dword %0, %1, %2" : "=v"(rhi[r]) : "v"(ob), "s"(rsbase[r]));
-    };
-    auto scale_tables = [&](const HalfData<N8> (&hd)[4], uint32_t (&TL)[4], uint32_t (&TH)[4]) {
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            TL[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x06040200u);
-            TH[r] = perm(hd[r].sc.y, hd[r].sc.x, 0x07050301u);
-        }
-    };
+    const GemmStage<N8, HAS_RES, TT> st(p, X, xsal, T, cfix, lds0, t0, rtw, wave, lane);
+    constexpr int NGL = TT / 4;
     // constants of the operand build, in VGPRs (a VOP3 instruction takes one literal)
     uint32_t T0 = 0x09080404u, T1 = 0x0E0E0D0Cu, K7 = 0x07070707u, K3 = 0x03030303u, K4 = 0x04000400u, KS = 0x80008000u;
     asm volatile("" : "+v"(T0), "+v"(T1), "+v"(K7), "+v"(K3), "+v"(K4), "+v"(KS));
@@ -635,34 +571,15 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     uint2 rb = make_uint2(0u, 0u);
     uint32_t a0[4][4], a1[4][4], ia[4], ib[4];
     uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int u = 0; u < TT; u++) x_gload1(0, 0, 0, u);
-#pragma unroll
-    for (int u = 0; u < TT; u++) x_gload1(0, 1, 1, u);
-    r_gload1(0, 0, 0, 0);
-    r_gload1(0, 0, 0, 1);
-    {
-        TileRegs<N8> t0r[4];
-        uint4_t ra0 = {0u, 0u, 0u, 0u};
-        uint2_t rb0 = {0u, 0u};
-#pragma unroll
-        for (int r = 0; r < 4; r++) fetch_hd1(0, t0r, r);
-        fetch_rec(0, ra0, rb0);
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(ra0), "+v"(rb0) : : "memory");
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            asm volatile("s_waitcnt vmcnt(0)" : "+v"(t0r[r].m), "+v"(t0r[r].s), "+v"(t0r[r].r), "+v"(t0r[r].sc), "+v"(t0r[r].ar));
-            t0r[r].rlo = 0u; t0r[r].rhi = 0u;
-            unpack_tile<N8>(t0r[r], 0, hd[r]);
-        }
-        ra = make_uint4(ra0.x, ra0.y, ra0.z, ra0.w);
-        rb = make_uint2(rb0.x, rb0.y);
-    }
+    st.x_gload(0, 0, 0);
+    st.x_gload(0, 1, 1);
+    st.r_gload(0, 0, 0);
+    st.first_records(hd, ra, rb);
     if (HAS_RES) {
 #pragma unroll
-        for (int r = 0; r < 4; r++) fetch_res_words1(rb.x, rlo, rhi, r);
+        for (int r = 0; r < 4; r++) st.fetch_res_words1(rb.x, rlo, rhi, r);
     }
-    scale_tables(hd, TL, TH);
+    st.scale_tables(hd, TL, TH);
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < 4; r++) { build_a(hd[r], TL[r], TH[r], 0, a0[r]); ia[r] = index_word24(hd[r].m[0], T0, T1, K7); }
@@ -684,12 +601,12 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
         auto nothing = [](int) {};
         // step 0 (window 0): builds step 1, fetches the next pass's records
         sstep(IntC<0>{}, a0, ia, [&](int r) { build_a(hd[r], TL[r], TH[r], 1, a1[r]); }, [&](int tt) { bread(0, 1, tt); },
-              [&](int tt) { if (tt % 2 == 0 && tt < 8) fetch_hd1(shn, tn, tt / 2); if (tt == 7) fetch_rec(shn, ran, rbn); });
+              [&](int tt) { if (tt % 2 == 0 && tt < 8) st.fetch_hd1(shn, tn, tt / 2); if (tt == 7) st.fetch_rec(shn, ran, rbn); });
         asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR + NH + NC) : "memory");     // window 1 and the gathered columns of this pass
         __syncthreads();                                            // ... everyone's; and everyone is done with window 0
         // step 1: builds step 2 (window 1) and its index word, loads window 0 of the next pass
         sstep(IntC<1>{}, a1, ia, [&](int r) { build_a(hd[r], TL[r], TH[r], 2, a0[r]); ib[r] = index_word24(hd[r].m[1], T0, T1, K7); },
-              [&](int tt) { bread(1, 0, tt); }, [&](int tt) { x_gload1(shn, 0, 0, tt); });
+              [&](int tt) { bread(1, 0, tt); }, [&](int tt) { st.x_gload1(shn, 0, 0, tt); });
         sstep(IntC<0>{}, a0, ib, [&](int r) { build_a(hd[r], TL[r], TH[r], 3, a1[r]); }, [&](int tt) { bread(1, 1, tt); }, nothing);
         // everything in flight has arrived
         asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]),
@@ -701,8 +618,8 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
         uint32_t TLn[4], THn[4];
 #pragma unroll
         for (int r = 0; r < 4; r++) { tn[r].rlo = 0u; tn[r].rhi = 0u; unpack_tile<N8>(tn[r], shn & 1, hn[r]); }
-        scale_tables(hn, TLn, THn);
-        auto next_loads = [&](int tt) { x_gload1(shn, 1, 1, tt); if (tt >= TT - NGL) r_gload1(shn, 0, par ^ 1, tt - (TT - NGL)); };
+        st.scale_tables(hn, TLn, THn);
+        auto next_loads = [&](int tt) { st.x_gload1(shn, 1, 1, tt); if (tt >= TT - NGL) st.r_gload1(shn, 0, par ^ 1, tt - (TT - NGL)); };
         auto reload_n = [&](int tt) { bread(0, 0, tt); };
         if (HAS_RES) {
             auto res_a = [&](int r) {
@@ -717,7 +634,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
             };
             sstep(IntC<1>{}, a1, ib, res_a, reload_g, next_loads);
             dstep(a0, [&](int r) { build_a(hn[r], TLn[r], THn[r], 0, a1[r]); ia[r] = index_word24(hn[r].m[0], T0, T1, K7); }, reload_n,
-                  [&](int tt) { if (tt < 4) fetch_res_words1(rbn.x, rlo, rhi, tt); });
+                  [&](int tt) { if (tt < 4) st.fetch_res_words1(rbn.x, rlo, rhi, tt); });
 #pragma unroll
             for (int r = 0; r < 4; r++)
 #pragma unroll
@@ -734,44 +651,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     }
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
 
-    // ---- further records of half blocks with more than 8 salient columns (as in gemm_tiled_kernel) ----
-    if (HAS_RES && p.sal_chunks > 1) {
-      for (int sh0 = 0; sh0 < nsh; sh0 += 64) {
-        const int shl = sh0 + lane < nsh ? sh0 + lane : nsh - 1;
-        const uint32_t need_l = p.sal_tab[(((int64_t)(4 * (shl >> 1)) * 2 + (shl & 1)) * p.sal_chunks) * 12 + 5];
-        uint64_t todo = __ballot(need_l > 1u && sh0 + lane < nsh);
-        while (todo) {
-            const int sh = sh0 + __builtin_ctzll(todo);
-            todo &= todo - 1;
-            const uint32_t* rec0 = p.sal_tab + (((int64_t)(4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 12;
-            const int nch = __builtin_amdgcn_readfirstlane((int)rec0[5]);
-            load_hd(sh, hd);
-            for (int c = 1; c < nch; c++) {
-                __syncthreads();
-                r_gload1(sh, c, 0, 0);
-                r_gload1(sh, c, 0, 1);
-                const uint4 rc = *reinterpret_cast<const uint4*>(rec0 + c * 12);
-                const uint32_t ord = rec0[c * 12 + 4];
-                load_res_words(ord, rlo, rhi);
-                asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
-                __syncthreads();
-                ResSel sel;
-                sel.sel0 = rc.x; sel.sel1 = rc.y; sel.bit0 = rc.z; sel.bit1 = rc.w;
-#pragma unroll
-                for (int r = 0; r < 4; r++)
-                    residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord & 31u), hd[r].ar | (hd[r].ar << 16), sel, a1[r]);
-#pragma unroll
-                for (int tt = 0; tt < TT; tt++) {
-                    const uint4 bt = *reinterpret_cast<const uint4*>(lds + G::XG + tt * 1024 + gx);
-                    const half8_t bv = __builtin_bit_cast(half8_t, bt);
-#pragma unroll
-                    for (int r = 0; r < 4; r++)
-                        acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(a1[r]), bv, acc[r][tt], 0, 0, 0);
-                }
-            }
-        }
-      }
-    }
+    st.further_records(acc, hd, a1, rlo, rhi, lds, nsh);
     __syncthreads();
     store_tile<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
 }
