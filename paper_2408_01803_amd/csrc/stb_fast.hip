@@ -15,13 +15,6 @@ using namespace stbt;
 #define STB_LUT_AHEAD 2
 #endif
 
-#ifdef STB_TRACE
-__device__ long long stb_trace_buf[4096 * 32];
-#define TRACE(slot) do { if (lane == 0) stb_trace_buf[((blockIdx.y * gridDim.x + blockIdx.x) * 16 + wave) % 4096 * 32 + (slot)] = wall_clock64(); } while (0)
-extern "C" int stb_trace_read(long long* host) { return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(stb_trace_buf), sizeof(long long) * 4096 * 32); }
-#else
-#define TRACE(slot) do {} while (0)
-#endif
 
 namespace {
 
@@ -146,7 +139,6 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
     constexpr int PH = STB_GEMV_PHASE;               // half tiles a wavefront streams between two reductions
     const int Wa = 2 * (p.nsb - ks * SPS < SPS ? p.nsb - ks * SPS : SPS);   // wavefronts of a row stream that have work
     const int q = 4 * sb + g;
-    TRACE(0);
 
     LaneOffsets lo = lane_offsets<N8>(lane, half);
     auto tile_of = [&](int rt) { return (int64_t)rt * p.nsb + sb; };
@@ -209,9 +201,7 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
             if (n_rw > 1) { const uint4_t* a = src + (t1i < rpieces ? t1i : 0); asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(rw1) : "v"(a)); }
         }
         if (active) fetch_main<N8>(t0, p, tile_of(clamp(r0)), lo);
-        TRACE(29);
         build_luts<N8>(&lut);                            // arithmetic only: overlaps with the loads in flight
-        TRACE(30);
         // the staging loads are older than the five of the first tile (which a wavefront without work has not issued)
         if (!active) asm volatile("s_waitcnt vmcnt(0)");
         asm volatile("s_waitcnt vmcnt(5)" : "+v"(sx0), "+v"(sx1), "+v"(sx2), "+v"(sx3), "+v"(sx4), "+v"(sx5), "+v"(sr), "+v"(rw0), "+v"(rw1));
@@ -225,7 +215,6 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
 #undef STB_STAGE_STORE
         if (HAS_RES && rI >= 0) *reinterpret_cast<uint4_t*>(&recs[rI * 12 + 4 * rpc]) = sr;
         __syncthreads();
-        TRACE(31);
         if (active) {
             const int ql = 4 * (sb - ks * SPS) + g;                   // block inside the split
             const char* xrow = xs + (i < B ? i : 0) * xstride + ql * 256;
@@ -262,10 +251,7 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
             fetch_tile<N8, false>(t1, p, tile_of(clamp(r0 + 1)), clamp(r0 + 1), lo);
             fetch_tile<N8, false>(t2, p, tile_of(clamp(r0 + 2)), clamp(r0 + 2), lo);
         }
-        TRACE(1);
         __syncthreads();                                 // every wavefront has taken its x: the area may be overwritten
-        TRACE(2);
-        TRACE(3);
     } else {
         // ---- every load that does not depend on another one goes out first: the packed planes of the first
         //      tile, x for the wavefront's columns, the first record of the salient-column table, the expansion
@@ -296,9 +282,7 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
                     asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "+v"(xr[t]) : "v"(xh), "n"(16 * t));
             }
         }
-        TRACE(29);
         build_luts<N8>(&lut);                            // arithmetic only: overlaps with the loads in flight
-        TRACE(30);
 
         // ---- the loads that depend on the table record (res_sign words of the first tile, x at the salient
         //      columns), then the second and third tile ----
@@ -307,7 +291,6 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
             if (HAS_RES) {
                 // the record has arrived once at most the 5 plane loads and 8 x loads behind it are outstanding
                 asm volatile("s_waitcnt vmcnt(13)" : "+v"(rec_a), "+v"(rec_b), "+v"(rec_p));
-                TRACE(31);
                 inv.sel.sel0 = rec_a.x; inv.sel.sel1 = rec_a.y; inv.sel.bit0 = rec_a.z; inv.sel.bit1 = rec_a.w;
                 inv.ord = rec_b.x;
                 nch = __builtin_amdgcn_readfirstlane((int)rec_b.y);
@@ -330,9 +313,7 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
             fetch_tile<N8, HAS_RES>(t1, p, tile_of(clamp(r0 + 1)), clamp(r0 + 1), lo);
             fetch_tile<N8, HAS_RES>(t2, p, tile_of(clamp(r0 + 2)), clamp(r0 + 2), lo);
         }
-        TRACE(1);
         __syncthreads();
-        TRACE(2);
 
         if (active) {
             // The first tile, x and the gathered x have arrived once only the 2 * L loads of the second and third
@@ -351,7 +332,6 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
 #pragma unroll
                 for (int v = 0; v < 4; v++) inv.xs[v] = h[2 * v] | (h[2 * v + 1] << 16);
             }
-            TRACE(3);
         }
 
     }
@@ -415,7 +395,6 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
         float* dst = part + ((int64_t)(wave * PH + slot) * 256 + lane);
 #pragma unroll
         for (int v = 0; v < 4; v++) dst[64 * v] = acc[v];
-        TRACE(14 + (slot < 5 ? slot : 5));
     };
 
     // The R tiles are taken in phases of PH (a multiple of 3, so that the three tile buffers keep their roles):
@@ -431,15 +410,12 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
         if (active) {
             for (int rt = ph0; rt < ph1; rt += 3) {
                 wait_tile<2 * L>(t0);
-                TRACE(8 + (rt - ph0 < 5 ? rt - ph0 : 5));
                 product(t0, rt, rt - ph0);
                 fetch_tile<N8, RES_GLOBAL>(t0, p, tile_of(clamp(rt + 3)), clamp(rt + 3), lo);
                 wait_tile<2 * L>(t1);
-                TRACE(8 + (rt + 1 - ph0 < 5 ? rt + 1 - ph0 : 5));
                 if (rt + 1 < ph1) product(t1, rt + 1, rt + 1 - ph0);
                 fetch_tile<N8, RES_GLOBAL>(t1, p, tile_of(clamp(rt + 4)), clamp(rt + 4), lo);
                 wait_tile<2 * L>(t2);
-                TRACE(8 + (rt + 2 - ph0 < 5 ? rt + 2 - ph0 : 5));
                 if (rt + 2 < ph1) product(t2, rt + 2, rt + 2 - ph0);
                 fetch_tile<N8, RES_GLOBAL>(t2, p, tile_of(clamp(rt + 5)), clamp(rt + 5), lo);
             }
@@ -469,9 +445,7 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
                 }
             }
         }
-        TRACE(5);
         __syncthreads();
-        TRACE(6);
         // outputs of this phase: (row stream, slot, b, row in tile), consecutive threads on consecutive rows
         const int total = RS * PH * B * 16;
         for (int o = threadIdx.x; o < total; o += blockDim.x) {
@@ -491,7 +465,6 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
         wait_tile<0>(t1);
         wait_tile<0>(t2);
     }
-    TRACE(7);
     if (S == 1) return;
 
     // ---- several column splits: the partial sums are in the workspace [split][16][n16]; take a ticket ----

@@ -32,13 +32,6 @@
 
 using namespace stbt;
 
-#ifdef STB_TRACE
-__device__ long long stb_trace_buf24[4096 * 32];
-#define TRACE(slot) do { if (lane == 0) stb_trace_buf24[((blockIdx.y * gridDim.x + blockIdx.x) * 8 + wave) % 4096 * 32 + (slot)] = wall_clock64(); } while (0)
-extern "C" int stb_trace_read24(long long* host) { return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(stb_trace_buf24), sizeof(long long) * 4096 * 32); }
-#else
-#define TRACE(slot) do {} while (0)
-#endif
 
 namespace {
 
@@ -274,7 +267,6 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
     char* const wreg = lds_base + (int64_t)wave * WREG;
     float* const part = reinterpret_cast<float*>(wreg + PART_OFF);
     uint32_t* const recs = reinterpret_cast<uint32_t*>(wreg + REC_OFF);         // [visit][block g][half][record 0 / 1] x 12
-    TRACE(0);
 
     if constexpr (MODE != 2) build_luts<N8>(lut);                // arithmetic only; the barrier comes after the staging
     half16_t xr[8];                                              // MODE 2: B operands of the 8 steps of a block
@@ -373,7 +365,6 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
             asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(sr) : "v"(src));
         }
         fetch24(t0, p, tile_of(clamp(r0)), o8, o4, o2);
-        TRACE(1);
         // The second and third tile go out after the operands are in registers: a compute unit keeps a limited
         // number of loads in flight, and the other wavefront of the SIMD should get its first tile early too
         // (issuing them here instead was measured: no faster with one wavefront per SIMD, slower with two).
@@ -417,7 +408,6 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
                 }
             }
         }
-        TRACE(2);
     }
     if constexpr (MODE != 2) __syncthreads();       // the scatter table is complete (every wavefront comes here)
     // ---- the wavefront takes the B operands, the records and the x of the salient columns of visit v back from LDS
@@ -516,7 +506,6 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         if (++pv == V) { pv = 0; ++prt; }            // t0 holds (r0, visit 0)
         fetch_next(t1);
         fetch_next(t2);
-        TRACE(4);
     }
 
     // index table of index_word and the other constants, in VGPRs (a VOP3 instruction takes one constant)
@@ -684,9 +673,7 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
                     for (int v = 0; v < 4; v++) dst[64 * v] += e[v];
                 }
         }
-        TRACE(6);
         __syncthreads();
-        TRACE(7);
         // outputs of this phase: (slot, b, row in tile), consecutive threads on consecutive rows
         const int total = (ph1 > ph0 ? ph1 - ph0 : 0) * B * 16;
         for (int o = threadIdx.x; o < total; o += nthr) {
@@ -710,7 +697,6 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
         wait24<0>(t1);
         wait24<0>(t2);
     }
-    TRACE(20);
     if (S == 1) return;
 
     // ---- several column splits: the partial sums are in the workspace [split][16][n16]; take a ticket.  They are
