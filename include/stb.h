@@ -218,7 +218,8 @@ int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const voi
  * generic kernel for any N:M (it rounds the dequantised salient weights to fp16).
  * Tiled 2:4 layers run on the structured-sparse matrix instruction (kept weights plus an index word as the operand,
  * Sec. 3.1 / App. C); Environment: STB_GEMM_KERNEL=dense (read at every call) keeps them on the dense-instruction
- * kernel that 4:8 and 6:8 layers use: for tests and comparisons.
+ * kernel that 4:8 and 6:8 layers use (16x16x32 form of the instruction); STB_GEMM_KERNEL=dense32 runs any tiled
+ * layer on the 32x32x16 form of that kernel: for tests and comparisons.
  * X: device fp16 [T][k], finite values (a padding column or token re-reads valid elements of X and meets zero
  * weights or an output that is never stored).  Y: device [T][n], fp16 or fp32, fully overwritten.  workspace: device scratch of at
  * least stb_gemm_workspace_bytes() bytes, 256-byte aligned (may be NULL when that is 0); it needs no
@@ -241,7 +242,9 @@ int stb_probe_read(const void* src, int64_t bytes, void* sink, void* stream);
 
 /* Measurement aid: `n_workgroups` workgroups of four wavefronts (one per SIMD) each issue `steps` x 32 matrix
  * instructions on 32 independent accumulators, with `valu` (0, 2 or 3) vector instructions after each.
- * kind 0: v_mfma_f32_16x16x32_f16 (the dense prefill kernel's), kind 1: v_smfmac_f32_16x16x64_f16 (the 2:4 one's).
+ * kind 0: v_mfma_f32_16x16x32_f16 (the dense prefill kernel's), kind 1: v_smfmac_f32_16x16x64_f16 (the 2:4 one's),
+ * kind 2: v_mfma_f32_32x32x16_f16, kind 3: v_smfmac_f32_32x32x32_f16 (the 32x32 forms, on 8 accumulators; no kernel
+ * here uses them yet: measured to see what a tile of that shape could reach).
  * Every thread writes 16 bytes to `sink` (device, 16-byte aligned, n_workgroups * 4096 bytes).  Timing it gives the
  * instruction rate this GPU sustains, the practical ceiling that the prefill kernels' TFLOP/s is compared with.
  * Errors: STB_ENULL, STB_EINVAL (other kind / valu, steps < 1, n_workgroups outside 1..65536), STB_EALIGN, STB_EHIP. */

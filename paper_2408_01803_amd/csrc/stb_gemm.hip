@@ -18,6 +18,7 @@
 // residual_chunk, its B operand from a compact copy of the salient columns of X that gemm_gather_kernel
 // writes to the workspace beforehand.
 #include <cstdlib>
+#include <cstring>
 
 #include "stb_tiled.hpp"
 
@@ -137,7 +138,10 @@ __device__ inline void load_to_lds(uint32_t lds_addr, uint32_t voff, const void*
 // out where they are written, K steps ahead of their use, and the compiler neither sinks them down to it nor
 // waits for them on its own (a load the compiler knows of makes it wait for everything in flight).
 // ------------------------------------------------------------------------------------------------
-template <int N8, bool HAS_RES, int TT>
+// WIDE (the kernel on the 32x32x16 instruction): lane 16 g + i is row 16 (g % 2) + i of a 32-row operand and K half
+// g / 2, so its record r = 2 rs + bs (0..3) is (row tile 2 rs + g % 2 of the wavefront, block 2 (g / 2) + bs of the
+// superblock) instead of (row tile r, block g): the same 256 records per wavefront and pass, dealt differently.
+template <int N8, bool HAS_RES, int TT, bool WIDE = false>
 struct GemmStage {
     typedef GmLds<TT> G;
     static constexpr int NGL = TT / 4;         // gathered-column loads per wavefront (16 token rows each)
@@ -146,6 +150,7 @@ struct GemmStage {
     const __half* xsal_t;                      // gathered salient columns at the workgroup's first token
     const uint32_t* rsbase[4];                 // res_sign words of the wavefront's four row tiles (uniform)
     uint32_t lds0, tok_last, k2, xpc[4], grow[NGL];
+    uint32_t dn[2], dres[2];                   // WIDE: from the uniform base of row-tile pair rs to the lane's own row tile, in tiles / res_sign bytes
     int cfix, rtw, wave, lane, i, g;
 
     __device__ GemmStage(const TiledPlanes& p_, const __half* X, const __half* xsal, int T, int cfix_, uint32_t lds0_, int t0,
@@ -173,9 +178,30 @@ struct GemmStage {
             grow[u] = (row < tok_last ? row : tok_last) * (uint32_t)E * 2u + (((uint32_t)lane & 3u) ^ (((uint32_t)lane >> 4) & 3u)) * 16u;
         }
 #pragma unroll
-        for (int r = 0; r < 4; r++) rsbase[r] = p.res_sign + (int64_t)row_tile(r) * p.res_words * 16;
+        for (int rs = 0; rs < 2; rs++) {
+            const int mine = rtw + 2 * rs + (g & 1) < p.nrt ? rtw + 2 * rs + (g & 1) : p.nrt - 1;
+            dn[rs] = WIDE ? (uint32_t)((mine - row_tile(2 * rs)) * p.nsb) : 0u;
+            dres[rs] = WIDE ? (uint32_t)((mine - row_tile(2 * rs)) * p.res_words) * 64u : 0u;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; r++) rsbase[r] = p.res_sign + (int64_t)base_tile(r) * p.res_words * 16;
     }
     __device__ int row_tile(int r) const { return rtw + r < p.nrt ? rtw + r : p.nrt - 1; }
+    // record r of the lane: the uniform row tile its loads start from, its block, its offsets inside the planes
+    __device__ int base_tile(int r) const { return WIDE ? row_tile(2 * (r >> 1)) : row_tile(r); }
+    __device__ int block_of(int r) const { return WIDE ? 2 * (g >> 1) + (r & 1) : g; }
+    __device__ LaneOffsets offsets(int sh, int r) const {
+        LaneOffsets lo = lane_offsets<N8>(WIDE ? 16 * block_of(r) + i : lane, sh & 1);
+        if (WIDE) {
+            const uint32_t d = dn[r >> 1];
+            lo.omask += d * (64u * 16u);
+            lo.osign += d * (64u * 2u * N8);
+            lo.oregion += d * (64u * 4u * N8);
+            lo.o8 += d * (64u * 8u);
+            lo.o2 += d * (64u * 2u);
+        }
+        return lo;
+    }
 
     // load u (0 .. TT-1) of the wavefront's share of window `win` of (superblock, half) sh into window buffer `buf`
     __device__ void x_gload1(int sh, int win, int buf, int u) const {
@@ -199,9 +225,8 @@ struct GemmStage {
     }
     // plain loads (tail loop only)
     __device__ void load_hd(int sh, HalfData<N8> (&hd)[4]) const {
-        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
 #pragma unroll
-        for (int r = 0; r < 4; r++) load_half<N8>(p, (int64_t)row_tile(r) * p.nsb + (sh >> 1), lo, sh & 1, hd[r]);
+        for (int r = 0; r < 4; r++) load_half<N8>(p, (int64_t)base_tile(r) * p.nsb + (sh >> 1), offsets(sh, r), sh & 1, hd[r]);
     }
     __device__ void load_res_words(uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4]) const {
         const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
@@ -212,23 +237,31 @@ struct GemmStage {
             rhi[r] = rsbase[r][wb * 16 + i];
         }
     }
+    // (WIDE: the words of record r alone, at the lane's own row tile)
+    __device__ void load_res_words1(uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4], int r) const {
+        const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+        const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+        const char* base = reinterpret_cast<const char*>(rsbase[r]) + dres[r >> 1];
+        rlo[r] = *reinterpret_cast<const uint32_t*>(base + (wa * 16 + i) * 4);
+        rhi[r] = *reinterpret_cast<const uint32_t*>(base + (wb * 16 + i) * 4);
+    }
     // asm loads: the table record of (superblock, half) sh (2 loads), the half records of row tile r (5 loads), the
     // res_sign words of row tile r (2 loads)
-    __device__ void fetch_rec(int sh, uint4_t& ra, uint2_t& rb) const {
+    __device__ void fetch_rec(int sh, uint4_t& ra, uint2_t& rb, int r = 0) const {
         if (HAS_RES) {
-            const uint32_t off = (uint32_t)(((4 * (sh >> 1) + g) * 2 + (sh & 1)) * p.sal_chunks) * 48u;
+            const uint32_t off = (uint32_t)(((4 * (sh >> 1) + block_of(r)) * 2 + (sh & 1)) * p.sal_chunks) * 48u;
             asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(ra) : "v"(off), "s"(p.sal_tab));
             asm volatile("global_load_dwordx2 %0, %1, %2 offset:16" : "=v"(rb) : "v"(off), "s"(p.sal_tab));
         }
     }
     __device__ void fetch_hd1(int sh, TileRegs<N8> (&tn)[4], int r) const {
-        const LaneOffsets lo = lane_offsets<N8>(lane, sh & 1);
-        fetch_main<N8>(tn[r], p, (int64_t)__builtin_amdgcn_readfirstlane(row_tile(r) * p.nsb + (sh >> 1)), lo);
+        const LaneOffsets lo = offsets(sh, r);
+        fetch_main<N8>(tn[r], p, (int64_t)__builtin_amdgcn_readfirstlane(base_tile(r) * p.nsb + (sh >> 1)), lo);
     }
     __device__ void fetch_res_words1(uint32_t ord, uint32_t (&rlo)[4], uint32_t (&rhi)[4], int r) const {
         const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
         const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
-        const uint32_t oa = (uint32_t)(wa * 16 + i) * 4u, ob = (uint32_t)(wb * 16 + i) * 4u;
+        const uint32_t oa = (uint32_t)(wa * 16 + i) * 4u + dres[r >> 1], ob = (uint32_t)(wb * 16 + i) * 4u + dres[r >> 1];
         asm volatile("global_load_dword %0, %1, %2" : "=v"(rlo[r]) : "v"(oa), "s"(rsbase[r]));
         asm volatile("global_load_dword %0, %1, %2" : "=v"(rhi[r]) : "v"(ob), "s"(rsbase[r]));
     }
@@ -244,14 +277,19 @@ struct GemmStage {
         }
     }
     // the first pass's half records and table record (asm loads here too), waited for on the spot
-    __device__ void first_records(HalfData<N8> (&hd)[4], uint4& ra, uint2& rb) const {
+    __device__ void first_records(HalfData<N8> (&hd)[4], uint4& ra, uint2& rb, uint4* ra_odd = nullptr, uint2* rb_odd = nullptr) const {
         TileRegs<N8> t0r[4];
-        uint4_t ra0 = {0u, 0u, 0u, 0u};
-        uint2_t rb0 = {0u, 0u};
+        uint4_t ra0 = {0u, 0u, 0u, 0u}, ra1 = {0u, 0u, 0u, 0u};
+        uint2_t rb0 = {0u, 0u}, rb1 = {0u, 0u};
 #pragma unroll
         for (int r = 0; r < 4; r++) fetch_hd1(0, t0r, r);
         fetch_rec(0, ra0, rb0);
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(ra0), "+v"(rb0) : : "memory");
+        if (WIDE) fetch_rec(0, ra1, rb1, 1);
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(ra0), "+v"(rb0), "+v"(ra1), "+v"(rb1) : : "memory");
+        if (WIDE) {
+            *ra_odd = make_uint4(ra1.x, ra1.y, ra1.z, ra1.w);
+            *rb_odd = make_uint2(rb1.x, rb1.y);
+        }
 #pragma unroll
         for (int r = 0; r < 4; r++) {
             asm volatile("s_waitcnt vmcnt(0)" : "+v"(t0r[r].m), "+v"(t0r[r].s), "+v"(t0r[r].r), "+v"(t0r[r].sc), "+v"(t0r[r].ar));
@@ -462,6 +500,276 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
 }
 
 // ------------------------------------------------------------------------------------------------
+// The same pipeline on v_mfma_f32_32x32x16_f16 (asked for by name, see stb_tiled_gemm).  Measured with nothing else
+// going on, a SIMD sustains about 2450 TFLOP/s (chip-wide) of these against about 1450 of the 16x16x32 form; in this
+// pipeline the two forms take the same time to within 1 %, which says that the matrix pipe is not what holds it up.
+// Per wavefront the tile is the same (64 rows x 128 tokens, 128 accumulator
+// registers: 2 x 4 tiles of 32 x 32) and so are the windows, the expansion and the loads; what differs is who holds
+// what (WIDE in GemmStage): an instruction contracts 8 columns of block 2 (g / 2) + bs from each K half, bs = 0 / 1
+// alternating, so a "step" below is the pair of them: 16 instructions, four operand builds, eight B reads.
+//   A  lane 16 g + i: row 16 (g % 2) + i of the 32-row tile rs (row tiles 2 rs, 2 rs + 1), K half g / 2
+//   B  lane 16 g + i: token 16 (g % 2) + i of the 32-token tile q, K half g / 2
+//   D  lane l, register v: token l % 32, row 8 (v / 4) + 4 (l / 32) + v % 4
+// ------------------------------------------------------------------------------------------------
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+template <int TT>
+__device__ inline void store_tile_wide(const float16_t (&acc)[2][TT / 2], char* lds, const TiledPlanes& p, void* __restrict__ Y,
+                                       int y_fp32, int T, int t0, int rtw, int wave, int lane) {
+    const int i = lane & 15, g = lane >> 4;
+    const int tl0 = 16 * (g & 1) + i, rl0 = 4 * (g >> 1);           // token inside a 32-token tile, first row inside an 8-row band
+    const bool wide = !y_fp32 && (p.n & 7) == 0 && ((uintptr_t)Y & 15) == 0 && (rtw + 4) * 16 <= p.n;     // uniform per wavefront
+    if (wide) {
+        // through LDS as in store_tile: token rows of 144 bytes, the wavefront's 64 rows in each
+        char* const ep = lds + wave * (16 * TT * 144);
+#pragma unroll
+        for (int rs = 0; rs < 2; rs++)
+#pragma unroll
+            for (int q = 0; q < TT / 2; q++)
+#pragma unroll
+                for (int vq = 0; vq < 4; vq++) {
+                    const __half2 lo = __floats2half2_rn(-acc[rs][q][4 * vq + 0], -acc[rs][q][4 * vq + 1]);
+                    const __half2 hi = __floats2half2_rn(-acc[rs][q][4 * vq + 2], -acc[rs][q][4 * vq + 3]);
+                    uint2 v;
+                    v.x = __builtin_bit_cast(uint32_t, lo);
+                    v.y = __builtin_bit_cast(uint32_t, hi);
+                    *reinterpret_cast<uint2*>(ep + (32 * q + tl0) * 144 + (32 * rs + 8 * vq + rl0) * 2) = v;
+                }
+        __half* const Yh = reinterpret_cast<__half*>(Y);
+#pragma unroll
+        for (int it = 0; it < 2 * TT; it++) {
+            const int tl = 8 * it + (lane >> 3), tok = t0 + tl;
+            const uint4 v = *reinterpret_cast<const uint4*>(ep + tl * 144 + (lane & 7) * 16);
+            if (tok < T) *reinterpret_cast<uint4*>(Yh + (int64_t)tok * p.n + rtw * 16 + (lane & 7) * 8) = v;
+        }
+        return;
+    }
+#pragma unroll
+    for (int rs = 0; rs < 2; rs++)
+#pragma unroll
+        for (int q = 0; q < TT / 2; q++) {
+            const int tok = t0 + 32 * q + tl0;
+            if (tok >= T) continue;
+#pragma unroll
+            for (int v = 0; v < 16; v++) {
+                const int row = rtw * 16 + 32 * rs + 8 * (v >> 2) + rl0 + (v & 3);
+                if (row >= p.n) continue;
+                const float val = -acc[rs][q][v];
+                if (y_fp32) reinterpret_cast<float*>(Y)[(int64_t)tok * p.n + row] = val;
+                else reinterpret_cast<__half*>(Y)[(int64_t)tok * p.n + row] = __float2half(val);
+            }
+        }
+}
+
+template <int N8, bool HAS_RES>
+__global__ __launch_bounds__(256) void gemm_wide_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
+                                                         void* __restrict__ Y, int y_fp32,
+                                                         const __half* __restrict__ xsal, int cfix) {
+    constexpr int TT = GM_TT;                                       // B operands per step: 4 token tiles of 32 x the 2 blocks of a K half
+    constexpr int TQ = TT / 2;
+    typedef GmLds<TT> G;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    ScatterLds& lut = *reinterpret_cast<ScatterLds*>(lds + G::LUT);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int i = lane & 15, g = lane >> 4;
+    const int t0 = blockIdx.x * G::TOK;
+    const int rtw = blockIdx.y * GM_ROWT + wave * 4;
+    const int nsh = p.nsb * 2;
+    build_luts<N8>(&lut);
+
+    float16_t acc[2][TQ];
+#pragma unroll
+    for (int rs = 0; rs < 2; rs++)
+#pragma unroll
+        for (int q = 0; q < TQ; q++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc[rs][q][v] = 0.0f;
+
+    const GemmStage<N8, HAS_RES, TT, true> st(p, X, xsal, T, cfix, lds0, t0, rtw, wave, lane);
+    constexpr int NGL = TT / 4;
+
+    // ---- the step: B operand u = (bs = u / TQ, token tile q = u % TQ) meets the A operands of records 2 rs + bs;
+    //      the two uses of an accumulator are TT instructions apart ----
+    uint4 b[TT];
+    auto kstep = [&](const uint32_t (&ac)[4][4], auto&& next_a, auto&& next_b, auto&& extra) {
+#pragma unroll
+        for (int u = 0; u < TT; u++) {
+            const half8_t bv = __builtin_bit_cast(half8_t, b[u]);
+#pragma unroll
+            for (int rs = 0; rs < 2; rs++)
+                acc[rs][u % TQ] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(ac[2 * rs + u / TQ]), bv, acc[rs][u % TQ], 0, 0, 0);
+            next_b(u);
+            if (u % (TT / 4) == 0) next_a(u / (TT / 4));
+            extra(u);
+        }
+    };
+    // B operand u: row 32 q + 16 (g % 2) + i of the window, piece 4 (2 (g / 2) + bs) + tq, at position piece ^ i
+    uint32_t bx[2][2][4];
+#pragma unroll
+    for (int buf = 0; buf < 2; buf++)
+#pragma unroll
+        for (int bs = 0; bs < 2; bs++)
+#pragma unroll
+            for (int tq = 0; tq < 4; tq++)
+                bx[buf][bs][tq] = (uint32_t)(G::XW + buf * G::XWSZ + (16 * (g & 1) + i) * 256 + ((4 * (2 * (g >> 1) + bs) + tq) ^ i) * 16);
+    auto bread = [&](int buf, int tq, int u) {
+        b[u] = *reinterpret_cast<const uint4*>(lds + (u % TQ) * 8192 + bx[buf][u / TQ][tq]);
+    };
+    // gathered columns: row as above (64 bytes each), piece 2 (g / 2) + bs at position piece ^ ((row / 4) % 4)
+    uint32_t gx[2];
+#pragma unroll
+    for (int bs = 0; bs < 2; bs++) gx[bs] = (uint32_t)((16 * (g & 1) + i) * 64 + ((2 * (g >> 1) + bs) ^ ((i >> 2) & 3)) * 16);
+
+    // ---- prologue ----
+    HalfData<N8> hd[4];
+    uint32_t TL[4], TH[4];
+    uint4 ra[2] = {make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u)};
+    uint2 rb[2] = {make_uint2(0u, 0u), make_uint2(0u, 0u)};
+    uint32_t a0[4][4], a1[4][4];
+    uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
+    st.x_gload(0, 0, 0);
+    st.x_gload(0, 1, 1);
+    st.r_gload(0, 0, 0);
+    st.first_records(hd, ra[0], rb[0], &ra[1], &rb[1]);
+    if (HAS_RES) {
+#pragma unroll
+        for (int r = 0; r < 4; r++) st.fetch_res_words1(rb[r & 1].x, rlo, rhi, r);
+    }
+    st.scale_tables(hd, TL, TH);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; r++) expand_group<N8>(hd[r], TL[r], TH[r], 0, lut_fetch<N8>(hd[r], 0, &lut, lane & 7), a0[r]);
+#pragma unroll
+    for (int u = 0; u < TT; u++) bread(0, 0, u);
+
+    // Loads of one pass, in issue order (the NR res_sign words of this pass are older than all of them):
+    //   [step 3, after the first barrier]  window 0 of the next pass (8)
+    //   [step 4]                           the next pass's half records and table records
+    //   [step 7, after the second barrier] window 1 (8) and gathered columns of the next pass
+    //   [residual step]                    res_sign words of the next pass (NR)
+    constexpr int NR = HAS_RES ? 8 : 0;
+    for (int sh = 0; sh < nsh; sh++) {
+        const int shn = sh + 1 < nsh ? sh + 1 : sh;
+        const int par = sh & 1;
+        TileRegs<N8> tn[4];
+        uint4_t ran[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+        uint2_t rbn[2] = {{0u, 0u}, {0u, 0u}};
+        auto produce = [&](int t, uint32_t (&an)[4][4]) {
+            return [&, t](int r) { expand_group<N8>(hd[r], TL[r], TH[r], t, lut_fetch<N8>(hd[r], t, &lut, lane & 7), an[r]); };
+        };
+        auto reload = [&](int t) { return [&, t](int u) { bread(t >> 2, t & 3, u); }; };
+        auto nothing = [](int) {};
+
+        kstep(a0, produce(1, a1), reload(1), nothing);
+        kstep(a1, produce(2, a0), reload(2), nothing);
+        kstep(a0, produce(3, a1), reload(3), nothing);
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR) : "memory");  // window 1 and the gathered columns of this pass are in LDS
+        __syncthreads();
+        kstep(a1, produce(4, a0), reload(4), [&](int u) { st.x_gload1(shn, 0, 0, u); });
+        kstep(a0, produce(5, a1), reload(5), [&](int u) {
+            if (u % 2 == 0) st.fetch_hd1(shn, tn, u / 2);
+            if (u == 5) st.fetch_rec(shn, ran[0], rbn[0], 0);
+            if (u == 7) st.fetch_rec(shn, ran[1], rbn[1], 1);
+        });
+        kstep(a1, produce(6, a0), reload(6), nothing);
+        kstep(a0, produce(7, a1), reload(7), nothing);
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]),
+                     "+v"(ran[0]), "+v"(rbn[0]), "+v"(ran[1]), "+v"(rbn[1]) : : "memory");
+#pragma unroll
+        for (int r = 0; r < 4; r++) asm volatile("s_waitcnt vmcnt(0)" : "+v"(tn[r].m), "+v"(tn[r].s), "+v"(tn[r].r), "+v"(tn[r].sc), "+v"(tn[r].ar));
+        __syncthreads();                                            // everyone is done with window 1
+        HalfData<N8> hn[4];
+        uint32_t TLn[4], THn[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) { tn[r].rlo = 0u; tn[r].rhi = 0u; unpack_tile<N8>(tn[r], shn & 1, hn[r]); }
+        st.scale_tables(hn, TLn, THn);
+        auto produce_n = [&](uint32_t (&an)[4][4]) {
+            return [&](int r) { expand_group<N8>(hn[r], TLn[r], THn[r], 0, lut_fetch<N8>(hn[r], 0, &lut, lane & 7), an[r]); };
+        };
+        auto reload_n = [&](int u) { bread(0, 0, u); };
+        auto next_loads = [&](int u) { st.x_gload1(shn, 1, 1, u); if (u >= TT - NGL) st.r_gload1(shn, 0, par ^ 1, u - (TT - NGL)); };
+        if (HAS_RES) {
+            // residual contraction (Eq. 4) of the first 8 salient columns of every half block
+            auto res_a = [&](int r) {
+                ResSel sel;
+                sel.sel0 = ra[r & 1].x; sel.sel1 = ra[r & 1].y; sel.bit0 = ra[r & 1].z; sel.bit1 = ra[r & 1].w;
+                residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], rb[r & 1].x & 31u), hd[r].ar | (hd[r].ar << 16), sel, a0[r]);
+            };
+            const uint32_t gbase = (uint32_t)(G::XG + par * G::XGSZ);
+            auto reload_g = [&](int u) { b[u] = *reinterpret_cast<const uint4*>(lds + (u % TQ) * 2048 + gbase + gx[u / TQ]); };
+            kstep(a1, res_a, reload_g, next_loads);
+            kstep(a0, produce_n(a1), reload_n, [&](int u) { if (u < 4) st.fetch_res_words1(rbn[u & 1].x, rlo, rhi, u); });
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+#pragma unroll
+                for (int v = 0; v < 4; v++) a0[r][v] = a1[r][v];
+        } else {
+            kstep(a1, produce_n(a0), reload_n, next_loads);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; r++) { hd[r] = hn[r]; TL[r] = TLn[r]; TH[r] = THn[r]; }
+#pragma unroll
+        for (int bs = 0; bs < 2; bs++) {
+            ra[bs] = make_uint4(ran[bs].x, ran[bs].y, ran[bs].z, ran[bs].w);
+            rb[bs] = make_uint2(rbn[bs].x, rbn[bs].y);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
+
+    // half blocks with more than 8 salient columns: their further records, one at a time (as further_records)
+    if (HAS_RES && p.sal_chunks > 1) {
+        for (int sh0 = 0; sh0 < nsh; sh0 += 64) {
+            const int shl = sh0 + lane < nsh ? sh0 + lane : nsh - 1;
+            const uint32_t need_l = p.sal_tab[(((int64_t)(4 * (shl >> 1)) * 2 + (shl & 1)) * p.sal_chunks) * 12 + 5];
+            uint64_t todo = __ballot(need_l > 1u && sh0 + lane < nsh);
+            while (todo) {
+                const int sh = sh0 + __builtin_ctzll(todo);
+                todo &= todo - 1;
+                const uint32_t* rec0[2];
+#pragma unroll
+                for (int bs = 0; bs < 2; bs++)
+                    rec0[bs] = p.sal_tab + (((int64_t)(4 * (sh >> 1) + 2 * (g >> 1) + bs) * 2 + (sh & 1)) * p.sal_chunks) * 12;
+                const int nch = __builtin_amdgcn_readfirstlane((int)rec0[0][5]);       // the same for the four blocks
+                st.load_hd(sh, hd);
+                for (int c = 1; c < nch; c++) {
+                    __syncthreads();                             // every wavefront is done with the gathered columns
+                    st.r_gload(sh, c, 0);
+                    uint4 rc[2];
+                    uint32_t ord[2];
+#pragma unroll
+                    for (int bs = 0; bs < 2; bs++) {
+                        rc[bs] = *reinterpret_cast<const uint4*>(rec0[bs] + c * 12);
+                        ord[bs] = rec0[bs][c * 12 + 4];
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; r++) st.load_res_words1(ord[r & 1], rlo, rhi, r);
+                    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+                    __syncthreads();
+#pragma unroll
+                    for (int r = 0; r < 4; r++) {
+                        ResSel sel;
+                        sel.sel0 = rc[r & 1].x; sel.sel1 = rc[r & 1].y; sel.bit0 = rc[r & 1].z; sel.bit1 = rc[r & 1].w;
+                        residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord[r & 1] & 31u), hd[r].ar | (hd[r].ar << 16), sel, a1[r]);
+                    }
+#pragma unroll
+                    for (int u = 0; u < TT; u++) {
+                        const uint4 bt = *reinterpret_cast<const uint4*>(lds + G::XG + (u % TQ) * 2048 + gx[u / TQ]);
+                        const half8_t bv = __builtin_bit_cast(half8_t, bt);
+#pragma unroll
+                        for (int rs = 0; rs < 2; rs++)
+                            acc[rs][u % TQ] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(a1[2 * rs + u / TQ]), bv, acc[rs][u % TQ], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    __syncthreads();                                                // every wavefront is done with LDS
+    store_tile_wide<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
 // 2:4 layers on the structured-sparse matrix instruction (Sec. 3.1 / App. C: the paper's own kernel form):
 // v_smfmac_f32_16x16x64_f16 takes the kept weights only (8 per lane = 16 columns of the lane's block) and an index
 // word that says which 2 of every 4 columns they are, and contracts them with 64 columns of X at once.  Half the
@@ -666,6 +974,16 @@ hipError_t launch_gemm(dim3 grid, hipStream_t st, const TiledPlanes& p, const __
     return hipGetLastError();
 }
 
+template <int N8, bool HAS_RES>
+hipError_t launch_gemm_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
+                            const __half* xsal, int cfix) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_wide_kernel<N8, HAS_RES>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((gemm_wide_kernel<N8, HAS_RES>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix);
+    return hipGetLastError();
+}
+
 template <bool HAS_RES>
 hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                          const __half* xsal, int cfix) {
@@ -685,32 +1003,50 @@ hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const 
 namespace {
 template <int KIND, int V>
 __global__ __launch_bounds__(256) void probe_mfma_kernel(int steps, float4_t* __restrict__ sink) {
+    typedef float float16_t __attribute__((ext_vector_type(16)));
+    constexpr bool WIDE = KIND >= 2;                    // 32x32 tiles: 8 accumulators of 16 registers, else 32 of 4
     float4_t acc[32];
+    float16_t accw[8];
 #pragma unroll
     for (int q = 0; q < 32; q++) acc[q] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int q = 0; q < 8; q++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) accw[q][e] = 0.0f;
     const uint32_t seed = threadIdx.x * 0x9E3779B9u + blockIdx.x;
     uint32_t w[8];
 #pragma unroll
     for (int j = 0; j < 8; j++) w[j] = 0x3C003C00u ^ ((seed >> j) & 0x00010001u);      // fp16 values next to 1.0
     const uint4 av4 = make_uint4(w[0], w[1], w[2], w[3]);
     const half8_t av = __builtin_bit_cast(half8_t, av4);
+    const half8_t bv = __builtin_bit_cast(half8_t, make_uint4(w[4], w[5], w[6], w[7]));
     typedef uint32_t u8v __attribute__((ext_vector_type(8)));
     const u8v bv8 = {w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]};
+    const half16_t bw = __builtin_bit_cast(half16_t, bv8);
     uint32_t x0 = seed, x1 = seed * 3u, x2 = seed * 5u;
     const uint32_t sel = 0x05040100u + (blockIdx.x & 1u);
     for (int it = 0; it < steps; it++) {
 #pragma unroll
         for (int q = 0; q < 32; q++) {
-            if (KIND == 0) acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, __builtin_bit_cast(half8_t, make_uint4(w[4], w[5], w[6], w[7])), acc[q], 0, 0, 0);
-            else acc[q] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(av, __builtin_bit_cast(half16_t, bv8), acc[q], 0x44444444, 0, 0);
+            if (KIND == 0) acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc[q], 0, 0, 0);
+            else if (KIND == 1) acc[q] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(av, bw, acc[q], 0x44444444, 0, 0);
+            else if (KIND == 2) accw[q % 8] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, accw[q % 8], 0, 0, 0);
+            else accw[q % 8] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(av, bw, accw[q % 8], 0x44444444, 0, 0);
             if (V >= 1) x0 = perm(x0, x1, sel);
             if (V >= 2) x1 = perm(x1, x2, sel);
             if (V >= 3) x2 = perm(x2, x0, sel);
         }
     }
-    float4_t t = acc[0];
+    float4_t t = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (WIDE) {
 #pragma unroll
-    for (int q = 1; q < 32; q++) t += acc[q];
+        for (int q = 0; q < 8; q++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) t[e % 4] += accw[q][e];
+    } else {
+#pragma unroll
+        for (int q = 0; q < 32; q++) t += acc[q];
+    }
     t[0] += (float)((x0 ^ x1 ^ x2) & 1u);
     sink[blockIdx.x * 256 + threadIdx.x] = t;
 }
@@ -727,6 +1063,12 @@ extern "C" int stb_tiled_probe_mfma(int kind, int valu, int steps, int n_workgro
     else if (kind == 1 && valu == 0) STB_PROBE(1, 0);
     else if (kind == 1 && valu == 2) STB_PROBE(1, 2);
     else if (kind == 1 && valu == 3) STB_PROBE(1, 3);
+    else if (kind == 2 && valu == 0) STB_PROBE(2, 0);
+    else if (kind == 2 && valu == 2) STB_PROBE(2, 2);
+    else if (kind == 2 && valu == 3) STB_PROBE(2, 3);
+    else if (kind == 3 && valu == 0) STB_PROBE(3, 0);
+    else if (kind == 3 && valu == 2) STB_PROBE(3, 2);
+    else if (kind == 3 && valu == 3) STB_PROBE(3, 3);
     else return STB_EINVAL;
 #undef STB_PROBE
     const hipError_t e = hipGetLastError();
@@ -756,10 +1098,12 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
         hipLaunchKernelGGL(gemm_gather_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, p,
                            (const __half*)X, T, (__half*)workspace, cfix);
     }
-    // STB_GEMM_KERNEL=dense in the environment (read at every call) keeps 2:4 layers on the dense-instruction kernel:
-    // the tests use it to run both kernels on every 2:4 case.
+    // STB_GEMM_KERNEL in the environment (read at every call): "dense" keeps 2:4 layers on the dense-instruction kernel,
+    // "dense32" runs the 32x32x16 form of that kernel on any layer: the tests use them to run every kernel on every
+    // case it can take.
     const char* which = std::getenv("STB_GEMM_KERNEL");
     const bool sparse_ok = L->cfg.N == 2 && L->cfg.M == 4 && !(which && which[0] == 'd');
+    const bool narrow = !(which && std::strcmp(which, "dense32") == 0);
     const int tok = sparse_ok ? GmLds<GM_TT24>::TOK : GmLds<GM_TT>::TOK;      // tokens per workgroup of the kernel that runs
     const dim3 grid((T + tok - 1) / tok, (p.nrt + GM_ROWT - 1) / GM_ROWT);
     const int n8 = 8 * L->cfg.N / L->cfg.M;
@@ -767,8 +1111,10 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
     const __half* xs = (const __half*)workspace;
     hipError_t e;
     if (sparse_ok) e = res ? launch_gemm24<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm24<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
-    else if (n8 == 4) e = res ? launch_gemm<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
-    else e = res ? launch_gemm<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
+    else if (narrow && n8 == 4) e = res ? launch_gemm<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
+    else if (narrow) e = res ? launch_gemm<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
+    else if (n8 == 4) e = res ? launch_gemm_wide<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm_wide<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
+    else e = res ? launch_gemm_wide<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm_wide<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
     *hip_err = (int)e;
     return e == hipSuccess ? STB_OK : STB_EHIP;
 }

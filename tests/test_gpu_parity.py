@@ -170,18 +170,23 @@ def test_gemm_small(small_case, torch_cuda, T):
         S.stb_gemm(c["pm"].dev_layout, xd, T, yd, y_fp32, c["pm"].new_gemm_workspace(T))
         torch.cuda.synchronize()
         _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T}")
-        if c["tiled"] and (c["N"], c["M"]) == (2, 4):
-            # tiled 2:4 layers go to the sparse-instruction kernel; the dense-instruction kernel is asked for by name
-            # (the library reads the variable at every call)
+        # The library picks one kernel per tiled layer (2:4: the sparse matrix instruction; otherwise the dense 16x16x32
+        # one); the others that can take the layer are asked for by name (the variable is read at every call).
+        others = []
+        if c["tiled"]:
+            others.append("dense32")
+            if (c["N"], c["M"]) == (2, 4):
+                others.append("dense")
+        for which in others:
             yd.fill_(float("nan"))
-            os.environ["STB_GEMM_KERNEL"] = "dense"
+            os.environ["STB_GEMM_KERNEL"] = which
             try:
-                _say(f"[step] stb_gemm T={T} fp32={y_fp32}, dense-instruction kernel")
+                _say(f"[step] stb_gemm T={T} fp32={y_fp32}, kernel asked for: {which}")
                 S.stb_gemm(c["pm"].dev_layout, xd, T, yd, y_fp32, c["pm"].new_gemm_workspace(T))
                 torch.cuda.synchronize()
             finally:
                 del os.environ["STB_GEMM_KERNEL"]
-            _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T} (dense-instruction kernel)")
+            _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T} (kernel asked for: {which})")
 
 
 def test_zero_activations_and_zero_weights(torch_cuda):
@@ -204,14 +209,14 @@ def test_zero_activations_and_zero_weights(torch_cuda):
 def test_probe_mfma_runs_and_rejects_bad_arguments(torch_cuda):
     torch = torch_cuda
     sink = torch.zeros(4 * 4096, dtype=torch.uint8, device="cuda")
-    for kind in (0, 1):
+    for kind in (0, 1, 2, 3):
         for valu in (0, 2, 3):
             S.stb_probe_mfma(kind, valu, 3, 4, sink)
     torch.cuda.synchronize()
     # fp16 operands next to 1.0 on zeroed accumulators: every sum is finite and positive
     out = sink.view(torch.float32).cpu().numpy()
     assert np.isfinite(out).all() and (out > 0).all()
-    for bad in ((2, 0, 3, 4), (0, 1, 3, 4), (0, 0, 0, 4), (0, 0, 3, 0)):
+    for bad in ((4, 0, 3, 4), (-1, 0, 3, 4), (0, 1, 3, 4), (0, 0, 0, 4), (0, 0, 3, 0)):
         with pytest.raises(S.StbError) as e:
             S.stb_probe_mfma(*bad, sink)
         assert e.value.status == S.STB_EINVAL
