@@ -257,7 +257,12 @@ def main():
             tf = flops / us / 1e6
             case = dict(T=T, n=spec.n, k=spec.k, nm=f"{spec.N}:{spec.M}", us=round(us, 1),
                         tflops=round(tf, 2), frac_of_f16_mfma_peak=round(tf / MFMA_F16_PEAK_TFLOPS, 4))
-            if (spec.N, spec.M) == (2, 4):
+            # which kernel the library runs (it reads STB_GEMM_KERNEL at every call; unset in an ordinary run)
+            asked = os.environ.get("STB_GEMM_KERNEL", "")
+            dense_name = ("gemm_wide_kernel (v_mfma_f32_32x32x16_f16)" if asked == "dense32"
+                          else "gemm_tiled_kernel (v_mfma_f32_16x16x32_f16)")
+            case["kernel"] = dense_name
+            if (spec.N, spec.M) == (2, 4) and not asked.startswith("d"):
                 # the sparse instruction multiplies the kept weights only: 2*T*n*k*N/M flops are executed, and
                 # `tflops` (2*T*n*k) is the dense-equivalent rate
                 case["kernel"] = "gemm24_kernel (v_smfmac_f32_16x16x64_f16)"
@@ -284,7 +289,7 @@ def main():
         result["gemm"] = {"cases": gemm,
                           "roofline": {"bound": "mfma", "achieved": best["tflops"], "peak": MFMA_F16_PEAK_TFLOPS,
                                        "unit": "TFLOP/s", "frac": best["frac_of_f16_mfma_peak"], "traffic": None,
-                                       "kernel": "gemm_tiled_kernel (stb_gemm), flops = 2*T*n*k executed on the "
+                                       "kernel": best["kernel"] + " (stb_gemm), flops = 2*T*n*k executed on the "
                                                  "dequantised tile"},
                           "instruction_issue_roof": roof}
 
