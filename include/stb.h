@@ -172,6 +172,30 @@ int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_bitmap, stb
  * Errors: STB_ENULL, STB_EINVAL (including a mask row that does not keep k*N/M weights). */
 int stb_unpack(const stb_layout_t* host, float* W_hat);
 
+/* The 2:4 group code of App. C ("D = A(E) x B + C": six bits per group of four columns), out of and into the mask
+ * and sign planes of a row-major 2:4 layout on the host.
+ *   E: host, [n][k/16] uint16, the meta index: the nibble at bits 4*(g % 4) of E[i][g / 4] belongs to group g of row
+ *      i (columns 4g .. 4g+3); its low two bits are the position (0..3) of the first kept weight of the group, its
+ *      high two bits the position of the second one (larger than the first).  The paper fixes the sizes (four index
+ *      bits per group, a uint16 per four groups) but not the bit order: this is the order in which the structured-
+ *      sparse matrix instructions take their index operand, and the word the 2:4 kernels here build in registers.
+ *   V: host, [n][k/16] uint8, the values: bit 2*(g % 4) + j of V[i][g / 4] is the sign of the j-th kept weight of
+ *      group g, 1 -> +1, 0 -> -1 (byte for byte the payload of the sign plane).
+ * stb_code24_export reads the planes and writes every element of E and V; stb_code24_import checks all of E first
+ * and then overwrites the mask and sign planes (padding bytes zero), leaving every other plane as it is.
+ * Errors: STB_ENULL, STB_EINVAL (tiled kind; a group that does not keep exactly two weights; an index nibble
+ * whose positions are equal or descending), STB_EALIGN, STB_EUNSUPPORTED (N:M other than 2:4). */
+int stb_code24_export(const stb_layout_t* host, uint16_t* E, uint8_t* V);
+int stb_code24_import(stb_layout_t* host, const uint16_t* E, const uint8_t* V);
+
+/* The meta index E (as in stb_code24_export) of a tiled 2:4 layout in device memory, written by a HIP kernel with
+ * the index function of the 2:4 kernels: what the structured-sparse matrix instruction is fed, laid out as the
+ * paper's uint16 words.  E_dev: device, [n][k/16] uint16, 16-byte aligned, fully overwritten.  Asynchronous on
+ * `stream`.  A padding group (nothing kept) never occurs inside [n][k]; a group that does not keep exactly two
+ * weights gives an unspecified nibble (stb_code24_export checks, this does not).
+ * Errors: STB_ENULL, STB_EINVAL (row-major kind), STB_EALIGN, STB_EUNSUPPORTED (N:M other than 2:4), STB_EHIP. */
+int stb_code24_index(const stb_layout_t* dev, uint16_t* E_dev, void* stream);
+
 /* Device dequantisation: same result as stb_unpack, bit for bit, written by a HIP kernel.
  * dev: layout (either kind) bound to device memory holding a copy of the packed image.  W_hat_dev: device,
  * n x k fp32.

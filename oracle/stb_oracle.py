@@ -15,6 +15,8 @@ What it follows (sections / equations / algorithms of the STBLLM paper):
                                     kept weight, a second one on salient columns, 2-bit group id,
                                     per-block channel-wise scales) plus the N:M position mask
   * average_bits                 -- Sec. 3.4 "Average Bits": N_param * N / M, Table 1
+  * code24_encode / code24_decode -- App. C: the six-bit code of a 2:4 group (uint16 meta index E per four
+                                    groups, uint8 of eight sign bits for the same 16 columns)
   * matmul                       -- the definition y = x . W_hat^T, evaluated in float64
 
 Readings taken where the paper is silent are listed in the repository's design notes; the ones that
@@ -376,6 +378,57 @@ def pack(W, xnorm, sal_bitmap, N: int, M: int, region_mode: int = 0, return_debu
     if return_debug:
         return planes, dict(mask=mask, ids=ids, tpos=tpos, breakpoints=breakpoints)
     return planes
+
+
+# ----------------------------------------------------------------------------------------------
+# The 2:4 group code of App. C
+# ----------------------------------------------------------------------------------------------
+def code24_encode(mask, sign_slots):
+    """Meta index E and value bytes V of a 2:4 matrix (App. C, "D = A(E) x B + C").
+
+    mask: (n, k) bool, exactly two kept weights in every group of four columns, k a multiple of 16.
+    sign_slots: (n, k/2) 0/1, the sign of every kept weight in column order, 1 -> +1, 0 -> -1.
+    E: (n, k/16) uint16; group g of a row owns the nibble at bits 4*(g % 4) of E[row, g // 4]; the low two bits
+       are the position (0..3) of its first kept weight, the high two bits the position of its second one.
+    V: (n, k/16) uint8; bit 2*(g % 4) + j = sign bit of the j-th kept weight of group g.
+    (The paper fixes four index bits and two value bits per group, a uint16 / uint8 per four groups, and
+    1 -> +1; the order of the bits inside them is the reading stated here.)
+    """
+    mask = np.asarray(mask, dtype=bool)
+    n, k = mask.shape
+    assert k % 16 == 0
+    groups = mask.reshape(n, k // 4, 4)
+    assert (groups.sum(axis=2) == 2).all(), "every group of four must keep exactly two weights"
+    first = np.full((n, k // 4), -1, dtype=np.int64)
+    second = np.full((n, k // 4), -1, dtype=np.int64)
+    for j in range(4):                                   # positions in ascending order
+        kept = groups[:, :, j]
+        is_second = kept & (first >= 0)
+        is_first = kept & (first < 0)
+        first = np.where(is_first, j, first)
+        second = np.where(is_second, j, second)
+    nibble = (first | (second << 2)).reshape(n, k // 16, 4)
+    E = np.zeros((n, k // 16), dtype=np.uint16)
+    for g in range(4):
+        E |= (nibble[:, :, g] << (4 * g)).astype(np.uint16)
+    V = np.packbits(np.asarray(sign_slots, dtype=np.uint8).reshape(n, k // 2), axis=1, bitorder="little")
+    return E, V
+
+
+def code24_decode(E, V):
+    """The dense ternary matrix (n, k) of -1 / 0 / +1 that (E, V) stand for."""
+    E = np.asarray(E, dtype=np.uint16)
+    V = np.asarray(V, dtype=np.uint8)
+    n, k16 = E.shape
+    A = np.zeros((n, k16 * 16), dtype=np.int8)
+    for i in range(n):
+        for c in range(k16):
+            for g in range(4):
+                nib = (int(E[i, c]) >> (4 * g)) & 15
+                for j, pos in enumerate((nib & 3, nib >> 2)):
+                    bit = (int(V[i, c]) >> (2 * g + j)) & 1
+                    A[i, 16 * c + 4 * g + pos] = 1 if bit else -1
+    return A
 
 
 # ----------------------------------------------------------------------------------------------

@@ -66,7 +66,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 
 _LIB = None
 
-EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_dequant", "stb_gemv",
+EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
            "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_strerror", "stb_last_hip_error")
 
 
@@ -87,6 +87,12 @@ def _lib():
     lib.stb_untile.argtypes = [P(stb_layout_t), P(stb_layout_t)]
     lib.stb_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32]
     lib.stb_unpack.argtypes = [P(stb_layout_t), C.c_void_p]
+    lib.stb_code24_export.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
+    lib.stb_code24_export.restype = C.c_int
+    lib.stb_code24_import.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
+    lib.stb_code24_import.restype = C.c_int
+    lib.stb_code24_index.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
+    lib.stb_code24_index.restype = C.c_int
     lib.stb_dequant.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
     lib.stb_gemv.argtypes = [P(stb_layout_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                              C.c_int64, C.c_void_p]
@@ -171,11 +177,34 @@ def stb_unpack(layout: stb_layout_t) -> np.ndarray:
     return out
 
 
+def stb_code24_export(layout: stb_layout_t):
+    """(E, V): the meta index [n][k/16] uint16 and the sign bytes [n][k/16] uint8 of a row-major 2:4 host layout."""
+    n, k16 = layout.cfg.n_out, layout.cfg.k_in // 16
+    E = np.empty((n, k16), dtype=np.uint16)
+    V = np.empty((n, k16), dtype=np.uint8)
+    _check(_lib().stb_code24_export(C.byref(layout), E.ctypes.data, V.ctypes.data), "stb_code24_export")
+    return E, V
+
+
+def stb_code24_import(layout: stb_layout_t, E: np.ndarray, V: np.ndarray) -> None:
+    n, k16 = layout.cfg.n_out, layout.cfg.k_in // 16
+    if E.shape != (n, k16) or V.shape != (n, k16) or E.dtype != np.uint16 or V.dtype != np.uint8:
+        raise ValueError("E must be uint16 [n][k/16] and V uint8 [n][k/16]")
+    E = np.ascontiguousarray(E)
+    V = np.ascontiguousarray(V)
+    _check(_lib().stb_code24_import(C.byref(layout), E.ctypes.data, V.ctypes.data), "stb_code24_import")
+
+
 def _stream_ptr(stream) -> int:
     if stream is None:
         import torch
         return torch.cuda.current_stream().cuda_stream
     return int(getattr(stream, "cuda_stream", stream))
+
+
+def stb_code24_index(layout_dev: stb_layout_t, E_dev, stream=None) -> None:
+    _check(_lib().stb_code24_index(C.byref(layout_dev), C.c_void_p(E_dev.data_ptr()),
+                                   C.c_void_p(_stream_ptr(stream))), "stb_code24_index")
 
 
 def stb_dequant(layout_dev: stb_layout_t, out_dev, stream=None) -> None:

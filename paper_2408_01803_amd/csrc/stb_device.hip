@@ -415,6 +415,19 @@ extern "C" int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stre
     return e == hipSuccess ? STB_OK : hip_fail(e);
 }
 
+extern "C" int stb_code24_index(const stb_layout_t* dev, uint16_t* E_dev, void* stream) {
+    if (!E_dev) return STB_ENULL;
+    int rc = stb_layout_check(dev);
+    if (rc) return rc;
+    if (dev->kind != STB_KIND_TILED) return STB_EINVAL;
+    if (dev->cfg.N != 2 || dev->cfg.M != 4) return STB_EUNSUPPORTED;
+    if ((uintptr_t)E_dev % 16) return STB_EALIGN;
+    int herr = 0;
+    rc = stb_tiled_meta_index(dev, E_dev, stream, &herr);
+    if (rc == STB_EHIP) g_last_hip_error = herr;
+    return rc;
+}
+
 extern "C" int64_t stb_gemv_workspace_bytes(const stb_cfg_t* cfg, int32_t B) {
     stb_layout_t tmp;
     int rc = stb_tiled_sizes(cfg, &tmp);

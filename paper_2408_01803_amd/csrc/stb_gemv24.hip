@@ -744,6 +744,31 @@ int64_t round_up256(int64_t v) { return (v + 255) / 256 * 256; }
 // instruction, 4 / 6: dense): out = {S column splits, R row tiles per workgroup, SPS wavefronts per workgroup, V visits
 // per wavefront, bytes of LDS per wavefront, offset of its records, offset of its partial tiles}.  Pure host
 // arithmetic (the tests check its invariants over many shapes).  STB_EUNSUPPORTED when nothing fits.
+// The index words of a whole 2:4 layer, written out as the meta index E of App. C ([n][k/16] uint16): the same
+// index_word() that feeds the sparse matrix instruction above, one thread per (row, block, half of 64 columns).
+namespace {
+__global__ __launch_bounds__(256) void meta_index_kernel(TiledPlanes p, uint16_t* __restrict__ E) {
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= (int64_t)p.n * p.nb * 2) return;
+    const int half = (int)(id & 1), b = (int)((id >> 1) % p.nb), row = (int)((id >> 1) / p.nb);
+    const int64_t tile = (int64_t)(row >> 4) * p.nsb + (b >> 2);
+    const int lane = 16 * (b & 3) + (row & 15);
+    const uint2 m = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(p.mask) + tile * 1024 + 512 * half + lane * 8);
+    const uint32_t T0 = 0x09080404u, T1 = 0x0E0E0D0Cu, K7 = 0x07070707u;
+    const uint32_t w0 = index_word(m.x, T0, T1, K7), w1 = index_word(m.y, T0, T1, K7);
+    *reinterpret_cast<uint2*>(E + (int64_t)row * (p.k / 16) + b * 8 + half * 4) = make_uint2(w0, w1);
+}
+}  // namespace
+
+extern "C" int stb_tiled_meta_index(const stb_layout_t* L, void* E, void* stream, int* hip_err) {
+    const TiledPlanes p = make_tiled(L);
+    const int64_t threads = (int64_t)p.n * p.nb * 2;
+    hipLaunchKernelGGL(meta_index_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, (hipStream_t)stream, p, (uint16_t*)E);
+    const hipError_t e = hipGetLastError();
+    *hip_err = (int)e;
+    return e == hipSuccess ? STB_OK : STB_EHIP;
+}
+
 extern "C" int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_splits, int* out) {
     if (nrt < 1 || nsb < 1 || B < 1 || B > 16 || (mode != 2 && mode != 4 && mode != 6) || !out) return STB_EUNSUPPORTED;
     const int64_t lds_max = LDS24 - (mode == 2 ? 0 : 32768);

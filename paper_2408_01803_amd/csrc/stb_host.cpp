@@ -683,6 +683,76 @@ extern "C" int stb_unpack(const stb_layout_t* L, float* W_hat) {
     return STB_OK;
 }
 
+// ------------------------------------------------------------------------------------------------
+// The 2:4 group code of App. C: a 16-bit meta index per four groups of four columns (which two of the four
+// are kept) and a byte of eight sign bits (1 -> +1) for the same 16 columns: six bits per group.
+// ------------------------------------------------------------------------------------------------
+namespace {
+int code24_shape_ok(const stb_layout_t* L) {
+    int rc = stb_layout_check(L);
+    if (rc) return rc;
+    if (L->kind != STB_KIND_ROWMAJOR) return STB_EINVAL;
+    if (L->cfg.N != 2 || L->cfg.M != 4) return STB_EUNSUPPORTED;
+    return STB_OK;
+}
+}  // namespace
+
+extern "C" int stb_code24_export(const stb_layout_t* L, uint16_t* E, uint8_t* V) {
+    if (!E || !V) return STB_ENULL;
+    int rc = code24_shape_ok(L);
+    if (rc) return rc;
+    const int n = L->cfg.n_out, k16 = L->cfg.k_in / 16;
+    for (int i = 0; i < n; i++) {
+        const uint8_t* mrow = (const uint8_t*)L->mask + (size_t)i * L->mask_stride;
+        const uint8_t* srow = (const uint8_t*)L->sign + (size_t)i * L->sign_stride;
+        for (int c = 0; c < k16; c++) {
+            const unsigned m16 = mrow[2 * c] | ((unsigned)mrow[2 * c + 1] << 8);
+            unsigned e = 0;
+            for (int g = 0; g < 4; g++) {
+                const unsigned nib = (m16 >> (4 * g)) & 15u;
+                int pos[2], cnt = 0;
+                for (int j = 0; j < 4; j++)
+                    if ((nib >> j) & 1u) { if (cnt < 2) pos[cnt] = j; cnt++; }
+                if (cnt != 2) return STB_EINVAL;
+                e |= (unsigned)(pos[0] | (pos[1] << 2)) << (4 * g);
+            }
+            E[(size_t)i * k16 + c] = (uint16_t)e;
+            V[(size_t)i * k16 + c] = srow[c];
+        }
+    }
+    return STB_OK;
+}
+
+extern "C" int stb_code24_import(stb_layout_t* L, const uint16_t* E, const uint8_t* V) {
+    if (!E || !V) return STB_ENULL;
+    int rc = code24_shape_ok(L);
+    if (rc) return rc;
+    const int n = L->cfg.n_out, k16 = L->cfg.k_in / 16;
+    for (size_t q = 0; q < (size_t)n * k16; q++)
+        for (int g = 0; g < 4; g++) {
+            const unsigned nib = (E[q] >> (4 * g)) & 15u;
+            if ((nib & 3u) >= (nib >> 2)) return STB_EINVAL;      // two different positions, lower one first
+        }
+    for (int i = 0; i < n; i++) {
+        uint8_t* mrow = (uint8_t*)L->mask + (size_t)i * L->mask_stride;
+        uint8_t* srow = (uint8_t*)L->sign + (size_t)i * L->sign_stride;
+        std::memset(mrow, 0, (size_t)L->mask_stride);
+        std::memset(srow, 0, (size_t)L->sign_stride);
+        for (int c = 0; c < k16; c++) {
+            const unsigned e = E[(size_t)i * k16 + c];
+            unsigned m16 = 0;
+            for (int g = 0; g < 4; g++) {
+                const unsigned nib = (e >> (4 * g)) & 15u;
+                m16 |= ((1u << (nib & 3u)) | (1u << (nib >> 2))) << (4 * g);
+            }
+            mrow[2 * c] = (uint8_t)(m16 & 255u);
+            mrow[2 * c + 1] = (uint8_t)(m16 >> 8);
+            srow[c] = V[(size_t)i * k16 + c];
+        }
+    }
+    return STB_OK;
+}
+
 extern "C" const char* stb_strerror(int status) {
     switch (status) {
         case STB_OK: return "ok";

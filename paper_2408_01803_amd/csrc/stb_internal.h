@@ -26,6 +26,8 @@ int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y
 // The launch shape stb_tiled_gemv24 takes (host arithmetic only; out[7] = S, R, SPS, V, LDS bytes per wavefront, record
 // offset, partial-tile offset).
 int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_splits, int* out);
+// The meta index of a tiled 2:4 layout, made by the decode kernel's own index function (stb_gemv24.hip).
+int stb_tiled_meta_index(const stb_layout_t* L, void* E, void* stream, int* hip_err);
 // Prefill kernel for the tiled order (stb_gemm.hip) and its scratch size for T tokens.
 int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void* Y, int y_fp32, void* workspace,
                    int64_t workspace_bytes, void* stream, int* hip_err);

@@ -103,7 +103,7 @@ def small_case(request, torch_cuda):
         assert (pm.plane(name) == np.ascontiguousarray(v).view(np.uint8).ravel()).all(), name
     pm.to_device(tiled=tiled)
     What = O.unpack(ref, n, k, N, M)
-    return dict(n=n, k=k, N=N, M=M, seed=seed, pm=pm, What=What, tiled=tiled)
+    return dict(n=n, k=k, N=N, M=M, seed=seed, pm=pm, What=What, tiled=tiled, ref=ref)
 
 
 def test_dequant_bit_exact_small(small_case, torch_cuda):
@@ -115,6 +115,31 @@ def test_dequant_bit_exact_small(small_case, torch_cuda):
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     assert (got.view(np.uint32) == c["What"].view(np.uint32)).all()
+
+
+def test_index_words_of_the_sparse_kernels_are_the_meta_index_small(small_case, torch_cuda):
+    """App. C: the uint16 meta index E.  The 2:4 kernels make their index operand from the mask bits in registers;
+    the same function, run over the whole layer, must give the oracle's E bit for bit."""
+    torch = torch_cuda
+    c = small_case
+    if not (c["tiled"] and (c["N"], c["M"]) == (2, 4)):
+        E_dev = torch.zeros((c["n"], c["k"] // 16), dtype=torch.int16, device="cuda")
+        with pytest.raises(S.StbError) as e:
+            S.stb_code24_index(c["pm"].dev_layout, E_dev)
+        assert e.value.status == (S.STB_EINVAL if not c["tiled"] else S.STB_EUNSUPPORTED)
+        return
+    n, k = c["n"], c["k"]
+    mask = np.unpackbits(c["ref"]["mask"], axis=1, bitorder="little")[:, :k].astype(bool)
+    slots = np.unpackbits(c["ref"]["sign"], axis=1, bitorder="little")[:, :k // 2]
+    E_ref, V_ref = O.code24_encode(mask, slots)
+    E_dev = torch.full((n, k // 16), -1, dtype=torch.int16, device="cuda")
+    _say("[step] stb_code24_index")
+    S.stb_code24_index(c["pm"].dev_layout, E_dev)
+    torch.cuda.synchronize()
+    assert (E_dev.cpu().numpy().view(np.uint16) == E_ref).all()
+    # and the host export of the same layer agrees with both
+    E_host, V_host = S.stb_code24_export(c["pm"].host_layout)
+    assert (E_host == E_ref).all() and (V_host == V_ref).all()
 
 
 @pytest.mark.parametrize("B", [1, 2, 3, 5, 8, 16, 31, 32])

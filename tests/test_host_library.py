@@ -261,3 +261,51 @@ def test_decode_launch_plan_invariants():
     assert seen_multi > 0
     # arguments outside the kernel's range are refused
     assert plan(16, 8, 17, 2, 7, out) != 0 and plan(16, 8, 1, 5, 7, out) != 0 and plan(0, 8, 1, 2, 7, out) != 0
+
+
+# ----------------------------------------------------------------------------------------------
+# the 2:4 group code of App. C, out of and into the mask and sign planes
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,k,seed", [(33, 256, 41), (5, 128, 42), (70, 1024, 43)])
+def test_code24_export_import_against_the_oracle(n, k, seed):
+    L = make_layer(n, k, seed)
+    ref, dbg = O.pack(L["W"], L["xnorm"], L["sal_bitmap"], 2, 4, 0, return_debug=True)
+    slots = np.unpackbits(ref["sign"], axis=1, bitorder="little")[:, :k // 2]
+    E_ref, V_ref = O.code24_encode(dbg["mask"], slots)
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], 2, 4, 0)
+    E, V = S.stb_code24_export(pm.host_layout)
+    assert E.dtype == np.uint16 and V.dtype == np.uint8
+    assert (E == E_ref).all() and (V == V_ref).all()
+    # what the code stands for is the signed mask of the dequantised matrix's kept positions
+    assert ((O.code24_decode(E, V) != 0) == dbg["mask"]).all()
+    # import into a copy whose mask and sign planes were wiped: every plane is back, byte for byte
+    before = pm.host_image.copy()
+    pm.plane("mask")[:] = 0xAA
+    pm.plane("sign")[:] = 0x55
+    S.stb_code24_import(pm.host_layout, E, V)
+    assert (pm.host_image == before).all()
+
+
+def test_code24_rejects_what_it_cannot_represent():
+    L = make_layer(16, 128, 44)
+    pm48 = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], 4, 8, 0)
+    E = np.zeros((16, 8), dtype=np.uint16)
+    V = np.zeros((16, 8), dtype=np.uint8)
+    lib = S.binding._lib()
+    assert lib.stb_code24_export(C.byref(pm48.host_layout), E.ctypes.data, V.ctypes.data) == S.STB_EUNSUPPORTED
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], 2, 4, 0)
+    assert lib.stb_code24_export(C.byref(pm.host_layout), None, V.ctypes.data) == S.STB_ENULL
+    lay_t, _img = pm.tiled()
+    assert lib.stb_code24_export(C.byref(lay_t), E.ctypes.data, V.ctypes.data) == S.STB_EINVAL
+    E, V = S.stb_code24_export(pm.host_layout)
+    before = pm.host_image.copy()
+    for bad in (0b0000, 0b0101, 0b0110):          # equal positions (0, 0) and (1, 1), descending (2, 1)
+        E2 = E.copy()
+        E2[3, 5] = (E2[3, 5] & 0xFF0F) | (bad << 4)
+        with pytest.raises(S.StbError) as e:
+            S.stb_code24_import(pm.host_layout, E2, V)
+        assert e.value.status == S.STB_EINVAL
+        assert (pm.host_image == before).all()    # checked before anything is written
+    # a mask group that keeps three weights cannot be exported
+    pm.plane("mask")[0] |= 0x07
+    assert lib.stb_code24_export(C.byref(pm.host_layout), E.ctypes.data, V.ctypes.data) == S.STB_EINVAL
