@@ -279,7 +279,7 @@ def main():
         roof = {}
         for kind, name, flop in ((0, "v_mfma_f32_16x16x32_f16", 16384.0), (1, "v_smfmac_f32_16x16x64_f16", 32768.0),
                                  (2, "v_mfma_f32_32x32x16_f16", 32768.0), (3, "v_smfmac_f32_32x32x32_f16", 65536.0)):
-            for valu in (0, 3):
+            for valu in (0, 3, 5, 8):
                 us = timed(torch, lambda r: S.stb_probe_mfma(kind, valu, steps, n_cu, sink), 3, warm=1)
                 ns = us * 1e3 / (steps * 32)
                 roof[f"{name}+{valu}valu"] = {"ns_per_instruction_per_simd": round(ns, 2),

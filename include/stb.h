@@ -265,12 +265,13 @@ int64_t stb_gemm_workspace_bytes(const stb_layout_t* layout, int32_t T);
 int stb_probe_read(const void* src, int64_t bytes, void* sink, void* stream);
 
 /* Measurement aid: `n_workgroups` workgroups of four wavefronts (one per SIMD) each issue `steps` x 32 matrix
- * instructions on 32 independent accumulators, with `valu` (0, 2 or 3) vector instructions after each.
+ * instructions on independent accumulators, with `valu` (0, 2, 3, 5 or 8) vector instructions (v_perm_b32 on eight
+ * independent registers) after each, in that order.
  * kind 0: v_mfma_f32_16x16x32_f16 (the dense prefill kernel's), kind 1: v_smfmac_f32_16x16x64_f16 (the 2:4 one's),
- * kind 2: v_mfma_f32_32x32x16_f16, kind 3: v_smfmac_f32_32x32x32_f16 (the 32x32 forms, on 8 accumulators; no kernel
- * here uses them yet: measured to see what a tile of that shape could reach).
+ * on 32 accumulators; kind 2: v_mfma_f32_32x32x16_f16, kind 3: v_smfmac_f32_32x32x32_f16, on 8 accumulators.
  * Every thread writes 16 bytes to `sink` (device, 16-byte aligned, n_workgroups * 4096 bytes).  Timing it gives the
- * instruction rate this GPU sustains, the practical ceiling that the prefill kernels' TFLOP/s is compared with.
+ * instruction rate this GPU sustains and how many vector instructions a matrix instruction hides: the practical
+ * ceiling that the prefill kernels' TFLOP/s is compared with.
  * Errors: STB_ENULL, STB_EINVAL (other kind / valu, steps < 1, n_workgroups outside 1..65536), STB_EALIGN, STB_EHIP. */
 int stb_probe_mfma(int32_t kind, int32_t valu, int32_t steps, int32_t n_workgroups, void* sink, void* stream);
 

@@ -500,9 +500,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
 }
 
 // ------------------------------------------------------------------------------------------------
-// The same pipeline on v_mfma_f32_32x32x16_f16 (asked for by name, see stb_tiled_gemm).  Measured with nothing else
-// going on, a SIMD sustains about 2450 TFLOP/s (chip-wide) of these against about 1450 of the 16x16x32 form; in this
-// pipeline the two forms take the same time to within 1 %, which says that the matrix pipe is not what holds it up.
+// The same pipeline on v_mfma_f32_32x32x16_f16 (asked for by name, see stb_tiled_gemm): half as many matrix
+// instructions for the same work, each of which hides more of the vector instructions that follow it (the probe
+// below: five against two).  In this pipeline the two forms take the same time to within 1 %: what a wavefront
+// issues besides the matrix instructions is what holds it up.
 // Per wavefront the tile is the same (64 rows x 128 tokens, 128 accumulator
 // registers: 2 x 4 tiles of 32 x 32) and so are the windows, the expansion and the loads; what differs is who holds
 // what (WIDE in GemmStage): an instruction contracts 8 columns of block 2 (g / 2) + bs from each K half, bs = 0 / 1
@@ -997,8 +998,10 @@ hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const 
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
-// Measurement aid: the rate at which one wavefront per SIMD issues the matrix instruction of the kernels above
-// (32 independent accumulators, as a K step has them), alone or with V vector instructions after each.
+// Measurement aid: the rate at which one wavefront per SIMD issues the matrix instructions of the kernels above (and
+// their 32x32 forms) on independent accumulators, alone or with V vector instructions after each.  (Accumulators are
+// updated in place: an earlier version let the compiler pick another destination, which cost four register copies
+// and a no-op per instruction and made the 16x16x32 form look a third slower than it is.)
 // ------------------------------------------------------------------------------------------------
 namespace {
 template <int KIND, int V>
@@ -1023,7 +1026,9 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int steps, float4_t* __
     typedef uint32_t u8v __attribute__((ext_vector_type(8)));
     const u8v bv8 = {w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7]};
     const half16_t bw = __builtin_bit_cast(half16_t, bv8);
-    uint32_t x0 = seed, x1 = seed * 3u, x2 = seed * 5u;
+    uint32_t x[8];                                      // eight independent chains of vector instructions
+#pragma unroll
+    for (int j = 0; j < 8; j++) x[j] = seed * (uint32_t)(2 * j + 3);
     const uint32_t sel = 0x05040100u + (blockIdx.x & 1u);
     for (int it = 0; it < steps; it++) {
 #pragma unroll
@@ -1032,9 +1037,13 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int steps, float4_t* __
             else if (KIND == 1) acc[q] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(av, bw, acc[q], 0x44444444, 0, 0);
             else if (KIND == 2) accw[q % 8] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, accw[q % 8], 0, 0, 0);
             else accw[q % 8] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(av, bw, accw[q % 8], 0x44444444, 0, 0);
-            if (V >= 1) x0 = perm(x0, x1, sel);
-            if (V >= 2) x1 = perm(x1, x2, sel);
-            if (V >= 3) x2 = perm(x2, x0, sel);
+            __builtin_amdgcn_sched_barrier(0);          // the vector instructions stay behind their matrix instruction
+#pragma unroll
+            for (int v = 0; v < V; v++) {
+                const int j = (q * V + v) % 8;
+                x[j] = perm(x[j], x[(j + 1) % 8], sel);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     float4_t t = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -1047,7 +1056,10 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int steps, float4_t* __
 #pragma unroll
         for (int q = 0; q < 32; q++) t += acc[q];
     }
-    t[0] += (float)((x0 ^ x1 ^ x2) & 1u);
+    uint32_t xx = 0u;
+#pragma unroll
+    for (int j = 0; j < 8; j++) xx ^= x[j];
+    t[0] += (float)(xx & 1u);
     sink[blockIdx.x * 256 + threadIdx.x] = t;
 }
 }  // namespace
@@ -1057,19 +1069,18 @@ extern "C" int stb_tiled_probe_mfma(int kind, int valu, int steps, int n_workgro
     const hipStream_t st = (hipStream_t)stream;
     float4_t* out = (float4_t*)sink;
 #define STB_PROBE(K, V) hipLaunchKernelGGL((probe_mfma_kernel<K, V>), grid, wg, 0, st, steps, out)
-    if (kind == 0 && valu == 0) STB_PROBE(0, 0);
-    else if (kind == 0 && valu == 2) STB_PROBE(0, 2);
-    else if (kind == 0 && valu == 3) STB_PROBE(0, 3);
-    else if (kind == 1 && valu == 0) STB_PROBE(1, 0);
-    else if (kind == 1 && valu == 2) STB_PROBE(1, 2);
-    else if (kind == 1 && valu == 3) STB_PROBE(1, 3);
-    else if (kind == 2 && valu == 0) STB_PROBE(2, 0);
-    else if (kind == 2 && valu == 2) STB_PROBE(2, 2);
-    else if (kind == 2 && valu == 3) STB_PROBE(2, 3);
-    else if (kind == 3 && valu == 0) STB_PROBE(3, 0);
-    else if (kind == 3 && valu == 2) STB_PROBE(3, 2);
-    else if (kind == 3 && valu == 3) STB_PROBE(3, 3);
+#define STB_PROBE_KIND(K) \
+    if (kind == K && valu == 0) STB_PROBE(K, 0); \
+    else if (kind == K && valu == 2) STB_PROBE(K, 2); \
+    else if (kind == K && valu == 3) STB_PROBE(K, 3); \
+    else if (kind == K && valu == 5) STB_PROBE(K, 5); \
+    else if (kind == K && valu == 8) STB_PROBE(K, 8)
+    STB_PROBE_KIND(0);
+    else STB_PROBE_KIND(1);
+    else STB_PROBE_KIND(2);
+    else STB_PROBE_KIND(3);
     else return STB_EINVAL;
+#undef STB_PROBE_KIND
 #undef STB_PROBE
     const hipError_t e = hipGetLastError();
     *hip_err = (int)e;

@@ -235,13 +235,13 @@ def test_probe_mfma_runs_and_rejects_bad_arguments(torch_cuda):
     torch = torch_cuda
     sink = torch.zeros(4 * 4096, dtype=torch.uint8, device="cuda")
     for kind in (0, 1, 2, 3):
-        for valu in (0, 2, 3):
+        for valu in (0, 2, 3, 5, 8):
             S.stb_probe_mfma(kind, valu, 3, 4, sink)
     torch.cuda.synchronize()
     # fp16 operands next to 1.0 on zeroed accumulators: every sum is finite and positive
     out = sink.view(torch.float32).cpu().numpy()
     assert np.isfinite(out).all() and (out > 0).all()
-    for bad in ((4, 0, 3, 4), (-1, 0, 3, 4), (0, 1, 3, 4), (0, 0, 0, 4), (0, 0, 3, 0)):
+    for bad in ((4, 0, 3, 4), (-1, 0, 3, 4), (0, 1, 3, 4), (2, 4, 3, 4), (0, 0, 0, 4), (0, 0, 3, 0)):
         with pytest.raises(S.StbError) as e:
             S.stb_probe_mfma(*bad, sink)
         assert e.value.status == S.STB_EINVAL
