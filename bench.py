@@ -265,7 +265,8 @@ def main():
             if (spec.N, spec.M) == (2, 4) and not asked.startswith("d"):
                 # the sparse instruction multiplies the kept weights only: 2*T*n*k*N/M flops are executed, and
                 # `tflops` (2*T*n*k) is the dense-equivalent rate
-                case["kernel"] = "gemm24_kernel (v_smfmac_f32_16x16x64_f16)"
+                case["kernel"] = ("gemm24_kernel (v_smfmac_f32_16x16x64_f16)" if asked == "sparse16"
+                                  else "gemm24_wide_kernel (v_smfmac_f32_32x32x32_f16)")
                 case["tflops_kept_weights"] = round(tf * spec.N / spec.M, 2)
                 case["frac_of_f16_mfma_peak_kept_weights"] = round(tf * spec.N / spec.M / MFMA_F16_PEAK_TFLOPS, 4)
             gemm.append(case)

@@ -241,9 +241,10 @@ int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const voi
  * the gathered salient columns of X, which the call first writes to the workspace); the row-major kind runs a
  * generic kernel for any N:M (it rounds the dequantised salient weights to fp16).
  * Tiled 2:4 layers run on the structured-sparse matrix instruction (kept weights plus an index word as the operand,
- * Sec. 3.1 / App. C); Environment: STB_GEMM_KERNEL=dense (read at every call) keeps them on the dense-instruction
- * kernel that 4:8 and 6:8 layers use (16x16x32 form of the instruction); STB_GEMM_KERNEL=dense32 runs any tiled
- * layer on the 32x32x16 form of that kernel: for tests and comparisons.
+ * Sec. 3.1 / App. C; its 32x32x32 form).  Environment, read at every call, for tests and comparisons:
+ * STB_GEMM_KERNEL=sparse16 runs them on the 16x16x64 form of that instruction, STB_GEMM_KERNEL=dense keeps them on
+ * the dense-instruction kernel that 4:8 and 6:8 layers use (16x16x32 form), STB_GEMM_KERNEL=dense32 runs any tiled
+ * layer on the 32x32x16 form of the dense kernel.
  * X: device fp16 [T][k], finite values (a padding column or token re-reads valid elements of X and meets zero
  * weights or an output that is never stored).  Y: device [T][n], fp16 or fp32, fully overwritten.  workspace: device scratch of at
  * least stb_gemm_workspace_bytes() bytes, 256-byte aligned (may be NULL when that is 0); it needs no

@@ -342,6 +342,58 @@ struct GemmStage {
             }
         }
     }
+    // The same for the kernels on the 32x32 instructions (WIDE records; acc[rs][q] = 32 rows x 32 tokens; gx[bs] = the
+    // lane's offset inside the gathered columns for block 2 (g / 2) + bs).
+    template <typename Acc>
+    __device__ void further_records_wide(Acc (&acc)[2][TT / 2], HalfData<N8> (&hd)[4], uint32_t (&a1)[4][4], uint32_t (&rlo)[4],
+                                         uint32_t (&rhi)[4], const char* lds, int nsh, const uint32_t (&gx)[2]) const {
+        constexpr int TQ = TT / 2;
+        if (!(HAS_RES && p.sal_chunks > 1)) return;
+        for (int sh0 = 0; sh0 < nsh; sh0 += 64) {
+            const int shl = sh0 + lane < nsh ? sh0 + lane : nsh - 1;
+            const uint32_t need_l = p.sal_tab[(((int64_t)(4 * (shl >> 1)) * 2 + (shl & 1)) * p.sal_chunks) * 12 + 5];
+            uint64_t todo = __ballot(need_l > 1u && sh0 + lane < nsh);
+            while (todo) {
+                const int sh = sh0 + __builtin_ctzll(todo);
+                todo &= todo - 1;
+                const uint32_t* rec0[2];
+#pragma unroll
+                for (int bs = 0; bs < 2; bs++)
+                    rec0[bs] = p.sal_tab + (((int64_t)(4 * (sh >> 1) + 2 * (g >> 1) + bs) * 2 + (sh & 1)) * p.sal_chunks) * 12;
+                const int nch = __builtin_amdgcn_readfirstlane((int)rec0[0][5]);       // the same for the four blocks
+                load_hd(sh, hd);
+                for (int c = 1; c < nch; c++) {
+                    __syncthreads();                             // every wavefront is done with the gathered columns
+                    r_gload(sh, c, 0);
+                    uint4 rc[2];
+                    uint32_t ord[2];
+#pragma unroll
+                    for (int bs = 0; bs < 2; bs++) {
+                        rc[bs] = *reinterpret_cast<const uint4*>(rec0[bs] + c * 12);
+                        ord[bs] = rec0[bs][c * 12 + 4];
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; r++) load_res_words1(ord[r & 1], rlo, rhi, r);
+                    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+                    __syncthreads();
+#pragma unroll
+                    for (int r = 0; r < 4; r++) {
+                        ResSel sel;
+                        sel.sel0 = rc[r & 1].x; sel.sel1 = rc[r & 1].y; sel.bit0 = rc[r & 1].z; sel.bit1 = rc[r & 1].w;
+                        residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord[r & 1] & 31u), hd[r].ar | (hd[r].ar << 16), sel, a1[r]);
+                    }
+#pragma unroll
+                    for (int u = 0; u < TT; u++) {
+                        const uint4 bt = *reinterpret_cast<const uint4*>(lds + G::XG + (u % TQ) * 2048 + gx[u / TQ]);
+                        const half8_t bv = __builtin_bit_cast(half8_t, bt);
+#pragma unroll
+                        for (int rs = 0; rs < 2; rs++)
+                            acc[rs][u % TQ] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(a1[2 * rs + u / TQ]), bv, acc[rs][u % TQ], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
 };
 
 template <int N8, bool HAS_RES>
@@ -718,53 +770,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(TiledPlanes p, const __h
     }
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
 
-    // half blocks with more than 8 salient columns: their further records, one at a time (as further_records)
-    if (HAS_RES && p.sal_chunks > 1) {
-        for (int sh0 = 0; sh0 < nsh; sh0 += 64) {
-            const int shl = sh0 + lane < nsh ? sh0 + lane : nsh - 1;
-            const uint32_t need_l = p.sal_tab[(((int64_t)(4 * (shl >> 1)) * 2 + (shl & 1)) * p.sal_chunks) * 12 + 5];
-            uint64_t todo = __ballot(need_l > 1u && sh0 + lane < nsh);
-            while (todo) {
-                const int sh = sh0 + __builtin_ctzll(todo);
-                todo &= todo - 1;
-                const uint32_t* rec0[2];
-#pragma unroll
-                for (int bs = 0; bs < 2; bs++)
-                    rec0[bs] = p.sal_tab + (((int64_t)(4 * (sh >> 1) + 2 * (g >> 1) + bs) * 2 + (sh & 1)) * p.sal_chunks) * 12;
-                const int nch = __builtin_amdgcn_readfirstlane((int)rec0[0][5]);       // the same for the four blocks
-                st.load_hd(sh, hd);
-                for (int c = 1; c < nch; c++) {
-                    __syncthreads();                             // every wavefront is done with the gathered columns
-                    st.r_gload(sh, c, 0);
-                    uint4 rc[2];
-                    uint32_t ord[2];
-#pragma unroll
-                    for (int bs = 0; bs < 2; bs++) {
-                        rc[bs] = *reinterpret_cast<const uint4*>(rec0[bs] + c * 12);
-                        ord[bs] = rec0[bs][c * 12 + 4];
-                    }
-#pragma unroll
-                    for (int r = 0; r < 4; r++) st.load_res_words1(ord[r & 1], rlo, rhi, r);
-                    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
-                    __syncthreads();
-#pragma unroll
-                    for (int r = 0; r < 4; r++) {
-                        ResSel sel;
-                        sel.sel0 = rc[r & 1].x; sel.sel1 = rc[r & 1].y; sel.bit0 = rc[r & 1].z; sel.bit1 = rc[r & 1].w;
-                        residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], ord[r & 1] & 31u), hd[r].ar | (hd[r].ar << 16), sel, a1[r]);
-                    }
-#pragma unroll
-                    for (int u = 0; u < TT; u++) {
-                        const uint4 bt = *reinterpret_cast<const uint4*>(lds + G::XG + (u % TQ) * 2048 + gx[u / TQ]);
-                        const half8_t bv = __builtin_bit_cast(half8_t, bt);
-#pragma unroll
-                        for (int rs = 0; rs < 2; rs++)
-                            acc[rs][u % TQ] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(a1[2 * rs + u / TQ]), bv, acc[rs][u % TQ], 0, 0, 0);
-                    }
-                }
-            }
-        }
-    }
+    st.further_records_wide(acc, hd, a1, rlo, rhi, lds, nsh, gx);
 
     __syncthreads();                                                // every wavefront is done with LDS
     store_tile_wide<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
@@ -965,6 +971,203 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     store_tile<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
 }
 
+// ------------------------------------------------------------------------------------------------
+// The 2:4 kernel on v_smfmac_f32_32x32x32_f16, the one that runs by default: gemm24_kernel with the lane mapping of
+// gemm_wide_kernel.  Half the matrix instructions for the same work (2 - 3 % faster with salient columns, a third
+// faster without: there the 16x16x64 kernel shuffles 200 accumulator registers per pass).  Operand layout of the instruction (found by probing single-element operands on the
+// device): A lane l = row l % 32, its 8 kept weights belong to dense K 16 (l / 32) .. + 15 (element e sits in the
+// group of four 4 (e / 2), at the position its two index bits 2e+1:2e of the half chosen by ABID name); B lane l =
+// token l % 32, element j = dense K 16 (j / 8) + 8 (l / 32) + j % 8; D as for the dense 32x32 form.
+// So K 0..15 of an instruction are 16 columns of block bs and K 16..31 the same columns of block 2 + bs, and a B
+// operand is two 16-byte pieces of the window row, P and P ^ 8, as in gemm24_kernel.
+// ------------------------------------------------------------------------------------------------
+template <bool HAS_RES>
+__global__ __launch_bounds__(256) void gemm24_wide_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
+                                                           void* __restrict__ Y, int y_fp32,
+                                                           const __half* __restrict__ xsal, int cfix) {
+    constexpr int N8 = 4;
+    constexpr int TT = GM_TT24;                                     // B operands per step: 4 token tiles of 32 x 2 (bs)
+    constexpr int TQ = TT / 2;
+    static_assert(TT == 8, "four records are built over eight B operand slots");
+    typedef GmLds<TT> G;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int i = lane & 15, g = lane >> 4;
+    const int t0 = blockIdx.x * G::TOK;
+    const int rtw = blockIdx.y * GM_ROWT + wave * 4;
+    const int nsh = p.nsb * 2;
+
+    float16_t acc[2][TQ];
+#pragma unroll
+    for (int rs = 0; rs < 2; rs++)
+#pragma unroll
+        for (int q = 0; q < TQ; q++)
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc[rs][q][v] = 0.0f;
+
+    const GemmStage<N8, HAS_RES, TT, true> st(p, X, xsal, T, cfix, lds0, t0, rtw, wave, lane);
+    constexpr int NGL = TT / 4;
+    uint32_t T0 = 0x09080404u, T1 = 0x0E0E0D0Cu, K7 = 0x07070707u, K3 = 0x03030303u, K4 = 0x04000400u, KS = 0x80008000u;
+    asm volatile("" : "+v"(T0), "+v"(T1), "+v"(K7), "+v"(K3), "+v"(K4), "+v"(KS));
+    // A operand of step s (columns 16 s .. 16 s + 15 of the half block of the record's block): 8 kept weights in slot order
+    auto build_a = [&](const HalfData<N8>& d, uint32_t TLr, uint32_t THr, int s, uint32_t (&W)[4]) {
+        const uint32_t rw = d.r[s >> 1], r2 = rw >> 2;
+#pragma unroll
+        for (int c = 0; c < 2; c++) {
+            const uint32_t bb = 2 * (s & 1) + c;
+            const uint32_t Z = perm(r2, rw, bb | (bb << 8) | ((4 + bb) << 16) | ((4 + bb) << 24));
+            W[2 * c] = perm(THr, TLr, and_or_v(Z, K3, K4));
+            W[2 * c + 1] = perm(THr, TLr, and_or_v(Z >> 4, K3, K4));
+        }
+        const uint32_t sbi = (uint32_t)s;
+        const uint32_t Xs = perm(d.s[0], d.s[0], 0x000C000Cu | (sbi << 8) | (sbi << 24));
+#pragma unroll
+        for (int q = 0; q < 4; q++) W[q] = and_or_v(pk_shl(Xs, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
+    };
+
+    // B operand u = (bs = u / TQ, token tile q = u % TQ) of step s, lane 16 g + i: row 32 q + 16 (g % 2) + i of the
+    // window s / 2, pieces P = 4 bs + 2 (s % 2) + g / 2 (block bs) and P + 8 (block 2 + bs), at positions P ^ i, (P + 8) ^ i
+    uint32_t bxl[2][2];
+#pragma unroll
+    for (int bs = 0; bs < 2; bs++)
+#pragma unroll
+        for (int u2 = 0; u2 < 2; u2++) bxl[bs][u2] = (uint32_t)((16 * (g & 1) + i) * 256 + ((4 * bs + 2 * u2 + (g >> 1)) ^ i) * 16);
+    uint8_t32 b[TT];
+    auto bread = [&](int buf, int u2, int u) {
+        const char* base = lds + G::XW + buf * G::XWSZ + (u % TQ) * 8192;
+        const uint4 lo = *reinterpret_cast<const uint4*>(base + bxl[u / TQ][u2]);
+        const uint4 hi = *reinterpret_cast<const uint4*>(base + (bxl[u / TQ][u2] ^ 128u));
+        b[u] = uint8_t32{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    };
+    uint32_t gx[2];
+#pragma unroll
+    for (int bs = 0; bs < 2; bs++) gx[bs] = (uint32_t)((16 * (g & 1) + i) * 64 + ((2 * (g >> 1) + bs) ^ ((i >> 2) & 3)) * 16);
+
+    // ---- K steps: a sparse one (16 sparse instructions) and the dense residual one (16 MFMAs on the low half of b[]) ----
+    auto sstep = [&](auto abid_, const uint32_t (&ac)[4][4], const uint32_t (&idx)[4], auto&& next_a, auto&& next_b, auto&& extra) {
+        constexpr int ABID = decltype(abid_)::value;
+#pragma unroll
+        for (int u = 0; u < TT; u++) {
+            const half16_t bv = __builtin_bit_cast(half16_t, b[u]);
+#pragma unroll
+            for (int rs = 0; rs < 2; rs++)
+                acc[rs][u % TQ] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(as_half8(ac[2 * rs + u / TQ]), bv, acc[rs][u % TQ], (int)idx[2 * rs + u / TQ], 0, ABID);
+            next_b(u);
+            if (u % 2 == 0) next_a(u / 2);
+            extra(u);
+        }
+    };
+    auto dstep = [&](const uint32_t (&ac)[4][4], auto&& next_a, auto&& next_b, auto&& extra) {
+#pragma unroll
+        for (int u = 0; u < TT; u++) {
+            const uint4 bl = make_uint4(b[u][0], b[u][1], b[u][2], b[u][3]);
+            const half8_t bv = __builtin_bit_cast(half8_t, bl);
+#pragma unroll
+            for (int rs = 0; rs < 2; rs++)
+                acc[rs][u % TQ] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(ac[2 * rs + u / TQ]), bv, acc[rs][u % TQ], 0, 0, 0);
+            next_b(u);
+            if (u % 2 == 0) next_a(u / 2);
+            extra(u);
+        }
+    };
+
+    // ---- prologue ----
+    HalfData<N8> hd[4];
+    uint32_t TL[4], TH[4];
+    uint4 ra[2] = {make_uint4(0u, 0u, 0u, 0u), make_uint4(0u, 0u, 0u, 0u)};
+    uint2 rb[2] = {make_uint2(0u, 0u), make_uint2(0u, 0u)};
+    uint32_t a0[4][4], a1[4][4], ia[4], ib[4];
+    uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
+    st.x_gload(0, 0, 0);
+    st.x_gload(0, 1, 1);
+    st.r_gload(0, 0, 0);
+    st.first_records(hd, ra[0], rb[0], &ra[1], &rb[1]);
+    if (HAS_RES) {
+#pragma unroll
+        for (int r = 0; r < 4; r++) st.fetch_res_words1(rb[r & 1].x, rlo, rhi, r);
+    }
+    st.scale_tables(hd, TL, TH);
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; r++) { build_a(hd[r], TL[r], TH[r], 0, a0[r]); ia[r] = index_word24(hd[r].m[0], T0, T1, K7); }
+#pragma unroll
+    for (int u = 0; u < TT; u++) bread(0, 0, u);
+
+    // Loads of one pass, in issue order (the NR res_sign words of this pass are older than all of them):
+    //   [step 0]                           the next pass's half records (NH) and table records (NC)
+    //   [step 1, after the first barrier]  window 0 of the next pass (8)
+    //   [step 3, after the second barrier] window 1 (8) and gathered columns of the next pass
+    //   [residual step]                    res_sign words of the next pass (NR)
+    constexpr int NR = HAS_RES ? 8 : 0, NC = HAS_RES ? 4 : 0, NH = 4 * TileLoads<false>::count;
+    for (int sh = 0; sh < nsh; sh++) {
+        const int shn = sh + 1 < nsh ? sh + 1 : sh;
+        const int par = sh & 1;
+        TileRegs<N8> tn[4];
+        uint4_t ran[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+        uint2_t rbn[2] = {{0u, 0u}, {0u, 0u}};
+        auto nothing = [](int) {};
+        sstep(IntC<0>{}, a0, ia, [&](int r) { build_a(hd[r], TL[r], TH[r], 1, a1[r]); }, [&](int u) { bread(0, 1, u); },
+              [&](int u) {
+                  if (u % 2 == 0) st.fetch_hd1(shn, tn, u / 2);
+                  if (u == 5) st.fetch_rec(shn, ran[0], rbn[0], 0);
+                  if (u == 7) st.fetch_rec(shn, ran[1], rbn[1], 1);
+              });
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR + NH + NC) : "memory");     // window 1 and the gathered columns of this pass
+        __syncthreads();
+        sstep(IntC<1>{}, a1, ia, [&](int r) { build_a(hd[r], TL[r], TH[r], 2, a0[r]); ib[r] = index_word24(hd[r].m[1], T0, T1, K7); },
+              [&](int u) { bread(1, 0, u); }, [&](int u) { st.x_gload1(shn, 0, 0, u); });
+        sstep(IntC<0>{}, a0, ib, [&](int r) { build_a(hd[r], TL[r], TH[r], 3, a1[r]); }, [&](int u) { bread(1, 1, u); }, nothing);
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]),
+                     "+v"(ran[0]), "+v"(rbn[0]), "+v"(ran[1]), "+v"(rbn[1]) : : "memory");
+#pragma unroll
+        for (int r = 0; r < 4; r++) asm volatile("s_waitcnt vmcnt(0)" : "+v"(tn[r].m), "+v"(tn[r].s), "+v"(tn[r].r), "+v"(tn[r].sc), "+v"(tn[r].ar));
+        __syncthreads();                                            // everyone is done with window 1
+        HalfData<N8> hn[4];
+        uint32_t TLn[4], THn[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) { tn[r].rlo = 0u; tn[r].rhi = 0u; unpack_tile<N8>(tn[r], shn & 1, hn[r]); }
+        st.scale_tables(hn, TLn, THn);
+        auto next_loads = [&](int u) { st.x_gload1(shn, 1, 1, u); if (u >= TT - NGL) st.r_gload1(shn, 0, par ^ 1, u - (TT - NGL)); };
+        auto reload_n = [&](int u) { bread(0, 0, u); };
+        if (HAS_RES) {
+            auto res_a = [&](int r) {
+                ResSel sel;
+                sel.sel0 = ra[r & 1].x; sel.sel1 = ra[r & 1].y; sel.bit0 = ra[r & 1].z; sel.bit1 = ra[r & 1].w;
+                residual_chunk(hd[r].m, __builtin_amdgcn_alignbit(rhi[r], rlo[r], rb[r & 1].x & 31u), hd[r].ar | (hd[r].ar << 16), sel, a0[r]);
+            };
+            const uint32_t gbase = (uint32_t)(G::XG + par * G::XGSZ);
+            auto reload_g = [&](int u) {
+                const uint4 v = *reinterpret_cast<const uint4*>(lds + (u % TQ) * 2048 + gbase + gx[u / TQ]);
+                b[u][0] = v.x; b[u][1] = v.y; b[u][2] = v.z; b[u][3] = v.w;
+            };
+            sstep(IntC<1>{}, a1, ib, res_a, reload_g, next_loads);
+            dstep(a0, [&](int r) { build_a(hn[r], TLn[r], THn[r], 0, a1[r]); ia[r] = index_word24(hn[r].m[0], T0, T1, K7); }, reload_n,
+                  [&](int u) { if (u < 4) st.fetch_res_words1(rbn[u & 1].x, rlo, rhi, u); });
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+#pragma unroll
+                for (int v = 0; v < 4; v++) a0[r][v] = a1[r][v];
+        } else {
+            sstep(IntC<1>{}, a1, ib, [&](int r) { build_a(hn[r], TLn[r], THn[r], 0, a0[r]); }, reload_n, next_loads);
+#pragma unroll
+            for (int r = 0; r < 4; r++) ia[r] = index_word24(hn[r].m[0], T0, T1, K7);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; r++) { hd[r] = hn[r]; TL[r] = TLn[r]; TH[r] = THn[r]; }
+#pragma unroll
+        for (int bs = 0; bs < 2; bs++) {
+            ra[bs] = make_uint4(ran[bs].x, ran[bs].y, ran[bs].z, ran[bs].w);
+            rb[bs] = make_uint2(rbn[bs].x, rbn[bs].y);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
+
+    st.further_records_wide(acc, hd, a1, rlo, rhi, lds, nsh, gx);
+    __syncthreads();
+    store_tile_wide<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
+}
+
 template <int N8, bool HAS_RES>
 hipError_t launch_gemm(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                        const __half* xsal, int cfix) {
@@ -982,6 +1185,16 @@ hipError_t launch_gemm_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, con
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL((gemm_wide_kernel<N8, HAS_RES>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix);
+    return hipGetLastError();
+}
+
+template <bool HAS_RES>
+hipError_t launch_gemm24_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
+                              const __half* xsal, int cfix) {
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm24_wide_kernel<HAS_RES>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((gemm24_wide_kernel<HAS_RES>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix);
     return hipGetLastError();
 }
 
@@ -1110,18 +1323,21 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
                            (const __half*)X, T, (__half*)workspace, cfix);
     }
     // STB_GEMM_KERNEL in the environment (read at every call): "dense" keeps 2:4 layers on the dense-instruction kernel,
-    // "dense32" runs the 32x32x16 form of that kernel on any layer: the tests use them to run every kernel on every
-    // case it can take.
+    // "dense32" runs the 32x32x16 form of that kernel on any layer, "sparse16" runs 2:4 layers on the 16x16x64 form of
+    // the sparse instruction instead of the 32x32x32 one: the tests use them to run every kernel on every case it can
+    // take.
     const char* which = std::getenv("STB_GEMM_KERNEL");
     const bool sparse_ok = L->cfg.N == 2 && L->cfg.M == 4 && !(which && which[0] == 'd');
     const bool narrow = !(which && std::strcmp(which, "dense32") == 0);
+    const bool sparse32 = sparse_ok && !(which && std::strcmp(which, "sparse16") == 0);
     const int tok = sparse_ok ? GmLds<GM_TT24>::TOK : GmLds<GM_TT>::TOK;      // tokens per workgroup of the kernel that runs
     const dim3 grid((T + tok - 1) / tok, (p.nrt + GM_ROWT - 1) / GM_ROWT);
     const int n8 = 8 * L->cfg.N / L->cfg.M;
     const __half* xh = (const __half*)X;
     const __half* xs = (const __half*)workspace;
     hipError_t e;
-    if (sparse_ok) e = res ? launch_gemm24<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm24<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
+    if (sparse32) e = res ? launch_gemm24_wide<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm24_wide<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
+    else if (sparse_ok) e = res ? launch_gemm24<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm24<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
     else if (narrow && n8 == 4) e = res ? launch_gemm<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
     else if (narrow) e = res ? launch_gemm<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
     else if (n8 == 4) e = res ? launch_gemm_wide<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm_wide<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);

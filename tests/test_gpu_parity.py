@@ -195,13 +195,14 @@ def test_gemm_small(small_case, torch_cuda, T):
         S.stb_gemm(c["pm"].dev_layout, xd, T, yd, y_fp32, c["pm"].new_gemm_workspace(T))
         torch.cuda.synchronize()
         _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T}")
-        # The library picks one kernel per tiled layer (2:4: the sparse matrix instruction; otherwise the dense 16x16x32
-        # one); the others that can take the layer are asked for by name (the variable is read at every call).
+        # The library picks one kernel per tiled layer (2:4: the sparse matrix instruction 32x32x32; otherwise the dense
+        # 16x16x32 one); the others that can take the layer (the other form of each, the dense ones on 2:4 layers) are
+        # asked for by name (the variable is read at every call).
         others = []
         if c["tiled"]:
             others.append("dense32")
             if (c["N"], c["M"]) == (2, 4):
-                others.append("dense")
+                others += ["dense", "sparse16"]
         for which in others:
             yd.fill_(float("nan"))
             os.environ["STB_GEMM_KERNEL"] = which
