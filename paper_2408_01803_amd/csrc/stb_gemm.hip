@@ -1212,9 +1212,10 @@ hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const 
 
 // ------------------------------------------------------------------------------------------------
 // Measurement aid: the rate at which one wavefront per SIMD issues the matrix instructions of the kernels above (and
-// their 32x32 forms) on independent accumulators, alone or with V vector instructions after each.  (Accumulators are
-// updated in place: an earlier version let the compiler pick another destination, which cost four register copies
-// and a no-op per instruction and made the 16x16x32 form look a third slower than it is.)
+// their 32x32 forms) on independent accumulators, alone or with V vector instructions after each.  (The scheduling
+// fences keep every accumulator updated in place: left to itself the compiler picks another destination register for
+// half of them, at four register copies and a no-op per instruction, and the 16x16x32 form looks a third slower than
+// it is.)
 // ------------------------------------------------------------------------------------------------
 namespace {
 template <int KIND, int V>
