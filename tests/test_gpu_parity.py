@@ -352,3 +352,17 @@ def test_full_size_layer(cfg, idx, torch_cuda):
             assert np.isfinite(y).all()
             worst = _within_bound(y[rows], y_ref, bound, f"{key} gemm T={T} {which}")
             _say(f"       {which}: worst error / bound on {len(rows)} sampled tokens = {worst:.2e}")
+        if tiled:
+            # the prefill kernels that the library does not pick by itself, on the same tokens
+            for asked in ["dense32"] + (["sparse16", "dense"] if (spec.N, spec.M) == (2, 4) else []):
+                yd.fill_(float("nan"))
+                os.environ["STB_GEMM_KERNEL"] = asked
+                try:
+                    S.stb_gemm(pm.dev_layout, xd, T, yd, False, pm.new_gemm_workspace(T))
+                    torch.cuda.synchronize()
+                finally:
+                    del os.environ["STB_GEMM_KERNEL"]
+                y = yd.float().cpu().numpy()
+                assert np.isfinite(y).all()
+                worst = _within_bound(y[rows], y_ref, bound, f"{key} gemm T={T} tiled, kernel asked for: {asked}")
+                _say(f"       tiled, {asked}: worst error / bound = {worst:.2e}")
