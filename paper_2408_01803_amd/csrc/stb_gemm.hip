@@ -795,6 +795,25 @@ __device__ inline uint32_t index_word24(uint32_t m, uint32_t T0, uint32_t T1, ui
     return (hi << 4) | lo;
 }
 
+// A operand of a sparse step s (columns 16 s .. 16 s + 15 of a half block): the 8 kept weights in slot order, scale
+// by region id and sign bit merged in (the first half of expand_group; nothing to spread).  K3, K4, KS: the constants
+// 0x03030303, 0x04000400, 0x80008000 in registers (a VOP3 instruction takes one literal).
+__device__ inline void sparse_operand(const HalfData<4>& d, uint32_t TLr, uint32_t THr, int s, uint32_t K3, uint32_t K4,
+                                      uint32_t KS, uint32_t (&W)[4]) {
+    const uint32_t rw = d.r[s >> 1], r2 = rw >> 2;
+#pragma unroll
+    for (int c = 0; c < 2; c++) {                             // byte 2 (s % 2) + c of the id word: 4 kept weights
+        const uint32_t bb = 2 * (s & 1) + c;
+        const uint32_t Z = perm(r2, rw, bb | (bb << 8) | ((4 + bb) << 16) | ((4 + bb) << 24));
+        W[2 * c] = perm(THr, TLr, and_or_v(Z, K3, K4));
+        W[2 * c + 1] = perm(THr, TLr, and_or_v(Z >> 4, K3, K4));
+    }
+    const uint32_t sbi = (uint32_t)s;                         // byte of the half's sign word
+    const uint32_t Xs = perm(d.s[0], d.s[0], 0x000C000Cu | (sbi << 8) | (sbi << 24));
+#pragma unroll
+    for (int q = 0; q < 4; q++) W[q] = and_or_v(pk_shl(Xs, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
+}
+
 template <bool HAS_RES>
 __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                       void* __restrict__ Y, int y_fp32,
@@ -821,20 +840,9 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     // constants of the operand build, in VGPRs (a VOP3 instruction takes one literal)
     uint32_t T0 = 0x09080404u, T1 = 0x0E0E0D0Cu, K7 = 0x07070707u, K3 = 0x03030303u, K4 = 0x04000400u, KS = 0x80008000u;
     asm volatile("" : "+v"(T0), "+v"(T1), "+v"(K7), "+v"(K3), "+v"(K4), "+v"(KS));
-    // A operand of step s (columns 16 s .. 16 s + 15 of the half block): its 8 kept weights in slot order
+    // A operand of step s (columns 16 s .. 16 s + 15 of the half block of the record's block)
     auto build_a = [&](const HalfData<N8>& d, uint32_t TLr, uint32_t THr, int s, uint32_t (&W)[4]) {
-        const uint32_t rw = d.r[s >> 1], r2 = rw >> 2;
-#pragma unroll
-        for (int c = 0; c < 2; c++) {                         // byte 2 (s % 2) + c of the id word: 4 kept weights
-            const uint32_t bb = 2 * (s & 1) + c;
-            const uint32_t Z = perm(r2, rw, bb | (bb << 8) | ((4 + bb) << 16) | ((4 + bb) << 24));
-            W[2 * c] = perm(THr, TLr, and_or_v(Z, K3, K4));
-            W[2 * c + 1] = perm(THr, TLr, and_or_v(Z >> 4, K3, K4));
-        }
-        const uint32_t sbi = (uint32_t)s;                     // byte of the half's sign word
-        const uint32_t Xs = perm(d.s[0], d.s[0], 0x000C000Cu | (sbi << 8) | (sbi << 24));
-#pragma unroll
-        for (int q = 0; q < 4; q++) W[q] = and_or_v(pk_shl(Xs, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
+        sparse_operand(d, TLr, THr, s, K3, K4, KS, W);
     };
 
     // B operand of a sparse step, lane 16 g + n of token tile tt: elements 0..7 = X[token][block g / 2, columns
@@ -1010,20 +1018,9 @@ __global__ __launch_bounds__(256) void gemm24_wide_kernel(TiledPlanes p, const _
     constexpr int NGL = TT / 4;
     uint32_t T0 = 0x09080404u, T1 = 0x0E0E0D0Cu, K7 = 0x07070707u, K3 = 0x03030303u, K4 = 0x04000400u, KS = 0x80008000u;
     asm volatile("" : "+v"(T0), "+v"(T1), "+v"(K7), "+v"(K3), "+v"(K4), "+v"(KS));
-    // A operand of step s (columns 16 s .. 16 s + 15 of the half block of the record's block): 8 kept weights in slot order
+    // A operand of step s (columns 16 s .. 16 s + 15 of the half block of the record's block)
     auto build_a = [&](const HalfData<N8>& d, uint32_t TLr, uint32_t THr, int s, uint32_t (&W)[4]) {
-        const uint32_t rw = d.r[s >> 1], r2 = rw >> 2;
-#pragma unroll
-        for (int c = 0; c < 2; c++) {
-            const uint32_t bb = 2 * (s & 1) + c;
-            const uint32_t Z = perm(r2, rw, bb | (bb << 8) | ((4 + bb) << 16) | ((4 + bb) << 24));
-            W[2 * c] = perm(THr, TLr, and_or_v(Z, K3, K4));
-            W[2 * c + 1] = perm(THr, TLr, and_or_v(Z >> 4, K3, K4));
-        }
-        const uint32_t sbi = (uint32_t)s;
-        const uint32_t Xs = perm(d.s[0], d.s[0], 0x000C000Cu | (sbi << 8) | (sbi << 24));
-#pragma unroll
-        for (int q = 0; q < 4; q++) W[q] = and_or_v(pk_shl(Xs, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
+        sparse_operand(d, TLr, THr, s, K3, K4, KS, W);
     };
 
     // B operand u = (bs = u / TQ, token tile q = u % TQ) of step s, lane 16 g + i: row 32 q + 16 (g % 2) + i of the
