@@ -268,6 +268,58 @@ def test_device_entry_points_reject_bad_arguments(torch_cuda):
 
 
 # --------------------------------------------------------------------------------------------------
+# random shapes: every kernel that can take a layer, on shapes nobody chose by hand
+# --------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", [21, 22, 23])
+def test_random_shapes_through_every_kernel(seed, torch_cuda):
+    torch = torch_cuda
+    rng = np.random.default_rng(seed)
+    for case in range(6):
+        N, M = [(2, 4), (4, 8), (6, 8), (2, 4)][rng.integers(0, 4)]
+        n = int(rng.integers(1, 500))
+        k = 128 * int(rng.integers(1, 44))
+        n_sal = int(rng.choice([0, max(1, k // 20), max(1, k // 8), min(k, 40)]))
+        mode = int(rng.integers(0, 2))
+        lseed = int(rng.integers(0, 1 << 30))
+        _say(f"[case] random {seed}/{case}: n={n} k={k} {N}:{M} salient={n_sal} mode={mode} seed={lseed}")
+        L = make_layer(n, k, lseed, "x8", n_salient=n_sal)
+        What = O.unpack(O.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode), n, k, N, M)
+        pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode).to_device(tiled=True)
+
+        def run(name, value, call):
+            if name:
+                os.environ[name] = value
+            try:
+                call()
+                torch.cuda.synchronize()
+            finally:
+                if name:
+                    del os.environ[name]
+
+        for B in sorted({int(b) for b in rng.integers(1, 33, 2)}):
+            x = make_x(B, k, lseed + B)
+            y_ref, bound = O.matmul(x, What)
+            xd = torch.from_numpy(x).cuda()
+            asks = [(None, None), ("STB_GEMV_KERNEL", "thin")]
+            asks += [("STB_GEMV_VISITS", v) for v in ("2", "3") if (k + 511) // 512 >= int(v) and B <= 16]
+            for name, value in asks:
+                yd = torch.full((B, n), float("nan"), dtype=torch.float16, device="cuda")
+                _say(f"[step] stb_gemv B={B} {name}={value}")
+                run(name, value, lambda: S.stb_gemv(pm.dev_layout, xd, B, yd, False, pm.workspace))
+                _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"random gemv B={B} {name}={value}")
+        for T in sorted({int(t) for t in rng.integers(1, 300, 2)}):
+            x = make_x(T, k, lseed + 1000 + T)
+            y_ref, bound = O.matmul(x, What)
+            xd = torch.from_numpy(x).cuda()
+            for value in [None, "dense32"] + (["dense", "sparse16"] if (N, M) == (2, 4) else []):
+                yd = torch.full((T, n), float("nan"), dtype=torch.float16, device="cuda")
+                _say(f"[step] stb_gemm T={T} STB_GEMM_KERNEL={value}")
+                run("STB_GEMM_KERNEL" if value else None, value,
+                    lambda: S.stb_gemm(pm.dev_layout, xd, T, yd, False, pm.new_gemm_workspace(T)))
+                _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"random gemm T={T} kernel={value}")
+
+
+# --------------------------------------------------------------------------------------------------
 # full-size workloads
 # --------------------------------------------------------------------------------------------------
 def _layer_key(cfg, spec):
