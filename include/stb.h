@@ -167,6 +167,19 @@ int stb_untile(const stb_layout_t* src_tiled, stb_layout_t* dst_rowmajor);
 int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_bitmap, stb_layout_t* out,
              int32_t n_threads);
 
+/* The salient columns of a layer (Alg. 2 "Salient", called once per 128-column block as in Alg. 1), for use as the
+ * sal_bitmap of stb_pack.  The Hessian of Alg. 1 (H = 2 X X^T, H^c = Cholesky((H + lambda I)^-1)) is taken as its
+ * diagonal, which the feature norms give: the salient matrix is S_ij = w_ij^2 (2 xnorm_j^2 + lambda).  Per block:
+ * candidates = the max_per_block columns with the largest column sums of S (ties: the lower column first); for
+ * i = 1 .. max_per_block the first i candidates are binarised together and all other columns of the block together
+ * (Eq. 1, one scale per row and group); the i with the smallest squared error is kept (the first such i).
+ * W: host, n x k row-major fp32.  xnorm: host, k values >= 0.  lambda >= 0.  max_per_block in 0..128 (the paper
+ * does not give the length of its top-k list).  sal_bitmap: host, k/32 words, fully overwritten.  n_selected
+ * (may be NULL): the number of salient columns.  Sums are float64 and sequential: the result is reproducible bit
+ * for bit.  Errors: STB_ENULL, STB_EINVAL, STB_ENONFINITE. */
+int stb_salient_columns(const float* W, int32_t n, int32_t k, const float* xnorm, double lambda,
+                        int32_t max_per_block, uint32_t* sal_bitmap, int32_t* n_selected);
+
 /* Host dequantisation of a packed matrix into dense fp32 (definition in the header comment).
  * host: layout bound to host memory.  W_hat: host, n x k row-major, fully overwritten.
  * Errors: STB_ENULL, STB_EINVAL (including a mask row that does not keep k*N/M weights). */

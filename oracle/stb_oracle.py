@@ -15,6 +15,7 @@ What it follows (sections / equations / algorithms of the STBLLM paper):
                                     kept weight, a second one on salient columns, 2-bit group id,
                                     per-block channel-wise scales) plus the N:M position mask
   * average_bits                 -- Sec. 3.4 "Average Bits": N_param * N / M, Table 1
+  * salient_columns              -- Alg. 2 "Salient" on a diagonal Hessian (Alg. 1: H = 2 X X^T, H^c = Cholesky((H + lambda I)^-1))
   * code24_encode / code24_decode -- App. C: the six-bit code of a 2:4 group (uint16 meta index E per four
                                     groups, uint8 of eight sign bits for the same 16 columns)
   * matmul                       -- the definition y = x . W_hat^T, evaluated in float64
@@ -378,6 +379,47 @@ def pack(W, xnorm, sal_bitmap, N: int, M: int, region_mode: int = 0, return_debu
     if return_debug:
         return planes, dict(mask=mask, ids=ids, tpos=tpos, breakpoints=breakpoints)
     return planes
+
+
+# ----------------------------------------------------------------------------------------------
+# Salient columns, Alg. 2 "Salient"
+# ----------------------------------------------------------------------------------------------
+def salient_columns(W, xnorm, lam: float, max_per_block: int) -> np.ndarray:
+    """The salient columns of every 128-column block (Alg. 1 calls Salient once per block), as a (k,) bool vector.
+
+    Reading: only the norms of the input features are known here, so the Hessian H = 2 X X^T is taken as its
+    diagonal, 2 xnorm_j^2; then H^c = Cholesky((H + lam I)^-1) is diagonal with [H^c_jj]^2 = 1 / (2 xnorm_j^2 + lam)
+    and the salient matrix S = W^2 / [H^c]^2 is w_ij^2 (2 xnorm_j^2 + lam).  The length of the top-k list is not
+    given in the paper: `max_per_block` is an input.  "binary" is the per-row scale of Eq. 1 over the columns of the
+    set (the reading taken everywhere else).
+    Steps: column score = sum_i S_ij; candidates = the max_per_block columns of the block with the largest score
+    (ties: the lower column first); for i = 1 .. len: binarise the first i candidates together and all other columns
+    of the block together, e_i = ||W - B||^2; keep the first i with the smallest e_i.
+    """
+    W = np.asarray(W, dtype=np.float64)
+    xn = np.asarray(xnorm, dtype=np.float32).astype(np.float64)
+    n, k = W.shape
+    assert k % BLOCK == 0 and 0 <= max_per_block <= BLOCK
+    out = np.zeros(k, dtype=bool)
+    for b in range(0, k, BLOCK):
+        Wb = W[:, b:b + BLOCK]
+        h = 2.0 * xn[b:b + BLOCK] * xn[b:b + BLOCK] + float(lam)
+        score = seq_colsum((Wb * Wb) * h[None, :])
+        order = np.argsort(-score, kind="stable")[:max_per_block]
+        absw, sgn = np.abs(Wb), sign_pm(Wb)
+        best, n_star = np.inf, 0
+        for i in range(1, len(order) + 1):
+            sal = np.zeros(BLOCK, dtype=bool)
+            sal[order[:i]] = True
+            member = np.broadcast_to(sal, (n, BLOCK))
+            a1, _ = binary(absw, member)
+            a2, _ = binary(absw, ~member)
+            B = np.where(member, a1[:, None], a2[:, None]) * sgn
+            e = seq_sum(seq_rowsum((Wb - B) * (Wb - B)))
+            if e < best:
+                best, n_star = e, i
+        out[b + order[:n_star]] = True
+    return out
 
 
 # ----------------------------------------------------------------------------------------------

@@ -66,7 +66,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 
 _LIB = None
 
-EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
+EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_salient_columns", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
            "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_strerror", "stb_last_hip_error")
 
 
@@ -87,6 +87,9 @@ def _lib():
     lib.stb_untile.argtypes = [P(stb_layout_t), P(stb_layout_t)]
     lib.stb_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32]
     lib.stb_unpack.argtypes = [P(stb_layout_t), C.c_void_p]
+    lib.stb_salient_columns.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_double, C.c_int32,
+                                        C.c_void_p, P(C.c_int32)]
+    lib.stb_salient_columns.restype = C.c_int
     lib.stb_code24_export.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
     lib.stb_code24_export.restype = C.c_int
     lib.stb_code24_import.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
@@ -174,6 +177,20 @@ def stb_pack(W: np.ndarray, xnorm: np.ndarray, sal_bitmap: np.ndarray, layout: s
 def stb_unpack(layout: stb_layout_t) -> np.ndarray:
     out = np.empty((layout.cfg.n_out, layout.cfg.k_in), dtype=np.float32)
     _check(_lib().stb_unpack(C.byref(layout), out.ctypes.data), "stb_unpack")
+    return out
+
+
+def stb_salient_columns(W: np.ndarray, xnorm: np.ndarray, lam: float, max_per_block: int) -> np.ndarray:
+    """sal_bitmap (k/32 uint32 words) of the columns that Alg. 2 "Salient" picks, block by block."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    xnorm = np.ascontiguousarray(xnorm, dtype=np.float32)
+    n, k = W.shape
+    if xnorm.shape != (k,):
+        raise ValueError("xnorm must have k entries")
+    out = np.zeros(max(k // 32, 1), dtype=np.uint32)
+    count = C.c_int32(0)
+    _check(_lib().stb_salient_columns(W.ctypes.data, n, k, xnorm.ctypes.data, float(lam), int(max_per_block),
+                                      out.ctypes.data, C.byref(count)), "stb_salient_columns")
     return out
 
 

@@ -684,6 +684,76 @@ extern "C" int stb_unpack(const stb_layout_t* L, float* W_hat) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Salient columns (Alg. 2 "Salient"), block by block, on the diagonal of the Hessian of Alg. 1:
+// S_ij = w_ij^2 (2 xnorm_j^2 + lambda); candidates = the columns with the largest column sums of S; the number
+// kept is the one whose two-group binarisation (Eq. 1, per row over each group) has the smallest squared error.
+// All sums are float64, sequential in ascending index, so that the result is reproducible bit for bit.
+// ------------------------------------------------------------------------------------------------
+extern "C" int stb_salient_columns(const float* W, int32_t n, int32_t k, const float* xnorm, double lambda,
+                                   int32_t max_per_block, uint32_t* sal_bitmap, int32_t* n_selected) {
+    if (!W || !xnorm || !sal_bitmap) return STB_ENULL;
+    if (n < 1 || k < STB_BLOCK || k % STB_BLOCK || max_per_block < 0 || max_per_block > STB_BLOCK) return STB_EINVAL;
+    if (!(lambda >= 0.0) || !std::isfinite(lambda)) return STB_EINVAL;
+    for (int j = 0; j < k; j++)
+        if (!(xnorm[j] >= 0.0f) || !std::isfinite(xnorm[j])) return STB_ENONFINITE;
+    for (size_t q = 0; q < (size_t)n * k; q++)
+        if (!std::isfinite(W[q])) return STB_ENONFINITE;
+    std::memset(sal_bitmap, 0, (size_t)k / 32 * sizeof(uint32_t));
+    int total = 0;
+    std::vector<double> score(STB_BLOCK), h(STB_BLOCK);
+    std::vector<int> order(STB_BLOCK);
+    std::vector<char> sal(STB_BLOCK);
+    for (int b = 0; b < k; b += STB_BLOCK) {
+        for (int j = 0; j < STB_BLOCK; j++) {
+            const double x = (double)xnorm[b + j];
+            h[j] = 2.0 * x * x + lambda;
+            score[j] = 0.0;
+        }
+        for (int i = 0; i < n; i++) {
+            const float* w = W + (size_t)i * k + b;
+            for (int j = 0; j < STB_BLOCK; j++) {
+                const double v = (double)w[j];
+                score[j] += (v * v) * h[j];
+            }
+        }
+        for (int j = 0; j < STB_BLOCK; j++) order[j] = j;
+        std::stable_sort(order.begin(), order.end(), [&](int a, int c) { return score[a] > score[c]; });
+        double best = std::numeric_limits<double>::infinity();
+        int n_star = 0;
+        std::fill(sal.begin(), sal.end(), 0);
+        for (int c = 1; c <= max_per_block; c++) {
+            sal[order[c - 1]] = 1;
+            double e = 0.0;
+            for (int i = 0; i < n; i++) {
+                const float* w = W + (size_t)i * k + b;
+                double s1 = 0.0, s2 = 0.0;
+                for (int j = 0; j < STB_BLOCK; j++) {
+                    const double a = std::fabs((double)w[j]);
+                    if (sal[j]) s1 += a; else s2 += a;
+                }
+                const double a1 = s1 / (double)c;
+                const double a2 = c < STB_BLOCK ? s2 / (double)(STB_BLOCK - c) : 0.0;
+                double er = 0.0;
+                for (int j = 0; j < STB_BLOCK; j++) {
+                    const double v = (double)w[j];
+                    const double bq = (sal[j] ? a1 : a2) * (v >= 0.0 ? 1.0 : -1.0);
+                    er += (v - bq) * (v - bq);
+                }
+                e += er;
+            }
+            if (e < best) { best = e; n_star = c; }
+        }
+        for (int c = 0; c < n_star; c++) {
+            const int j = b + order[c];
+            sal_bitmap[j >> 5] |= 1u << (j & 31);
+        }
+        total += n_star;
+    }
+    if (n_selected) *n_selected = total;
+    return STB_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
 // The 2:4 group code of App. C: a 16-bit meta index per four groups of four columns (which two of the four
 // are kept) and a byte of eight sign bits (1 -> +1) for the same 16 columns: six bits per group.
 // ------------------------------------------------------------------------------------------------

@@ -309,3 +309,41 @@ def test_code24_rejects_what_it_cannot_represent():
     # a mask group that keeps three weights cannot be exported
     pm.plane("mask")[0] |= 0x07
     assert lib.stb_code24_export(C.byref(pm.host_layout), E.ctypes.data, V.ctypes.data) == S.STB_EINVAL
+
+
+# ----------------------------------------------------------------------------------------------
+# salient columns (Alg. 2 "Salient")
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,k,seed,kind,max_per_block,lam", [
+    (24, 256, 51, "x8", 20, 0.01), (7, 128, 52, "t3", 128, 0.0), (40, 384, 53, "x8", 16, 1.0),
+    (64, 512, 54, "x8", 0, 0.5), (33, 1024, 55, "t3", 9, 0.01), (128, 256, 56, "x8", 40, 100.0)])
+def test_salient_columns_bit_exact_against_the_oracle(n, k, seed, kind, max_per_block, lam):
+    L = make_layer(n, k, seed, kind)
+    ref = O.salient_columns(L["W"], L["xnorm"], lam, max_per_block)
+    bm = S.stb_salient_columns(L["W"], L["xnorm"], lam, max_per_block)
+    assert bm.dtype == np.uint32 and bm.shape == (k // 32,)
+    assert (O.bitmap_to_bool(bm, k) == ref).all()
+    # and the bitmap is what stb_pack takes
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], bm, 4, 8, 0)
+    ref_planes = O.pack(L["W"], L["xnorm"], bm, 4, 8, 0)
+    for name, v in _oracle_bytes(ref_planes).items():
+        assert (pm.plane(name) == v).all(), name
+
+
+def test_salient_columns_reject_bad_arguments():
+    L = make_layer(8, 128, 57)
+    lib = S.binding._lib()
+    W = np.ascontiguousarray(L["W"], dtype=np.float32)
+    xn = np.ascontiguousarray(L["xnorm"], dtype=np.float32)
+    out = np.zeros(4, dtype=np.uint32)
+    call = lambda w, n, k, x, lam, m, o: lib.stb_salient_columns(w, n, k, x, C.c_double(lam), m, o, None)
+    assert call(None, 8, 128, xn.ctypes.data, 0.1, 4, out.ctypes.data) == S.STB_ENULL
+    assert call(W.ctypes.data, 8, 100, xn.ctypes.data, 0.1, 4, out.ctypes.data) == S.STB_EINVAL
+    assert call(W.ctypes.data, 8, 128, xn.ctypes.data, -1.0, 4, out.ctypes.data) == S.STB_EINVAL
+    assert call(W.ctypes.data, 8, 128, xn.ctypes.data, 0.1, 129, out.ctypes.data) == S.STB_EINVAL
+    bad = W.copy()
+    bad[3, 7] = np.nan
+    assert call(bad.ctypes.data, 8, 128, xn.ctypes.data, 0.1, 4, out.ctypes.data) == S.STB_ENONFINITE
+    xb = xn.copy()
+    xb[5] = -1.0
+    assert call(W.ctypes.data, 8, 128, xb.ctypes.data, 0.1, 4, out.ctypes.data) == S.STB_ENONFINITE

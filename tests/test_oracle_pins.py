@@ -548,3 +548,70 @@ def test_code24_decodes_to_the_signed_mask():
     assert (A2[:, plain] == np.sign(What[:, plain]).astype(np.int8)).all()
     with pytest.raises(AssertionError):
         O.code24_encode(np.ones((1, 16), dtype=bool), np.zeros((1, 8), dtype=np.uint8))
+
+
+# ----------------------------------------------------------------------------------------------
+# salient columns (Alg. 2 "Salient" on the diagonal of the Hessian)
+# ----------------------------------------------------------------------------------------------
+def _salient_by_loops(W, xnorm, lam, max_per_block):
+    """The same selection written as plain loops, with the closed form of the binarisation error
+    (sum w^2 - cnt alpha^2 per row and group) in place of the explicit residual."""
+    n, k = W.shape
+    out = np.zeros(k, dtype=bool)
+    for b in range(0, k, 128):
+        score = [sum(float(W[i, b + j]) ** 2 * (2.0 * float(xnorm[b + j]) ** 2 + lam) for i in range(n)) for j in range(128)]
+        order = sorted(range(128), key=lambda j: (-score[j], j))[:max_per_block]
+        best, n_star = math.inf, 0
+        for c in range(1, len(order) + 1):
+            chosen = set(order[:c])
+            e = 0.0
+            for i in range(n):
+                for group in (chosen, set(range(128)) - chosen):
+                    a = [abs(float(W[i, b + j])) for j in group]
+                    if a:
+                        e += sum(v * v for v in a) - sum(a) ** 2 / len(a)
+            if e < best * (1 - 1e-12):
+                best, n_star = e, c
+        for j in order[:n_star]:
+            out[b + j] = True
+    return out
+
+
+def test_salient_columns_match_plain_loops_with_the_closed_form_error():
+    rng = np.random.default_rng(12)
+    W = rng.standard_normal((5, 256)) * 0.02
+    W[:, [3, 40, 77, 130, 131, 250]] *= 6.0
+    xn = np.abs(rng.normal(1.0, 0.3, 256)).astype(np.float32)
+    got = O.salient_columns(W.astype(np.float32), xn, 0.01, 10)
+    assert (got == _salient_by_loops(W.astype(np.float32), xn, 0.01, 10)).all()
+    assert got.any() and set(np.flatnonzero(got).tolist()) <= {3, 40, 77, 130, 131, 250}     # only amplified columns
+
+
+def test_salient_columns_find_the_planted_columns_of_the_workload_recipe():
+    for seed in (31, 32):
+        L = make_layer(48, 512, seed, "x8")
+        planted = O.bitmap_to_bool(L["sal_bitmap"], 512)
+        got = O.salient_columns(L["W"], L["xnorm"], 0.01, 32)
+        assert (got == planted).all()
+
+
+def test_salient_columns_invariances_ties_and_empty_list():
+    rng = np.random.default_rng(13)
+    W = (rng.standard_normal((6, 128)) * 0.02).astype(np.float32)
+    W[:, [5, 9, 100]] *= 5.0
+    xn = np.abs(rng.normal(1.0, 0.3, 128)).astype(np.float32)
+    base = O.salient_columns(W, xn, 0.5, 12)
+    # a common factor on W, or on (xnorm^2, lambda) together, changes no ranking and no comparison of errors
+    assert (O.salient_columns(W * np.float32(4.0), xn, 0.5, 12) == base).all()
+    assert (O.salient_columns(W, xn * np.float32(2.0), 2.0, 12) == base).all()
+    # lambda far above 2 xnorm^2: the ranking is the column energy alone, whatever xnorm says
+    big = O.salient_columns(W, xn, 1e12, 3)
+    flat = O.salient_columns(W, np.ones(128, dtype=np.float32), 1e12, 3)
+    assert (big == flat).all()
+    # an empty candidate list selects nothing
+    assert not O.salient_columns(W, xn, 0.5, 0).any()
+    # two identical outlier columns, one candidate: the lower column is taken
+    W2 = (rng.standard_normal((4, 128)) * 0.02).astype(np.float32)
+    W2[:, 70] = W2[:, 20] = np.float32(0.9)
+    one = O.salient_columns(W2, np.ones(128, dtype=np.float32), 0.0, 1)
+    assert list(np.flatnonzero(one)) == [20]
