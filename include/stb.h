@@ -167,6 +167,14 @@ int stb_untile(const stb_layout_t* src_tiled, stb_layout_t* dst_rowmajor);
 int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_bitmap, stb_layout_t* out,
              int32_t n_threads);
 
+/* Layer-wise N:M assignment (Sec. 3.3).  stb_layer_l2_norm: omega = the L2 norm of `count` host fp32 weights
+ * (float64, sequential).  stb_layer_nm_assignment: for layers with norms omega[0 .. n_layers), alpha_i = omega_i /
+ * sum(omega) (1 / n_layers each if the sum is 0) and N_i / M = alpha_i + (1 - alpha_i) * r_target; N_out[i] is the
+ * nearest integer to M times that ratio (a half rounds up), kept inside 1..M (the paper gives the ratio, not the
+ * rounding).  r_target in [0, 1].  Errors: STB_ENULL, STB_EINVAL, STB_ENONFINITE (NaN/Inf weight or norm, negative norm). */
+int stb_layer_l2_norm(const float* W, int64_t count, double* omega);
+int stb_layer_nm_assignment(const double* omega, int32_t n_layers, double r_target, int32_t M, int32_t* N_out);
+
 /* The salient columns of a layer (Alg. 2 "Salient", called once per 128-column block as in Alg. 1), for use as the
  * sal_bitmap of stb_pack.  The Hessian of Alg. 1 (H = 2 X X^T, H^c = Cholesky((H + lambda I)^-1)) is taken as its
  * diagonal, which the feature norms give: the salient matrix is S_ij = w_ij^2 (2 xnorm_j^2 + lambda).  Per block:

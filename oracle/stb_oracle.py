@@ -15,6 +15,7 @@ What it follows (sections / equations / algorithms of the STBLLM paper):
                                     kept weight, a second one on salient columns, 2-bit group id,
                                     per-block channel-wise scales) plus the N:M position mask
   * average_bits                 -- Sec. 3.4 "Average Bits": N_param * N / M, Table 1
+  * layer_nm_assignment          -- Sec. 3.3 "Layer-wise N:M Assignment"
   * salient_columns              -- Alg. 2 "Salient" on a diagonal Hessian (Alg. 1: H = 2 X X^T, H^c = Cholesky((H + lambda I)^-1))
   * code24_encode / code24_decode -- App. C: the six-bit code of a 2:4 group (uint16 meta index E per four
                                     groups, uint8 of eight sign bits for the same 16 columns)
@@ -379,6 +380,34 @@ def pack(W, xnorm, sal_bitmap, N: int, M: int, region_mode: int = 0, return_debu
     if return_debug:
         return planes, dict(mask=mask, ids=ids, tpos=tpos, breakpoints=breakpoints)
     return planes
+
+
+# ----------------------------------------------------------------------------------------------
+# Layer-wise N:M assignment, Sec. 3.3
+# ----------------------------------------------------------------------------------------------
+def layer_l2_norm(W) -> float:
+    """omega of Sec. 3.3: the L2 norm of a layer's weights (float64, sequential sum of squares in row-major order)."""
+    W = np.asarray(W, dtype=np.float64)
+    return float(np.sqrt(seq_sum(W * W)))
+
+
+def layer_nm_assignment(omegas, r_target: float, M: int = 8):
+    """N_i of every layer for a target ratio (Sec. 3.3): alpha_i = omega_i / sum(omega),
+    N_i / M = alpha_i + (1 - alpha_i) * r_target.
+
+    Readings: the paper gives the ratio but not how it becomes an integer N: the nearest integer to M * ratio (a half
+    rounds up), kept inside 1..M.  As printed, the ratio never falls below r_target (alpha_i >= 0), so the mean ratio
+    over the layers lies above the target by the mean of alpha_i (1 - r_target); the text's example of layers below
+    the target (3:8 around 4:8) does not follow from the formula, and the formula is what is implemented.
+    Returns (N int64 (L,), ratio float64 (L,)).
+    """
+    om = np.asarray(omegas, dtype=np.float64)
+    assert om.ndim == 1 and om.size >= 1 and (om >= 0).all() and 0.0 <= r_target <= 1.0 and M >= 1
+    total = seq_sum(om)
+    alpha = om / total if total > 0 else np.full(om.shape, 1.0 / om.size)
+    ratio = alpha + (1.0 - alpha) * float(r_target)
+    N = np.clip(np.floor(M * ratio + 0.5), 1, M).astype(np.int64)
+    return N, ratio
 
 
 # ----------------------------------------------------------------------------------------------

@@ -66,7 +66,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 
 _LIB = None
 
-EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_salient_columns", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
+EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
            "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_strerror", "stb_last_hip_error")
 
 
@@ -90,6 +90,10 @@ def _lib():
     lib.stb_salient_columns.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_double, C.c_int32,
                                         C.c_void_p, P(C.c_int32)]
     lib.stb_salient_columns.restype = C.c_int
+    lib.stb_layer_l2_norm.argtypes = [C.c_void_p, C.c_int64, P(C.c_double)]
+    lib.stb_layer_l2_norm.restype = C.c_int
+    lib.stb_layer_nm_assignment.argtypes = [C.c_void_p, C.c_int32, C.c_double, C.c_int32, C.c_void_p]
+    lib.stb_layer_nm_assignment.restype = C.c_int
     lib.stb_code24_export.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
     lib.stb_code24_export.restype = C.c_int
     lib.stb_code24_import.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
@@ -191,6 +195,21 @@ def stb_salient_columns(W: np.ndarray, xnorm: np.ndarray, lam: float, max_per_bl
     count = C.c_int32(0)
     _check(_lib().stb_salient_columns(W.ctypes.data, n, k, xnorm.ctypes.data, float(lam), int(max_per_block),
                                       out.ctypes.data, C.byref(count)), "stb_salient_columns")
+    return out
+
+
+def stb_layer_l2_norm(W: np.ndarray) -> float:
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    out = C.c_double(0.0)
+    _check(_lib().stb_layer_l2_norm(W.ctypes.data, W.size, C.byref(out)), "stb_layer_l2_norm")
+    return float(out.value)
+
+
+def stb_layer_nm_assignment(omegas, r_target: float, M: int = 8) -> np.ndarray:
+    om = np.ascontiguousarray(omegas, dtype=np.float64)
+    out = np.zeros(om.size, dtype=np.int32)
+    _check(_lib().stb_layer_nm_assignment(om.ctypes.data, om.size, float(r_target), int(M), out.ctypes.data),
+           "stb_layer_nm_assignment")
     return out
 
 

@@ -684,6 +684,41 @@ extern "C" int stb_unpack(const stb_layout_t* L, float* W_hat) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Layer-wise N:M assignment (Sec. 3.3): alpha_i = omega_i / sum omega, N_i / M = alpha_i + (1 - alpha_i) R_target.
+// ------------------------------------------------------------------------------------------------
+extern "C" int stb_layer_l2_norm(const float* W, int64_t count, double* omega) {
+    if (!W || !omega) return STB_ENULL;
+    if (count < 0) return STB_EINVAL;
+    double s = 0.0;
+    for (int64_t q = 0; q < count; q++) {
+        const double v = (double)W[q];
+        if (!std::isfinite(v)) return STB_ENONFINITE;
+        s += v * v;
+    }
+    *omega = std::sqrt(s);
+    return STB_OK;
+}
+
+extern "C" int stb_layer_nm_assignment(const double* omega, int32_t n_layers, double r_target, int32_t M, int32_t* N_out) {
+    if (!omega || !N_out) return STB_ENULL;
+    if (n_layers < 1 || M < 1 || !(r_target >= 0.0 && r_target <= 1.0)) return STB_EINVAL;
+    double total = 0.0;
+    for (int i = 0; i < n_layers; i++) {
+        if (!std::isfinite(omega[i]) || omega[i] < 0.0) return STB_ENONFINITE;
+        total += omega[i];
+    }
+    for (int i = 0; i < n_layers; i++) {
+        const double alpha = total > 0.0 ? omega[i] / total : 1.0 / (double)n_layers;
+        const double ratio = alpha + (1.0 - alpha) * r_target;
+        double nn = std::floor((double)M * ratio + 0.5);
+        if (nn < 1.0) nn = 1.0;
+        if (nn > (double)M) nn = (double)M;
+        N_out[i] = (int32_t)nn;
+    }
+    return STB_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
 // Salient columns (Alg. 2 "Salient"), block by block, on the diagonal of the Hessian of Alg. 1:
 // S_ij = w_ij^2 (2 xnorm_j^2 + lambda); candidates = the columns with the largest column sums of S; the number
 // kept is the one whose two-group binarisation (Eq. 1, per row over each group) has the smallest squared error.

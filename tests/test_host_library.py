@@ -347,3 +347,25 @@ def test_salient_columns_reject_bad_arguments():
     xb = xn.copy()
     xb[5] = -1.0
     assert call(W.ctypes.data, 8, 128, xb.ctypes.data, 0.1, 4, out.ctypes.data) == S.STB_ENONFINITE
+
+
+# ----------------------------------------------------------------------------------------------
+# layer-wise N:M assignment (Sec. 3.3)
+# ----------------------------------------------------------------------------------------------
+def test_layer_nm_assignment_against_the_oracle():
+    # a synthetic stack of layers of different shapes and scales
+    shapes = [(64, 256), (64, 256), (256, 64), (128, 128), (32, 512), (96, 384)]
+    layers = [make_layer(n, k, 60 + i)["W"] * np.float32(1.0 + 0.7 * i) for i, (n, k) in enumerate(shapes)]
+    om_ref = [O.layer_l2_norm(W) for W in layers]
+    om = [S.stb_layer_l2_norm(W) for W in layers]
+    assert om == om_ref                                     # bit for bit: same sequential float64 sum
+    for R in (0.5, 0.25, 0.75, 0.0, 1.0):
+        N_ref, _ = O.layer_nm_assignment(om_ref, R, 8)
+        assert S.stb_layer_nm_assignment(om, R, 8).tolist() == N_ref.tolist()
+    assert S.stb_layer_nm_assignment(om, 0.5, 4).tolist() == O.layer_nm_assignment(om_ref, 0.5, 4)[0].tolist()
+    with pytest.raises(S.StbError) as e:
+        S.stb_layer_nm_assignment(om, 1.5, 8)
+    assert e.value.status == S.STB_EINVAL
+    with pytest.raises(S.StbError) as e:
+        S.stb_layer_nm_assignment([1.0, float("nan")], 0.5, 8)
+    assert e.value.status == S.STB_ENONFINITE

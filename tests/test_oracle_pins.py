@@ -615,3 +615,36 @@ def test_salient_columns_invariances_ties_and_empty_list():
     W2[:, 70] = W2[:, 20] = np.float32(0.9)
     one = O.salient_columns(W2, np.ones(128, dtype=np.float32), 0.0, 1)
     assert list(np.flatnonzero(one)) == [20]
+
+
+# ----------------------------------------------------------------------------------------------
+# layer-wise N:M assignment (Sec. 3.3)
+# ----------------------------------------------------------------------------------------------
+def test_layer_nm_assignment_closed_forms():
+    # equal norms: alpha = 1/L for every layer, ratio = 1/L + (1 - 1/L) R
+    for L_, R in ((4, 0.5), (32, 0.5), (10, 0.25)):
+        N, ratio = O.layer_nm_assignment(np.full(L_, 3.7), R, 8)
+        assert np.allclose(ratio, 1.0 / L_ + (1.0 - 1.0 / L_) * R, rtol=0, atol=1e-15)
+        assert (N == math.floor(8 * (1.0 / L_ + (1.0 - 1.0 / L_) * R) + 0.5)).all()
+    # one layer: alpha = 1, nothing is pruned; a layer of norm 0 sits exactly at the target
+    assert O.layer_nm_assignment([2.0], 0.5, 8)[0].tolist() == [8]
+    N, ratio = O.layer_nm_assignment([0.0, 5.0], 0.5, 8)
+    assert ratio.tolist() == [0.5, 1.0] and N.tolist() == [4, 8]
+    # as printed the ratio never falls below the target and grows with the layer's norm
+    rng = np.random.default_rng(3)
+    om = rng.uniform(0.1, 9.0, 40)
+    N, ratio = O.layer_nm_assignment(om, 0.5, 8)
+    assert (ratio >= 0.5).all() and (ratio <= 1.0).all()
+    order = np.argsort(om)
+    assert (np.diff(ratio[order]) >= 0).all() and (np.diff(N[order]) >= 0).all()
+    # mean ratio = R + mean(alpha) (1 - R) = R + (1 - R) / L
+    assert abs(ratio.mean() - (0.5 + 0.5 / 40)) < 1e-12
+    # many small layers: everyone approaches the target
+    assert (O.layer_nm_assignment(np.ones(4096), 0.5, 8)[0] == 4).all()
+
+
+def test_layer_l2_norm_is_the_frobenius_norm():
+    rng = np.random.default_rng(4)
+    W = rng.standard_normal((7, 33)).astype(np.float32)
+    assert abs(O.layer_l2_norm(W) - np.linalg.norm(W.astype(np.float64))) < 1e-12
+    assert O.layer_l2_norm(np.array([[3.0, 4.0]])) == 5.0
