@@ -320,6 +320,45 @@ def test_random_shapes_through_every_kernel(seed, torch_cuda):
 
 
 # --------------------------------------------------------------------------------------------------
+# a stack of layers at the N:8 that the layer-wise assignment gives each of them (Sec. 3.3)
+# --------------------------------------------------------------------------------------------------
+def test_layer_wise_assignment_feeds_the_kernels(torch_cuda):
+    torch = torch_cuda
+    shapes = [(96, 512), (64, 384), (130, 256), (48, 1024), (80, 640)]
+    scales = [0.2, 1.0, 3.0, 0.5, 9.0]
+    layers = [make_layer(n, k, 70 + i) for i, (n, k) in enumerate(shapes)]
+    for L, c in zip(layers, scales):
+        L["W"] = (L["W"] * np.float32(c)).astype(np.float32)
+    om = [S.stb_layer_l2_norm(L["W"]) for L in layers]
+    N = S.stb_layer_nm_assignment(om, 0.375, 8)                 # target 3:8
+    assert N.tolist() == O.layer_nm_assignment([O.layer_l2_norm(L["W"]) for L in layers], 0.375, 8)[0].tolist()
+    assert len(set(N.tolist())) >= 3, N                         # the stack really is mixed
+    _say(f"[case] layer-wise assignment: N of 8 = {N.tolist()}")
+    for (n, k), L, Ni in zip(shapes, layers, N.tolist()):
+        sal = S.stb_salient_columns(L["W"], L["xnorm"], 0.01, 16)
+        assert (O.bitmap_to_bool(sal, k) == O.salient_columns(L["W"], L["xnorm"], 0.01, 16)).all()
+        ref = O.pack(L["W"], L["xnorm"], sal, Ni, 8, 0)
+        What = O.unpack(ref, n, k, Ni, 8)
+        pm = S.PackedMatrix.pack(L["W"], L["xnorm"], sal, Ni, 8, 0).to_device(tiled=_tiled_ok(Ni, 8))
+        for B in (1, 7):
+            x = make_x(B, k, 7 * Ni + B)
+            y_ref, bound = O.matmul(x, What)
+            yd = torch.full((B, n), float("nan"), dtype=torch.float16, device="cuda")
+            _say(f"[step] stb_gemv {n}x{k} {Ni}:8 B={B}")
+            S.stb_gemv(pm.dev_layout, torch.from_numpy(x).cuda(), B, yd, False, pm.workspace)
+            torch.cuda.synchronize()
+            _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"assigned {Ni}:8 gemv B={B}")
+        T = 70
+        x = make_x(T, k, 11 * Ni)
+        y_ref, bound = O.matmul(x, What)
+        yd = torch.full((T, n), float("nan"), dtype=torch.float16, device="cuda")
+        _say(f"[step] stb_gemm {n}x{k} {Ni}:8 T={T}")
+        S.stb_gemm(pm.dev_layout, torch.from_numpy(x).cuda(), T, yd, False, pm.new_gemm_workspace(T))
+        torch.cuda.synchronize()
+        _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"assigned {Ni}:8 gemm T={T}")
+
+
+# --------------------------------------------------------------------------------------------------
 # full-size workloads
 # --------------------------------------------------------------------------------------------------
 def _layer_key(cfg, spec):
