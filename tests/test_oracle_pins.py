@@ -413,6 +413,163 @@ def test_worked_example_from_golden_file():
     assert float(np.float16(np.float32(0.5 / 61))) == D
 
 
+def _read_spec(name):
+    spec = {}
+    for line in open(os.path.join(GOLDEN, name)):
+        if line.strip() and not line.startswith("#"):
+            key, *vals = line.split()
+            spec[key] = vals
+    return spec
+
+
+def test_worked_example_with_salient_columns_from_golden_file():
+    # Eq. 4 / Alg. 2 Res_Approx on the kept salient weights of each row, Alg. 1's NonSalientAwareQuant on the
+    # columns outside the salient set (all rows of the block), Eq. 6 scales over non-salient members only
+    spec = _read_spec("worked_example_salient.txt")
+    D = {"D0": float(spec["D0"][0]), "D1": float(spec["D1"][0])}
+
+    def val(v):
+        neg = v.startswith("-")
+        name = v.lstrip("-")
+        x = D[name] if name in D else float(name)
+        return -x if neg else x
+
+    assert float(np.float16(np.float32(1.75 / 58))) == D["D0"] == 2.0 ** -6 * (1 + 953 / 1024)
+    assert float(np.float16(np.float32(4.375 / 60))) == D["D1"] == 2.0 ** -4 * (1 + 171 / 1024)
+    W = np.zeros((2, 128), dtype=np.float32)
+    W[0, :16] = [float(v) for v in spec["row0_first16"]]
+    W[1, :16] = float(spec["row1_factor"][0]) * W[0, :16]
+    cols = np.array([int(v) for v in spec["salient_cols"]])
+    P, dbg = O.pack(W, np.ones(128, dtype=np.float32), cols_to_bitmap(cols, 128), 2, 4, 0, return_debug=True)
+    kept = [int(v) for v in spec["kept_first16"]]
+    assert dbg["mask"][0, :16].astype(int).tolist() == kept
+    assert dbg["mask"][1, :16].astype(int).tolist() == kept
+    t = int(spec["best_t"][0])
+    assert dbg["breakpoints"][0, 0] == (t * (0.8 / 159.0) + 0.1) * 8.0
+    assert dbg["breakpoints"][0, 1] == 2.0 * dbg["breakpoints"][0, 0]
+    for i in range(2):
+        for j, v in enumerate(spec[f"ids_row{i}"]):
+            if v != "-":
+                assert dbg["ids"][i, j] == int(v), (i, j)
+        assert float(P["scales"][i, 0, 3]) == float(spec["alpha_o"][i])
+        assert float(P["res_scale"][i, 0]) == float(spec["alpha_r"][i])
+        assert np.float32(P["scales"][i, 0, :]).tolist() == [np.float32(val(v)) for v in spec[f"scales_row{i}"]]
+        assert int(P["res_sign"][i, 0]) == int(spec["res_sign_byte0"][i])
+        assert not P["res_sign"][i, 1:].any()
+    What = O.unpack(P, 2, 128, 2, 4)
+    for i in range(2):
+        assert What[i, :16].tolist() == [np.float32(val(v)) for v in spec[f"what_row{i}"]], i
+        rest = np.float32([val(v) for v in spec[f"what_rest_group_row{i}"]])
+        assert (What[i, 16:].reshape(28, 4) == rest[None, :]).all()
+    assert (What == _decode_bitwise(P, 2, 128, 2, 4)).all()
+
+
+def _f16_through_f32(v):
+    return float(np.float16(np.float32(v)))
+
+
+@pytest.mark.parametrize("N,M,mode,kind,seed", [(2, 4, 0, "t3", 61), (4, 8, 0, "x8", 62), (6, 8, 1, "x8", 63)])
+def test_pack_of_blocks_with_salient_columns_against_plain_loops(N, M, mode, kind, seed):
+    """Everything pack() stores for a block, recomputed in scalar Python from W, the mask and the salient set alone:
+    Eq. 4 (alpha_o, R against the stored alpha_o, t, alpha_r, the res_sign bits), Alg. 1's argument of
+    NonSalientAwareQuant (break points from the kept weights outside the salient columns, all rows of the block),
+    Eq. 6 (one scale per row and region over non-salient members only), the ids, and the dequantised values."""
+    n, k = 6, 256
+    Lr = make_layer(n, k, seed, kind, n_salient=24)
+    W = Lr["W"].astype(np.float64)
+    P, dbg = O.pack(Lr["W"], Lr["xnorm"], Lr["sal_bitmap"], N, M, mode, return_debug=True)
+    mask = dbg["mask"]
+    sal = np.zeros(k, dtype=bool)
+    sal[Lr["sal_cols"]] = True
+    assert (mask[:, sal].sum() > 0) and (~mask[:, sal]).sum() > 0        # kept and pruned salient weights both occur
+    ordinal = {int(c): u for u, c in enumerate(Lr["sal_cols"])}
+    What = O.unpack(P, n, k, N, M)
+    for q in range(k // 128):
+        cols = range(q * 128, (q + 1) * 128)
+        # --- salient part, per row
+        for i in range(n):
+            members = [j for j in cols if sal[j] and mask[i, j]]
+            if not members:
+                assert float(P["scales"][i, q, 3]) == 0.0 and float(P["res_scale"][i, q]) == 0.0
+                continue
+            acc = 0.0
+            for j in members:
+                acc += abs(W[i, j])
+            a_o = _f16_through_f32(acc / len(members))
+            assert float(P["scales"][i, q, 3]) == a_o
+            acc = 0.0
+            tsign = {}
+            for j in members:
+                s = 1.0 if W[i, j] >= 0 else -1.0
+                R = W[i, j] - a_o * s
+                tsign[j] = 1.0 if R >= 0 else -1.0
+                acc += abs(R)
+            a_r = _f16_through_f32(acc / len(members))
+            assert float(P["res_scale"][i, q]) == a_r
+            for j in cols:
+                if sal[j]:
+                    u = ordinal[j]
+                    bit = (int(P["res_sign"][i, u // 8]) >> (u % 8)) & 1
+                    assert bit == (1 if (mask[i, j] and tsign[j] > 0) else 0), (i, j)
+            for j in members:
+                s = 1.0 if W[i, j] >= 0 else -1.0
+                assert dbg["ids"][i, j] == 3
+                assert What[i, j] == np.float32(np.float32(s * a_o) + np.float32(tsign[j] * a_r)), (i, j)
+                # the residual makes the reconstruction at least as good as the first term alone
+            e1 = sum((W[i, j] - a_o * (1.0 if W[i, j] >= 0 else -1.0)) ** 2 for j in members)
+            e2 = sum((W[i, j] - float(What[i, j])) ** 2 for j in members)
+            assert e2 <= e1 * (1 + 1e-3) + 1e-12
+        # --- non-salient part: break points over all rows
+        ns = [(i, j) for i in range(n) for j in cols if mask[i, j] and not sal[j]]
+        mags = [abs(W[i, j]) for (i, j) in ns]
+        if mode == 1:
+            a = sorted(mags)
+            m = len(a)
+            p1, p2 = a[-(-m // 3) - 1], a[-(-2 * m // 3) - 1]
+        else:
+            mx = max(mags)
+            best, p1, p2 = math.inf, 0.0, 0.0
+            for tc in range(160):
+                c1 = (tc * (0.8 / 159.0) + 0.1) * mx
+                c2 = 2.0 * c1
+                if c2 > 0.9 * mx:
+                    continue
+                err = 0.0
+                for i in range(n):
+                    groups = {0: [], 1: [], 2: []}
+                    for j in cols:
+                        if mask[i, j] and not sal[j]:
+                            a = abs(W[i, j])
+                            groups[2 if a > c2 else (1 if a > c1 else 0)].append(a)
+                    for g in groups.values():
+                        if g:
+                            mean = math.fsum(g) / len(g)
+                            err += math.fsum((v - mean) ** 2 for v in g)
+                if err < best * (1 - 1e-12):
+                    best, p1, p2 = err, c1, c2
+        assert math.isclose(dbg["breakpoints"][q, 0], p1, rel_tol=1e-14)
+        assert math.isclose(dbg["breakpoints"][q, 1], p2, rel_tol=1e-14)
+        # --- ids and region scales, non-salient members only
+        for i in range(n):
+            sums, cnts = [0.0, 0.0, 0.0], [0, 0, 0]
+            for j in cols:
+                if mask[i, j] and not sal[j]:
+                    a = abs(W[i, j])
+                    r = 2 if a > p2 else (1 if a > p1 else 0)
+                    assert dbg["ids"][i, j] == r
+                    sums[r] += a
+                    cnts[r] += 1
+            for r in range(3):
+                want = _f16_through_f32(sums[r] / cnts[r]) if cnts[r] else 0.0
+                assert float(P["scales"][i, q, r]) == want, (i, q, r)
+            for j in cols:
+                if mask[i, j] and not sal[j]:
+                    s = 1.0 if W[i, j] >= 0 else -1.0
+                    assert What[i, j] == np.float32(s * float(P["scales"][i, q, int(dbg["ids"][i, j])]))
+                elif not mask[i, j]:
+                    assert What[i, j] == 0.0
+
+
 def test_pack_is_a_fixed_point_of_pack_unpack():
     # W_hat is already structured-binary: packing it again (same mask pattern via its own scores is not
     # guaranteed, so re-use the support by scoring W_hat itself) must reproduce W_hat on its support
