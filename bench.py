@@ -257,7 +257,7 @@ def main():
             tf = flops / us / 1e6
             case = dict(T=T, n=spec.n, k=spec.k, nm=f"{spec.N}:{spec.M}", us=round(us, 1),
                         tflops=round(tf, 2), frac_of_f16_mfma_peak=round(tf / MFMA_F16_PEAK_TFLOPS, 4))
-            # which kernel the library runs (it reads STB_GEMM_KERNEL at every call; unset in an ordinary run)
+            # which kernel the library runs
             asked = os.environ.get("STB_GEMM_KERNEL", "")
             dense_name = ("gemm_wide_kernel (v_mfma_f32_32x32x16_f16)" if asked == "dense32"
                           else "gemm_tiled_kernel (v_mfma_f32_16x16x32_f16)")

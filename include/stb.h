@@ -235,10 +235,6 @@ int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream);
  * with k > 4096; for smaller k the launcher may still split columns to balance the grid).  The
  * counters (its first 4 * ceil(n / 16) bytes) must be zero before the first call that uses the buffer; every
  * call leaves them zero.  Calls that share a workspace must not overlap in time.
- * Environment: STB_GEMV_KERNEL=thin (read at every call) makes the tiled kind use its older kernel with thin
- * wavefronts, which otherwise only runs when the LDS areas of the default kernel do not fit; STB_GEMV_VISITS=2
- * or 3 makes the default kernel take that many superblocks per wavefront where the layer has as many (it chooses
- * that by itself for wide layers at small batches, instead of column splits).  Both are for tests.
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
 int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32,
              void* workspace, int64_t workspace_bytes, void* stream);
@@ -262,10 +258,7 @@ int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const voi
  * the gathered salient columns of X, which the call first writes to the workspace); the row-major kind runs a
  * generic kernel for any N:M (it rounds the dequantised salient weights to fp16).
  * Tiled 2:4 layers run on the structured-sparse matrix instruction (kept weights plus an index word as the operand,
- * Sec. 3.1 / App. C; its 32x32x32 form).  Environment, read at every call, for tests and comparisons:
- * STB_GEMM_KERNEL=sparse16 runs them on the 16x16x64 form of that instruction, STB_GEMM_KERNEL=dense keeps them on
- * the dense-instruction kernel that 4:8 and 6:8 layers use (16x16x32 form), STB_GEMM_KERNEL=dense32 runs any tiled
- * layer on the 32x32x16 form of the dense kernel.
+ * Sec. 3.1 / App. C; its 32x32x32 form).
  * X: device fp16 [T][k], finite values (a padding column or token re-reads valid elements of X and meets zero
  * weights or an output that is never stored).  Y: device [T][n], fp16 or fp32, fully overwritten.  workspace: device scratch of at
  * least stb_gemm_workspace_bytes() bytes, 256-byte aligned (may be NULL when that is 0); it needs no
@@ -296,6 +289,18 @@ int stb_probe_read(const void* src, int64_t bytes, void* sink, void* stream);
  * ceiling that the prefill kernels' TFLOP/s is compared with.
  * Errors: STB_ENULL, STB_EINVAL (other kind / valu, steps < 1, n_workgroups outside 1..65536), STB_EALIGN, STB_EHIP. */
 int stb_probe_mfma(int32_t kind, int32_t valu, int32_t steps, int32_t n_workgroups, void* sink, void* stream);
+
+/* Test hook: forces kernel choices that ordinary shapes would not reach, for every later call in this process (the
+ * values are process-wide; set them while no other thread is inside stb_gemv / stb_gemm).
+ *   gemv_kernel  0 automatic; 1 the tiled kind uses its older decode kernel with thin wavefronts, which otherwise
+ *                only runs when the LDS areas of the default kernel do not fit
+ *   gemv_visits  0 automatic; 2 or 3: the default decode kernel takes that many superblocks per wavefront where the
+ *                layer has as many (it chooses that by itself for wide layers at small batches)
+ *   gemm_kernel  0 automatic; 1 keeps 2:4 layers on the dense-instruction prefill kernel (16x16x32 form); 2 runs any
+ *                tiled layer on the 32x32x16 form of the dense kernel; 3 runs 2:4 layers on the 16x16x64 form of the
+ *                sparse instruction
+ * Errors: STB_EINVAL (a value outside the lists above; nothing is changed then). */
+int stb_set_kernel_override(int32_t gemv_kernel, int32_t gemv_visits, int32_t gemm_kernel);
 
 /* Text for a status code (static storage). */
 const char* stb_strerror(int status);

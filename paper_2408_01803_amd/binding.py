@@ -67,7 +67,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 _LIB = None
 
 EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
-           "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_strerror", "stb_last_hip_error")
+           "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_set_kernel_override", "stb_strerror", "stb_last_hip_error")
 
 
 def _lib():
@@ -115,6 +115,8 @@ def _lib():
     lib.stb_probe_read.restype = C.c_int
     lib.stb_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.stb_probe_mfma.restype = C.c_int
+    lib.stb_set_kernel_override.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+    lib.stb_set_kernel_override.restype = C.c_int
     lib.stb_strerror.argtypes = [C.c_int]
     lib.stb_strerror.restype = C.c_char_p
     lib.stb_last_hip_error.restype = C.c_int
@@ -304,6 +306,14 @@ def stb_probe_read(src_dev, nbytes: int, sink_dev, stream=None) -> None:
 def stb_probe_mfma(kind: int, valu: int, steps: int, n_workgroups: int, sink_dev, stream=None) -> None:
     _check(_lib().stb_probe_mfma(kind, valu, steps, n_workgroups, C.c_void_p(sink_dev.data_ptr()),
                                  C.c_void_p(_stream_ptr(stream))), "stb_probe_mfma")
+
+
+def stb_set_kernel_override(gemv_kernel: int = 0, gemv_visits: int = 0, gemm_kernel: int = 0) -> None:
+    _check(_lib().stb_set_kernel_override(gemv_kernel, gemv_visits, gemm_kernel), "stb_set_kernel_override")
+
+
+GEMV_THIN = 1
+GEMM_DENSE, GEMM_DENSE32, GEMM_SPARSE16 = 1, 2, 3
 
 
 def new_device_scratch(nbytes: int, device="cuda:0", zero: bool = False):

@@ -1,6 +1,8 @@
 // Device side of libstb for gfx950: dequantisation, decode GEMV and prefill GEMM on the packed planes.
 // C ABI in include/stb.h.  Everything here runs on the caller's stream; nothing allocates.
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <hip/hip_fp16.h>
 
 #include "stb_internal.h"
@@ -375,6 +377,20 @@ hipError_t launch_gemv_generic(const Planes& p, const void* x, void* y, int y_fp
 // C ABI
 // ------------------------------------------------------------------------------------------------
 extern "C" int stb_last_hip_error(void) { return g_last_hip_error; }
+
+static std::atomic<int> g_override[3] = {{0}, {0}, {0}};
+
+extern "C" int stb_kernel_override(int which) { return which >= 0 && which < 3 ? g_override[which].load(std::memory_order_relaxed) : 0; }
+
+extern "C" int stb_set_kernel_override(int32_t gemv_kernel, int32_t gemv_visits, int32_t gemm_kernel) {
+    if (gemv_kernel < 0 || gemv_kernel > 1 || (gemv_visits != 0 && gemv_visits != 2 && gemv_visits != 3) ||
+        gemm_kernel < 0 || gemm_kernel > 3)
+        return STB_EINVAL;
+    g_override[0].store(gemv_kernel, std::memory_order_relaxed);
+    g_override[1].store(gemv_visits, std::memory_order_relaxed);
+    g_override[2].store(gemm_kernel, std::memory_order_relaxed);
+    return STB_OK;
+}
 
 extern "C" int stb_probe_read(const void* src, int64_t bytes, void* sink, void* stream) {
     if (!src || !sink) return STB_ENULL;

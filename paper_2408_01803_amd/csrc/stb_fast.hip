@@ -555,10 +555,9 @@ static hipError_t launch_gemv_stream(const TiledPlanes& p, const __half* x, int 
 extern "C" int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
                               int64_t workspace_bytes, void* stream, int* hip_err) {
     if (!stb_tiled_supported(L)) return STB_EUNSUPPORTED;
-    // STB_GEMV_KERNEL=thin in the environment (read at every call) sends every launch to the kernel below: the
-    // tests use it, because on ordinary shapes the fat-wavefront kernel takes everything.
-    const char* which = std::getenv("STB_GEMV_KERNEL");
-    const bool thin_only = which && which[0] == 't';
+    // stb_set_kernel_override can send every launch to the kernel below: the tests use it, because on ordinary
+    // shapes the fat-wavefront kernel takes everything.
+    const bool thin_only = stb_kernel_override(0) == 1;
     if (!thin_only && B <= 16) {                                    // the kernel with fat wavefronts, if its LDS areas fit
         const int rc = stb_tiled_gemv24(L, x, B, y, y_fp32, workspace, workspace_bytes, max_splits(L->n_super), stream, hip_err);
         if (rc != STB_EUNSUPPORTED) return rc;

@@ -1320,14 +1320,13 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
         hipLaunchKernelGGL(gemm_gather_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, p,
                            (const __half*)X, T, (__half*)workspace, cfix);
     }
-    // STB_GEMM_KERNEL in the environment (read at every call): "dense" keeps 2:4 layers on the dense-instruction kernel,
-    // "dense32" runs the 32x32x16 form of that kernel on any layer, "sparse16" runs 2:4 layers on the 16x16x64 form of
-    // the sparse instruction instead of the 32x32x32 one: the tests use them to run every kernel on every case it can
-    // take.
-    const char* which = std::getenv("STB_GEMM_KERNEL");
-    const bool sparse_ok = L->cfg.N == 2 && L->cfg.M == 4 && !(which && which[0] == 'd');
-    const bool narrow = !(which && std::strcmp(which, "dense32") == 0);
-    const bool sparse32 = sparse_ok && !(which && std::strcmp(which, "sparse16") == 0);
+    // stb_set_kernel_override: 1 keeps 2:4 layers on the dense-instruction kernel, 2 runs the 32x32x16 form of that
+    // kernel on any layer, 3 runs 2:4 layers on the 16x16x64 form of the sparse instruction instead of the 32x32x32
+    // one: the tests use them to run every kernel on every case it can take.
+    const int which = stb_kernel_override(2);
+    const bool sparse_ok = L->cfg.N == 2 && L->cfg.M == 4 && which != 1 && which != 2;
+    const bool narrow = which != 2;
+    const bool sparse32 = sparse_ok && which != 3;
     const int tok = sparse_ok ? GmLds<GM_TT24>::TOK : GmLds<GM_TT>::TOK;      // tokens per workgroup of the kernel that runs
     const dim3 grid((T + tok - 1) / tok, (p.nrt + GM_ROWT - 1) / GM_ROWT);
     const int n8 = 8 * L->cfg.N / L->cfg.M;

@@ -26,8 +26,6 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
-#include <cstdlib>
-
 #include "stb_tiled.hpp"
 
 using namespace stbt;
@@ -784,10 +782,10 @@ extern "C" int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_
     const int xbytes = (B < 16 ? B + 1 : 16) * 1040;
     int S = 0, R = 0, SPS = 0, V = 0, wreg = 0, rec_off = 0, part_off = 0;
     int64_t best_cost = 0;
-    // STB_GEMV_VISITS=2 or 3 in the environment (read at every call) restricts the choice to that many visits where
-    // such a shape exists: the tests use it, because small layers never choose several visits themselves.
-    const char* vis = std::getenv("STB_GEMV_VISITS");
-    const int v_only = vis && (vis[0] == '2' || vis[0] == '3') && nsb >= vis[0] - '0' ? vis[0] - '0' : 0;
+    // stb_set_kernel_override can restrict the choice to 2 or 3 visits where such a shape exists: the tests use it,
+    // because small layers never choose several visits themselves.
+    const int asked = stb_kernel_override(1);
+    const int v_only = (asked == 2 || asked == 3) && nsb >= asked ? asked : 0;
     for (int v = 1; v <= 3; v++) {
         if (v_only && v != v_only) continue;
         for (int s = (nsb + 8 * v - 1) / (8 * v); s <= max_splits && s * v <= nsb; s++) {

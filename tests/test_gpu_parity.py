@@ -3,6 +3,7 @@
 Bars: packed bytes and dequantised fp32 weights bit-exact; outputs within
 |y_gpu - y_oracle| <= 2e-3 * sum_j |x_j| |W_hat_ij| (and exactly 0 where that bound is 0).
 """
+import contextlib
 import hashlib
 import json
 import os
@@ -33,6 +34,19 @@ def torch_cuda():
     assert torch.cuda.is_available(), "no GPU visible"
     torch.cuda.set_device(0)
     return torch
+
+
+@contextlib.contextmanager
+def forced(gemv_kernel=0, gemv_visits=0, gemm_kernel=0):
+    """Kernels that ordinary shapes would not reach, asked for through the library's test hook."""
+    S.stb_set_kernel_override(gemv_kernel, gemv_visits, gemm_kernel)
+    try:
+        yield
+    finally:
+        S.stb_set_kernel_override(0, 0, 0)
+
+
+GEMM_KERNELS = {"dense": S.GEMM_DENSE, "dense32": S.GEMM_DENSE32, "sparse16": S.GEMM_SPARSE16}
 
 
 def _within_bound(y_gpu, y_ref, bound, what):
@@ -157,28 +171,22 @@ def test_gemv_small(small_case, torch_cuda, B, y_fp32):
     _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemv B={B}")
     if c["tiled"]:
         # the tiled order has two decode kernels; ordinary shapes all go to the one with fat wavefronts, so the
-        # other one is asked for by name (the library reads the variable at every call)
+        # other one is asked for through the test hook
         yd.fill_(float("nan"))
-        os.environ["STB_GEMV_KERNEL"] = "thin"
-        try:
+        with forced(gemv_kernel=S.GEMV_THIN):
             _say(f"[step] stb_gemv B={B} fp32={y_fp32}, thin-wavefront kernel")
             S.stb_gemv(c["pm"].dev_layout, xd, B, yd, y_fp32, c["pm"].workspace)
             torch.cuda.synchronize()
-        finally:
-            del os.environ["STB_GEMV_KERNEL"]
         _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemv B={B} (thin-wavefront kernel)")
         # ... and small layers never choose several superblock visits per wavefront themselves
-        for visits in ("2", "3"):
-            if (c["k"] + 511) // 512 < int(visits) or B > 16:
+        for visits in (2, 3):
+            if (c["k"] + 511) // 512 < visits or B > 16:
                 continue
             yd.fill_(float("nan"))
-            os.environ["STB_GEMV_VISITS"] = visits
-            try:
+            with forced(gemv_visits=visits):
                 _say(f"[step] stb_gemv B={B} fp32={y_fp32}, {visits} visits per wavefront")
                 S.stb_gemv(c["pm"].dev_layout, xd, B, yd, y_fp32, c["pm"].workspace)
                 torch.cuda.synchronize()
-            finally:
-                del os.environ["STB_GEMV_VISITS"]
             _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemv B={B} ({visits} visits per wavefront)")
 
 
@@ -197,7 +205,7 @@ def test_gemm_small(small_case, torch_cuda, T):
         _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T}")
         # The library picks one kernel per tiled layer (2:4: the sparse matrix instruction 32x32x32; otherwise the dense
         # 16x16x32 one); the others that can take the layer (the other form of each, the dense ones on 2:4 layers) are
-        # asked for by name (the variable is read at every call).
+        # asked for through the test hook.
         others = []
         if c["tiled"]:
             others.append("dense32")
@@ -205,13 +213,10 @@ def test_gemm_small(small_case, torch_cuda, T):
                 others += ["dense", "sparse16"]
         for which in others:
             yd.fill_(float("nan"))
-            os.environ["STB_GEMM_KERNEL"] = which
-            try:
+            with forced(gemm_kernel=GEMM_KERNELS[which]):
                 _say(f"[step] stb_gemm T={T} fp32={y_fp32}, kernel asked for: {which}")
                 S.stb_gemm(c["pm"].dev_layout, xd, T, yd, y_fp32, c["pm"].new_gemm_workspace(T))
                 torch.cuda.synchronize()
-            finally:
-                del os.environ["STB_GEMM_KERNEL"]
             _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T} (kernel asked for: {which})")
 
 
@@ -286,35 +291,30 @@ def test_random_shapes_through_every_kernel(seed, torch_cuda):
         What = O.unpack(O.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode), n, k, N, M)
         pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode).to_device(tiled=True)
 
-        def run(name, value, call):
-            if name:
-                os.environ[name] = value
-            try:
+        def run(hook, call):
+            with forced(**hook):
                 call()
                 torch.cuda.synchronize()
-            finally:
-                if name:
-                    del os.environ[name]
 
         for B in sorted({int(b) for b in rng.integers(1, 33, 2)}):
             x = make_x(B, k, lseed + B)
             y_ref, bound = O.matmul(x, What)
             xd = torch.from_numpy(x).cuda()
-            asks = [(None, None), ("STB_GEMV_KERNEL", "thin")]
-            asks += [("STB_GEMV_VISITS", v) for v in ("2", "3") if (k + 511) // 512 >= int(v) and B <= 16]
-            for name, value in asks:
+            asks = [{}, dict(gemv_kernel=S.GEMV_THIN)]
+            asks += [dict(gemv_visits=v) for v in (2, 3) if (k + 511) // 512 >= v and B <= 16]
+            for hook in asks:
                 yd = torch.full((B, n), float("nan"), dtype=torch.float16, device="cuda")
-                _say(f"[step] stb_gemv B={B} {name}={value}")
-                run(name, value, lambda: S.stb_gemv(pm.dev_layout, xd, B, yd, False, pm.workspace))
-                _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"random gemv B={B} {name}={value}")
+                _say(f"[step] stb_gemv B={B} {hook}")
+                run(hook, lambda: S.stb_gemv(pm.dev_layout, xd, B, yd, False, pm.workspace))
+                _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"random gemv B={B} {hook}")
         for T in sorted({int(t) for t in rng.integers(1, 300, 2)}):
             x = make_x(T, k, lseed + 1000 + T)
             y_ref, bound = O.matmul(x, What)
             xd = torch.from_numpy(x).cuda()
             for value in [None, "dense32"] + (["dense", "sparse16"] if (N, M) == (2, 4) else []):
                 yd = torch.full((T, n), float("nan"), dtype=torch.float16, device="cuda")
-                _say(f"[step] stb_gemm T={T} STB_GEMM_KERNEL={value}")
-                run("STB_GEMM_KERNEL" if value else None, value,
+                _say(f"[step] stb_gemm T={T} kernel asked for: {value}")
+                run(dict(gemm_kernel=GEMM_KERNELS[value]) if value else {},
                     lambda: S.stb_gemm(pm.dev_layout, xd, T, yd, False, pm.new_gemm_workspace(T)))
                 _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"random gemm T={T} kernel={value}")
 
@@ -447,12 +447,9 @@ def test_full_size_layer(cfg, idx, torch_cuda):
             # the prefill kernels that the library does not pick by itself, on the same tokens
             for asked in ["dense32"] + (["sparse16", "dense"] if (spec.N, spec.M) == (2, 4) else []):
                 yd.fill_(float("nan"))
-                os.environ["STB_GEMM_KERNEL"] = asked
-                try:
+                with forced(gemm_kernel=GEMM_KERNELS[asked]):
                     S.stb_gemm(pm.dev_layout, xd, T, yd, False, pm.new_gemm_workspace(T))
                     torch.cuda.synchronize()
-                finally:
-                    del os.environ["STB_GEMM_KERNEL"]
                 y = yd.float().cpu().numpy()
                 assert np.isfinite(y).all()
                 worst = _within_bound(y[rows], y_ref, bound, f"{key} gemm T={T} tiled, kernel asked for: {asked}")
