@@ -243,12 +243,24 @@ int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t
  * argument. */
 int64_t stb_gemv_workspace_bytes(const stb_cfg_t* cfg, int32_t B);
 
-/* Several independent layers with the same B in one launch sequence on one stream (q/k/v or gate/up
- * share x in a decoder layer).  dev, x, y: host arrays of n_layers pointers.  The layers run one after
- * another and share `workspace`, which must cover the largest stb_gemv_workspace_bytes() among them.
- * Errors: as stb_gemv; the first failing layer stops the sequence. */
+/* Several independent layers at the same B as one launch: the matrices of a decoder layer that share their input
+ * (q, k and v; gate and up) or any other list.  Decode is bound by memory traffic (App. C "Theory Analysis", small
+ * N), and a single layer of a few tens of MB is over before the memory system has ramped up; one launch over the
+ * list streams all of them back to back.  Tiled layouts at 2:4, 4:8 or 6:8 run as one kernel per 8 layers whose grid is
+ * the layers' grids one after the other (batches above 16 in two passes); any other list runs layer after layer.
+ * dev, x, y: host arrays of n_layers pointers (x[l], y[l] as in stb_gemv; entries of x may be equal).  Results are the
+ * same bits as n_layers calls of stb_gemv.
+ * workspace: device scratch of at least stb_gemv_batched_workspace_bytes() bytes, 256-byte aligned; layer l owns its
+ * own slice (the slices follow each other in the order of the list, each as large as round_up(stb_gemv_workspace_bytes
+ * of the layer, 256)), whose first 4 * ceil(n / 16) bytes must be zero before the first call and are left zero.
+ * Calls that share a workspace must not overlap in time.
+ * Errors: as stb_gemv; nothing is launched unless every layer's arguments are valid. */
 int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const void* const* x, int32_t B,
                      void* const* y, int32_t y_fp32, void* workspace, int64_t workspace_bytes, void* stream);
+
+/* Scratch bytes stb_gemv_batched needs for the layers described by cfgs[0 .. n_layers) at batch B; negative
+ * stb_status on a bad argument. */
+int64_t stb_gemv_batched_workspace_bytes(int32_t n_layers, const stb_cfg_t* const* cfgs, int32_t B);
 
 /* Prefill-time product (compute-bound regime, App. C: large N = batch x sequence length):
  *   Y[t][i] = sum_j X[t][j] * W_hat[i][j],  t < T.

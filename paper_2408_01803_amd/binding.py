@@ -67,7 +67,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 _LIB = None
 
 EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
-           "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_set_kernel_override", "stb_strerror", "stb_last_hip_error")
+           "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemv_batched_workspace_bytes", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_set_kernel_override", "stb_strerror", "stb_last_hip_error")
 
 
 def _lib():
@@ -107,6 +107,8 @@ def _lib():
     lib.stb_gemv_workspace_bytes.restype = C.c_int64
     lib.stb_gemv_batched.argtypes = [C.c_int32, P(P(stb_layout_t)), P(C.c_void_p), C.c_int32,
                                      P(C.c_void_p), C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.stb_gemv_batched_workspace_bytes.argtypes = [C.c_int32, P(P(stb_cfg_t)), C.c_int32]
+    lib.stb_gemv_batched_workspace_bytes.restype = C.c_int64
     lib.stb_gemm.argtypes = [P(stb_layout_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
                              C.c_void_p, C.c_int64, C.c_void_p]
     lib.stb_gemm_workspace_bytes.argtypes = [P(stb_layout_t), C.c_int32]
@@ -281,6 +283,16 @@ def stb_gemv_batched(layouts_dev: Sequence[stb_layout_t], xs_dev, B: int, ys_dev
     ws_ptr, ws_bytes = _ws(workspace)
     _check(_lib().stb_gemv_batched(n, lay, xs, B, ys, int(y_fp32), ws_ptr, ws_bytes,
                                    C.c_void_p(_stream_ptr(stream))), "stb_gemv_batched")
+
+
+def stb_gemv_batched_workspace_bytes(cfgs: Sequence[stb_cfg_t], B: int) -> int:
+    n = len(cfgs)
+    CP = C.POINTER(stb_cfg_t)
+    arr = (CP * n)(*[C.pointer(c) for c in cfgs])
+    r = _lib().stb_gemv_batched_workspace_bytes(n, arr, B)
+    if r < 0:
+        raise StbError(int(r), "stb_gemv_batched_workspace_bytes")
+    return int(r)
 
 
 def stb_gemm_workspace_bytes(layout: stb_layout_t, T: int) -> int:

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <mutex>
+#include <vector>
 #include <hip/hip_fp16.h>
 
 #include "stb_internal.h"
@@ -452,8 +454,10 @@ extern "C" int64_t stb_gemv_workspace_bytes(const stb_cfg_t* cfg, int32_t B) {
     return stb_tiled_gemv_workspace(tmp.n_row_tiles, tmp.n_super);
 }
 
-extern "C" int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32,
-                        void* workspace, int64_t workspace_bytes, void* stream) {
+// stb_gemv with the partial sums of the column splits at byte offset part_off of the workspace (-1: directly behind
+// the arrival counters, the layout stb_gemv documents).
+static int gemv_impl(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32,
+                     void* workspace, int64_t workspace_bytes, int64_t part_off, void* stream) {
     if (!x || !y) return STB_ENULL;
     int rc = stb_layout_check(dev);
     if (rc) return rc;
@@ -467,7 +471,7 @@ extern "C" int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void*
             void* yb = y_fp32 ? (void*)((float*)y + (size_t)done * dev->cfg.n_out)
                               : (void*)((__half*)y + (size_t)done * dev->cfg.n_out);
             int herr = 0;
-            rc = stb_tiled_gemv(dev, xb, nb, yb, y_fp32, workspace, workspace_bytes, stream, &herr);
+            rc = stb_tiled_gemv(dev, xb, nb, yb, y_fp32, workspace, workspace_bytes, part_off, stream, &herr);
             if (rc == STB_EHIP) g_last_hip_error = herr;
             if (rc) return rc;
         }
@@ -495,13 +499,88 @@ extern "C" int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void*
     return e == hipSuccess ? STB_OK : hip_fail(e);
 }
 
+extern "C" int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32,
+                        void* workspace, int64_t workspace_bytes, void* stream) {
+    return gemv_impl(dev, x, B, y, y_fp32, workspace, workspace_bytes, -1, stream);
+}
+
+// Each layer of a batched call owns a slice of the workspace: its arrival counters, then its partial sums.
+static int64_t round_up256_(int64_t v) { return (v + 255) / 256 * 256; }
+static int64_t batched_slice(const stb_cfg_t* cfg, int32_t B, int64_t* counter_bytes) {
+    stb_layout_t tmp;
+    int rc = stb_tiled_sizes(cfg, &tmp);
+    if (rc) return rc;
+    if (B < 1 || B > STB_MAX_BATCH) return STB_EINVAL;
+    const int64_t total = stb_tiled_gemv_workspace(tmp.n_row_tiles, tmp.n_super);
+    if (counter_bytes) *counter_bytes = round_up256_(4 * (int64_t)tmp.n_row_tiles);
+    return round_up256_(total);
+}
+
+extern "C" int64_t stb_gemv_batched_workspace_bytes(int32_t n_layers, const stb_cfg_t* const* cfgs, int32_t B) {
+    if (!cfgs) return STB_ENULL;
+    if (n_layers < 1) return STB_EINVAL;
+    int64_t total = 0;
+    for (int l = 0; l < n_layers; l++) {
+        if (!cfgs[l]) return STB_ENULL;
+        const int64_t b = batched_slice(cfgs[l], B, nullptr);
+        if (b < 0) return b;
+        total += b;
+    }
+    return total;
+}
+
 extern "C" int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const void* const* x,
                                 int32_t B, void* const* y, int32_t y_fp32, void* workspace,
                                 int64_t workspace_bytes, void* stream) {
     if (!dev || !x || !y) return STB_ENULL;
-    if (n_layers < 1) return STB_EINVAL;
+    if (n_layers < 1 || B < 1 || B > STB_MAX_BATCH || (y_fp32 != 0 && y_fp32 != 1) || workspace_bytes < 0) return STB_EINVAL;
+    if (workspace && (uintptr_t)workspace % 256) return STB_EALIGN;
+    // validate everything before the first launch; cut the workspace into one slice per layer
+    std::vector<int64_t> off(n_layers), cnt_bytes(n_layers), len(n_layers);
+    int64_t total = 0;
+    bool grouped = true;
     for (int l = 0; l < n_layers; l++) {
-        int rc = stb_gemv(dev[l], x[l], B, y[l], y_fp32, workspace, workspace_bytes, stream);
+        if (!dev[l] || !x[l] || !y[l]) return STB_ENULL;
+        const int rc = stb_layout_check(dev[l]);
+        if (rc) return rc;
+        if ((uintptr_t)x[l] % 16 || (uintptr_t)y[l] % 4) return STB_EALIGN;
+        const int64_t b = batched_slice(&dev[l]->cfg, B, &cnt_bytes[l]);
+        if (b < 0) return (int)b;
+        off[l] = total; len[l] = b;
+        total += b;
+        if (dev[l]->kind != STB_KIND_TILED || !stb_tiled_supported(dev[l])) grouped = false;
+    }
+    const bool have_ws = workspace && workspace_bytes >= total;
+    if (!have_ws && workspace && workspace_bytes > 0) return STB_EINVAL;      // a workspace that is too small
+    if (grouped && stb_kernel_override(0) == 0) {
+        // layers in runs of up to 8 per launch, batch rows in chunks of 16
+        bool fell_back = false;
+        for (int l0 = 0; l0 < n_layers && !fell_back; l0 += 8) {
+            const int nl = n_layers - l0 < 8 ? n_layers - l0 : 8;
+            for (int done = 0; done < B; done += 16) {
+                const int nb = B - done < 16 ? B - done : 16;
+                const void* xs[8]; void* ys[8]; void* cnts[8]; void* parts[8]; int64_t pbytes[8];
+                for (int j = 0; j < nl; j++) {
+                    const stb_layout_t* L = dev[l0 + j];
+                    xs[j] = (const __half*)x[l0 + j] + (size_t)done * L->cfg.k_in;
+                    ys[j] = y_fp32 ? (void*)((float*)y[l0 + j] + (size_t)done * L->cfg.n_out)
+                                   : (void*)((__half*)y[l0 + j] + (size_t)done * L->cfg.n_out);
+                    cnts[j] = have_ws ? (char*)workspace + off[l0 + j] : nullptr;
+                    parts[j] = have_ws ? (char*)workspace + off[l0 + j] + cnt_bytes[l0 + j] : nullptr;
+                    pbytes[j] = have_ws ? len[l0 + j] - cnt_bytes[l0 + j] : 0;
+                }
+                int herr = 0;
+                const int rc = stb_tiled_gemv24_group(nl, dev + l0, xs, nb, ys, y_fp32, cnts, parts, pbytes, stream, &herr);
+                if (rc == STB_EUNSUPPORTED && l0 == 0 && done == 0) { fell_back = true; break; }   // nothing was launched yet
+                if (rc == STB_EHIP) g_last_hip_error = herr;
+                if (rc) return rc;
+            }
+        }
+        if (!fell_back) return STB_OK;
+    }
+    for (int l = 0; l < n_layers; l++) {
+        const int rc = gemv_impl(dev[l], x[l], B, y[l], y_fp32, have_ws ? (char*)workspace + off[l] : nullptr,
+                                 have_ws ? len[l] : 0, -1, stream);
         if (rc) return rc;
     }
     return STB_OK;

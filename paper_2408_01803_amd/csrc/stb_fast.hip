@@ -553,13 +553,13 @@ static hipError_t launch_gemv_stream(const TiledPlanes& p, const __half* x, int 
 }
 
 extern "C" int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
-                              int64_t workspace_bytes, void* stream, int* hip_err) {
+                              int64_t workspace_bytes, int64_t part_off, void* stream, int* hip_err) {
     if (!stb_tiled_supported(L)) return STB_EUNSUPPORTED;
     // stb_set_kernel_override can send every launch to the kernel below: the tests use it, because on ordinary
     // shapes the fat-wavefront kernel takes everything.
     const bool thin_only = stb_kernel_override(0) == 1;
     if (!thin_only && B <= 16) {                                    // the kernel with fat wavefronts, if its LDS areas fit
-        const int rc = stb_tiled_gemv24(L, x, B, y, y_fp32, workspace, workspace_bytes, max_splits(L->n_super), stream, hip_err);
+        const int rc = stb_tiled_gemv24(L, x, B, y, y_fp32, workspace, workspace_bytes, part_off, max_splits(L->n_super), stream, hip_err);
         if (rc != STB_EUNSUPPORTED) return rc;
     }
     const TiledPlanes p = make_tiled(L);
@@ -585,10 +585,11 @@ extern "C" int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void*
     if (best_S == 0) return STB_EINVAL;
     const int S = best_S, R = best_R, SPS = best_sps, RS = 16 / (2 * SPS);
     const int G = (p.nrt + RS * R - 1) / (RS * R);
-    const int64_t need = stb_tiled_gemv_workspace(p.nrt, p.nsb);
     if (S > 1) {
         if (!workspace) return STB_ENULL;
-        if (workspace_bytes < need) return STB_EINVAL;
+        if (part_off < 0) part_off = round_up256(4 * (int64_t)p.nrt);
+        if (part_off % 256 || part_off < 4 * (int64_t)p.nrt) return STB_EINVAL;
+        if (workspace_bytes < part_off + (int64_t)S * 16 * 16 * p.nrt * 4) return STB_EINVAL;
         if ((uintptr_t)workspace % 256) return STB_EALIGN;
     }
     const size_t lds = (size_t)16 * STB_GEMV_PHASE * 256 * sizeof(float);   // + 32 KB of tables: 128 KB of LDS
@@ -596,7 +597,7 @@ extern "C" int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void*
     const hipStream_t st = (hipStream_t)stream;
     const __half* xh = (const __half*)x;
     uint32_t* cnt = (uint32_t*)workspace;
-    float* part = S > 1 ? (float*)((char*)workspace + round_up256(4 * (int64_t)p.nrt)) : nullptr;
+    float* part = S > 1 ? (float*)((char*)workspace + part_off) : nullptr;
     const bool res = p.res_words > 0;
     hipError_t e;
     if (kept_per_8(L) == 4)

@@ -26,6 +26,9 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 
+#include <atomic>
+#include <cstddef>
+
 #include "stb_tiled.hpp"
 
 using namespace stbt;
@@ -226,17 +229,46 @@ struct Res24 {
     uint32_t sh;        // bit of the first entry inside the first word
 };
 
+// One layer of a launch: its planes, vectors, scratch and launch shape (see stb_tiled_gemv24_plan), and where its
+// workgroups sit in the launch's grid.  A launch takes up to GROUP24_MAX layers (the matrices of a decoder layer that
+// share their input, say): the grid is the layers' grids one after the other, and a workgroup finds its layer by its
+// index.  The descriptors travel by value in the kernel arguments, so a launch needs no table in device memory and can
+// be captured in a HIP graph.
+struct Gemv24Layer {
+    TiledPlanes p;
+    const __half* x;
+    void* y;
+    float* ws_part;
+    uint32_t* ws_count;
+    int R, SPS, PHT, WREG, REC_OFF, PART_OFF, V, XS;
+    int G, S;                 // workgroups along the rows, column splits: the layer owns G * S workgroups ...
+    int block0;               // ... starting at this one
+    int variant;              // MODE | HAS_RES << 3 | MULTI << 4
+};
+constexpr int GROUP24_MAX = 8;
+struct Gemv24Group {
+    int n_layers, B, y_fp32, pad;
+    Gemv24Layer l[GROUP24_MAX];
+};
+
+// Dynamic LDS of a workgroup: [0, 16) the ticket of the column splits; dense modes: the scatter table (32 KB); then one
+// region of WREG bytes per wavefront.
+constexpr int LDS24_HEAD = 16;
+
 template <int MODE, bool HAS_RES, bool MULTI>
-__global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half* __restrict__ x, int B,
-                                                      void* __restrict__ y, int y_fp32, int R, int SPS, int PHT,
-                                                      int WREG, int REC_OFF, int PART_OFF, int V_, int XS,
-                                                      float* __restrict__ ws_part, uint32_t* __restrict__ ws_count) {
-    __shared__ uint32_t ticket;
-    const int V = MULTI ? V_ : 1;                                // visits per wavefront (a kernel of its own for V > 1: the code is larger)
+__device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, const int y_fp32, const int gr, const int ks,
+                                            char* const dyn) {
+    const TiledPlanes& p = d.p;
+    const __half* __restrict__ const x = d.x;
+    void* __restrict__ const y = d.y;
+    const int R = d.R, SPS = d.SPS, PHT = d.PHT, WREG = d.WREG, REC_OFF = d.REC_OFF, PART_OFF = d.PART_OFF, XS = d.XS;
+    float* __restrict__ const ws_part = d.ws_part;
+    uint32_t* __restrict__ const ws_count = d.ws_count;
+    uint32_t& ticket = *reinterpret_cast<uint32_t*>(dyn);
+    const int V = MULTI ? d.V : 1;                               // visits per wavefront
     constexpr int N8 = MODE == 6 ? 6 : 4;
     typedef typename TileOf<MODE>::type Tile;
-    __shared__ uint4 lut_mem[MODE == 2 ? 1 : 256 * 8];           // dense modes: the scatter table, eight copies
-    ScatterLds* const lut = reinterpret_cast<ScatterLds*>(lut_mem);
+    ScatterLds* const lut = reinterpret_cast<ScatterLds*>(dyn + LDS24_HEAD);      // dense modes: the scatter table, eight copies
     // Each wavefront owns a region of LDS of WREG bytes: its slice of x ([row][1040 bytes], B rows and one of zeros),
     // its 16 salient-column records at REC_OFF, its partial products [PHT][256] fp32 at PART_OFF (with one visit
     // per wavefront: 0, on top of the x rows, which are in registers by then).  A wavefront stages all of it itself,
@@ -246,16 +278,16 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
     // for every row tile and adds their products up in registers, so that no other workgroup holds a part of the
     // row's sum; it keeps V slices of x (XS bytes apart) and V record sets in LDS and takes the operands of a
     // visit from there before each product.
-    extern __shared__ __attribute__((aligned(16))) char lds_base[];
+    char* const lds_base = dyn + LDS24_HEAD + (MODE == 2 ? 0 : (int)sizeof(ScatterLds));
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int i = lane & 15, g = lane >> 4;
-    const int nthr = blockDim.x;                                  // 64 * SPS: one wavefront per superblock of the split
-    const int gr = blockIdx.x, ks = blockIdx.y, S = gridDim.y;
+    const int nthr = blockDim.x;                                  // at least 64 * SPS: one wavefront per superblock of the split
+    const int S = d.S;
     const int sb = ks * SPS * V + wave;                           // superblock of the first visit
     const int r0 = gr * R;
     const int r1 = r0 + R < p.nrt ? r0 + R : p.nrt;
     const int rl = r1 - 1;
-    const bool active = sb < p.nsb;                               // uniform per wavefront
+    const bool active = wave < SPS && sb < p.nsb;                 // uniform per wavefront (a launch of several layers has the widest layer's wavefronts)
     const int Wa = p.nsb - ks * SPS * V < SPS ? p.nsb - ks * SPS * V : SPS;   // wavefronts with work
     auto sb_of = [&](int v) { return sb + v * SPS < p.nsb ? sb + v * SPS : sb; };       // a visit past the last superblock re-reads the first
     auto tile_of = [&](int rt, int v = 0) { return rt * p.nsb + sb_of(v); };
@@ -723,18 +755,35 @@ __global__ __launch_bounds__(512) void gemv24_kernel(TiledPlanes p, const __half
     }
 }
 
-template <int MODE, bool HAS_RES, bool MULTI>
-hipError_t launch24(const TiledPlanes& p, const __half* x, int B, void* y, int y_fp32, int R, int SPS, int PHT, int wreg, int rec_off,
-                    int part_off, int V, int xs, dim3 grid, float* ws_part, uint32_t* ws_count, hipStream_t st) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv24_kernel<MODE, HAS_RES, MULTI>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS24 - (MODE == 2 ? 0 : 32768));
-    if (attr != hipSuccess) return attr;
-    hipLaunchKernelGGL((gemv24_kernel<MODE, HAS_RES, MULTI>), grid, dim3(64 * SPS), (size_t)SPS * wreg, st, p, x, B, y, y_fp32, R, SPS, PHT,
-                       wreg, rec_off, part_off, V, xs, ws_part, ws_count);
-    return hipGetLastError();
+// The launch: workgroup b belongs to the layer whose range of workgroups holds b and runs that layer's variant of
+// the body.  Every variant fits two wavefronts per SIMD, so putting them into one kernel costs no occupancy.
+__global__ __launch_bounds__(512) void gemv24_group_kernel(const Gemv24Group a) {
+    extern __shared__ __attribute__((aligned(16))) char dyn24[];
+    int li = 0;
+    for (int l = 1; l < a.n_layers; l++)
+        if ((int)blockIdx.x >= a.l[l].block0) li = l;
+    li = __builtin_amdgcn_readfirstlane(li);
+    // the descriptor comes out of the kernel-argument segment with scalar loads (indexing the by-value argument would
+    // make a private copy of it, and the plane pointers must sit in scalar registers)
+    typedef const __attribute__((address_space(4))) char* kernarg_ptr;
+    const kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+    Gemv24Layer d;
+    __builtin_memcpy(&d, ka + offsetof(Gemv24Group, l) + (size_t)li * sizeof(Gemv24Layer), sizeof(Gemv24Layer));
+    const int local = (int)blockIdx.x - d.block0;
+    const int ks = local / d.G, gr = local - ks * d.G;
+    switch (d.variant) {
+#define STB24_CASE(MODE, RES, MULTI) case (MODE | (RES ? 8 : 0) | (MULTI ? 16 : 0)): gemv24_body<MODE, RES, MULTI>(d, a.B, a.y_fp32, gr, ks, dyn24); break;
+        STB24_CASE(2, false, false) STB24_CASE(2, true, false) STB24_CASE(2, false, true) STB24_CASE(2, true, true)
+        STB24_CASE(4, false, false) STB24_CASE(4, true, false) STB24_CASE(4, false, true) STB24_CASE(4, true, true)
+        STB24_CASE(6, false, false) STB24_CASE(6, true, false) STB24_CASE(6, false, true) STB24_CASE(6, true, true)
+#undef STB24_CASE
+        default: break;
+    }
 }
 
 int64_t round_up256(int64_t v) { return (v + 255) / 256 * 256; }
+// Largest number of column splits the plan may choose for n_super superblocks (the workspace is sized for it).
+int max_splits24(int n_super) { return (n_super + 1) / 2 + 3; }
 
 }  // namespace
 
@@ -813,42 +862,73 @@ extern "C" int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_
     return STB_OK;
 }
 
-// Picks the launch shape and runs the kernel; returns STB_EUNSUPPORTED (and launches nothing) when the layout
-// is not 2:4 or a staging area would not fit, so that the caller can fall back to the general kernel.
-extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
-                                int64_t workspace_bytes, int max_splits, void* stream, int* hip_err) {
-    if (B < 1 || B > 16 || (8 * L->cfg.N) % L->cfg.M != 0) return STB_EUNSUPPORTED;
-    const int n8 = 8 * L->cfg.N / L->cfg.M;
-    const int mode = L->cfg.M == 4 && L->cfg.N == 2 ? 2 : n8;      // 2: sparse instruction; 4, 6: dense with the scatter table
-    if (mode != 2 && mode != 4 && mode != 6) return STB_EUNSUPPORTED;
-    if (L->region_bytes >= (1ll << 31) || L->res_bytes >= (1ll << 31)) return STB_EUNSUPPORTED;   // 32-bit offsets inside a plane
-    const TiledPlanes p = make_tiled(L);
-    int plan[7];
-    if (stb_tiled_gemv24_plan(p.nrt, p.nsb, B, mode, max_splits, plan) != STB_OK) return STB_EUNSUPPORTED;
-    const int S = plan[0], R = plan[1], SPS = plan[2], V = plan[3], wreg = plan[4], rec_off = plan[5], part_off = plan[6];
+// Plans and launches one kernel over n_layers tiled layouts (1 .. GROUP24_MAX) at the same batch; layer l reads xs[l],
+// writes ys[l] and keeps the arrival counters of its column splits at counters[l] (4 bytes per row tile, zero before
+// and after) and their partial sums at partials[l] (partial_bytes[l] bytes).  Returns STB_EUNSUPPORTED, and launches
+// nothing, when a layout is not 2:4 / 4:8 / 6:8 or a staging area would not fit, so that the caller can fall back to
+// the general kernel layer by layer.
+extern "C" int stb_tiled_gemv24_group(int n_layers, const stb_layout_t* const* Ls, const void* const* xs, int B,
+                                      void* const* ys, int y_fp32, void* const* counters, void* const* partials,
+                                      const int64_t* partial_bytes, void* stream, int* hip_err) {
+    if (n_layers < 1 || n_layers > GROUP24_MAX || B < 1 || B > 16) return STB_EUNSUPPORTED;
+    Gemv24Group a;
+    a.n_layers = n_layers; a.B = B; a.y_fp32 = y_fp32; a.pad = 0;
     const int xbytes = (B < 16 ? B + 1 : 16) * 1040;
-    const int G = (p.nrt + R - 1) / R;
-    const int PHT = R < PHASE24 ? R : PHASE24;
-    const bool res = p.res_words > 0;
-    if (S > 1) {
-        if (!workspace) return STB_ENULL;
-        if (workspace_bytes < round_up256(4 * (int64_t)p.nrt) + (int64_t)S * 16 * 16 * p.nrt * 4) return STB_EINVAL;
-        if ((uintptr_t)workspace % 256) return STB_EALIGN;
+    int blocks = 0, sps_max = 1;
+    int64_t lds = 0;
+    for (int l = 0; l < n_layers; l++) {
+        const stb_layout_t* L = Ls[l];
+        if ((8 * L->cfg.N) % L->cfg.M != 0) return STB_EUNSUPPORTED;
+        const int n8 = 8 * L->cfg.N / L->cfg.M;
+        const int mode = L->cfg.M == 4 && L->cfg.N == 2 ? 2 : n8;      // 2: sparse instruction; 4, 6: dense with the scatter table
+        if (mode != 2 && mode != 4 && mode != 6) return STB_EUNSUPPORTED;
+        if (L->region_bytes >= (1ll << 31) || L->res_bytes >= (1ll << 31)) return STB_EUNSUPPORTED;   // 32-bit offsets inside a plane
+        Gemv24Layer& d = a.l[l];
+        d.p = make_tiled(L);
+        int plan[7];
+        if (stb_tiled_gemv24_plan(d.p.nrt, d.p.nsb, B, mode, max_splits24(d.p.nsb), plan) != STB_OK) return STB_EUNSUPPORTED;
+        d.S = plan[0]; d.R = plan[1]; d.SPS = plan[2]; d.V = plan[3]; d.WREG = plan[4]; d.REC_OFF = plan[5]; d.PART_OFF = plan[6];
+        d.XS = xbytes;
+        d.G = (d.p.nrt + d.R - 1) / d.R;
+        d.PHT = d.R < PHASE24 ? d.R : PHASE24;
+        d.block0 = blocks;
+        d.variant = mode | (d.p.res_words > 0 ? 8 : 0) | (d.V > 1 ? 16 : 0);
+        d.x = (const __half*)xs[l];
+        d.y = ys[l];
+        d.ws_count = nullptr; d.ws_part = nullptr;
+        if (d.S > 1) {
+            if (!counters[l] || !partials[l]) return STB_ENULL;
+            if (partial_bytes[l] < (int64_t)d.S * 16 * 16 * d.p.nrt * 4) return STB_EINVAL;
+            if ((uintptr_t)counters[l] % 4 || (uintptr_t)partials[l] % 256) return STB_EALIGN;
+            d.ws_count = (uint32_t*)counters[l];
+            d.ws_part = (float*)partials[l];
+        }
+        blocks += d.G * d.S;
+        if (d.SPS > sps_max) sps_max = d.SPS;
+        const int64_t need = LDS24_HEAD + (mode == 2 ? 0 : (int64_t)sizeof(ScatterLds)) + (int64_t)d.SPS * d.WREG;
+        if (need > lds) lds = need;
     }
-    uint32_t* cnt = (uint32_t*)workspace;
-    float* part = S > 1 ? (float*)((char*)workspace + round_up256(4 * (int64_t)p.nrt)) : nullptr;
-    const __half* xh = (const __half*)x;
-    const dim3 grid(G, S);
-    const hipStream_t st = (hipStream_t)stream;
-    hipError_t e;
-#define STB24_ARGS p, xh, B, y, y_fp32, R, SPS, PHT, wreg, rec_off, part_off, V, xbytes, grid, part, cnt, st
-#define STB24_GO(MODE) (V > 1 ? (res ? launch24<MODE, true, true>(STB24_ARGS) : launch24<MODE, false, true>(STB24_ARGS)) \
-                              : (res ? launch24<MODE, true, false>(STB24_ARGS) : launch24<MODE, false, false>(STB24_ARGS)))
-    if (mode == 2) e = STB24_GO(2);
-    else if (mode == 4) e = STB24_GO(4);
-    else e = STB24_GO(6);
-#undef STB24_GO
-#undef STB24_ARGS
+    for (int l = n_layers; l < GROUP24_MAX; l++) a.l[l] = a.l[0];
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load(std::memory_order_acquire)) {
+        const hipError_t e = hipFuncSetAttribute((const void*)gemv24_group_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS24 + LDS24_HEAD);
+        if (e != hipSuccess) { *hip_err = (int)e; return STB_EHIP; }
+        attr_set.store(true, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(gemv24_group_kernel, dim3(blocks), dim3(64 * sps_max), (size_t)lds, (hipStream_t)stream, a);
+    const hipError_t e = hipGetLastError();
     *hip_err = (int)e;
     return e == hipSuccess ? STB_OK : STB_EHIP;
+}
+
+extern "C" int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
+                                int64_t workspace_bytes, int64_t ws_part_off, int max_splits, void* stream, int* hip_err) {
+    (void)max_splits;
+    if (ws_part_off < 0) ws_part_off = round_up256(4 * (int64_t)L->n_row_tiles);
+    if (ws_part_off % 256 || ws_part_off < 4 * (int64_t)L->n_row_tiles) return STB_EINVAL;
+    if (workspace && (uintptr_t)workspace % 256) return STB_EALIGN;
+    void* cnt = workspace;
+    void* part = workspace ? (char*)workspace + ws_part_off : nullptr;
+    const int64_t part_bytes = workspace && workspace_bytes > ws_part_off ? workspace_bytes - ws_part_off : 0;
+    return stb_tiled_gemv24_group(1, &L, &x, B, &y, y_fp32, &cnt, &part, &part_bytes, stream, hip_err);
 }

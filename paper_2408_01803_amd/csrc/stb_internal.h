@@ -19,15 +19,21 @@ int stb_layout_check(const stb_layout_t* L);
 // code of a failed launch in *hip_err.  stb_tiled_supported: 1 iff the fast kernels cover this N:M.
 int stb_tiled_supported(const stb_layout_t* L);
 int stb_tiled_dequant(const stb_layout_t* L, float* out, void* stream, int* hip_err);
+// The workspace holds the arrival counters of the column splits (4 bytes per row tile, at its start) and their partial
+// sums at byte offset part_off (a multiple of 256, at least 4 * n_row_tiles; -1 = directly behind the counters).
 int stb_tiled_gemv(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
-                   int64_t workspace_bytes, void* stream, int* hip_err);
+                   int64_t workspace_bytes, int64_t part_off, void* stream, int* hip_err);
 // Scratch bytes of the tiled decode kernels for L's shape.
 int64_t stb_tiled_gemv_workspace(int n_row_tiles, int n_super);
 // Decode kernel with one fat wavefront per superblock (stb_gemv24.hip): 2:4 layouts on the sparse matrix-core
 // instruction, 4:8 / 6:8 (and 3:4) on the dense one.  Returns STB_EUNSUPPORTED, without launching anything, when
 // its staging areas would not fit: the caller then runs the older kernel.  max_splits bounds the number of column splits (the workspace is sized for that many).
 int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y_fp32, void* workspace,
-                     int64_t workspace_bytes, int max_splits, void* stream, int* hip_err);
+                     int64_t workspace_bytes, int64_t part_off, int max_splits, void* stream, int* hip_err);
+// One launch of that kernel over up to 8 layers at the same batch (B <= 16); see stb_gemv24.hip.
+int stb_tiled_gemv24_group(int n_layers, const stb_layout_t* const* Ls, const void* const* xs, int B, void* const* ys,
+                           int y_fp32, void* const* counters, void* const* partials, const int64_t* partial_bytes,
+                           void* stream, int* hip_err);
 // The launch shape stb_tiled_gemv24 takes (host arithmetic only; out[7] = S, R, SPS, V, LDS bytes per wavefront, record
 // offset, partial-tile offset).
 int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_splits, int* out);

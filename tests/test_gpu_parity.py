@@ -273,6 +273,101 @@ def test_device_entry_points_reject_bad_arguments(torch_cuda):
 
 
 # --------------------------------------------------------------------------------------------------
+# several layers in one launch
+# --------------------------------------------------------------------------------------------------
+def _bits(t):
+    a = t.cpu().numpy()
+    return a.view(np.uint32 if a.dtype == np.float32 else np.uint16)
+
+
+@pytest.mark.parametrize("B", [1, 3, 16, 21])
+def test_gemv_batched_is_one_launch_with_the_bits_of_single_calls(torch_cuda, B):
+    """A list of layers that differ in everything (N:M, rows, columns, column splits, salient columns or none, a shared
+    input vector) through stb_gemv_batched: against the oracle, and bit for bit against stb_gemv layer by layer."""
+    torch = torch_cuda
+    shapes = [(130, 1024, 6, 8, 1, 0.05), (40, 1024, 6, 8, 0, 0.05), (257, 4608, 2, 4, 0, 0.05), (64, 512, 4, 8, 0, 0.0),
+              (17, 9728, 4, 8, 1, 0.02), (5, 128, 2, 4, 0, 0.05), (100, 1024, 4, 8, 0, 0.1), (33, 640, 6, 8, 1, 0.0),
+              (48, 1024, 2, 4, 1, 0.15), (96, 512, 5, 8, 0, 0.05)]
+    layers = []
+    xs_by_k = {}
+    for j, (n, k, N, M, mode, frac) in enumerate(shapes):
+        L = make_layer(n, k, 300 + j, "x8", n_salient=int(frac * k))
+        What = O.unpack(O.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode), n, k, N, M)
+        pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode).to_device(tiled=_tiled_ok(N, M))
+        if k not in xs_by_k:
+            x = make_x(B, k, 300 + k)
+            xs_by_k[k] = (x, torch.from_numpy(x).cuda())
+        layers.append(dict(n=n, k=k, pm=pm, What=What))
+    for sel, what in ((range(9), "nine tiled layers: two launches"), (range(3), "three layers"), (range(10), "a row-major layer in the list"),
+                      ([4], "one layer")):
+        sel = list(sel)
+        for y_fp32 in (False, True):
+            dt = torch.float32 if y_fp32 else torch.float16
+            ys = [torch.full((B, layers[j]["n"]), float("nan"), dtype=dt, device="cuda") for j in sel]
+            ws = S.new_device_scratch(S.stb_gemv_batched_workspace_bytes([layers[j]["pm"].cfg for j in sel], B), zero=True)
+            for rnd in range(2):                       # twice on the same workspace: the counters are left zero
+                for yb in ys:
+                    yb.fill_(float("nan"))
+                _say(f"[step] stb_gemv_batched B={B} fp32={y_fp32}: {what}, call {rnd}")
+                S.stb_gemv_batched([layers[j]["pm"].dev_layout for j in sel], [xs_by_k[layers[j]["k"]][1] for j in sel], B, ys,
+                                   y_fp32, ws)
+                torch.cuda.synchronize()
+                for j, yb in zip(sel, ys):
+                    ly = layers[j]
+                    y_ref, bound = O.matmul(xs_by_k[ly["k"]][0], ly["What"])
+                    _within_bound(yb.float().cpu().numpy(), y_ref, bound, f"batched gemv layer {j} B={B}")
+                    y1 = torch.full((B, ly["n"]), float("nan"), dtype=dt, device="cuda")
+                    S.stb_gemv(ly["pm"].dev_layout, xs_by_k[ly["k"]][1], B, y1, y_fp32, ly["pm"].workspace)
+                    torch.cuda.synchronize()
+                    assert (_bits(yb) == _bits(y1)).all(), f"layer {j}: batched and single calls differ"
+
+
+def test_gemv_batched_rejects_bad_arguments(torch_cuda):
+    torch = torch_cuda
+    L = make_layer(40, 4608, 9)
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], 2, 4, 1).to_device(tiled=True)
+    xd = torch.zeros((1, 4608), dtype=torch.float16, device="cuda")
+    yd = torch.zeros((1, 40), dtype=torch.float16, device="cuda")
+    need = S.stb_gemv_batched_workspace_bytes([pm.cfg, pm.cfg], 1)
+    assert need == 2 * S.stb_gemv_batched_workspace_bytes([pm.cfg], 1) and need % 256 == 0
+    small = S.new_device_scratch(need - 256, zero=True)
+    with pytest.raises(S.StbError) as e:
+        S.stb_gemv_batched([pm.dev_layout, pm.dev_layout], [xd, xd], 1, [yd, yd], False, small)
+    assert e.value.status == S.STB_EINVAL
+    with pytest.raises(S.StbError) as e:
+        S.stb_gemv_batched([pm.dev_layout], [xd], 33, [yd], False, small)
+    assert e.value.status == S.STB_EINVAL
+
+
+def test_decode_is_bitwise_reproducible_across_launch_shapes(torch_cuda):
+    """The reduction order of the decode kernels is fixed (wavefronts in order inside a workgroup, column splits in
+    order through the workspace): repeated calls give identical bits, and so do calls whose workgroups run in another
+    order because other layers share the launch."""
+    torch = torch_cuda
+    n, k, B = 200, 9728, 5
+    L = make_layer(n, k, 77, "t3")
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], 2, 4, 0).to_device(tiled=True)
+    L2 = make_layer(64, k, 78)
+    pm2 = S.PackedMatrix.pack(L2["W"], L2["xnorm"], L2["sal_bitmap"], 4, 8, 0).to_device(tiled=True)
+    xd = torch.from_numpy(make_x(B, k, 77)).cuda()
+    outs = []
+    for rep in range(3):
+        y = torch.full((B, n), float("nan"), dtype=torch.float32, device="cuda")
+        S.stb_gemv(pm.dev_layout, xd, B, y, True, pm.workspace)
+        torch.cuda.synchronize()
+        outs.append(_bits(y))
+    ws = S.new_device_scratch(S.stb_gemv_batched_workspace_bytes([pm2.cfg, pm.cfg, pm2.cfg], B), zero=True)
+    y = torch.full((B, n), float("nan"), dtype=torch.float32, device="cuda")
+    ya, yb = (torch.empty((B, 64), dtype=torch.float32, device="cuda") for _ in range(2))
+    S.stb_gemv_batched([pm2.dev_layout, pm.dev_layout, pm2.dev_layout], [xd, xd, xd], B, [ya, y, yb], True, ws)
+    torch.cuda.synchronize()
+    outs.append(_bits(y))
+    for o in outs[1:]:
+        assert (o == outs[0]).all()
+    assert (_bits(ya) == _bits(yb)).all()
+
+
+# --------------------------------------------------------------------------------------------------
 # random shapes: every kernel that can take a layer, on shapes nobody chose by hand
 # --------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("seed", [21, 22, 23])
