@@ -62,7 +62,8 @@ typedef enum stb_status {
     STB_EALIGN = -3,      /* a plane pointer is not 16-byte aligned */
     STB_ENONFINITE = -4,  /* NaN or Inf in W or xnorm, or xnorm < 0 */
     STB_EHIP = -5,        /* a HIP call failed; the HIP error code is returned by stb_last_hip_error() */
-    STB_EUNSUPPORTED = -6 /* valid request that this build has no kernel for */
+    STB_EUNSUPPORTED = -6, /* valid request that this build has no kernel for */
+    STB_ETOOBIG = -7      /* stb_gemv_static: the problem needs more scratch than the library's static device array holds */
 } stb_status;
 
 /* Problem description. block must be 128. region_mode: 0 = break-point search of Alg. 2
@@ -238,6 +239,20 @@ int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream);
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
 int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32,
              void* workspace, int64_t workspace_bytes, void* stream);
+
+/* stb_gemv for callers that cannot allocate or bring a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same product, same kernels and the same bits in y as stb_gemv, but the scratch of
+ * the column splits lives in a device array that is part of the library's code object (STB_GEMV_STATIC_SCRATCH_BYTES
+ * bytes on every GPU the library runs on, held until the process ends); the call allocates nothing and needs no set-up
+ * call (the array's address on the current device is looked up at the first call there).
+ * Limits: ceil(n / 16) <= 16384 row tiles, and 65536 + splits * 1024 * ceil(n / 16) bytes <= the array, where splits is
+ * the number of column splits the launcher takes for the shape (1 for k <= 4096; the 70B-shaped layers of the
+ * workloads need at most 4 MB); beyond that the call returns STB_ETOOBIG and launches nothing.
+ * Every call on one GPU uses the same array: calls that overlap in time on one GPU (two streams, two threads) race.
+ * The arrival counters at the start of the array are zero when the library is loaded and every call leaves them zero.
+ * Errors: as stb_gemv, plus STB_ETOOBIG and STB_EUNSUPPORTED (device ordinal >= 64). */
+#define STB_GEMV_STATIC_SCRATCH_BYTES (8 * 1024 * 1024)
+int stb_gemv_static(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32, void* stream);
 
 /* Scratch bytes stb_gemv needs for (cfg, B), for either kind of layout; negative stb_status on a bad
  * argument. */

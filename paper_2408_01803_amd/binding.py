@@ -19,7 +19,8 @@ STB_BLOCK = 128
 STB_MAX_BATCH = 32
 STB_PLANE_ALIGN = 256
 
-STB_OK, STB_EINVAL, STB_ENULL, STB_EALIGN, STB_ENONFINITE, STB_EHIP, STB_EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+STB_OK, STB_EINVAL, STB_ENULL, STB_EALIGN, STB_ENONFINITE, STB_EHIP, STB_EUNSUPPORTED, STB_ETOOBIG = 0, -1, -2, -3, -4, -5, -6, -7
+STB_GEMV_STATIC_SCRATCH_BYTES = 8 * 1024 * 1024
 
 
 class StbError(RuntimeError):
@@ -67,7 +68,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 _LIB = None
 
 EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
-           "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemv_batched_workspace_bytes", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_set_kernel_override", "stb_strerror", "stb_last_hip_error")
+           "stb_gemv_static", "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemv_batched_workspace_bytes", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_set_kernel_override", "stb_strerror", "stb_last_hip_error")
 
 
 def _lib():
@@ -103,6 +104,8 @@ def _lib():
     lib.stb_dequant.argtypes = [P(stb_layout_t), C.c_void_p, C.c_void_p]
     lib.stb_gemv.argtypes = [P(stb_layout_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                              C.c_int64, C.c_void_p]
+    lib.stb_gemv_static.argtypes = [P(stb_layout_t), C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.stb_gemv_static.restype = C.c_int
     lib.stb_gemv_workspace_bytes.argtypes = [P(stb_cfg_t), C.c_int32]
     lib.stb_gemv_workspace_bytes.restype = C.c_int64
     lib.stb_gemv_batched.argtypes = [C.c_int32, P(P(stb_layout_t)), P(C.c_void_p), C.c_int32,
@@ -271,6 +274,12 @@ def stb_gemv(layout_dev: stb_layout_t, x_dev, B: int, y_dev, y_fp32: bool = Fals
     _check(_lib().stb_gemv(C.byref(layout_dev), C.c_void_p(x_dev.data_ptr()), B,
                            C.c_void_p(y_dev.data_ptr()), int(y_fp32), ws_ptr, ws_bytes,
                            C.c_void_p(_stream_ptr(stream))), "stb_gemv")
+
+
+def stb_gemv_static(layout_dev: stb_layout_t, x_dev, B: int, y_dev, y_fp32: bool = False, stream=None) -> None:
+    _check(_lib().stb_gemv_static(C.byref(layout_dev), C.c_void_p(x_dev.data_ptr()), B,
+                                  C.c_void_p(y_dev.data_ptr()), int(y_fp32), C.c_void_p(_stream_ptr(stream))),
+           "stb_gemv_static")
 
 
 def stb_gemv_batched(layouts_dev: Sequence[stb_layout_t], xs_dev, B: int, ys_dev, y_fp32: bool = False,

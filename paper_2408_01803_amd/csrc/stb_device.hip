@@ -504,6 +504,52 @@ extern "C" int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void*
     return gemv_impl(dev, x, B, y, y_fp32, workspace, workspace_bytes, -1, stream);
 }
 
+// ------------------------------------------------------------------------------------------------
+// stb_gemv_static: the scratch lives in a device array of this library instead of a caller's buffer.
+// ------------------------------------------------------------------------------------------------
+// [0, STB_STATIC_COUNTER_BYTES): arrival counters (zero when the library is loaded; every call leaves them zero);
+// behind them the partial sums of the column splits (no initialisation needed).
+static __device__ __align__(256) unsigned char scratch[STB_GEMV_STATIC_SCRATCH_BYTES];
+constexpr int64_t STB_STATIC_COUNTER_BYTES = 65536;
+constexpr int STB_STATIC_MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[STB_STATIC_MAX_DEVICES] = {};   // the array's address on each device, once looked up
+
+// The device address of `scratch` on the current device (each GPU holds its own copy of the array).  The array's name
+// is a host-side handle: only the pointer that hipGetSymbolAddress returns may be given to a kernel.
+static int static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= STB_STATIC_MAX_DEVICES) return STB_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!ptr || (uintptr_t)ptr % 256) return STB_EALIGN;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return STB_OK;
+}
+
+extern "C" int stb_gemv_static(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32, void* stream) {
+    if (!dev) return STB_ENULL;
+    // the counters of ceil(n / 16) row tiles must fit their fixed area; the partial sums are checked by the launcher
+    // against what is left of the array (it knows how many column splits it takes)
+    if (dev->kind == STB_KIND_TILED && 4 * (int64_t)dev->n_row_tiles > STB_STATIC_COUNTER_BYTES) return STB_ETOOBIG;
+    void* ptr = nullptr;
+    int rc = static_scratch(&ptr);
+    if (rc) return rc;
+    rc = gemv_impl(dev, x, B, y, y_fp32, ptr, STB_GEMV_STATIC_SCRATCH_BYTES, STB_STATIC_COUNTER_BYTES, stream);
+    // the only size check a valid layout can fail with this buffer is the one on the partial sums
+    if (rc == STB_EINVAL && dev->kind == STB_KIND_TILED && stb_layout_check(dev) == STB_OK && x && y && B >= 1 &&
+        B <= STB_MAX_BATCH && (y_fp32 == 0 || y_fp32 == 1))
+        return STB_ETOOBIG;
+    return rc;
+}
+
 // Each layer of a batched call owns a slice of the workspace: its arrival counters, then its partial sums.
 static int64_t round_up256_(int64_t v) { return (v + 255) / 256 * 256; }
 static int64_t batched_slice(const stb_cfg_t* cfg, int32_t B, int64_t* counter_bytes) {

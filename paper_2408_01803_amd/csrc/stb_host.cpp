@@ -867,6 +867,7 @@ extern "C" const char* stb_strerror(int status) {
         case STB_ENONFINITE: return "NaN/Inf in W or xnorm, or negative xnorm";
         case STB_EHIP: return "HIP call failed (see stb_last_hip_error)";
         case STB_EUNSUPPORTED: return "no kernel for this configuration";
+        case STB_ETOOBIG: return "problem needs more scratch than the library's static device array holds";
         default: return "unknown status";
     }
 }
