@@ -69,13 +69,33 @@ def build_pool(S, torch, pm, pool_bytes, tiled=True, min_copies=2):
     return buf, layouts
 
 
-def timed(torch, fn, reps, warm=3, rounds=3):
+def timed(torch, fn, reps, warm=3, rounds=3, graph=False):
     """Median and fastest average time of fn() in microseconds over `rounds` runs of `reps` calls, events on the
-    current stream."""
+    stream the calls are launched on.  graph=True: the `reps` calls are captured once in a HIP graph and each run is
+    one replay (a launch through the Python binding costs the host more time than a short kernel runs)."""
     for _ in range(warm):
         fn(0)
     torch.cuda.synchronize()
     out = []
+    if graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for r in range(reps):
+                    fn(r)
+            g.replay()
+            side.synchronize()
+            for _ in range(rounds):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(side)
+                g.replay()
+                e1.record(side)
+                side.synchronize()
+                out.append(e0.elapsed_time(e1) * 1e3 / reps)
+        torch.cuda.current_stream().wait_stream(side)
+        return statistics.median(out), min(out)
     r = 0
     for _ in range(rounds):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -238,7 +258,8 @@ def main():
     torch.cuda.empty_cache()
 
     def decode_rows(cfg, spec, pm, batches):
-        """One row per batch: a single stb_gemv call per launch, rotating over copies of the layer."""
+        """One row per batch: a single stb_gemv call per launch, rotating over copies of the layer (30 launches in a
+        HIP graph, replayed)."""
         rows = []
         tiled = tiled_ok(spec)
         buf, layouts = build_pool(S, torch, pm, ROW_POOL_BYTES, tiled=tiled)
@@ -246,7 +267,7 @@ def main():
         for Bq in batches:
             x = torch.from_numpy(make_x(Bq, spec.k, spec.seed)).cuda()
             y = torch.empty((Bq, spec.n), dtype=torch.float16, device="cuda")
-            med, best = timed(torch, lambda r: S.stb_gemv(layouts[r % len(layouts)], x, Bq, y, False, wsl), 30)
+            med, best = timed(torch, lambda r: S.stb_gemv(layouts[r % len(layouts)], x, Bq, y, False, wsl), 30, graph=True)
             rows.append(dict(workload=cfg, layer=spec.name, n=spec.n, k=spec.k, nm=f"{spec.N}:{spec.M}", B=Bq,
                              us=round(med, 2), us_best=round(best, 2), packed_mb=round(pm.packed_bytes / 1e6, 2),
                              packed_gbs=round(pm.packed_bytes / med / 1e3, 1),
@@ -327,7 +348,7 @@ def main():
         for nbytes in (17_968_384, 93_585_408):
             stride = (nbytes + 255) // 256 * 256
             ncopy = (base.numel() - off0) // stride
-            med, best = timed(torch, lambda r: S.stb_probe_read(base[off0 + (r % ncopy) * stride:], nbytes, sink), 30)
+            med, best = timed(torch, lambda r: S.stb_probe_read(base[off0 + (r % ncopy) * stride:], nbytes, sink), 30, graph=True)
             roofs.append({"bytes": nbytes, "us": round(med, 2), "us_best": round(best, 2), "gbs": round(nbytes / med / 1e3, 1)})
         result["stream_read_roof"] = {"sizes": roofs, "note": "plain 128-bit-load read kernel, one launch per buffer, "
                                                               "same launch-to-launch timing as decode_rows"}

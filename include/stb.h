@@ -321,13 +321,16 @@ int stb_probe_mfma(int32_t kind, int32_t valu, int32_t steps, int32_t n_workgrou
  * values are process-wide; set them while no other thread is inside stb_gemv / stb_gemm).
  *   gemv_kernel  0 automatic; 1 the tiled kind uses its older decode kernel with thin wavefronts, which otherwise
  *                only runs when the LDS areas of the default kernel do not fit
- *   gemv_visits  0 automatic; 2 or 3: the default decode kernel takes that many superblocks per wavefront where the
- *                layer has as many (it chooses that by itself for wide layers at small batches)
+ *   gemv_visits  0 automatic; 1 .. 8: the default decode kernel takes that many superblocks per wavefront where the
+ *                layer has as many and its staging areas fit (it chooses that by itself for wide layers at small
+ *                batches)
+ *   gemv_splits  0 automatic; 1 .. 64: the default decode kernel cuts the columns into that many splits where such a
+ *                launch shape exists (otherwise the request is ignored)
  *   gemm_kernel  0 automatic; 1 keeps 2:4 layers on the dense-instruction prefill kernel (16x16x32 form); 2 runs any
  *                tiled layer on the 32x32x16 form of the dense kernel; 3 runs 2:4 layers on the 16x16x64 form of the
  *                sparse instruction
  * Errors: STB_EINVAL (a value outside the lists above; nothing is changed then). */
-int stb_set_kernel_override(int32_t gemv_kernel, int32_t gemv_visits, int32_t gemm_kernel);
+int stb_set_kernel_override(int32_t gemv_kernel, int32_t gemv_visits, int32_t gemv_splits, int32_t gemm_kernel);
 
 /* Text for a status code (static storage). */
 const char* stb_strerror(int status);

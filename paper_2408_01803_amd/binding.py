@@ -120,7 +120,7 @@ def _lib():
     lib.stb_probe_read.restype = C.c_int
     lib.stb_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
     lib.stb_probe_mfma.restype = C.c_int
-    lib.stb_set_kernel_override.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+    lib.stb_set_kernel_override.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     lib.stb_set_kernel_override.restype = C.c_int
     lib.stb_strerror.argtypes = [C.c_int]
     lib.stb_strerror.restype = C.c_char_p
@@ -329,8 +329,8 @@ def stb_probe_mfma(kind: int, valu: int, steps: int, n_workgroups: int, sink_dev
                                  C.c_void_p(_stream_ptr(stream))), "stb_probe_mfma")
 
 
-def stb_set_kernel_override(gemv_kernel: int = 0, gemv_visits: int = 0, gemm_kernel: int = 0) -> None:
-    _check(_lib().stb_set_kernel_override(gemv_kernel, gemv_visits, gemm_kernel), "stb_set_kernel_override")
+def stb_set_kernel_override(gemv_kernel: int = 0, gemv_visits: int = 0, gemv_splits: int = 0, gemm_kernel: int = 0) -> None:
+    _check(_lib().stb_set_kernel_override(gemv_kernel, gemv_visits, gemv_splits, gemm_kernel), "stb_set_kernel_override")
 
 
 GEMV_THIN = 1

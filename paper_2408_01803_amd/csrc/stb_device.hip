@@ -380,17 +380,18 @@ hipError_t launch_gemv_generic(const Planes& p, const void* x, void* y, int y_fp
 // ------------------------------------------------------------------------------------------------
 extern "C" int stb_last_hip_error(void) { return g_last_hip_error; }
 
-static std::atomic<int> g_override[3] = {{0}, {0}, {0}};
+static std::atomic<int> g_override[4] = {{0}, {0}, {0}, {0}};
 
-extern "C" int stb_kernel_override(int which) { return which >= 0 && which < 3 ? g_override[which].load(std::memory_order_relaxed) : 0; }
+extern "C" int stb_kernel_override(int which) { return which >= 0 && which < 4 ? g_override[which].load(std::memory_order_relaxed) : 0; }
 
-extern "C" int stb_set_kernel_override(int32_t gemv_kernel, int32_t gemv_visits, int32_t gemm_kernel) {
-    if (gemv_kernel < 0 || gemv_kernel > 1 || (gemv_visits != 0 && gemv_visits != 2 && gemv_visits != 3) ||
+extern "C" int stb_set_kernel_override(int32_t gemv_kernel, int32_t gemv_visits, int32_t gemv_splits, int32_t gemm_kernel) {
+    if (gemv_kernel < 0 || gemv_kernel > 1 || gemv_visits < 0 || gemv_visits > 8 || gemv_splits < 0 || gemv_splits > 64 ||
         gemm_kernel < 0 || gemm_kernel > 3)
         return STB_EINVAL;
     g_override[0].store(gemv_kernel, std::memory_order_relaxed);
     g_override[1].store(gemv_visits, std::memory_order_relaxed);
     g_override[2].store(gemm_kernel, std::memory_order_relaxed);
+    g_override[3].store(gemv_splits, std::memory_order_relaxed);
     return STB_OK;
 }
 

@@ -39,6 +39,7 @@ namespace {
 typedef _Float16 half16_t __attribute__((ext_vector_type(16)));
 
 constexpr int LDS24 = 160 * 1024 - 64; // dynamic LDS a workgroup may ask for (a few bytes are static)
+constexpr int MAXV24 = 8;             // most superblocks a wavefront visits per row tile
 constexpr int PHASE24 = 15;           // row tiles between two reductions (a multiple of 3: three tile buffers)
 
 // Packed operands of one (row, block): mask, sign and id words of the two half blocks, scales, alpha_r.
@@ -305,23 +306,17 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
     ResSel sel2[2];                                              // second record (half blocks with 9..16 salient columns)
     uint32_t xs2[2][4];
     int nch0 = 0, nch1 = 0;
-    // per visit: byte offsets of the res_sign words (half 0 low / high, half 1 low / high); separate variables and
-    // uniform branches, not an array indexed by the visit (that would live in scratch memory)
-    uint32_t ova[4] = {0u, 0u, 0u, 0u}, ovb[4] = {0u, 0u, 0u, 0u}, ovc[4] = {0u, 0u, 0u, 0u};
+    // byte offsets of the res_sign words (half 0 low / high, half 1 low / high) of the visit the fetches are at
+    uint32_t ovp[4] = {0u, 0u, 0u, 0u};
     Tile t0 = {}, t1 = {}, t2 = {};
     constexpr int LMAIN = TileOf<MODE>::lmain;
     constexpr int L = LMAIN + (HAS_RES ? LRES24 : 0);            // loads per tile in the streaming loop
-    auto fetch_res = [&](Tile& t, int rt, int v) {
-        if constexpr (HAS_RES) {
-            const int rtu = __builtin_amdgcn_readfirstlane(rt);
-            if (!MULTI || v == 0) fetch24_res(t, p, rtu, ova[0], ova[1], ova[2], ova[3]);  // v is uniform
-            else if (v == 1) fetch24_res(t, p, rtu, ovb[0], ovb[1], ovb[2], ovb[3]);
-            else fetch24_res(t, p, rtu, ovc[0], ovc[1], ovc[2], ovc[3]);
-        }
+    auto fetch_res = [&](Tile& t, int rt) {
+        if constexpr (HAS_RES) fetch24_res(t, p, __builtin_amdgcn_readfirstlane(rt), ovp[0], ovp[1], ovp[2], ovp[3]);
     };
     auto fetch_tile = [&](Tile& t, int rt, int v) {
         fetch24(t, p, tile_of(__builtin_amdgcn_readfirstlane(rt), __builtin_amdgcn_readfirstlane(v)), o8, o4, o2);
-        fetch_res(t, rt, v);
+        fetch_res(t, rt);
     };
     if (MULTI && active) {
         // ---- several visits: the slices of x and the record sets go from global memory straight to LDS (no staging
@@ -498,12 +493,33 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
             }
         }
     };
-    // producer side of the three tile buffers: the next (row tile, visit) to fetch, row tile first
-    int prt = r0, pv = 0;
+    // producer side of the three tile buffers.  Order of the products of a workgroup: phase by phase (PHT row tiles),
+    // inside a phase visit by visit, inside a visit row tile by row tile -- so that a wavefront takes the operands of a
+    // visit (64 registers of x, the gathered salient x) once per phase and visit, not once per product.
+    // the res_sign offsets of visit v, from its records in LDS (the tiles are fetched ahead of the visits' other operands)
+    auto res_offsets = [&](int v) {
+        const int ve = sb + v * SPS < p.nsb ? v : 0;
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const uint32_t ord = recs[ve * 192 + (g * 2 + h) * 24 + 4];
+            const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
+            const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
+            ovp[2 * h] = (uint32_t)(wa * 16 + i) * 4u;
+            ovp[2 * h + 1] = (uint32_t)(wb * 16 + i) * 4u;
+        }
+    };
+    int p_ph0 = r0, p_n = r1 - r0 < PHT ? r1 - r0 : PHT, p_i = 0, p_v = 0;
+    auto advance = [&]() {
+        if (++p_i == p_n) {
+            p_i = 0;
+            if (++p_v == V) { p_v = 0; p_ph0 += p_n; p_n = r1 - p_ph0 < PHT ? r1 - p_ph0 : PHT; }
+            if (MULTI && HAS_RES) res_offsets(p_v);
+        }
+    };
     auto fetch_next = [&](Tile& t) {
-        if (prt <= rl) {
-            fetch_tile(t, prt, pv);
-            if (++pv == V) { pv = 0; ++prt; }
+        if (p_n > 0) {
+            fetch_tile(t, p_ph0 + p_i, p_v);
+            advance();
         } else {
             fetch_tile(t, rl, V - 1);                // past the end: the last one again (same number of loads on every path)
         }
@@ -511,29 +527,15 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
     if (active) {
         if (!MULTI) {
             visit_setup(0);
-            ova[0] = inv[0].o0; ova[1] = inv[0].o1; ova[2] = inv[1].o0; ova[3] = inv[1].o1;
+            ovp[0] = inv[0].o0; ovp[1] = inv[0].o1; ovp[2] = inv[1].o0; ovp[3] = inv[1].o1;
         } else if (HAS_RES) {
-            // the res_sign offsets of every visit (the tiles are fetched ahead of the visits' other operands)
-            auto res_offsets = [&](int v, uint32_t (&o)[4]) {
-                const int ve = sb + v * SPS < p.nsb ? v : 0;
-#pragma unroll
-                for (int h = 0; h < 2; h++) {
-                    const uint32_t ord = recs[ve * 192 + (g * 2 + h) * 24 + 4];
-                    const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
-                    const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
-                    o[2 * h] = (uint32_t)(wa * 16 + i) * 4u;
-                    o[2 * h + 1] = (uint32_t)(wb * 16 + i) * 4u;
-                }
-            };
-            res_offsets(0, ova);
-            res_offsets(1, ovb);
-            if (V > 2) res_offsets(2, ovc);
+            res_offsets(0);
         }
         // with one visit the partial products overwrite the x rows: every read above must have returned
         __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
         __builtin_amdgcn_sched_barrier(0);
-        fetch_res(t0, clamp(r0), 0);
-        if (++pv == V) { pv = 0; ++prt; }            // t0 holds (r0, visit 0)
+        fetch_res(t0, clamp(r0));
+        if (p_n > 0) advance();                      // t0 holds (r0, visit 0)
         fetch_next(t1);
         fetch_next(t2);
     }
@@ -630,6 +632,13 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
         acc = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
     };
 
+    auto add_partial = [&](int slot) {
+        float* dst = part + (slot * 256 + lane);
+#pragma unroll
+        for (int v = 0; v < 4; v++) dst[64 * v] += acc[v];
+        acc = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    };
+
     // Half blocks with more than 16 salient columns: the records after the second, outside the streaming loop (rare).
     auto extra_records = [&](int rt, int v) {
         const int64_t rstride = (int64_t)p.res_words * 16;
@@ -675,22 +684,27 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
         const int ph0 = r0 + ph;
         const int ph1 = ph0 + PHT < r1 ? ph0 + PHT : r1;
         if (active) {
-            // consumer side of the three tile buffers: the (row tile, visit) of the next product.  A row tile's sum is
-            // stored after its last visit; a step past the phase's last tile only keeps the fetches going.
-            int crt = ph0, cv = 0;
+            // consumer side of the three tile buffers: the (visit, row tile) of the next product, in the producer's
+            // order.  The first visit stores a row tile's product, the others add theirs to it (LDS adds: the sum over
+            // the visits is taken in visit order, whatever the launch shape of other layers).  A step past the phase's
+            // last product only keeps the fetches going.
+            const int cn = ph1 - ph0;
+            int ci = 0, cv = cn > 0 ? 0 : V;
             auto step = [&](Tile& t) {
                 wait24_main<2 * L + (HAS_RES ? LRES24 : 0)>(t);
-                if (crt < ph1) {
+                if (cv < V) {
                     if (sb + cv * SPS < p.nsb) {
-                        if (MULTI) visit_setup(cv);
-                        product(t, crt, crt - ph0);
-                        if (MULTI && HAS_RES && (nch0 > 2 || nch1 > 2)) acc += extra_records(crt, cv);
+                        if (MULTI && ci == 0) visit_setup(cv);
+                        product(t, ph0 + ci, ci);
+                        if (MULTI && HAS_RES && (nch0 > 2 || nch1 > 2)) acc += extra_records(ph0 + ci, cv);
+                        if (!MULTI || cv == 0) store_partial(ci);
+                        else add_partial(ci);
                     }
-                    if (++cv == V) { store_partial(crt - ph0); cv = 0; ++crt; }
+                    if (++ci == cn) { ci = 0; ++cv; }
                 }
                 fetch_next(t);
             };
-            while (crt < ph1) {
+            while (cv < V) {
                 step(t0);
                 step(t1);
                 step(t2);
@@ -819,25 +833,28 @@ extern "C" int stb_tiled_meta_index(const stb_layout_t* L, void* E, void* stream
 extern "C" int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_splits, int* out) {
     if (nrt < 1 || nsb < 1 || B < 1 || B > 16 || (mode != 2 && mode != 4 && mode != 6) || !out) return STB_EUNSUPPORTED;
     const int64_t lds_max = LDS24 - (mode == 2 ? 0 : 32768);
-    // Column splits of SPS <= 8 wavefronts; a wavefront takes V superblocks (V = 1: its own; V = 2, 3: it visits
-    // them one after the other for every row tile); a workgroup owns R row tiles.  Among the shapes whose LDS fits,
-    // take the one with the lowest estimated time, in ns: per (row tile, superblock) product ~750 on the sparse
-    // instruction, ~1000 on the dense one, ~200 more when the operands of a visit have to be taken from LDS first;
+    // Column splits of SPS <= 8 wavefronts; a wavefront takes V superblocks (V = 1: its own; V = 2 .. 8: it visits
+    // them one after the other, each visit over all row tiles of a phase); a workgroup owns R row tiles.  Among the
+    // shapes whose LDS fits, take the one with the lowest estimated time, in ns: per (row tile, superblock) product
+    // ~750 on the sparse instruction, ~1000 on the dense one; ~800 per visit for taking its operands from LDS;
     // R * V products for each of the ceil(SPS / 4) wavefronts of a SIMD, times the rounds the grid needs on 256
-    // compute units; adding the column splits up through the workspace costs ~2000 plus ~90 per split and batch
+    // compute units; adding the column splits up through the workspace costs ~3000 plus ~90 per split and batch
     // row.  Ties go to the fewest splits.
     // LDS of one wavefront: per visit the x rows (B rows and one of zeros, 1040 bytes each) and 16 records; the PHT
     // partial tiles lie on top of the x rows when there is one visit, behind everything otherwise.
     const int xbytes = (B < 16 ? B + 1 : 16) * 1040;
     int S = 0, R = 0, SPS = 0, V = 0, wreg = 0, rec_off = 0, part_off = 0;
     int64_t best_cost = 0;
-    // stb_set_kernel_override can restrict the choice to 2 or 3 visits where such a shape exists: the tests use it,
+    // stb_set_kernel_override can restrict the choice to a number of visits where such a shape exists: the tests use it,
     // because small layers never choose several visits themselves.
-    const int asked = stb_kernel_override(1);
-    const int v_only = (asked == 2 || asked == 3) && nsb >= asked ? asked : 0;
-    for (int v = 1; v <= 3; v++) {
-        if (v_only && v != v_only) continue;
+    const int asked = stb_kernel_override(1), asked_s = stb_kernel_override(3);
+    const int v_only = asked >= 1 && asked <= MAXV24 && nsb >= asked ? asked : 0;
+    const int s_only = asked_s >= 1 && asked_s <= max_splits && asked_s * (v_only ? v_only : 1) <= nsb ? asked_s : 0;
+    for (int pass = 0; pass < 2 && S == 0; pass++)             // second pass: a forced shape that does not exist is ignored
+    for (int v = 1; v <= MAXV24; v++) {
+        if (pass == 0 && v_only && v != v_only) continue;
         for (int s = (nsb + 8 * v - 1) / (8 * v); s <= max_splits && s * v <= nsb; s++) {
+            if (pass == 0 && s_only && s != s_only) continue;
             const int sps = (nsb + s * v - 1) / (s * v);
             if (sps > 8 || (s - 1) * sps * v >= nsb) continue;   // a split must own at least one superblock
             if ((s * v - 1) * sps >= nsb) continue;              // ... and so must the last visit of the last split
@@ -852,8 +869,12 @@ extern "C" int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_
                 ro = v * xbytes; po = ro + v * 768; w = po + pht * 1024;
             }
             if ((int64_t)sps * w > lds_max) continue;
-            const int64_t cost = (int64_t)((mode == 2 ? 750 : 1000) + (v > 1 ? 200 : 0)) * r * v * ((sps + 3) / 4) * ((g * s + 255) / 256)
-                                 + (s > 1 ? 2000 + (int64_t)90 * s * B : 0);
+            const int phases = (r + pht - 1) / pht;
+            // two wavefronts of a SIMD take turns at its issue port; a lone one leaves it idle while it waits (measured:
+            // 1.45 times the time per product)
+            const int64_t per_wave = (int64_t)(mode == 2 ? 750 : 1000) * r * v + (v > 1 ? (int64_t)800 * v * phases : 0);
+            const int64_t per_simd = sps <= 4 ? per_wave * 29 / 20 : per_wave * ((sps + 3) / 4);
+            const int64_t cost = per_simd * ((g * s + 255) / 256) + (s > 1 ? 3000 + (int64_t)90 * s * B : 0);
             if (S == 0 || cost < best_cost) { best_cost = cost; S = s; R = r; SPS = sps; V = v; wreg = w; rec_off = ro; part_off = po; }
         }
     }

@@ -7,8 +7,8 @@
 extern "C" {
 #endif
 // The kernel choices forced by stb_set_kernel_override (stb_device.hip): which = 0 decode kernel (0 automatic,
-// 1 thin wavefronts), 1 superblock visits per wavefront of the decode kernel (0 automatic, 2, 3), 2 prefill kernel
-// (0 automatic, 1 dense 16x16x32, 2 dense 32x32x16, 3 sparse 16x16x64).
+// 1 thin wavefronts), 1 superblock visits per wavefront of the decode kernel (0 automatic, 1 .. 8), 2 prefill kernel
+// (0 automatic, 1 dense 16x16x32, 2 dense 32x32x16, 3 sparse 16x16x64), 3 column splits of the decode kernel (0 automatic).
 int stb_kernel_override(int which);
 
 // STB_OK iff the size fields agree with the closed form for L->cfg and every required plane pointer is

@@ -37,13 +37,13 @@ def torch_cuda():
 
 
 @contextlib.contextmanager
-def forced(gemv_kernel=0, gemv_visits=0, gemm_kernel=0):
+def forced(gemv_kernel=0, gemv_visits=0, gemv_splits=0, gemm_kernel=0):
     """Kernels that ordinary shapes would not reach, asked for through the library's test hook."""
-    S.stb_set_kernel_override(gemv_kernel, gemv_visits, gemm_kernel)
+    S.stb_set_kernel_override(gemv_kernel, gemv_visits, gemv_splits, gemm_kernel)
     try:
         yield
     finally:
-        S.stb_set_kernel_override(0, 0, 0)
+        S.stb_set_kernel_override(0, 0, 0, 0)
 
 
 GEMM_KERNELS = {"dense": S.GEMM_DENSE, "dense32": S.GEMM_DENSE32, "sparse16": S.GEMM_SPARSE16}
@@ -179,7 +179,7 @@ def test_gemv_small(small_case, torch_cuda, B, y_fp32):
             torch.cuda.synchronize()
         _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemv B={B} (thin-wavefront kernel)")
         # ... and small layers never choose several superblock visits per wavefront themselves
-        for visits in (2, 3):
+        for visits in (2, 3, 5, 8):
             if (c["k"] + 511) // 512 < visits or B > 16:
                 continue
             yd.fill_(float("nan"))
@@ -396,7 +396,7 @@ def test_random_shapes_through_every_kernel(seed, torch_cuda):
             y_ref, bound = O.matmul(x, What)
             xd = torch.from_numpy(x).cuda()
             asks = [{}, dict(gemv_kernel=S.GEMV_THIN)]
-            asks += [dict(gemv_visits=v) for v in (2, 3) if (k + 511) // 512 >= v and B <= 16]
+            asks += [dict(gemv_visits=v) for v in (2, 3, 4, 7) if (k + 511) // 512 >= v and B <= 16]
             for hook in asks:
                 yd = torch.full((B, n), float("nan"), dtype=torch.float16, device="cuda")
                 _say(f"[step] stb_gemv B={B} {hook}")

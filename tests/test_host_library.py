@@ -244,7 +244,7 @@ def test_decode_launch_plan_invariants():
                         continue
                     Sn, R, SPS, V, wreg, rec_off, part_off = list(out)
                     what = (mode, nsb, nrt, B, list(out))
-                    assert 1 <= SPS <= 8 and 1 <= V <= 3 and 1 <= Sn <= max_splits and R >= 1, what
+                    assert 1 <= SPS <= 8 and 1 <= V <= 8 and 1 <= Sn <= max_splits and R >= 1, what
                     assert Sn * SPS * V >= nsb, what                      # every superblock has a wavefront and a visit
                     assert (Sn - 1) * SPS * V < nsb, what                 # no empty split
                     assert (Sn * V - 1) * SPS < nsb, what                 # no empty last visit
