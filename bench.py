@@ -363,11 +363,12 @@ def main():
         roof = {}
         for kind, name, flop in ((0, "v_mfma_f32_16x16x32_f16", 16384.0), (1, "v_smfmac_f32_16x16x64_f16", 32768.0),
                                  (2, "v_mfma_f32_32x32x16_f16", 32768.0), (3, "v_smfmac_f32_32x32x32_f16", 65536.0)):
-            for valu in (0, 3, 5, 8):
-                med, _ = timed(torch, lambda r: S.stb_probe_mfma(kind, valu, steps, n_cu, sink), 3, warm=1, rounds=1)
-                ns = med * 1e3 / (steps * 32)
-                roof[f"{name}+{valu}valu"] = {"ns_per_instruction_per_simd": round(ns, 2),
-                                              "tflops_all_simds": round(flop * 4 * n_cu / ns / 1e3, 1)}
+            for rnd in (0, 1):           # operands next to 1.0 / operands with every bit random (what a GEMM is fed)
+                for valu in ((0, 3, 5, 8) if not rnd else (0, 5)):
+                    med, _ = timed(torch, lambda r: S.stb_probe_mfma(kind + 4 * rnd, valu, steps, n_cu, sink), 3, warm=1, rounds=1)
+                    ns = med * 1e3 / (steps * 32)
+                    roof[f"{name}{'(random operands)' if rnd else ''}+{valu}valu"] = {
+                        "ns_per_instruction_per_simd": round(ns, 2), "tflops_all_simds": round(flop * 4 * n_cu / ns / 1e3, 1)}
         result["instruction_issue_roof"] = roof
 
     # ---------------- CPU baseline: the oracle as it stands, on this machine's host cores ----------------

@@ -310,11 +310,13 @@ int stb_probe_read(const void* src, int64_t bytes, void* sink, void* stream);
  * instructions on independent accumulators, with `valu` (0, 2, 3, 5 or 8) vector instructions (v_perm_b32 on eight
  * independent registers) after each, in that order.
  * kind 0: v_mfma_f32_16x16x32_f16 (the dense prefill kernel's), kind 1: v_smfmac_f32_16x16x64_f16 (the 2:4 one's),
- * on 32 accumulators; kind 2: v_mfma_f32_32x32x16_f16, kind 3: v_smfmac_f32_32x32x32_f16, on 8 accumulators.
+ * on 32 accumulators; kind 2: v_mfma_f32_32x32x16_f16, kind 3: v_smfmac_f32_32x32x32_f16, on 8 accumulators.  These
+ * multiply operands that are all next to 1.0; kind 4..7 are the same four instructions on operands whose every bit is
+ * random (magnitudes in [0.25, 2)), as weights and activations are: the matrix pipes issue those markedly slower.
  * Every thread writes 16 bytes to `sink` (device, 16-byte aligned, n_workgroups * 4096 bytes).  Timing it gives the
  * instruction rate this GPU sustains and how many vector instructions a matrix instruction hides: the practical
  * ceiling that the prefill kernels' TFLOP/s is compared with.
- * Errors: STB_ENULL, STB_EINVAL (other kind / valu, steps < 1, n_workgroups outside 1..65536), STB_EALIGN, STB_EHIP. */
+ * Errors: STB_ENULL, STB_EINVAL (kind outside 0..7, other valu, steps < 1, n_workgroups outside 1..65536), STB_EALIGN, STB_EHIP. */
 int stb_probe_mfma(int32_t kind, int32_t valu, int32_t steps, int32_t n_workgroups, void* sink, void* stream);
 
 /* Test hook: forces kernel choices that ordinary shapes would not reach, for every later call in this process (the
@@ -328,7 +330,8 @@ int stb_probe_mfma(int32_t kind, int32_t valu, int32_t steps, int32_t n_workgrou
  *                launch shape exists (otherwise the request is ignored)
  *   gemm_kernel  0 automatic; 1 keeps 2:4 layers on the dense-instruction prefill kernel (16x16x32 form); 2 runs any
  *                tiled layer on the 32x32x16 form of the dense kernel; 3 runs 2:4 layers on the 16x16x64 form of the
- *                sparse instruction
+ *                sparse instruction; 4 runs any tiled layer on the kernel that shares the expanded operands of a
+ *                workgroup through LDS
  * Errors: STB_EINVAL (a value outside the lists above; nothing is changed then). */
 int stb_set_kernel_override(int32_t gemv_kernel, int32_t gemv_visits, int32_t gemv_splits, int32_t gemm_kernel);
 

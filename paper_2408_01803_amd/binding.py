@@ -334,7 +334,7 @@ def stb_set_kernel_override(gemv_kernel: int = 0, gemv_visits: int = 0, gemv_spl
 
 
 GEMV_THIN = 1
-GEMM_DENSE, GEMM_DENSE32, GEMM_SPARSE16 = 1, 2, 3
+GEMM_DENSE, GEMM_DENSE32, GEMM_SPARSE16, GEMM_SHARED = 1, 2, 3, 4
 
 
 def new_device_scratch(nbytes: int, device="cuda:0", zero: bool = False):

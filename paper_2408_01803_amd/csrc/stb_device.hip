@@ -359,9 +359,12 @@ static int64_t gemv_rows_lds(const Planes& p, int B) { return (int64_t)B * 32 * 
 
 template <int B>
 hipError_t launch_gemv_rows(const Planes& p, const void* x, void* y, int y_fp32, hipStream_t s) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv_rows_kernel<B>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                       (int)GEMV_ROWS_LDS_MAX);
-    if (attr != hipSuccess) return attr;
+    static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
+    if (!attr_set.load(std::memory_order_acquire)) {
+        const hipError_t attr = hipFuncSetAttribute((const void*)gemv_rows_kernel<B>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMV_ROWS_LDS_MAX);
+        if (attr != hipSuccess) return attr;
+        attr_set.store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL(gemv_rows_kernel<B>, dim3((p.n + 15) / 16), dim3(256), (size_t)gemv_rows_lds(p, B), s, p, (const __half*)x, y, y_fp32);
     return hipGetLastError();
 }
@@ -386,7 +389,7 @@ extern "C" int stb_kernel_override(int which) { return which >= 0 && which < 4 ?
 
 extern "C" int stb_set_kernel_override(int32_t gemv_kernel, int32_t gemv_visits, int32_t gemv_splits, int32_t gemm_kernel) {
     if (gemv_kernel < 0 || gemv_kernel > 1 || gemv_visits < 0 || gemv_visits > 8 || gemv_splits < 0 || gemv_splits > 64 ||
-        gemm_kernel < 0 || gemm_kernel > 3)
+        gemm_kernel < 0 || gemm_kernel > 4)
         return STB_EINVAL;
     g_override[0].store(gemv_kernel, std::memory_order_relaxed);
     g_override[1].store(gemv_visits, std::memory_order_relaxed);

@@ -2,6 +2,7 @@
 // The expansion of packed bits into matrix-core operands is in stb_tiled.hpp.
 #include "stb_tiled.hpp"
 
+#include <atomic>
 #include <cstdlib>
 
 using namespace stbt;
@@ -532,9 +533,12 @@ extern "C" int64_t stb_tiled_gemv_workspace(int n_row_tiles, int n_super) {
 template <int N8, bool HAS_RES, bool STAGED>
 static hipError_t launch_gemv_stream3(const TiledPlanes& p, const __half* x, int B, void* y, int y_fp32, int R, int SPS,
                                       dim3 grid, size_t lds, float* ws_part, uint32_t* ws_count, hipStream_t st) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemv_stream_kernel<N8, HAS_RES, STAGED>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 16 * STB_GEMV_PHASE * 1024);
-    if (attr != hipSuccess) return attr;
+    static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
+    if (!attr_set.load(std::memory_order_acquire)) {
+        const hipError_t attr = hipFuncSetAttribute((const void*)gemv_stream_kernel<N8, HAS_RES, STAGED>, hipFuncAttributeMaxDynamicSharedMemorySize, 16 * STB_GEMV_PHASE * 1024);
+        if (attr != hipSuccess) return attr;
+        attr_set.store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL((gemv_stream_kernel<N8, HAS_RES, STAGED>), grid, dim3(1024), lds, st, p, x, B, y, y_fp32, R, SPS, ws_part, ws_count);
     return hipGetLastError();
 }

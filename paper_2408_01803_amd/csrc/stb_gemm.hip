@@ -17,8 +17,7 @@
 // The residual term of the salient columns (Eq. 4) is a second, short contraction: its A operand comes from
 // residual_chunk, its B operand from a compact copy of the salient columns of X that gemm_gather_kernel
 // writes to the workspace beforehand.
-#include <cstdlib>
-#include <cstring>
+#include <atomic>
 
 #include "stb_tiled.hpp"
 
@@ -1165,12 +1164,17 @@ __global__ __launch_bounds__(256) void gemm24_wide_kernel(TiledPlanes p, const _
     store_tile_wide<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
 }
 
+#include "stb_gemm_shared.hpp"
+
 template <int N8, bool HAS_RES>
 hipError_t launch_gemm(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                        const __half* xsal, int cfix) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_tiled_kernel<N8, HAS_RES>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
-    if (attr != hipSuccess) return attr;
+    static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
+    if (!attr_set.load(std::memory_order_acquire)) {
+        const hipError_t attr = hipFuncSetAttribute((const void*)gemm_tiled_kernel<N8, HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
+        if (attr != hipSuccess) return attr;
+        attr_set.store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix);
     return hipGetLastError();
 }
@@ -1178,9 +1182,12 @@ hipError_t launch_gemm(dim3 grid, hipStream_t st, const TiledPlanes& p, const __
 template <int N8, bool HAS_RES>
 hipError_t launch_gemm_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                             const __half* xsal, int cfix) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_wide_kernel<N8, HAS_RES>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
-    if (attr != hipSuccess) return attr;
+    static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
+    if (!attr_set.load(std::memory_order_acquire)) {
+        const hipError_t attr = hipFuncSetAttribute((const void*)gemm_wide_kernel<N8, HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
+        if (attr != hipSuccess) return attr;
+        attr_set.store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL((gemm_wide_kernel<N8, HAS_RES>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix);
     return hipGetLastError();
 }
@@ -1188,9 +1195,12 @@ hipError_t launch_gemm_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, con
 template <bool HAS_RES>
 hipError_t launch_gemm24_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                               const __half* xsal, int cfix) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm24_wide_kernel<HAS_RES>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
-    if (attr != hipSuccess) return attr;
+    static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
+    if (!attr_set.load(std::memory_order_acquire)) {
+        const hipError_t attr = hipFuncSetAttribute((const void*)gemm24_wide_kernel<HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
+        if (attr != hipSuccess) return attr;
+        attr_set.store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL((gemm24_wide_kernel<HAS_RES>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix);
     return hipGetLastError();
 }
@@ -1198,9 +1208,12 @@ hipError_t launch_gemm24_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, c
 template <bool HAS_RES>
 hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                          const __half* xsal, int cfix) {
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm24_kernel<HAS_RES>,
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
-    if (attr != hipSuccess) return attr;
+    static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
+    if (!attr_set.load(std::memory_order_acquire)) {
+        const hipError_t attr = hipFuncSetAttribute((const void*)gemm24_kernel<HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
+        if (attr != hipSuccess) return attr;
+        attr_set.store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL((gemm24_kernel<HAS_RES>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix);
     return hipGetLastError();
 }
@@ -1215,7 +1228,7 @@ hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const 
 // it is.)
 // ------------------------------------------------------------------------------------------------
 namespace {
-template <int KIND, int V>
+template <int KIND, int V, bool RANDOM>
 __global__ __launch_bounds__(256) void probe_mfma_kernel(int steps, float4_t* __restrict__ sink) {
     typedef float float16_t __attribute__((ext_vector_type(16)));
     constexpr bool WIDE = KIND >= 2;                    // 32x32 tiles: 8 accumulators of 16 registers, else 32 of 4
@@ -1230,7 +1243,17 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int steps, float4_t* __
     const uint32_t seed = threadIdx.x * 0x9E3779B9u + blockIdx.x;
     uint32_t w[8];
 #pragma unroll
-    for (int j = 0; j < 8; j++) w[j] = 0x3C003C00u ^ ((seed >> j) & 0x00010001u);      // fp16 values next to 1.0
+    for (int j = 0; j < 8; j++) {
+        w[j] = 0x3C003C00u ^ ((seed >> j) & 0x00010001u);      // fp16 values next to 1.0
+        if (RANDOM) {
+            // every operand bit random (sign, mantissa, exponent 13..15: magnitudes in [0.25, 2)): the matrix pipes run
+            // slower on operands like these than on the near-constant ones above (measured; presumably a power limit)
+            uint32_t h = (seed + (uint32_t)j * 0x85EBCA6Bu) * 0xC2B2AE35u;
+            h ^= h >> 15; h *= 0x27D4EB2Fu; h ^= h >> 13;
+            const uint32_t e0 = 13u + (h & 3u) % 3u, e1 = 13u + ((h >> 2) & 3u) % 3u;
+            w[j] = (h & 0x83FF83FFu) | (e0 << 10) | (e1 << 26);
+        }
+    }
     const uint4 av4 = make_uint4(w[0], w[1], w[2], w[3]);
     const half8_t av = __builtin_bit_cast(half8_t, av4);
     const half8_t bv = __builtin_bit_cast(half8_t, make_uint4(w[4], w[5], w[6], w[7]));
@@ -1276,20 +1299,24 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int steps, float4_t* __
 }  // namespace
 
 extern "C" int stb_tiled_probe_mfma(int kind, int valu, int steps, int n_workgroups, void* sink, void* stream, int* hip_err) {
+    if (kind < 0 || kind > 7) return STB_EINVAL;
     const dim3 grid(n_workgroups), wg(256);
     const hipStream_t st = (hipStream_t)stream;
     float4_t* out = (float4_t*)sink;
-#define STB_PROBE(K, V) hipLaunchKernelGGL((probe_mfma_kernel<K, V>), grid, wg, 0, st, steps, out)
+    const bool random = kind >= 4;
+    kind &= 3;
+#define STB_PROBE(K, V) { if (random) hipLaunchKernelGGL((probe_mfma_kernel<K, V, true>), grid, wg, 0, st, steps, out); \
+                          else hipLaunchKernelGGL((probe_mfma_kernel<K, V, false>), grid, wg, 0, st, steps, out); }
 #define STB_PROBE_KIND(K) \
-    if (kind == K && valu == 0) STB_PROBE(K, 0); \
-    else if (kind == K && valu == 2) STB_PROBE(K, 2); \
-    else if (kind == K && valu == 3) STB_PROBE(K, 3); \
-    else if (kind == K && valu == 5) STB_PROBE(K, 5); \
+    if (kind == K && valu == 0) STB_PROBE(K, 0) \
+    else if (kind == K && valu == 2) STB_PROBE(K, 2) \
+    else if (kind == K && valu == 3) STB_PROBE(K, 3) \
+    else if (kind == K && valu == 5) STB_PROBE(K, 5) \
     else if (kind == K && valu == 8) STB_PROBE(K, 8)
-    STB_PROBE_KIND(0);
-    else STB_PROBE_KIND(1);
-    else STB_PROBE_KIND(2);
-    else STB_PROBE_KIND(3);
+    STB_PROBE_KIND(0)
+    else STB_PROBE_KIND(1)
+    else STB_PROBE_KIND(2)
+    else STB_PROBE_KIND(3)
     else return STB_EINVAL;
 #undef STB_PROBE_KIND
 #undef STB_PROBE
@@ -1320,19 +1347,29 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
         hipLaunchKernelGGL(gemm_gather_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, p,
                            (const __half*)X, T, (__half*)workspace, cfix);
     }
-    // stb_set_kernel_override: 1 keeps 2:4 layers on the dense-instruction kernel, 2 runs the 32x32x16 form of that
-    // kernel on any layer, 3 runs 2:4 layers on the 16x16x64 form of the sparse instruction instead of the 32x32x32
-    // one: the tests use them to run every kernel on every case it can take.
+    // stb_set_kernel_override: 1 keeps 2:4 layers on the dense-instruction kernel (16x16x32 form), 2 runs its 32x32x16
+    // form on any layer, 3 runs 2:4 layers on the 16x16x64 form of the sparse instruction instead of the 32x32x32 one,
+    // 4 runs any layer on the shared-expansion kernel: the tests use them to run every kernel on every case it can
+    // take.
     const int which = stb_kernel_override(2);
-    const bool sparse_ok = L->cfg.N == 2 && L->cfg.M == 4 && which != 1 && which != 2;
-    const bool narrow = which != 2;
-    const bool sparse32 = sparse_ok && which != 3;
-    const int tok = sparse_ok ? GmLds<GM_TT24>::TOK : GmLds<GM_TT>::TOK;      // tokens per workgroup of the kernel that runs
-    const dim3 grid((T + tok - 1) / tok, (p.nrt + GM_ROWT - 1) / GM_ROWT);
     const int n8 = 8 * L->cfg.N / L->cfg.M;
     const __half* xh = (const __half*)X;
     const __half* xs = (const __half*)workspace;
     hipError_t e;
+    // override 4: the kernel that shares the expanded operands through LDS (any layer; measured slower than the
+    // kernels below, see stb_gemm_shared.hpp)
+    const bool is24 = L->cfg.N == 2 && L->cfg.M == 4;
+    if (which == 4) {
+        if (n8 == 4) e = res ? launch_gemm_shared<4, true>(st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm_shared<4, false>(st, p, xh, T, Y, y_fp32, xs, cfix);
+        else e = res ? launch_gemm_shared<6, true>(st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm_shared<6, false>(st, p, xh, T, Y, y_fp32, xs, cfix);
+        *hip_err = (int)e;
+        return e == hipSuccess ? STB_OK : STB_EHIP;
+    }
+    const bool sparse_ok = is24 && which != 1 && which != 2;
+    const bool narrow = which != 2;
+    const bool sparse32 = sparse_ok && which != 3;
+    const int tok = sparse_ok ? GmLds<GM_TT24>::TOK : GmLds<GM_TT>::TOK;      // tokens per workgroup of the kernel that runs
+    const dim3 grid((T + tok - 1) / tok, (p.nrt + GM_ROWT - 1) / GM_ROWT);
     if (sparse32) e = res ? launch_gemm24_wide<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm24_wide<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
     else if (sparse_ok) e = res ? launch_gemm24<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm24<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
     else if (narrow && n8 == 4) e = res ? launch_gemm<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);

@@ -46,7 +46,7 @@ def forced(gemv_kernel=0, gemv_visits=0, gemv_splits=0, gemm_kernel=0):
         S.stb_set_kernel_override(0, 0, 0, 0)
 
 
-GEMM_KERNELS = {"dense": S.GEMM_DENSE, "dense32": S.GEMM_DENSE32, "sparse16": S.GEMM_SPARSE16}
+GEMM_KERNELS = {"dense": S.GEMM_DENSE, "dense32": S.GEMM_DENSE32, "sparse16": S.GEMM_SPARSE16, "shared": S.GEMM_SHARED}
 
 
 def _within_bound(y_gpu, y_ref, bound, what):
@@ -204,11 +204,12 @@ def test_gemm_small(small_case, torch_cuda, T):
         torch.cuda.synchronize()
         _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T}")
         # The library picks one kernel per tiled layer (2:4: the sparse matrix instruction 32x32x32; otherwise the dense
-        # 16x16x32 one); the others that can take the layer (the other form of each, the dense ones on 2:4 layers) are
-        # asked for through the test hook.
+        # 16x16x32 one); the others that can take the layer (the 32x32x16 form, the kernel that shares the expanded
+        # operands through LDS, the dense one and the other sparse form on 2:4 layers) are asked for through the test
+        # hook.
         others = []
         if c["tiled"]:
-            others.append("dense32")
+            others += ["dense32", "shared"]
             if (c["N"], c["M"]) == (2, 4):
                 others += ["dense", "sparse16"]
         for which in others:
@@ -240,14 +241,14 @@ def test_zero_activations_and_zero_weights(torch_cuda):
 def test_probe_mfma_runs_and_rejects_bad_arguments(torch_cuda):
     torch = torch_cuda
     sink = torch.zeros(4 * 4096, dtype=torch.uint8, device="cuda")
-    for kind in (0, 1, 2, 3):
+    for kind in range(8):
         for valu in (0, 2, 3, 5, 8):
             S.stb_probe_mfma(kind, valu, 3, 4, sink)
     torch.cuda.synchronize()
-    # fp16 operands next to 1.0 on zeroed accumulators: every sum is finite and positive
+    # (the last launch, random operands of magnitude below 2 on zeroed accumulators: every sum is finite)
     out = sink.view(torch.float32).cpu().numpy()
-    assert np.isfinite(out).all() and (out > 0).all()
-    for bad in ((4, 0, 3, 4), (-1, 0, 3, 4), (0, 1, 3, 4), (2, 4, 3, 4), (0, 0, 0, 4), (0, 0, 3, 0)):
+    assert np.isfinite(out).all()
+    for bad in ((8, 0, 3, 4), (-1, 0, 3, 4), (0, 1, 3, 4), (2, 4, 3, 4), (0, 0, 0, 4), (0, 0, 3, 0)):
         with pytest.raises(S.StbError) as e:
             S.stb_probe_mfma(*bad, sink)
         assert e.value.status == S.STB_EINVAL
@@ -406,7 +407,7 @@ def test_random_shapes_through_every_kernel(seed, torch_cuda):
             x = make_x(T, k, lseed + 1000 + T)
             y_ref, bound = O.matmul(x, What)
             xd = torch.from_numpy(x).cuda()
-            for value in [None, "dense32"] + (["dense", "sparse16"] if (N, M) == (2, 4) else []):
+            for value in [None, "dense32", "shared"] + (["dense", "sparse16"] if (N, M) == (2, 4) else []):
                 yd = torch.full((T, n), float("nan"), dtype=torch.float16, device="cuda")
                 _say(f"[step] stb_gemm T={T} kernel asked for: {value}")
                 run(dict(gemm_kernel=GEMM_KERNELS[value]) if value else {},
@@ -519,10 +520,25 @@ def test_full_size_layer(cfg, idx, torch_cuda):
         torch.cuda.synchronize()
         worst = _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"{key} gemv B={B}")
         _say(f"       worst error / bound = {worst:.2e}")
+        if tiled and (cfg, idx) in ((2, 1), (5, 4), (3, 2)) and B <= 16:
+            # the decode kernels and launch shapes that the library does not pick for this layer, at full size: the
+            # thin-wavefront kernel, several superblock visits per wavefront, other numbers of column splits
+            nsb = (spec.k + 511) // 512
+            hooks = [dict(gemv_kernel=S.GEMV_THIN)] + [dict(gemv_visits=v) for v in (2, 3, 5) if v <= nsb]
+            hooks += [dict(gemv_visits=1, gemv_splits=sp) for sp in (2, 4, 7) if sp <= nsb]
+            for hook in hooks:
+                yd.fill_(float("nan"))
+                with forced(**hook):
+                    S.stb_gemv(pm.dev_layout, xd, B, yd, False, pm.workspace)
+                    torch.cuda.synchronize()
+                worst = _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"{key} gemv B={B} {hook}")
+                _say(f"       {hook}: worst error / bound = {worst:.2e}")
     for T in wl["prefill_tokens"]:
         x = make_x(T, spec.k, spec.seed)
+        # one token out of every tile of 16 (every workgroup and every matrix-instruction tile of every prefill kernel
+        # is compared), plus the edges
         rng = np.random.default_rng(spec.seed + T)
-        rows = np.unique(np.concatenate([[0, 1, 63, 64, T - 65, T - 2, T - 1], rng.integers(0, T, 57)]))
+        rows = np.unique(np.concatenate([[0, 1, 63, 64, T - 65, T - 2, T - 1], 16 * np.arange(T // 16) + rng.integers(0, 16, T // 16)]))
         x64 = x[rows].astype(np.float64)
         y_ref, bound = x64 @ W64.T, np.abs(x64) @ A64.T
         xd = torch.from_numpy(x).cuda()
@@ -540,7 +556,7 @@ def test_full_size_layer(cfg, idx, torch_cuda):
             _say(f"       {which}: worst error / bound on {len(rows)} sampled tokens = {worst:.2e}")
         if tiled:
             # the prefill kernels that the library does not pick by itself, on the same tokens
-            for asked in ["dense32"] + (["sparse16", "dense"] if (spec.N, spec.M) == (2, 4) else []):
+            for asked in ["dense32", "shared"] + (["dense", "sparse16"] if (spec.N, spec.M) == (2, 4) else []):
                 yd.fill_(float("nan"))
                 with forced(gemm_kernel=GEMM_KERNELS[asked]):
                     S.stb_gemm(pm.dev_layout, xd, T, yd, False, pm.new_gemm_workspace(T))
