@@ -263,8 +263,10 @@ int64_t stb_gemv_workspace_bytes(const stb_cfg_t* cfg, int32_t B);
  * N), and a single layer of a few tens of MB is over before the memory system has ramped up; one launch over the
  * list streams all of them back to back.  Tiled layouts at 2:4, 4:8 or 6:8 run as one kernel per 8 layers whose grid is
  * the layers' grids one after the other (batches above 16 in two passes); any other list runs layer after layer.
- * dev, x, y: host arrays of n_layers pointers (x[l], y[l] as in stb_gemv; entries of x may be equal).  Results are the
- * same bits as n_layers calls of stb_gemv.
+ * dev, x, y: host arrays of n_layers pointers (x[l], y[l] as in stb_gemv; entries of x may be equal).  Every layer of
+ * a launch gets a share of the compute units in proportion to its size, so its partial sums may be added in another
+ * order than in a call of stb_gemv: results are reproducible bit for bit from call to call, within rounding of those
+ * of single calls.
  * workspace: device scratch of at least stb_gemv_batched_workspace_bytes() bytes, 256-byte aligned; layer l owns its
  * own slice (the slices follow each other in the order of the list, each as large as round_up(stb_gemv_workspace_bytes
  * of the layer, 256)), whose first 4 * ceil(n / 16) bytes must be zero before the first call and are left zero.

@@ -830,16 +830,17 @@ extern "C" int stb_tiled_meta_index(const stb_layout_t* L, void* E, void* stream
     return e == hipSuccess ? STB_OK : STB_EHIP;
 }
 
-extern "C" int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_splits, int* out) {
-    if (nrt < 1 || nsb < 1 || B < 1 || B > 16 || (mode != 2 && mode != 4 && mode != 6) || !out) return STB_EUNSUPPORTED;
+extern "C" int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_splits, int cus, int* out) {
+    if (nrt < 1 || nsb < 1 || B < 1 || B > 16 || (mode != 2 && mode != 4 && mode != 6) || cus < 1 || cus > 256 || !out) return STB_EUNSUPPORTED;
     const int64_t lds_max = LDS24 - (mode == 2 ? 0 : 32768);
     // Column splits of SPS <= 8 wavefronts; a wavefront takes V superblocks (V = 1: its own; V = 2 .. 8: it visits
     // them one after the other, each visit over all row tiles of a phase); a workgroup owns R row tiles.  Among the
     // shapes whose LDS fits, take the one with the lowest estimated time, in ns: per (row tile, superblock) product
     // ~750 on the sparse instruction, ~1000 on the dense one; ~800 per visit for taking its operands from LDS;
-    // R * V products for each of the ceil(SPS / 4) wavefronts of a SIMD, times the rounds the grid needs on 256
-    // compute units; adding the column splits up through the workspace costs ~3000 plus ~90 per split and batch
-    // row.  Ties go to the fewest splits.
+    // R * V products for each of the ceil(SPS / 4) wavefronts of a SIMD, times the rounds the grid needs on `cus`
+    // compute units (256 for a layer that has the chip to itself; a layer's share of them when several layers run as
+    // one launch); adding the column splits up through the workspace costs ~3000 plus ~90 per split and batch row.
+    // Ties go to the fewest splits.
     // LDS of one wavefront: per visit the x rows (B rows and one of zeros, 1040 bytes each) and 16 records; the PHT
     // partial tiles lie on top of the x rows when there is one visit, behind everything otherwise.
     const int xbytes = (B < 16 ? B + 1 : 16) * 1040;
@@ -858,7 +859,7 @@ extern "C" int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_
             const int sps = (nsb + s * v - 1) / (s * v);
             if (sps > 8 || (s - 1) * sps * v >= nsb) continue;   // a split must own at least one superblock
             if ((s * v - 1) * sps >= nsb) continue;              // ... and so must the last visit of the last split
-            const int groups = 256 / s > 0 ? 256 / s : 1;
+            const int groups = cus / s > 0 ? cus / s : 1;
             const int r = (nrt + groups - 1) / groups, g = (nrt + r - 1) / r;
             const int pht = r < PHASE24 ? r : PHASE24;
             int w, ro, po;
@@ -874,7 +875,7 @@ extern "C" int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_
             // 1.45 times the time per product)
             const int64_t per_wave = (int64_t)(mode == 2 ? 750 : 1000) * r * v + (v > 1 ? (int64_t)800 * v * phases : 0);
             const int64_t per_simd = sps <= 4 ? per_wave * 29 / 20 : per_wave * ((sps + 3) / 4);
-            const int64_t cost = per_simd * ((g * s + 255) / 256) + (s > 1 ? 3000 + (int64_t)90 * s * B : 0);
+            const int64_t cost = per_simd * ((g * s + cus - 1) / cus) + (s > 1 ? 3000 + (int64_t)90 * s * B : 0);
             if (S == 0 || cost < best_cost) { best_cost = cost; S = s; R = r; SPS = sps; V = v; wreg = w; rec_off = ro; part_off = po; }
         }
     }
@@ -897,8 +898,18 @@ extern "C" int stb_tiled_gemv24_group(int n_layers, const stb_layout_t* const* L
     const int xbytes = (B < 16 ? B + 1 : 16) * 1040;
     int blocks = 0, sps_max = 1;
     int64_t lds = 0;
+    // every layer gets a share of the 256 compute units in proportion to its work, so that the layers of a launch run
+    // side by side and end together instead of each being cut for the whole chip
+    int64_t work[GROUP24_MAX], total_work = 0;
+    for (int l = 0; l < n_layers; l++) {
+        const bool sparse = Ls[l]->cfg.M == 4 && Ls[l]->cfg.N == 2;
+        work[l] = (int64_t)Ls[l]->n_row_tiles * Ls[l]->n_super * (sparse ? 3 : 4);
+        total_work += work[l];
+    }
     for (int l = 0; l < n_layers; l++) {
         const stb_layout_t* L = Ls[l];
+        int cus = n_layers == 1 ? 256 : (int)((256 * work[l] + total_work / 2) / (total_work > 0 ? total_work : 1));
+        cus = cus < 1 ? 1 : (cus > 256 ? 256 : cus);
         if ((8 * L->cfg.N) % L->cfg.M != 0) return STB_EUNSUPPORTED;
         const int n8 = 8 * L->cfg.N / L->cfg.M;
         const int mode = L->cfg.M == 4 && L->cfg.N == 2 ? 2 : n8;      // 2: sparse instruction; 4, 6: dense with the scatter table
@@ -907,7 +918,7 @@ extern "C" int stb_tiled_gemv24_group(int n_layers, const stb_layout_t* const* L
         Gemv24Layer& d = a.l[l];
         d.p = make_tiled(L);
         int plan[7];
-        if (stb_tiled_gemv24_plan(d.p.nrt, d.p.nsb, B, mode, max_splits24(d.p.nsb), plan) != STB_OK) return STB_EUNSUPPORTED;
+        if (stb_tiled_gemv24_plan(d.p.nrt, d.p.nsb, B, mode, max_splits24(d.p.nsb), cus, plan) != STB_OK) return STB_EUNSUPPORTED;
         d.S = plan[0]; d.R = plan[1]; d.SPS = plan[2]; d.V = plan[3]; d.WREG = plan[4]; d.REC_OFF = plan[5]; d.PART_OFF = plan[6];
         d.XS = xbytes;
         d.G = (d.p.nrt + d.R - 1) / d.R;

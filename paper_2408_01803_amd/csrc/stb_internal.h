@@ -34,9 +34,9 @@ int stb_tiled_gemv24(const stb_layout_t* L, const void* x, int B, void* y, int y
 int stb_tiled_gemv24_group(int n_layers, const stb_layout_t* const* Ls, const void* const* xs, int B, void* const* ys,
                            int y_fp32, void* const* counters, void* const* partials, const int64_t* partial_bytes,
                            void* stream, int* hip_err);
-// The launch shape stb_tiled_gemv24 takes (host arithmetic only; out[7] = S, R, SPS, V, LDS bytes per wavefront, record
-// offset, partial-tile offset).
-int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_splits, int* out);
+// The launch shape stb_tiled_gemv24 takes for a layer that may use `cus` (1..256) compute units (host arithmetic only;
+// out[7] = S, R, SPS, V, LDS bytes per wavefront, record offset, partial-tile offset).
+int stb_tiled_gemv24_plan(int nrt, int nsb, int B, int mode, int max_splits, int cus, int* out);
 // The meta index of a tiled 2:4 layout, made by the decode kernel's own index function (stb_gemv24.hip).
 int stb_tiled_meta_index(const stb_layout_t* L, void* E, void* stream, int* hip_err);
 // Prefill kernel for the tiled order (stb_gemm.hip) and its scratch size for T tokens.

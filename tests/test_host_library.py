@@ -228,7 +228,7 @@ def test_decode_launch_plan_invariants():
     import ctypes as C
     lib = S.binding._lib()
     plan = lib.stb_tiled_gemv24_plan
-    plan.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_int)]
+    plan.argtypes = [C.c_int] * 6 + [C.POINTER(C.c_int)]
     plan.restype = C.c_int
     out = (C.c_int * 7)()
     LDS, PHASE = 160 * 1024 - 64, 15
@@ -238,17 +238,17 @@ def test_decode_launch_plan_invariants():
         for nsb in list(range(1, 60)) + [64, 100, 112]:
             max_splits = (nsb + 1) // 2 + 3            # the bound the workspace is sized for
             for nrt in (1, 2, 3, 16, 63, 256, 257, 320, 512, 688, 864, 1792, 4000):
-                for B in (1, 2, 4, 5, 8, 15, 16):
-                    rc = plan(nrt, nsb, B, mode, max_splits, out)
+                for B, cus in ((1, 256), (2, 256), (4, 256), (5, 256), (8, 256), (15, 256), (16, 256), (1, 25), (1, 128), (4, 1), (16, 77)):
+                    rc = plan(nrt, nsb, B, mode, max_splits, cus, out)
                     if rc != 0:
                         continue
                     Sn, R, SPS, V, wreg, rec_off, part_off = list(out)
-                    what = (mode, nsb, nrt, B, list(out))
+                    what = (mode, nsb, nrt, B, cus, list(out))
                     assert 1 <= SPS <= 8 and 1 <= V <= 8 and 1 <= Sn <= max_splits and R >= 1, what
                     assert Sn * SPS * V >= nsb, what                      # every superblock has a wavefront and a visit
                     assert (Sn - 1) * SPS * V < nsb, what                 # no empty split
                     assert (Sn * V - 1) * SPS < nsb, what                 # no empty last visit
-                    assert R == -(-nrt // max(256 // Sn, 1)), what           # row tiles per workgroup: one round on 256 units if it can be
+                    assert R == -(-nrt // max(cus // Sn, 1)), what        # row tiles per workgroup: one round on the layer's units if it can be
                     pht = min(R, PHASE)
                     assert pht == R or pht % 3 == 0, what                 # phases end on a whole round of the three tile buffers
                     xbytes = (B + 1 if B < 16 else 16) * 1040
@@ -260,7 +260,8 @@ def test_decode_launch_plan_invariants():
                     assert SPS * wreg <= lds_max, what
     assert seen_multi > 0
     # arguments outside the kernel's range are refused
-    assert plan(16, 8, 17, 2, 7, out) != 0 and plan(16, 8, 1, 5, 7, out) != 0 and plan(0, 8, 1, 2, 7, out) != 0
+    assert plan(16, 8, 17, 2, 7, 256, out) != 0 and plan(16, 8, 1, 5, 7, 256, out) != 0 and plan(0, 8, 1, 2, 7, 256, out) != 0
+    assert plan(16, 8, 1, 2, 7, 0, out) != 0 and plan(16, 8, 1, 2, 7, 257, out) != 0
 
 
 # ----------------------------------------------------------------------------------------------
