@@ -11,6 +11,8 @@ What it follows (sections / equations / algorithms of the STBLLM paper):
   * residual_binary              -- Eq. 4, Alg. 2 "Res_Approx"
   * search_breakpoints           -- Alg. 2 "NonSalientAwareQuant", Eq. 5-6, ratio p2 = 2 p1 (App. A)
   * region_ids                   -- Alg. 2 "Trisection": sparse |w|>p2, intermediate p1<|w|<=p2, dense |w|<=p1
+  * hessian_factor, pack_obc     -- Alg. 1 in full: H = 2 X^T X, H^c = Cholesky((H + lambda I)^-1), Standardized Importance
+                                    on each 128-column slice, block-wise error compensation of the later columns
   * pack / unpack                -- the storage the paper accounts for in "Average Bits" (1 sign bit per
                                     kept weight, a second one on salient columns, 2-bit group id,
                                     per-block channel-wise scales) plus the N:M position mask
@@ -379,6 +381,122 @@ def pack(W, xnorm, sal_bitmap, N: int, M: int, region_mode: int = 0, return_debu
     )
     if return_debug:
         return planes, dict(mask=mask, ids=ids, tpos=tpos, breakpoints=breakpoints)
+    return planes
+
+
+def _emit_planes(n, k, N, M, mask, signpos, ids, tpos, scales, res_scale, sal_bitmap):
+    """The bit planes of pack() from per-weight decisions (mask, sign >= 0, group id, residual sign) and the scales."""
+    sal = bitmap_to_bool(sal_bitmap, k)
+    S = int(sal.sum())
+    L = layout_sizes(n, k, N, M, S)
+    nb = L["n_blocks"]
+    slots = k * N // M
+    sign_slots = signpos[mask].reshape(n, slots)
+    id_slots = ids[mask].reshape(n, slots)
+    id_bits = np.zeros((n, 2 * slots), dtype=np.uint8)
+    id_bits[:, 0::2] = id_slots & 1
+    id_bits[:, 1::2] = id_slots >> 1
+    return dict(
+        mask=np.packbits(mask, axis=1, bitorder="little"),
+        sign=_bits_to_bytes(sign_slots, L["sign_stride"]),
+        region=_bits_to_bytes(id_bits, L["region_stride"]),
+        res_sign=(_bits_to_bytes((tpos & mask)[:, sal], L["res_stride"]) if S > 0
+                  else np.zeros((n, 0), dtype=np.uint8)),
+        scales=scales,
+        res_scale=res_scale,
+        sal_bitmap=np.ascontiguousarray(sal_bitmap, dtype="<u4").copy(),
+        sal_block_prefix=np.concatenate(
+            [[0], np.cumsum(sal.reshape(nb, BLOCK).sum(axis=1))]).astype("<u4"),
+    )
+
+
+def hessian_factor(X, lam: float) -> np.ndarray:
+    """H^c of Alg. 1 for calibration activations X (r samples x k input features):
+    H = 2 X^T X (the Hessian of the layer's squared output error), H^c = the upper-triangular Cholesky factor of
+    (H + lam I)^-1, i.e. H^c^T H^c = (H + lam I)^-1.
+
+    Readings: the paper writes H = 2 X X^T for X in R^{r x d}; the Hessian over the d = k input features is meant.
+    Its "Cholesky(.)" does not say which triangle: only the upper factor has non-zero entries H^c[b:b+beta, b+beta:]
+    for the compensation step to use, so the upper one it is.
+    """
+    X = np.asarray(X, dtype=np.float64)
+    k = X.shape[1]
+    H = 2.0 * (X.T @ X) + float(lam) * np.eye(k)
+    Hinv = np.linalg.inv(H)
+    Hinv = 0.5 * (Hinv + Hinv.T)
+    return np.ascontiguousarray(np.linalg.cholesky(Hinv).T)
+
+
+def pack_obc(W, Hc, xnorm, sal_bitmap, N: int, M: int, region_mode: int = 0, return_debug: bool = False):
+    """Alg. 1 as a whole: block after block (128 columns), on a float64 working copy of W:
+      1. Standardized Importance of the block's slice (Alg. 1 calls it on W[:, b:b+beta]: sums, mean and deviation of
+         Eq. 3 over the slice) and the N:M mask from it
+      2. residual binarisation of the kept salient weights, break points and trisection of the kept non-salient ones,
+         exactly as pack() does per block -> B, the dequantised block (what inference will multiply by)
+      3. E = (W_block - B) / diag(H^c)_block  (column j of the error is divided by H^c[j, j])
+      4. W[:, later columns] -= E . H^c[block, later columns]
+    Hc: (k, k) upper-triangular factor from hessian_factor(), or None: then steps 3-4 are skipped, which leaves pack()
+    with the per-block Standardized Importance of Alg. 1 instead of the whole-layer one of Eq. 3.
+    The salient column set is an input, as in pack().
+
+    Readings: "E <- (W - B) / H^c_{b:b+beta, b:b+beta}" divides column j by the diagonal entry H^c[j, j] (the scaling
+    of a column's error in the optimal-brain-compression update that the comment in Alg. 1 names); the product of step
+    4 is accumulated over the block's columns in ascending order, one multiply and one add per term.
+    """
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    n, k = W.shape
+    sal = bitmap_to_bool(sal_bitmap, k)
+    nb = k // BLOCK
+    xn = np.asarray(xnorm, dtype=np.float32)
+    Wd = W.astype(np.float64)
+    mask = np.zeros((n, k), dtype=bool)
+    signpos = np.zeros((n, k), dtype=bool)
+    ids = np.zeros((n, k), dtype=np.uint8)
+    tpos = np.zeros((n, k), dtype=bool)
+    scales = np.zeros((n, nb, 4), dtype=np.float16)
+    res_scale = np.zeros((n, nb), dtype=np.float16)
+    for q in range(nb):
+        c0, c1 = q * BLOCK, (q + 1) * BLOCK
+        Wb = Wd[:, c0:c1].copy()
+        absb = np.abs(Wb)
+        mb = nm_mask(standardized_importance(Wb, xn[c0:c1]), N, M)
+        kept_sal = mb & sal[None, c0:c1]
+        kept_ns = mb & ~sal[None, c0:c1]
+        a_o, a_r, t = residual_binary(Wb, kept_sal)
+        if region_mode == 0:
+            p1, p2 = search_breakpoints(Wb, kept_ns)
+        elif region_mode == 1:
+            p1, p2 = tertile_breakpoints(Wb, kept_ns)
+        else:
+            raise ValueError("region_mode must be 0 or 1")
+        rid = region_ids(absb, p1, p2)
+        for r in (DENSE, INTER, SPARSE):
+            alpha, _ = binary(absb, kept_ns & (rid == r))
+            scales[:, q, r] = to_f16(alpha)
+        rid[kept_sal] = SALIENT
+        scales[:, q, SALIENT] = a_o
+        res_scale[:, q] = a_r
+        mask[:, c0:c1] = mb
+        signpos[:, c0:c1] = Wb >= 0
+        ids[:, c0:c1] = rid
+        tpos[:, c0:c1] = t
+        if Hc is not None and c1 < k:
+            # B: the dequantised block, with the stored (fp16) scales and the one fp32 addition of salient weights
+            s = np.where(Wb >= 0, np.float32(1), np.float32(-1))
+            a = np.take_along_axis(scales[:, q, :].astype(np.float32), rid.astype(np.int64), axis=1)
+            B = (s * a).astype(np.float32)
+            tt = np.where(t, np.float32(1), np.float32(-1))
+            both = (s * a).astype(np.float32) + (tt * res_scale[:, q].astype(np.float32)[:, None]).astype(np.float32)
+            B = np.where(kept_sal, both.astype(np.float32), B)
+            B = np.where(mb, B, np.float32(0)).astype(np.float64)
+            E = (Wb - B) / np.diag(Hc)[None, c0:c1]
+            acc = np.zeros((n, k - c1), dtype=np.float64)
+            for c in range(BLOCK):                      # ascending, one multiply and one add per term
+                acc += E[:, c:c + 1] * Hc[c0 + c:c0 + c + 1, c1:]
+            Wd[:, c1:] -= acc
+    planes = _emit_planes(n, k, N, M, mask, signpos, ids, tpos, scales, res_scale, sal_bitmap)
+    if return_debug:
+        return planes, dict(mask=mask, ids=ids, tpos=tpos, W_final=Wd)
     return planes
 
 

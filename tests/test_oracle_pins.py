@@ -805,3 +805,133 @@ def test_layer_l2_norm_is_the_frobenius_norm():
     W = rng.standard_normal((7, 33)).astype(np.float32)
     assert abs(O.layer_l2_norm(W) - np.linalg.norm(W.astype(np.float64))) < 1e-12
     assert O.layer_l2_norm(np.array([[3.0, 4.0]])) == 5.0
+
+
+# ----------------------------------------------------------------------------------------------
+# Alg. 1 as a whole: per-block Standardized Importance and block-wise error compensation
+# ----------------------------------------------------------------------------------------------
+
+def _same_planes(P, Q):
+    return all(np.array_equal(np.asarray(P[key]), np.asarray(Q[key])) for key in P)
+
+
+def _correlated_x(r, k, seed, mix=0.5):
+    rng = _rng(seed)
+    return rng.standard_normal((r, k)) @ (np.eye(k) + mix * rng.standard_normal((k, k)) / np.sqrt(k))
+
+
+def test_obc_worked_example_from_golden_file():
+    spec = _read_spec("worked_example_obc.txt")
+    D = {"D": float(spec["D"][0]), "D2": float(spec["D2"][0])}
+    assert float(np.float16(np.float32(0.5 / 61))) == D["D"]
+    assert float(np.float16(np.float32(0.5 / 63))) == D["D2"] == 2.0 ** -7 * (1 + 16 / 1024)
+
+    def val(v):
+        name = v.lstrip("-")
+        x = D[name] if name in D else float(name)
+        return -x if v.startswith("-") else x
+
+    W = np.zeros((1, 256), dtype=np.float32)
+    W[0, :8] = [float(v) for v in spec["first8"]]
+    Hc = np.eye(256)
+    for r, c, v in zip(spec["hc"][0::3], spec["hc"][1::3], spec["hc"][2::3]):
+        Hc[int(r), int(c)] = float(v)
+    P, dbg = O.pack_obc(W, Hc, np.ones(256, dtype=np.float32), np.zeros(8, dtype="<u4"), 2, 4, 0, return_debug=True)
+    assert dbg["W_final"][0, 133] == float(spec["w_after_133"][0])
+    assert dbg["W_final"][0, 140] == float(spec["w_after_140"][0])
+    changed = np.flatnonzero(dbg["W_final"][0] != W[0].astype(np.float64))
+    assert changed.tolist() == [133, 140]
+    What = O.unpack(P, 1, 256, 2, 4)[0]
+    assert What[:8].tolist() == [np.float32(val(v)) for v in spec["what0_first8"]]
+    assert (What[8:128].reshape(30, 4) == np.float32([val(v) for v in spec["what0_rest_group"]])[None, :]).all()
+    assert What[132:136].tolist() == [np.float32(val(v)) for v in spec["what1_132_135"]]
+    assert What[140:144].tolist() == [np.float32(val(v)) for v in spec["what1_140_143"]]
+    rest = np.delete(What[128:].reshape(32, 4), [1, 3], axis=0)
+    assert (rest == np.float32([val(v) for v in spec["what1_rest_group"]])[None, :]).all()
+    assert np.float32(P["scales"][0, 1]).tolist() == [np.float32(val(v)) for v in spec["scales_block1"]]
+    assert (What == _decode_bitwise(P, 1, 256, 2, 4)[0]).all()
+
+
+@pytest.mark.parametrize("N,M,mode,kind,seed", [(2, 4, 0, "t3", 71), (4, 8, 0, "x8", 72), (6, 8, 1, "x8", 73)])
+def test_obc_without_coupling_is_pack_on_every_slice(N, M, mode, kind, seed):
+    # no factor, or a diagonal one: nothing moves, and each block is packed from its own slice alone
+    # (Alg. 1 calls SI on W[:, b:b+beta]): block q of the result is pack() of that slice
+    n, k = 21, 384
+    L = make_layer(n, k, seed, kind, n_salient=18)
+    P0 = O.pack_obc(L["W"], None, L["xnorm"], L["sal_bitmap"], N, M, mode)
+    d = 0.25 + _rng(seed).random(k)
+    assert _same_planes(P0, O.pack_obc(L["W"], np.diag(d), L["xnorm"], L["sal_bitmap"], N, M, mode))
+    W0 = O.unpack(P0, n, k, N, M)
+    for q in range(k // 128):
+        sl = slice(128 * q, 128 * q + 128)
+        Pq = O.pack(L["W"][:, sl], L["xnorm"][sl], L["sal_bitmap"][4 * q:4 * q + 4], N, M, mode)
+        assert np.array_equal(W0[:, sl], O.unpack(Pq, n, 128, N, M)), q
+        assert np.array_equal(P0["scales"][:, q], Pq["scales"][:, 0])
+        assert np.array_equal(P0["res_scale"][:, q], Pq["res_scale"][:, 0])
+        assert np.array_equal(P0["mask"][:, 16 * q:16 * q + 16], Pq["mask"])
+    # bit budget and prefix table are those of pack()
+    Pl = O.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode)
+    for key in Pl:
+        assert np.asarray(Pl[key]).shape == np.asarray(P0[key]).shape and np.asarray(Pl[key]).dtype == np.asarray(P0[key]).dtype
+    assert np.array_equal(Pl["sal_block_prefix"], P0["sal_block_prefix"])
+
+
+def test_obc_with_a_single_block_is_pack():
+    # beta = k: there are no later columns, and the slice is the layer, so Eq. 3 over the layer = SI of Alg. 1
+    n, k = 33, 128
+    L = make_layer(n, k, 74, "x8", n_salient=9)
+    Hc = O.hessian_factor(_correlated_x(300, k, 75), 0.01)
+    assert _same_planes(O.pack(L["W"], L["xnorm"], L["sal_bitmap"], 4, 8, 0),
+                        O.pack_obc(L["W"], Hc, L["xnorm"], L["sal_bitmap"], 4, 8, 0))
+
+
+def test_hessian_factor_is_the_upper_cholesky_factor_of_the_damped_inverse():
+    k = 96
+    X = _correlated_x(400, k, 76)
+    lam = 0.05
+    Hc = O.hessian_factor(X, lam)
+    assert np.array_equal(Hc, np.triu(Hc)) and (np.diag(Hc) > 0).all()
+    H = 2.0 * X.T @ X + lam * np.eye(k)
+    assert np.allclose(Hc.T @ Hc @ H, np.eye(k), atol=1e-9)
+    # orthogonal features: H is diagonal, and so is the factor, 1 / sqrt(2 |x_j|^2 + lam)
+    Q, _ = np.linalg.qr(_rng(77).standard_normal((200, 40)))
+    s = 0.5 + _rng(78).random(40)
+    Hd = O.hessian_factor(Q * s, lam)
+    assert np.allclose(Hd, np.diag(1.0 / np.sqrt(2.0 * s * s + lam)), atol=1e-12)
+
+
+def test_obc_update_is_the_least_squares_compensation_when_the_block_factor_is_diagonal():
+    # With (H + lam I)^-1 = H^c^T H^c, fixing the first block to B and choosing the later columns freely to minimise
+    # |X (W' - W)^T|^2 (+ lam |.|^2) moves them by -(W - B)_blk (Hinv_bb)^-1 Hinv_b,rest -- the optimal-brain-surgeon
+    # update.  Alg. 1 divides by the diagonal of H^c only; the two agree when the block's own factor is diagonal.
+    n, k = 17, 256
+    L = make_layer(n, k, 79, "t3", n_salient=8)
+    rng = _rng(80)
+    Hc = np.triu(0.05 * rng.standard_normal((k, k)), 1)
+    Hc[:128, :128] = 0.0
+    Hc += np.diag(0.5 + rng.random(k))
+    P, dbg = O.pack_obc(L["W"], Hc, L["xnorm"], L["sal_bitmap"], 2, 4, 0, return_debug=True)
+    B0 = O.unpack(P, n, k, 2, 4)[:, :128].astype(np.float64)
+    W = L["W"].astype(np.float64)
+    Hinv = Hc.T @ Hc
+    delta = -(W[:, :128] - B0) @ np.linalg.solve(Hinv[:128, :128], Hinv[:128, 128:])
+    assert np.allclose(dbg["W_final"][:, 128:], W[:, 128:] + delta, rtol=0, atol=1e-12)
+    assert np.abs(delta).max() > 1e-3
+    # and it is the minimiser: the gradient of the quadratic form over the later columns vanishes there
+    H = np.linalg.inv(Hinv)
+    D = np.concatenate([B0 - W[:, :128], delta], axis=1)       # W' - W with the first block fixed to B
+    assert np.abs((D @ H)[:, 128:]).max() < 1e-8 * np.abs(D @ H).max()
+
+
+@pytest.mark.parametrize("N,M,seed", [(4, 8, 81), (6, 8, 82), (2, 4, 83)])
+def test_obc_lowers_the_layer_output_error(N, M, seed):
+    n, k = 48, 512
+    L = make_layer(n, k, seed, "x8", n_salient=24)
+    X = _correlated_x(1024, k, seed + 100, mix=0.8)
+    Hc = O.hessian_factor(X, 0.01 * np.mean(np.diag(2.0 * X.T @ X)))
+    W = L["W"].astype(np.float64)
+    err = []
+    for factor in (None, Hc):
+        What = O.unpack(O.pack_obc(L["W"], factor, L["xnorm"], L["sal_bitmap"], N, M, 0), n, k, N, M)
+        err.append(np.linalg.norm(X @ (W - What).T))
+    assert err[1] < 0.97 * err[0], err
