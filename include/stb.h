@@ -155,7 +155,7 @@ int stb_tile(const stb_layout_t* src_rowmajor, stb_layout_t* dst_tiled);
 int stb_untile(const stb_layout_t* src_tiled, stb_layout_t* dst_rowmajor);
 
 /* Structured binarisation of one linear layer on the host (Alg. 1 without its Hessian steps: the salient
- * column set is an input and there is no error compensation between blocks):
+ * column set is an input and there is no error compensation between blocks; stb_pack_obc has them):
  *   Standardized Importance over the whole layer (Eq. 3) -> N:M mask (ties keep the lower column) ->
  *   per 128-column block: residual binarisation of kept salient weights per row (Eq. 4), break points
  *   over the kept non-salient weights of all rows (Alg. 2 "NonSalientAwareQuant", or tertiles), one scale
@@ -167,6 +167,21 @@ int stb_untile(const stb_layout_t* src_tiled, stb_layout_t* dst_rowmajor);
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_ENONFINITE. */
 int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_bitmap, stb_layout_t* out,
              int32_t n_threads);
+
+/* Alg. 1 with its block loop: blocks of 128 columns from left to right, on a float64 working copy of W,
+ *   Standardized Importance (Eq. 3) of the block's slice alone (row sums, column sums, mean and deviation over the
+ *   n x 128 slice) -> N:M mask -> residual binarisation, break points and scales as in stb_pack -> B, the block as
+ *   inference dequantises it -> E = (W_block - B) with column j divided by Hc[j][j] ->
+ *   W[:, later columns] -= E . Hc[block rows, later columns], each output's 128 terms added in ascending column
+ *   order, one multiplication and one addition per term.
+ * Hc: host, k x k row-major float64, the upper-triangular Cholesky factor of (H + lambda I)^-1 with H = 2 X^T X
+ * over the calibration activations (Hc^T Hc = (H + lambda I)^-1); only the diagonal and the part right of each
+ * diagonal block are read.  Hc == NULL skips the compensation: the result is stb_pack with the per-block
+ * Standardized Importance of Alg. 1 in place of the whole-layer one.  The salient column set is an input.
+ * All other arguments, the output and its reproducibility are those of stb_pack.
+ * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_ENONFINITE (also a zero, NaN or Inf on Hc's diagonal). */
+int stb_pack_obc(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
+                 stb_layout_t* out, int32_t n_threads);
 
 /* Layer-wise N:M assignment (Sec. 3.3).  stb_layer_l2_norm: omega = the L2 norm of `count` host fp32 weights
  * (float64, sequential).  stb_layer_nm_assignment: for layers with norms omega[0 .. n_layers), alpha_i = omega_i /

@@ -411,6 +411,151 @@ double trisection_error(const BlockScratch& s, int n, double p1, double p2) {
     return total;
 }
 
+// One block of 128 columns: residual binarisation of the kept salient weights (Eq. 4), break points and region
+// scales of the kept non-salient ones (Alg. 2 NonSalientAwareQuant / Trisection, Eq. 6).  W has row stride `ldw`;
+// `keep`, `ids`, `tpos` are n x k byte maps.  `nt` threads share the break-point candidates.
+template <class T>
+void quantise_block(const T* W, size_t ldw, int q, const stb_cfg_t& cfg, const uint8_t* keep, const uint32_t* sal_bitmap,
+                    uint8_t* ids, uint8_t* tpos, uint16_t* scales, uint16_t* res_scale, int nt) {
+    const int n = cfg.n_out, k = cfg.k_in, N = cfg.N, M = cfg.M, nb = k / STB_BLOCK;
+    const int c0 = q * STB_BLOCK;
+    BlockScratch s;
+    s.start.resize(n + 1);
+    s.a.reserve((size_t)n * STB_BLOCK * N / M);
+    s.col.reserve((size_t)n * STB_BLOCK * N / M);
+    double mx = 0.0;
+    for (int i = 0; i < n; i++) {
+        const T* w = W + (size_t)i * ldw + c0;
+        const uint8_t* kp = keep + (size_t)i * k + c0;
+        // salient part of this (row, block): Eq. 4
+        double so = 0.0;
+        int co = 0;
+        for (int c = 0; c < STB_BLOCK; c++)
+            if (kp[c] && sal_bit(sal_bitmap, c0 + c)) { so += std::fabs((double)w[c]); co++; }
+        const uint16_t ao16 = f64_to_f16_bits(co > 0 ? so / (double)co : 0.0);
+        const double ao = (double)f16_bits_to_f32(ao16);
+        double sr = 0.0;
+        for (int c = 0; c < STB_BLOCK; c++)
+            if (kp[c] && sal_bit(sal_bitmap, c0 + c)) {
+                const double sg = w[c] >= (T)0 ? 1.0 : -1.0;
+                const double r = (double)w[c] - ao * sg;
+                sr += std::fabs(r);
+                tpos[(size_t)i * k + c0 + c] = r >= 0.0 ? 1 : 0;
+            }
+        scales[((size_t)i * nb + q) * 4 + 3] = ao16;
+        res_scale[(size_t)i * nb + q] = f64_to_f16_bits(co > 0 ? sr / (double)co : 0.0);
+        // non-salient kept magnitudes
+        s.start[i] = (int32_t)s.a.size();
+        for (int c = 0; c < STB_BLOCK; c++)
+            if (kp[c] && !sal_bit(sal_bitmap, c0 + c)) {
+                const double a = std::fabs((double)w[c]);
+                s.a.push_back(a);
+                s.col.push_back((uint8_t)c);
+                if (a > mx) mx = a;
+            }
+    }
+    s.start[n] = (int32_t)s.a.size();
+
+    double p1 = 0.0, p2 = 0.0;
+    if (cfg.region_mode == 0) {
+        // Alg. 2 NonSalientAwareQuant: 160 candidates c_t = 0.1 + t*(0.8/159), p2 = 2*p1,
+        // skipped when p2 > 0.9*max; first strict minimum wins
+        const double step = (0.9 - 0.1) / 159.0;
+        double best = std::numeric_limits<double>::infinity();
+        // the candidates' errors are independent of each other: taken by `nt` threads, compared in order afterwards
+        double err[160];
+        parallel_for(160, nt, [&](int64_t t) {
+            const double c = (t == 159) ? 0.9 : (double)t * step + 0.1;
+            const double q1 = c * mx, q2 = 2.0 * q1;
+            err[t] = q2 > 0.9 * mx ? std::numeric_limits<double>::infinity() : trisection_error(s, n, q1, q2);
+        });
+        for (int t = 0; t < 160; t++) {
+            const double c = (t == 159) ? 0.9 : (double)t * step + 0.1;
+            const double q1 = c * mx, q2 = 2.0 * q1;
+            if (q2 > 0.9 * mx) continue;
+            if (err[t] < best) { best = err[t]; p1 = q1; p2 = q2; }
+        }
+    } else {
+        std::vector<double> sorted(s.a);
+        std::sort(sorted.begin(), sorted.end());
+        const size_t m = sorted.size();
+        if (m > 0) {
+            p1 = sorted[(m + 2) / 3 - 1];
+            p2 = sorted[(2 * m + 2) / 3 - 1];
+        }
+    }
+    for (int i = 0; i < n; i++) {
+        const double* a = s.a.data() + s.start[i];
+        const uint8_t* col = s.col.data() + s.start[i];
+        const int cnt = s.start[i + 1] - s.start[i];
+        double sum[3] = {0.0, 0.0, 0.0};
+        int c3[3] = {0, 0, 0};
+        for (int e = 0; e < cnt; e++) {
+            const int r = a[e] > p2 ? 2 : (a[e] > p1 ? 1 : 0);
+            sum[r] += a[e];
+            c3[r]++;
+            ids[(size_t)i * k + c0 + col[e]] = (uint8_t)r;
+        }
+        for (int r = 0; r < 3; r++)
+            scales[((size_t)i * nb + q) * 4 + r] = f64_to_f16_bits(c3[r] > 0 ? sum[r] / (double)c3[r] : 0.0);
+        const uint8_t* kp = keep + (size_t)i * k + c0;
+        for (int c = 0; c < STB_BLOCK; c++)
+            if (kp[c] && sal_bit(sal_bitmap, c0 + c)) ids[(size_t)i * k + c0 + c] = 3;
+    }
+}
+
+// The bit planes, the salient bitmap and its per-block prefix from the per-weight decisions.  The sign plane takes
+// the sign of W as it was when its block was quantised (row stride `ldw`).
+template <class T>
+int emit_planes(const T* W, size_t ldw, const stb_cfg_t& cfg, const uint8_t* keep, const uint8_t* ids, const uint8_t* tpos,
+                const uint32_t* sal_bitmap, stb_layout_t* out, int nt) {
+    const int n = cfg.n_out, k = cfg.k_in, nb = k / STB_BLOCK;
+    const int slots = k * cfg.N / cfg.M;
+    std::vector<int32_t> ordinal(k);   // index of column j among the salient columns
+    {
+        int u = 0;
+        for (int j = 0; j < k; j++) { ordinal[j] = u; u += sal_bit(sal_bitmap, j); }
+    }
+    std::atomic<int> badrow(0);
+    parallel_for(n, nt, [&](int64_t i) {
+        uint8_t* mrow = (uint8_t*)out->mask + (size_t)i * out->mask_stride;
+        uint8_t* srow = (uint8_t*)out->sign + (size_t)i * out->sign_stride;
+        uint8_t* rrow = (uint8_t*)out->region + (size_t)i * out->region_stride;
+        uint8_t* trow = cfg.n_salient ? (uint8_t*)out->res_sign + (size_t)i * out->res_stride : nullptr;
+        std::memset(mrow, 0, out->mask_stride);
+        std::memset(srow, 0, out->sign_stride);
+        std::memset(rrow, 0, out->region_stride);
+        if (trow) std::memset(trow, 0, out->res_stride);
+        const T* w = W + (size_t)i * ldw;
+        const uint8_t* kp = keep + (size_t)i * k;
+        int slot = 0;
+        for (int j = 0; j < k; j++) {
+            if (!kp[j]) continue;
+            mrow[j >> 3] |= (uint8_t)(1u << (j & 7));
+            if (w[j] >= (T)0) srow[slot >> 3] |= (uint8_t)(1u << (slot & 7));
+            const unsigned id = ids[(size_t)i * k + j];
+            rrow[slot >> 2] |= (uint8_t)(id << ((slot & 3) * 2));
+            if (id == 3 && tpos[(size_t)i * k + j]) {
+                const int u = ordinal[j];
+                trow[u >> 3] |= (uint8_t)(1u << (u & 7));
+            }
+            slot++;
+        }
+        if (slot != slots) badrow.store(1);
+    });
+    if (badrow.load()) return STB_EINVAL;
+    std::memcpy(out->sal_bitmap, sal_bitmap, (size_t)k / 8);
+    {
+        uint32_t run = 0;
+        for (int q = 0; q <= nb; q++) {
+            out->sal_block_prefix[q] = run;
+            if (q < nb)
+                for (int c = 0; c < STB_BLOCK; c++) run += sal_bit(sal_bitmap, q * STB_BLOCK + c);
+        }
+    }
+    return STB_OK;
+}
+
 }  // namespace
 
 extern "C" int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_bitmap, stb_layout_t* out,
@@ -421,7 +566,6 @@ extern "C" int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_
     if (out->kind != STB_KIND_ROWMAJOR) return STB_EINVAL;
     const stb_cfg_t cfg = out->cfg;
     const int n = cfg.n_out, k = cfg.k_in, N = cfg.N, M = cfg.M, nb = k / STB_BLOCK;
-    const int slots = k * N / M;
     int nt = n_threads > 0 ? n_threads : (int)std::thread::hardware_concurrency();
     if (nt < 1) nt = 1;
 
@@ -512,130 +656,156 @@ extern "C" int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_
     uint16_t* scales = out->scales;
     uint16_t* res_scale = out->res_scale;
     parallel_for(nb, nt, [&](int64_t q) {
-        const int c0 = (int)q * STB_BLOCK;
-        BlockScratch s;
-        s.start.resize(n + 1);
-        s.a.reserve((size_t)n * STB_BLOCK * N / M);
-        s.col.reserve((size_t)n * STB_BLOCK * N / M);
-        double mx = 0.0;
-        for (int i = 0; i < n; i++) {
-            const float* w = W + (size_t)i * k + c0;
-            const uint8_t* kp = keep.data() + (size_t)i * k + c0;
-            // salient part of this (row, block): Eq. 4
-            double so = 0.0;
-            int co = 0;
-            for (int c = 0; c < STB_BLOCK; c++)
-                if (kp[c] && sal_bit(sal_bitmap, c0 + c)) { so += std::fabs((double)w[c]); co++; }
-            const uint16_t ao16 = f64_to_f16_bits(co > 0 ? so / (double)co : 0.0);
-            const double ao = (double)f16_bits_to_f32(ao16);
-            double sr = 0.0;
-            for (int c = 0; c < STB_BLOCK; c++)
-                if (kp[c] && sal_bit(sal_bitmap, c0 + c)) {
-                    const double sg = w[c] >= 0.0f ? 1.0 : -1.0;
-                    const double r = (double)w[c] - ao * sg;
-                    sr += std::fabs(r);
-                    tpos[(size_t)i * k + c0 + c] = r >= 0.0 ? 1 : 0;
-                }
-            scales[((size_t)i * nb + q) * 4 + 3] = ao16;
-            res_scale[(size_t)i * nb + q] = f64_to_f16_bits(co > 0 ? sr / (double)co : 0.0);
-            // non-salient kept magnitudes
-            s.start[i] = (int32_t)s.a.size();
-            for (int c = 0; c < STB_BLOCK; c++)
-                if (kp[c] && !sal_bit(sal_bitmap, c0 + c)) {
-                    const double a = std::fabs((double)w[c]);
-                    s.a.push_back(a);
-                    s.col.push_back((uint8_t)c);
-                    if (a > mx) mx = a;
-                }
-        }
-        s.start[n] = (int32_t)s.a.size();
-
-        double p1 = 0.0, p2 = 0.0;
-        if (cfg.region_mode == 0) {
-            // Alg. 2 NonSalientAwareQuant: 160 candidates c_t = 0.1 + t*(0.8/159), p2 = 2*p1,
-            // skipped when p2 > 0.9*max; first strict minimum wins
-            const double step = (0.9 - 0.1) / 159.0;
-            double best = std::numeric_limits<double>::infinity();
-            for (int t = 0; t < 160; t++) {
-                const double c = (t == 159) ? 0.9 : (double)t * step + 0.1;
-                const double q1 = c * mx, q2 = 2.0 * q1;
-                if (q2 > 0.9 * mx) continue;
-                const double e = trisection_error(s, n, q1, q2);
-                if (e < best) { best = e; p1 = q1; p2 = q2; }
-            }
-        } else {
-            std::vector<double> sorted(s.a);
-            std::sort(sorted.begin(), sorted.end());
-            const size_t m = sorted.size();
-            if (m > 0) {
-                p1 = sorted[(m + 2) / 3 - 1];
-                p2 = sorted[(2 * m + 2) / 3 - 1];
-            }
-        }
-        for (int i = 0; i < n; i++) {
-            const double* a = s.a.data() + s.start[i];
-            const uint8_t* col = s.col.data() + s.start[i];
-            const int cnt = s.start[i + 1] - s.start[i];
-            double sum[3] = {0.0, 0.0, 0.0};
-            int c3[3] = {0, 0, 0};
-            for (int e = 0; e < cnt; e++) {
-                const int r = a[e] > p2 ? 2 : (a[e] > p1 ? 1 : 0);
-                sum[r] += a[e];
-                c3[r]++;
-                ids[(size_t)i * k + c0 + col[e]] = (uint8_t)r;
-            }
-            for (int r = 0; r < 3; r++)
-                scales[((size_t)i * nb + q) * 4 + r] = f64_to_f16_bits(c3[r] > 0 ? sum[r] / (double)c3[r] : 0.0);
-            const uint8_t* kp = keep.data() + (size_t)i * k + c0;
-            for (int c = 0; c < STB_BLOCK; c++)
-                if (kp[c] && sal_bit(sal_bitmap, c0 + c)) ids[(size_t)i * k + c0 + c] = 3;
-        }
+        quantise_block(W, (size_t)k, (int)q, cfg, keep.data(), sal_bitmap, ids.data(), tpos.data(), scales, res_scale, 1);
     });
 
-    // ---- bit planes ----
-    std::vector<int32_t> ordinal(k);   // index of column j among the salient columns
+    return emit_planes(W, (size_t)k, cfg, keep.data(), ids.data(), tpos.data(), sal_bitmap, out, nt);
+}
+
+// ------------------------------------------------------------------------------------------------
+// packer with the block loop of Alg. 1: Standardized Importance per 128-column slice and block-wise error
+// compensation of the later columns
+// ------------------------------------------------------------------------------------------------
+extern "C" int stb_pack_obc(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
+                            stb_layout_t* out, int32_t n_threads) {
+    if (!W || !xnorm || !sal_bitmap || !out) return STB_ENULL;
+    int rc = stb_layout_check(out);
+    if (rc) return rc;
+    if (out->kind != STB_KIND_ROWMAJOR) return STB_EINVAL;
+    const stb_cfg_t cfg = out->cfg;
+    const int n = cfg.n_out, k = cfg.k_in, N = cfg.N, M = cfg.M, nb = k / STB_BLOCK;
+    int nt = n_threads > 0 ? n_threads : (int)std::thread::hardware_concurrency();
+    if (nt < 1) nt = 1;
     {
-        int u = 0;
-        for (int j = 0; j < k; j++) { ordinal[j] = u; u += sal_bit(sal_bitmap, j); }
+        int cnt = 0;
+        for (int j = 0; j < k; j++) cnt += sal_bit(sal_bitmap, j);
+        if (cnt != cfg.n_salient) return STB_EINVAL;
     }
-    std::atomic<int> badrow(0);
-    parallel_for(n, nt, [&](int64_t i) {
-        uint8_t* mrow = (uint8_t*)out->mask + (size_t)i * out->mask_stride;
-        uint8_t* srow = (uint8_t*)out->sign + (size_t)i * out->sign_stride;
-        uint8_t* rrow = (uint8_t*)out->region + (size_t)i * out->region_stride;
-        uint8_t* trow = cfg.n_salient ? (uint8_t*)out->res_sign + (size_t)i * out->res_stride : nullptr;
-        std::memset(mrow, 0, out->mask_stride);
-        std::memset(srow, 0, out->sign_stride);
-        std::memset(rrow, 0, out->region_stride);
-        if (trow) std::memset(trow, 0, out->res_stride);
-        const float* w = W + (size_t)i * k;
-        const uint8_t* kp = keep.data() + (size_t)i * k;
-        int slot = 0;
+    for (int j = 0; j < k; j++)
+        if (!(xnorm[j] >= 0.0f) || !std::isfinite(xnorm[j])) return STB_ENONFINITE;
+    if (Hc)
         for (int j = 0; j < k; j++) {
-            if (!kp[j]) continue;
-            mrow[j >> 3] |= (uint8_t)(1u << (j & 7));
-            if (w[j] >= 0.0f) srow[slot >> 3] |= (uint8_t)(1u << (slot & 7));
-            const unsigned id = ids[(size_t)i * k + j];
-            rrow[slot >> 2] |= (uint8_t)(id << ((slot & 3) * 2));
-            if (id == 3 && tpos[(size_t)i * k + j]) {
-                const int u = ordinal[j];
-                trow[u >> 3] |= (uint8_t)(1u << (u & 7));
-            }
-            slot++;
+            const double d = Hc[(size_t)j * k + j];
+            if (!std::isfinite(d) || d == 0.0) return STB_ENONFINITE;
         }
-        if (slot != slots) badrow.store(1);
+
+    // float64 working copy: columns right of the current block receive the compensation
+    std::vector<double> Wd((size_t)n * k);
+    std::atomic<int> bad(0);
+    parallel_for(n, nt, [&](int64_t i) {
+        for (int j = 0; j < k; j++) {
+            const float v = W[(size_t)i * k + j];
+            if (!std::isfinite(v)) bad.store(1);
+            Wd[(size_t)i * k + j] = (double)v;
+        }
     });
-    if (badrow.load()) return STB_EINVAL;
-    std::memcpy(out->sal_bitmap, sal_bitmap, (size_t)k / 8);
-    {
-        uint32_t run = 0;
-        for (int q = 0; q <= nb; q++) {
-            out->sal_block_prefix[q] = run;
-            if (q < nb)
-                for (int c = 0; c < STB_BLOCK; c++) run += sal_bit(sal_bitmap, q * STB_BLOCK + c);
-        }
+    if (bad.load()) return STB_ENONFINITE;
+
+    std::vector<uint8_t> keep((size_t)n * k), ids((size_t)n * k, 0), tpos((size_t)n * k, 0);
+    std::vector<double> rs(n), rowacc(n), cs(STB_BLOCK), E(Hc ? (size_t)n * STB_BLOCK : 0);
+    uint16_t* scales = out->scales;
+    uint16_t* res_scale = out->res_scale;
+    const double cnt = (double)n * (double)STB_BLOCK;
+
+    for (int q = 0; q < nb; q++) {
+        const int c0 = q * STB_BLOCK, c1 = c0 + STB_BLOCK;
+        // ---- Standardized Importance over the slice (Eq. 3 with the sums, mean and deviation of the slice) ----
+        parallel_for(n, nt, [&](int64_t i) {
+            const double* w = Wd.data() + (size_t)i * k + c0;
+            double s = 0.0;
+            for (int c = 0; c < STB_BLOCK; c++) s += std::fabs(w[c]);
+            rs[i] = s;
+        });
+        parallel_for(8, nt, [&](int64_t part) {         // column sums add the rows in ascending order
+            for (int c = (int)part * 16; c < (int)part * 16 + 16; c++) cs[c] = 0.0;
+            for (int i = 0; i < n; i++) {
+                const double* w = Wd.data() + (size_t)i * k + c0;
+                for (int c = (int)part * 16; c < (int)part * 16 + 16; c++) cs[c] += std::fabs(w[c]);
+            }
+        });
+        auto mu_at = [&](int i, int c) -> double {
+            const double a = std::fabs(Wd[(size_t)i * k + c0 + c]);
+            const double t1 = rs[i] > 0.0 ? a / rs[i] : 0.0;
+            const double t2 = cs[c] > 0.0 ? a / cs[c] : 0.0;
+            return t1 + t2;
+        };
+        parallel_for(n, nt, [&](int64_t i) {
+            double s = 0.0;
+            for (int c = 0; c < STB_BLOCK; c++) s += mu_at((int)i, c);
+            rowacc[i] = s;
+        });
+        double tot = 0.0;
+        for (int i = 0; i < n; i++) tot += rowacc[i];
+        const double mean = tot / cnt;
+        parallel_for(n, nt, [&](int64_t i) {
+            double s = 0.0;
+            for (int c = 0; c < STB_BLOCK; c++) {
+                const double d = mu_at((int)i, c) - mean;
+                s += d * d;
+            }
+            rowacc[i] = s;
+        });
+        tot = 0.0;
+        for (int i = 0; i < n; i++) tot += rowacc[i];
+        double sd = std::sqrt(tot / cnt);
+        if (sd == 0.0) sd = 1.0;
+        parallel_for(n, nt, [&](int64_t i) {
+            uint8_t* kp = keep.data() + (size_t)i * k + c0;
+            double sc[8];
+            for (int g = 0; g < STB_BLOCK / M; g++) {
+                for (int p = 0; p < M; p++) {
+                    sc[p] = ((mu_at((int)i, g * M + p) - mean) / sd) * (double)xnorm[c0 + g * M + p];
+                    kp[g * M + p] = 0;
+                }
+                for (int p = 0; p < M; p++) {
+                    int better = 0;
+                    for (int o = 0; o < M; o++)
+                        if (sc[o] > sc[p] || (sc[o] == sc[p] && o < p)) better++;
+                    if (better < N) kp[g * M + p] = 1;
+                }
+            }
+        });
+
+        quantise_block(Wd.data(), (size_t)k, q, cfg, keep.data(), sal_bitmap, ids.data(), tpos.data(), scales, res_scale, nt);
+
+        if (!Hc || c1 >= k) continue;
+        // ---- E = (W_block - B) / diag(H^c): B is the block as inference sees it (fp16 scales, one fp32 addition) ----
+        parallel_for(n, nt, [&](int64_t i) {
+            const double* w = Wd.data() + (size_t)i * k + c0;
+            const uint8_t* kp = keep.data() + (size_t)i * k + c0;
+            float sc4[4];
+            for (int r = 0; r < 4; r++) sc4[r] = f16_bits_to_f32(scales[((size_t)i * nb + q) * 4 + r]);
+            const float ar = f16_bits_to_f32(res_scale[(size_t)i * nb + q]);
+            for (int c = 0; c < STB_BLOCK; c++) {
+                float b = 0.0f;
+                if (kp[c]) {
+                    const unsigned id = ids[(size_t)i * k + c0 + c];
+                    b = w[c] >= 0.0 ? sc4[id] : -sc4[id];
+                    if (id == 3) b = b + (tpos[(size_t)i * k + c0 + c] ? ar : -ar);
+                }
+                E[(size_t)i * STB_BLOCK + c] = (w[c] - (double)b) / Hc[(size_t)(c0 + c) * k + c0 + c];
+            }
+        });
+        // ---- W[:, later] -= E . H^c[block, later]: per output the block's 128 terms in ascending order ----
+        const int TJ = 256;
+        const int tiles = (k - c1 + TJ - 1) / TJ;
+        parallel_for(tiles, nt, [&](int64_t t) {
+            const int j0 = c1 + (int)t * TJ, jn = std::min(TJ, k - j0);
+            double acc[TJ];
+            for (int i = 0; i < n; i++) {
+                const double* e = E.data() + (size_t)i * STB_BLOCK;
+                for (int j = 0; j < jn; j++) acc[j] = 0.0;
+                for (int c = 0; c < STB_BLOCK; c++) {
+                    const double ec = e[c];
+                    const double* h = Hc + (size_t)(c0 + c) * k + j0;
+                    for (int j = 0; j < jn; j++) acc[j] += ec * h[j];
+                }
+                double* w = Wd.data() + (size_t)i * k + j0;
+                for (int j = 0; j < jn; j++) w[j] -= acc[j];
+            }
+        });
     }
-    return STB_OK;
+    return emit_planes(Wd.data(), (size_t)k, cfg, keep.data(), ids.data(), tpos.data(), sal_bitmap, out, nt);
 }
 
 // ------------------------------------------------------------------------------------------------

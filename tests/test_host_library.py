@@ -111,6 +111,48 @@ def test_packer_and_host_dequant_are_bit_exact_against_the_oracle(n, k, N, M, mo
     assert (pm.unpack() == O.unpack(ref_planes, n, k, N, M)).all()
 
 
+def _calibration_factor(k, seed, mix=0.6):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((2 * k, k)) @ (np.eye(k) + mix * rng.standard_normal((k, k)) / np.sqrt(k))
+    return X, O.hessian_factor(X, 0.01 * np.mean(np.diag(2.0 * X.T @ X)))
+
+
+@pytest.mark.parametrize("n,k,N,M,mode,kind,seed", [c for c in CASES if c[1] > 128] + [(16, 128, 4, 8, 0, "x8", 9)])
+@pytest.mark.parametrize("compensate", [True, False])
+def test_block_loop_packer_is_bit_exact_against_the_oracle(n, k, N, M, mode, kind, seed, compensate):
+    # Alg. 1 with its block loop: per-slice Standardized Importance, and (with a factor) the compensation of the
+    # later columns, whose float64 sums must follow the stated order for every later decision to agree
+    L = make_layer(n, k, seed, kind)
+    Hc = _calibration_factor(k, seed + 500)[1] if compensate else None
+    ref = O.pack_obc(L["W"], Hc, L["xnorm"], L["sal_bitmap"], N, M, mode)
+    pm = S.PackedMatrix.pack_obc(L["W"], Hc, L["xnorm"], L["sal_bitmap"], N, M, mode, n_threads=3)
+    for name, v in _oracle_bytes(ref).items():
+        got = pm.plane(name)
+        assert got.shape == v.shape, name
+        assert (got == v).all(), name
+    assert (pm.unpack() == O.unpack(ref, n, k, N, M)).all()
+    one = S.PackedMatrix.pack_obc(L["W"], Hc, L["xnorm"], L["sal_bitmap"], N, M, mode, n_threads=1)
+    assert (one.host_image == pm.host_image).all()
+
+
+def test_block_loop_packer_lowers_the_output_error_and_checks_its_factor():
+    n, k = 64, 768
+    L = make_layer(n, k, 31, "x8")
+    X, Hc = _calibration_factor(k, 32, mix=0.8)
+    W = L["W"].astype(np.float64)
+    plain = S.PackedMatrix.pack_obc(L["W"], None, L["xnorm"], L["sal_bitmap"], 4, 8).unpack()
+    comp = S.PackedMatrix.pack_obc(L["W"], Hc, L["xnorm"], L["sal_bitmap"], 4, 8).unpack()
+    assert np.linalg.norm(X @ (W - comp).T) < 0.97 * np.linalg.norm(X @ (W - plain).T)
+    bad = Hc.copy()
+    bad[5, 5] = 0.0
+    with pytest.raises(S.StbError) as e:
+        S.PackedMatrix.pack_obc(L["W"], bad, L["xnorm"], L["sal_bitmap"], 4, 8)
+    assert e.value.status == S.STB_ENONFINITE
+    bad[5, 5] = np.nan
+    with pytest.raises(S.StbError):
+        S.PackedMatrix.pack_obc(L["W"], bad, L["xnorm"], L["sal_bitmap"], 4, 8)
+
+
 def test_packer_result_does_not_depend_on_thread_count():
     L = make_layer(96, 512, 17)
     a = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], 4, 8, 0, n_threads=1)

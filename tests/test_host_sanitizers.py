@@ -27,6 +27,7 @@ CHILD = textwrap.dedent('''
     lib.stb_tile.argtypes = [P(B.stb_layout_t), P(B.stb_layout_t)]
     lib.stb_untile.argtypes = [P(B.stb_layout_t), P(B.stb_layout_t)]
     lib.stb_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(B.stb_layout_t), C.c_int32]
+    lib.stb_pack_obc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, P(B.stb_layout_t), C.c_int32]
     lib.stb_unpack.argtypes = [P(B.stb_layout_t), C.c_void_p]
     lib.stb_salient_columns.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_double, C.c_int32, C.c_void_p, P(C.c_int32)]
     lib.stb_layer_l2_norm.argtypes = [C.c_void_p, C.c_int64, P(C.c_double)]
@@ -52,6 +53,11 @@ CHILD = textwrap.dedent('''
             assert lib.stb_pack(L["W"].ctypes.data, L["xnorm"].ctypes.data, L["sal_bitmap"].ctypes.data, C.byref(lay), threads) == 0
         out = np.empty((n, k), dtype=np.float32)
         assert lib.stb_unpack(C.byref(lay), out.ctypes.data) == 0
+        if k <= 640:                                   # the block loop of Alg. 1, with and without a factor
+            Hc = np.triu(0.02 * np.random.default_rng(n).standard_normal((k, k)), 1) + np.eye(k)
+            for factor in (None, Hc.ctypes.data):
+                assert lib.stb_pack_obc(L["W"].ctypes.data, factor, L["xnorm"].ctypes.data, L["sal_bitmap"].ctypes.data, C.byref(lay), 3) == 0
+            assert lib.stb_unpack(C.byref(lay), out.ctypes.data) == 0
         assert np.isfinite(out).all()
         if (8 * N) %% M == 0 and 8 * N // M in (4, 6):
             tl, timg = image(lib.stb_tiled_sizes, cfg)
@@ -77,6 +83,7 @@ CHILD = textwrap.dedent('''
     lay = B.stb_layout_t()
     assert lib.stb_layout_sizes(C.byref(bad), C.byref(lay)) != 0
     assert lib.stb_pack(None, None, None, C.byref(lay), 1) != 0
+    assert lib.stb_pack_obc(None, None, None, None, C.byref(lay), 1) != 0
     maps = open("/proc/self/maps").read()
     assert "libasan" in maps and "libubsan" in maps, "the sanitizer runtimes are not loaded"
     print("SANITIZED_OK")
