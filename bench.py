@@ -110,7 +110,7 @@ def timed(torch, fn, reps, warm=3, rounds=3, graph=False):
 
 
 def tiled_ok(spec):
-    return (8 * spec.N) % spec.M == 0 and (8 * spec.N // spec.M) in (4, 6)
+    return (8 * spec.N) % spec.M == 0 and (8 * spec.N // spec.M) in (3, 4, 5, 6)
 
 
 def pack_spec(S, make_layer, spec):

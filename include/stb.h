@@ -84,7 +84,7 @@ typedef struct stb_cfg {
  *
  * kind = STB_KIND_ROWMAJOR: the planes exactly as described above ("STB1").
  * kind = STB_KIND_TILED: the device order read by the fast kernels, a byte permutation of STB1 plus zero
- * padding.  Rows are grouped in tiles of 16 and 128-column blocks in groups of 4 ("superblock", 512
+ * padding (3:8 and 5:8: a bit permutation, see "slots" below).  Rows are grouped in tiles of 16 and 128-column blocks in groups of 4 ("superblock", 512
  * columns); a tile record holds one 64-lane wavefront's operands, lane = 16*(block % 4) + (row % 16):
  *   mask      [row_tile][super][half][lane][8 bytes]    the mask bytes of (row, block), columns 64*half .. 64*half+63
  *   sign      [row_tile][super][lane][sign_stride]      sign bits of the block's 128*N/M kept weights
@@ -92,6 +92,12 @@ typedef struct stb_cfg {
  *             sign / region are cut into two halves like mask ([row_tile][super][half][lane][stride/2], the
  *             kept weights of columns 64*half ..) when their stride is a multiple of 8 bytes, so that each
  *             half is a whole number of 32-bit words (2:4 and 4:8: both; 6:8: region only)
+ *             slots: layers that keep 3 or 5 of 8 columns are stored in the records of 4:8 / 6:8 (sign_stride 8 /
+ *             12, region_stride 16 / 24), one slot per group of 8 columns left zero: the kept columns of a
+ *             group take the slots they would have if the group's lowest pruned column were kept as well,
+ *             so that the kernels of 4:8 and 6:8 read them unchanged (the mask byte tells them which slot is
+ *             the unused one).  The tiled image of such a layer is 3.25 (5:8) or 2.25 (3:8) bits per weight
+ *             of mask, sign and id planes, against 2.875 and 2.125 in STB1.
  *   scales    [row_tile][super][lane][4] fp16, res_scale [row_tile][super][lane] fp16
  *   res_sign  [row_tile][word][row % 16] uint32: the STB1 row strings cut into 32-bit words and transposed
  *             inside each row tile (res_stride / 4 words per row)
@@ -147,10 +153,11 @@ int stb_layout_bind(stb_layout_t* layout, void* base);
  * Errors: STB_ENULL, STB_EINVAL. */
 int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out);
 
-/* Host-side byte permutation STB1 -> tiled order (and back).  Both layouts must describe the same cfg and
+/* Host-side permutation STB1 -> tiled order (and back).  Both layouts must describe the same cfg and
  * be bound to caller-allocated host memory; every byte of the destination is written.  stb_tile also fills
  * dst->max_sal_block and dst->max_sal_half.  stb_untile(stb_tile(x)) == x bit for bit.
- * Errors: STB_ENULL, STB_EINVAL (kind or cfg mismatch), STB_EALIGN. */
+ * Errors: STB_ENULL, STB_EINVAL (kind or cfg mismatch; at 3:8 and 5:8 also a group of 8 columns whose mask byte
+ * does not keep exactly N), STB_EALIGN. */
 int stb_tile(const stb_layout_t* src_rowmajor, stb_layout_t* dst_tiled);
 int stb_untile(const stb_layout_t* src_tiled, stb_layout_t* dst_rowmajor);
 
@@ -241,7 +248,7 @@ int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream);
 
 /* Decode-time product (memory-bound regime, App. C "Theory Analysis": small N = batch):
  *   y[b][i] = sum_j x[b][j] * W_hat[i][j],  b < B <= 32.
- * dev: either kind; the tiled kind runs the wavefront-tiled matrix-core kernel (N:M in {2:4, 4:8, 6:8}; it
+ * dev: either kind; the tiled kind runs the wavefront-tiled matrix-core kernel (N:M in {2:4, 3:8, 4:8, 5:8, 6:8, 3:4}; it
  * assumes the stored scales are >= 0, as stb_pack writes them), the row-major kind a generic kernel for any
  * N:M.
  * x: device fp16 [B][k] row-major.  y: device [B][n] row-major, fp16 (y_fp32 = 0) or fp32 (y_fp32 = 1),
@@ -276,7 +283,7 @@ int64_t stb_gemv_workspace_bytes(const stb_cfg_t* cfg, int32_t B);
 /* Several independent layers at the same B as one launch: the matrices of a decoder layer that share their input
  * (q, k and v; gate and up) or any other list.  Decode is bound by memory traffic (App. C "Theory Analysis", small
  * N), and a single layer of a few tens of MB is over before the memory system has ramped up; one launch over the
- * list streams all of them back to back.  Tiled layouts at 2:4, 4:8 or 6:8 run as one kernel per 8 layers whose grid is
+ * list streams all of them back to back.  Tiled layouts at 2:4, 3:8, 4:8, 5:8 or 6:8 run as one kernel per 8 layers whose grid is
  * the layers' grids one after the other (batches above 16 in two passes); any other list runs layer after layer.
  * dev, x, y: host arrays of n_layers pointers (x[l], y[l] as in stb_gemv; entries of x may be equal).  Every layer of
  * a launch gets a share of the compute units in proportion to its size, so its partial sums may be added in another
@@ -298,7 +305,7 @@ int64_t stb_gemv_batched_workspace_bytes(int32_t n_layers, const stb_cfg_t* cons
  *   Y[t][i] = sum_j X[t][j] * W_hat[i][j],  t < T.
  * The weights are dequantised to fp16 on the fly and contracted on the matrix cores with fp32 accumulation.
  * dev: the tiled kind runs the matrix-core kernel that expands the packed bits straight into MFMA operands
- * (N:M in {2:4, 4:8, 6:8}; the residual term of the salient columns is a second, short contraction against
+ * (N:M in {2:4, 3:8, 4:8, 5:8, 6:8, 3:4}; the residual term of the salient columns is a second, short contraction against
  * the gathered salient columns of X, which the call first writes to the workspace); the row-major kind runs a
  * generic kernel for any N:M (it rounds the dequantised salient weights to fp16).
  * Tiled 2:4 layers run on the structured-sparse matrix instruction (kept weights plus an index word as the operand,

@@ -501,12 +501,9 @@ __global__ __launch_bounds__(1024) void gemv_stream_kernel(TiledPlanes p, const 
 // ------------------------------------------------------------------------------------------------
 // launchers (internal ABI, see stb_internal.h)
 // ------------------------------------------------------------------------------------------------
-static int kept_per_8(const stb_layout_t* L) { return 8 * L->cfg.N / L->cfg.M; }
+static int kept_per_8(const stb_layout_t* L) { return stb_tiled_slots(&L->cfg); }    // slots the planes hold per 8 columns
 
-extern "C" int stb_tiled_supported(const stb_layout_t* L) {
-    const int n8 = kept_per_8(L);
-    return (8 * L->cfg.N) % L->cfg.M == 0 && (n8 == 4 || n8 == 6);
-}
+extern "C" int stb_tiled_supported(const stb_layout_t* L) { return stb_tiled_slots(&L->cfg) != 0; }
 
 extern "C" int stb_tiled_dequant(const stb_layout_t* L, float* out, void* stream, int* hip_err) {
     if (!stb_tiled_supported(L)) return STB_EUNSUPPORTED;

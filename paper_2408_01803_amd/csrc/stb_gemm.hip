@@ -1352,7 +1352,7 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
     // 4 runs any layer on the shared-expansion kernel: the tests use them to run every kernel on every case it can
     // take.
     const int which = stb_kernel_override(2);
-    const int n8 = 8 * L->cfg.N / L->cfg.M;
+    const int n8 = stb_tiled_slots(&L->cfg);             // slots per 8 columns in the planes (4 or 6)
     const __half* xh = (const __half*)X;
     const __half* xs = (const __half*)workspace;
     hipError_t e;

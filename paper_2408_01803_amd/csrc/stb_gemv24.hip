@@ -910,8 +910,8 @@ extern "C" int stb_tiled_gemv24_group(int n_layers, const stb_layout_t* const* L
         const stb_layout_t* L = Ls[l];
         int cus = n_layers == 1 ? 256 : (int)((256 * work[l] + total_work / 2) / (total_work > 0 ? total_work : 1));
         cus = cus < 1 ? 1 : (cus > 256 ? 256 : cus);
-        if ((8 * L->cfg.N) % L->cfg.M != 0) return STB_EUNSUPPORTED;
-        const int n8 = 8 * L->cfg.N / L->cfg.M;
+        const int n8 = stb_tiled_slots(&L->cfg);          // slots per 8 columns in the planes
+        if (n8 == 0) return STB_EUNSUPPORTED;
         const int mode = L->cfg.M == 4 && L->cfg.N == 2 ? 2 : n8;      // 2: sparse instruction; 4, 6: dense with the scatter table
         if (mode != 2 && mode != 4 && mode != 6) return STB_EUNSUPPORTED;
         if (L->region_bytes >= (1ll << 31) || L->res_bytes >= (1ll << 31)) return STB_EUNSUPPORTED;   // 32-bit offsets inside a plane

@@ -164,6 +164,10 @@ extern "C" int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out) {
     out->mask_stride = 16;
     out->sign_stride = 16 * cfg->N / cfg->M;                     // 128*N/M sign bits per block
     out->region_stride = 32 * cfg->N / cfg->M;
+    if (stb_tiled_padded(cfg)) {                                 // 3 or 5 of 8: stored with the slots of 4 or 6 of 8
+        out->sign_stride = 2 * stb_tiled_slots(cfg);
+        out->region_stride = 4 * stb_tiled_slots(cfg);
+    }
     out->res_stride = out->n_salient_pad / 8;
     out->mask_bytes = rec * out->mask_stride;
     out->sign_bytes = rec * out->sign_stride;
@@ -234,9 +238,13 @@ bool same_cfg(const stb_cfg_t& a, const stb_cfg_t& b) {
 }
 
 // Copies every (row, block) record between the two orders; to_tiled selects the direction.
-void permute_records(const stb_layout_t* rm, const stb_layout_t* tl, bool to_tiled) {
+// Returns STB_EINVAL when a padded layout (3 or 5 kept of 8) meets a mask byte with another number of bits.
+int permute_records(const stb_layout_t* rm, const stb_layout_t* tl, bool to_tiled) {
     const int n = rm->cfg.n_out, nb = rm->n_blocks, nsb = tl->n_super;
     const int64_t SB = tl->sign_stride, RB = tl->region_stride;
+    const bool padded = stb_tiled_padded(&rm->cfg);
+    const int t8 = stb_tiled_slots(&rm->cfg), n8 = 8 * rm->cfg.N / rm->cfg.M;
+    const int64_t RSB = 2 * n8, RRB = 4 * n8;               // row-major bytes per block when padded (M = 8)
     uint8_t* rmask = (uint8_t*)rm->mask; uint8_t* tmask = (uint8_t*)tl->mask;
     uint8_t* rsign = (uint8_t*)rm->sign; uint8_t* tsign = (uint8_t*)tl->sign;
     uint8_t* rreg = (uint8_t*)rm->region; uint8_t* treg = (uint8_t*)tl->region;
@@ -257,9 +265,46 @@ void permute_records(const stb_layout_t* rm, const stb_layout_t* tl, bool to_til
                     mv(a_rm, t_plane + rec * bytes, bytes);
                 }
             };
-            mv_rec(rmask + (int64_t)r * rm->mask_stride + 16 * q, tmask, 16);
-            mv_rec(rsign + (int64_t)r * rm->sign_stride + SB * q, tsign, SB);
-            mv_rec(rreg + (int64_t)r * rm->region_stride + RB * q, treg, RB);
+            uint8_t* mrow = rmask + (int64_t)r * rm->mask_stride + 16 * q;
+            mv_rec(mrow, tmask, 16);                       // from here on the row-major mask is valid in both directions
+            if (!padded) {
+                mv_rec(rsign + (int64_t)r * rm->sign_stride + SB * q, tsign, SB);
+                mv_rec(rreg + (int64_t)r * rm->region_stride + RB * q, treg, RB);
+            } else {
+                // slot s of the block (kept weights in column order) <-> slot t8 * group + rank of its column among
+                // the group's kept columns and the lowest pruned one
+                uint8_t* srow = rsign + (int64_t)r * rm->sign_stride + RSB * q;
+                uint8_t* grow = rreg + (int64_t)r * rm->region_stride + RRB * q;
+                uint8_t ps[12] = {0}, pr[24] = {0};
+                if (!to_tiled) {
+                    mv_rec(ps, tsign, SB);
+                    mv_rec(pr, treg, RB);
+                    std::memset(srow, 0, (size_t)RSB);
+                    std::memset(grow, 0, (size_t)RRB);
+                }
+                int slot = 0;
+                for (int g = 0; g < 16; g++) {
+                    const unsigned mb = mrow[g];
+                    if (__builtin_popcount(mb) != n8) return STB_EINVAL;
+                    const unsigned aug = mb | (~mb & (mb + 1u));
+                    for (int c = 0; c < 8; c++) {
+                        if (!((mb >> c) & 1u)) continue;
+                        const int t = t8 * g + __builtin_popcount(aug & ((1u << c) - 1u));
+                        if (to_tiled) {
+                            ps[t >> 3] |= (uint8_t)(((srow[slot >> 3] >> (slot & 7)) & 1u) << (t & 7));
+                            pr[t >> 2] |= (uint8_t)(((grow[slot >> 2] >> ((slot & 3) * 2)) & 3u) << ((t & 3) * 2));
+                        } else {
+                            srow[slot >> 3] |= (uint8_t)(((ps[t >> 3] >> (t & 7)) & 1u) << (slot & 7));
+                            grow[slot >> 2] |= (uint8_t)(((pr[t >> 2] >> ((t & 3) * 2)) & 3u) << ((slot & 3) * 2));
+                        }
+                        slot++;
+                    }
+                }
+                if (to_tiled) {
+                    mv_rec(ps, tsign, SB);
+                    mv_rec(pr, treg, RB);
+                }
+            }
             mv((uint8_t*)(rm->scales + ((int64_t)r * nb + q) * 4), (uint8_t*)(tl->scales + rec * 4), 8);
             mv((uint8_t*)(rm->res_scale + (int64_t)r * nb + q), (uint8_t*)(tl->res_scale + rec), 2);
         }
@@ -270,6 +315,7 @@ void permute_records(const stb_layout_t* rm, const stb_layout_t* tl, bool to_til
                 mv((uint8_t*)rm->res_sign + (int64_t)r * rm->res_stride + 4 * w,
                    (uint8_t*)tl->res_sign + (((int64_t)(r / 16) * words + w) * 16 + r % 16) * 4, 4);
     }
+    return STB_OK;
 }
 
 // Fills the derived table of salient columns (layout in stb.h); returns the largest count of one block.
@@ -348,7 +394,8 @@ extern "C" int stb_tile(const stb_layout_t* src, stb_layout_t* dst) {
     std::memset(dst->scales, 0, dst->scales_bytes);
     std::memset(dst->res_scale, 0, dst->res_scale_bytes);
     std::memset(dst->sal_bitmap, 0, dst->salmap_bytes);
-    permute_records(src, dst, true);
+    rc = permute_records(src, dst, true);
+    if (rc) return rc;
     const int nb = src->n_blocks, nsb = dst->n_super, k = src->cfg.k_in;
     std::memcpy(dst->sal_bitmap, src->sal_bitmap, src->salmap_bytes);
     for (int q = 0; q <= nsb * 4; q++) dst->sal_block_prefix[q] = src->sal_block_prefix[std::min(q, nb)];
@@ -368,7 +415,8 @@ extern "C" int stb_untile(const stb_layout_t* src, stb_layout_t* dst) {
         return STB_EINVAL;
     std::memset(dst->sign, 0, dst->sign_bytes);       // row padding of the sign / region planes
     std::memset(dst->region, 0, dst->region_bytes);
-    permute_records(dst, src, false);
+    rc = permute_records(dst, src, false);
+    if (rc) return rc;
     std::memcpy(dst->sal_bitmap, src->sal_bitmap, dst->salmap_bytes);
     for (int q = 0; q <= dst->n_blocks; q++) dst->sal_block_prefix[q] = src->sal_block_prefix[q];
     return STB_OK;

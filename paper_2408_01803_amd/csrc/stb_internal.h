@@ -3,6 +3,20 @@
 #define STB_INTERNAL_H
 #include "stb.h"
 
+// Slots per 8 columns that the tiled order stores sign bits and group ids for: 4 for layers that keep 3 or 4 of 8
+// columns (2:4, 4:8, 3:8), 6 for 5 or 6 of 8 (5:8, 6:8, 3:4); 0 for every other N:M (those stay on the row-major
+// kernels).  With 3 or 5 kept columns one slot per group is padding: the kept columns are numbered as if the lowest
+// pruned column of the group were kept too, and the slot of that phantom column is never read.
+static inline int stb_tiled_slots(const stb_cfg_t* c) {
+    if (c->M < 1 || (8 * c->N) % c->M != 0) return 0;
+    const int n8 = 8 * c->N / c->M;
+    return n8 == 3 || n8 == 4 ? 4 : (n8 == 5 || n8 == 6 ? 6 : 0);
+}
+static inline int stb_tiled_padded(const stb_cfg_t* c) {
+    const int t8 = stb_tiled_slots(c);
+    return t8 != 0 && 8 * c->N / c->M != t8;
+}
+
 #ifdef __cplusplus
 extern "C" {
 #endif

@@ -105,7 +105,7 @@ __device__ inline uint32_t window32(const uint32_t* w, int off) {
 
 // ------------------------------------------------------------------------------------------------
 // Scatter table: for mask byte mb, four v_perm selectors that place the slot-ordered weights of the
-// 8-column group at their columns.  N8 = kept weights per 8 columns (4 for 2:4 and 4:8, 6 for 6:8).
+// 8-column group at their columns.  N8 = slots per 8 columns (4 for 2:4, 4:8 and 3:8; 6 for 6:8 and 5:8).
 // Registers W0 = slots 0,1; W1 = slots 2,3; W2 = slots 4,5.  Selectors 0,1 address {W1:W0}; for N8 = 6
 // selectors 2,3 address {W2:W1} (columns 4..7 can only hold slots 2..5), for N8 = 4 they address {W1:W0}.
 // ------------------------------------------------------------------------------------------------
@@ -127,7 +127,10 @@ __device__ inline uint4 scatter_entry(uint32_t mb) {
             const int pcol = 2 * v + h;
             uint32_t two = 0x0C0Cu;
             if ((mb >> pcol) & 1u) {
-                int r = __popc(mb & ((1u << pcol) - 1u));
+                // a group that keeps one column less than the table's N8 (3 of 8 with N8 = 4, 5 of 8 with N8 = 6) numbers
+                // its slots as if its lowest pruned column were kept as well: that slot is padding in the planes
+                const uint32_t aug = __popc(mb) == N8 - 1 ? (mb | (~mb & (mb + 1u))) : mb;
+                int r = __popc(aug & ((1u << pcol) - 1u));
                 if (N8 == 6 && v >= 2) r -= 2;
                 r = r < 0 ? 0 : (r > 3 ? 3 : r);
                 two = (uint32_t)(2 * r) | ((uint32_t)(2 * r + 1) << 8);

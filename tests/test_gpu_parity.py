@@ -95,11 +95,15 @@ SMALL = [
     (5, 128, 2, 4, 0, "x8", 111),
     (1, 128, 4, 8, 1, "x8", 112),
     (17, 256, 6, 8, 0, "t3", 113),
+    # 3 and 5 kept of 8 (Sec. 3.3, Table 1): in the tiled order these use the slots of 4:8 / 6:8 with one unused per group
+    (150, 896, 3, 8, 0, "x8", 114),
+    (70, 1536, 5, 8, 1, "t3", 115, 120),
+    (33, 4608, 3, 8, 0, "x8", 116),
 ]
 
 
 def _tiled_ok(N, M):
-    return (8 * N) % M == 0 and (8 * N // M) in (4, 6)
+    return (8 * N) % M == 0 and (8 * N // M) in (3, 4, 5, 6)
 
 
 SMALL_KINDS = [(c, tiled) for c in SMALL for tiled in (False, True) if not tiled or _tiled_ok(c[2], c[3])]

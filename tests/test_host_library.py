@@ -94,6 +94,7 @@ CASES = [
     (130, 640, 4, 8, 1, "t3", 6),
     (17, 1024, 2, 4, 1, "x8", 7),
     (1, 128, 1, 4, 0, "x8", 8),
+    (24, 384, 3, 8, 0, "x8", 10),
 ]
 
 
@@ -189,10 +190,15 @@ def test_tile_untile_round_trip_is_a_byte_permutation(n, k, N, M, mode, kind, se
     pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode)
     tl, timg = pm.tiled()
     assert tl.kind == S.STB_KIND_TILED and tl.n_row_tiles == (n + 15) // 16 and tl.n_super == (k // 128 + 3) // 4
+    # 3 or 5 kept of 8: the tiled order holds the sign bits and ids in the slots of 4 / 6 of 8, one slot per group unused
+    padded = M == 8 and N in (3, 5)
+    t8 = N + 1 if padded else None
     # same multiset of payload bytes: sorted bytes of each per-row plane agree up to zero padding
     for name, off, size in (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_bytes"),
                             ("region", "off_region", "region_bytes"), ("scales", "off_scales", "scales_bytes"),
                             ("res_scale", "off_res_scale", "res_scale_bytes")):
+        if padded and name in ("sign", "region"):
+            continue
         a = np.sort(pm.plane(name))
         b = np.sort(timg[getattr(tl, off):getattr(tl, off) + getattr(tl, size)])
         a, b = a[a != 0], b[b != 0]
@@ -205,8 +211,35 @@ def test_tile_untile_round_trip_is_a_byte_permutation(n, k, N, M, mode, kind, se
     # mask / sign / region: lane records [row_tile][super][lane = 16*(block % 4) + row % 16], cut into two halves
     # ([row_tile][super][half][lane]) when the record is a multiple of 8 bytes
     nrt, nsb, nb = tl.n_row_tiles, tl.n_super, k // 128
-    for name, off, size, rec in (("mask", "off_mask", "mask_bytes", 16), ("sign", "off_sign", "sign_bytes", 16 * N // M),
-                                 ("region", "off_region", "region_bytes", 32 * N // M)):
+    planes_rm = {name: pm.plane(name).reshape(n, -1) for name in ("mask", "sign", "region")}
+    sign_rec, region_rec = 16 * N // M, 32 * N // M
+    if padded:
+        # the same records written out slot by slot: the kept columns of a group of 8 are numbered together with the
+        # group's lowest pruned column, which takes a slot that stays zero
+        nb_ = k // 128
+        mask_bits = np.unpackbits(planes_rm["mask"], axis=1, bitorder="little")[:, :k]
+        sign_bits = np.unpackbits(planes_rm["sign"], axis=1, bitorder="little")
+        reg_bits = np.unpackbits(planes_rm["region"], axis=1, bitorder="little")
+        ps = np.zeros((n, nb_, 16 * t8), np.uint8)
+        pr = np.zeros((n, nb_, 16 * t8, 2), np.uint8)
+        for i in range(n):
+            slot = 0
+            for g in range(k // 8):
+                kept = mask_bits[i, 8 * g:8 * g + 8].astype(bool)
+                assert kept.sum() == N
+                aug = kept.copy()
+                aug[np.flatnonzero(~kept)[0]] = True
+                for c in np.flatnonzero(kept):
+                    t = t8 * (g % 16) + int(aug[:c].sum())
+                    ps[i, g // 16, t] = sign_bits[i, slot]
+                    pr[i, g // 16, t] = reg_bits[i, 2 * slot:2 * slot + 2]
+                    slot += 1
+        planes_rm["sign"] = np.packbits(ps.reshape(n, -1), axis=1, bitorder="little")
+        planes_rm["region"] = np.packbits(pr.reshape(n, -1), axis=1, bitorder="little")
+        sign_rec, region_rec = 2 * t8, 4 * t8
+        assert tl.sign_stride == sign_rec and tl.region_stride == region_rec
+    for name, off, size, rec in (("mask", "off_mask", "mask_bytes", 16), ("sign", "off_sign", "sign_bytes", sign_rec),
+                                 ("region", "off_region", "region_bytes", region_rec)):
         t = timg[getattr(tl, off):getattr(tl, off) + getattr(tl, size)]
         if rec % 8 == 0:
             t = t.reshape(nrt, nsb, 2, 4, 16, rec // 2).transpose(0, 4, 1, 3, 2, 5)      # [rt][i][sb][g][half][bytes]
@@ -214,7 +247,7 @@ def test_tile_untile_round_trip_is_a_byte_permutation(n, k, N, M, mode, kind, se
             t = t.reshape(nrt, nsb, 4, 16, rec).transpose(0, 3, 1, 2, 4)                 # [rt][i][sb][g][bytes]
         t = t.reshape(nrt * 16, nsb * 4, rec)
         rm = np.zeros((nrt * 16, nsb * 4, rec), np.uint8)
-        rm[:n, :nb] = pm.plane(name).reshape(n, -1)[:, :nb * rec].reshape(n, nb, rec)
+        rm[:n, :nb] = planes_rm[name][:, :nb * rec].reshape(n, nb, rec)
         assert (t == rm).all(), name
     # res_sign: the row strings cut into 32-bit words, transposed inside each 16-row tile
     if tl.res_bytes:
@@ -247,6 +280,15 @@ def test_tile_untile_round_trip_is_a_byte_permutation(n, k, N, M, mode, kind, se
         v8 = valid.reshape(nbk, 2, C, 8)
         assert (sel == np.where(v8, (p8 >> 3) & 7, 0x0C)).all()
         assert (bit == np.where(v8, 1 << (p8 & 7), 0)).all()
+
+
+def test_tile_of_padded_slots_rejects_a_group_with_the_wrong_number_of_kept_columns():
+    L = make_layer(16, 256, 5)
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], 5, 8)
+    pm.plane("mask")[3] |= 0xFF
+    with pytest.raises(S.StbError) as e:
+        pm.tiled()
+    assert e.value.status == S.STB_EINVAL
 
 
 def test_tile_rejects_mismatched_layouts():
