@@ -324,6 +324,17 @@ def main():
                 if not a.no_gemm and w["prefill_tokens"]:
                     gemm_all += gemm_rows(cfg, spec, pm, w["prefill_tokens"])
                 del pm
+        # the paper's other ratios (Sec. 3.3, Table 1) on the shape of workload 1: 3:8 and 5:8 run on the same kernels as
+        # 4:8 and 6:8 (their tiled image carries one unused slot per group of 8 columns)
+        from workloads.synth import LayerSpec
+        for Nk in (3, 5):
+            spec = LayerSpec(f"linear_{Nk}of8", 4096, 4096, Nk, 8, 0, "x8", 10 + Nk)
+            pm = pack_spec(S, make_layer, spec)
+            if not a.no_extra:
+                decode_all += decode_rows("1 (ratio varied)", spec, pm, [1])
+            if not a.no_gemm:
+                gemm_all += gemm_rows("1 (ratio varied)", spec, pm, [2048])
+            del pm
     if decode_all:
         result["decode_rows"] = decode_all
     if gemm_all:

@@ -190,6 +190,22 @@ int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_bitmap, stb
 int stb_pack_obc(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
                  stb_layout_t* out, int32_t n_threads);
 
+/* stb_pack on the GPU (Eq. 1-6, Sec. 3.1, Alg. 2 as in stb_pack): weights, feature norms and the salient bitmap in
+ * device memory in, the STB1 planes in device memory out, bit for bit what stb_pack writes for the same inputs.  Every
+ * float64 sum is taken in the order stb_pack takes it (a row's columns from left to right, the rows from the top
+ * down, one thread per sum); rows, columns, blocks and the break-point candidates of Alg. 2 run side by side.
+ * W: device, n x k row-major fp32, 16-byte aligned.  xnorm: device, k values >= 0.  sal_bitmap: device, k/32 words.
+ * out: row-major layout (stb_layout_sizes) bound to device memory; every byte of every plane is written.
+ * si_per_block: 0 = Standardized Importance over the whole layer (Eq. 3, as stb_pack); 1 = over each 128-column slice
+ * (as Alg. 1 calls it; the result is that of stb_pack_obc without a factor).
+ * workspace: device, at least stb_pack_device_workspace_bytes() bytes (< 0: a stb_status), 256-byte aligned.
+ * The call enqueues its kernels on `stream` and waits for them: what the kernels find (a NaN, a bitmap that does not
+ * hold cfg.n_salient columns) comes back as the status.
+ * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_ENONFINITE, STB_EHIP. */
+int64_t stb_pack_device_workspace_bytes(const stb_cfg_t* cfg, int32_t si_per_block);
+int stb_pack_device(const float* W, const float* xnorm, const uint32_t* sal_bitmap, const stb_layout_t* out,
+                    int32_t si_per_block, void* workspace, int64_t workspace_bytes, void* stream);
+
 /* Layer-wise N:M assignment (Sec. 3.3).  stb_layer_l2_norm: omega = the L2 norm of `count` host fp32 weights
  * (float64, sequential).  stb_layer_nm_assignment: for layers with norms omega[0 .. n_layers), alpha_i = omega_i /
  * sum(omega) (1 / n_layers each if the sum is 0) and N_i / M = alpha_i + (1 - alpha_i) * r_target; N_out[i] is the

@@ -67,7 +67,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 
 _LIB = None
 
-EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_pack_obc", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
+EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_pack_obc", "stb_pack_device", "stb_pack_device_workspace_bytes", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
            "stb_gemv_static", "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemv_batched_workspace_bytes", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_set_kernel_override", "stb_strerror", "stb_last_hip_error")
 
 
@@ -89,6 +89,11 @@ def _lib():
     lib.stb_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32]
     lib.stb_pack_obc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32]
     lib.stb_pack_obc.restype = C.c_int
+    lib.stb_pack_device_workspace_bytes.argtypes = [P(stb_cfg_t), C.c_int32]
+    lib.stb_pack_device_workspace_bytes.restype = C.c_int64
+    lib.stb_pack_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32, C.c_void_p, C.c_int64,
+                                    C.c_void_p]
+    lib.stb_pack_device.restype = C.c_int
     lib.stb_unpack.argtypes = [P(stb_layout_t), C.c_void_p]
     lib.stb_salient_columns.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_double, C.c_int32,
                                         C.c_void_p, P(C.c_int32)]
@@ -199,6 +204,28 @@ def stb_pack_obc(W: np.ndarray, Hc: Optional[np.ndarray], xnorm: np.ndarray, sal
         assert Hc.shape == (k, k)
     _check(_lib().stb_pack_obc(W.ctypes.data, None if Hc is None else Hc.ctypes.data, xnorm.ctypes.data,
                                sal_bitmap.ctypes.data, C.byref(layout), n_threads), "stb_pack_obc")
+
+
+def stb_pack_device_workspace_bytes(cfg: stb_cfg_t, si_per_block: bool = False) -> int:
+    r = int(_lib().stb_pack_device_workspace_bytes(C.byref(cfg), int(bool(si_per_block))))
+    if r < 0:
+        _check(r, "stb_pack_device_workspace_bytes")
+    return r
+
+
+def stb_pack_device(W, xnorm, sal_bitmap, out_dev: stb_layout_t, si_per_block: bool = False, workspace=None,
+                    stream: Optional[int] = None) -> None:
+    """W, xnorm, sal_bitmap: CUDA tensors (float32 [n][k], float32 [k], int32 [k/32]); out_dev: row-major layout bound
+    to device memory; workspace: uint8 CUDA tensor from new_device_scratch."""
+    import torch
+    cfg = out_dev.cfg
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and tuple(W.shape) == (cfg.n_out, cfg.k_in)
+    assert xnorm.is_cuda and xnorm.dtype == torch.float32 and xnorm.is_contiguous() and xnorm.numel() == cfg.k_in
+    assert sal_bitmap.is_cuda and sal_bitmap.dtype == torch.int32 and sal_bitmap.numel() == cfg.k_in // 32
+    _check(_lib().stb_pack_device(W.data_ptr(), xnorm.data_ptr(), sal_bitmap.data_ptr(), C.byref(out_dev),
+                                  int(bool(si_per_block)), workspace.data_ptr() if workspace is not None else None,
+                                  workspace.numel() if workspace is not None else 0, _stream_ptr(stream)),
+           "stb_pack_device")
 
 
 def stb_unpack(layout: stb_layout_t) -> np.ndarray:

@@ -17,7 +17,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
 
 HOST_SOURCES = ["stb_host.cpp"]
-DEVICE_SOURCES = ["stb_device.hip", "stb_fast.hip", "stb_gemv24.hip", "stb_gemm.hip"]
+DEVICE_SOURCES = ["stb_device.hip", "stb_fast.hip", "stb_gemv24.hip", "stb_gemm.hip", "stb_pack.hip"]
 
 HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-pthread"]
 DEVICE_FLAGS = ["-O3", "-std=c++17", "-fPIC", f"--offload-arch={ARCH}",

@@ -383,6 +383,31 @@ hipError_t launch_gemv_generic(const Planes& p, const void* x, void* y, int y_fp
 // ------------------------------------------------------------------------------------------------
 extern "C" int stb_last_hip_error(void) { return g_last_hip_error; }
 
+// ------------------------------------------------------------------------------------------------
+// packer on the GPU
+// ------------------------------------------------------------------------------------------------
+extern "C" int64_t stb_pack_device_workspace_bytes(const stb_cfg_t* cfg, int32_t si_per_block) {
+    stb_layout_t probe;
+    const int rc = stb_layout_sizes(cfg, &probe);       // validates cfg
+    if (rc) return rc;
+    return stb_pack_gpu_workspace(cfg, si_per_block != 0);
+}
+
+extern "C" int stb_pack_device(const float* W, const float* xnorm, const uint32_t* sal_bitmap, const stb_layout_t* out,
+                               int32_t si_per_block, void* workspace, int64_t workspace_bytes, void* stream) {
+    if (!W || !xnorm || !sal_bitmap || !out || !workspace) return STB_ENULL;
+    const int rc0 = stb_layout_check(out);
+    if (rc0) return rc0;
+    if (out->kind != STB_KIND_ROWMAJOR) return STB_EINVAL;
+    if ((uintptr_t)W % 16 || (uintptr_t)xnorm % 4 || (uintptr_t)sal_bitmap % 4 || (uintptr_t)workspace % 256) return STB_EALIGN;
+    if (workspace_bytes < stb_pack_gpu_workspace(&out->cfg, si_per_block != 0)) return STB_EINVAL;
+    int herr = 0;
+    const int rc = stb_pack_gpu(W, xnorm, sal_bitmap, out, si_per_block != 0, workspace, stream, &herr);
+    if (rc == STB_EHIP) g_last_hip_error = herr;
+    return rc;
+}
+
+
 static std::atomic<int> g_override[4] = {{0}, {0}, {0}, {0}};
 
 extern "C" int stb_kernel_override(int which) { return which >= 0 && which < 4 ? g_override[which].load(std::memory_order_relaxed) : 0; }

@@ -57,6 +57,11 @@ int stb_tiled_meta_index(const stb_layout_t* L, void* E, void* stream, int* hip_
 int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void* Y, int y_fp32, void* workspace,
                    int64_t workspace_bytes, void* stream, int* hip_err);
 int64_t stb_tiled_gemm_workspace(const stb_layout_t* L, int T);
+// The packer on the GPU (stb_pack.hip): `out` is a checked row-major layout bound to device memory, the workspace holds
+// stb_pack_gpu_workspace() bytes.  Waits for the stream before it returns.
+int64_t stb_pack_gpu_workspace(const stb_cfg_t* cfg, int per_block);
+int stb_pack_gpu(const float* W, const float* xnorm, const uint32_t* sal_bitmap, const stb_layout_t* out, int per_block,
+                 void* workspace, void* stream, int* hip_err);
 // Issue-rate probe of the matrix instructions the prefill kernels use (stb_gemm.hip); see stb_probe_mfma in stb.h.
 int stb_tiled_probe_mfma(int kind, int valu, int steps, int n_workgroups, void* sink, void* stream, int* hip_err);
 #ifdef __cplusplus

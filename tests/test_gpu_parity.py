@@ -109,6 +109,101 @@ def _tiled_ok(N, M):
 SMALL_KINDS = [(c, tiled) for c in SMALL for tiled in (False, True) if not tiled or _tiled_ok(c[2], c[3])]
 
 
+def _pack_on_device(torch, W, xnorm, sal_bitmap, N, M, mode, per_block=False):
+    """stb_pack_device on device copies of the inputs; returns the holder whose host image received the planes."""
+    n, k = W.shape
+    S_ = int(np.unpackbits(np.ascontiguousarray(sal_bitmap, dtype="<u4").view(np.uint8)).sum())
+    pm = S.PackedMatrix(S.make_cfg(n, k, N, M, S_, mode))
+    img = S.new_device_scratch(pm.host_layout.image_bytes)
+    img.fill_(0xAB)                                   # every byte of every plane has to be written
+    lay = pm.clone_layout_for(img.data_ptr(), False)
+    ws = S.new_device_scratch(S.stb_pack_device_workspace_bytes(pm.cfg, per_block))
+    ws.fill_(0xCD)
+    Wd = torch.from_numpy(np.ascontiguousarray(W, dtype=np.float32)).cuda()
+    xd = torch.from_numpy(np.ascontiguousarray(xnorm, dtype=np.float32)).cuda()
+    sd = torch.from_numpy(np.ascontiguousarray(sal_bitmap, dtype="<u4").view(np.int32)).cuda()
+    S.stb_pack_device(Wd, xd, sd, lay, per_block, ws)
+    pm.host_image[:] = img.cpu().numpy()
+    return pm
+
+
+PACK_CASES = SMALL + [(300, 2048, 4, 8, 0, "x8", 117), (300, 1280, 6, 8, 1, "t3", 118), (77, 384, 3, 8, 1, "x8", 119)]
+
+
+@pytest.mark.parametrize("case", PACK_CASES, ids=lambda c: f"{c[0]}x{c[1]}_{c[2]}of{c[3]}_m{c[4]}")
+@pytest.mark.parametrize("per_block", [False, True], ids=["layer_si", "block_si"])
+def test_device_packer_is_bit_exact_against_the_oracle(case, per_block, torch_cuda):
+    n, k, N, M, mode, kind, seed, *rest = case
+    _say(f"[case] device packer {n}x{k} {N}:{M} mode {mode} per_block {per_block}")
+    L = make_layer(n, k, seed, kind, n_salient=rest[0] if rest else None)
+    if per_block:
+        ref = O.pack_obc(L["W"], None, L["xnorm"], L["sal_bitmap"], N, M, mode)
+    else:
+        ref = O.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode)
+    pm = _pack_on_device(torch_cuda, L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode, per_block)
+    for name, v in ref.items():
+        got = pm.plane(name)
+        want = np.ascontiguousarray(v).view(np.uint8).ravel()
+        assert got.shape == want.shape, name
+        assert (got == want).all(), (name, int((got != want).sum()))
+
+
+def test_device_packer_edge_cases_and_errors(torch_cuda):
+    torch = torch_cuda
+    k = 256
+    # all-zero weights (every score ties, every scale is 0), and a block whose columns are all salient
+    Z = np.zeros((5, k), dtype=np.float32)
+    none = np.zeros(k // 32, dtype=np.uint32)
+    ones = np.ones(k, dtype=np.float32)
+    pm = _pack_on_device(torch, Z, ones, none, 2, 4, 0)
+    for name, v in O.pack(Z, ones, none, 2, 4, 0).items():
+        assert (pm.plane(name) == np.ascontiguousarray(v).view(np.uint8).ravel()).all(), name
+    L = make_layer(9, k, 23, n_salient=0)
+    bm = np.zeros(k // 32, dtype=np.uint32)
+    bm[4:8] = 0xFFFFFFFF
+    xn = L["xnorm"].copy()
+    xn[::7] = 0.0
+    for mode in (0, 1):
+        pm = _pack_on_device(torch, L["W"], xn, bm, 6, 8, mode)
+        for name, v in O.pack(L["W"], xn, bm, 6, 8, mode).items():
+            assert (pm.plane(name) == np.ascontiguousarray(v).view(np.uint8).ravel()).all(), (mode, name)
+    # what the kernels find comes back as a status
+    L = make_layer(20, k, 24)
+    bad = L["W"].copy()
+    bad[7, 130] = np.nan
+    with pytest.raises(S.StbError) as e:
+        _pack_on_device(torch, bad, L["xnorm"], L["sal_bitmap"], 4, 8, 0)
+    assert e.value.status == S.STB_ENONFINITE
+    xb = L["xnorm"].copy()
+    xb[3] = -1.0
+    with pytest.raises(S.StbError) as e:
+        _pack_on_device(torch, L["W"], xb, L["sal_bitmap"], 4, 8, 0)
+    assert e.value.status == S.STB_ENONFINITE
+    # a bitmap that does not hold cfg.n_salient columns
+    pm = S.PackedMatrix(S.make_cfg(20, k, 4, 8, 5, 0))
+    img = S.new_device_scratch(pm.host_layout.image_bytes)
+    lay = pm.clone_layout_for(img.data_ptr(), False)
+    ws = S.new_device_scratch(S.stb_pack_device_workspace_bytes(pm.cfg))
+    Wd = torch.from_numpy(L["W"]).cuda()
+    xd = torch.from_numpy(L["xnorm"]).cuda()
+    sd = torch.from_numpy(L["sal_bitmap"].view(np.int32)).cuda()
+    with pytest.raises(S.StbError) as e:
+        S.stb_pack_device(Wd, xd, sd, lay, False, ws)
+    assert e.value.status == S.STB_EINVAL
+    with pytest.raises(S.StbError) as e:
+        S.stb_pack_device(Wd, xd, sd, lay, False, ws[256:])
+    assert e.value.status == S.STB_EINVAL                     # workspace too small
+    with pytest.raises(S.StbError) as e:
+        S.stb_pack_device(Wd, xd, sd, lay, False, ws[8:])
+    assert e.value.status == S.STB_EALIGN
+    tl = S.stb_tiled_sizes(pm.cfg)
+    timg = S.new_device_scratch(tl.image_bytes)
+    S.stb_layout_bind(tl, timg.data_ptr())
+    with pytest.raises(S.StbError) as e:
+        S.stb_pack_device(Wd, xd, sd, tl, False, ws)
+    assert e.value.status == S.STB_EINVAL                     # the packer writes the row-major order
+
+
 @pytest.fixture(scope="module", params=SMALL_KINDS,
                 ids=lambda c: f"{c[0][0]}x{c[0][1]}_{c[0][2]}of{c[0][3]}_m{c[0][4]}{'_s%d' % c[0][7] if len(c[0]) > 7 else ''}_{'tiled' if c[1] else 'rowmajor'}")
 def small_case(request, torch_cuda):
@@ -496,13 +591,22 @@ def test_full_size_layer(cfg, idx, torch_cuda):
     digests = json.load(open(GOLDEN)) if os.path.exists(GOLDEN) else {}
     L = make_layer(spec.n, spec.k, spec.seed, spec.salient_kind)
     pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], spec.N, spec.M, spec.region_mode)
-    del L
     if key not in digests:
         pytest.skip(f"no oracle digest stored for {key}")
     for name, _, _ in S.PLANE_FIELDS:
         assert hashlib.sha256(pm.plane(name).tobytes()).hexdigest() == digests[key][name], name
     assert pm.packed_bytes == digests[key]["total_bytes"]
     _say("[step] packed planes match the oracle digests")
+    _say("[step] stb_pack_device")
+    import time
+    t0 = time.time()
+    dp = _pack_on_device(torch, L["W"], L["xnorm"], L["sal_bitmap"], spec.N, spec.M, spec.region_mode)
+    _say(f"       {time.time() - t0:.2f} s with the copies to and from the device")
+    for name, _, _ in S.PLANE_FIELDS:
+        assert hashlib.sha256(dp.plane(name).tobytes()).hexdigest() == digests[key][name], ("device packer", name)
+    del L, dp
+    torch.cuda.empty_cache()
+    _say("[step] the device packer's planes match the oracle digests")
 
     What = O.unpack(_oracle_planes_from(pm), spec.n, spec.k, spec.N, spec.M)
     tiled = _tiled_ok(spec.N, spec.M)
