@@ -113,11 +113,45 @@ def tiled_ok(spec):
     return (8 * spec.N) % spec.M == 0 and (8 * spec.N // spec.M) in (3, 4, 5, 6)
 
 
-def pack_spec(S, make_layer, spec):
-    t0 = time.time()
+PACK_ROWS = []          # (workload layer, host seconds, device seconds) of layers packed both ways
+
+
+def pack_on_device(S, torch, L, spec, pm):
+    """stb_pack_device on the same inputs; returns the median time of three runs and checks the bytes against the
+    host packer's."""
+    img = S.new_device_scratch(pm.host_layout.image_bytes)
+    lay = pm.clone_layout_for(img.data_ptr(), False)
+    ws = S.new_device_scratch(S.stb_pack_device_workspace_bytes(pm.cfg))
+    Wd = torch.from_numpy(L["W"]).cuda()
+    xd = torch.from_numpy(L["xnorm"]).cuda()
+    sd = torch.from_numpy(np.ascontiguousarray(L["sal_bitmap"], dtype="<u4").view(np.int32)).cuda()
+    times = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        S.stb_pack_device(Wd, xd, sd, lay, False, ws)          # waits for its stream
+        times.append(time.perf_counter() - t0)
+    got = img.cpu().numpy()
+    same = all(bool((got[getattr(pm.host_layout, off):getattr(pm.host_layout, off) + getattr(pm.host_layout, size)]
+                     == pm.plane(name)).all()) for name, off, size in S.PLANE_FIELDS)
+    del img, ws, Wd, xd, sd
+    torch.cuda.empty_cache()
+    return statistics.median(times), same
+
+
+def pack_spec(S, make_layer, spec, torch=None):
     L = make_layer(spec.n, spec.k, spec.seed, spec.salient_kind)
+    t0 = time.time()
     pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], spec.N, spec.M, spec.region_mode)
-    log(f"packed {spec.name} {spec.n}x{spec.k} {spec.N}:{spec.M}: {pm.packed_bytes / 1e6:.2f} MB in {time.time() - t0:.1f} s")
+    host_s = time.time() - t0
+    if torch is not None:
+        dev_s, same = pack_on_device(S, torch, L, spec, pm)
+        PACK_ROWS.append(dict(layer=spec.name, n=spec.n, k=spec.k, nm=f"{spec.N}:{spec.M}",
+                              host_seconds=round(host_s, 3), host_threads=os.cpu_count(),
+                              device_seconds=round(dev_s, 4), weights_gbs_device=round(4.0 * spec.n * spec.k / dev_s / 1e9, 1),
+                              same_bytes_as_host=same))
+        log("pack row:", PACK_ROWS[-1])
+    log(f"packed {spec.name} {spec.n}x{spec.k} {spec.N}:{spec.M}: {pm.packed_bytes / 1e6:.2f} MB in {host_s:.1f} s")
     return pm
 
 
@@ -159,7 +193,7 @@ def main():
     # ---------------- headline: decode step over workload 5 at batch 1 ----------------
     wl = WORKLOADS[5]
     B = 1
-    packed5 = {spec.name: pack_spec(S, make_layer, spec) for spec in wl["layers"]}
+    packed5 = {spec.name: pack_spec(S, make_layer, spec, None if a.no_extra else torch) for spec in wl["layers"]}
     specs5 = {spec.name: spec for spec in wl["layers"]}
     step_bytes = sum(pm.packed_bytes for pm in packed5.values())
     copies = max(2, int(np.ceil(POOL_BYTES / step_bytes)))
@@ -335,6 +369,9 @@ def main():
             if not a.no_gemm:
                 gemm_all += gemm_rows("1 (ratio varied)", spec, pm, [2048])
             del pm
+    if PACK_ROWS:
+        result["pack_rows"] = {"rows": PACK_ROWS, "note": "stb_pack (host threads) and stb_pack_device (fp32 weights already "
+                               "in HBM, the call waits for its kernels) on the layers of workload 5; same bytes"}
     if decode_all:
         result["decode_rows"] = decode_all
     if gemm_all:

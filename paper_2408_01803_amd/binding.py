@@ -79,6 +79,13 @@ def _lib():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                           "(or paper_2408_01803_amd/build.py) first")
+    # The device tensors that callers pass come from PyTorch, whose wheel carries its own copy of the HIP runtime.  It
+    # has to be in the process before this library is, so that the library's kernels resolve to that same runtime
+    # (loaded the other way round, two runtimes coexist and every launch fails with "no device").
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     P = C.POINTER
     lib.stb_layout_sizes.argtypes = [P(stb_cfg_t), P(stb_layout_t)]
