@@ -69,6 +69,9 @@ def build_pool(S, torch, pm, pool_bytes, tiled=True, min_copies=2):
     return buf, layouts
 
 
+USE_GRAPHS = True       # --no-graph: every timed launch comes from the host (what a counter run wants to see)
+
+
 def timed(torch, fn, reps, warm=3, rounds=3, graph=False):
     """Median and fastest average time of fn() in microseconds over `rounds` runs of `reps` calls, events on the
     stream the calls are launched on.  graph=True: the `reps` calls are captured once in a HIP graph and each run is
@@ -77,7 +80,7 @@ def timed(torch, fn, reps, warm=3, rounds=3, graph=False):
         fn(0)
     torch.cuda.synchronize()
     out = []
-    if graph:
+    if graph and USE_GRAPHS:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -182,6 +185,8 @@ def main():
     import paper_2408_01803_amd as S
     from workloads import WORKLOADS, make_layer, make_x
 
+    global USE_GRAPHS
+    USE_GRAPHS = not a.no_graph
     if not os.path.exists(S.LIB_PATH):
         sys.exit("bench.py: libstb.so is missing; run __graft_entry__.build() first")
     assert torch.cuda.is_available(), "bench.py needs a GPU"

@@ -100,7 +100,7 @@ __global__ void k_col_sums(PK a) {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= a.k) return;
     double s = 0.0;
-#pragma unroll 8
+#pragma unroll 32
     for (int i = 0; i < a.n; i++) s += fabs((double)a.W[(size_t)i * a.k + j]);
     a.cs[j] = s;
     const float x = a.xnorm[j];
@@ -113,7 +113,7 @@ __global__ void k_total(PK a) {
     const int sc = blockIdx.x * blockDim.x + threadIdx.x;
     if (sc >= a.nbS) return;
     double tot = 0.0;
-#pragma unroll 8
+#pragma unroll 32
     for (int i = 0; i < a.n; i++) tot += a.rowacc[(size_t)i * a.nbS + sc];
     const double cnt = (double)a.n * (double)(a.per_block ? STB_BLOCK : a.k);
     if (MODE == 0) a.stats[2 * sc] = tot / cnt;
@@ -165,14 +165,21 @@ __global__ void k_block_salient(PK a) {
     double so = 0.0;
     int co = 0;
     uint32_t mx = 0, members = 0;
-    for (int c = 0; c < STB_BLOCK; c++) {
-        if (!((m[c >> 5] >> (c & 31)) & 1u)) continue;
-        const float wf = w[c];
-        if ((sb[c >> 5] >> (c & 31)) & 1u) { so += fabs((double)wf); co++; }
-        else {
-            const uint32_t bits = __float_as_uint(fabsf(wf));      // magnitudes order like their bit patterns
-            mx = bits > mx ? bits : mx;
-            members++;
+    const float4* w4 = reinterpret_cast<const float4*>(w);          // 16 bytes per load: a cache line serves 8 loads, not 32
+    for (int c4 = 0; c4 < STB_BLOCK / 4; c4++) {
+        const float4 v = w4[c4];
+        const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int c = 4 * c4 + u;
+            if (!((m[c >> 5] >> (c & 31)) & 1u)) continue;
+            const float wf = e[u];
+            if ((sb[c >> 5] >> (c & 31)) & 1u) { so += fabs((double)wf); co++; }
+            else {
+                const uint32_t bits = __float_as_uint(fabsf(wf));      // magnitudes order like their bit patterns
+                mx = bits > mx ? bits : mx;
+                members++;
+            }
         }
     }
     const uint16_t ao16 = stb_f64_to_f16_bits(co > 0 ? so / (double)co : 0.0);
@@ -264,8 +271,8 @@ __global__ void k_pick_breakpoints(PK a, int q_first) {
         double s = 0.0;
         if (!skip) {
             const double* e = a.err + (size_t)qb * a.n * CAND + t;
-#pragma unroll 8
-            for (int i = 0; i < a.n; i++) s += e[(size_t)i * CAND];
+#pragma unroll 32
+            for (int i = 0; i < a.n; i++) s += e[(size_t)i * CAND];           // the loads run ahead, the additions stay in order
         }
         tot[t] = s;
     }
@@ -301,11 +308,15 @@ __global__ void k_select_hist(PK a, int pass) {
     const uint8_t* mrow = a.mask + (size_t)i * a.mask_stride + 16 * q;
     const int shift = 24 - 8 * pass;
     const uint32_t pre0 = a.sel[4 * q + 0], pre1 = a.sel[4 * q + 2];
+    const float4* w4 = reinterpret_cast<const float4*>(w);
     for (int b = 0; b < 16; b++) {
         const uint32_t keep = mrow[b] & ~((a.sal[4 * q + (b >> 2)] >> (8 * (b & 3))) & 0xFFu);
+        const float4 v0 = w4[2 * b], v1 = w4[2 * b + 1];
+        const float e[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
         for (int c = 0; c < 8; c++) {
             if (!((keep >> c) & 1u)) continue;
-            const uint32_t bits = __float_as_uint(fabsf(w[8 * b + c]));
+            const uint32_t bits = __float_as_uint(fabsf(e[c]));
             const uint32_t hi = pass == 0 ? 0u : bits >> (shift + 8), dig = (bits >> shift) & 255u;
             if (hi == pre0) atomicAdd(a.hist + ((size_t)q * 2 + 0) * 256 + dig, 1u);
             if (hi == pre1) atomicAdd(a.hist + ((size_t)q * 2 + 1) * 256 + dig, 1u);
@@ -351,11 +362,15 @@ __global__ void k_assign(PK a) {
     int c3[3] = {0, 0, 0};
     uint32_t sacc = 0, racc = 0;        // bits of the sign byte / id byte being filled
     int slot = 0;
+    const float4* w4 = reinterpret_cast<const float4*>(w);
     for (int b = 0; b < 16; b++) {
         const uint32_t mb = mrow[b], sb = (a.sal[4 * q + (b >> 2)] >> (8 * (b & 3))) & 0xFFu;
+        const float4 v0 = w4[2 * b], v1 = w4[2 * b + 1];
+        const float e[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
         for (int c = 0; c < 8; c++) {
             if (!((mb >> c) & 1u)) continue;
-            const float wf = w[8 * b + c];
+            const float wf = e[c];
             uint32_t id = 3;
             if (!((sb >> c) & 1u)) {
                 const double av = fabs((double)wf);
@@ -414,9 +429,9 @@ WsPlan plan_workspace(const stb_cfg_t& c, int per_block) {
     p.p12 = o; o += up256(nb * 16);
     p.hist = o; o += up256(nb * 2 * 256 * 4);
     p.sel = o; o += up256(nb * 16);
-    // candidate errors: as many blocks at once as fit into 256 MiB, at least one
+    // candidate errors: as many blocks at once as fit into 1 GiB, at least one
     const int64_t per_block_bytes = n * CAND * 8;
-    int64_t batch = (256ll << 20) / per_block_bytes;
+    int64_t batch = (1ll << 30) / per_block_bytes;
     batch = batch < 1 ? 1 : (batch > nb ? nb : batch);
     p.batch = (int)batch;
     p.err = o; o += up256(c.region_mode == 0 ? batch * per_block_bytes : 0);
