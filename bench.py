@@ -42,8 +42,15 @@ ROW_POOL_BYTES = 600 << 20     # per-layer rotation of the breakdown rows: more 
 # HBM bytes per decode step / per prefill launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE on this command (offline
 # runs, scaled by what the same counters read for a copy of known size); the summaries under profiles/ give the runs.
 # None = not measured for the build that is checked in.
-MEASURED_DECODE_TRAFFIC_BYTES_PER_LAUNCH = None
-MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH = None
+# Decode: 89.56 MB read + 0.26 MB written per launch, average of the step's four launches
+# (profiles/gemv24_group_kernel_workload5_decode_b1.md).  Prefill: bytes read + written per launch of the cases that were
+# measured, keyed by (T, n, k) (profiles/gemm_kernels_workloads4_5_prefill.md).
+MEASURED_DECODE_TRAFFIC_BYTES_PER_LAUNCH = 89_820_000
+MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH = {
+    (2048, 4096, 4096): 89_200_000, (8192, 4096, 4096): 421_500_000, (2048, 11008, 4096): 245_900_000,
+    (8192, 11008, 4096): 1_151_000_000, (2048, 8192, 8192): 387_000_000, (2048, 1024, 8192): 75_100_000,
+    (2048, 28672, 8192): 1_164_600_000, (2048, 8192, 28672): 1_092_100_000,
+}
 
 # The calls of one decode step over workload 5, by layer name: layers of a group share their input vector.
 DECODE_GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))
@@ -289,7 +296,7 @@ def main():
                    "ms_per_step_host_launches": round(eager_ms_per_step, 4)},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_DECODE_TRAFFIC_BYTES_PER_LAUNCH,
-                     "kernel": "gemv24_kernel (stb_gemv_batched on tiled layouts)", "us_per_launch": round(launch_us, 2),
+                     "kernel": "gemv24_group_kernel (stb_gemv_batched on tiled layouts)", "us_per_launch": round(launch_us, 2),
                      "algorithmic_bytes_per_launch": int(algo_per_step / launches_per_step),
                      "launches_per_step": launches_per_step},
     }
@@ -385,7 +392,7 @@ def main():
         result["gemm"] = {"rows": gemm_all,
                           "roofline": {"bound": "mfma", "achieved": best["tflops"], "peak": MFMA_F16_PEAK_TFLOPS,
                                        "unit": "TFLOP/s", "frac": best["frac_of_f16_mfma_peak"],
-                                       "traffic": MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH,
+                                       "traffic": MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH.get((best["T"], best["n"], best["k"])),
                                        "kernel": best["kernel"] + " (stb_gemm), flops = 2*T*n*k executed on the "
                                                  f"dequantised tile; best dense-instruction row: workload {best['workload']} "
                                                  f"{best['layer']} T={best['T']}"}}
