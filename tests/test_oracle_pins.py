@@ -464,6 +464,25 @@ def test_worked_example_with_salient_columns_from_golden_file():
     assert (What == _decode_bitwise(P, 2, 128, 2, 4)).all()
 
 
+def test_salient_weights_do_not_move_the_break_points_or_the_region_scales():
+    # Alg. 1 hands only the columns outside the salient set to NonSalientAwareQuant, and Eq. 6 averages region members:
+    # rescaling the salient weights must leave both alone
+    n, k = 24, 256
+    L = make_layer(n, k, 64, "x8", n_salient=14)
+    sal = np.zeros(k, dtype=bool)
+    sal[L["sal_cols"]] = True
+    # 8:8 keeps every weight, so the mask cannot move with the importance scores
+    P0, d0 = O.pack(L["W"], L["xnorm"], L["sal_bitmap"], 8, 8, 0, return_debug=True)
+    W2 = L["W"].copy()
+    W2[:, sal] *= np.float32(3.0)
+    P1, d1 = O.pack(W2, L["xnorm"], L["sal_bitmap"], 8, 8, 0, return_debug=True)
+    assert d0["mask"].all() and d1["mask"].all()
+    assert np.array_equal(d0["breakpoints"], d1["breakpoints"])
+    assert np.array_equal(P0["scales"][:, :, :3], P1["scales"][:, :, :3])
+    assert np.array_equal(d0["ids"], d1["ids"])
+    assert not np.array_equal(P0["scales"][:, :, 3], P1["scales"][:, :, 3])
+
+
 def _f16_through_f32(v):
     return float(np.float16(np.float32(v)))
 
