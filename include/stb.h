@@ -161,6 +161,12 @@ int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out);
 int stb_tile(const stb_layout_t* src_rowmajor, stb_layout_t* dst_tiled);
 int stb_untile(const stb_layout_t* src_tiled, stb_layout_t* dst_rowmajor);
 
+/* stb_tile with both images in device memory (say, the output of stb_pack_device): same bytes as stb_tile, and
+ * dst->max_sal_block / max_sal_half are set in the caller's struct.  The small tables that depend on the salient
+ * bitmap alone are made on the host (the bitmap is copied there and the tables back), the planes are permuted by
+ * kernels; the call waits for `stream` before it returns.  Errors: as stb_tile, and STB_EHIP. */
+int stb_tile_device(const stb_layout_t* src_rowmajor_dev, stb_layout_t* dst_tiled_dev, void* stream);
+
 /* Structured binarisation of one linear layer on the host (Alg. 1 without its Hessian steps: the salient
  * column set is an input and there is no error compensation between blocks; stb_pack_obc has them):
  *   Standardized Importance over the whole layer (Eq. 3) -> N:M mask (ties keep the lower column) ->

@@ -67,7 +67,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 
 _LIB = None
 
-EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_pack", "stb_pack_obc", "stb_pack_device", "stb_pack_device_workspace_bytes", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
+EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_tile_device", "stb_pack", "stb_pack_obc", "stb_pack_device", "stb_pack_device_workspace_bytes", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
            "stb_gemv_static", "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemv_batched_workspace_bytes", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_set_kernel_override", "stb_strerror", "stb_last_hip_error")
 
 
@@ -93,6 +93,8 @@ def _lib():
     lib.stb_tiled_sizes.argtypes = [P(stb_cfg_t), P(stb_layout_t)]
     lib.stb_tile.argtypes = [P(stb_layout_t), P(stb_layout_t)]
     lib.stb_untile.argtypes = [P(stb_layout_t), P(stb_layout_t)]
+    lib.stb_tile_device.argtypes = [P(stb_layout_t), P(stb_layout_t), C.c_void_p]
+    lib.stb_tile_device.restype = C.c_int
     lib.stb_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32]
     lib.stb_pack_obc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32]
     lib.stb_pack_obc.restype = C.c_int
@@ -186,6 +188,11 @@ def stb_tile(src_rowmajor: stb_layout_t, dst_tiled: stb_layout_t) -> None:
 
 def stb_untile(src_tiled: stb_layout_t, dst_rowmajor: stb_layout_t) -> None:
     _check(_lib().stb_untile(C.byref(src_tiled), C.byref(dst_rowmajor)), "stb_untile")
+
+
+def stb_tile_device(src_rowmajor_dev: stb_layout_t, dst_tiled_dev: stb_layout_t, stream: Optional[int] = None) -> None:
+    _check(_lib().stb_tile_device(C.byref(src_rowmajor_dev), C.byref(dst_tiled_dev), C.c_void_p(_stream_ptr(stream))),
+           "stb_tile_device")
 
 
 def stb_pack(W: np.ndarray, xnorm: np.ndarray, sal_bitmap: np.ndarray, layout: stb_layout_t,

@@ -386,6 +386,24 @@ extern "C" int stb_last_hip_error(void) { return g_last_hip_error; }
 // ------------------------------------------------------------------------------------------------
 // packer on the GPU
 // ------------------------------------------------------------------------------------------------
+extern "C" int stb_tile_device(const stb_layout_t* src, stb_layout_t* dst, void* stream) {
+    int rc = stb_layout_check(src);
+    if (rc) return rc;
+    if (!dst) return STB_ENULL;
+    dst->max_sal_block = 0;
+    dst->max_sal_half = 0;
+    rc = stb_layout_check(dst);
+    if (rc) return rc;
+    const stb_cfg_t &a = src->cfg, &b = dst->cfg;
+    if (src->kind != STB_KIND_ROWMAJOR || dst->kind != STB_KIND_TILED || a.n_out != b.n_out || a.k_in != b.k_in ||
+        a.N != b.N || a.M != b.M || a.block != b.block || a.n_salient != b.n_salient)
+        return STB_EINVAL;
+    int herr = 0;
+    rc = stb_tile_gpu(src, dst, stream, &herr);
+    if (rc == STB_EHIP) g_last_hip_error = herr;
+    return rc;
+}
+
 extern "C" int64_t stb_pack_device_workspace_bytes(const stb_cfg_t* cfg, int32_t si_per_block) {
     stb_layout_t probe;
     const int rc = stb_layout_sizes(cfg, &probe);       // validates cfg

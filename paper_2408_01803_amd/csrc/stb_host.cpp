@@ -341,6 +341,25 @@ int fill_sal_tab(const stb_layout_t* tl, const uint32_t* bitmap, int k, const ui
 
 }  // namespace
 
+// The derived tables of the tiled order from the salient bitmap alone (host arrays): bitmap and prefix padded to whole
+// superblocks, the table of salient columns, the two maxima.  Shared by stb_tile and the device tiling.
+extern "C" int stb_host_tiled_tables(const stb_layout_t* tl, const uint32_t* bitmap, const uint32_t* prefix,
+                                     uint32_t* bitmap_out, uint32_t* prefix_out, uint32_t* sal_tab_out, int* max_block,
+                                     int* max_half) {
+    const int nb = tl->n_blocks, nsb = tl->n_super, k = tl->cfg.k_in;
+    std::memset(bitmap_out, 0, (size_t)tl->salmap_bytes);
+    std::memcpy(bitmap_out, bitmap, (size_t)k / 8);
+    for (int q = 0; q <= nsb * 4; q++) prefix_out[q] = prefix[std::min(q, nb)];
+    *max_block = 0;
+    *max_half = 0;
+    if (tl->cfg.n_salient) {
+        stb_layout_t tmp = *tl;
+        tmp.sal_tab = sal_tab_out;
+        *max_block = fill_sal_tab(&tmp, bitmap, k, prefix_out, max_half);
+    }
+    return STB_OK;
+}
+
 extern "C" int stb_tile(const stb_layout_t* src, stb_layout_t* dst) {
     int rc = stb_layout_check(src);
     if (rc) return rc;

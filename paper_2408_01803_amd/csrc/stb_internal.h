@@ -57,6 +57,12 @@ int stb_tiled_meta_index(const stb_layout_t* L, void* E, void* stream, int* hip_
 int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void* Y, int y_fp32, void* workspace,
                    int64_t workspace_bytes, void* stream, int* hip_err);
 int64_t stb_tiled_gemm_workspace(const stb_layout_t* L, int T);
+// Host: the derived tables of the tiled order (padded bitmap and prefix, table of salient columns, maxima) from the
+// row-major bitmap and prefix; the output arrays hold tl->salmap_bytes, tl->salprefix_bytes, tl->saltab_bytes.
+int stb_host_tiled_tables(const stb_layout_t* tl, const uint32_t* bitmap, const uint32_t* prefix, uint32_t* bitmap_out,
+                          uint32_t* prefix_out, uint32_t* sal_tab_out, int* max_block, int* max_half);
+// stb_tile with both images in device memory (stb_pack.hip); sets dst->max_sal_block / max_sal_half; waits for the stream.
+int stb_tile_gpu(const stb_layout_t* src, stb_layout_t* dst, void* stream, int* hip_err);
 // The packer on the GPU (stb_pack.hip): `out` is a checked row-major layout bound to device memory, the workspace holds
 // stb_pack_gpu_workspace() bytes.  Waits for the stream before it returns.
 int64_t stb_pack_gpu_workspace(const stb_cfg_t* cfg, int per_block);

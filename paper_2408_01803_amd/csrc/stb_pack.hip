@@ -10,6 +10,8 @@
 // loop.  Division and square root of float64 are correctly rounded on this hardware, as on the host.
 #include <hip/hip_runtime.h>
 
+#include <vector>
+
 #include "stb_f16.h"
 #include "stb_internal.h"
 
@@ -517,5 +519,150 @@ extern "C" int stb_pack_gpu(const float* W, const float* xnorm, const uint32_t* 
     if (e != hipSuccess) return STB_EHIP;
     if (status & ST_NONFINITE) return STB_ENONFINITE;
     if (status & ~ST_NONFINITE) return STB_EINVAL;
+    return STB_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// stb_tile in device memory: the record permutation of the host routine, one thread per (row, block)
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+static __device__ uint32_t tile_status;
+
+struct TK {
+    const uint8_t* rmask; const uint8_t* rsign; const uint8_t* rreg; const uint16_t* rscales; const uint16_t* rres_scale;
+    const uint32_t* rres_sign;
+    uint8_t* tmask; uint8_t* tsign; uint8_t* treg; uint16_t* tscales; uint16_t* tres_scale; uint32_t* tres_sign;
+    int64_t rmask_stride, rsign_stride, rreg_stride, rres_stride;
+    int n, nb, nsb, SB, RB, RSB, RRB, padded, t8, n8, res_words;
+    uint32_t* status;
+};
+
+// bytes [0, bytes) of a record: whole, or cut in two halves stored [tile][half][lane] when it is a multiple of 8 bytes
+__device__ inline void put_record(uint8_t* plane, int64_t tile, int lane, const uint8_t* src, int bytes) {
+    if (bytes % 8 == 0) {
+        const int hb = bytes / 2;
+        for (int h = 0; h < 2; h++) {
+            uint8_t* dst = plane + tile * 64 * bytes + (int64_t)h * 32 * bytes + (int64_t)lane * hb;
+            for (int b = 0; b < hb; b++) dst[b] = src[h * hb + b];
+        }
+    } else {
+        uint8_t* dst = plane + (tile * 64 + lane) * bytes;
+        for (int b = 0; b < bytes; b++) dst[b] = src[b];
+    }
+}
+
+__global__ void k_tile_records(TK a) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)a.n * a.nb) return;
+    const int r = (int)(idx / a.nb), q = (int)(idx % a.nb);
+    const int64_t tile = (int64_t)(r / 16) * a.nsb + q / 4;
+    const int lane = 16 * (q % 4) + (r % 16);
+    const uint8_t* mrow = a.rmask + (int64_t)r * a.rmask_stride + 16 * q;
+    put_record(a.tmask, tile, lane, mrow, 16);
+    if (!a.padded) {
+        put_record(a.tsign, tile, lane, a.rsign + (int64_t)r * a.rsign_stride + (int64_t)a.SB * q, a.SB);
+        put_record(a.treg, tile, lane, a.rreg + (int64_t)r * a.rreg_stride + (int64_t)a.RB * q, a.RB);
+    } else {
+        // 3 or 5 kept of 8: slot s of the block -> slot t8 * group + rank of its column among the group's kept columns
+        // and the lowest pruned one
+        const uint8_t* srow = a.rsign + (int64_t)r * a.rsign_stride + (int64_t)a.RSB * q;
+        const uint8_t* grow = a.rreg + (int64_t)r * a.rreg_stride + (int64_t)a.RRB * q;
+        uint8_t ps[12], pr[24];
+        for (int b = 0; b < 12; b++) ps[b] = 0;
+        for (int b = 0; b < 24; b++) pr[b] = 0;
+        int slot = 0;
+        bool bad = false;
+        for (int g = 0; g < 16; g++) {
+            const unsigned mb = mrow[g];
+            if (__popc(mb) != a.n8) { bad = true; break; }
+            const unsigned aug = mb | (~mb & (mb + 1u));
+            for (int c = 0; c < 8; c++) {
+                if (!((mb >> c) & 1u)) continue;
+                const int t = a.t8 * g + __popc(aug & ((1u << c) - 1u));
+                ps[t >> 3] |= (uint8_t)(((srow[slot >> 3] >> (slot & 7)) & 1u) << (t & 7));
+                pr[t >> 2] |= (uint8_t)(((grow[slot >> 2] >> ((slot & 3) * 2)) & 3u) << ((t & 3) * 2));
+                slot++;
+            }
+        }
+        if (bad) { atomicOr(a.status, 4u); return; }
+        put_record(a.tsign, tile, lane, ps, a.SB);
+        put_record(a.treg, tile, lane, pr, a.RB);
+    }
+    const int64_t rec = tile * 64 + lane;
+    for (int u = 0; u < 4; u++) a.tscales[rec * 4 + u] = a.rscales[((int64_t)r * a.nb + q) * 4 + u];
+    a.tres_scale[rec] = a.rres_scale[(int64_t)r * a.nb + q];
+}
+
+// res_sign: the row strings cut into 32-bit words and transposed inside each 16-row tile; one thread per (row, word)
+__global__ void k_tile_res(TK a) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)a.n * a.res_words) return;
+    const int r = (int)(idx / a.res_words), w = (int)(idx % a.res_words);
+    a.tres_sign[((int64_t)(r / 16) * a.res_words + w) * 16 + r % 16] = a.rres_sign[(int64_t)r * (a.rres_stride / 4) + w];
+}
+
+}  // namespace
+
+// src: checked row-major layout, dst: checked tiled layout of the same cfg, both bound to device memory.
+extern "C" int stb_tile_gpu(const stb_layout_t* src, stb_layout_t* dst, void* stream, int* hip_err) {
+    const hipStream_t st = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    auto ok = [&](hipError_t r) { if (e == hipSuccess && r != hipSuccess) e = r; return e == hipSuccess; };
+    const int k = src->cfg.k_in, nb = src->n_blocks;
+    // the derived tables depend on the salient bitmap only: they are made on the host and copied
+    std::vector<uint32_t> bitmap((size_t)k / 32), prefix((size_t)nb + 1);
+    ok(hipMemcpyAsync(bitmap.data(), src->sal_bitmap, (size_t)k / 8, hipMemcpyDeviceToHost, st));
+    ok(hipMemcpyAsync(prefix.data(), src->sal_block_prefix, 4 * ((size_t)nb + 1), hipMemcpyDeviceToHost, st));
+    ok(hipStreamSynchronize(st));
+    if (e != hipSuccess) { *hip_err = (int)e; return STB_EHIP; }
+    std::vector<uint32_t> bm_out((size_t)dst->salmap_bytes / 4), pf_out((size_t)dst->salprefix_bytes / 4),
+        tab((size_t)dst->saltab_bytes / 4 + 1, 0u);
+    int mx = 0, mh = 0;
+    stb_host_tiled_tables(dst, bitmap.data(), prefix.data(), bm_out.data(), pf_out.data(), tab.data(), &mx, &mh);
+    ok(hipMemcpyAsync(dst->sal_bitmap, bm_out.data(), (size_t)dst->salmap_bytes, hipMemcpyHostToDevice, st));
+    ok(hipMemcpyAsync(dst->sal_block_prefix, pf_out.data(), (size_t)dst->salprefix_bytes, hipMemcpyHostToDevice, st));
+    if (dst->saltab_bytes) ok(hipMemcpyAsync(dst->sal_tab, tab.data(), (size_t)dst->saltab_bytes, hipMemcpyHostToDevice, st));
+    // padding rows and blocks of the planes are zero
+    ok(hipMemsetAsync(dst->mask, 0, (size_t)dst->mask_bytes, st));
+    ok(hipMemsetAsync(dst->sign, 0, (size_t)dst->sign_bytes, st));
+    ok(hipMemsetAsync(dst->region, 0, (size_t)dst->region_bytes, st));
+    ok(hipMemsetAsync(dst->scales, 0, (size_t)dst->scales_bytes, st));
+    ok(hipMemsetAsync(dst->res_scale, 0, (size_t)dst->res_scale_bytes, st));
+    if (dst->res_bytes) ok(hipMemsetAsync(dst->res_sign, 0, (size_t)dst->res_bytes, st));
+    TK a;
+    a.rmask = (const uint8_t*)src->mask; a.rsign = (const uint8_t*)src->sign; a.rreg = (const uint8_t*)src->region;
+    a.rscales = src->scales; a.rres_scale = src->res_scale; a.rres_sign = (const uint32_t*)src->res_sign;
+    a.tmask = (uint8_t*)dst->mask; a.tsign = (uint8_t*)dst->sign; a.treg = (uint8_t*)dst->region;
+    a.tscales = dst->scales; a.tres_scale = dst->res_scale; a.tres_sign = (uint32_t*)dst->res_sign;
+    a.rmask_stride = src->mask_stride; a.rsign_stride = src->sign_stride; a.rreg_stride = src->region_stride;
+    a.rres_stride = src->res_stride;
+    a.n = src->cfg.n_out; a.nb = nb; a.nsb = dst->n_super;
+    a.SB = (int)dst->sign_stride; a.RB = (int)dst->region_stride;
+    a.padded = stb_tiled_padded(&src->cfg); a.t8 = stb_tiled_slots(&src->cfg); a.n8 = 8 * src->cfg.N / src->cfg.M;
+    a.RSB = 2 * a.n8; a.RRB = 4 * a.n8;
+    a.res_words = (int)(src->res_stride / 4);
+    // what the kernel finds (a mask byte with the wrong number of bits in a padded layout) comes back through a word
+    // of the library's own device memory; calls that overlap on one GPU share it
+    uint32_t* status_dev = nullptr;
+    ok(hipGetSymbolAddress((void**)&status_dev, HIP_SYMBOL(tile_status)));
+    if (e != hipSuccess) { *hip_err = (int)e; return STB_EHIP; }
+    ok(hipMemsetAsync(status_dev, 0, 4, st));
+    a.status = status_dev;
+    const int64_t recs = (int64_t)a.n * a.nb;
+    hipLaunchKernelGGL(k_tile_records, dim3((unsigned)((recs + 255) / 256)), dim3(256), 0, st, a);
+    if (a.res_words > 0) {
+        const int64_t words = (int64_t)a.n * a.res_words;
+        hipLaunchKernelGGL(k_tile_res, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, a);
+    }
+    ok(hipGetLastError());
+    uint32_t status = 0;
+    ok(hipMemcpyAsync(&status, status_dev, 4, hipMemcpyDeviceToHost, st));
+    ok(hipStreamSynchronize(st));          // also: the host arrays of the tables must outlive their copies
+    *hip_err = (int)e;
+    if (e != hipSuccess) return STB_EHIP;
+    if (status) return STB_EINVAL;
+    dst->max_sal_block = mx;
+    dst->max_sal_half = mh;
     return STB_OK;
 }

@@ -148,6 +148,50 @@ def test_device_packer_is_bit_exact_against_the_oracle(case, per_block, torch_cu
         assert (got == want).all(), (name, int((got != want).sum()))
 
 
+TILE_CASES = [c for c in PACK_CASES if _tiled_ok(c[2], c[3])]
+
+
+@pytest.mark.parametrize("case", TILE_CASES, ids=lambda c: f"{c[0]}x{c[1]}_{c[2]}of{c[3]}_m{c[4]}")
+def test_pack_and_tile_on_the_device_feed_the_kernels(case, torch_cuda):
+    """Weights in HBM -> stb_pack_device -> stb_tile_device -> stb_gemv, nothing through the host: the tiled image is
+    the host's byte for byte, and the product agrees with the oracle."""
+    torch = torch_cuda
+    n, k, N, M, mode, kind, seed, *rest = case
+    _say(f"[case] device pack + tile {n}x{k} {N}:{M}")
+    L = make_layer(n, k, seed, kind, n_salient=rest[0] if rest else None)
+    host = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode)
+    tl_host, timg_host = host.tiled()
+    rimg = S.new_device_scratch(host.host_layout.image_bytes)
+    rlay = host.clone_layout_for(rimg.data_ptr(), False)
+    ws = S.new_device_scratch(S.stb_pack_device_workspace_bytes(host.cfg))
+    S.stb_pack_device(torch.from_numpy(L["W"]).cuda(), torch.from_numpy(L["xnorm"]).cuda(),
+                      torch.from_numpy(L["sal_bitmap"].view(np.int32)).cuda(), rlay, False, ws)
+    timg = S.new_device_scratch(tl_host.image_bytes)
+    timg.fill_(0xEE)
+    tlay = S.stb_tiled_sizes(host.cfg)
+    S.stb_layout_bind(tlay, timg.data_ptr())
+    S.stb_tile_device(rlay, tlay)
+    assert (tlay.max_sal_block, tlay.max_sal_half) == (tl_host.max_sal_block, tl_host.max_sal_half)
+    got = timg.cpu().numpy()
+    for name, off, size in S.PLANE_FIELDS + (("sal_tab", "off_saltab", "saltab_bytes"),):
+        o, sz = getattr(tl_host, off), getattr(tl_host, size)
+        assert (got[o:o + sz] == timg_host[o:o + sz]).all(), name
+    What = O.unpack(O.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode), n, k, N, M)
+    for B in (1, 7):
+        x = make_x(B, k, seed)
+        y_ref, bound = O.matmul(x, What)
+        xd = torch.from_numpy(x).cuda()
+        yd = torch.empty((B, n), dtype=torch.float32, device="cuda")
+        wsg = S.new_device_scratch(S.stb_gemv_workspace_bytes(host.cfg, B), zero=True)
+        S.stb_gemv(tlay, xd, B, yd, True, wsg)
+        torch.cuda.synchronize()
+        _within_bound(yd.cpu().numpy(), y_ref, bound, f"gemv on the device-made image, B={B}")
+    # the mismatch checks of stb_tile hold here too
+    with pytest.raises(S.StbError) as e:
+        S.stb_tile_device(tlay, tlay)
+    assert e.value.status == S.STB_EINVAL
+
+
 def test_device_packer_edge_cases_and_errors(torch_cuda):
     torch = torch_cuda
     k = 256
@@ -617,6 +661,20 @@ def test_full_size_layer(cfg, idx, torch_cuda):
         pm.to_device(tiled=True)
     else:
         pm = row_major
+    if tiled:
+        _say("[step] stb_tile_device")
+        tl_host, timg_host = pm.tiled()
+        timg = S.new_device_scratch(tl_host.image_bytes)
+        tlay = S.stb_tiled_sizes(pm.cfg)
+        S.stb_layout_bind(tlay, timg.data_ptr())
+        S.stb_tile_device(row_major.dev_layout, tlay)
+        assert (tlay.max_sal_block, tlay.max_sal_half) == (tl_host.max_sal_block, tl_host.max_sal_half)
+        got = timg.cpu().numpy()
+        for name, off, size in S.PLANE_FIELDS + (("sal_tab", "off_saltab", "saltab_bytes"),):
+            o, sz = getattr(tl_host, off), getattr(tl_host, size)
+            assert (got[o:o + sz] == timg_host[o:o + sz]).all(), ("device tiling", name)
+        del timg, got
+        torch.cuda.empty_cache()
     for which, holder in (("row-major", row_major), ("tiled", pm if tiled else None)):
         if holder is None:
             continue
