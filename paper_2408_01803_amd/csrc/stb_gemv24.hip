@@ -299,7 +299,9 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
     float* const part = reinterpret_cast<float*>(wreg + PART_OFF);
     uint32_t* const recs = reinterpret_cast<uint32_t*>(wreg + REC_OFF);         // [visit][block g][half][record 0 / 1] x 12
 
-    if constexpr (MODE != 2) build_luts<N8>(lut);                // arithmetic only; the barrier comes after the staging
+    // the scatter table is built while the first loads are in flight (wavefronts without work build it right away);
+    // arithmetic and LDS stores only, the barrier comes after the staging
+    if constexpr (MODE != 2) { if (!active) build_luts<N8>(lut); }
     half16_t xr[8];                                              // MODE 2: B operands of the 8 steps of a block
     half8_t xd[16];                                              // dense modes: of the 16 steps
     Res24 inv[2];                                                // first record of the lane's block, per half
@@ -347,6 +349,7 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
             }
         }
         fetch24(t0, p, tile_of(clamp(r0)), o8, o4, o2);
+        if constexpr (MODE != 2) build_luts<N8>(lut);
         asm volatile("s_waitcnt vmcnt(%0)" : : "n"(LMAIN) : "memory");
         if (HAS_RES && lane < 48 && lane % 3 == 2) {
             // the pieces with the column positions become byte offsets inside a staged row (see below)
@@ -390,6 +393,7 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
             asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(sr) : "v"(src));
         }
         fetch24(t0, p, tile_of(clamp(r0)), o8, o4, o2);
+        if constexpr (MODE != 2) build_luts<N8>(lut);
         // The second and third tile go out after the operands are in registers: a compute unit keeps a limited
         // number of loads in flight, and the other wavefront of the SIMD should get its first tile early too
         // (issuing them here instead was measured: no faster with one wavefront per SIMD, slower with two).
