@@ -332,6 +332,10 @@ int64_t stb_gemv_batched_workspace_bytes(int32_t n_layers, const stb_cfg_t* cons
  * generic kernel for any N:M (it rounds the dequantised salient weights to fp16).
  * Tiled 2:4 layers run on the structured-sparse matrix instruction (kept weights plus an index word as the operand,
  * Sec. 3.1 / App. C; its 32x32x32 form).
+ * When T and n are so small that a (128 tokens x 256 rows) tile per workgroup would leave most of the chip idle (fewer
+ * than 200 workgroups), the 512-column superblocks are dealt to up to 16 groups of workgroups that each leave an fp32
+ * partial tile in the workspace, and a second kernel adds the partial tiles in a fixed order: the result is
+ * reproducible, and equal to the unsplit one up to fp32 summation order.
  * X: device fp16 [T][k], finite values (a padding column or token re-reads valid elements of X and meets zero
  * weights or an output that is never stored).  Y: device [T][n], fp16 or fp32, fully overwritten.  workspace: device scratch of at
  * least stb_gemm_workspace_bytes() bytes, 256-byte aligned (may be NULL when that is 0); it needs no

@@ -690,7 +690,7 @@ extern "C" int64_t stb_gemm_workspace_bytes(const stb_layout_t* layout, int32_t 
     if (layout->max_sal_half < 0 || layout->max_sal_half > 8 * ref.sal_chunks) return STB_EINVAL;
     stb_layout_t tmp = ref;
     tmp.max_sal_half = layout->max_sal_half;
-    return layout->cfg.n_salient > 0 ? stb_tiled_gemm_workspace(&tmp, T) : 0;
+    return stb_tiled_gemm_workspace(&tmp, T);      // gathered salient columns of X, partial tiles of a K split
 }
 
 extern "C" int stb_gemm(const stb_layout_t* dev, const void* X, int32_t T, void* Y, int32_t y_fp32,

@@ -276,14 +276,14 @@ struct GemmStage {
         }
     }
     // the first pass's half records and table record (asm loads here too), waited for on the spot
-    __device__ void first_records(HalfData<N8> (&hd)[4], uint4& ra, uint2& rb, uint4* ra_odd = nullptr, uint2* rb_odd = nullptr) const {
+    __device__ void first_records(int shb, HalfData<N8> (&hd)[4], uint4& ra, uint2& rb, uint4* ra_odd = nullptr, uint2* rb_odd = nullptr) const {
         TileRegs<N8> t0r[4];
         uint4_t ra0 = {0u, 0u, 0u, 0u}, ra1 = {0u, 0u, 0u, 0u};
         uint2_t rb0 = {0u, 0u}, rb1 = {0u, 0u};
 #pragma unroll
-        for (int r = 0; r < 4; r++) fetch_hd1(0, t0r, r);
-        fetch_rec(0, ra0, rb0);
-        if (WIDE) fetch_rec(0, ra1, rb1, 1);
+        for (int r = 0; r < 4; r++) fetch_hd1(shb, t0r, r);
+        fetch_rec(shb, ra0, rb0);
+        if (WIDE) fetch_rec(shb, ra1, rb1, 1);
         asm volatile("s_waitcnt vmcnt(0)" : "+v"(ra0), "+v"(rb0), "+v"(ra1), "+v"(rb1) : : "memory");
         if (WIDE) {
             *ra_odd = make_uint4(ra1.x, ra1.y, ra1.z, ra1.w);
@@ -293,7 +293,7 @@ struct GemmStage {
         for (int r = 0; r < 4; r++) {
             asm volatile("s_waitcnt vmcnt(0)" : "+v"(t0r[r].m), "+v"(t0r[r].s), "+v"(t0r[r].r), "+v"(t0r[r].sc), "+v"(t0r[r].ar));
             t0r[r].rlo = 0u; t0r[r].rhi = 0u;
-            unpack_tile<N8>(t0r[r], 0, hd[r]);
+            unpack_tile<N8>(t0r[r], shb & 1, hd[r]);
         }
         ra = make_uint4(ra0.x, ra0.y, ra0.z, ra0.w);
         rb = make_uint2(rb0.x, rb0.y);
@@ -302,10 +302,10 @@ struct GemmStage {
     // (few: a record covers 8 of the 64 columns).  Kept out of the main loops so that they stay one straight line of
     // K steps (a branch around matrix instructions costs two register copies of the accumulators).
     __device__ void further_records(float4_t (&acc)[4][TT], HalfData<N8> (&hd)[4], uint32_t (&a1)[4][4], uint32_t (&rlo)[4],
-                                    uint32_t (&rhi)[4], const char* lds, int nsh) const {
+                                    uint32_t (&rhi)[4], const char* lds, int shb, int nsh) const {
         if (!(HAS_RES && p.sal_chunks > 1)) return;
         const uint32_t gx = (uint32_t)(i * 64 + (g ^ ((i >> 2) & 3)) * 16);
-        for (int sh0 = 0; sh0 < nsh; sh0 += 64) {
+        for (int sh0 = shb; sh0 < nsh; sh0 += 64) {
             // which of the next 64 half blocks have such records: lane l looks at half block sh0 + l
             const int shl = sh0 + lane < nsh ? sh0 + lane : nsh - 1;
             const uint32_t need_l = p.sal_tab[(((int64_t)(4 * (shl >> 1)) * 2 + (shl & 1)) * p.sal_chunks) * 12 + 5];
@@ -345,10 +345,10 @@ struct GemmStage {
     // lane's offset inside the gathered columns for block 2 (g / 2) + bs).
     template <typename Acc>
     __device__ void further_records_wide(Acc (&acc)[2][TT / 2], HalfData<N8> (&hd)[4], uint32_t (&a1)[4][4], uint32_t (&rlo)[4],
-                                         uint32_t (&rhi)[4], const char* lds, int nsh, const uint32_t (&gx)[2]) const {
+                                         uint32_t (&rhi)[4], const char* lds, int shb, int nsh, const uint32_t (&gx)[2]) const {
         constexpr int TQ = TT / 2;
         if (!(HAS_RES && p.sal_chunks > 1)) return;
-        for (int sh0 = 0; sh0 < nsh; sh0 += 64) {
+        for (int sh0 = shb; sh0 < nsh; sh0 += 64) {
             const int shl = sh0 + lane < nsh ? sh0 + lane : nsh - 1;
             const uint32_t need_l = p.sal_tab[(((int64_t)(4 * (shl >> 1)) * 2 + (shl & 1)) * p.sal_chunks) * 12 + 5];
             uint64_t todo = __ballot(need_l > 1u && sh0 + lane < nsh);
@@ -398,7 +398,7 @@ struct GemmStage {
 template <int N8, bool HAS_RES>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                           void* __restrict__ Y, int y_fp32,
-                                                          const __half* __restrict__ xsal, int cfix) {
+                                                          const __half* __restrict__ xsal, int cfix, int sbs, float* __restrict__ part) {
     constexpr int TT = GM_TT;
     typedef GmLds<TT> G;
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -408,7 +408,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     const int i = lane & 15, g = lane >> 4;
     const int t0 = blockIdx.x * G::TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;                // first row tile of this wavefront
-    const int nsh = p.nsb * 2;                                      // (superblock, half) pairs
+    // K split: this workgroup contracts the superblocks [sbs * blockIdx.z, + sbs) and leaves an fp32 partial tile
+    const int shb = sbs ? 2 * sbs * (int)blockIdx.z : 0;           // first (superblock, half) pair: even
+    const int nsh = sbs && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
+    if (sbs) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
     build_luts<N8>(&lut);
 
     float4_t acc[4][TT];
@@ -457,10 +460,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     uint2 rb = make_uint2(0u, 0u);
     uint32_t a0[4][4], a1[4][4];
     uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
-    st.x_gload(0, 0, 0);
-    st.x_gload(0, 1, 1);
-    st.r_gload(0, 0, 0);
-    st.first_records(hd, ra, rb);
+    st.x_gload(shb, 0, 0);
+    st.x_gload(shb, 1, 1);
+    st.r_gload(shb, 0, 0);
+    st.first_records(shb, hd, ra, rb);
     if (HAS_RES) st.fetch_res_words(rb.x, rlo, rhi);
     st.scale_tables(hd, TL, TH);
     __syncthreads();
@@ -475,7 +478,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     //   [step 7, after the second barrier] window 1 (8) and gathered columns (NG) of the next pass
     //   [residual step]                    res_sign words of the next pass (NR)
     constexpr int NG = HAS_RES ? 2 : 0, NR = HAS_RES ? 8 : 0, NC = HAS_RES ? 2 : 0, NH = 4 * TileLoads<false>::count;
-    for (int sh = 0; sh < nsh; sh++) {
+    for (int sh = shb; sh < nsh; sh++) {
         const int shn = sh + 1 < nsh ? sh + 1 : sh;                 // the last pass prefetches its own data again
         const int par = sh & 1;
         TileRegs<N8> tn[4];
@@ -544,7 +547,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     // nothing may still be on its way to this workgroup's LDS or registers from here on
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
 
-    st.further_records(acc, hd, a1, rlo, rhi, lds, nsh);
+    st.further_records(acc, hd, a1, rlo, rhi, lds, shb, nsh);
 
     __syncthreads();                                                // every wavefront is done with LDS
     store_tile<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
@@ -616,7 +619,7 @@ __device__ inline void store_tile_wide(const float16_t (&acc)[2][TT / 2], char* 
 template <int N8, bool HAS_RES>
 __global__ __launch_bounds__(256) void gemm_wide_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                          void* __restrict__ Y, int y_fp32,
-                                                         const __half* __restrict__ xsal, int cfix) {
+                                                         const __half* __restrict__ xsal, int cfix, int sbs, float* __restrict__ part) {
     constexpr int TT = GM_TT;                                       // B operands per step: 4 token tiles of 32 x the 2 blocks of a K half
     constexpr int TQ = TT / 2;
     typedef GmLds<TT> G;
@@ -627,7 +630,10 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(TiledPlanes p, const __h
     const int i = lane & 15, g = lane >> 4;
     const int t0 = blockIdx.x * G::TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;
-    const int nsh = p.nsb * 2;
+    // K split: this workgroup contracts the superblocks [sbs * blockIdx.z, + sbs) and leaves an fp32 partial tile
+    const int shb = sbs ? 2 * sbs * (int)blockIdx.z : 0;           // first (superblock, half) pair: even
+    const int nsh = sbs && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
+    if (sbs) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
     build_luts<N8>(&lut);
 
     float16_t acc[2][TQ];
@@ -680,10 +686,10 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(TiledPlanes p, const __h
     uint2 rb[2] = {make_uint2(0u, 0u), make_uint2(0u, 0u)};
     uint32_t a0[4][4], a1[4][4];
     uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
-    st.x_gload(0, 0, 0);
-    st.x_gload(0, 1, 1);
-    st.r_gload(0, 0, 0);
-    st.first_records(hd, ra[0], rb[0], &ra[1], &rb[1]);
+    st.x_gload(shb, 0, 0);
+    st.x_gload(shb, 1, 1);
+    st.r_gload(shb, 0, 0);
+    st.first_records(shb, hd, ra[0], rb[0], &ra[1], &rb[1]);
     if (HAS_RES) {
 #pragma unroll
         for (int r = 0; r < 4; r++) st.fetch_res_words1(rb[r & 1].x, rlo, rhi, r);
@@ -701,7 +707,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(TiledPlanes p, const __h
     //   [step 7, after the second barrier] window 1 (8) and gathered columns of the next pass
     //   [residual step]                    res_sign words of the next pass (NR)
     constexpr int NR = HAS_RES ? 8 : 0;
-    for (int sh = 0; sh < nsh; sh++) {
+    for (int sh = shb; sh < nsh; sh++) {
         const int shn = sh + 1 < nsh ? sh + 1 : sh;
         const int par = sh & 1;
         TileRegs<N8> tn[4];
@@ -769,7 +775,7 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(TiledPlanes p, const __h
     }
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
 
-    st.further_records_wide(acc, hd, a1, rlo, rhi, lds, nsh, gx);
+    st.further_records_wide(acc, hd, a1, rlo, rhi, lds, shb, nsh, gx);
 
     __syncthreads();                                                // every wavefront is done with LDS
     store_tile_wide<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
@@ -816,7 +822,7 @@ __device__ inline void sparse_operand(const HalfData<4>& d, uint32_t TLr, uint32
 template <bool HAS_RES>
 __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                       void* __restrict__ Y, int y_fp32,
-                                                      const __half* __restrict__ xsal, int cfix) {
+                                                      const __half* __restrict__ xsal, int cfix, int sbs, float* __restrict__ part) {
     constexpr int N8 = 4;
     constexpr int TT = GM_TT24;
     typedef GmLds<TT> G;
@@ -826,7 +832,10 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     const int i = lane & 15, g = lane >> 4;
     const int t0 = blockIdx.x * G::TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;
-    const int nsh = p.nsb * 2;
+    // K split: this workgroup contracts the superblocks [sbs * blockIdx.z, + sbs) and leaves an fp32 partial tile
+    const int shb = sbs ? 2 * sbs * (int)blockIdx.z : 0;           // first (superblock, half) pair: even
+    const int nsh = sbs && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
+    if (sbs) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
 
     float4_t acc[4][TT];
 #pragma unroll
@@ -893,10 +902,10 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     uint2 rb = make_uint2(0u, 0u);
     uint32_t a0[4][4], a1[4][4], ia[4], ib[4];
     uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
-    st.x_gload(0, 0, 0);
-    st.x_gload(0, 1, 1);
-    st.r_gload(0, 0, 0);
-    st.first_records(hd, ra, rb);
+    st.x_gload(shb, 0, 0);
+    st.x_gload(shb, 1, 1);
+    st.r_gload(shb, 0, 0);
+    st.first_records(shb, hd, ra, rb);
     if (HAS_RES) {
 #pragma unroll
         for (int r = 0; r < 4; r++) st.fetch_res_words1(rb.x, rlo, rhi, r);
@@ -914,7 +923,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     //   [step 3, after the second barrier] window 1 (8) and gathered columns (NG) of the next pass
     //   [residual step]                    res_sign words of the next pass (NR)
     constexpr int NR = HAS_RES ? 8 : 0, NC = HAS_RES ? 2 : 0, NH = 4 * TileLoads<false>::count;
-    for (int sh = 0; sh < nsh; sh++) {
+    for (int sh = shb; sh < nsh; sh++) {
         const int shn = sh + 1 < nsh ? sh + 1 : sh;
         const int par = sh & 1;
         TileRegs<N8> tn[4];
@@ -973,7 +982,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     }
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
 
-    st.further_records(acc, hd, a1, rlo, rhi, lds, nsh);
+    st.further_records(acc, hd, a1, rlo, rhi, lds, shb, nsh);
     __syncthreads();
     store_tile<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
 }
@@ -991,7 +1000,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
 template <bool HAS_RES>
 __global__ __launch_bounds__(256) void gemm24_wide_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                            void* __restrict__ Y, int y_fp32,
-                                                           const __half* __restrict__ xsal, int cfix) {
+                                                           const __half* __restrict__ xsal, int cfix, int sbs, float* __restrict__ part) {
     constexpr int N8 = 4;
     constexpr int TT = GM_TT24;                                     // B operands per step: 4 token tiles of 32 x 2 (bs)
     constexpr int TQ = TT / 2;
@@ -1003,7 +1012,10 @@ __global__ __launch_bounds__(256) void gemm24_wide_kernel(TiledPlanes p, const _
     const int i = lane & 15, g = lane >> 4;
     const int t0 = blockIdx.x * G::TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;
-    const int nsh = p.nsb * 2;
+    // K split: this workgroup contracts the superblocks [sbs * blockIdx.z, + sbs) and leaves an fp32 partial tile
+    const int shb = sbs ? 2 * sbs * (int)blockIdx.z : 0;           // first (superblock, half) pair: even
+    const int nsh = sbs && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
+    if (sbs) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
 
     float16_t acc[2][TQ];
 #pragma unroll
@@ -1075,10 +1087,10 @@ __global__ __launch_bounds__(256) void gemm24_wide_kernel(TiledPlanes p, const _
     uint2 rb[2] = {make_uint2(0u, 0u), make_uint2(0u, 0u)};
     uint32_t a0[4][4], a1[4][4], ia[4], ib[4];
     uint32_t rlo[4] = {0u, 0u, 0u, 0u}, rhi[4] = {0u, 0u, 0u, 0u};
-    st.x_gload(0, 0, 0);
-    st.x_gload(0, 1, 1);
-    st.r_gload(0, 0, 0);
-    st.first_records(hd, ra[0], rb[0], &ra[1], &rb[1]);
+    st.x_gload(shb, 0, 0);
+    st.x_gload(shb, 1, 1);
+    st.r_gload(shb, 0, 0);
+    st.first_records(shb, hd, ra[0], rb[0], &ra[1], &rb[1]);
     if (HAS_RES) {
 #pragma unroll
         for (int r = 0; r < 4; r++) st.fetch_res_words1(rb[r & 1].x, rlo, rhi, r);
@@ -1096,7 +1108,7 @@ __global__ __launch_bounds__(256) void gemm24_wide_kernel(TiledPlanes p, const _
     //   [step 3, after the second barrier] window 1 (8) and gathered columns of the next pass
     //   [residual step]                    res_sign words of the next pass (NR)
     constexpr int NR = HAS_RES ? 8 : 0, NC = HAS_RES ? 4 : 0, NH = 4 * TileLoads<false>::count;
-    for (int sh = 0; sh < nsh; sh++) {
+    for (int sh = shb; sh < nsh; sh++) {
         const int shn = sh + 1 < nsh ? sh + 1 : sh;
         const int par = sh & 1;
         TileRegs<N8> tn[4];
@@ -1159,62 +1171,73 @@ __global__ __launch_bounds__(256) void gemm24_wide_kernel(TiledPlanes p, const _
     }
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(rlo[0]), "+v"(rlo[1]), "+v"(rlo[2]), "+v"(rlo[3]), "+v"(rhi[0]), "+v"(rhi[1]), "+v"(rhi[2]), "+v"(rhi[3]) : : "memory");
 
-    st.further_records_wide(acc, hd, a1, rlo, rhi, lds, nsh, gx);
+    st.further_records_wide(acc, hd, a1, rlo, rhi, lds, shb, nsh, gx);
     __syncthreads();
     store_tile_wide<TT>(acc, lds, p, Y, y_fp32, T, t0, rtw, wave, lane);
+}
+
+// K split: the partial tiles [split][T][n] (fp32, already negated back) are added in split order and stored as Y.
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __restrict__ part, int S, int64_t count,
+                                                                 void* __restrict__ Y, int y_fp32) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= count) return;
+    float s = part[e];
+    for (int c = 1; c < S; c++) s += part[(int64_t)c * count + e];
+    if (y_fp32) reinterpret_cast<float*>(Y)[e] = s;
+    else reinterpret_cast<__half*>(Y)[e] = __float2half(s);
 }
 
 #include "stb_gemm_shared.hpp"
 
 template <int N8, bool HAS_RES>
 hipError_t launch_gemm(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
-                       const __half* xsal, int cfix) {
+                       const __half* xsal, int cfix, int sbs, float* part) {
     static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
     if (!attr_set.load(std::memory_order_acquire)) {
         const hipError_t attr = hipFuncSetAttribute((const void*)gemm_tiled_kernel<N8, HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
         if (attr != hipSuccess) return attr;
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix);
+    hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
     return hipGetLastError();
 }
 
 template <int N8, bool HAS_RES>
 hipError_t launch_gemm_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
-                            const __half* xsal, int cfix) {
+                            const __half* xsal, int cfix, int sbs, float* part) {
     static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
     if (!attr_set.load(std::memory_order_acquire)) {
         const hipError_t attr = hipFuncSetAttribute((const void*)gemm_wide_kernel<N8, HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
         if (attr != hipSuccess) return attr;
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((gemm_wide_kernel<N8, HAS_RES>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix);
+    hipLaunchKernelGGL((gemm_wide_kernel<N8, HAS_RES>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
     return hipGetLastError();
 }
 
 template <bool HAS_RES>
 hipError_t launch_gemm24_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
-                              const __half* xsal, int cfix) {
+                              const __half* xsal, int cfix, int sbs, float* part) {
     static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
     if (!attr_set.load(std::memory_order_acquire)) {
         const hipError_t attr = hipFuncSetAttribute((const void*)gemm24_wide_kernel<HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
         if (attr != hipSuccess) return attr;
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((gemm24_wide_kernel<HAS_RES>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix);
+    hipLaunchKernelGGL((gemm24_wide_kernel<HAS_RES>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
     return hipGetLastError();
 }
 
 template <bool HAS_RES>
 hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
-                         const __half* xsal, int cfix) {
+                         const __half* xsal, int cfix, int sbs, float* part) {
     static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
     if (!attr_set.load(std::memory_order_acquire)) {
         const hipError_t attr = hipFuncSetAttribute((const void*)gemm24_kernel<HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
         if (attr != hipSuccess) return attr;
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((gemm24_kernel<HAS_RES>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix);
+    hipLaunchKernelGGL((gemm24_kernel<HAS_RES>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
     return hipGetLastError();
 }
 
@@ -1328,8 +1351,30 @@ extern "C" int stb_tiled_probe_mfma(int kind, int valu, int steps, int n_workgro
 static int64_t round_up256(int64_t v) { return (v + 255) / 256 * 256; }
 static int cfix_of(const stb_layout_t* L) { return (L->max_sal_half + 7) / 8; }
 
+// K split: with fewer than 200 workgroups in the (token tile, row group) grid the superblocks are dealt to up to 16
+// groups of workgroups, each of which leaves an fp32 partial tile in the workspace; a second kernel adds them in order.
+// Returns the number of superblocks per group (0: no split) and the number of groups.
+static int gemm_split(const stb_layout_t* L, int T, int tok, int* groups) {
+    const int64_t base = (int64_t)((T + tok - 1) / tok) * ((L->n_row_tiles + GM_ROWT - 1) / GM_ROWT);
+    *groups = 1;
+    if (base >= 200 || L->n_super < 2) return 0;
+    int S = (int)((256 + base - 1) / base);
+    S = S > 16 ? 16 : S;
+    S = S > L->n_super ? L->n_super : S;
+    if (S < 2) return 0;
+    const int sbs = (L->n_super + S - 1) / S;
+    *groups = (L->n_super + sbs - 1) / sbs;
+    return *groups > 1 ? sbs : 0;
+}
+static int64_t gather_bytes(const stb_layout_t* L, int T) { return round_up256((int64_t)T * L->n_super * 2 * cfix_of(L) * 32 * 2); }
+
 extern "C" int64_t stb_tiled_gemm_workspace(const stb_layout_t* L, int T) {
-    return round_up256((int64_t)T * L->n_super * 2 * cfix_of(L) * 32 * 2);
+    // the gathered salient columns of X, then the partial tiles of a K split (both token-tile sizes give the same
+    // number of groups or fewer for the larger one: take the larger need)
+    int g0 = 1, g1 = 1;
+    const int s0 = gemm_split(L, T, GmLds<GM_TT>::TOK, &g0), s1 = gemm_split(L, T, GmLds<GM_TT24>::TOK, &g1);
+    const int gmax = (s0 ? g0 : 0) > (s1 ? g1 : 0) ? (s0 ? g0 : 0) : (s1 ? g1 : 0);
+    return gather_bytes(L, T) + round_up256((int64_t)gmax * T * L->cfg.n_out * 4);
 }
 
 extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void* Y, int y_fp32, void* workspace,
@@ -1339,10 +1384,13 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
     const int cfix = cfix_of(L);
     const bool res = p.res_words > 0 && cfix > 0;
     const hipStream_t st = (hipStream_t)stream;
-    if (res) {
+    const int64_t need = stb_tiled_gemm_workspace(L, T);
+    if (need > 0) {
         if (!workspace) return STB_ENULL;
-        if (workspace_bytes < stb_tiled_gemm_workspace(L, T)) return STB_EINVAL;
+        if (workspace_bytes < need) return STB_EINVAL;
         if ((uintptr_t)workspace % 256) return STB_EALIGN;
+    }
+    if (res) {
         const int64_t pieces = (int64_t)T * p.nsb * 2 * cfix * 4;
         hipLaunchKernelGGL(gemm_gather_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, p,
                            (const __half*)X, T, (__half*)workspace, cfix);
@@ -1369,13 +1417,21 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
     const bool narrow = which != 2;
     const bool sparse32 = sparse_ok && which != 3;
     const int tok = sparse_ok ? GmLds<GM_TT24>::TOK : GmLds<GM_TT>::TOK;      // tokens per workgroup of the kernel that runs
-    const dim3 grid((T + tok - 1) / tok, (p.nrt + GM_ROWT - 1) / GM_ROWT);
-    if (sparse32) e = res ? launch_gemm24_wide<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm24_wide<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
-    else if (sparse_ok) e = res ? launch_gemm24<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm24<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
-    else if (narrow && n8 == 4) e = res ? launch_gemm<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
-    else if (narrow) e = res ? launch_gemm<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
-    else if (n8 == 4) e = res ? launch_gemm_wide<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm_wide<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
-    else e = res ? launch_gemm_wide<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix) : launch_gemm_wide<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix);
+    int groups = 1;
+    const int sbs = gemm_split(L, T, tok, &groups);
+    float* part = sbs ? (float*)((char*)workspace + gather_bytes(L, T)) : nullptr;
+    const dim3 grid((T + tok - 1) / tok, (p.nrt + GM_ROWT - 1) / GM_ROWT, groups);
+    if (sparse32) e = res ? launch_gemm24_wide<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm24_wide<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
+    else if (sparse_ok) e = res ? launch_gemm24<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm24<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
+    else if (narrow && n8 == 4) e = res ? launch_gemm<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
+    else if (narrow) e = res ? launch_gemm<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
+    else if (n8 == 4) e = res ? launch_gemm_wide<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm_wide<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
+    else e = res ? launch_gemm_wide<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm_wide<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
+    if (e == hipSuccess && sbs) {
+        const int64_t count = (int64_t)T * p.n;
+        hipLaunchKernelGGL(gemm_splitk_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, part, groups, count, Y, y_fp32);
+        e = hipGetLastError();
+    }
     *hip_err = (int)e;
     return e == hipSuccess ? STB_OK : STB_EHIP;
 }
