@@ -364,6 +364,32 @@ def test_gemm_small(small_case, torch_cuda, T):
             _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemm T={T} (kernel asked for: {which})")
 
 
+@pytest.mark.parametrize("N,M", [(4, 8), (2, 4), (6, 8)])
+def test_gemm_with_a_k_split_is_reproducible_and_matches_the_oracle(N, M, torch_cuda):
+    # few tokens on a wide layer: the superblocks are dealt to groups of workgroups whose fp32 partial tiles a second
+    # kernel adds in a fixed order (9 superblocks here, the last group is ragged)
+    torch = torch_cuda
+    n, k, T = 300, 4608, 70
+    _say(f"[case] gemm K split {n}x{k} {N}:{M} T={T}")
+    L = make_layer(n, k, 120 + N, "x8")
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, 0).to_device(tiled=True)
+    What = O.unpack(_oracle_planes_from(pm), n, k, N, M)
+    x = make_x(T, k, 121)
+    y_ref, bound = O.matmul(x, What)
+    xd = torch.from_numpy(x).cuda()
+    ws = pm.new_gemm_workspace(T)
+    assert ws is not None and ws.numel() >= 2 * T * n * 4          # room for at least two partial tiles
+    outs = []
+    for y_fp32 in (False, True, True):
+        ws.fill_(0x7F)                                                 # the workspace needs no initialisation
+        yd = torch.full((T, n), float("nan"), dtype=torch.float32 if y_fp32 else torch.float16, device="cuda")
+        S.stb_gemm(pm.dev_layout, xd, T, yd, y_fp32, ws)
+        torch.cuda.synchronize()
+        outs.append(yd.cpu().numpy())
+        _within_bound(outs[-1], y_ref, bound, f"gemm K split fp32={y_fp32}")
+    assert (outs[1].view(np.uint32) == outs[2].view(np.uint32)).all()
+
+
 def test_zero_activations_and_zero_weights(torch_cuda):
     torch = torch_cuda
     n, k = 70, 256
