@@ -501,6 +501,58 @@ def test_gemv_batched_is_one_launch_with_reproducible_bits(torch_cuda, B):
                 assert (_bits(ys[0]) == _bits(y1)).all()
 
 
+def test_decode_calls_captured_in_a_hip_graph_replay_with_the_eager_bits(torch_cuda):
+    # stb_gemv / stb_gemv_batched / stb_gemv_static enqueue kernels only (no memset, no allocation, no synchronisation),
+    # so a serving loop may capture them once and replay: every replay, with eager work and synchronisations between
+    # the replays, must give the bits of the eager calls (the arrival counters of the column splits return to zero
+    # by themselves)
+    torch = torch_cuda
+    specs = [(200, 4608, 2, 4, 131), (96, 4608, 4, 8, 132), (130, 1024, 6, 8, 133)]
+    B = 3
+    pms, xs, refs = [], [], []
+    for n, k, N, M, seed in specs:
+        L = make_layer(n, k, seed, "x8")
+        pms.append(S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, 0).to_device(tiled=True))
+        xs.append(torch.from_numpy(make_x(B, k, seed)).cuda())
+    ws = S.new_device_scratch(S.stb_gemv_batched_workspace_bytes([pm.cfg for pm in pms], B), zero=True)
+    ws1 = pms[0].new_workspace()
+
+    def step(ys, y_single, y_static):
+        S.stb_gemv_batched([pm.dev_layout for pm in pms], xs, B, ys, True, ws)
+        S.stb_gemv(pms[0].dev_layout, xs[0], B, y_single, True, ws1)
+        S.stb_gemv_static(pms[0].dev_layout, xs[0], B, y_static, True)
+
+    def fresh():
+        return ([torch.full((B, pm.cfg.n_out), float("nan"), dtype=torch.float32, device="cuda") for pm in pms],
+                torch.full((B, pms[0].cfg.n_out), float("nan"), dtype=torch.float32, device="cuda"),
+                torch.full((B, pms[0].cfg.n_out), float("nan"), dtype=torch.float32, device="cuda"))
+
+    eager = fresh()
+    step(*eager)
+    torch.cuda.synchronize()
+    want = [t.cpu().numpy().copy() for t in eager[0]] + [eager[1].cpu().numpy().copy(), eager[2].cpu().numpy().copy()]
+    assert all(np.isfinite(w).all() for w in want)
+    outs = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step(*outs)
+    torch.cuda.current_stream().wait_stream(side)
+    for replay in range(4):
+        for t in outs[0] + [outs[1], outs[2]]:
+            t.fill_(float("nan"))
+        scratch = fresh()
+        step(*scratch)                                   # eager work of the program itself between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = [t.cpu().numpy() for t in outs[0]] + [outs[1].cpu().numpy(), outs[2].cpu().numpy()]
+        for a, b in zip(got, want):
+            assert (a.view(np.uint32) == b.view(np.uint32)).all(), f"replay {replay}"
+
+
 def test_gemv_batched_rejects_bad_arguments(torch_cuda):
     torch = torch_cuda
     L = make_layer(40, 4608, 9)
