@@ -395,7 +395,7 @@ struct GemmStage {
     }
 };
 
-template <int N8, bool HAS_RES>
+template <int N8, bool HAS_RES, bool SPLIT>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                           void* __restrict__ Y, int y_fp32,
                                                           const __half* __restrict__ xsal, int cfix, int sbs, float* __restrict__ part) {
@@ -409,9 +409,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
     const int t0 = blockIdx.x * G::TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;                // first row tile of this wavefront
     // K split: this workgroup contracts the superblocks [sbs * blockIdx.z, + sbs) and leaves an fp32 partial tile
-    const int shb = sbs ? 2 * sbs * (int)blockIdx.z : 0;           // first (superblock, half) pair: even
-    const int nsh = sbs && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
-    if (sbs) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
+    // (a template parameter: the kernel without a split keeps the registers it had before the split existed)
+    const int shb = SPLIT ? 2 * sbs * (int)blockIdx.z : 0;         // first (superblock, half) pair: even
+    const int nsh = SPLIT && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
+    if constexpr (SPLIT) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
     build_luts<N8>(&lut);
 
     float4_t acc[4][TT];
@@ -616,7 +617,7 @@ __device__ inline void store_tile_wide(const float16_t (&acc)[2][TT / 2], char* 
         }
 }
 
-template <int N8, bool HAS_RES>
+template <int N8, bool HAS_RES, bool SPLIT>
 __global__ __launch_bounds__(256) void gemm_wide_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                          void* __restrict__ Y, int y_fp32,
                                                          const __half* __restrict__ xsal, int cfix, int sbs, float* __restrict__ part) {
@@ -631,9 +632,10 @@ __global__ __launch_bounds__(256) void gemm_wide_kernel(TiledPlanes p, const __h
     const int t0 = blockIdx.x * G::TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;
     // K split: this workgroup contracts the superblocks [sbs * blockIdx.z, + sbs) and leaves an fp32 partial tile
-    const int shb = sbs ? 2 * sbs * (int)blockIdx.z : 0;           // first (superblock, half) pair: even
-    const int nsh = sbs && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
-    if (sbs) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
+    // (a template parameter: the kernel without a split keeps the registers it had before the split existed)
+    const int shb = SPLIT ? 2 * sbs * (int)blockIdx.z : 0;         // first (superblock, half) pair: even
+    const int nsh = SPLIT && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
+    if constexpr (SPLIT) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
     build_luts<N8>(&lut);
 
     float16_t acc[2][TQ];
@@ -819,7 +821,7 @@ __device__ inline void sparse_operand(const HalfData<4>& d, uint32_t TLr, uint32
     for (int q = 0; q < 4; q++) W[q] = and_or_v(pk_shl(Xs, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
 }
 
-template <bool HAS_RES>
+template <bool HAS_RES, bool SPLIT>
 __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                       void* __restrict__ Y, int y_fp32,
                                                       const __half* __restrict__ xsal, int cfix, int sbs, float* __restrict__ part) {
@@ -833,9 +835,10 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
     const int t0 = blockIdx.x * G::TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;
     // K split: this workgroup contracts the superblocks [sbs * blockIdx.z, + sbs) and leaves an fp32 partial tile
-    const int shb = sbs ? 2 * sbs * (int)blockIdx.z : 0;           // first (superblock, half) pair: even
-    const int nsh = sbs && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
-    if (sbs) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
+    // (a template parameter: the kernel without a split keeps the registers it had before the split existed)
+    const int shb = SPLIT ? 2 * sbs * (int)blockIdx.z : 0;         // first (superblock, half) pair: even
+    const int nsh = SPLIT && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
+    if constexpr (SPLIT) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
 
     float4_t acc[4][TT];
 #pragma unroll
@@ -997,7 +1000,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
 // So K 0..15 of an instruction are 16 columns of block bs and K 16..31 the same columns of block 2 + bs, and a B
 // operand is two 16-byte pieces of the window row, P and P ^ 8, as in gemm24_kernel.
 // ------------------------------------------------------------------------------------------------
-template <bool HAS_RES>
+template <bool HAS_RES, bool SPLIT>
 __global__ __launch_bounds__(256) void gemm24_wide_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                            void* __restrict__ Y, int y_fp32,
                                                            const __half* __restrict__ xsal, int cfix, int sbs, float* __restrict__ part) {
@@ -1013,9 +1016,10 @@ __global__ __launch_bounds__(256) void gemm24_wide_kernel(TiledPlanes p, const _
     const int t0 = blockIdx.x * G::TOK;
     const int rtw = blockIdx.y * GM_ROWT + wave * 4;
     // K split: this workgroup contracts the superblocks [sbs * blockIdx.z, + sbs) and leaves an fp32 partial tile
-    const int shb = sbs ? 2 * sbs * (int)blockIdx.z : 0;           // first (superblock, half) pair: even
-    const int nsh = sbs && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
-    if (sbs) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
+    // (a template parameter: the kernel without a split keeps the registers it had before the split existed)
+    const int shb = SPLIT ? 2 * sbs * (int)blockIdx.z : 0;         // first (superblock, half) pair: even
+    const int nsh = SPLIT && 2 * sbs * ((int)blockIdx.z + 1) < p.nsb * 2 ? 2 * sbs * ((int)blockIdx.z + 1) : p.nsb * 2;   // one past the last
+    if constexpr (SPLIT) { Y = part + (int64_t)blockIdx.z * T * p.n; y_fp32 = 1; }
 
     float16_t acc[2][TQ];
 #pragma unroll
@@ -1192,52 +1196,68 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __
 template <int N8, bool HAS_RES>
 hipError_t launch_gemm(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                        const __half* xsal, int cfix, int sbs, float* part) {
-    static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
-    if (!attr_set.load(std::memory_order_acquire)) {
-        const hipError_t attr = hipFuncSetAttribute((const void*)gemm_tiled_kernel<N8, HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
+    // two instantiations: with and without the K split
+    static std::atomic<bool> attr_set[2] = {{false}, {false}};         // a failure is not remembered: the next call tries again
+    const int sp = sbs ? 1 : 0;
+    const void* fn = sp ? (const void*)gemm_tiled_kernel<N8, HAS_RES, true> : (const void*)gemm_tiled_kernel<N8, HAS_RES, false>;
+    if (!attr_set[sp].load(std::memory_order_acquire)) {
+        const hipError_t attr = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
         if (attr != hipSuccess) return attr;
-        attr_set.store(true, std::memory_order_release);
+        attr_set[sp].store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    if (sp) hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES, true>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    else hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES, false>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
     return hipGetLastError();
 }
 
 template <int N8, bool HAS_RES>
 hipError_t launch_gemm_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                             const __half* xsal, int cfix, int sbs, float* part) {
-    static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
-    if (!attr_set.load(std::memory_order_acquire)) {
-        const hipError_t attr = hipFuncSetAttribute((const void*)gemm_wide_kernel<N8, HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
+    // two instantiations: with and without the K split
+    static std::atomic<bool> attr_set[2] = {{false}, {false}};         // a failure is not remembered: the next call tries again
+    const int sp = sbs ? 1 : 0;
+    const void* fn = sp ? (const void*)gemm_wide_kernel<N8, HAS_RES, true> : (const void*)gemm_wide_kernel<N8, HAS_RES, false>;
+    if (!attr_set[sp].load(std::memory_order_acquire)) {
+        const hipError_t attr = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
         if (attr != hipSuccess) return attr;
-        attr_set.store(true, std::memory_order_release);
+        attr_set[sp].store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((gemm_wide_kernel<N8, HAS_RES>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    if (sp) hipLaunchKernelGGL((gemm_wide_kernel<N8, HAS_RES, true>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    else hipLaunchKernelGGL((gemm_wide_kernel<N8, HAS_RES, false>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
     return hipGetLastError();
 }
 
 template <bool HAS_RES>
 hipError_t launch_gemm24_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                               const __half* xsal, int cfix, int sbs, float* part) {
-    static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
-    if (!attr_set.load(std::memory_order_acquire)) {
-        const hipError_t attr = hipFuncSetAttribute((const void*)gemm24_wide_kernel<HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
+    // two instantiations: with and without the K split
+    static std::atomic<bool> attr_set[2] = {{false}, {false}};         // a failure is not remembered: the next call tries again
+    const int sp = sbs ? 1 : 0;
+    const void* fn = sp ? (const void*)gemm24_wide_kernel<HAS_RES, true> : (const void*)gemm24_wide_kernel<HAS_RES, false>;
+    if (!attr_set[sp].load(std::memory_order_acquire)) {
+        const hipError_t attr = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
         if (attr != hipSuccess) return attr;
-        attr_set.store(true, std::memory_order_release);
+        attr_set[sp].store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((gemm24_wide_kernel<HAS_RES>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    if (sp) hipLaunchKernelGGL((gemm24_wide_kernel<HAS_RES, true>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    else hipLaunchKernelGGL((gemm24_wide_kernel<HAS_RES, false>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
     return hipGetLastError();
 }
 
 template <bool HAS_RES>
 hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                          const __half* xsal, int cfix, int sbs, float* part) {
-    static std::atomic<bool> attr_set{false};         // a failure is not remembered: the next call tries again
-    if (!attr_set.load(std::memory_order_acquire)) {
-        const hipError_t attr = hipFuncSetAttribute((const void*)gemm24_kernel<HAS_RES>, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
+    // two instantiations: with and without the K split
+    static std::atomic<bool> attr_set[2] = {{false}, {false}};         // a failure is not remembered: the next call tries again
+    const int sp = sbs ? 1 : 0;
+    const void* fn = sp ? (const void*)gemm24_kernel<HAS_RES, true> : (const void*)gemm24_kernel<HAS_RES, false>;
+    if (!attr_set[sp].load(std::memory_order_acquire)) {
+        const hipError_t attr = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
         if (attr != hipSuccess) return attr;
-        attr_set.store(true, std::memory_order_release);
+        attr_set[sp].store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL((gemm24_kernel<HAS_RES>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    if (sp) hipLaunchKernelGGL((gemm24_kernel<HAS_RES, true>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    else hipLaunchKernelGGL((gemm24_kernel<HAS_RES, false>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
     return hipGetLastError();
 }
 
