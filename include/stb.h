@@ -114,6 +114,11 @@ typedef struct stb_cfg {
  *                         half
  *               [6]       number of entries in this record (0..8)        [7] zero
  *               [8..11]   uint16 p_e of the 8 entries, 0xFFFF if the entry does not exist
+ *   res_t     [row_tile][super][lane] uint32, a derived copy of res_sign bits in lane-record order (the decode kernel
+ *             reads one word per tile and lane instead of four scattered ones): bit e (e < 16) = the res_sign bit of
+ *             the e-th salient column of the half of columns 0..63 of (row, block), bit 16 + e = the same for the
+ *             half of columns 64..127; bits of entries that do not exist are 0.  Entries past the 16th of a half
+ *             are read from res_sign.
  * Rows >= n and blocks >= k/128 of the padding are all-zero (nothing kept). */
 #define STB_KIND_ROWMAJOR 0
 #define STB_KIND_TILED 1
@@ -137,6 +142,8 @@ typedef struct stb_layout {
     int64_t image_bytes;       /* size of one allocation holding all planes at the offsets above */
     uint32_t *mask, *sign, *region, *res_sign, *sal_bitmap, *sal_block_prefix, *sal_tab;
     uint16_t *scales, *res_scale;
+    int64_t res_t_bytes, off_res_t;   /* tiled, S > 0: the plane res_t (below), else 0 */
+    uint32_t *res_t;
 } stb_layout_t;
 
 /* Closed-form sizes and image offsets for `cfg` (Sec. 3.4 "Average Bits" gives the payload: N/M sign bits

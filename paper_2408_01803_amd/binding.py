@@ -54,6 +54,7 @@ class stb_layout_t(C.Structure):
         + [(name, C.c_void_p) for name in (
             "mask", "sign", "region", "res_sign", "sal_bitmap", "sal_block_prefix", "sal_tab",
             "scales", "res_scale")]
+        + [("res_t_bytes", C.c_int64), ("off_res_t", C.c_int64), ("res_t", C.c_void_p)]
     )
 
 

@@ -45,6 +45,20 @@ def build(verbose: bool = True) -> str:
     # the translation units are independent: compile them side by side (five processes)
     with ThreadPoolExecutor(max_workers=len(cmds)) as pool:
         list(pool.map(_run, cmds))
+    # the loads issued from asm statements must keep their distance from scalar restores (see isa_check)
+    try:
+        from . import isa_check
+    except ImportError:                      # run as a script
+        sys.path.insert(0, PKG)
+        import isa_check
+    dev = [os.path.join(CSRC, src) for src in DEVICE_SOURCES]
+    with ThreadPoolExecutor(max_workers=len(dev)) as pool:
+        found = list(pool.map(lambda src: isa_check.check_source(src, BUILD, HIPCC, [*DEVICE_FLAGS, *inc]), dev))
+    for src, f in zip(DEVICE_SOURCES, found):
+        for w_line, w, m_line, m, ws in f:
+            print(f"{src}.s:{m_line}: '{m}' reads a scalar that '{w}' (line {w_line}) wrote {ws} wait states earlier", flush=True)
+    if any(found):
+        raise RuntimeError("scalar-to-vector-memory hazard in the generated code: see the lines above")
     tmp = LIB + ".tmp"
     _run([HIPCC, "-shared", "-fPIC", f"--offload-arch={ARCH}", "-o", tmp, *objs, "-pthread"])
     shutil.move(tmp, LIB)

@@ -49,10 +49,16 @@ struct Tile24 {
     uint2_t r0, r1;
     uint2_t sc;
     uint32_t ar;
-    uint32_t e00, e01, e10, e11;      // res_sign words: half 0 low / high, half 1 low / high
+    uint32_t et;                      // res_t word: residual sign bits of the first 16 salient columns of half 0 | half 1 << 16
 };
 constexpr int LMAIN24 = 8;            // load instructions per tile: packed planes ...
-constexpr int LRES24 = 4;             // ... and res_sign words
+constexpr int LRES24 = 1;             // ... and the res_t word
+
+// A vector-memory instruction that takes an SGPR written by a vector-ALU instruction less than five wait states
+// earlier reads the old value (the hardware does not interlock this case).  The compiler pads its own loads, but it
+// does not look into an asm statement -- and it restores spilled scalars with v_readlane right in front of their
+// use.  So every asm statement with a scalar base starts with five wait states of its own.
+#define STB24_SGPR_SETTLE "s_nop 4\n\t"
 
 // The loads are asm statements with the plane base in SGPRs; wait24 names their destination registers.  Between
 // a fetch and its wait the registers must not pass through a copy or a join of two definitions (the compiler
@@ -62,34 +68,34 @@ __device__ inline void fetch24(Tile24& d, const TiledPlanes& p, int tile, uint32
     // launcher), so that the only scalars a fetch needs are the five plane pointers.
     const uint32_t t10 = (uint32_t)tile << 10;
     const uint32_t vm = t10 + o8, vs = (t10 >> 1) + o4, vc = (t10 >> 1) + o8, va = (t10 >> 3) + o2;
-    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.m0) : "v"(vm), "s"(p.mask));
-    asm volatile("global_load_dwordx2 %0, %1, %2 offset:512" : "=v"(d.m1) : "v"(vm), "s"(p.mask));
-    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.s0) : "v"(vs), "s"(p.sign));
-    asm volatile("global_load_dword %0, %1, %2 offset:256" : "=v"(d.s1) : "v"(vs), "s"(p.sign));
-    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.r0) : "v"(vm), "s"(p.region));
-    asm volatile("global_load_dwordx2 %0, %1, %2 offset:512" : "=v"(d.r1) : "v"(vm), "s"(p.region));
-    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.sc) : "v"(vc), "s"(p.scales));
-    asm volatile("global_load_ushort %0, %1, %2" : "=v"(d.ar) : "v"(va), "s"(p.res_scale));
+    asm volatile(STB24_SGPR_SETTLE
+                 "global_load_dwordx2 %0, %8, %12\n\t"
+                 "global_load_dwordx2 %1, %8, %12 offset:512\n\t"
+                 "global_load_dword %2, %9, %13\n\t"
+                 "global_load_dword %3, %9, %13 offset:256\n\t"
+                 "global_load_dwordx2 %4, %8, %14\n\t"
+                 "global_load_dwordx2 %5, %8, %14 offset:512\n\t"
+                 "global_load_dwordx2 %6, %10, %15\n\t"
+                 "global_load_ushort %7, %11, %16"
+                 : "=&v"(d.m0), "=&v"(d.m1), "=&v"(d.s0), "=&v"(d.s1), "=&v"(d.r0), "=&v"(d.r1), "=&v"(d.sc), "=&v"(d.ar)
+                 : "v"(vm), "v"(vs), "v"(vc), "v"(va), "s"(p.mask), "s"(p.sign), "s"(p.region), "s"(p.scales), "s"(p.res_scale));
 }
 
-// The four res_sign words of the lane's row in row tile rt: byte offsets o[h][0 / 1] inside the tile's words.
-__device__ inline void fetch24_res(Tile24& d, const TiledPlanes& p, int rt, uint32_t o00, uint32_t o01, uint32_t o10, uint32_t o11) {
-    const uint32_t base = (uint32_t)rt * (uint32_t)p.res_words * 64u;
-    const uint32_t v00 = base + o00, v01 = base + o01, v10 = base + o10, v11 = base + o11;
-    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e00) : "v"(v00), "s"(p.res_sign));
-    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e01) : "v"(v01), "s"(p.res_sign));
-    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e10) : "v"(v10), "s"(p.res_sign));
-    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e11) : "v"(v11), "s"(p.res_sign));
+// The res_t word of the lane's (row, block) in tile `tile` (lane records of 4 bytes: the lane offset of the sign plane).
+template <typename T>
+__device__ inline void fetch24_res(T& d, const TiledPlanes& p, int tile, uint32_t o4) {
+    const uint32_t v = ((uint32_t)tile << 8) + o4;
+    asm volatile(STB24_SGPR_SETTLE "global_load_dword %0, %1, %2" : "=&v"(d.et) : "v"(v), "s"(p.res_t));
 }
 
 template <int K>
 __device__ inline void wait24(Tile24& d) {
-    asm volatile("s_waitcnt vmcnt(%12)"
+    asm volatile("s_waitcnt vmcnt(%9)"
                  : "+v"(d.m0), "+v"(d.m1), "+v"(d.s0), "+v"(d.s1), "+v"(d.r0), "+v"(d.r1), "+v"(d.sc), "+v"(d.ar),
-                   "+v"(d.e00), "+v"(d.e01), "+v"(d.e10), "+v"(d.e11)
+                   "+v"(d.et)
                  : "n"(K));
 }
-// The same in two steps: the packed planes (the older loads of a tile), then the res_sign words.
+// The same in two steps: the packed planes (the older loads of a tile), then the res_t word.
 template <int K>
 __device__ inline void wait24_main(Tile24& d) {
     asm volatile("s_waitcnt vmcnt(%8)"
@@ -98,7 +104,7 @@ __device__ inline void wait24_main(Tile24& d) {
 }
 template <int K, typename T>
 __device__ inline void wait24_res(T& d) {
-    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(d.e00), "+v"(d.e01), "+v"(d.e10), "+v"(d.e11) : "n"(K));
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(d.et) : "n"(K));
 }
 
 // The same for 6:8 layers: 12 bytes of sign bits per block (not cut in halves), 12 bytes of ids per half block.
@@ -108,7 +114,7 @@ struct Tile68 {
     uint3_t r0, r1;
     uint2_t sc;
     uint32_t ar;
-    uint32_t e00, e01, e10, e11;
+    uint32_t et;
 };
 constexpr int LMAIN68 = 7;
 
@@ -117,29 +123,23 @@ __device__ inline void fetch24(Tile68& d, const TiledPlanes& p, int tile, uint32
     const uint32_t o12 = o4 * 3u;
     const uint32_t vm = t10 + o8, vs = (uint32_t)tile * 768u + o12, vr = (uint32_t)tile * 1536u + o12;
     const uint32_t vc = (t10 >> 1) + o8, va = (t10 >> 3) + o2;
-    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.m0) : "v"(vm), "s"(p.mask));
-    asm volatile("global_load_dwordx2 %0, %1, %2 offset:512" : "=v"(d.m1) : "v"(vm), "s"(p.mask));
-    asm volatile("global_load_dwordx3 %0, %1, %2" : "=v"(d.s) : "v"(vs), "s"(p.sign));
-    asm volatile("global_load_dwordx3 %0, %1, %2" : "=v"(d.r0) : "v"(vr), "s"(p.region));
-    asm volatile("global_load_dwordx3 %0, %1, %2 offset:768" : "=v"(d.r1) : "v"(vr), "s"(p.region));
-    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(d.sc) : "v"(vc), "s"(p.scales));
-    asm volatile("global_load_ushort %0, %1, %2" : "=v"(d.ar) : "v"(va), "s"(p.res_scale));
-}
-
-__device__ inline void fetch24_res(Tile68& d, const TiledPlanes& p, int rt, uint32_t o00, uint32_t o01, uint32_t o10, uint32_t o11) {
-    const uint32_t base = (uint32_t)rt * (uint32_t)p.res_words * 64u;
-    const uint32_t v00 = base + o00, v01 = base + o01, v10 = base + o10, v11 = base + o11;
-    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e00) : "v"(v00), "s"(p.res_sign));
-    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e01) : "v"(v01), "s"(p.res_sign));
-    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e10) : "v"(v10), "s"(p.res_sign));
-    asm volatile("global_load_dword %0, %1, %2" : "=v"(d.e11) : "v"(v11), "s"(p.res_sign));
+    asm volatile(STB24_SGPR_SETTLE
+                 "global_load_dwordx2 %0, %7, %12\n\t"
+                 "global_load_dwordx2 %1, %7, %12 offset:512\n\t"
+                 "global_load_dwordx3 %2, %8, %13\n\t"
+                 "global_load_dwordx3 %3, %9, %14\n\t"
+                 "global_load_dwordx3 %4, %9, %14 offset:768\n\t"
+                 "global_load_dwordx2 %5, %10, %15\n\t"
+                 "global_load_ushort %6, %11, %16"
+                 : "=&v"(d.m0), "=&v"(d.m1), "=&v"(d.s), "=&v"(d.r0), "=&v"(d.r1), "=&v"(d.sc), "=&v"(d.ar)
+                 : "v"(vm), "v"(vs), "v"(vr), "v"(vc), "v"(va), "s"(p.mask), "s"(p.sign), "s"(p.region), "s"(p.scales), "s"(p.res_scale));
 }
 
 template <int K>
 __device__ inline void wait24(Tile68& d) {
-    asm volatile("s_waitcnt vmcnt(%11)"
+    asm volatile("s_waitcnt vmcnt(%8)"
                  : "+v"(d.m0), "+v"(d.m1), "+v"(d.s), "+v"(d.r0), "+v"(d.r1), "+v"(d.sc), "+v"(d.ar),
-                   "+v"(d.e00), "+v"(d.e01), "+v"(d.e10), "+v"(d.e11)
+                   "+v"(d.et)
                  : "n"(K));
 }
 template <int K>
@@ -220,14 +220,12 @@ __device__ inline uint32_t index_word(uint32_t m, uint32_t T0, uint32_t T1, uint
 
 // One wavefront-wide global -> LDS load of 16 bytes per active lane: lane l's bytes land at LDS address m0 + 16 * l.
 __device__ inline void load_to_lds24(uint32_t lds_addr, uint32_t voff, const void* base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\t" STB24_SGPR_SETTLE "global_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
 }
 
 struct Res24 {
     ResSel sel;
     uint32_t xs[4];     // x at the 8 salient columns of the record (B operand of the dense instruction)
-    uint32_t o0, o1;    // byte offsets, inside a row tile's res_sign words, of the two words with the half's bits
-    uint32_t sh;        // bit of the first entry inside the first word
 };
 
 // One layer of a launch: its planes, vectors, scratch and launch shape (see stb_tiled_gemv24_plan), and where its
@@ -308,17 +306,15 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
     ResSel sel2[2];                                              // second record (half blocks with 9..16 salient columns)
     uint32_t xs2[2][4];
     int nch0 = 0, nch1 = 0;
-    // byte offsets of the res_sign words (half 0 low / high, half 1 low / high) of the visit the fetches are at
-    uint32_t ovp[4] = {0u, 0u, 0u, 0u};
     Tile t0 = {}, t1 = {}, t2 = {};
     constexpr int LMAIN = TileOf<MODE>::lmain;
     constexpr int L = LMAIN + (HAS_RES ? LRES24 : 0);            // loads per tile in the streaming loop
-    auto fetch_res = [&](Tile& t, int rt) {
-        if constexpr (HAS_RES) fetch24_res(t, p, __builtin_amdgcn_readfirstlane(rt), ovp[0], ovp[1], ovp[2], ovp[3]);
+    auto fetch_res = [&](Tile& t, int rt, int v) {
+        if constexpr (HAS_RES) fetch24_res(t, p, tile_of(__builtin_amdgcn_readfirstlane(rt), __builtin_amdgcn_readfirstlane(v)), o4);
     };
     auto fetch_tile = [&](Tile& t, int rt, int v) {
         fetch24(t, p, tile_of(__builtin_amdgcn_readfirstlane(rt), __builtin_amdgcn_readfirstlane(v)), o8, o4, o2);
-        fetch_res(t, rt);
+        fetch_res(t, rt, v);
     };
     if (MULTI && active) {
         // ---- several visits: the slices of x and the record sets go from global memory straight to LDS (no staging
@@ -482,11 +478,6 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
                 const uint32_t ord = rb.x;
                 const int nc = __builtin_amdgcn_readfirstlane((int)rb.y);
                 if (h == 0) nch0 = nc; else nch1 = nc;
-                inv[h].sh = ord & 31u;
-                const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
-                const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
-                inv[h].o0 = (uint32_t)(wa * 16 + i) * 4u;
-                inv[h].o1 = (uint32_t)(wb * 16 + i) * 4u;
                 gather(rp, inv[h].xs);
                 if (nc > 1) {                        // the second record of the half block
                     const uint4_t rc = *reinterpret_cast<const uint4_t*>(rec + 12);
@@ -500,24 +491,11 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
     // producer side of the three tile buffers.  Order of the products of a workgroup: phase by phase (PHT row tiles),
     // inside a phase visit by visit, inside a visit row tile by row tile -- so that a wavefront takes the operands of a
     // visit (64 registers of x, the gathered salient x) once per phase and visit, not once per product.
-    // the res_sign offsets of visit v, from its records in LDS (the tiles are fetched ahead of the visits' other operands)
-    auto res_offsets = [&](int v) {
-        const int ve = sb + v * SPS < p.nsb ? v : 0;
-#pragma unroll
-        for (int h = 0; h < 2; h++) {
-            const uint32_t ord = recs[ve * 192 + (g * 2 + h) * 24 + 4];
-            const int wa = (int)(ord >> 5) < p.res_words ? (int)(ord >> 5) : p.res_words - 1;
-            const int wb = wa + 1 < p.res_words ? wa + 1 : wa;
-            ovp[2 * h] = (uint32_t)(wa * 16 + i) * 4u;
-            ovp[2 * h + 1] = (uint32_t)(wb * 16 + i) * 4u;
-        }
-    };
     int p_ph0 = r0, p_n = r1 - r0 < PHT ? r1 - r0 : PHT, p_i = 0, p_v = 0;
     auto advance = [&]() {
         if (++p_i == p_n) {
             p_i = 0;
             if (++p_v == V) { p_v = 0; p_ph0 += p_n; p_n = r1 - p_ph0 < PHT ? r1 - p_ph0 : PHT; }
-            if (MULTI && HAS_RES) res_offsets(p_v);
         }
     };
     auto fetch_next = [&](Tile& t) {
@@ -529,16 +507,11 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
         }
     };
     if (active) {
-        if (!MULTI) {
-            visit_setup(0);
-            ovp[0] = inv[0].o0; ovp[1] = inv[0].o1; ovp[2] = inv[1].o0; ovp[3] = inv[1].o1;
-        } else if (HAS_RES) {
-            res_offsets(0);
-        }
+        if (!MULTI) visit_setup(0);
         // with one visit the partial products overwrite the x rows: every read above must have returned
         __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
         __builtin_amdgcn_sched_barrier(0);
-        fetch_res(t0, clamp(r0));
+        fetch_res(t0, clamp(r0), 0);
         if (p_n > 0) advance();                      // t0 holds (r0, visit 0)
         fetch_next(t1);
         fetch_next(t2);
@@ -611,13 +584,12 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
             }
         }
         if (HAS_RES) {
-            wait24_res<2 * L>(tr);                    // the tile's res_sign words: younger than its packed planes
+            wait24_res<2 * L>(tr);                    // the tile's res_t word: younger than its packed planes
             const uint32_t ar1 = tr.ar & 0xFFFFu, ar2 = ar1 | (ar1 << 16);
 #pragma unroll
             for (int h = 0; h < 2; h++) {
                 if ((h == 0 ? nch0 : nch1) > 0) {
-                    const uint32_t rlo = h == 0 ? tr.e00 : tr.e10, rhi = h == 0 ? tr.e01 : tr.e11;
-                    const uint32_t rb = __builtin_amdgcn_alignbit(rhi, rlo, inv[h].sh);
+                    const uint32_t rb = h == 0 ? tr.et : tr.et >> 16;      // bits 0..7: first record, 8..15: second
                     uint32_t o[4];
                     residual_chunk(&mw[2 * h], rb, ar2, inv[h].sel, o);
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(o), as_half8(inv[h].xs), acc, 0, 0, 0);

@@ -61,7 +61,7 @@ namespace {
 void place_planes(stb_layout_t* out) {
     out->total_bytes = out->mask_bytes + out->sign_bytes + out->region_bytes + out->res_bytes +
                        out->scales_bytes + out->res_scale_bytes + out->salmap_bytes + out->salprefix_bytes +
-                       out->saltab_bytes;
+                       out->saltab_bytes + out->res_t_bytes;
     int64_t off = 0;
     auto place = [&](int64_t bytes) {
         int64_t o = off;
@@ -77,6 +77,7 @@ void place_planes(stb_layout_t* out) {
     out->off_salmap = place(out->salmap_bytes);
     out->off_salprefix = place(out->salprefix_bytes);
     out->off_saltab = place(out->saltab_bytes);
+    out->off_res_t = place(out->res_t_bytes);
     out->image_bytes = off;
 }
 
@@ -142,6 +143,7 @@ extern "C" int stb_tiled_sizes(const stb_cfg_t* cfg, stb_layout_t* out) {
     out->salmap_bytes = nsb * 4 * 16;
     out->salprefix_bytes = 4 * (nsb * 4 + 1);
     out->saltab_bytes = nsb * 4 * 2 * out->sal_chunks * 48;
+    out->res_t_bytes = cfg->n_salient > 0 ? rec * 4 : 0;
     place_planes(out);
     return STB_OK;
 }
@@ -159,6 +161,7 @@ extern "C" int stb_layout_bind(stb_layout_t* L, void* base) {
     L->sal_bitmap = (uint32_t*)(b + L->off_salmap);
     L->sal_block_prefix = (uint32_t*)(b + L->off_salprefix);
     L->sal_tab = (uint32_t*)(b + L->off_saltab);
+    L->res_t = (uint32_t*)(b + L->off_res_t);
     return STB_OK;
 }
 
@@ -180,11 +183,11 @@ extern "C" int stb_layout_check(const stb_layout_t* L) {
         return STB_EINVAL;
     if (L->kind == STB_KIND_TILED && (L->max_sal_block < 0 || L->max_sal_block > 16 * L->sal_chunks ||
                                       L->max_sal_half < 0 || L->max_sal_half > 8 * L->sal_chunks)) return STB_EINVAL;
-    const void* ptrs[9] = {L->mask, L->sign, L->region, L->res_sign, L->scales, L->res_scale,
-                           L->sal_bitmap, L->sal_block_prefix, L->sal_tab};
-    for (int i = 0; i < 9; i++) {
-        if ((i == 3 || i == 8) && L->cfg.n_salient == 0) continue;   // res_sign / sal_tab may be absent
-        if (i == 8 && L->kind == STB_KIND_ROWMAJOR) continue;
+    const void* ptrs[10] = {L->mask, L->sign, L->region, L->res_sign, L->scales, L->res_scale,
+                            L->sal_bitmap, L->sal_block_prefix, L->sal_tab, L->res_t};
+    for (int i = 0; i < 10; i++) {
+        if ((i == 3 || i >= 8) && L->cfg.n_salient == 0) continue;   // res_sign / sal_tab / res_t may be absent
+        if (i >= 8 && L->kind == STB_KIND_ROWMAJOR) continue;
         if (!ptrs[i]) return STB_ENULL;
         if ((uintptr_t)ptrs[i] % 16) return STB_EALIGN;
     }
@@ -341,6 +344,30 @@ int fill_sal_tab(const stb_layout_t* tl, const uint32_t* bitmap, int k, const ui
 
 }  // namespace
 
+// res_t of the tiled order: per (row, block) the res_sign bits of the first 16 salient columns of each half block,
+// half 0 in bits 0..15, half 1 in bits 16..31, at the lane record of (row, block).
+void fill_res_t(const stb_layout_t* rm, const stb_layout_t* tl) {
+    const int n = rm->cfg.n_out, nb = rm->n_blocks, nsb = tl->n_super;
+    std::memset(tl->res_t, 0, (size_t)tl->res_t_bytes);
+    for (int r = 0; r < n; r++) {
+        const uint32_t* row = (const uint32_t*)((const uint8_t*)rm->res_sign + (int64_t)r * rm->res_stride);
+        for (int q = 0; q < nb; q++) {
+            uint32_t ord = rm->sal_block_prefix[q], word = 0;
+            for (int h = 0; h < 2; h++) {
+                int e = 0;
+                for (int c = 64 * h; c < 64 * h + 64; c++) {
+                    if (!sal_bit(rm->sal_bitmap, q * STB_BLOCK + c)) continue;
+                    if (e < 16 && ((row[ord >> 5] >> (ord & 31)) & 1u)) word |= 1u << (16 * h + e);
+                    e++;
+                    ord++;
+                }
+            }
+            const int64_t tile = (int64_t)(r / 16) * nsb + q / 4;
+            tl->res_t[tile * 64 + 16 * (q % 4) + (r % 16)] = word;
+        }
+    }
+}
+
 // The derived tables of the tiled order from the salient bitmap alone (host arrays): bitmap and prefix padded to whole
 // superblocks, the table of salient columns, the two maxima.  Shared by stb_tile and the device tiling.
 extern "C" int stb_host_tiled_tables(const stb_layout_t* tl, const uint32_t* bitmap, const uint32_t* prefix,
@@ -384,6 +411,7 @@ extern "C" int stb_tile(const stb_layout_t* src, stb_layout_t* dst) {
     for (int q = 0; q <= nsb * 4; q++) dst->sal_block_prefix[q] = src->sal_block_prefix[std::min(q, nb)];
     int mh = 0;
     const int mx = dst->cfg.n_salient ? fill_sal_tab(dst, src->sal_bitmap, k, dst->sal_block_prefix, &mh) : 0;
+    if (dst->cfg.n_salient) fill_res_t(src, dst);
     dst->max_sal_block = mx;
     dst->max_sal_half = mh;
     return STB_OK;

@@ -602,6 +602,30 @@ __global__ void k_tile_res(TK a) {
     a.tres_sign[((int64_t)(r / 16) * a.res_words + w) * 16 + r % 16] = a.rres_sign[(int64_t)r * (a.rres_stride / 4) + w];
 }
 
+// res_t: per (row, block) the res_sign bits of the first 16 salient columns of each half block; one thread per record
+__global__ void k_tile_res_t(TK a, const uint32_t* __restrict__ bitmap, const uint32_t* __restrict__ prefix,
+                             uint32_t* __restrict__ res_t) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)a.n * a.nb) return;
+    const int r = (int)(idx / a.nb), q = (int)(idx % a.nb);
+    const uint32_t* row = a.rres_sign + (int64_t)r * (a.rres_stride / 4);
+    uint32_t ord = prefix[q], word = 0;
+    for (int h = 0; h < 2; h++) {
+        int e = 0;
+        for (int u = 0; u < 2; u++) {
+            uint32_t bits = bitmap[4 * q + 2 * h + u];
+            while (bits) {
+                bits &= bits - 1;
+                if (e < 16 && ((row[ord >> 5] >> (ord & 31)) & 1u)) word |= 1u << (16 * h + e);
+                e++;
+                ord++;
+            }
+        }
+    }
+    const int64_t tile = (int64_t)(r / 16) * a.nsb + q / 4;
+    res_t[tile * 64 + 16 * (q % 4) + (r % 16)] = word;
+}
+
 }  // namespace
 
 // src: checked row-major layout, dst: checked tiled layout of the same cfg, both bound to device memory.
@@ -616,6 +640,14 @@ extern "C" int stb_tile_gpu(const stb_layout_t* src, stb_layout_t* dst, void* st
     ok(hipMemcpyAsync(prefix.data(), src->sal_block_prefix, 4 * ((size_t)nb + 1), hipMemcpyDeviceToHost, st));
     ok(hipStreamSynchronize(st));
     if (e != hipSuccess) { *hip_err = (int)e; return STB_EHIP; }
+    {   // the kernels index the res_sign rows through these tables: they must describe cfg.n_salient columns
+        uint32_t run = 0;
+        for (int q = 0; q < nb; q++) {
+            if (prefix[q] != run) return STB_EINVAL;
+            for (int u = 0; u < 4; u++) run += (uint32_t)__builtin_popcount(bitmap[4 * q + u]);
+        }
+        if (prefix[nb] != run || run != (uint32_t)src->cfg.n_salient) return STB_EINVAL;
+    }
     std::vector<uint32_t> bm_out((size_t)dst->salmap_bytes / 4), pf_out((size_t)dst->salprefix_bytes / 4),
         tab((size_t)dst->saltab_bytes / 4 + 1, 0u);
     int mx = 0, mh = 0;
@@ -630,6 +662,7 @@ extern "C" int stb_tile_gpu(const stb_layout_t* src, stb_layout_t* dst, void* st
     ok(hipMemsetAsync(dst->scales, 0, (size_t)dst->scales_bytes, st));
     ok(hipMemsetAsync(dst->res_scale, 0, (size_t)dst->res_scale_bytes, st));
     if (dst->res_bytes) ok(hipMemsetAsync(dst->res_sign, 0, (size_t)dst->res_bytes, st));
+    if (dst->res_t_bytes) ok(hipMemsetAsync(dst->res_t, 0, (size_t)dst->res_t_bytes, st));
     TK a;
     a.rmask = (const uint8_t*)src->mask; a.rsign = (const uint8_t*)src->sign; a.rreg = (const uint8_t*)src->region;
     a.rscales = src->scales; a.rres_scale = src->res_scale; a.rres_sign = (const uint32_t*)src->res_sign;
@@ -654,6 +687,8 @@ extern "C" int stb_tile_gpu(const stb_layout_t* src, stb_layout_t* dst, void* st
     if (a.res_words > 0) {
         const int64_t words = (int64_t)a.n * a.res_words;
         hipLaunchKernelGGL(k_tile_res, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(k_tile_res_t, dim3((unsigned)((recs + 255) / 256)), dim3(256), 0, st, a, src->sal_bitmap,
+                           src->sal_block_prefix, dst->res_t);
     }
     ok(hipGetLastError());
     uint32_t status = 0;

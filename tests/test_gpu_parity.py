@@ -173,7 +173,7 @@ def test_pack_and_tile_on_the_device_feed_the_kernels(case, torch_cuda):
     S.stb_tile_device(rlay, tlay)
     assert (tlay.max_sal_block, tlay.max_sal_half) == (tl_host.max_sal_block, tl_host.max_sal_half)
     got = timg.cpu().numpy()
-    for name, off, size in S.PLANE_FIELDS + (("sal_tab", "off_saltab", "saltab_bytes"),):
+    for name, off, size in S.PLANE_FIELDS + (("sal_tab", "off_saltab", "saltab_bytes"), ("res_t", "off_res_t", "res_t_bytes")):
         o, sz = getattr(tl_host, off), getattr(tl_host, size)
         assert (got[o:o + sz] == timg_host[o:o + sz]).all(), name
     What = O.unpack(O.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode), n, k, N, M)
@@ -748,7 +748,7 @@ def test_full_size_layer(cfg, idx, torch_cuda):
         S.stb_tile_device(row_major.dev_layout, tlay)
         assert (tlay.max_sal_block, tlay.max_sal_half) == (tl_host.max_sal_block, tl_host.max_sal_half)
         got = timg.cpu().numpy()
-        for name, off, size in S.PLANE_FIELDS + (("sal_tab", "off_saltab", "saltab_bytes"),):
+        for name, off, size in S.PLANE_FIELDS + (("sal_tab", "off_saltab", "saltab_bytes"), ("res_t", "off_res_t", "res_t_bytes")):
             o, sz = getattr(tl_host, off), getattr(tl_host, size)
             assert (got[o:o + sz] == timg_host[o:o + sz]).all(), ("device tiling", name)
         del timg, got

@@ -256,6 +256,21 @@ def test_tile_untile_round_trip_is_a_byte_permutation(n, k, N, M, mode, kind, se
         rm = np.zeros((tl.n_row_tiles * 16, words), "<u4")
         rm[:n] = pm.plane("res_sign").view("<u4").reshape(n, words)
         assert (t.transpose(0, 2, 1).reshape(-1, words) == rm).all()
+    # res_t: per (row, block) lane record, the res_sign bits of the first 16 salient columns of each half block
+    if tl.res_bytes:
+        assert tl.res_t_bytes == nrt * nsb * 64 * 4
+        rt = timg[tl.off_res_t:tl.off_res_t + tl.res_t_bytes].view("<u4").reshape(nrt, nsb, 4, 16)
+        rs_bits = np.unpackbits(pm.plane("res_sign").reshape(n, -1), axis=1, bitorder="little")
+        sal_cols = [int(c) for c in L["sal_cols"]]
+        want = np.zeros((nrt * 16, nsb * 4), np.uint32)
+        for q in range(nb):
+            for h in range(2):
+                entries = [u for u, c in enumerate(sal_cols) if 128 * q + 64 * h <= c < 128 * q + 64 * h + 64][:16]
+                for e, u in enumerate(entries):
+                    want[:n, q] |= rs_bits[:, u].astype(np.uint32) << np.uint32(16 * h + e)
+        assert (rt.transpose(0, 3, 1, 2).reshape(nrt * 16, nsb * 4) == want).all()
+    else:
+        assert tl.res_t_bytes == 0
     # sal_tab: per half block, records of 8 salient columns with the selectors that gather their mask bytes
     if len(L["sal_cols"]):
         C = tl.sal_chunks
