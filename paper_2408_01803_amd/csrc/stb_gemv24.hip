@@ -63,29 +63,52 @@ constexpr int LRES24 = 1;             // ... and the res_t word
 // The loads are asm statements with the plane base in SGPRs; wait24 names their destination registers.  Between
 // a fetch and its wait the registers must not pass through a copy or a join of two definitions (the compiler
 // does not know that the data arrives later).
-__device__ inline void fetch24(Tile24& d, const TiledPlanes& p, int tile, uint32_t o8, uint32_t o4, uint32_t o2) {
-    // The tile's position goes into the 32-bit lane offset (the planes are smaller than 2 GiB: checked by the
-    // launcher), so that the only scalars a fetch needs are the five plane pointers.
+// Byte offsets of the lane's records in tile 0 of each plane, counted from the lowest plane address of the layer
+// (`image`): with them a tile's loads need one scalar base, and the tile's position goes into the 32-bit offsets
+// (the launcher checks that the planes lie within 4 GiB of that address).
+struct LaneOff24 {
+    uint32_t m, s, r, c, a, t;        // mask, sign, region, scales, res_scale, res_t
+};
+
+// The loads of one tile, one asm statement: packed planes first, then (RES) the res_t word.
+template <bool RES>
+__device__ inline void fetch24(Tile24& d, const char* image, int tile, const LaneOff24& lo) {
     const uint32_t t10 = (uint32_t)tile << 10;
-    const uint32_t vm = t10 + o8, vs = (t10 >> 1) + o4, vc = (t10 >> 1) + o8, va = (t10 >> 3) + o2;
-    asm volatile(STB24_SGPR_SETTLE
-                 "global_load_dwordx2 %0, %8, %12\n\t"
-                 "global_load_dwordx2 %1, %8, %12 offset:512\n\t"
-                 "global_load_dword %2, %9, %13\n\t"
-                 "global_load_dword %3, %9, %13 offset:256\n\t"
-                 "global_load_dwordx2 %4, %8, %14\n\t"
-                 "global_load_dwordx2 %5, %8, %14 offset:512\n\t"
-                 "global_load_dwordx2 %6, %10, %15\n\t"
-                 "global_load_ushort %7, %11, %16"
-                 : "=&v"(d.m0), "=&v"(d.m1), "=&v"(d.s0), "=&v"(d.s1), "=&v"(d.r0), "=&v"(d.r1), "=&v"(d.sc), "=&v"(d.ar)
-                 : "v"(vm), "v"(vs), "v"(vc), "v"(va), "s"(p.mask), "s"(p.sign), "s"(p.region), "s"(p.scales), "s"(p.res_scale));
+    const uint32_t vm = t10 + lo.m, vr = t10 + lo.r, vs = (t10 >> 1) + lo.s, vc = (t10 >> 1) + lo.c, va = (t10 >> 3) + lo.a;
+    if constexpr (RES) {
+        const uint32_t vt = (t10 >> 2) + lo.t;
+        asm volatile(STB24_SGPR_SETTLE
+                     "global_load_dwordx2 %0, %9, %15\n\t"
+                     "global_load_dwordx2 %1, %9, %15 offset:512\n\t"
+                     "global_load_dword %2, %10, %15\n\t"
+                     "global_load_dword %3, %10, %15 offset:256\n\t"
+                     "global_load_dwordx2 %4, %11, %15\n\t"
+                     "global_load_dwordx2 %5, %11, %15 offset:512\n\t"
+                     "global_load_dwordx2 %6, %12, %15\n\t"
+                     "global_load_ushort %7, %13, %15\n\t"
+                     "global_load_dword %8, %14, %15"
+                     : "=&v"(d.m0), "=&v"(d.m1), "=&v"(d.s0), "=&v"(d.s1), "=&v"(d.r0), "=&v"(d.r1), "=&v"(d.sc), "=&v"(d.ar), "=&v"(d.et)
+                     : "v"(vm), "v"(vs), "v"(vr), "v"(vc), "v"(va), "v"(vt), "s"(image));
+    } else {
+        asm volatile(STB24_SGPR_SETTLE
+                     "global_load_dwordx2 %0, %8, %13\n\t"
+                     "global_load_dwordx2 %1, %8, %13 offset:512\n\t"
+                     "global_load_dword %2, %9, %13\n\t"
+                     "global_load_dword %3, %9, %13 offset:256\n\t"
+                     "global_load_dwordx2 %4, %10, %13\n\t"
+                     "global_load_dwordx2 %5, %10, %13 offset:512\n\t"
+                     "global_load_dwordx2 %6, %11, %13\n\t"
+                     "global_load_ushort %7, %12, %13"
+                     : "=&v"(d.m0), "=&v"(d.m1), "=&v"(d.s0), "=&v"(d.s1), "=&v"(d.r0), "=&v"(d.r1), "=&v"(d.sc), "=&v"(d.ar)
+                     : "v"(vm), "v"(vs), "v"(vr), "v"(vc), "v"(va), "s"(image));
+    }
 }
 
-// The res_t word of the lane's (row, block) in tile `tile` (lane records of 4 bytes: the lane offset of the sign plane).
+// The res_t word of the lane's (row, block) in tile `tile` alone (lane records of 4 bytes).
 template <typename T>
-__device__ inline void fetch24_res(T& d, const TiledPlanes& p, int tile, uint32_t o4) {
-    const uint32_t v = ((uint32_t)tile << 8) + o4;
-    asm volatile(STB24_SGPR_SETTLE "global_load_dword %0, %1, %2" : "=&v"(d.et) : "v"(v), "s"(p.res_t));
+__device__ inline void fetch24_res(T& d, const char* image, int tile, const LaneOff24& lo) {
+    const uint32_t v = ((uint32_t)tile << 8) + lo.t;
+    asm volatile(STB24_SGPR_SETTLE "global_load_dword %0, %1, %2" : "=&v"(d.et) : "v"(v), "s"(image));
 }
 
 template <int K>
@@ -118,21 +141,36 @@ struct Tile68 {
 };
 constexpr int LMAIN68 = 7;
 
-__device__ inline void fetch24(Tile68& d, const TiledPlanes& p, int tile, uint32_t o8, uint32_t o4, uint32_t o2) {
+template <bool RES>
+__device__ inline void fetch24(Tile68& d, const char* image, int tile, const LaneOff24& lo) {
     const uint32_t t10 = (uint32_t)tile << 10;
-    const uint32_t o12 = o4 * 3u;
-    const uint32_t vm = t10 + o8, vs = (uint32_t)tile * 768u + o12, vr = (uint32_t)tile * 1536u + o12;
-    const uint32_t vc = (t10 >> 1) + o8, va = (t10 >> 3) + o2;
-    asm volatile(STB24_SGPR_SETTLE
-                 "global_load_dwordx2 %0, %7, %12\n\t"
-                 "global_load_dwordx2 %1, %7, %12 offset:512\n\t"
-                 "global_load_dwordx3 %2, %8, %13\n\t"
-                 "global_load_dwordx3 %3, %9, %14\n\t"
-                 "global_load_dwordx3 %4, %9, %14 offset:768\n\t"
-                 "global_load_dwordx2 %5, %10, %15\n\t"
-                 "global_load_ushort %6, %11, %16"
-                 : "=&v"(d.m0), "=&v"(d.m1), "=&v"(d.s), "=&v"(d.r0), "=&v"(d.r1), "=&v"(d.sc), "=&v"(d.ar)
-                 : "v"(vm), "v"(vs), "v"(vr), "v"(vc), "v"(va), "s"(p.mask), "s"(p.sign), "s"(p.region), "s"(p.scales), "s"(p.res_scale));
+    const uint32_t vm = t10 + lo.m, vs = (uint32_t)tile * 768u + lo.s, vr = (uint32_t)tile * 1536u + lo.r;
+    const uint32_t vc = (t10 >> 1) + lo.c, va = (t10 >> 3) + lo.a;
+    if constexpr (RES) {
+        const uint32_t vt = (t10 >> 2) + lo.t;
+        asm volatile(STB24_SGPR_SETTLE
+                     "global_load_dwordx2 %0, %8, %14\n\t"
+                     "global_load_dwordx2 %1, %8, %14 offset:512\n\t"
+                     "global_load_dwordx3 %2, %9, %14\n\t"
+                     "global_load_dwordx3 %3, %10, %14\n\t"
+                     "global_load_dwordx3 %4, %10, %14 offset:768\n\t"
+                     "global_load_dwordx2 %5, %11, %14\n\t"
+                     "global_load_ushort %6, %12, %14\n\t"
+                     "global_load_dword %7, %13, %14"
+                     : "=&v"(d.m0), "=&v"(d.m1), "=&v"(d.s), "=&v"(d.r0), "=&v"(d.r1), "=&v"(d.sc), "=&v"(d.ar), "=&v"(d.et)
+                     : "v"(vm), "v"(vs), "v"(vr), "v"(vc), "v"(va), "v"(vt), "s"(image));
+    } else {
+        asm volatile(STB24_SGPR_SETTLE
+                     "global_load_dwordx2 %0, %7, %12\n\t"
+                     "global_load_dwordx2 %1, %7, %12 offset:512\n\t"
+                     "global_load_dwordx3 %2, %8, %12\n\t"
+                     "global_load_dwordx3 %3, %9, %12\n\t"
+                     "global_load_dwordx3 %4, %9, %12 offset:768\n\t"
+                     "global_load_dwordx2 %5, %10, %12\n\t"
+                     "global_load_ushort %6, %11, %12"
+                     : "=&v"(d.m0), "=&v"(d.m1), "=&v"(d.s), "=&v"(d.r0), "=&v"(d.r1), "=&v"(d.sc), "=&v"(d.ar)
+                     : "v"(vm), "v"(vs), "v"(vr), "v"(vc), "v"(va), "s"(image));
+    }
 }
 
 template <int K>
@@ -235,6 +273,8 @@ struct Res24 {
 // be captured in a HIP graph.
 struct Gemv24Layer {
     TiledPlanes p;
+    const char* image;        // lowest address of the streamed planes; their offsets from it (all below 4 GiB):
+    uint32_t off_mask, off_sign, off_region, off_scales, off_res_scale, off_res_t;
     const __half* x;
     void* y;
     float* ws_part;
@@ -309,12 +349,15 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
     Tile t0 = {}, t1 = {}, t2 = {};
     constexpr int LMAIN = TileOf<MODE>::lmain;
     constexpr int L = LMAIN + (HAS_RES ? LRES24 : 0);            // loads per tile in the streaming loop
+    const char* const image = d.image;
+    const uint32_t o12 = o4 * 3u;
+    const LaneOff24 lo = {d.off_mask + o8, d.off_sign + (MODE == 6 ? o12 : o4), d.off_region + (MODE == 6 ? o12 : o8),
+                          d.off_scales + o8, d.off_res_scale + o2, d.off_res_t + o4};
     auto fetch_res = [&](Tile& t, int rt, int v) {
-        if constexpr (HAS_RES) fetch24_res(t, p, tile_of(__builtin_amdgcn_readfirstlane(rt), __builtin_amdgcn_readfirstlane(v)), o4);
+        if constexpr (HAS_RES) fetch24_res(t, image, tile_of(__builtin_amdgcn_readfirstlane(rt), __builtin_amdgcn_readfirstlane(v)), lo);
     };
     auto fetch_tile = [&](Tile& t, int rt, int v) {
-        fetch24(t, p, tile_of(__builtin_amdgcn_readfirstlane(rt), __builtin_amdgcn_readfirstlane(v)), o8, o4, o2);
-        fetch_res(t, rt, v);
+        fetch24<HAS_RES>(t, image, tile_of(__builtin_amdgcn_readfirstlane(rt), __builtin_amdgcn_readfirstlane(v)), lo);
     };
     if (MULTI && active) {
         // ---- several visits: the slices of x and the record sets go from global memory straight to LDS (no staging
@@ -344,7 +387,7 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
                 load_to_lds24(lds_w + REC_OFF + v * 768, off, p.sal_tab);
             }
         }
-        fetch24(t0, p, tile_of(clamp(r0)), o8, o4, o2);
+        fetch24<false>(t0, image, tile_of(clamp(r0)), lo);
         if constexpr (MODE != 2) build_luts<N8>(lut);
         asm volatile("s_waitcnt vmcnt(%0)" : : "n"(LMAIN) : "memory");
         if (HAS_RES && lane < 48 && lane % 3 == 2) {
@@ -388,7 +431,7 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
             const uint32_t* src = p.sal_tab + (((int64_t)sb * 8 + rI) * p.sal_chunks + (rc < p.sal_chunks ? rc : 0)) * 12 + 4 * rpc;
             asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(sr) : "v"(src));
         }
-        fetch24(t0, p, tile_of(clamp(r0)), o8, o4, o2);
+        fetch24<false>(t0, image, tile_of(clamp(r0)), lo);
         if constexpr (MODE != 2) build_luts<N8>(lut);
         // The second and third tile go out after the operands are in registers: a compute unit keeps a limited
         // number of loads in flight, and the other wavefront of the SIMD should get its first tile early too
@@ -890,9 +933,27 @@ extern "C" int stb_tiled_gemv24_group(int n_layers, const stb_layout_t* const* L
         if (n8 == 0) return STB_EUNSUPPORTED;
         const int mode = L->cfg.M == 4 && L->cfg.N == 2 ? 2 : n8;      // 2: sparse instruction; 4, 6: dense with the scatter table
         if (mode != 2 && mode != 4 && mode != 6) return STB_EUNSUPPORTED;
-        if (L->region_bytes >= (1ll << 31) || L->res_bytes >= (1ll << 31)) return STB_EUNSUPPORTED;   // 32-bit offsets inside a plane
         Gemv24Layer& d = a.l[l];
         d.p = make_tiled(L);
+        {
+            // one scalar base for the streamed planes: every byte of them must lie within 4 GiB of the lowest plane
+            // (an image laid out by stb_tiled_sizes does unless it is larger than that)
+            const bool has_t = L->cfg.n_salient > 0;
+            const uintptr_t at[6] = {(uintptr_t)L->mask, (uintptr_t)L->sign, (uintptr_t)L->region, (uintptr_t)L->scales,
+                                     (uintptr_t)L->res_scale, has_t ? (uintptr_t)L->res_t : (uintptr_t)L->mask};
+            const int64_t size[6] = {L->mask_bytes, L->sign_bytes, L->region_bytes, L->scales_bytes, L->res_scale_bytes,
+                                     has_t ? L->res_t_bytes : 0};
+            uintptr_t low = at[0];
+            for (int i = 1; i < 6; i++) low = at[i] < low ? at[i] : low;
+            uint32_t off[6];
+            for (int i = 0; i < 6; i++) {
+                if (size[i] < 0 || (uint64_t)(at[i] - low) + (uint64_t)size[i] > 0xFFFFFFFFull) return STB_EUNSUPPORTED;
+                off[i] = (uint32_t)(at[i] - low);
+            }
+            d.image = (const char*)low;
+            d.off_mask = off[0]; d.off_sign = off[1]; d.off_region = off[2]; d.off_scales = off[3];
+            d.off_res_scale = off[4]; d.off_res_t = off[5];
+        }
         int plan[7];
         if (stb_tiled_gemv24_plan(d.p.nrt, d.p.nsb, B, mode, max_splits24(d.p.nsb), cus, plan) != STB_OK) return STB_EUNSUPPORTED;
         d.S = plan[0]; d.R = plan[1]; d.SPS = plan[2]; d.V = plan[3]; d.WREG = plan[4]; d.REC_OFF = plan[5]; d.PART_OFF = plan[6];
