@@ -38,7 +38,6 @@ struct TiledPlanes {
     const uint32_t* sal_bitmap; // [nsb*4][4]
     const uint32_t* sal_prefix; // [nsb*4 + 1]
     const uint32_t* sal_tab;    // [nsb*4][2][sal_chunks][12]
-    const uint32_t* res_t;      // [nrt][nsb][64]: residual sign bits of the first 16 salient columns of each half block
     int n, k, nb, nrt, nsb;
     int res_words;              // uint32 per row of res_sign (0 if no salient columns)
     int sal_chunks;
@@ -55,7 +54,6 @@ inline TiledPlanes make_tiled(const stb_layout_t* L) {
     p.sal_bitmap = L->sal_bitmap;
     p.sal_prefix = L->sal_block_prefix;
     p.sal_tab = L->sal_tab;
-    p.res_t = L->res_t;
     p.n = L->cfg.n_out;
     p.k = L->cfg.k_in;
     p.nb = L->n_blocks;
