@@ -42,10 +42,10 @@ ROW_POOL_BYTES = 600 << 20     # per-layer rotation of the breakdown rows: more 
 # HBM bytes per decode step / per prefill launch from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE on this command (offline
 # runs, scaled by what the same counters read for a copy of known size); the summaries under profiles/ give the runs.
 # None = not measured for the build that is checked in.
-# Decode: 89.56 MB read + 0.26 MB written per launch, average of the step's four launches
+# Decode: 94.50 MB read + 0.26 MB written per launch, average of the step's four launches
 # (profiles/gemv24_group_kernel_workload5_decode_b1.md).  Prefill: bytes read + written per launch of the cases that were
 # measured, keyed by (T, n, k) (profiles/gemm_kernels_workloads4_5_prefill.md).
-MEASURED_DECODE_TRAFFIC_BYTES_PER_LAUNCH = 89_820_000
+MEASURED_DECODE_TRAFFIC_BYTES_PER_LAUNCH = 94_760_000
 MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH = {
     (2048, 4096, 4096): 89_200_000, (8192, 4096, 4096): 421_500_000, (2048, 11008, 4096): 245_900_000,
     (8192, 11008, 4096): 1_151_000_000, (2048, 8192, 8192): 387_000_000, (2048, 1024, 8192): 75_100_000,
