@@ -287,12 +287,18 @@ int stb_dequant(const stb_layout_t* dev, float* W_hat_dev, void* stream);
  * with k > 4096; for smaller k the launcher may still split columns to balance the grid).  The
  * counters (its first 4 * ceil(n / 16) bytes) must be zero before the first call that uses the buffer; every
  * call leaves them zero.  Calls that share a workspace must not overlap in time.
+ * B > 16: the decode kernel takes 16 rows of x per pass.  A tiled layer other than 2:4 runs instead as one pass of
+ * the prefill kernel (the form of stb_gemm for up to 64 tokens: the weights are expanded once for all rows) when the
+ * workspace is as large as stb_gemv_workspace_bytes(cfg, B) asks; with a smaller one (sized for B <= 16, say), on 2:4
+ * layers and under stb_set_kernel_override it runs as two passes of the decode kernel.  Both ways meet the same
+ * error bound; their results differ within rounding.
  * Errors: STB_ENULL, STB_EINVAL, STB_EALIGN, STB_EHIP. */
 int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32,
              void* workspace, int64_t workspace_bytes, void* stream);
 
 /* stb_gemv for callers that cannot allocate or bring a workspace: code under HIP graph capture, tight serving loops,
- * harnesses that forbid hipMalloc.  Same product, same kernels and the same bits in y as stb_gemv, but the scratch of
+ * harnesses that forbid hipMalloc.  Same product, the decode kernels and (for B <= 16, 2:4 layers and any workspace
+ * too small for stb_gemv's one-pass form) the same bits in y as stb_gemv -- B > 16 always runs as two passes here -- but the scratch of
  * the column splits lives in a device array that is part of the library's code object (STB_GEMV_STATIC_SCRATCH_BYTES
  * bytes on every GPU the library runs on, held until the process ends); the call allocates nothing and needs no set-up
  * call (the array's address on the current device is looked up at the first call there).
@@ -306,7 +312,8 @@ int stb_gemv(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t
 int stb_gemv_static(const stb_layout_t* dev, const void* x, int32_t B, void* y, int32_t y_fp32, void* stream);
 
 /* Scratch bytes stb_gemv needs for (cfg, B), for either kind of layout; negative stb_status on a bad
- * argument. */
+ * argument.  For B > 16 on N:M other than 2:4 this includes the scratch of the one-pass form (see stb_gemv), sized
+ * for any placement of the salient columns. */
 int64_t stb_gemv_workspace_bytes(const stb_cfg_t* cfg, int32_t B);
 
 /* Several independent layers at the same B as one launch: the matrices of a decoder layer that share their input
@@ -320,7 +327,7 @@ int64_t stb_gemv_workspace_bytes(const stb_cfg_t* cfg, int32_t B);
  * of single calls.
  * workspace: device scratch of at least stb_gemv_batched_workspace_bytes() bytes, 256-byte aligned; layer l owns its
  * own slice (the slices follow each other in the order of the list, each as large as round_up(stb_gemv_workspace_bytes
- * of the layer, 256)), whose first 4 * ceil(n / 16) bytes must be zero before the first call and are left zero.
+ * of the layer at a batch of 16 or less, 256)), whose first 4 * ceil(n / 16) bytes must be zero before the first call and are left zero.
  * Calls that share a workspace must not overlap in time.
  * Errors: as stb_gemv; nothing is launched unless every layer's arguments are valid. */
 int stb_gemv_batched(int32_t n_layers, const stb_layout_t* const* dev, const void* const* x, int32_t B,

@@ -493,12 +493,24 @@ extern "C" int stb_code24_index(const stb_layout_t* dev, uint16_t* E_dev, void* 
     return rc;
 }
 
+// Batches above 16 on layers that the dense matrix instruction serves: one pass of the prefill kernel's small-token
+// form instead of two passes of the decode kernel (the weights are expanded once for all rows of x).  Its scratch
+// sits behind the decode kernel's, whose arrival counters must stay zero.
+static bool gemv_takes_gemm(const stb_layout_t* L, int B) {
+    return B > 16 && L->kind == STB_KIND_TILED && !(L->cfg.N == 2 && L->cfg.M == 4) &&
+           stb_kernel_override(0) == 0 && stb_kernel_override(1) == 0 && stb_kernel_override(2) == 0 && stb_kernel_override(3) == 0;
+}
+static int64_t gemv_area(const stb_layout_t* L) { return (stb_tiled_gemv_workspace(L->n_row_tiles, L->n_super) + 255) / 256 * 256; }
+
 extern "C" int64_t stb_gemv_workspace_bytes(const stb_cfg_t* cfg, int32_t B) {
     stb_layout_t tmp;
     int rc = stb_tiled_sizes(cfg, &tmp);
     if (rc) return rc;
     if (B < 1 || B > STB_MAX_BATCH) return STB_EINVAL;
-    return stb_tiled_gemv_workspace(tmp.n_row_tiles, tmp.n_super);
+    const int64_t decode = stb_tiled_gemv_workspace(tmp.n_row_tiles, tmp.n_super);
+    if (B <= 16 || (cfg->N == 2 && cfg->M == 4) || stb_tiled_slots(cfg) == 0) return decode;
+    tmp.max_sal_half = 8 * tmp.sal_chunks;             // sized for any placement of the salient columns
+    return gemv_area(&tmp) + stb_tiled_gemm_workspace(&tmp, B);
 }
 
 // stb_gemv with the partial sums of the column splits at byte offset part_off of the workspace (-1: directly behind
@@ -511,7 +523,15 @@ static int gemv_impl(const stb_layout_t* dev, const void* x, int32_t B, void* y,
     if (B < 1 || B > STB_MAX_BATCH || (y_fp32 != 0 && y_fp32 != 1) || workspace_bytes < 0) return STB_EINVAL;
     if ((uintptr_t)x % 16 || (uintptr_t)y % 4) return STB_EALIGN;
     if (dev->kind == STB_KIND_TILED) {
-        // the matrix-core kernel takes up to 16 rows of x per launch
+        if (part_off < 0 && gemv_takes_gemm(dev, B) && workspace && (uintptr_t)workspace % 256 == 0 &&
+            workspace_bytes >= gemv_area(dev) + stb_tiled_gemm_workspace(dev, B)) {
+            int herr = 0;
+            const int64_t off = gemv_area(dev);
+            rc = stb_tiled_gemm(dev, x, B, y, y_fp32, (char*)workspace + off, workspace_bytes - off, stream, &herr);
+            if (rc == STB_EHIP) g_last_hip_error = herr;
+            if (rc != STB_EUNSUPPORTED) return rc;
+        }
+        // the decode kernel takes up to 16 rows of x per launch
         for (int done = 0; done < B; done += 16) {
             const int nb = B - done < 16 ? B - done : 16;
             const void* xb = (const __half*)x + (size_t)done * dev->cfg.k_in;

@@ -44,6 +44,7 @@ struct GmLds {
     static constexpr int TOTAL24 = LUT;            // without (sparse kernel)
 };
 constexpr int GM_TT = 8, GM_TT24 = 8;       // (12 in the dense kernel was measured: 15 - 30 % slower, fewer and fatter workgroups)
+constexpr int GM_SMALL_TT = 4, GM_SMALL_TOK = 16 * GM_SMALL_TT;     // launches of up to 64 tokens
 
 // Workspace: xsal[T][E] fp16, E = nsb * 2 * cfix * 32; entry ((sb*2 + half)*cfix + c)*32 + g*8 + e holds X at the
 // e-th salient column of record c of (block 4*sb + g, half), 0 where the record has no such entry.
@@ -395,11 +396,10 @@ struct GemmStage {
     }
 };
 
-template <int N8, bool HAS_RES, bool SPLIT>
+template <int N8, bool HAS_RES, bool SPLIT, int TT = GM_TT>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                           void* __restrict__ Y, int y_fp32,
                                                           const __half* __restrict__ xsal, int cfix, int sbs, float* __restrict__ part) {
-    constexpr int TT = GM_TT;
     typedef GmLds<TT> G;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     ScatterLds& lut = *reinterpret_cast<ScatterLds*>(lds + G::LUT);
@@ -500,7 +500,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(TiledPlanes p, const __
         // (the loads are spread over the token tiles of a step, a few at a time: the four wavefronts share one path
         //  to memory, and a burst of loads stalls them all)
         kstep(a1, produce(4, a0), reload(4), [&](int tt) { st.x_gload1(shn, 0, 0, tt); });
-        kstep(a0, produce(5, a1), reload(5), [&](int tt) { if (tt % 2 == 0 && tt < 8) st.fetch_hd1(shn, tn, tt / 2); if (tt == 7) st.fetch_rec(shn, ran, rbn); });
+        kstep(a0, produce(5, a1), reload(5), [&](int tt) { if (tt % (TT / 4) == 0) st.fetch_hd1(shn, tn, tt / (TT / 4)); if (tt == TT - 1) st.fetch_rec(shn, ran, rbn); });
         kstep(a1, produce(6, a0), reload(6), nothing);
         kstep(a0, produce(7, a1), reload(7), nothing);
         // everything in flight has arrived: window 0 of the next pass, its half records and table record, and the
@@ -821,12 +821,11 @@ __device__ inline void sparse_operand(const HalfData<4>& d, uint32_t TLr, uint32
     for (int q = 0; q < 4; q++) W[q] = and_or_v(pk_shl(Xs, 7 - 2 * q, 6 - 2 * q), KS, W[q]);
 }
 
-template <bool HAS_RES, bool SPLIT>
+template <bool HAS_RES, bool SPLIT, int TT = GM_TT24>
 __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half* __restrict__ X, int T,
                                                       void* __restrict__ Y, int y_fp32,
                                                       const __half* __restrict__ xsal, int cfix, int sbs, float* __restrict__ part) {
     constexpr int N8 = 4;
-    constexpr int TT = GM_TT24;
     typedef GmLds<TT> G;
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
@@ -935,7 +934,7 @@ __global__ __launch_bounds__(256) void gemm24_kernel(TiledPlanes p, const __half
         auto nothing = [](int) {};
         // step 0 (window 0): builds step 1, fetches the next pass's records
         sstep(IntC<0>{}, a0, ia, [&](int r) { build_a(hd[r], TL[r], TH[r], 1, a1[r]); }, [&](int tt) { bread(0, 1, tt); },
-              [&](int tt) { if (tt % 2 == 0 && tt < 8) st.fetch_hd1(shn, tn, tt / 2); if (tt == 7) st.fetch_rec(shn, ran, rbn); });
+              [&](int tt) { if (tt % (TT / 4) == 0) st.fetch_hd1(shn, tn, tt / (TT / 4)); if (tt == TT - 1) st.fetch_rec(shn, ran, rbn); });
         asm volatile("s_waitcnt vmcnt(%0)" : : "n"(NR + NH + NC) : "memory");     // window 1 and the gathered columns of this pass
         __syncthreads();                                            // ... everyone's; and everyone is done with window 0
         // step 1: builds step 2 (window 1) and its index word, loads window 0 of the next pass
@@ -1193,20 +1192,20 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __
 
 #include "stb_gemm_shared.hpp"
 
-template <int N8, bool HAS_RES>
+template <int N8, bool HAS_RES, int TT = GM_TT>
 hipError_t launch_gemm(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                        const __half* xsal, int cfix, int sbs, float* part) {
     // two instantiations: with and without the K split
     static std::atomic<bool> attr_set[2] = {{false}, {false}};         // a failure is not remembered: the next call tries again
     const int sp = sbs ? 1 : 0;
-    const void* fn = sp ? (const void*)gemm_tiled_kernel<N8, HAS_RES, true> : (const void*)gemm_tiled_kernel<N8, HAS_RES, false>;
+    const void* fn = sp ? (const void*)gemm_tiled_kernel<N8, HAS_RES, true, TT> : (const void*)gemm_tiled_kernel<N8, HAS_RES, false, TT>;
     if (!attr_set[sp].load(std::memory_order_acquire)) {
-        const hipError_t attr = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT>::TOTAL);
+        const hipError_t attr = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<TT>::TOTAL);
         if (attr != hipSuccess) return attr;
         attr_set[sp].store(true, std::memory_order_release);
     }
-    if (sp) hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES, true>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
-    else hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES, false>), grid, dim3(256), GmLds<GM_TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    if (sp) hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES, true, TT>), grid, dim3(256), GmLds<TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    else hipLaunchKernelGGL((gemm_tiled_kernel<N8, HAS_RES, false, TT>), grid, dim3(256), GmLds<TT>::TOTAL, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
     return hipGetLastError();
 }
 
@@ -1244,20 +1243,20 @@ hipError_t launch_gemm24_wide(dim3 grid, hipStream_t st, const TiledPlanes& p, c
     return hipGetLastError();
 }
 
-template <bool HAS_RES>
+template <bool HAS_RES, int TT = GM_TT24>
 hipError_t launch_gemm24(dim3 grid, hipStream_t st, const TiledPlanes& p, const __half* X, int T, void* Y, int y_fp32,
                          const __half* xsal, int cfix, int sbs, float* part) {
     // two instantiations: with and without the K split
     static std::atomic<bool> attr_set[2] = {{false}, {false}};         // a failure is not remembered: the next call tries again
     const int sp = sbs ? 1 : 0;
-    const void* fn = sp ? (const void*)gemm24_kernel<HAS_RES, true> : (const void*)gemm24_kernel<HAS_RES, false>;
+    const void* fn = sp ? (const void*)gemm24_kernel<HAS_RES, true, TT> : (const void*)gemm24_kernel<HAS_RES, false, TT>;
     if (!attr_set[sp].load(std::memory_order_acquire)) {
-        const hipError_t attr = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<GM_TT24>::TOTAL24);
+        const hipError_t attr = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GmLds<TT>::TOTAL24);
         if (attr != hipSuccess) return attr;
         attr_set[sp].store(true, std::memory_order_release);
     }
-    if (sp) hipLaunchKernelGGL((gemm24_kernel<HAS_RES, true>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
-    else hipLaunchKernelGGL((gemm24_kernel<HAS_RES, false>), grid, dim3(256), GmLds<GM_TT24>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    if (sp) hipLaunchKernelGGL((gemm24_kernel<HAS_RES, true, TT>), grid, dim3(256), GmLds<TT>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
+    else hipLaunchKernelGGL((gemm24_kernel<HAS_RES, false, TT>), grid, dim3(256), GmLds<TT>::TOTAL24, st, p, X, T, Y, y_fp32, xsal, cfix, sbs, part);
     return hipGetLastError();
 }
 
@@ -1436,12 +1435,18 @@ extern "C" int stb_tiled_gemm(const stb_layout_t* L, const void* X, int T, void*
     const bool sparse_ok = is24 && which != 1 && which != 2;
     const bool narrow = which != 2;
     const bool sparse32 = sparse_ok && which != 3;
-    const int tok = sparse_ok ? GmLds<GM_TT24>::TOK : GmLds<GM_TT>::TOK;      // tokens per workgroup of the kernel that runs
+    // up to GM_SMALL_TOK tokens: the instantiations with half as many token tiles per workgroup (half the matrix
+    // instructions on padding; 2:4 layers take the 16x16x64 form, whose pipeline is written for any tile count)
+    const bool small = which == 0 && T <= GM_SMALL_TOK;
+    const int tok = small ? GM_SMALL_TOK : sparse_ok ? GmLds<GM_TT24>::TOK : GmLds<GM_TT>::TOK;      // tokens per workgroup of the kernel that runs
     int groups = 1;
     const int sbs = gemm_split(L, T, tok, &groups);
     float* part = sbs ? (float*)((char*)workspace + gather_bytes(L, T)) : nullptr;
     const dim3 grid((T + tok - 1) / tok, (p.nrt + GM_ROWT - 1) / GM_ROWT, groups);
-    if (sparse32) e = res ? launch_gemm24_wide<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm24_wide<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
+    if (small && sparse_ok) e = res ? launch_gemm24<true, GM_SMALL_TT>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm24<false, GM_SMALL_TT>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
+    else if (small && n8 == 4) e = res ? launch_gemm<4, true, GM_SMALL_TT>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm<4, false, GM_SMALL_TT>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
+    else if (small) e = res ? launch_gemm<6, true, GM_SMALL_TT>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm<6, false, GM_SMALL_TT>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
+    else if (sparse32) e = res ? launch_gemm24_wide<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm24_wide<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
     else if (sparse_ok) e = res ? launch_gemm24<true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm24<false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
     else if (narrow && n8 == 4) e = res ? launch_gemm<4, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm<4, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);
     else if (narrow) e = res ? launch_gemm<6, true>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part) : launch_gemm<6, false>(grid, st, p, xh, T, Y, y_fp32, xs, cfix, sbs, part);

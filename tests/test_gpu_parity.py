@@ -496,7 +496,10 @@ def test_gemv_batched_is_one_launch_with_reproducible_bits(torch_cuda, B):
             if len(sel) == 1:                          # a list of one layer is the single call
                 ly = layers[sel[0]]
                 y1 = torch.full((B, ly["n"]), float("nan"), dtype=dt, device="cuda")
-                S.stb_gemv(ly["pm"].dev_layout, xs_by_k[ly["k"]][1], B, y1, y_fp32, ly["pm"].workspace)
+                # (with a workspace sized for 16 rows: above 16 rows stb_gemv then runs the decode kernel twice, as the
+                #  batched call does, instead of one pass of the prefill kernel)
+                ws1 = S.new_device_scratch(S.stb_gemv_workspace_bytes(ly["pm"].cfg, min(B, 16)), zero=True)
+                S.stb_gemv(ly["pm"].dev_layout, xs_by_k[ly["k"]][1], B, y1, y_fp32, ws1)
                 torch.cuda.synchronize()
                 assert (_bits(ys[0]) == _bits(y1)).all()
 
