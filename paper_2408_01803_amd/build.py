@@ -56,9 +56,12 @@ def build(verbose: bool = True) -> str:
         found = list(pool.map(lambda src: isa_check.check_source(src, BUILD, HIPCC, [*DEVICE_FLAGS, *inc]), dev))
     for src, f in zip(DEVICE_SOURCES, found):
         for w_line, w, m_line, m, ws in f:
-            print(f"{src}.s:{m_line}: '{m}' reads a scalar that '{w}' (line {w_line}) wrote {ws} wait states earlier", flush=True)
+            if ws < 0:
+                print(f"{src}: {m}: {w}", flush=True)
+            else:
+                print(f"{src}.s:{m_line}: '{m}' reads a scalar that '{w}' (line {w_line}) wrote {ws} wait states earlier", flush=True)
     if any(found):
-        raise RuntimeError("scalar-to-vector-memory hazard in the generated code: see the lines above")
+        raise RuntimeError("hazard in the generated code (asm loads): see the lines above")
     tmp = LIB + ".tmp"
     _run([HIPCC, "-shared", "-fPIC", f"--offload-arch={ARCH}", "-o", tmp, *objs, "-pthread"])
     shutil.move(tmp, LIB)

@@ -10,7 +10,13 @@ their streaming loads from `asm` statements, so every build is checked:
   * `hazards` walks that text backwards from every vector-memory instruction with scalar operands, over all
     control-flow predecessors, and reports each vector-ALU write of one of those scalars within five wait states.
 
-`build()` runs the check on every device source and fails on a finding; tests call it too.
+A second rule has the same root: the destination registers of a load issued from an `asm` statement hold nothing
+until the hand-written wait, so they must not be copied in between.  The compiler keeps to that as long as it has
+registers; once it spills vector registers to scratch it may save exactly such a register, and the kernel computes
+with what was there before the load (seen once with a tighter occupancy bound: wrong numbers, no fault).
+`spilled_asm_kernels` lists the kernels that spill a vector register straight after one of their `asm` loads wrote it.
+
+`build()` runs both checks on every device source and fails on a finding; tests call them too.
 """
 from __future__ import annotations
 
@@ -117,6 +123,60 @@ def hazards(isa_text: str) -> List[Tuple[int, str, int, str, int]]:
     return found
 
 
+def _vregs(text: str) -> set:
+    out = set()
+    for m in re.finditer(r"\bv\[(\d+):(\d+)\]|\bv(\d+)\b", text):
+        if m.group(1):
+            out |= set(range(int(m.group(1)), int(m.group(2)) + 1))
+        else:
+            out.add(int(m.group(3)))
+    return out
+
+
+def spilled_asm_kernels(isa_text: str) -> List[Tuple[str, List[int]]]:
+    """(kernel, registers) for every kernel that spills a vector register whose last writer, going back from the
+    spill in program order, is a vector-memory load inside an asm statement (no wait in between)."""
+    lines = isa_text.splitlines()
+    kernel_at: List[str] = []
+    in_asm_at: List[bool] = []
+    cur, in_asm = None, False
+    for raw in lines:
+        s = raw.strip()
+        m = re.match(r"^([A-Za-z_][\w$]*):", raw)
+        if m and not raw.startswith("."):
+            cur = m.group(1)
+        if s.startswith(";;#ASMSTART"):
+            in_asm = True
+        elif s.startswith(";;#ASMEND"):
+            in_asm = False
+        kernel_at.append(cur)
+        in_asm_at.append(in_asm)
+    found: Dict[str, set] = {}
+    for i, raw in enumerate(lines):
+        s = raw.strip()
+        if not s.startswith("scratch_store") or "Spill" not in s:
+            continue
+        ops = _operands(s.split(";")[0])
+        regs = _vregs(ops[1] if len(ops) > 1 else "")
+        for j in range(i - 1, max(i - 2000, -1), -1):
+            if kernel_at[j] != kernel_at[i] or not regs:
+                break
+            t = lines[j].split(";")[0].strip() if not lines[j].strip().startswith(";;#") else ""
+            if not t or t.endswith(":") or t.startswith("."):
+                continue
+            op = t.split()[0]
+            if op == "s_waitcnt" and "vmcnt" in t:
+                break                                   # whatever was in flight has been waited for (or counted) here
+            if op.startswith(("v_", "ds_read", "ds_load")) or (op.startswith(_VMEM) and "load" in op and "lds" not in op):
+                dst = _vregs(_operands(t)[0]) if _operands(t) else set()
+                hit = dst & regs
+                if hit:
+                    if in_asm_at[j] and op.startswith(_VMEM):
+                        found.setdefault(kernel_at[i], set()).update(hit)
+                    regs = regs - hit
+    return [(k, sorted(v)) for k, v in found.items()]
+
+
 def compile_to_isa(source: str, out_path: str, hipcc: str, flags: List[str]) -> str:
     cmd = [hipcc, *flags, "-S", "--offload-device-only", "-o", out_path, source]
     subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
@@ -124,6 +184,9 @@ def compile_to_isa(source: str, out_path: str, hipcc: str, flags: List[str]) -> 
         return f.read()
 
 
-def check_source(source: str, build_dir: str, hipcc: str, flags: List[str]) -> List[Tuple[int, str, int, str, int]]:
+def check_source(source: str, build_dir: str, hipcc: str, flags: List[str]) -> List[tuple]:
+    """Findings of both checks for one device source (empty: clean)."""
     out = os.path.join(build_dir, os.path.basename(source) + ".s")
-    return hazards(compile_to_isa(source, out, hipcc, flags))
+    text = compile_to_isa(source, out, hipcc, flags)
+    return hazards(text) + [(0, f"spills v{regs}", 0, f"kernel {name}: destinations of its asm loads", -1)
+                            for name, regs in spilled_asm_kernels(text)]

@@ -83,6 +83,41 @@ def test_carry_outputs_count_as_vector_alu_writes():
     assert len(isa_check.hazards(CARRY_OUT)) == 1
 
 
+SPILL_OF_A_LOAD_IN_FLIGHT = """
+kernel:
+\t;;#ASMSTART
+\tglobal_load_dwordx2 v[10:11], v1, s[4:5]
+\t;;#ASMEND
+\tv_add_u32_e32 v2, v3, v4
+\tscratch_store_dword off, v11, off offset:4 ; 4-byte Folded Spill
+\t;;#ASMSTART
+\ts_waitcnt vmcnt(0)
+\t;;#ASMEND
+\ts_endpgm
+"""
+
+SPILL_OF_A_COMPUTED_VALUE = """
+kernel:
+\t;;#ASMSTART
+\tglobal_load_dwordx2 v[10:11], v1, s[4:5]
+\t;;#ASMEND
+\t;;#ASMSTART
+\ts_waitcnt vmcnt(0)
+\t;;#ASMEND
+\tv_add_u32_e32 v11, v10, v11
+\tscratch_store_dword off, v11, off offset:4 ; 4-byte Folded Spill
+\ts_endpgm
+"""
+
+
+def test_a_spill_of_a_register_that_an_asm_load_has_just_written_is_found():
+    assert isa_check.spilled_asm_kernels(SPILL_OF_A_LOAD_IN_FLIGHT) == [("kernel", [11])]
+
+
+def test_a_spill_of_a_value_computed_after_the_wait_is_no_finding():
+    assert isa_check.spilled_asm_kernels(SPILL_OF_A_COMPUTED_VALUE) == []
+
+
 def test_the_device_sources_of_the_package_are_clean(tmp_path):
     inc = ["-I" + os.path.join(stb_build.ROOT, "include"), "-I" + stb_build.CSRC]
     srcs = [os.path.join(stb_build.CSRC, s) for s in stb_build.DEVICE_SOURCES]
