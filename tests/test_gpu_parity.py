@@ -333,6 +333,38 @@ def test_gemv_small(small_case, torch_cuda, B, y_fp32):
             _within_bound(yd.float().cpu().numpy(), y_ref, bound, f"gemv B={B} ({visits} visits per wavefront)")
 
 
+def test_gemv_with_planes_more_than_4_gib_apart(torch_cuda):
+    """The default decode kernel addresses the streamed planes of a layer from one scalar base with 32-bit offsets, so
+    it takes a layout only if its planes lie within 4 GiB of each other; any other layout (planes bound one by one to
+    separate allocations, say) must still give the product, through the kernel with 64-bit plane addresses."""
+    torch = torch_cuda
+    n, k, N, M = 130, 640, 4, 8
+    L = make_layer(n, k, 77, "x8")
+    What = O.unpack(O.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, 0), n, k, N, M)
+    pm = S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, 0)
+    lay, img = pm.host_pair(True)
+    far = (9 << 29)                                                   # 4.5 GiB, a multiple of the plane alignment
+    big = torch.empty(far + 2 * lay.image_bytes + 4096, dtype=torch.uint8, device="cuda")
+    off = (-big.data_ptr()) % 256
+    near_view = big[off:off + lay.image_bytes]
+    far_view = big[off + far:off + far + lay.image_bytes]
+    near_view.copy_(torch.from_numpy(img))
+    far_view.copy_(torch.from_numpy(img))
+    dl = pm.clone_layout_for(far_view.data_ptr(), True)               # every plane in the far copy ...
+    dl.mask = near_view.data_ptr() + dl.off_mask                      # ... except the mask plane
+    assert abs(dl.mask - dl.sign) > (1 << 32)
+    ws = pm.new_workspace()
+    for B in (1, 7, 16):
+        x = make_x(B, k, 78)
+        y_ref, bound = O.matmul(x, What)
+        xd = torch.from_numpy(x).cuda()
+        yd = torch.full((B, n), float("nan"), dtype=torch.float32, device="cuda")
+        _say(f"[step] stb_gemv B={B}, mask plane 4.5 GiB away from the other planes")
+        S.stb_gemv(dl, xd, B, yd, True, ws)
+        torch.cuda.synchronize()
+        _within_bound(yd.cpu().numpy(), y_ref, bound, f"gemv B={B}, planes far apart")
+
+
 @pytest.mark.parametrize("T", [1, 63, 64, 200, 333])
 def test_gemm_small(small_case, torch_cuda, T):
     torch = torch_cuda
