@@ -408,8 +408,8 @@ __device__ __forceinline__ void gemv24_body(const Gemv24Layer& d, const int B, c
     }
     if (!MULTI && active) {
         // ---- all loads go out before the first wait: lane l brings columns 8l .. 8l+7 of the superblock for every
-        //      batch row (one 16-byte load per row), lanes 0..23 the 8 records, then the res_sign words of the row
-        //      tiles in 16-byte pieces, then the packed planes of the first three row tiles ----
+        //      batch row (one 16-byte load per row), lanes 0..47 the 16-byte pieces of the (block, half) records, then
+        //      the packed planes of the first row tile ----
         const int col = sb * 512 + lane * 8;
         const bool col_ok = col < p.k;
         const __half* xsrc = x + (col_ok ? col : 0);
