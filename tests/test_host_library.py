@@ -469,3 +469,22 @@ def test_layer_nm_assignment_against_the_oracle():
     with pytest.raises(S.StbError) as e:
         S.stb_layer_nm_assignment([1.0, float("nan")], 0.5, 8)
     assert e.value.status == S.STB_ENONFINITE
+
+
+def test_decode_workspace_sizes_for_batches_above_16():
+    """Up to 16 rows the scratch is that of the decode kernel alone; above 16 rows a layer other than 2:4 may run as
+    one pass of the prefill kernel, whose scratch sits behind the decode kernel's: the size asked for grows with the
+    batch, never shrinks below the decode kernel's, and 2:4 layers (two decode passes) keep theirs."""
+    for (n, k, N, M, sal) in ((5120, 13824, 6, 8, 691), (4096, 4096, 4, 8, 204), (130, 640, 5, 8, 0), (11008, 4096, 2, 4, 204)):
+        cfg = S.make_cfg(n, k, N, M, sal)
+        w1, w16, w17, w32 = (S.stb_gemv_workspace_bytes(cfg, B) for B in (1, 16, 17, 32))
+        assert w1 == w16 >= 0
+        if (N, M) == (2, 4):
+            assert w17 == w32 == w16
+        else:
+            assert w16 < w17 <= w32
+            assert w17 % 256 == 0 and w32 % 256 == 0
+    cfg = S.make_cfg(4096, 4096, 4, 8, 0)
+    for B in (0, 33):
+        with pytest.raises(S.StbError):
+            S.stb_gemv_workspace_bytes(cfg, B)
