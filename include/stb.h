@@ -343,7 +343,7 @@ int64_t stb_gemv_batched_workspace_bytes(int32_t n_layers, const stb_cfg_t* cons
  * dev: the tiled kind runs the matrix-core kernel that expands the packed bits straight into MFMA operands
  * (N:M in {2:4, 3:8, 4:8, 5:8, 6:8, 3:4}; the residual term of the salient columns is a second, short contraction against
  * the gathered salient columns of X, which the call first writes to the workspace); the row-major kind runs a
- * generic kernel for any N:M (it rounds the dequantised salient weights to fp16).
+ * generic kernel for any N:M (the two terms of a salient weight go through two contractions there too).
  * Tiled 2:4 layers run on the structured-sparse matrix instruction (kept weights plus an index word as the operand,
  * Sec. 3.1 / App. C; its 32x32x32 form).
  * When T and n are so small that a (128 tokens x 256 rows) tile per workgroup would leave most of the chip idle (fewer

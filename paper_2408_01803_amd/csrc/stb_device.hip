@@ -97,18 +97,24 @@ __device__ inline WordCtx load_word(const Planes& p, int row, int w) {
 
 // Dequantised value of bit position `pos` of the word (must be a kept position), `rank` = number of
 // kept positions below it inside the word.
-__device__ inline float decode_kept(const WordCtx& c, int pos, int rank) {
+// The two terms of a kept position: s * scale (an fp16 value) and, on a salient column, t * alpha_r (else 0).
+__device__ inline float decode_kept_terms(const WordCtx& c, int pos, int rank, float* residual) {
     const int slot = c.slot0 + rank;
     const bool plus = (c.srow[slot >> 3] >> (slot & 7)) & 1;
     const unsigned id = (c.rrow[slot >> 2] >> ((slot & 3) * 2)) & 3u;
     const float a = id == 0 ? c.a0 : (id == 1 ? c.a1 : (id == 2 ? c.a2 : c.a3));
-    float v = plus ? a : -a;
+    *residual = 0.0f;
     if (id == 3 && c.trow) {
         const int u = c.ord0 + __popc(c.salw & ((1u << pos) - 1u));
         const bool tplus = (c.trow[u >> 3] >> (u & 7)) & 1;
-        v = v + (tplus ? c.ar : -c.ar);      // one fp32 addition
+        *residual = tplus ? c.ar : -c.ar;
     }
-    return v;
+    return plus ? a : -a;
+}
+__device__ inline float decode_kept(const WordCtx& c, int pos, int rank) {
+    float r;
+    const float v = decode_kept_terms(c, pos, rank, &r);
+    return v + r;                            // one fp32 addition (adding 0 changes nothing)
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -171,6 +177,8 @@ __global__ __launch_bounds__(256) void gemv_generic_kernel(Planes p, const __hal
 // ------------------------------------------------------------------------------------------------
 // Generic prefill GEMM (any N:M): 64 tokens x 64 output rows per workgroup, one 128-column block per
 // step; the W tile is dequantised to fp16 in LDS, the contraction runs on v_mfma_f32_32x32x8_f16.
+// A salient weight s * alpha_o + t * alpha_r is not an fp16 value in general: its two terms (both fp16 values) go
+// to two tiles and two contractions, as in the tiled kernels, so that no product is taken with a rounded weight.
 // ------------------------------------------------------------------------------------------------
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
@@ -183,7 +191,9 @@ constexpr int GPAD = 8;          // halves of row padding in LDS
 __global__ __launch_bounds__(256) void gemm_generic_kernel(Planes p, const __half* __restrict__ X, int T,
                                                             void* __restrict__ Y, int y_fp32) {
     __shared__ __attribute__((aligned(16))) _Float16 Ws[GN][GK + GPAD];
+    __shared__ __attribute__((aligned(16))) _Float16 Rs[GN][GK + GPAD];     // residual terms (layers with salient columns)
     __shared__ __attribute__((aligned(16))) _Float16 Xs[GT][GK + GPAD];
+    const bool has_res = p.res_sign != nullptr;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n0 = blockIdx.x * GN, t0 = blockIdx.y * GT;
     const int wt = (wave >> 1) * 32, wn = (wave & 1) * 32;     // sub-tile of this wavefront
@@ -196,20 +206,22 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Planes p, const __hal
         // ---- W tile: thread (r, seg) decodes mask word 4q + seg of row n0 + r ----
         {
             _Float16* dst = &Ws[r][seg * 32];
+            _Float16* dres = &Rs[r][seg * 32];
             const int row = n0 + r;
             if (row < p.n) {
                 const WordCtx c = load_word(p, row, q * 4 + seg);
                 int rank = 0;
                 for (int pos = 0; pos < 32; pos++) {
-                    float v = 0.0f;
+                    float v = 0.0f, res = 0.0f;
                     if ((c.m >> pos) & 1u) {
-                        v = decode_kept(c, pos, rank);
+                        v = decode_kept_terms(c, pos, rank, &res);
                         rank++;
                     }
-                    dst[pos] = (_Float16)v;
+                    dst[pos] = (_Float16)v;                        // exact: v and res are +- an fp16 scale, or 0
+                    if (has_res) dres[pos] = (_Float16)res;
                 }
             } else {
-                for (int pos = 0; pos < 32; pos++) dst[pos] = (_Float16)0.0f;
+                for (int pos = 0; pos < 32; pos++) { dst[pos] = (_Float16)0.0f; if (has_res) dres[pos] = (_Float16)0.0f; }
             }
         }
         // ---- X tile: thread (r, seg) copies 32 halves of token t0 + r ----
@@ -233,6 +245,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(Planes p, const __hal
             const half4_t a = *reinterpret_cast<const half4_t*>(&Xs[wt + (lane & 31)][kc]);
             const half4_t b = *reinterpret_cast<const half4_t*>(&Ws[wn + (lane & 31)][kc]);
             acc = __builtin_amdgcn_mfma_f32_32x32x8f16(a, b, acc, 0, 0, 0);
+            if (has_res) {
+                const half4_t b2 = *reinterpret_cast<const half4_t*>(&Rs[wn + (lane & 31)][kc]);
+                acc = __builtin_amdgcn_mfma_f32_32x32x8f16(a, b2, acc, 0, 0, 0);
+            }
         }
         __syncthreads();
     }
