@@ -918,11 +918,13 @@ extern "C" int stb_tiled_gemv24_group(int n_layers, const stb_layout_t* const* L
     int blocks = 0, sps_max = 1;
     int64_t lds = 0;
     // every layer gets a share of the 256 compute units in proportion to its work, so that the layers of a launch run
-    // side by side and end together instead of each being cut for the whole chip
+    // side by side and end together instead of each being cut for the whole chip (work of a (row tile, superblock):
+    // the vector instructions its product issues, as counted on the three kinds of layer)
     int64_t work[GROUP24_MAX], total_work = 0;
     for (int l = 0; l < n_layers; l++) {
         const bool sparse = Ls[l]->cfg.M == 4 && Ls[l]->cfg.N == 2;
-        work[l] = (int64_t)Ls[l]->n_row_tiles * Ls[l]->n_super * (sparse ? 3 : 4);
+        const int per_tile = sparse ? 314 : stb_tiled_slots(&Ls[l]->cfg) == 6 ? 560 : 378;
+        work[l] = (int64_t)Ls[l]->n_row_tiles * Ls[l]->n_super * per_tile;
         total_work += work[l];
     }
     for (int l = 0; l < n_layers; l++) {
