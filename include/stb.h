@@ -188,6 +188,20 @@ int stb_tile_device(const stb_layout_t* src_rowmajor_dev, stb_layout_t* dst_tile
 int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_bitmap, stb_layout_t* out,
              int32_t n_threads);
 
+/* The factor H^c that Alg. 1 takes ("H = 2 X X^T", "H^c = Cholesky((H + lambda I)^-1)") from calibration
+ * activations: H = 2 X^T X over the k input features, Hc = the upper-triangular factor with Hc^T Hc = (H + lambda I)^-1
+ * (the triangle whose entries right of a diagonal block the compensation step reads), computed as the inverse of the
+ * upper-triangular R with R R^T = H + lambda I.  Float64 throughout, every entry one sequential sum: reproducible
+ * bit for bit and independent of n_threads; it agrees with a LAPACK inverse-then-Cholesky to rounding, not bit for bit.
+ * X: host, r x k row-major fp32 (r samples).  lambda >= 0.  Hc: host, k x k row-major float64, fully overwritten
+ * (zeros below the diagonal); it serves as the working array: the only other storage is a float64 copy of X.  xnorm (may be NULL):
+ * host, k floats, the L2 norm of each feature over the samples (the xnorm of stb_pack and stb_salient_columns).
+ * Cost: (r + k / 3) k^2 multiply-adds on the host.
+ * Errors: STB_ENULL, STB_EINVAL, STB_ENONFINITE (NaN/Inf in X, or H + lambda I not positive definite in floating
+ * point: more samples or a larger lambda are needed). */
+int stb_hessian_factor(const float* X, int32_t r, int32_t k, double lambda, double* Hc, float* xnorm,
+                       int32_t n_threads);
+
 /* Alg. 1 with its block loop: blocks of 128 columns from left to right, on a float64 working copy of W,
  *   Standardized Importance (Eq. 3) of the block's slice alone (row sums, column sums, mean and deviation over the
  *   n x 128 slice) -> N:M mask -> residual binarisation, break points and scales as in stb_pack -> B, the block as

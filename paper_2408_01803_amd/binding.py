@@ -68,7 +68,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 
 _LIB = None
 
-EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_tile_device", "stb_pack", "stb_pack_obc", "stb_pack_device", "stb_pack_device_workspace_bytes", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
+EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_tile_device", "stb_pack", "stb_pack_obc", "stb_hessian_factor", "stb_pack_device", "stb_pack_device_workspace_bytes", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
            "stb_gemv_static", "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemv_batched_workspace_bytes", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_set_kernel_override", "stb_strerror", "stb_last_hip_error")
 
 
@@ -99,6 +99,8 @@ def _lib():
     lib.stb_pack.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32]
     lib.stb_pack_obc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32]
     lib.stb_pack_obc.restype = C.c_int
+    lib.stb_hessian_factor.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_void_p, C.c_void_p, C.c_int32]
+    lib.stb_hessian_factor.restype = C.c_int
     lib.stb_pack_device_workspace_bytes.argtypes = [P(stb_cfg_t), C.c_int32]
     lib.stb_pack_device_workspace_bytes.restype = C.c_int64
     lib.stb_pack_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32, C.c_void_p, C.c_int64,
@@ -170,6 +172,17 @@ def stb_layout_sizes(cfg: stb_cfg_t) -> stb_layout_t:
     out = stb_layout_t()
     _check(_lib().stb_layout_sizes(C.byref(cfg), C.byref(out)), "stb_layout_sizes")
     return out
+
+
+def stb_hessian_factor(X, lam: float, n_threads: int = 0):
+    """(Hc, xnorm) for calibration activations X (r x k fp32, host): see stb_hessian_factor in stb.h."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    r, k = X.shape
+    Hc = np.empty((k, k), dtype=np.float64)
+    xnorm = np.empty(k, dtype=np.float32)
+    _check(_lib().stb_hessian_factor(X.ctypes.data_as(C.c_void_p), r, k, C.c_double(lam), Hc.ctypes.data_as(C.c_void_p),
+                                     xnorm.ctypes.data_as(C.c_void_p), n_threads), "stb_hessian_factor")
+    return Hc, xnorm
 
 
 def stb_layout_bind(layout: stb_layout_t, base_ptr: int) -> stb_layout_t:

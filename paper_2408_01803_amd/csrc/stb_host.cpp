@@ -725,6 +725,86 @@ extern "C" int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_
 // packer with the block loop of Alg. 1: Standardized Importance per 128-column slice and block-wise error
 // compensation of the later columns
 // ------------------------------------------------------------------------------------------------
+// ------------------------------------------------------------------------------------------------
+// H^c of Alg. 1 from calibration activations: H = 2 X^T X, H^c = upper Cholesky factor of (H + lambda I)^-1.
+// With H + lambda I = R R^T, R upper triangular (the factorisation that starts at the last column), the inverse is
+// R^-T R^-1, so H^c = R^-1: one factorisation and one triangular inverse, both in place in the output array.
+// Every entry is one thread's sequential float64 sum in a fixed order: the result does not depend on n_threads.
+// ------------------------------------------------------------------------------------------------
+extern "C" int stb_hessian_factor(const float* X, int32_t r, int32_t k, double lambda, double* Hc, float* xnorm,
+                                  int32_t n_threads) {
+    if (!X || !Hc) return STB_ENULL;
+    if (r < 1 || k < 1 || !(lambda >= 0.0) || !std::isfinite(lambda)) return STB_EINVAL;
+    const int nt = n_threads > 0 ? n_threads : (int)std::thread::hardware_concurrency();
+    const int64_t K = k;
+    std::atomic<bool> bad(false);
+    // upper triangle of H + lambda I (sums over the samples in ascending order); zeros below the diagonal.
+    // (X is transposed first so that a feature's samples are contiguous: k * r doubles of scratch.)
+    std::vector<double> Xt((size_t)K * (size_t)r);
+    parallel_for(K, nt, [&](int64_t i) {
+        double* dst = Xt.data() + (size_t)i * r;
+        for (int64_t t = 0; t < r; t++) dst[t] = (double)X[t * K + i];
+    });
+    parallel_for(K, nt, [&](int64_t i) {
+        double* row = Hc + i * K;
+        const double* xi = Xt.data() + (size_t)i * r;
+        for (int64_t j = 0; j < i; j++) row[j] = 0.0;
+        for (int64_t j = i; j < K; j++) {
+            const double* xj = Xt.data() + (size_t)j * r;
+            double s = 0.0;
+            for (int64_t t = 0; t < r; t++) s += xi[t] * xj[t];
+            row[j] = 2.0 * s + (i == j ? lambda : 0.0);
+            if (!std::isfinite(row[j])) bad.store(true);
+            if (i == j && xnorm) xnorm[i] = (float)std::sqrt(s);
+        }
+    });
+    std::vector<double>().swap(Xt);
+    if (bad.load()) return STB_ENONFINITE;
+    // R R^T = H, from the last column to the first: R[j][j] = sqrt(H[j][j] - sum_{m>j} R[j][m]^2),
+    // R[i][j] = (H[i][j] - sum_{m>j} R[i][m] R[j][m]) / R[j][j] for i < j
+    const int64_t CH = 64;                                 // rows per task
+    for (int64_t j = K - 1; j >= 0; j--) {
+        double* rj = Hc + j * K;
+        double d = rj[j];
+        for (int64_t m = j + 1; m < K; m++) d -= rj[m] * rj[m];
+        if (!(d > 0.0) || !std::isfinite(d)) return STB_ENONFINITE;      // not positive definite in floating point
+        const double piv = std::sqrt(d);
+        rj[j] = piv;
+        const int64_t tasks = (j + CH - 1) / CH;
+        parallel_for(tasks, tasks * CH * (K - j) < 200000 ? 1 : nt, [&](int64_t c) {
+            const int64_t hi = std::min<int64_t>(j, (c + 1) * CH);
+            for (int64_t i = c * CH; i < hi; i++) {
+                double* ri = Hc + i * K;
+                double v = ri[j];
+                for (int64_t m = j + 1; m < K; m++) v -= ri[m] * rj[m];
+                ri[j] = v / piv;
+            }
+        });
+    }
+    // U = R^-1 in place, column by column from the left: U[j][j] = 1 / R[j][j],
+    // U[i][j] = -(sum_{m=i}^{j-1} U[i][m] R[m][j]) U[j][j] for i < j (columns m < j of U are final, column j of R is
+    // copied out before it is overwritten)
+    std::vector<double> col((size_t)K);
+    for (int64_t j = 0; j < K; j++) {
+        for (int64_t m = 0; m <= j; m++) col[(size_t)m] = Hc[m * K + j];
+        const double ujj = 1.0 / col[(size_t)j];
+        Hc[j * K + j] = ujj;
+        const int64_t tasks = (j + CH - 1) / CH;
+        parallel_for(tasks, tasks * CH * j < 200000 ? 1 : nt, [&](int64_t c) {
+            const int64_t hi = std::min<int64_t>(j, (c + 1) * CH);
+            for (int64_t i = c * CH; i < hi; i++) {
+                const double* ui = Hc + i * K;
+                double v = 0.0;
+                for (int64_t m = i; m < j; m++) v += ui[m] * col[(size_t)m];
+                Hc[i * K + j] = -v * ujj;
+            }
+        });
+    }
+    for (int64_t i = 0; i < K; i++)
+        if (!std::isfinite(Hc[i * K + i])) return STB_ENONFINITE;
+    return STB_OK;
+}
+
 extern "C" int stb_pack_obc(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
                             stb_layout_t* out, int32_t n_threads) {
     if (!W || !xnorm || !sal_bitmap || !out) return STB_ENULL;

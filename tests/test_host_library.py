@@ -488,3 +488,62 @@ def test_decode_workspace_sizes_for_batches_above_16():
     for B in (0, 33):
         with pytest.raises(S.StbError):
             S.stb_gemv_workspace_bytes(cfg, B)
+
+
+@pytest.mark.parametrize("k,r,seed", [(128, 300, 41), (384, 500, 42), (257, 257, 43)])
+def test_hessian_factor_against_the_oracle_and_its_defining_identity(k, r, seed):
+    """stb_hessian_factor (factorisation from the last column, then a triangular inverse) against the oracle's
+    inverse-then-Cholesky: the factor with a positive diagonal is unique, so the two agree to rounding; and the
+    identity that defines it, Hc^T Hc (H + lambda I) = I."""
+    rng = np.random.default_rng(seed)
+    X = (rng.standard_normal((r, k)) @ (np.eye(k) + 0.5 * rng.standard_normal((k, k)) / np.sqrt(k))).astype(np.float32)
+    H = 2.0 * X.astype(np.float64).T @ X.astype(np.float64)
+    lam = 0.01 * float(np.mean(np.diag(H)))
+    Hc, xnorm = S.stb_hessian_factor(X, lam, n_threads=3)
+    ref = O.hessian_factor(X, lam)
+    assert (np.tril(Hc, -1) == 0.0).all() and (np.diag(Hc) > 0).all()
+    assert np.abs(Hc - ref).max() <= 1e-9 * np.abs(ref).max()
+    assert np.abs(Hc.T @ Hc @ (H + lam * np.eye(k)) - np.eye(k)).max() < 1e-8
+    assert np.allclose(xnorm, np.sqrt(np.sum(X.astype(np.float64) ** 2, axis=0)), rtol=1e-6, atol=0)
+    one, xn1 = S.stb_hessian_factor(X, lam, n_threads=1)
+    assert (one.view(np.uint64) == Hc.view(np.uint64)).all() and (xn1 == xnorm).all()
+
+
+def test_hessian_factor_closed_form_for_orthogonal_features_and_errors():
+    # orthogonal features: H is diagonal and the factor is 1 / sqrt(2 |x_j|^2 + lambda) on the diagonal
+    k = 128
+    d = np.arange(1, k + 1, dtype=np.float32)
+    X = np.diag(d)
+    Hc, xnorm = S.stb_hessian_factor(X, 0.5)
+    assert (Hc[~np.eye(k, dtype=bool)] == 0.0).all()
+    assert np.allclose(np.diag(Hc), 1.0 / np.sqrt(2.0 * d.astype(np.float64) ** 2 + 0.5), rtol=1e-15)
+    assert (xnorm == d).all()
+    # fewer samples than features and no damping: not positive definite
+    with pytest.raises(S.StbError) as e:
+        S.stb_hessian_factor(np.ones((3, 128), dtype=np.float32), 0.0)
+    assert e.value.status == S.STB_ENONFINITE
+    bad = np.ones((4, 128), dtype=np.float32)
+    bad[1, 5] = np.nan
+    with pytest.raises(S.StbError) as e:
+        S.stb_hessian_factor(bad, 1.0)
+    assert e.value.status == S.STB_ENONFINITE
+    with pytest.raises(S.StbError) as e:
+        S.stb_hessian_factor(np.ones((4, 128), dtype=np.float32), -1.0)
+    assert e.value.status == S.STB_EINVAL
+
+
+def test_calibration_activations_to_packed_layer_inside_the_library():
+    """X -> stb_hessian_factor (factor and feature norms) -> stb_salient_columns -> stb_pack_obc: the chain Alg. 1
+    describes, with no step outside the library; the packed bytes equal the oracle's for the same factor array."""
+    n, k, N, M = 48, 384, 4, 8
+    L = make_layer(n, k, 77, "x8")
+    rng = np.random.default_rng(78)
+    X = (rng.standard_normal((2 * k, k)) @ (np.eye(k) + 0.6 * rng.standard_normal((k, k)) / np.sqrt(k))).astype(np.float32)
+    lam = 0.01 * float(np.mean(2.0 * np.sum(X.astype(np.float64) ** 2, axis=0)))
+    Hc, xnorm = S.stb_hessian_factor(X, lam)
+    bitmap = S.stb_salient_columns(L["W"], xnorm, lam, 8)
+    ref = O.pack_obc(L["W"], Hc, xnorm, bitmap, N, M, 0)
+    pm = S.PackedMatrix.pack_obc(L["W"], Hc, xnorm, bitmap, N, M, 0)
+    for name, v in _oracle_bytes(ref).items():
+        assert (pm.plane(name) == v).all(), name
+    assert (pm.unpack() == O.unpack(ref, n, k, N, M)).all()

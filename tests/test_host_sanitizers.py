@@ -54,6 +54,13 @@ CHILD = textwrap.dedent('''
         out = np.empty((n, k), dtype=np.float32)
         assert lib.stb_unpack(C.byref(lay), out.ctypes.data) == 0
         if k <= 640:                                   # the block loop of Alg. 1, with and without a factor
+            Xc = np.random.default_rng(n).standard_normal((k + 7, k)).astype(np.float32)
+            Hf = np.empty((k, k), dtype=np.float64)
+            xn = np.empty(k, dtype=np.float32)
+            lib.stb_hessian_factor.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_void_p, C.c_void_p, C.c_int32]
+            assert lib.stb_hessian_factor(Xc.ctypes.data, k + 7, k, 0.5, Hf.ctypes.data, xn.ctypes.data, 3) == 0
+            assert lib.stb_hessian_factor(Xc.ctypes.data, k + 7, k, 0.5, Hf.ctypes.data, None, 1) == 0
+            assert np.isfinite(Hf).all() and (np.tril(Hf, -1) == 0).all()
             Hc = np.triu(0.02 * np.random.default_rng(n).standard_normal((k, k)), 1) + np.eye(k)
             for factor in (None, Hc.ctypes.data):
                 assert lib.stb_pack_obc(L["W"].ctypes.data, factor, L["xnorm"].ctypes.data, L["sal_bitmap"].ctypes.data, C.byref(lay), 3) == 0
