@@ -217,6 +217,21 @@ int stb_hessian_factor(const float* X, int32_t r, int32_t k, double lambda, doub
 int stb_pack_obc(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
                  stb_layout_t* out, int32_t n_threads);
 
+/* stb_pack_obc with the compensation step on the GPU (the rest of the block loop stays on the host): the float64
+ * working copy of W and the factor live in the device workspace, the host quantises block after block, sends the
+ * block's error matrix E (n x 128) and fetches the next block's columns; the update
+ *   W[:, later columns] -= E . Hc[block rows, later columns]
+ * runs as a kernel with the arithmetic stb_pack_obc states (per output the 128 terms in ascending column order, one
+ * multiplication and one addition per term), so the packed bytes equal those of stb_pack_obc bit for bit.  The
+ * update is n k^2 / 2 float64 multiply-adds in all, the largest part of the block loop's arithmetic.
+ * W, Hc, xnorm, sal_bitmap, out: host, as for stb_pack_obc (Hc == NULL: the call is stb_pack_obc without a factor and
+ * the workspace is not used).  workspace: device, 256-byte aligned, stb_pack_obc_hybrid_workspace_bytes(cfg) bytes
+ * (8 n k + 8 k^2 + 1024 n, rounded up).  The call copies between host and device on `stream` and waits for it.
+ * Errors: as stb_pack_obc, plus STB_EHIP, STB_EUNSUPPORTED (more than 524280 rows). */
+int64_t stb_pack_obc_hybrid_workspace_bytes(const stb_cfg_t* cfg);
+int stb_pack_obc_hybrid(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
+                        stb_layout_t* out, int32_t n_threads, void* workspace, int64_t workspace_bytes, void* stream);
+
 /* stb_pack on the GPU (Eq. 1-6, Sec. 3.1, Alg. 2 as in stb_pack): weights, feature norms and the salient bitmap in
  * device memory in, the STB1 planes in device memory out, bit for bit what stb_pack writes for the same inputs.  Every
  * float64 sum is taken in the order stb_pack takes it (a row's columns from left to right, the rows from the top

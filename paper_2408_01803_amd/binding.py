@@ -68,7 +68,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 
 _LIB = None
 
-EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_tile_device", "stb_pack", "stb_pack_obc", "stb_hessian_factor", "stb_pack_device", "stb_pack_device_workspace_bytes", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
+EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_tile_device", "stb_pack", "stb_pack_obc", "stb_hessian_factor", "stb_pack_obc_hybrid", "stb_pack_obc_hybrid_workspace_bytes", "stb_pack_device", "stb_pack_device_workspace_bytes", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
            "stb_gemv_static", "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemv_batched_workspace_bytes", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_set_kernel_override", "stb_strerror", "stb_last_hip_error")
 
 
@@ -101,6 +101,11 @@ def _lib():
     lib.stb_pack_obc.restype = C.c_int
     lib.stb_hessian_factor.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_void_p, C.c_void_p, C.c_int32]
     lib.stb_hessian_factor.restype = C.c_int
+    lib.stb_pack_obc_hybrid.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32,
+                                        C.c_void_p, C.c_int64, C.c_void_p]
+    lib.stb_pack_obc_hybrid.restype = C.c_int
+    lib.stb_pack_obc_hybrid_workspace_bytes.argtypes = [P(stb_cfg_t)]
+    lib.stb_pack_obc_hybrid_workspace_bytes.restype = C.c_int64
     lib.stb_pack_device_workspace_bytes.argtypes = [P(stb_cfg_t), C.c_int32]
     lib.stb_pack_device_workspace_bytes.restype = C.c_int64
     lib.stb_pack_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, P(stb_layout_t), C.c_int32, C.c_void_p, C.c_int64,
@@ -232,6 +237,33 @@ def stb_pack_obc(W: np.ndarray, Hc: Optional[np.ndarray], xnorm: np.ndarray, sal
         assert Hc.shape == (k, k)
     _check(_lib().stb_pack_obc(W.ctypes.data, None if Hc is None else Hc.ctypes.data, xnorm.ctypes.data,
                                sal_bitmap.ctypes.data, C.byref(layout), n_threads), "stb_pack_obc")
+
+
+def stb_pack_obc_hybrid_workspace_bytes(cfg: stb_cfg_t) -> int:
+    r = int(_lib().stb_pack_obc_hybrid_workspace_bytes(C.byref(cfg)))
+    if r < 0:
+        _check(r, "stb_pack_obc_hybrid_workspace_bytes")
+    return r
+
+
+def stb_pack_obc_hybrid(W: np.ndarray, Hc: Optional[np.ndarray], xnorm: np.ndarray, sal_bitmap: np.ndarray,
+                        layout: stb_layout_t, n_threads: int = 0, workspace=None, stream: Optional[int] = None) -> None:
+    """stb_pack_obc with the compensation update on the GPU; `workspace`: uint8 device tensor (allocated if None)."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    xnorm = np.ascontiguousarray(xnorm, dtype=np.float32)
+    sal_bitmap = np.ascontiguousarray(sal_bitmap, dtype=np.uint32)
+    k = layout.cfg.k_in
+    assert W.shape == (layout.cfg.n_out, k) and xnorm.shape == (k,) and sal_bitmap.shape == (k // 32,)
+    if Hc is not None:
+        Hc = np.ascontiguousarray(Hc, dtype=np.float64)
+        assert Hc.shape == (k, k)
+        if workspace is None:
+            workspace = new_device_scratch(stb_pack_obc_hybrid_workspace_bytes(layout.cfg))
+    _check(_lib().stb_pack_obc_hybrid(W.ctypes.data, None if Hc is None else Hc.ctypes.data, xnorm.ctypes.data,
+                                      sal_bitmap.ctypes.data, C.byref(layout), n_threads,
+                                      None if workspace is None else workspace.data_ptr(),
+                                      0 if workspace is None else workspace.numel(),
+                                      _stream_ptr(stream) if Hc is not None else None), "stb_pack_obc_hybrid")
 
 
 def stb_pack_device_workspace_bytes(cfg: stb_cfg_t, si_per_block: bool = False) -> int:
@@ -447,6 +479,15 @@ class PackedMatrix:
         S = int(np.unpackbits(sal_bitmap.view(np.uint8)).sum())
         pm = cls(make_cfg(n, k, N, M, S, region_mode))
         stb_pack_obc(W, Hc, xnorm, sal_bitmap, pm.host_layout, n_threads)
+        return pm
+
+    @classmethod
+    def pack_obc_hybrid(cls, W, Hc, xnorm, sal_bitmap, N: int, M: int, region_mode: int = 0, n_threads: int = 0):
+        n, k = W.shape
+        sal_bitmap = np.ascontiguousarray(sal_bitmap, dtype=np.uint32)
+        S = int(np.unpackbits(sal_bitmap.view(np.uint8)).sum())
+        pm = cls(make_cfg(n, k, N, M, S, region_mode))
+        stb_pack_obc_hybrid(W, Hc, xnorm, sal_bitmap, pm.host_layout, n_threads)
         return pm
 
     @property

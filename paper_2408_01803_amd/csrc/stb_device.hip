@@ -442,6 +442,29 @@ extern "C" int stb_pack_device(const float* W, const float* xnorm, const uint32_
 }
 
 
+extern "C" int64_t stb_pack_obc_hybrid_workspace_bytes(const stb_cfg_t* cfg) {
+    stb_layout_t tmp;
+    const int rc = stb_layout_sizes(cfg, &tmp);
+    if (rc) return rc;
+    return stb_pack_obc_gpu_workspace(cfg);
+}
+
+extern "C" int stb_pack_obc_hybrid(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
+                                   stb_layout_t* out, int32_t n_threads, void* workspace, int64_t workspace_bytes,
+                                   void* stream) {
+    if (!Hc) return stb_pack_obc(W, nullptr, xnorm, sal_bitmap, out, n_threads);     // no compensation: nothing for the GPU
+    if (!W || !xnorm || !sal_bitmap || !out || !workspace) return STB_ENULL;
+    const int rc0 = stb_layout_check(out);
+    if (rc0) return rc0;
+    if (out->kind != STB_KIND_ROWMAJOR) return STB_EINVAL;
+    if ((uintptr_t)workspace % 256) return STB_EALIGN;
+    if (workspace_bytes < stb_pack_obc_gpu_workspace(&out->cfg)) return STB_EINVAL;
+    int herr = 0;
+    const int rc = stb_pack_obc_gpu(W, Hc, xnorm, sal_bitmap, out, n_threads, workspace, stream, &herr);
+    if (rc == STB_EHIP) g_last_hip_error = herr;
+    return rc;
+}
+
 static std::atomic<int> g_override[4] = {{0}, {0}, {0}, {0}};
 
 extern "C" int stb_kernel_override(int which) { return which >= 0 && which < 4 ? g_override[which].load(std::memory_order_relaxed) : 0; }

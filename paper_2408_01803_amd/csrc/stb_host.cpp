@@ -805,8 +805,13 @@ extern "C" int stb_hessian_factor(const float* X, int32_t r, int32_t k, double l
     return STB_OK;
 }
 
-extern "C" int stb_pack_obc(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
-                            stb_layout_t* out, int32_t n_threads) {
+// The block loop of Alg. 1.  `accel` == nullptr: everything on the host.  Otherwise the float64 working copy that
+// receives the compensation lives with the accelerator (a GPU): `start` hands it the initial copy, `fetch` brings the
+// current values of a block's 128 columns back into the host copy before the block is quantised, `update` takes the
+// block's error matrix E (n x 128, row-major) and applies W[:, later] -= E . H^c[block, later] there.  The arithmetic
+// of `update` is fixed (see below), so both ways give the same bytes.
+extern "C" int stb_pack_obc_with(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
+                                 stb_layout_t* out, int32_t n_threads, const stb_obc_accel_t* accel) {
     if (!W || !xnorm || !sal_bitmap || !out) return STB_ENULL;
     int rc = stb_layout_check(out);
     if (rc) return rc;
@@ -839,6 +844,10 @@ extern "C" int stb_pack_obc(const float* W, const double* Hc, const float* xnorm
         }
     });
     if (bad.load()) return STB_ENONFINITE;
+    if (accel && Hc) {
+        rc = accel->start(accel->ctx, Wd.data());
+        if (rc) return rc;
+    }
 
     std::vector<uint8_t> keep((size_t)n * k), ids((size_t)n * k, 0), tpos((size_t)n * k, 0);
     std::vector<double> rs(n), rowacc(n), cs(STB_BLOCK), E(Hc ? (size_t)n * STB_BLOCK : 0);
@@ -848,6 +857,10 @@ extern "C" int stb_pack_obc(const float* W, const double* Hc, const float* xnorm
 
     for (int q = 0; q < nb; q++) {
         const int c0 = q * STB_BLOCK, c1 = c0 + STB_BLOCK;
+        if (accel && Hc && q > 0) {
+            rc = accel->fetch(accel->ctx, q, Wd.data());
+            if (rc) return rc;
+        }
         // ---- Standardized Importance over the slice (Eq. 3 with the sums, mean and deviation of the slice) ----
         parallel_for(n, nt, [&](int64_t i) {
             const double* w = Wd.data() + (size_t)i * k + c0;
@@ -926,6 +939,11 @@ extern "C" int stb_pack_obc(const float* W, const double* Hc, const float* xnorm
             }
         });
         // ---- W[:, later] -= E . H^c[block, later]: per output the block's 128 terms in ascending order ----
+        if (accel) {
+            rc = accel->update(accel->ctx, q, E.data());
+            if (rc) return rc;
+            continue;
+        }
         const int TJ = 256;
         const int tiles = (k - c1 + TJ - 1) / TJ;
         parallel_for(tiles, nt, [&](int64_t t) {
@@ -945,6 +963,11 @@ extern "C" int stb_pack_obc(const float* W, const double* Hc, const float* xnorm
         });
     }
     return emit_planes(Wd.data(), (size_t)k, cfg, keep.data(), ids.data(), tpos.data(), sal_bitmap, out, nt);
+}
+
+extern "C" int stb_pack_obc(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
+                            stb_layout_t* out, int32_t n_threads) {
+    return stb_pack_obc_with(W, Hc, xnorm, sal_bitmap, out, n_threads, nullptr);
 }
 
 // ------------------------------------------------------------------------------------------------

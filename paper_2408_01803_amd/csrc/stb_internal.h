@@ -68,6 +68,21 @@ int stb_tile_gpu(const stb_layout_t* src, stb_layout_t* dst, void* stream, int* 
 int64_t stb_pack_gpu_workspace(const stb_cfg_t* cfg, int per_block);
 int stb_pack_gpu(const float* W, const float* xnorm, const uint32_t* sal_bitmap, const stb_layout_t* out, int per_block,
                  void* workspace, void* stream, int* hip_err);
+// The block loop of Alg. 1 with its float64 working copy kept by an accelerator (stb_host.cpp runs the loop,
+// stb_pack.hip provides the three calls for a GPU): `start` receives the initial n x k copy, `fetch` writes the current
+// values of block q's columns into the host copy (row stride k), `update` applies the compensation of block q from its
+// error matrix E (n x 128).  Each returns a stb_status.
+typedef struct {
+    void* ctx;
+    int (*start)(void* ctx, const double* Wd_host);
+    int (*fetch)(void* ctx, int q, double* Wd_host);
+    int (*update)(void* ctx, int q, const double* E_host);
+} stb_obc_accel_t;
+int stb_pack_obc_with(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
+                      stb_layout_t* out, int32_t n_threads, const stb_obc_accel_t* accel);
+int64_t stb_pack_obc_gpu_workspace(const stb_cfg_t* cfg);
+int stb_pack_obc_gpu(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap, stb_layout_t* out,
+                     int32_t n_threads, void* workspace, void* stream, int* hip_err);
 // Issue-rate probe of the matrix instructions the prefill kernels use (stb_gemm.hip); see stb_probe_mfma in stb.h.
 int stb_tiled_probe_mfma(int kind, int valu, int steps, int n_workgroups, void* sink, void* stream, int* hip_err);
 #ifdef __cplusplus

@@ -447,6 +447,114 @@ extern "C" int64_t stb_pack_gpu_workspace(const stb_cfg_t* cfg, int per_block) {
     return plan_workspace(*cfg, per_block).total;
 }
 
+// ------------------------------------------------------------------------------------------------
+// The compensation step of Alg. 1 on the GPU: the float64 working copy of W and the factor H^c stay in HBM, the host
+// quantises block after block (stb_pack_obc_with) and sends each block's error matrix E.
+//   W[i][j] -= sum_c E[i][c] * Hc[c0 + c][j]   for the columns j right of the block,
+// the 128 terms in ascending c, one multiplication and one addition per term (no fused multiply-add: see the pragma
+// at the top), the sum subtracted once -- the host loop's arithmetic, so the bytes that come out are the same.
+// A workgroup takes OBC_TI rows x 256 columns: E's rows from LDS (every lane reads the same word), H^c coalesced.
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int OBC_TI = 8;
+
+__global__ __launch_bounds__(256) void k_obc_update(double* __restrict__ Wd, const double* __restrict__ E,
+                                                    const double* __restrict__ Hc, int n, int k, int c0) {
+    __shared__ double e[OBC_TI][STB_BLOCK];
+    const int c1 = c0 + STB_BLOCK;
+    const int i0 = (int)blockIdx.y * OBC_TI;
+    for (int t = threadIdx.x; t < OBC_TI * STB_BLOCK; t += 256) {
+        const int r = t / STB_BLOCK, c = t % STB_BLOCK;
+        e[r][c] = i0 + r < n ? E[(size_t)(i0 + r) * STB_BLOCK + c] : 0.0;
+    }
+    __syncthreads();
+    const int j = c1 + (int)blockIdx.x * 256 + (int)threadIdx.x;
+    if (j >= k) return;
+    double acc[OBC_TI];
+#pragma unroll
+    for (int r = 0; r < OBC_TI; r++) acc[r] = 0.0;
+    const double* h = Hc + (size_t)c0 * k + j;
+    for (int c = 0; c < STB_BLOCK; c++) {
+        const double hv = h[(size_t)c * k];
+#pragma unroll
+        for (int r = 0; r < OBC_TI; r++) acc[r] += e[r][c] * hv;
+    }
+#pragma unroll
+    for (int r = 0; r < OBC_TI; r++)
+        if (i0 + r < n) Wd[(size_t)(i0 + r) * k + j] -= acc[r];
+}
+
+struct ObcGpu {
+    int n, k;
+    double* Wd;
+    double* Hc;
+    double* E;
+    hipStream_t st;
+    int hip_err;
+};
+
+int obc_fail(ObcGpu* g, hipError_t e) { g->hip_err = (int)e; return STB_EHIP; }
+
+int obc_start(void* ctx, const double* Wd_host) {
+    ObcGpu* g = (ObcGpu*)ctx;
+    hipError_t e = hipMemcpyAsync(g->Wd, Wd_host, (size_t)g->n * g->k * 8, hipMemcpyHostToDevice, g->st);
+    if (e == hipSuccess) e = hipStreamSynchronize(g->st);
+    return e == hipSuccess ? STB_OK : obc_fail(g, e);
+}
+
+int obc_fetch(void* ctx, int q, double* Wd_host) {
+    ObcGpu* g = (ObcGpu*)ctx;
+    const size_t pitch = (size_t)g->k * 8, off = (size_t)q * STB_BLOCK;
+    hipError_t e = hipMemcpy2DAsync(Wd_host + off, pitch, g->Wd + off, pitch, (size_t)STB_BLOCK * 8, (size_t)g->n,
+                                    hipMemcpyDeviceToHost, g->st);
+    if (e == hipSuccess) e = hipStreamSynchronize(g->st);      // the update kernels of the blocks before are done too
+    return e == hipSuccess ? STB_OK : obc_fail(g, e);
+}
+
+int obc_update(void* ctx, int q, const double* E_host) {
+    ObcGpu* g = (ObcGpu*)ctx;
+    const int c1 = (q + 1) * STB_BLOCK;
+    if (c1 >= g->k) return STB_OK;
+    hipError_t e = hipMemcpyAsync(g->E, E_host, (size_t)g->n * STB_BLOCK * 8, hipMemcpyHostToDevice, g->st);
+    if (e == hipSuccess) e = hipStreamSynchronize(g->st);      // the host reuses its E for the next block
+    if (e != hipSuccess) return obc_fail(g, e);
+    const dim3 grid((unsigned)((g->k - c1 + 255) / 256), (unsigned)((g->n + OBC_TI - 1) / OBC_TI));
+    hipLaunchKernelGGL(k_obc_update, grid, dim3(256), 0, g->st, g->Wd, g->E, g->Hc, g->n, g->k, q * STB_BLOCK);
+    e = hipGetLastError();
+    return e == hipSuccess ? STB_OK : obc_fail(g, e);
+}
+
+
+}  // namespace
+
+extern "C" int64_t stb_pack_obc_gpu_workspace(const stb_cfg_t* cfg) {
+    const int64_t n = cfg->n_out, k = cfg->k_in;
+    return up256(n * k * 8) + up256(k * k * 8) + up256(n * STB_BLOCK * 8);
+}
+
+// W, Hc (not NULL), xnorm, sal_bitmap, out: host, as stb_pack_obc takes them; workspace: device.
+extern "C" int stb_pack_obc_gpu(const float* W, const double* Hc, const float* xnorm, const uint32_t* sal_bitmap,
+                                stb_layout_t* out, int32_t n_threads, void* workspace, void* stream, int* hip_err) {
+    const int64_t n = out->cfg.n_out, k = out->cfg.k_in;
+    if ((n + OBC_TI - 1) / OBC_TI > 65535) return STB_EUNSUPPORTED;          // rows of the update grid
+    ObcGpu g;
+    g.n = (int)n; g.k = (int)k; g.st = (hipStream_t)stream; g.hip_err = 0;
+    g.Wd = (double*)workspace;
+    g.Hc = (double*)((char*)workspace + up256(n * k * 8));
+    g.E = (double*)((char*)workspace + up256(n * k * 8) + up256(k * k * 8));
+    hipError_t e = hipMemcpyAsync(g.Hc, Hc, (size_t)k * k * 8, hipMemcpyHostToDevice, g.st);
+    if (e == hipSuccess) e = hipStreamSynchronize(g.st);
+    if (e != hipSuccess) { *hip_err = (int)e; return STB_EHIP; }
+    stb_obc_accel_t accel;
+    accel.ctx = &g; accel.start = obc_start; accel.fetch = obc_fetch; accel.update = obc_update;
+    const int rc = stb_pack_obc_with(W, Hc, xnorm, sal_bitmap, out, n_threads, &accel);
+    e = hipStreamSynchronize(g.st);                    // nothing of this call is still running when it returns
+    if (rc == STB_EHIP) *hip_err = g.hip_err;
+    else if (rc == STB_OK && e != hipSuccess) { *hip_err = (int)e; return STB_EHIP; }
+    return rc;
+}
+
 // out: row-major layout bound to device memory (checked by the caller).  Runs on `stream` and waits for it: the status
 // word comes back before the call returns.
 extern "C" int stb_pack_gpu(const float* W, const float* xnorm, const uint32_t* sal_bitmap, const stb_layout_t* out,

@@ -151,6 +151,27 @@ def test_device_packer_is_bit_exact_against_the_oracle(case, per_block, torch_cu
 TILE_CASES = [c for c in PACK_CASES if _tiled_ok(c[2], c[3])]
 
 
+@pytest.mark.parametrize("n,k,N,M,mode,seed", [(48, 384, 4, 8, 0, 61), (37, 640, 6, 8, 1, 62), (130, 1024, 2, 4, 0, 63),
+                                                (19, 256, 5, 8, 0, 64), (300, 2048, 4, 8, 0, 65)])
+def test_block_loop_packer_with_the_update_on_the_gpu_is_bit_exact(torch_cuda, n, k, N, M, mode, seed):
+    """stb_pack_obc_hybrid (the compensation update of Alg. 1 as a kernel, the rest of the block loop on the host)
+    against the oracle's pack_obc and against the all-host stb_pack_obc: the same bytes."""
+    L = make_layer(n, k, seed, "x8")
+    rng = np.random.default_rng(seed + 500)
+    X = (rng.standard_normal((2 * k, k)) @ (np.eye(k) + 0.6 * rng.standard_normal((k, k)) / np.sqrt(k))).astype(np.float32)
+    Hc, _ = S.stb_hessian_factor(X, 0.01 * float(np.mean(2.0 * np.sum(X.astype(np.float64) ** 2, axis=0))))
+    _say(f"[step] stb_pack_obc_hybrid {n}x{k} {N}:{M} mode {mode}")
+    pm = S.PackedMatrix.pack_obc_hybrid(L["W"], Hc, L["xnorm"], L["sal_bitmap"], N, M, mode, n_threads=3)
+    host = S.PackedMatrix.pack_obc(L["W"], Hc, L["xnorm"], L["sal_bitmap"], N, M, mode, n_threads=3)
+    assert (pm.host_image == host.host_image).all()
+    if n * k <= 130 * 1024:                                # the oracle's block loop is slow
+        ref = O.pack_obc(L["W"], Hc, L["xnorm"], L["sal_bitmap"], N, M, mode)
+        assert (pm.unpack() == O.unpack(ref, n, k, N, M)).all()
+    # without a factor the call is the host packer with per-block importance and touches no device memory
+    plain = S.PackedMatrix.pack_obc_hybrid(L["W"], None, L["xnorm"], L["sal_bitmap"], N, M, mode)
+    assert (plain.host_image == S.PackedMatrix.pack_obc(L["W"], None, L["xnorm"], L["sal_bitmap"], N, M, mode).host_image).all()
+
+
 @pytest.mark.parametrize("case", TILE_CASES, ids=lambda c: f"{c[0]}x{c[1]}_{c[2]}of{c[3]}_m{c[4]}")
 def test_pack_and_tile_on_the_device_feed_the_kernels(case, torch_cuda):
     """Weights in HBM -> stb_pack_device -> stb_tile_device -> stb_gemv, nothing through the host: the tiled image is
