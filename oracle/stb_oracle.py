@@ -543,15 +543,29 @@ def salient_columns(W, xnorm, lam: float, max_per_block: int) -> np.ndarray:
     (ties: the lower column first); for i = 1 .. len: binarise the first i candidates together and all other columns
     of the block together, e_i = ||W - B||^2; keep the first i with the smallest e_i.
     """
-    W = np.asarray(W, dtype=np.float64)
     xn = np.asarray(xnorm, dtype=np.float32).astype(np.float64)
+    h = 2.0 * xn * xn + float(lam)
+    return _salient_select(W, lambda Wb, b: (Wb * Wb) * h[None, b:b + BLOCK], max_per_block)
+
+
+def salient_columns_hc(W, Hc, max_per_block: int) -> np.ndarray:
+    """Salient(W, H^c) of Alg. 2 with the factor itself: the salient matrix of a block is W^2 divided by the square of
+    the diagonal of H^c's diagonal block, S_ij = w_ij^2 / (H^c_jj)^2; everything after the scores is as in
+    salient_columns().  Hc: (k, k) factor from hessian_factor() (only its diagonal is read)."""
+    d = np.diagonal(np.asarray(Hc, dtype=np.float64)).copy()
+    assert (d != 0).all()
+    return _salient_select(W, lambda Wb, b: (Wb * Wb) / (d * d)[None, b:b + BLOCK], max_per_block)
+
+
+def _salient_select(W, salient_matrix, max_per_block: int) -> np.ndarray:
+    """The steps of Salient() after the salient matrix: column scores, candidates, the count with the least error."""
+    W = np.asarray(W, dtype=np.float64)
     n, k = W.shape
     assert k % BLOCK == 0 and 0 <= max_per_block <= BLOCK
     out = np.zeros(k, dtype=bool)
     for b in range(0, k, BLOCK):
         Wb = W[:, b:b + BLOCK]
-        h = 2.0 * xn[b:b + BLOCK] * xn[b:b + BLOCK] + float(lam)
-        score = seq_colsum((Wb * Wb) * h[None, :])
+        score = seq_colsum(salient_matrix(Wb, b))
         order = np.argsort(-score, kind="stable")[:max_per_block]
         absw, sgn = np.abs(Wb), sign_pm(Wb)
         best, n_star = np.inf, 0

@@ -793,6 +793,55 @@ def test_salient_columns_invariances_ties_and_empty_list():
     assert list(np.flatnonzero(one)) == [20]
 
 
+def _salient_hc_by_loops(W, d, max_per_block):
+    """Salient(W, H^c) of Alg. 2 in plain loops: S_ij = w_ij^2 / d_j^2 with d the diagonal of the factor."""
+    n, k = W.shape
+    out = np.zeros(k, dtype=bool)
+    for b in range(0, k, 128):
+        score = [sum(float(W[i, b + j]) ** 2 / (float(d[b + j]) * float(d[b + j])) for i in range(n)) for j in range(128)]
+        order = sorted(range(128), key=lambda j: (-score[j], j))[:max_per_block]
+        best, n_star = math.inf, 0
+        for c in range(1, len(order) + 1):
+            chosen = set(order[:c])
+            e = 0.0
+            for i in range(n):
+                for group in (chosen, set(range(128)) - chosen):
+                    a = [abs(float(W[i, b + j])) for j in group]
+                    if a:
+                        e += sum(v * v for v in a) - sum(a) ** 2 / len(a)
+            if e < best * (1 - 1e-12):
+                best, n_star = e, c
+        for j in order[:n_star]:
+            out[b + j] = True
+    return out
+
+
+def test_salient_columns_from_the_factor_against_plain_loops_and_the_diagonal_reading():
+    rng = np.random.default_rng(14)
+    W = (rng.standard_normal((5, 256)) * 0.02).astype(np.float32)
+    W[:, [3, 40, 77, 130, 131, 250]] *= 6.0
+    X = rng.standard_normal((600, 256)) @ (np.eye(256) + 0.4 * rng.standard_normal((256, 256)) / 16.0)
+    Hc = O.hessian_factor(X, 0.3)
+    got = O.salient_columns_hc(W, Hc, 10)
+    assert (got == _salient_hc_by_loops(W, np.diagonal(Hc), 10)).all()
+    assert got.any() and set(np.flatnonzero(got).tolist()) <= {3, 40, 77, 130, 131, 250}
+    # only the diagonal of the factor is read; a common factor on it changes no ranking
+    assert (O.salient_columns_hc(W, np.diag(np.diagonal(Hc)), 10) == got).all()
+    assert (O.salient_columns_hc(W, 4.0 * Hc, 10) == got).all()
+    # orthogonal features: the factor is diagonal, 1 / sqrt(2 |x_j|^2 + lambda), and the selection is the one that
+    # salient_columns() makes from the feature norms
+    xn = np.abs(rng.normal(1.0, 0.3, 256)).astype(np.float32)
+    Hd = O.hessian_factor(np.diag(xn.astype(np.float64)), 0.01)
+    assert (O.salient_columns_hc(W, Hd, 10) == O.salient_columns(W, xn, 0.01, 10)).all()
+    # a feature with a small H^c_jj (a large Hessian entry: a loud feature) is preferred among equal weights
+    W2 = np.full((4, 128), 0.01, dtype=np.float32)
+    W2[:, [7, 90]] = 0.5
+    d = np.ones(128)
+    d[90] = 0.25
+    one = O.salient_columns_hc(W2, np.diag(d), 1)
+    assert list(np.flatnonzero(one)) == [90]
+
+
 # ----------------------------------------------------------------------------------------------
 # layer-wise N:M assignment (Sec. 3.3)
 # ----------------------------------------------------------------------------------------------
