@@ -269,6 +269,13 @@ int stb_layer_nm_assignment(const double* omega, int32_t n_layers, double r_targ
 int stb_salient_columns(const float* W, int32_t n, int32_t k, const float* xnorm, double lambda,
                         int32_t max_per_block, uint32_t* sal_bitmap, int32_t* n_selected);
 
+/* The same selection with the factor of Alg. 1 itself, as Alg. 2 writes it: S_ij = w_ij^2 / (Hc[j][j])^2, the square of
+ * the diagonal of the factor's diagonal block.  Hc: host, k x k row-major float64 (from stb_hessian_factor, say; only
+ * its diagonal is read).  Everything else as stb_salient_columns.
+ * Errors: STB_ENULL, STB_EINVAL, STB_ENONFINITE (also a zero, NaN or Inf on Hc's diagonal). */
+int stb_salient_columns_hc(const float* W, int32_t n, int32_t k, const double* Hc, int32_t max_per_block,
+                           uint32_t* sal_bitmap, int32_t* n_selected);
+
 /* Host dequantisation of a packed matrix into dense fp32 (definition in the header comment).
  * host: layout bound to host memory.  W_hat: host, n x k row-major, fully overwritten.
  * Errors: STB_ENULL, STB_EINVAL (including a mask row that does not keep k*N/M weights). */

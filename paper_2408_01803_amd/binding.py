@@ -68,7 +68,7 @@ PLANE_FIELDS = (("mask", "off_mask", "mask_bytes"), ("sign", "off_sign", "sign_b
 
 _LIB = None
 
-EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_tile_device", "stb_pack", "stb_pack_obc", "stb_hessian_factor", "stb_pack_obc_hybrid", "stb_pack_obc_hybrid_workspace_bytes", "stb_pack_device", "stb_pack_device_workspace_bytes", "stb_unpack", "stb_salient_columns", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
+EXPORTS = ("stb_layout_sizes", "stb_layout_bind", "stb_tiled_sizes", "stb_tile", "stb_untile", "stb_tile_device", "stb_pack", "stb_pack_obc", "stb_hessian_factor", "stb_pack_obc_hybrid", "stb_pack_obc_hybrid_workspace_bytes", "stb_pack_device", "stb_pack_device_workspace_bytes", "stb_unpack", "stb_salient_columns", "stb_salient_columns_hc", "stb_layer_l2_norm", "stb_layer_nm_assignment", "stb_code24_export", "stb_code24_import", "stb_code24_index", "stb_dequant", "stb_gemv",
            "stb_gemv_static", "stb_gemv_workspace_bytes", "stb_gemv_batched", "stb_gemv_batched_workspace_bytes", "stb_gemm", "stb_gemm_workspace_bytes", "stb_probe_read", "stb_probe_mfma", "stb_set_kernel_override", "stb_strerror", "stb_last_hip_error")
 
 
@@ -115,6 +115,8 @@ def _lib():
     lib.stb_salient_columns.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_double, C.c_int32,
                                         C.c_void_p, P(C.c_int32)]
     lib.stb_salient_columns.restype = C.c_int
+    lib.stb_salient_columns_hc.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, P(C.c_int32)]
+    lib.stb_salient_columns_hc.restype = C.c_int
     lib.stb_layer_l2_norm.argtypes = [C.c_void_p, C.c_int64, P(C.c_double)]
     lib.stb_layer_l2_norm.restype = C.c_int
     lib.stb_layer_nm_assignment.argtypes = [C.c_void_p, C.c_int32, C.c_double, C.c_int32, C.c_void_p]
@@ -305,6 +307,20 @@ def stb_salient_columns(W: np.ndarray, xnorm: np.ndarray, lam: float, max_per_bl
     count = C.c_int32(0)
     _check(_lib().stb_salient_columns(W.ctypes.data, n, k, xnorm.ctypes.data, float(lam), int(max_per_block),
                                       out.ctypes.data, C.byref(count)), "stb_salient_columns")
+    return out
+
+
+def stb_salient_columns_hc(W: np.ndarray, Hc: np.ndarray, max_per_block: int) -> np.ndarray:
+    """sal_bitmap of the columns that Alg. 2 "Salient" picks with the diagonal of the factor Hc (k x k float64)."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    Hc = np.ascontiguousarray(Hc, dtype=np.float64)
+    n, k = W.shape
+    if Hc.shape != (k, k):
+        raise ValueError("Hc must be k x k")
+    out = np.zeros(max(k // 32, 1), dtype=np.uint32)
+    count = C.c_int32(0)
+    _check(_lib().stb_salient_columns_hc(W.ctypes.data, n, k, Hc.ctypes.data, int(max_per_block), out.ctypes.data,
+                                         C.byref(count)), "stb_salient_columns_hc")
     return out
 
 

@@ -1056,31 +1056,25 @@ extern "C" int stb_layer_nm_assignment(const double* omega, int32_t n_layers, do
 // kept is the one whose two-group binarisation (Eq. 1, per row over each group) has the smallest squared error.
 // All sums are float64, sequential in ascending index, so that the result is reproducible bit for bit.
 // ------------------------------------------------------------------------------------------------
-extern "C" int stb_salient_columns(const float* W, int32_t n, int32_t k, const float* xnorm, double lambda,
-                                   int32_t max_per_block, uint32_t* sal_bitmap, int32_t* n_selected) {
-    if (!W || !xnorm || !sal_bitmap) return STB_ENULL;
-    if (n < 1 || k < STB_BLOCK || k % STB_BLOCK || max_per_block < 0 || max_per_block > STB_BLOCK) return STB_EINVAL;
-    if (!(lambda >= 0.0) || !std::isfinite(lambda)) return STB_EINVAL;
-    for (int j = 0; j < k; j++)
-        if (!(xnorm[j] >= 0.0f) || !std::isfinite(xnorm[j])) return STB_ENONFINITE;
+namespace {
+// Salient() of Alg. 2 after the salient matrix: S_ij = w_ij^2 * f_j (divide == false) or w_ij^2 / f_j (divide == true).
+int salient_select(const float* W, int n, int k, const double* f, bool divide, int max_per_block, uint32_t* sal_bitmap,
+                   int32_t* n_selected) {
     for (size_t q = 0; q < (size_t)n * k; q++)
         if (!std::isfinite(W[q])) return STB_ENONFINITE;
     std::memset(sal_bitmap, 0, (size_t)k / 32 * sizeof(uint32_t));
     int total = 0;
-    std::vector<double> score(STB_BLOCK), h(STB_BLOCK);
+    std::vector<double> score(STB_BLOCK);
     std::vector<int> order(STB_BLOCK);
     std::vector<char> sal(STB_BLOCK);
     for (int b = 0; b < k; b += STB_BLOCK) {
-        for (int j = 0; j < STB_BLOCK; j++) {
-            const double x = (double)xnorm[b + j];
-            h[j] = 2.0 * x * x + lambda;
-            score[j] = 0.0;
-        }
+        const double* h = f + b;
+        for (int j = 0; j < STB_BLOCK; j++) score[j] = 0.0;
         for (int i = 0; i < n; i++) {
             const float* w = W + (size_t)i * k + b;
             for (int j = 0; j < STB_BLOCK; j++) {
                 const double v = (double)w[j];
-                score[j] += (v * v) * h[j];
+                score[j] += divide ? (v * v) / h[j] : (v * v) * h[j];
             }
         }
         for (int j = 0; j < STB_BLOCK; j++) order[j] = j;
@@ -1118,6 +1112,35 @@ extern "C" int stb_salient_columns(const float* W, int32_t n, int32_t k, const f
     }
     if (n_selected) *n_selected = total;
     return STB_OK;
+}
+}  // namespace
+
+extern "C" int stb_salient_columns(const float* W, int32_t n, int32_t k, const float* xnorm, double lambda,
+                                   int32_t max_per_block, uint32_t* sal_bitmap, int32_t* n_selected) {
+    if (!W || !xnorm || !sal_bitmap) return STB_ENULL;
+    if (n < 1 || k < STB_BLOCK || k % STB_BLOCK || max_per_block < 0 || max_per_block > STB_BLOCK) return STB_EINVAL;
+    if (!(lambda >= 0.0) || !std::isfinite(lambda)) return STB_EINVAL;
+    for (int j = 0; j < k; j++)
+        if (!(xnorm[j] >= 0.0f) || !std::isfinite(xnorm[j])) return STB_ENONFINITE;
+    std::vector<double> f((size_t)k);
+    for (int j = 0; j < k; j++) {
+        const double x = (double)xnorm[j];
+        f[(size_t)j] = 2.0 * x * x + lambda;
+    }
+    return salient_select(W, n, k, f.data(), false, max_per_block, sal_bitmap, n_selected);
+}
+
+extern "C" int stb_salient_columns_hc(const float* W, int32_t n, int32_t k, const double* Hc, int32_t max_per_block,
+                                      uint32_t* sal_bitmap, int32_t* n_selected) {
+    if (!W || !Hc || !sal_bitmap) return STB_ENULL;
+    if (n < 1 || k < STB_BLOCK || k % STB_BLOCK || max_per_block < 0 || max_per_block > STB_BLOCK) return STB_EINVAL;
+    std::vector<double> f((size_t)k);
+    for (int j = 0; j < k; j++) {
+        const double d = Hc[(size_t)j * k + j];
+        if (!std::isfinite(d) || d == 0.0) return STB_ENONFINITE;
+        f[(size_t)j] = d * d;
+    }
+    return salient_select(W, n, k, f.data(), true, max_per_block, sal_bitmap, n_selected);
 }
 
 // ------------------------------------------------------------------------------------------------

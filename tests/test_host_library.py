@@ -541,9 +541,28 @@ def test_calibration_activations_to_packed_layer_inside_the_library():
     X = (rng.standard_normal((2 * k, k)) @ (np.eye(k) + 0.6 * rng.standard_normal((k, k)) / np.sqrt(k))).astype(np.float32)
     lam = 0.01 * float(np.mean(2.0 * np.sum(X.astype(np.float64) ** 2, axis=0)))
     Hc, xnorm = S.stb_hessian_factor(X, lam)
-    bitmap = S.stb_salient_columns(L["W"], xnorm, lam, 8)
+    bitmap = S.stb_salient_columns_hc(L["W"], Hc, 8)
+    assert (O.bitmap_to_bool(bitmap, k) == O.salient_columns_hc(L["W"], Hc, 8)).all() and bitmap.any()
     ref = O.pack_obc(L["W"], Hc, xnorm, bitmap, N, M, 0)
     pm = S.PackedMatrix.pack_obc(L["W"], Hc, xnorm, bitmap, N, M, 0)
     for name, v in _oracle_bytes(ref).items():
         assert (pm.plane(name) == v).all(), name
     assert (pm.unpack() == O.unpack(ref, n, k, N, M)).all()
+
+
+@pytest.mark.parametrize("n,k,seed,max_per_block", [(48, 512, 91, 16), (7, 128, 92, 128), (130, 384, 93, 5)])
+def test_salient_columns_from_the_factor_bit_exact_against_the_oracle(n, k, seed, max_per_block):
+    L = make_layer(n, k, seed, "x8")
+    rng = np.random.default_rng(seed)
+    X = (rng.standard_normal((k + 50, k)) @ (np.eye(k) + 0.5 * rng.standard_normal((k, k)) / np.sqrt(k))).astype(np.float32)
+    Hc, _ = S.stb_hessian_factor(X, 0.5)
+    got = O.bitmap_to_bool(S.stb_salient_columns_hc(L["W"], Hc, max_per_block), k)
+    assert (got == O.salient_columns_hc(L["W"], Hc, max_per_block)).all()
+    bad = Hc.copy()
+    bad[3, 3] = 0.0
+    with pytest.raises(S.StbError) as e:
+        S.stb_salient_columns_hc(L["W"], bad, max_per_block)
+    assert e.value.status == S.STB_ENONFINITE
+    with pytest.raises(S.StbError) as e:
+        S.stb_salient_columns_hc(L["W"], Hc, 129)
+    assert e.value.status == S.STB_EINVAL
