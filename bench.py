@@ -323,7 +323,7 @@ def main():
         torch.cuda.empty_cache()
         return rows
 
-    def gemm_rows(cfg, spec, pm, tokens):
+    def gemm_rows(cfg, spec, pm, tokens, graph=False):
         rows = []
         pm.to_device(tiled=tiled_ok(spec))
         for T in tokens:
@@ -332,7 +332,7 @@ def main():
             wsg = pm.new_gemm_workspace(T)
             flops = 2.0 * T * spec.n * spec.k
             reps = max(2, min(10, int(2e12 / flops)))
-            med, best = timed(torch, lambda r: S.stb_gemm(pm.dev_layout, X, T, Y, False, wsg), reps, warm=2)
+            med, best = timed(torch, lambda r: S.stb_gemm(pm.dev_layout, X, T, Y, False, wsg), reps, warm=2, graph=graph)
             tf = flops / med / 1e6
             row = dict(workload=cfg, layer=spec.name, T=T, n=spec.n, k=spec.k, nm=f"{spec.N}:{spec.M}",
                        us=round(med, 1), us_best=round(best, 1), tflops=round(tf, 2),
@@ -349,7 +349,7 @@ def main():
         torch.cuda.empty_cache()
         return rows
 
-    decode_all, gemm_all = [], []
+    decode_all, gemm_all, gemm_small = [], [], []
     if not a.no_extra:
         for spec in wl["layers"]:
             decode_all += decode_rows(5, spec, packed5[spec.name], wl["decode_batches"])
@@ -369,6 +369,10 @@ def main():
                     decode_all += decode_rows(cfg, spec, pm, w["decode_batches"])
                 if not a.no_gemm and w["prefill_tokens"]:
                     gemm_all += gemm_rows(cfg, spec, pm, w["prefill_tokens"])
+                if not a.no_gemm and not a.no_extra and cfg == 3:
+                    # launches of up to 64 tokens run their own instantiation of the prefill kernels (it is also what
+                    # stb_gemv takes for B = 17 .. 32 on these layers: compare the B = 32 decode rows)
+                    gemm_small += gemm_rows("3 (small launches)", spec, pm, [32, 64], graph=True)
                 del pm
         # the paper's other ratios (Sec. 3.3, Table 1) on the shape of workload 1: 3:8 and 5:8 run on the same kernels as
         # 4:8 and 6:8 (their tiled image carries one unused slot per group of 8 columns)
@@ -397,6 +401,9 @@ def main():
                                                  f"dequantised tile; best dense-instruction row: workload {best['workload']} "
                                                  f"{best['layer']} T={best['T']}"}}
 
+    if gemm_small:
+        result["gemm_small_rows"] = {"rows": gemm_small, "note": "stb_gemm at 32 and 64 tokens (launches in a HIP graph, as "
+                                     "the decode rows are timed); not part of the roofline row above"}
     if not a.no_extra:
         # streaming-read rate of a plain kernel on buffers of two sizes (an 18 MB layer and a 93 MB one), rotating over
         # a pool larger than the last-level cache, same launch-to-launch timing as the rows above

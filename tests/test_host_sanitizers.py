@@ -61,6 +61,10 @@ CHILD = textwrap.dedent('''
             assert lib.stb_hessian_factor(Xc.ctypes.data, k + 7, k, 0.5, Hf.ctypes.data, xn.ctypes.data, 3) == 0
             assert lib.stb_hessian_factor(Xc.ctypes.data, k + 7, k, 0.5, Hf.ctypes.data, None, 1) == 0
             assert np.isfinite(Hf).all() and (np.tril(Hf, -1) == 0).all()
+            bm = np.zeros(k // 32, dtype=np.uint32)
+            cnt = C.c_int32(0)
+            lib.stb_salient_columns_hc.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, P(C.c_int32)]
+            assert lib.stb_salient_columns_hc(L["W"].ctypes.data, n, k, Hf.ctypes.data, 9, bm.ctypes.data, C.byref(cnt)) == 0
             Hc = np.triu(0.02 * np.random.default_rng(n).standard_normal((k, k)), 1) + np.eye(k)
             for factor in (None, Hc.ctypes.data):
                 assert lib.stb_pack_obc(L["W"].ctypes.data, factor, L["xnorm"].ctypes.data, L["sal_bitmap"].ctypes.data, C.byref(lay), 3) == 0
