@@ -175,7 +175,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=200,
+                    help="untimed steps before the timed ones (the step time falls for about 180 steps, 25 ms, after the "
+                         "GPU has been idle: fewer warm-up steps time the ramp, not the kernel)")
     ap.add_argument("--replays", type=int, default=7, help="timed replays of the graph of K steps (median is reported)")
     ap.add_argument("--no-gemm", action="store_true", help="skip the prefill rows")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
@@ -253,7 +255,8 @@ def main():
             with torch.cuda.graph(graph, stream=side):
                 for _ in range(a.steps):
                     decode_step()
-            graph.replay()                       # untimed replay
+            for _ in range(max(1, -(-a.warmup // max(1, a.steps)))):     # untimed replays: the W warm-up steps once more
+                graph.replay()
             side.synchronize()
             for _ in range(max(1, a.replays)):   # each timed region is one replay = exactly K steps
                 g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
