@@ -79,14 +79,24 @@ def build_pool(S, torch, pm, pool_bytes, tiled=True, min_copies=2):
 USE_GRAPHS = True       # --no-graph: every timed launch comes from the host (what a counter run wants to see)
 
 
+WARM_SECONDS = 0.03       # untimed work before a row is timed: an idle GPU takes about 25 ms of work to reach its steady rate
+
+
 def timed(torch, fn, reps, warm=3, rounds=3, graph=False):
     """Median and fastest average time of fn() in microseconds over `rounds` runs of `reps` calls, events on the
     stream the calls are launched on.  graph=True: the `reps` calls are captured once in a HIP graph and each run is
-    one replay (a launch through the Python binding costs the host more time than a short kernel runs)."""
+    one replay (a launch through the Python binding costs the host more time than a short kernel runs).  Before the
+    timed runs the GPU is kept busy with the same calls for WARM_SECONDS (the rows follow host work -- packing the
+    next layer -- during which the GPU idles and clocks down)."""
     for _ in range(warm):
         fn(0)
     torch.cuda.synchronize()
     out = []
+
+    def keep_busy(run):
+        t_end = time.perf_counter() + WARM_SECONDS
+        while time.perf_counter() < t_end:
+            run()
     if graph and USE_GRAPHS:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -97,6 +107,7 @@ def timed(torch, fn, reps, warm=3, rounds=3, graph=False):
                     fn(r)
             g.replay()
             side.synchronize()
+            keep_busy(lambda: (g.replay(), side.synchronize()))
             for _ in range(rounds):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(side)
@@ -107,6 +118,7 @@ def timed(torch, fn, reps, warm=3, rounds=3, graph=False):
         torch.cuda.current_stream().wait_stream(side)
         return statistics.median(out), min(out)
     r = 0
+    keep_busy(lambda: (fn(0), torch.cuda.synchronize()))
     for _ in range(rounds):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
