@@ -7,8 +7,10 @@ Headline workload: the LLaMA-70B-shaped decoder layer (q/o 8192x8192 and k/v 102
 is one pass over all seven matrices: four calls of stb_gemv_batched in the order a decoder layer needs them (q, k and v
 share their input; o; gate and up share theirs; down).  Each step reads another copy of the packed weights (tiled
 device order) out of a pool of more than 1 GiB, so the weights come from HBM and not from the 256 MB last-level cache.
-Inputs are resident in HBM before the timed region.  The K steps are captured once in a HIP graph; the graph is
-replayed several times and `ms_per_step` is the median replay divided by K (the fastest replay is reported beside it).
+Inputs are resident in HBM before the timed region.  After W warm-up steps (default 200: the step time of a GPU that
+has been idle falls for about 180 steps) the K steps are captured once in a HIP graph; the graph is replayed W / K
+times untimed, then several times timed, and `ms_per_step` is the median timed replay divided by K (the fastest
+replay is reported beside it).
 `value` is packed-weight GB/s (bytes of the packed format) over the whole timed region, launch gaps included.
 
 `roofline` describes the dominant kernel, the decode GEMV: algorithmic bytes per launch (packed planes + x + y) divided
