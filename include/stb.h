@@ -191,7 +191,7 @@ int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_bitmap, stb
 /* The factor H^c that Alg. 1 takes ("H = 2 X X^T", "H^c = Cholesky((H + lambda I)^-1)") from calibration
  * activations: H = 2 X^T X over the k input features, Hc = the upper-triangular factor with Hc^T Hc = (H + lambda I)^-1
  * (the triangle whose entries right of a diagonal block the compensation step reads), computed as the inverse of the
- * upper-triangular R with R R^T = H + lambda I.  Float64 throughout, every entry one sequential sum: reproducible
+ * upper-triangular R with R R^T = H + lambda I.  Float64 throughout, every entry one sum in a fixed order: reproducible
  * bit for bit and independent of n_threads; it agrees with a LAPACK inverse-then-Cholesky to rounding, not bit for bit.
  * X: host, r x k row-major fp32 (r samples).  lambda >= 0.  Hc: host, k x k row-major float64, fully overwritten
  * (zeros below the diagonal); it serves as the working array: the only other storage is a float64 copy of X.  xnorm (may be NULL):

@@ -729,8 +729,26 @@ extern "C" int stb_pack(const float* W, const float* xnorm, const uint32_t* sal_
 // H^c of Alg. 1 from calibration activations: H = 2 X^T X, H^c = upper Cholesky factor of (H + lambda I)^-1.
 // With H + lambda I = R R^T, R upper triangular (the factorisation that starts at the last column), the inverse is
 // R^-T R^-1, so H^c = R^-1: one factorisation and one triangular inverse, both in place in the output array.
-// Every entry is one thread's sequential float64 sum in a fixed order: the result does not depend on n_threads.
+// Every entry is one thread's float64 sum in a fixed order (dot4 below): the result does not depend on n_threads.
 // ------------------------------------------------------------------------------------------------
+namespace {
+// sum_t a[t] * b[t] over [0, n) as four interleaved partial sums (t mod 4), added ((s0 + s1) + (s2 + s3)) and then
+// the tail in order: a fixed order, and four independent addition chains for the processor.
+inline double dot4(const double* a, const double* b, int64_t n) {
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int64_t t = 0;
+    for (; t + 4 <= n; t += 4) {
+        s0 += a[t] * b[t];
+        s1 += a[t + 1] * b[t + 1];
+        s2 += a[t + 2] * b[t + 2];
+        s3 += a[t + 3] * b[t + 3];
+    }
+    double s = (s0 + s1) + (s2 + s3);
+    for (; t < n; t++) s += a[t] * b[t];
+    return s;
+}
+}  // namespace
+
 extern "C" int stb_hessian_factor(const float* X, int32_t r, int32_t k, double lambda, double* Hc, float* xnorm,
                                   int32_t n_threads) {
     if (!X || !Hc) return STB_ENULL;
@@ -751,8 +769,7 @@ extern "C" int stb_hessian_factor(const float* X, int32_t r, int32_t k, double l
         for (int64_t j = 0; j < i; j++) row[j] = 0.0;
         for (int64_t j = i; j < K; j++) {
             const double* xj = Xt.data() + (size_t)j * r;
-            double s = 0.0;
-            for (int64_t t = 0; t < r; t++) s += xi[t] * xj[t];
+            const double s = dot4(xi, xj, r);
             row[j] = 2.0 * s + (i == j ? lambda : 0.0);
             if (!std::isfinite(row[j])) bad.store(true);
             if (i == j && xnorm) xnorm[i] = (float)std::sqrt(s);
@@ -761,42 +778,54 @@ extern "C" int stb_hessian_factor(const float* X, int32_t r, int32_t k, double l
     std::vector<double>().swap(Xt);
     if (bad.load()) return STB_ENONFINITE;
     // R R^T = H, from the last column to the first: R[j][j] = sqrt(H[j][j] - sum_{m>j} R[j][m]^2),
-    // R[i][j] = (H[i][j] - sum_{m>j} R[i][m] R[j][m]) / R[j][j] for i < j
-    const int64_t CH = 64;                                 // rows per task
-    for (int64_t j = K - 1; j >= 0; j--) {
-        double* rj = Hc + j * K;
-        double d = rj[j];
-        for (int64_t m = j + 1; m < K; m++) d -= rj[m] * rj[m];
-        if (!(d > 0.0) || !std::isfinite(d)) return STB_ENONFINITE;      // not positive definite in floating point
-        const double piv = std::sqrt(d);
-        rj[j] = piv;
-        const int64_t tasks = (j + CH - 1) / CH;
-        parallel_for(tasks, tasks * CH * (K - j) < 200000 ? 1 : nt, [&](int64_t c) {
-            const int64_t hi = std::min<int64_t>(j, (c + 1) * CH);
+    // R[i][j] = (H[i][j] - sum_{m>j} R[i][m] R[j][m]) / R[j][j] for i < j.  Columns are taken in panels of NB: the
+    // panel's own rows first (one thread), then every row above the panel on its own (row i needs rows j of the
+    // panel, which are final by then, and its own entries right of j).
+    const int64_t NB = 32, CH = 16;                        // panel width, rows per task
+    std::vector<double> piv((size_t)NB);
+    for (int64_t j1 = K; j1 > 0; j1 -= NB) {
+        const int64_t j0 = std::max<int64_t>(0, j1 - NB);
+        for (int64_t j = j1 - 1; j >= j0; j--) {
+            double* rj = Hc + j * K;
+            const double d = rj[j] - dot4(rj + j + 1, rj + j + 1, K - j - 1);
+            if (!(d > 0.0) || !std::isfinite(d)) return STB_ENONFINITE;      // not positive definite in floating point
+            const double pv = std::sqrt(d);
+            piv[(size_t)(j - j0)] = pv;
+            rj[j] = pv;
+            for (int64_t i = j0; i < j; i++) {
+                double* ri = Hc + i * K;
+                ri[j] = (ri[j] - dot4(ri + j + 1, rj + j + 1, K - j - 1)) / pv;
+            }
+        }
+        const int64_t tasks = (j0 + CH - 1) / CH;
+        parallel_for(tasks, nt, [&](int64_t c) {
+            const int64_t hi = std::min<int64_t>(j0, (c + 1) * CH);
             for (int64_t i = c * CH; i < hi; i++) {
                 double* ri = Hc + i * K;
-                double v = ri[j];
-                for (int64_t m = j + 1; m < K; m++) v -= ri[m] * rj[m];
-                ri[j] = v / piv;
+                for (int64_t j = j1 - 1; j >= j0; j--)
+                    ri[j] = (ri[j] - dot4(ri + j + 1, Hc + j * K + j + 1, K - j - 1)) / piv[(size_t)(j - j0)];
             }
         });
     }
-    // U = R^-1 in place, column by column from the left: U[j][j] = 1 / R[j][j],
-    // U[i][j] = -(sum_{m=i}^{j-1} U[i][m] R[m][j]) U[j][j] for i < j (columns m < j of U are final, column j of R is
-    // copied out before it is overwritten)
-    std::vector<double> col((size_t)K);
-    for (int64_t j = 0; j < K; j++) {
-        for (int64_t m = 0; m <= j; m++) col[(size_t)m] = Hc[m * K + j];
-        const double ujj = 1.0 / col[(size_t)j];
-        Hc[j * K + j] = ujj;
-        const int64_t tasks = (j + CH - 1) / CH;
-        parallel_for(tasks, tasks * CH * j < 200000 ? 1 : nt, [&](int64_t c) {
-            const int64_t hi = std::min<int64_t>(j, (c + 1) * CH);
+    // U = R^-1 in place, panel after panel from the left: U[j][j] = 1 / R[j][j],
+    // U[i][j] = -(sum_{m=i}^{j-1} U[i][m] R[m][j]) U[j][j] for i < j.  The panel's columns of R are copied out, its
+    // diagonal is set, then every row is on its own (entries left of j in the row are final or made just before).
+    std::vector<double> cols((size_t)NB * (size_t)K), ujj((size_t)NB);
+    for (int64_t j0 = 0; j0 < K; j0 += NB) {
+        const int64_t j1 = std::min<int64_t>(K, j0 + NB);
+        for (int64_t j = j0; j < j1; j++) {
+            double* col = cols.data() + (size_t)(j - j0) * K;
+            for (int64_t m = 0; m <= j; m++) col[m] = Hc[m * K + j];
+            ujj[(size_t)(j - j0)] = 1.0 / col[j];
+        }
+        for (int64_t j = j0; j < j1; j++) Hc[j * K + j] = ujj[(size_t)(j - j0)];
+        const int64_t tasks = (j1 - 1 + CH - 1) / CH;
+        parallel_for(tasks, nt, [&](int64_t c) {
+            const int64_t hi = std::min<int64_t>(j1 - 1, (c + 1) * CH);
             for (int64_t i = c * CH; i < hi; i++) {
-                const double* ui = Hc + i * K;
-                double v = 0.0;
-                for (int64_t m = i; m < j; m++) v += ui[m] * col[(size_t)m];
-                Hc[i * K + j] = -v * ujj;
+                double* ui = Hc + i * K;
+                for (int64_t j = std::max<int64_t>(j0, i + 1); j < j1; j++)
+                    ui[j] = -dot4(ui + i, cols.data() + (size_t)(j - j0) * K + i, j - i) * ujj[(size_t)(j - j0)];
             }
         });
     }
