@@ -566,3 +566,10 @@ def test_salient_columns_from_the_factor_bit_exact_against_the_oracle(n, k, seed
     with pytest.raises(S.StbError) as e:
         S.stb_salient_columns_hc(L["W"], Hc, 129)
     assert e.value.status == S.STB_EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys, os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
