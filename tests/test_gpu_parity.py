@@ -213,6 +213,49 @@ def test_pack_and_tile_on_the_device_feed_the_kernels(case, torch_cuda):
     assert e.value.status == S.STB_EINVAL
 
 
+def test_device_packer_and_tiling_on_random_shapes(torch_cuda):
+    """40 seeded random layers (any of the five ratios, 1 .. 1200 rows, up to 5000 columns, none / few / many / crowded
+    salient columns, both region modes, both scopes of the importance): stb_pack_device and stb_tile_device give the
+    host's planes byte for byte."""
+    torch = torch_cuda
+    rng = np.random.default_rng(20240801)
+    for case in range(40):
+        N, M = [(2, 4), (3, 8), (4, 8), (5, 8), (6, 8)][rng.integers(0, 5)]
+        n = int(rng.integers(1, 1200))
+        k = 128 * int(rng.integers(1, 40))
+        nsal = int(rng.choice([0, max(1, k // 20), max(1, k // 6), min(k, 60)]))
+        mode, per_block, seed = int(rng.integers(0, 2)), bool(rng.integers(0, 2)), int(rng.integers(0, 1 << 30))
+        _say(f"[case {case}] device pack + tile n={n} k={k} {N}:{M} sal={nsal} mode={mode} per_block={per_block} seed={seed}")
+        L = make_layer(n, k, seed, "x8", n_salient=nsal)
+        if rng.integers(0, 3) == 0 and nsal >= 40:          # crowd the salient columns into the first two blocks
+            cols = np.sort(rng.choice(min(k, 256), min(nsal, min(k, 256)), replace=False))
+            bits = np.zeros(k, dtype=np.uint8)
+            bits[cols] = 1
+            L["sal_bitmap"] = np.packbits(bits, bitorder="little").view("<u4").copy()
+        host = (S.PackedMatrix.pack_obc(L["W"], None, L["xnorm"], L["sal_bitmap"], N, M, mode) if per_block
+                else S.PackedMatrix.pack(L["W"], L["xnorm"], L["sal_bitmap"], N, M, mode))
+        tl_host, timg_host = host.tiled()
+        rimg = S.new_device_scratch(host.host_layout.image_bytes)
+        rlay = host.clone_layout_for(rimg.data_ptr(), False)
+        ws = S.new_device_scratch(S.stb_pack_device_workspace_bytes(host.cfg, per_block))
+        S.stb_pack_device(torch.from_numpy(L["W"]).cuda(), torch.from_numpy(L["xnorm"]).cuda(),
+                          torch.from_numpy(L["sal_bitmap"].view(np.int32)).cuda(), rlay, per_block, ws)
+        got = rimg.cpu().numpy()
+        for name, off, size in S.PLANE_FIELDS:
+            o, sz = getattr(host.host_layout, off), getattr(host.host_layout, size)
+            assert (got[o:o + sz] == host.host_image[o:o + sz]).all(), (case, name)
+        timg = S.new_device_scratch(tl_host.image_bytes)
+        timg.fill_(0xEE)
+        tlay = S.stb_tiled_sizes(host.cfg)
+        S.stb_layout_bind(tlay, timg.data_ptr())
+        S.stb_tile_device(rlay, tlay)
+        assert (tlay.max_sal_block, tlay.max_sal_half) == (tl_host.max_sal_block, tl_host.max_sal_half)
+        got = timg.cpu().numpy()
+        for name, off, size in S.PLANE_FIELDS + (("sal_tab", "off_saltab", "saltab_bytes"), ("res_t", "off_res_t", "res_t_bytes")):
+            o, sz = getattr(tl_host, off), getattr(tl_host, size)
+            assert (got[o:o + sz] == timg_host[o:o + sz]).all(), (case, name)
+
+
 def test_device_packer_edge_cases_and_errors(torch_cuda):
     torch = torch_cuda
     k = 256
