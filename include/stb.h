@@ -9,8 +9,9 @@
  * (Eq. 4, Alg. 2 "Res_Approx").
  *
  * Conventions for every function:
- *   - returns STB_OK (0) or a negative stb_status; never throws, never allocates device memory,
- *     never synchronises the stream;
+ *   - returns STB_OK (0) or a negative stb_status; never throws, never allocates device memory, and does not
+ *     synchronise the stream -- except the packing calls whose description says that they wait for it
+ *     (stb_pack_device, stb_tile_device, stb_pack_obc_hybrid: what their kernels find is their return value);
  *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device memory of the current
  *     device; the caller owns every buffer, before and after the call;
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); device work is only
